@@ -1,0 +1,152 @@
+/*
+ * monarch.h -- C ABI of the MI355X (gfx950) Monarch Mixer hot-path library.
+ *
+ * The library implements the Monarch matrix multiply of Monarch Mixer (M2,
+ * arXiv 2310.12109, Sec. 3.1) and its two uses in an M2 layer (Sec. 3.2):
+ * the Monarch-factored DFT inside the causal gated long convolution (Eq. 2,
+ * Thm 3) and the block-diagonal / Monarch MLP (Eq. 3).
+ *
+ * Common rules for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the library
+ *     never frees or keeps it), densely packed in the stated row-major layout
+ *     and 16-byte aligned.  `factors` arrays and `host_out` are HOST pointers.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as an opaque
+ *     pointer; NULL is the null stream) and never synchronise the device.
+ *   - `ws` is caller-provided device scratch of at least the size the matching
+ *     *_workspace_bytes query returns (may be NULL when that size is 0).  Its
+ *     contents are undefined after the call; calls sharing one ws must not overlap.
+ *   - Output buffers must not alias inputs.
+ *   - Return value: MONARCH_OK (0) or a negative error code.  All argument and
+ *     shape checks happen before any device work, so a failing call has no side
+ *     effect.  monarch_last_error() gives a thread-local message for the last
+ *     failure.  The library never throws, aborts or prints.
+ *   - I/O element types: MONARCH_F32 or MONARCH_BF16 (MONARCH_F16 is reserved
+ *     and returns MONARCH_EDTYPE).  Arithmetic accumulates in fp32 always.
+ *   - Index conventions: 0-based; omega_N = exp(+2*pi*i/N) (the paper's sign);
+ *     sigma_(b,N)(i1*b+i0) = i0*(N/b)+i1 and (P_(b,N) x)[i] = x[sigma(i)]
+ *     (appendix notation); block-diagonal factors are stored [block][out][in].
+ */
+#ifndef MONARCH_H
+#define MONARCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MONARCH_F32 = 0, MONARCH_BF16 = 1, MONARCH_F16 = 2 } monarch_dtype;
+
+enum {
+    MONARCH_OK = 0,
+    MONARCH_EINVAL = -1,     /* null pointer, misalignment, aliasing, bad flag      */
+    MONARCH_ESHAPE = -2,     /* sizes inconsistent, non-factorable or unsupported   */
+    MONARCH_EDTYPE = -3,     /* element type not supported by this entry point      */
+    MONARCH_EWORKSPACE = -4, /* ws is NULL or smaller than the query says           */
+    MONARCH_EHIP = -5        /* a HIP call failed; message holds hipGetErrorString  */
+};
+
+typedef void *monarch_stream_t;
+
+/* Human-readable name of an error code (static storage). */
+const char *monarch_strerror(int code);
+/* Message of the last failing call on this thread ("" if none). */
+const char *monarch_last_error(void);
+
+/*
+ * Permutation sigma_(b,N) of Sec. 3.1 / appendix notation, as indices:
+ * host_out[i1*b + i0] = i0*(N/b) + i1.  Host-only helper (no device work) so
+ * that index maps can be checked bit-exactly.  host_out: N int32 on the host.
+ * Errors: EINVAL (null), ESHAPE (b <= 0, N <= 0 or b does not divide N).
+ */
+int monarch_permutation_index(int b, int N, int32_t *host_out);
+
+/*
+ * Order-2 Monarch matrix multiply (Sec. 3.1, M = P L P R P), batched:
+ *   y[v,:] = P3 * L * P2 * R * P1 * x[v,:],   v in [0, batch).
+ * R: [nbR][r_out][r_in] is applied first, L: [nbL][l_out][l_in] second, with
+ * d_in = nbR*r_in, d_mid = nbR*r_out = nbL*l_in, d_out = nbL*l_out and
+ * P1 = P_(r_in,d_in), P2 = P_(nbR,d_mid), P3 = P_(nbL,d_out).  The paper's
+ * square case has all six sizes equal to b = sqrt(N).
+ * x: (batch, d_in), y: (batch, d_out), R, L, x, y all of type dt.
+ * Errors: EINVAL, ESHAPE (d_mid mismatch, sizes < 1, a row too large for the
+ * on-chip tile: d_in + d_mid or d_out beyond 8192), EDTYPE, EHIP.
+ */
+int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t batch,
+                   int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
+                   monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_matmul_workspace_bytes(int64_t batch, int nbR, int r_out, int r_in,
+                                      int nbL, int l_out, int l_in, monarch_dtype dt);
+
+/*
+ * Monarch-factored DFT (appendix, DFT corollary; order 3 per the p-variate
+ * section):  X[r,:] = F_N x[r,:],  F_N[m,j] = omega_N^(m j), unnormalised,
+ * natural output order.  N = factors[0]*...*factors[nf-1], nf in {2,3}; the
+ * first block-diagonal factor contracts the most significant input digit
+ * (size factors[0]), twiddles are folded into the later factors.
+ * x: rows x N reals of type dt (real_input = 1) or rows x N interleaved
+ * (re,im) pairs of type dt (real_input = 0).  X: rows x N interleaved fp32.
+ * monarch_ifft is the exact inverse (minus sign, 1/N included); X is
+ * interleaved fp32, x is real (real_output = 1, imaginary part dropped) or
+ * interleaved complex, of type dt.
+ * Errors: EINVAL, ESHAPE (nf not 2 or 3, product != N, factor < 2, N > 2^24),
+ * EDTYPE, EWORKSPACE, EHIP.
+ */
+int monarch_fft(const void *x, void *X, int64_t rows, int N, const int *factors, int nf,
+                int real_input, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+int monarch_ifft(const void *X, void *x, int64_t rows, int N, const int *factors, int nf,
+                 int real_output, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_fft_workspace_bytes(int64_t rows, int N, const int *factors, int nf, monarch_dtype dt);
+
+/*
+ * Gated long convolution through the Monarch DFT (Sec. 3.2 Eq. 2 with the
+ * gated form of the same section; Thm 3; appendix review of FFT convolution):
+ *   y[b,h,t] = g_out[b,h,t] * sum_s k[h,(t-s)] * (g_in[b,h,s] * u[b,h,s]),  t in [0,n),
+ * computed as  F^-1( (F k') o (F u') )  with k', u' zero-padded to nfft and F
+ * the Monarch DFT with the given factors (nfft = prod factors).
+ *   causal = 1: taps k[h,0..klen-1] at lags 0..klen-1, sum over s <= t; needs
+ *               nfft >= n + klen - 1 (no wrap-around), klen <= n.
+ *   causal = 0: circular convolution of length nfft truncated to n: lag
+ *               (t-s) mod nfft, so negative lags live at the end of k
+ *               (klen <= nfft); this is the bidirectional kernel of M2-BERT.
+ * u, y, g_in, g_out: (B,H,n); k: (H,klen); all of type dt.  g_in and/or g_out
+ * may be NULL (no gate).
+ * Errors: EINVAL, ESHAPE (as monarch_fft; n > nfft; aliasing sizes), EDTYPE,
+ * EWORKSPACE, EHIP.
+ */
+int monarch_causal_conv(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                        int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                        int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
+                        monarch_stream_t stream);
+size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nfft,
+                                           const int *factors, int nf, monarch_dtype dt);
+
+/*
+ * Monarch MLP, the dimension mixer (Sec. 3.2 Eq. 3):
+ *   y[t,:] = W2 * act(W1 * x[t,:] + b1) + b2,   t in [0, tokens),
+ * W1: d -> d_hidden, W2: d_hidden -> d.
+ *   order 1: Wi = diag of nb blocks (the M2-BERT dimension mixer);
+ *            W1_R: [nb][d_hidden/nb][d/nb], W2_R: [nb][d/nb][d_hidden/nb];
+ *            W1_L, W2_L must be NULL.
+ *   order 2: Wi = P L P R P as in monarch_matmul with nb blocks per factor and
+ *            inner widths mid1, mid2 (0 means d):
+ *            W1_R: [nb][mid1/nb][d/nb], W1_L: [nb][d_hidden/nb][mid1/nb],
+ *            W2_R: [nb][mid2/nb][d_hidden/nb], W2_L: [nb][d/nb][mid2/nb].
+ * act: 0 none, 1 ReLU, 2 GELU (exact, erf form).  b1 (d_hidden) and b2 (d) may
+ * be NULL.  x, y: (tokens, d); everything of type dt.
+ * Errors: EINVAL, ESHAPE (nb does not divide the widths, order not 1 or 2,
+ * widths beyond the on-chip tile), EDTYPE, EWORKSPACE, EHIP.
+ */
+int monarch_mlp(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb, int order,
+                const void *W1_R, const void *W1_L, const void *b1,
+                const void *W2_R, const void *W2_L, const void *b2,
+                int mid1, int mid2, int act, monarch_dtype dt, void *ws, size_t ws_bytes,
+                monarch_stream_t stream);
+size_t monarch_mlp_workspace_bytes(int64_t tokens, int d, int d_hidden, int nb, int order,
+                                   int mid1, int mid2, monarch_dtype dt);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONARCH_H */

@@ -1,0 +1,108 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+Only input generation lives here (random draws, decay envelopes, the dense
+gate projections that sit *outside* the Monarch hot path, bf16 rounding of
+inputs).  Nothing of the method's arithmetic: both the CPU oracle's tests and
+the GPU path's tests/benchmark consume these arrays unchanged.
+
+All generators return float32 numpy arrays; with ``bf16=True`` every array is
+first rounded to the nearest bf16 value (ties to even) so that the GPU path
+(which stores bf16) and the oracle (which reads the float32 array) see exactly
+the same numbers.
+"""
+import numpy as np
+
+
+def round_to_bf16(a):
+    """Round float32 values to the nearest bfloat16 (ties to even); result stays float32."""
+    x = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    bias = ((x >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((x + bias) & np.uint32(0xFFFF0000)).view(np.float32)
+
+
+def _finish(d, bf16):
+    if not bf16:
+        return {k: (np.ascontiguousarray(v, dtype=np.float32) if isinstance(v, np.ndarray) else v)
+                for k, v in d.items()}
+    return {k: (round_to_bf16(v) if isinstance(v, np.ndarray) else v) for k, v in d.items()}
+
+
+def monarch_matmul_inputs(batch=64, b=16, seed=0, bf16=False):
+    """Config 1: square order-2 Monarch, N = b*b; L, R ~ N(0, 1/b), x ~ N(0, 1)."""
+    rng = np.random.default_rng(seed)
+    N = b * b
+    x = rng.standard_normal((batch, N))
+    R = rng.standard_normal((b, b, b)) / np.sqrt(b)
+    L = rng.standard_normal((b, b, b)) / np.sqrt(b)
+    return _finish({"x": x, "R": R, "L": L}, bf16)
+
+
+def monarch_matmul_rect_inputs(batch, nbR, r_out, r_in, nbL, l_out, l_in, seed=0, bf16=False):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((batch, nbR * r_in))
+    R = rng.standard_normal((nbR, r_out, r_in)) / np.sqrt(r_in)
+    L = rng.standard_normal((nbL, l_out, l_in)) / np.sqrt(l_in)
+    return _finish({"x": x, "R": R, "L": L}, bf16)
+
+
+def decaying_kernel(rng, H, klen, rate=0.01, two_sided=False, nfft=None):
+    """k[h,t] = N(0,1) * exp(-rate*t).  two_sided: length nfft, lag -l stored at nfft-l."""
+    if not two_sided:
+        t = np.arange(klen)
+        return rng.standard_normal((H, klen)) * np.exp(-rate * t)[None, :]
+    lag = np.arange(nfft)
+    dist = np.minimum(lag, nfft - lag)
+    return rng.standard_normal((H, nfft)) * np.exp(-rate * dist)[None, :]
+
+
+def conv_inputs(B, H, n, seed, gates="projected", bf16=False, two_sided_nfft=None):
+    """Configs 2-5: u ~ N(0,1); k decaying Gaussian; gates either dense projections
+    of u over the channel axis with W ~ N(0, 1/H) (config 2) or plain N(0,1)."""
+    rng = np.random.default_rng(seed)
+    u = rng.standard_normal((B, H, n)).astype(np.float32)
+    if two_sided_nfft:
+        k = decaying_kernel(rng, H, two_sided_nfft, two_sided=True, nfft=two_sided_nfft)
+    else:
+        k = decaying_kernel(rng, H, n)
+    if gates == "projected":
+        W1 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float32)
+        W2 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float32)
+        g_in = np.einsum("bhn,hg->bgn", u, W1)
+        g_out = np.einsum("bhn,hg->bgn", u, W2)
+    elif gates == "normal":
+        g_in = rng.standard_normal((B, H, n)).astype(np.float32)
+        g_out = rng.standard_normal((B, H, n)).astype(np.float32)
+    else:
+        g_in = g_out = None
+    return _finish({"u": u, "k": k, "g_in": g_in, "g_out": g_out}, bf16)
+
+
+def mlp_inputs(tokens, d, d_hidden, nb, order, seed, bf16=True, std=0.02, bias=True):
+    """Configs 3b / 5b: x ~ N(0,1), weights ~ N(0, std^2); order-2 layers use d_mid = d."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((tokens, d)).astype(np.float32)
+    out = {"x": x}
+    if order == 1:
+        out["W1_R"] = rng.standard_normal((nb, d_hidden // nb, d // nb)) * std
+        out["W2_R"] = rng.standard_normal((nb, d // nb, d_hidden // nb)) * std
+        out["W1_L"] = out["W2_L"] = None
+    else:
+        out["W1_R"] = rng.standard_normal((nb, d // nb, d // nb)) * std
+        out["W1_L"] = rng.standard_normal((nb, d_hidden // nb, d // nb)) * std
+        out["W2_R"] = rng.standard_normal((nb, d // nb, d_hidden // nb)) * std
+        out["W2_L"] = rng.standard_normal((nb, d // nb, d // nb)) * std
+    out["b1"] = rng.standard_normal(d_hidden) * std if bias else None
+    out["b2"] = rng.standard_normal(d) * std if bias else None
+    return _finish(out, bf16)
+
+
+# The five named configurations (shapes only; tensors come from the functions above).
+CONFIGS = {
+    "c1_matmul": dict(batch=64, b=16, seed=0),
+    "c2_conv": dict(B=8, H=768, n=1024, nfft=2048, factors=(64, 32), seed=1, gates="projected"),
+    "c3a_conv": dict(B=32, H=768, n=128, nfft=256, factors=(16, 16), seed=2, gates="normal"),
+    "c3b_mlp": dict(tokens=32 * 128, d=768, d_hidden=3072, nb=4, seed=2),
+    "c4_conv": dict(B=4, H=768, n=8192, nfft=16384, factors=(128, 128), seed=3, gates="projected"),
+    "c5a_conv": dict(B=1, H=256, n=131072, nfft=262144, factors=(64, 64, 64), seed=4, gates="normal"),
+    "c5b_mlp": dict(tokens=65536, d=1024, d_hidden=4096, nb=16, seed=4),
+}
