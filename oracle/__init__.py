@@ -102,6 +102,17 @@ def dft(x):
     return X.reshape(x.shape)
 
 
+def dft_bins(x, bins):
+    """Selected output bins of dft(x): X[r, bins[q]] for every row (for sizes where O(N^2) is too slow)."""
+    x = _c128(x)
+    x2 = x.reshape(-1, x.shape[-1])
+    bins = np.ascontiguousarray(np.asarray(bins, dtype=np.int32))
+    out = np.empty((x2.shape[0], bins.shape[0]), dtype=np.complex128)
+    lib().oracle_dft_bins(_p(x2), _p(out), ctypes.c_int64(x2.shape[0]), ctypes.c_int(x2.shape[1]),
+                          _p(bins), ctypes.c_int(bins.shape[0]))
+    return out
+
+
 def idft(X):
     """Inverse of dft: x[r,j] = (1/N) sum_m X[r,m] omega_N^(-m j)."""
     X = _c128(X)

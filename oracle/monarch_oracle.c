@@ -242,6 +242,19 @@ void oracle_dft(const cplx *x, cplx *X, int64_t rows, int N)
         }
 }
 
+/* The same definition for a chosen list of output bins only (large N):
+ * Xb[r,q] = sum_j x[r,j] * omega_N^(bins[q] j). */
+void oracle_dft_bins(const cplx *x, cplx *Xb, int64_t rows, int N, const int32_t *bins, int nbins)
+{
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int q = 0; q < nbins; ++q) {
+            cplx s = 0.0;
+            for (int j = 0; j < N; ++j) s += x[(size_t)r * N + j] * omega_pow(N, (int64_t)bins[q] * j);
+            Xb[(size_t)r * nbins + q] = s;
+        }
+}
+
 /* x[r,j] = (1/N) sum_m X[r,m] * omega_N^(-m j): the inverse of oracle_dft. */
 void oracle_idft(const cplx *X, cplx *x, int64_t rows, int N)
 {

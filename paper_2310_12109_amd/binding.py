@@ -1,0 +1,190 @@
+"""Thin ctypes binding of libmonarch.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA(ROCm) tensors used purely as device memory; every step of the
+computation runs inside the library's HIP kernels on torch's current stream.  There is no
+fallback: if the library is missing, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmonarch.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "(or python paper_2310_12109_amd/build.py) first; there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+F32, BF16, F16 = 0, 1, 2
+OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
+
+_vp, _i, _i64, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+_ip = ctypes.POINTER(ctypes.c_int)
+
+_lib.monarch_strerror.restype = ctypes.c_char_p
+_lib.monarch_strerror.argtypes = [_i]
+_lib.monarch_last_error.restype = ctypes.c_char_p
+_lib.monarch_permutation_index.argtypes = [_i, _i, _vp]
+_lib.monarch_matmul.argtypes = [_vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_matmul_workspace_bytes.restype = _sz
+_lib.monarch_matmul_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
+_lib.monarch_fft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_ifft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_fft_workspace_bytes.restype = _sz
+_lib.monarch_fft_workspace_bytes.argtypes = [_i64, _i, _ip, _i, _i]
+_lib.monarch_causal_conv.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_causal_conv_workspace_bytes.restype = _sz
+_lib.monarch_causal_conv_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _ip, _i, _i]
+_lib.monarch_mlp.argtypes = [_vp, _vp, _i64, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_mlp_workspace_bytes.restype = _sz
+_lib.monarch_mlp_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
+
+EXPORTS = [
+    "monarch_strerror", "monarch_last_error", "monarch_permutation_index",
+    "monarch_matmul", "monarch_matmul_workspace_bytes",
+    "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
+    "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
+    "monarch_mlp", "monarch_mlp_workspace_bytes",
+]
+
+
+class MonarchError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        msg = _lib.monarch_last_error().decode()
+        super().__init__(f"{_lib.monarch_strerror(code).decode()} ({code}): {msg}")
+
+
+def raw():
+    """The ctypes library handle (for tests that exercise the error paths directly)."""
+    return _lib
+
+
+def _check(code):
+    if code != OK:
+        raise MonarchError(code)
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _factors(factors):
+    arr = (ctypes.c_int * len(factors))(*[int(f) for f in factors])
+    return arr, len(factors)
+
+
+def _workspace(nbytes, ws, device):
+    if nbytes == 0:
+        return None, 0
+    if ws is None:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    if ws.numel() * ws.element_size() < nbytes:
+        raise ValueError(f"workspace too small: need {nbytes} bytes")
+    return ws, ws.numel() * ws.element_size()
+
+
+def monarch_permutation_index(b, N):
+    out = torch.empty(N, dtype=torch.int32)
+    _check(_lib.monarch_permutation_index(b, N, out.data_ptr()))
+    return out
+
+
+def monarch_matmul(x, R, L, out=None):
+    nbR, r_out, r_in = R.shape
+    nbL, l_out, l_in = L.shape
+    batch = x.shape[0]
+    y = out if out is not None else torch.empty((batch, nbL * l_out), dtype=x.dtype, device=x.device)
+    _check(_lib.monarch_matmul(_ptr(x), _ptr(R), _ptr(L), _ptr(y), batch, nbR, r_out, r_in, nbL, l_out, l_in,
+                               _dt(x), None, 0, _stream()))
+    return y
+
+
+def monarch_fft_workspace_bytes(rows, N, factors, dt=F32):
+    f, nf = _factors(factors)
+    return _lib.monarch_fft_workspace_bytes(rows, N, f, nf, dt)
+
+
+def monarch_fft(x, factors, real_input, ws=None, out=None):
+    f, nf = _factors(factors)
+    N = 1
+    for v in factors:
+        N *= int(v)
+    rows = x.numel() // (N if real_input else 2 * N)
+    X = out if out is not None else torch.empty((rows, N, 2), dtype=torch.float32, device=x.device)
+    ws, nbytes = _workspace(_lib.monarch_fft_workspace_bytes(rows, N, f, nf, _dt(x)), ws, x.device)
+    _check(_lib.monarch_fft(_ptr(x), _ptr(X), rows, N, f, nf, 1 if real_input else 0, _dt(x),
+                            _ptr(ws), nbytes, _stream()))
+    return X
+
+
+def monarch_ifft(X, factors, real_output, dtype=torch.float32, ws=None, out=None):
+    f, nf = _factors(factors)
+    N = 1
+    for v in factors:
+        N *= int(v)
+    rows = X.numel() // (2 * N)
+    shape = (rows, N) if real_output else (rows, N, 2)
+    x = out if out is not None else torch.empty(shape, dtype=dtype, device=X.device)
+    ws, nbytes = _workspace(_lib.monarch_fft_workspace_bytes(rows, N, f, nf, _dt(x)), ws, X.device)
+    _check(_lib.monarch_ifft(_ptr(X), _ptr(x), rows, N, f, nf, 1 if real_output else 0, _dt(x),
+                             _ptr(ws), nbytes, _stream()))
+    return x
+
+
+def monarch_causal_conv_workspace_bytes(B, H, n, klen, factors, dt):
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    return _lib.monarch_causal_conv_workspace_bytes(B, H, n, klen, nfft, f, nf, dt)
+
+
+def monarch_causal_conv(u, k, g_in, g_out, factors, causal=True, ws=None, out=None):
+    B, H, n = u.shape
+    klen = k.shape[1]
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    y = out if out is not None else torch.empty_like(u)
+    ws, nbytes = _workspace(_lib.monarch_causal_conv_workspace_bytes(B, H, n, klen, nfft, f, nf, _dt(u)), ws, u.device)
+    _check(_lib.monarch_causal_conv(_ptr(u), _ptr(k), _ptr(g_in), _ptr(g_out), _ptr(y), B, H, n, klen, nfft,
+                                    f, nf, 1 if causal else 0, _dt(u), _ptr(ws), nbytes, _stream()))
+    return y
+
+
+def monarch_mlp_workspace_bytes(tokens, d, d_hidden, nb, order, mid1=0, mid2=0, dt=BF16):
+    return _lib.monarch_mlp_workspace_bytes(tokens, d, d_hidden, nb, order, mid1, mid2, dt)
+
+
+def monarch_mlp(x, W1_R, W1_L, b1, W2_R, W2_L, b2, nb, order, act, d_hidden, mid1=0, mid2=0, ws=None, out=None):
+    tokens, d = x.shape
+    y = out if out is not None else torch.empty_like(x)
+    ws, nbytes = _workspace(_lib.monarch_mlp_workspace_bytes(tokens, d, d_hidden, nb, order, mid1, mid2, _dt(x)),
+                            ws, x.device)
+    _check(_lib.monarch_mlp(_ptr(x), _ptr(y), tokens, d, d_hidden, nb, order, _ptr(W1_R), _ptr(W1_L), _ptr(b1),
+                            _ptr(W2_R), _ptr(W2_L), _ptr(b2), mid1, mid2, act, _dt(x), _ptr(ws), nbytes, _stream()))
+    return y

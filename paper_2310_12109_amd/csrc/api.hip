@@ -1,0 +1,420 @@
+// C-ABI entry points: argument checks first (no device work until they pass), then dispatch.
+#include <stdarg.h>
+#include <string.h>
+
+#include "kernels.h"
+
+namespace monarch {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+void clear_error() { g_err[0] = 0; }
+
+static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+// Half-open byte ranges [a, a+na) and [b, b+nb) intersect.
+static bool overlaps(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+static int check_dtype(monarch_dtype dt)
+{
+    if (dt == MONARCH_F32 || dt == MONARCH_BF16) return MONARCH_OK;
+    if (dt == MONARCH_F16) return fail(MONARCH_EDTYPE, "fp16 I/O is reserved and not implemented");
+    return fail(MONARCH_EDTYPE, "unknown element type %d", (int)dt);
+}
+
+static int check_factors(int N, const int *factors, int nf)
+{
+    if (!factors) return fail(MONARCH_EINVAL, "factors is NULL");
+    if (nf != 2 && nf != 3) return fail(MONARCH_ESHAPE, "nf must be 2 or 3 (got %d)", nf);
+    if (N < 4 || N > (1 << 24)) return fail(MONARCH_ESHAPE, "transform length %d outside [4, 2^24]", N);
+    int64_t prod = 1;
+    for (int i = 0; i < nf; ++i) {
+        if (factors[i] < 2) return fail(MONARCH_ESHAPE, "factor %d is %d (< 2)", i, factors[i]);
+        prod *= factors[i];
+    }
+    if (prod != N) return fail(MONARCH_ESHAPE, "factors multiply to %lld, not %d", (long long)prod, N);
+    return MONARCH_OK;
+}
+
+// Fills the digit geometry of pass q of an nf-factor transform.
+static void set_pass_geometry(FftPass &p, int N, const int *factors, int nf, int q)
+{
+    p.N = N;
+    p.nf = nf;
+    for (int i = 0; i < 3; ++i) p.factors[i] = i < nf ? factors[i] : 1;
+    int O = 1, S = 1;
+    for (int i = 0; i < q; ++i) O *= factors[i];
+    for (int i = q + 1; i < nf; ++i) S *= factors[i];
+    p.O = O;
+    p.f = factors[q];
+    p.S = S;
+}
+
+static FftPass blank_pass()
+{
+    FftPass p;
+    memset(&p, 0, sizeof(p));
+    p.scale = 1.0f;
+    p.H = 1;
+    return p;
+}
+
+}  // namespace monarch
+
+using namespace monarch;
+
+extern "C" {
+
+const char *monarch_strerror(int code)
+{
+    switch (code) {
+    case MONARCH_OK: return "ok";
+    case MONARCH_EINVAL: return "invalid argument";
+    case MONARCH_ESHAPE: return "unsupported or inconsistent shape";
+    case MONARCH_EDTYPE: return "unsupported element type";
+    case MONARCH_EWORKSPACE: return "workspace missing or too small";
+    case MONARCH_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+    }
+}
+
+const char *monarch_last_error(void) { return g_err; }
+
+int monarch_permutation_index(int b, int N, int32_t *host_out)
+{
+    clear_error();
+    if (!host_out) return fail(MONARCH_EINVAL, "host_out is NULL");
+    if (b <= 0 || N <= 0 || N % b != 0) return fail(MONARCH_ESHAPE, "b=%d must be positive and divide N=%d", b, N);
+    const int q = N / b;
+    for (int i = 0; i < N; ++i) host_out[i] = (i % b) * q + i / b;
+    return MONARCH_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// monarch_matmul
+// ---------------------------------------------------------------------------------------------
+
+size_t monarch_matmul_workspace_bytes(int64_t, int, int, int, int, int, int, monarch_dtype) { return 0; }
+
+int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t batch,
+                   int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
+                   monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    (void)ws; (void)ws_bytes;
+    clear_error();
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (batch < 0) return fail(MONARCH_ESHAPE, "negative batch");
+    if (nbR < 1 || r_out < 1 || r_in < 1 || nbL < 1 || l_out < 1 || l_in < 1)
+        return fail(MONARCH_ESHAPE, "all block counts and block sizes must be >= 1");
+    if ((int64_t)nbR * r_out != (int64_t)nbL * l_in)
+        return fail(MONARCH_ESHAPE, "d_mid mismatch: nbR*r_out=%lld but nbL*l_in=%lld",
+                    (long long)nbR * r_out, (long long)nbL * l_in);
+    const int64_t d_in = (int64_t)nbR * r_in, d_mid = (int64_t)nbR * r_out, d_out = (int64_t)nbL * l_out;
+    if (d_in > 65536 || d_mid > 65536 || d_out > 65536 || !matmul_generic_fits((int)d_in, (int)d_mid, (int)d_out))
+        return fail(MONARCH_ESHAPE, "row widths %lld/%lld/%lld exceed the on-chip tile",
+                    (long long)d_in, (long long)d_mid, (long long)d_out);
+    if (batch == 0) return MONARCH_OK;   // nothing to read or write: empty tensors may be NULL
+    if (!x || !R || !L || !y) return fail(MONARCH_EINVAL, "x, R, L and y must be non-NULL");
+    if (misaligned(x) || misaligned(R) || misaligned(L) || misaligned(y))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt);
+    if (overlaps(y, (size_t)batch * d_out * es, x, (size_t)batch * d_in * es))
+        return fail(MONARCH_EINVAL, "y overlaps x");
+    return launch_matmul_generic(x, R, L, nullptr, y, batch, nbR, r_out, r_in, nbL, l_out, l_in, 2, 0,
+                                 dt, dt, dt, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// monarch_fft / monarch_ifft
+// ---------------------------------------------------------------------------------------------
+
+size_t monarch_fft_workspace_bytes(int64_t rows, int N, const int *factors, int nf, monarch_dtype dt)
+{
+    (void)factors; (void)dt;
+    if (rows <= 0 || N <= 0) return 0;
+    const size_t buf = align_up((size_t)rows * N * sizeof(float2), 256);
+    return nf >= 3 ? 2 * buf : buf;
+}
+
+static int fft_common(const void *src, void *dst, int64_t rows, int N, const int *factors, int nf,
+                      int is_real, int inverse, monarch_dtype dt, void *ws, size_t ws_bytes,
+                      hipStream_t s)
+{
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    rc = check_factors(N, factors, nf);
+    if (rc) return rc;
+    if (rows < 0) return fail(MONARCH_ESHAPE, "negative rows");
+    if (is_real != 0 && is_real != 1) return fail(MONARCH_EINVAL, "real flag must be 0 or 1");
+    if (rows == 0) return MONARCH_OK;
+    if (!src || !dst) return fail(MONARCH_EINVAL, "input and output must be non-NULL");
+    if (misaligned(src) || misaligned(dst) || misaligned(ws)) return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t need = monarch_fft_workspace_bytes(rows, N, factors, nf, dt);
+    if (need && (!ws || ws_bytes < need))
+        return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
+    const size_t spec_bytes = (size_t)rows * N * sizeof(float2);
+    const size_t typed_bytes = (size_t)rows * N * dtype_size(dt) * (is_real ? 1 : 2);
+    if (overlaps(src, inverse ? spec_bytes : typed_bytes, dst, inverse ? typed_bytes : spec_bytes))
+        return fail(MONARCH_EINVAL, "output overlaps input");
+
+    const size_t buf = align_up(spec_bytes, 256);
+    void *bufs[2] = {ws, (char *)ws + buf};
+    const void *cur = src;
+    for (int q = 0; q < nf; ++q) {
+        FftPass p = blank_pass();
+        set_pass_geometry(p, N, factors, nf, q);
+        p.rows = rows;
+        p.dt = dt;
+        p.n_valid = N;
+        p.in = cur;
+        if (q == 0)
+            p.load = inverse ? LD_C32_CONJ : (is_real ? LD_REAL : LD_CPLX);
+        else
+            p.load = LD_C32;
+        if (q == nf - 1) {
+            p.out = dst;
+            if (!inverse) p.store = ST_C32_NATURAL;
+            else {
+                p.store = is_real ? ST_REAL_SCALE_GATE : ST_CPLX_CONJ_SCALE;
+                p.scale = 1.0f / (float)N;
+            }
+        } else {
+            p.out = bufs[q & 1];
+            p.store = ST_C32;
+        }
+        rc = launch_fft_pass(p, s);
+        if (rc) return rc;
+        cur = p.out;
+    }
+    return MONARCH_OK;
+}
+
+int monarch_fft(const void *x, void *X, int64_t rows, int N, const int *factors, int nf,
+                int real_input, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    clear_error();
+    return fft_common(x, X, rows, N, factors, nf, real_input, 0, dt, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int monarch_ifft(const void *X, void *x, int64_t rows, int N, const int *factors, int nf,
+                 int real_output, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    clear_error();
+    return fft_common(X, x, rows, N, factors, nf, real_output, 1, dt, ws, ws_bytes, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// monarch_causal_conv
+// ---------------------------------------------------------------------------------------------
+
+static int conv_check(int B, int H, int n, int klen, int nfft, const int *factors, int nf, int causal,
+                      monarch_dtype dt)
+{
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    rc = check_factors(nfft, factors, nf);
+    if (rc) return rc;
+    if (B < 0 || H < 0) return fail(MONARCH_ESHAPE, "negative B or H");
+    if (n < 1 || klen < 1) return fail(MONARCH_ESHAPE, "n and klen must be >= 1");
+    if (causal != 0 && causal != 1) return fail(MONARCH_EINVAL, "causal must be 0 or 1");
+    if (n > nfft) return fail(MONARCH_ESHAPE, "n=%d exceeds nfft=%d", n, nfft);
+    if (causal) {
+        if (klen > n) return fail(MONARCH_ESHAPE, "causal kernel longer than the sequence (klen=%d, n=%d)", klen, n);
+        if ((int64_t)n + klen - 1 > nfft)
+            return fail(MONARCH_ESHAPE, "nfft=%d < n+klen-1=%d: the circular convolution would wrap", nfft, n + klen - 1);
+    } else if (klen > nfft) {
+        return fail(MONARCH_ESHAPE, "klen=%d exceeds nfft=%d", klen, nfft);
+    }
+    return MONARCH_OK;
+}
+
+size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nfft,
+                                           const int *factors, int nf, monarch_dtype dt)
+{
+    (void)n; (void)klen; (void)factors; (void)nf; (void)dt;
+    if (B <= 0 || H <= 0 || nfft <= 0) return 0;
+    const size_t rows = (size_t)B * H;
+    const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
+    const size_t kf = align_up((size_t)H * nfft * sizeof(float2), 256);
+    return 2 * buf + kf;
+}
+
+int monarch_causal_conv(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                        int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                        int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
+                        monarch_stream_t stream)
+{
+    clear_error();
+    int rc = conv_check(B, H, n, klen, nfft, factors, nf, causal, dt);
+    if (rc) return rc;
+    if (B == 0 || H == 0) return MONARCH_OK;
+    if (!u || !k || !y) return fail(MONARCH_EINVAL, "u, k and y must be non-NULL");
+    if (misaligned(u) || misaligned(k) || misaligned(y) || misaligned(g_in) || misaligned(g_out) || misaligned(ws))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt);
+    const size_t rows = (size_t)B * H;
+    const size_t act_bytes = rows * n * es;
+    if (overlaps(y, act_bytes, u, act_bytes) || overlaps(y, act_bytes, g_in, act_bytes) ||
+        overlaps(y, act_bytes, g_out, act_bytes) || overlaps(y, act_bytes, k, (size_t)H * klen * es))
+        return fail(MONARCH_EINVAL, "y overlaps an input");
+    const size_t need = monarch_causal_conv_workspace_bytes(B, H, n, klen, nfft, factors, nf, dt);
+    if (need && (!ws || ws_bytes < need))
+        return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
+    hipStream_t s = (hipStream_t)stream;
+
+    const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
+    void *bufs[2] = {ws, (char *)ws + buf};
+    float2 *kf = (float2 *)((char *)ws + 2 * buf);
+
+    // 1. k_f = F k'  (H rows), staged through the row buffers.
+    // 2. u_f = F (g_in o u)'  (B*H rows), left in natural order in one of the row buffers.
+    const void *cur = nullptr;
+    for (int which = 0; which < 2; ++which) {
+        cur = which == 0 ? k : u;
+        for (int q = 0; q < nf; ++q) {
+            FftPass p = blank_pass();
+            set_pass_geometry(p, nfft, factors, nf, q);
+            p.rows = which == 0 ? H : (int64_t)rows;
+            p.dt = dt;
+            p.in = cur;
+            if (q == 0) {
+                p.load = LD_REAL;
+                p.n_valid = which == 0 ? klen : n;
+                p.gate = which == 0 ? nullptr : g_in;
+            } else {
+                p.load = LD_C32;
+            }
+            if (q == nf - 1) {
+                p.store = ST_C32_NATURAL;
+                p.out = which == 0 ? (void *)kf : bufs[q & 1];
+            } else {
+                p.store = ST_C32;
+                p.out = bufs[q & 1];
+            }
+            rc = launch_fft_pass(p, s);
+            if (rc) return rc;
+            cur = p.out;
+        }
+    }
+    // 3. y = Re F^-1 (k_f o u_f), first n entries, times g_out:  F^-1 z = conj(F conj(z)) / N.
+    const int first_out = (cur == bufs[0]) ? 1 : 0;
+    for (int q = 0; q < nf; ++q) {
+        FftPass p = blank_pass();
+        set_pass_geometry(p, nfft, factors, nf, q);
+        p.rows = (int64_t)rows;
+        p.dt = dt;
+        p.in = cur;
+        if (q == 0) {
+            p.load = LD_C32_CONJ_MULK;
+            p.kf = kf;
+            p.H = H;
+        } else {
+            p.load = LD_C32;
+        }
+        if (q == nf - 1) {
+            p.store = ST_REAL_SCALE_GATE;
+            p.out = y;
+            p.gate = g_out;
+            p.n_valid = n;
+            p.scale = 1.0f / (float)nfft;
+        } else {
+            p.store = ST_C32;
+            p.out = bufs[(first_out + q) & 1];
+        }
+        rc = launch_fft_pass(p, s);
+        if (rc) return rc;
+        cur = p.out;
+    }
+    return MONARCH_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// monarch_mlp
+// ---------------------------------------------------------------------------------------------
+
+static int mlp_check(int64_t tokens, int d, int d_hidden, int nb, int order, int &mid1, int &mid2,
+                     int act, monarch_dtype dt)
+{
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (tokens < 0) return fail(MONARCH_ESHAPE, "negative token count");
+    if (d < 1 || d_hidden < 1 || nb < 1) return fail(MONARCH_ESHAPE, "d, d_hidden and nb must be >= 1");
+    if (order != 1 && order != 2) return fail(MONARCH_ESHAPE, "order must be 1 or 2 (got %d)", order);
+    if (act < 0 || act > 2) return fail(MONARCH_EINVAL, "act must be 0, 1 or 2");
+    if (d % nb || d_hidden % nb) return fail(MONARCH_ESHAPE, "nb=%d must divide d=%d and d_hidden=%d", nb, d, d_hidden);
+    if (order == 2) {
+        if (mid1 == 0) mid1 = d;
+        if (mid2 == 0) mid2 = d;
+        if (mid1 < 1 || mid2 < 1 || mid1 % nb || mid2 % nb)
+            return fail(MONARCH_ESHAPE, "nb=%d must divide mid1=%d and mid2=%d", nb, mid1, mid2);
+        if (!matmul_generic_fits(d, mid1, d_hidden) || !matmul_generic_fits(d_hidden, mid2, d))
+            return fail(MONARCH_ESHAPE, "layer widths exceed the on-chip tile");
+    } else {
+        mid1 = mid2 = 0;
+        if (!matmul_generic_fits(d, d_hidden, d_hidden) || !matmul_generic_fits(d_hidden, d, d))
+            return fail(MONARCH_ESHAPE, "layer widths exceed the on-chip tile");
+    }
+    return MONARCH_OK;
+}
+
+size_t monarch_mlp_workspace_bytes(int64_t tokens, int d, int d_hidden, int nb, int order,
+                                   int mid1, int mid2, monarch_dtype dt)
+{
+    (void)d; (void)nb; (void)order; (void)mid1; (void)mid2; (void)dt;
+    if (tokens <= 0 || d_hidden <= 0) return 0;
+    return align_up((size_t)tokens * d_hidden * sizeof(float), 256);   // hidden activations, fp32
+}
+
+int monarch_mlp(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb, int order,
+                const void *W1_R, const void *W1_L, const void *b1,
+                const void *W2_R, const void *W2_L, const void *b2,
+                int mid1, int mid2, int act, monarch_dtype dt, void *ws, size_t ws_bytes,
+                monarch_stream_t stream)
+{
+    clear_error();
+    int rc = mlp_check(tokens, d, d_hidden, nb, order, mid1, mid2, act, dt);
+    if (rc) return rc;
+    if (tokens == 0) return MONARCH_OK;
+    if (!x || !y || !W1_R || !W2_R) return fail(MONARCH_EINVAL, "x, y, W1_R and W2_R must be non-NULL");
+    if (order == 2 && (!W1_L || !W2_L)) return fail(MONARCH_EINVAL, "order 2 needs W1_L and W2_L");
+    if (order == 1 && (W1_L || W2_L)) return fail(MONARCH_EINVAL, "order 1 takes no W1_L / W2_L");
+    if (misaligned(x) || misaligned(y) || misaligned(W1_R) || misaligned(W1_L) || misaligned(b1) ||
+        misaligned(W2_R) || misaligned(W2_L) || misaligned(b2) || misaligned(ws))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt);
+    if (overlaps(y, (size_t)tokens * d * es, x, (size_t)tokens * d * es)) return fail(MONARCH_EINVAL, "y overlaps x");
+    const size_t need = monarch_mlp_workspace_bytes(tokens, d, d_hidden, nb, order, mid1, mid2, dt);
+    if (need && (!ws || ws_bytes < need))
+        return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
+    hipStream_t s = (hipStream_t)stream;
+
+    // Layer 1 writes the activated hidden vector (fp32) to the workspace, layer 2 reads it.
+    if (order == 1) {
+        rc = launch_matmul_generic(x, W1_R, nullptr, b1, ws, tokens, nb, d_hidden / nb, d / nb, 1, 1, 1, 1, act,
+                                   dt, dt, MONARCH_F32, s);
+        if (rc) return rc;
+        return launch_matmul_generic(ws, W2_R, nullptr, b2, y, tokens, nb, d / nb, d_hidden / nb, 1, 1, 1, 1, 0,
+                                     MONARCH_F32, dt, dt, s);
+    }
+    rc = launch_matmul_generic(x, W1_R, W1_L, b1, ws, tokens, nb, mid1 / nb, d / nb, nb, d_hidden / nb, mid1 / nb,
+                               2, act, dt, dt, MONARCH_F32, s);
+    if (rc) return rc;
+    return launch_matmul_generic(ws, W2_R, W2_L, b2, y, tokens, nb, mid2 / nb, d_hidden / nb, nb, d / nb, mid2 / nb,
+                                 2, 0, MONARCH_F32, dt, dt, s);
+}
+
+}  // extern "C"

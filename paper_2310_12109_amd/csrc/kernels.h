@@ -1,0 +1,40 @@
+// Host-side launchers of the HIP kernels; argument checks are done by the callers in api.hip.
+#pragma once
+
+#include "common.h"
+
+namespace monarch {
+
+// ---- generic fp32-arithmetic kernels (any shape) -------------------------------------------
+
+// y = act(P3 L P2 R P1 x + bias) (order 2) or y = act(diag(R) x + bias) (order 1: L ignored).
+// x: (batch, d_in) of type dt_in, y: (batch, d_out) of type dt_out, weights/bias of type dt_w.
+int launch_matmul_generic(const void *x, const void *R, const void *L, const void *bias, void *y,
+                          int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
+                          int order, int act, monarch_dtype dt_in, monarch_dtype dt_w,
+                          monarch_dtype dt_out, hipStream_t s);
+// Largest d_in/d_out + d_mid the generic kernel can hold on chip.
+bool matmul_generic_fits(int d_in, int d_mid, int d_out);
+
+enum FftLoad { LD_C32 = 0, LD_C32_CONJ = 1, LD_C32_CONJ_MULK = 2, LD_REAL = 3, LD_CPLX = 4 };
+enum FftStore { ST_C32 = 0, ST_C32_NATURAL = 1, ST_CPLX_CONJ_SCALE = 2, ST_REAL_SCALE_GATE = 3 };
+
+struct FftPass {
+    const void *in;      // see FftLoad
+    void *out;           // see FftStore
+    const void *gate;    // LD_REAL: optional per-element gate (same layout as in); ST_REAL_SCALE_GATE: optional output gate
+    const float2 *kf;    // LD_C32_CONJ_MULK: spectrum (H, N)
+    int64_t rows;
+    int N;               // transform length
+    int O, f, S;         // the row is viewed as [O][f][S]; this pass contracts the middle digit
+    int nf;              // number of factors of the whole transform and the factors themselves
+    int factors[3];
+    int n_valid;         // LD_REAL: entries at positions >= n_valid are zero; ST_REAL: only t < n_valid is stored
+    int H;               // LD_C32_CONJ_MULK: row r uses kf row r % H
+    float scale;         // store scale (1/N for the inverse)
+    int load, store;
+    monarch_dtype dt;    // element type of typed loads/stores
+};
+int launch_fft_pass(const FftPass &p, hipStream_t s);
+
+}  // namespace monarch

@@ -1,0 +1,135 @@
+"""C-ABI checks that need no GPU: the library loads, exports what the header declares,
+and rejects bad arguments before any device work."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2310_12109_amd", "libmonarch.so")
+HEADER = os.path.join(ROOT, "include", "monarch.h")
+
+EINVAL, ESHAPE, EDTYPE, EWORKSPACE = -1, -2, -3, -4
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail("libmonarch.so is not built; run __graft_entry__.build() first")
+    from paper_2310_12109_amd import binding
+    return binding.raw()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(monarch_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in monarch.h but not exported"
+
+
+def test_binding_lists_the_same_names(lib):
+    from paper_2310_12109_amd import binding
+    assert sorted(binding.EXPORTS) == _declared_functions()
+
+
+@pytest.mark.parametrize("b,N", [(1, 1), (2, 6), (3, 6), (16, 256), (64, 2048), (32, 2048), (7, 49)])
+def test_permutation_index_bit_exact_against_oracle(lib, b, N):
+    out = np.empty(N, dtype=np.int32)
+    assert lib.monarch_permutation_index(b, N, out.ctypes.data_as(ctypes.c_void_p)) == 0
+    assert np.array_equal(out, oracle.perm(b, N))
+
+
+def test_permutation_index_errors(lib):
+    out = np.empty(8, dtype=np.int32)
+    assert lib.monarch_permutation_index(2, 8, None) == EINVAL
+    assert lib.monarch_permutation_index(3, 8, out.ctypes.data_as(ctypes.c_void_p)) == ESHAPE
+    assert b"divide" in lib.monarch_last_error()
+
+
+FAKE = 0x1000   # aligned, never dereferenced: every call below must fail before touching it
+
+
+def test_matmul_rejects_bad_arguments(lib):
+    f = lib.monarch_matmul
+    assert f(None, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == EINVAL
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 8, 16, 16, 0, None, 0, None) == ESHAPE   # d_mid mismatch
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 0, 16, 16, 16, 16, 16, 0, None, 0, None) == ESHAPE
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 2, None, 0, None) == EDTYPE   # fp16 reserved
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 9, None, 0, None) == EDTYPE
+    assert f(FAKE + 4, FAKE, FAKE, FAKE * 2, 4, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == EINVAL  # misaligned
+    assert f(FAKE, FAKE * 4, FAKE * 8, FAKE, 4, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == EINVAL  # y aliases x
+    assert f(FAKE, FAKE, FAKE, FAKE, -1, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == ESHAPE
+    assert f(FAKE, FAKE, FAKE, FAKE * 64, 4, 256, 256, 256, 256, 256, 256, 0, None, 0, None) == ESHAPE  # too wide
+    assert lib.monarch_strerror(ESHAPE) and lib.monarch_last_error()
+
+
+def test_fft_rejects_bad_arguments(lib):
+    fac = (ctypes.c_int * 3)(64, 32, 1)
+    bad = (ctypes.c_int * 2)(64, 31)
+    one = (ctypes.c_int * 2)(2048, 1)
+    f = lib.monarch_fft
+    assert f(FAKE, FAKE * 1024, 4, 2048, fac, 1, 1, 0, FAKE, 1 << 30, None) == ESHAPE       # nf = 1
+    assert f(FAKE, FAKE * 1024, 4, 2048, bad, 2, 1, 0, FAKE, 1 << 30, None) == ESHAPE       # product
+    assert f(FAKE, FAKE * 1024, 4, 2048, one, 2, 1, 0, FAKE, 1 << 30, None) == ESHAPE       # factor < 2
+    assert f(FAKE, FAKE * 1024, 4, 2048, None, 2, 1, 0, FAKE, 1 << 30, None) == EINVAL
+    assert f(FAKE, FAKE * 1024, 4, 2048, fac, 2, 1, 0, None, 0, None) == EWORKSPACE
+    assert f(FAKE, FAKE * 1024, 4, 2048, fac, 2, 1, 0, FAKE, 100, None) == EWORKSPACE
+    assert f(FAKE, None, 4, 2048, fac, 2, 1, 0, FAKE, 1 << 30, None) == EINVAL
+    assert f(FAKE, FAKE * 1024, 4, 2048, fac, 2, 7, 0, FAKE, 1 << 30, None) == EINVAL       # real flag
+    assert lib.monarch_ifft(FAKE, FAKE * 1024, 4, 2048, fac, 2, 1, 2, FAKE, 1 << 30, None) == EDTYPE
+    need = lib.monarch_fft_workspace_bytes(4, 2048, fac, 2, 0)
+    assert need >= 4 * 2048 * 8
+
+
+def test_conv_rejects_bad_arguments(lib):
+    fac = (ctypes.c_int * 2)(64, 32)
+    f = lib.monarch_causal_conv
+    big = 1 << 40
+    args = dict(B=8, H=4, n=1024, klen=1024, nfft=2048)
+
+    def call(u=FAKE, k=FAKE * 2, y=FAKE * 1 << 20, causal=1, dt=0, ws=FAKE * 1 << 24, wsb=big, **kw):
+        a = dict(args); a.update(kw)
+        return f(u, k, None, None, y, a["B"], a["H"], a["n"], a["klen"], a["nfft"], fac, 2, causal, dt, ws, wsb, None)
+
+    assert call(u=None) == EINVAL
+    assert call(n=2049) == ESHAPE
+    assert call(n=1025, klen=1025) == ESHAPE            # would wrap around
+    assert call(klen=2000) == ESHAPE                    # causal kernel longer than the sequence
+    assert call(klen=4096, causal=0) == ESHAPE
+    assert call(causal=2) == EINVAL
+    assert call(dt=2) == EDTYPE
+    assert call(ws=None, wsb=0) == EWORKSPACE
+    assert call(wsb=64) == EWORKSPACE
+    assert call(y=FAKE) == EINVAL                        # y aliases u
+    assert lib.monarch_causal_conv_workspace_bytes(8, 4, 1024, 1024, 2048, fac, 2, 0) > 0
+
+
+def test_mlp_rejects_bad_arguments(lib):
+    f = lib.monarch_mlp
+    Y = FAKE << 20
+
+    def call(x=FAKE, y=Y, tokens=16, d=768, dh=3072, nb=4, order=1, w1l=None, w2l=None, act=2, dt=1,
+             ws=FAKE << 24, wsb=1 << 40, mid1=0, mid2=0):
+        return f(x, y, tokens, d, dh, nb, order, FAKE, w1l, None, FAKE, w2l, None, mid1, mid2, act, dt, ws, wsb, None)
+
+    assert call(x=None) == EINVAL
+    assert call(nb=5) == ESHAPE
+    assert call(order=3) == ESHAPE
+    assert call(act=5) == EINVAL
+    assert call(order=2) == EINVAL                       # order 2 without the L factors
+    assert call(order=1, w1l=FAKE) == EINVAL
+    assert call(order=2, w1l=FAKE, w2l=FAKE, mid1=770) == ESHAPE
+    assert call(dt=2) == EDTYPE
+    assert call(ws=None, wsb=0) == EWORKSPACE
+    assert call(y=FAKE) == EINVAL
+    assert lib.monarch_mlp_workspace_bytes(16, 768, 3072, 4, 1, 0, 0, 1) >= 16 * 3072 * 4

@@ -1,0 +1,153 @@
+"""GPU parity: monarch_causal_conv against the oracle's direct O(n^2) sum (Eq. 2 / Thm 3)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL_BF16, TOL_F32, announce, dev, host, rel_l2
+from paper_2310_12109_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2310_12109_amd import binding
+    return binding
+
+
+def _run(mm, w, factors, bf16, causal=True):
+    y = mm.monarch_causal_conv(dev(w["u"], bf16), dev(w["k"], bf16), dev(w["g_in"], bf16), dev(w["g_out"], bf16),
+                               factors, causal=causal)
+    return host(y)
+
+
+def _oracle(w, nfft, causal=True):
+    return oracle.causal_conv(w["u"], w["k"], w["g_in"], w["g_out"], nfft=nfft, causal=causal)
+
+
+@pytest.mark.parametrize("factors", [(64, 32), (32, 64)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config2_full_tensor(mm, factors, bf16):
+    # B=8, H=768, n=1024 zero-padded to 2048: every output element against the direct sum.
+    announce("conv c2", factors, "bf16" if bf16 else "fp32")
+    c = workloads.CONFIGS["c2_conv"]
+    w = workloads.conv_inputs(c["B"], c["H"], c["n"], c["seed"], gates="projected", bf16=bf16)
+    y = _run(mm, w, factors, bf16)
+    want = _oracle(w, 2048)
+    assert rel_l2(y, want) <= (TOL_BF16 if bf16 else TOL_F32)
+    # per-row check as well, so that one bad row cannot hide in the global norm
+    num = np.linalg.norm((y - want).reshape(-1, c["n"]), axis=1)
+    den = np.linalg.norm(want.reshape(-1, c["n"]), axis=1)
+    assert (num / den).max() <= (2.5 * TOL_BF16 if bf16 else 5 * TOL_F32)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config3a_causal(mm, bf16):
+    announce("conv c3a causal", "bf16" if bf16 else "fp32")
+    c = workloads.CONFIGS["c3a_conv"]
+    w = workloads.conv_inputs(c["B"], c["H"], c["n"], c["seed"], gates="normal", bf16=bf16)
+    y = _run(mm, w, (16, 16), bf16)
+    assert rel_l2(y, _oracle(w, 256)) <= (TOL_BF16 if bf16 else TOL_F32)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config3a_bidirectional(mm, bf16):
+    # two-sided kernel of length nfft with negative lags wrapped to the end (causal = 0)
+    announce("conv c3a bidirectional", "bf16" if bf16 else "fp32")
+    c = workloads.CONFIGS["c3a_conv"]
+    w = workloads.conv_inputs(4, c["H"], c["n"], c["seed"], gates="normal", bf16=bf16, two_sided_nfft=256)
+    y = _run(mm, w, (16, 16), bf16, causal=False)
+    assert rel_l2(y, _oracle(w, 256, causal=False)) <= (TOL_BF16 if bf16 else TOL_F32)
+
+
+@pytest.mark.parametrize("B,H,n,klen,factors,gates", [
+    (3, 5, 100, 37, (16, 16), "normal"),
+    (1, 1, 1, 1, (2, 2), "none"),
+    (2, 3, 50, 50, (10, 12), "normal"),
+    (2, 3, 50, 21, (4, 5, 6), "normal"),
+    (3, 2, 512, 512, (8, 8, 16), "none"),
+    (5, 7, 1000, 1000, (64, 32), "normal"),
+    (1, 2, 128, 128, (16, 32), "normal"),     # nfft = 4n
+])
+def test_ragged_shapes_fp32(mm, B, H, n, klen, factors, gates):
+    announce("conv ragged", B, H, n, klen, factors, gates)
+    nfft = int(np.prod(factors))
+    w = workloads.conv_inputs(B, H, n, seed=n + klen, gates=gates)
+    w["k"] = np.ascontiguousarray(w["k"][:, :klen])
+    y = _run(mm, w, factors, False)
+    assert rel_l2(y, _oracle(w, nfft)) <= TOL_F32
+
+
+def test_single_gate_and_bf16_odd_batch(mm):
+    announce("conv one gate, odd B, bf16")
+    w = workloads.conv_inputs(3, 4, 1024, seed=8, gates="normal", bf16=True)
+    w["g_in"] = None
+    y = _run(mm, w, (64, 32), True)
+    assert rel_l2(y, _oracle(w, 2048)) <= TOL_BF16
+    w2 = workloads.conv_inputs(3, 4, 1024, seed=8, gates="normal", bf16=True)
+    w2["g_out"] = None
+    y2 = _run(mm, w2, (64, 32), True)
+    assert rel_l2(y2, _oracle(w2, 2048)) <= TOL_BF16
+
+
+def test_delta_kernel_and_causality(mm):
+    announce("conv delta / causality")
+    B, H, n = 2, 3, 1024
+    w = workloads.conv_inputs(B, H, n, seed=5, gates="normal")
+    k0 = np.zeros((H, n), dtype=np.float32); k0[:, 0] = 1.0
+    w0 = dict(w, k=k0)
+    y = _run(mm, w0, (64, 32), False)
+    assert rel_l2(y, w["g_out"].astype(np.float64) * w["g_in"] * w["u"]) <= TOL_F32
+    # Thm 3: changing u from t0 on leaves y before t0 unchanged (up to rounding on the GPU).
+    t0 = 400
+    w2 = dict(w, u=w["u"].copy())
+    w2["u"][..., t0:] = np.random.default_rng(1).standard_normal((B, H, n - t0)).astype(np.float32)
+    ya, yb = _run(mm, w, (64, 32), False), _run(mm, w2, (64, 32), False)
+    assert rel_l2(ya[..., :t0], yb[..., :t0]) <= 2 * TOL_F32
+    assert rel_l2(ya[..., t0:], yb[..., t0:]) > 1e-2
+
+
+def test_empty_batch(mm):
+    announce("conv empty")
+    u = torch.empty((0, 4, 128), device="cuda")
+    k = torch.zeros((4, 128), device="cuda")
+    y = mm.monarch_causal_conv(u, k, None, None, (16, 16))
+    assert y.shape == (0, 4, 128)
+
+
+def _sampled_rows_check(mm, cfg, bf16, nrows, tol):
+    c = workloads.CONFIGS[cfg]
+    B, H, n, factors = c["B"], c["H"], c["n"], c["factors"]
+    nfft = int(np.prod(factors))
+    w = workloads.conv_inputs(B, H, n, c["seed"], gates=c["gates"], bf16=bf16)
+    y = _run(mm, w, factors, bf16)
+    rng = np.random.default_rng(0)
+    rows = rng.choice(B * H, size=nrows, replace=False)
+    rows[0] = 0; rows[-1] = B * H - 1
+    worst = 0.0
+    for r in rows:
+        b, h = divmod(int(r), H)
+        sub = {key: (None if w[key] is None else w[key][b:b + 1, h:h + 1]) for key in ("u", "g_in", "g_out")}
+        want = oracle.causal_conv(sub["u"], w["k"][h:h + 1], sub["g_in"], sub["g_out"], nfft=nfft)
+        worst = max(worst, rel_l2(y[b, h], want[0, 0]))
+    assert worst <= tol
+    # library screen over every row (not the oracle): float64 FFT convolution of the same inputs
+    gi = 1.0 if w["g_in"] is None else w["g_in"].astype(np.float64)
+    go = 1.0 if w["g_out"] is None else w["g_out"].astype(np.float64)
+    ref = np.fft.irfft(np.fft.rfft(gi * w["u"], nfft) * np.fft.rfft(w["k"].astype(np.float64), nfft)[None], nfft)[..., :n] * go
+    assert rel_l2(y, ref) <= tol
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config4_sampled_rows(mm, bf16):
+    # B=4, H=768, n=8192 padded to 16384 = 128x128: the oracle's direct sum on 16 seeded rows.
+    announce("conv c4 sampled", "bf16" if bf16 else "fp32")
+    _sampled_rows_check(mm, "c4_conv", bf16, 16, TOL_BF16 if bf16 else TOL_F32)
+
+
+@pytest.mark.parametrize("bf16", [True])
+def test_config5a_order3_sampled_rows(mm, bf16):
+    # B=1, H=256, n=131072 padded to 262144 = 64^3: the oracle's direct sum on 2 seeded rows.
+    announce("conv c5a sampled", "bf16" if bf16 else "fp32")
+    _sampled_rows_check(mm, "c5a_conv", bf16, 2, TOL_BF16 if bf16 else TOL_F32)

@@ -1,0 +1,78 @@
+"""GPU parity: monarch_mlp (block-diagonal / Monarch MLP, Eq. 3) against the dense-materialised oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL_BF16, TOL_F32, announce, dev, host, rel_l2
+from paper_2310_12109_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2310_12109_amd import binding
+    return binding
+
+
+def _run(mm, w, nb, order, act, d_hidden, bf16):
+    keys = ("W1_R", "W1_L", "b1", "W2_R", "W2_L", "b2")
+    t = {k: dev(w[k], bf16) for k in keys}
+    y = mm.monarch_mlp(dev(w["x"], bf16), t["W1_R"], t["W1_L"], t["b1"], t["W2_R"], t["W2_L"], t["b2"],
+                       nb, order, act, d_hidden)
+    return host(y)
+
+
+def _oracle(w, nb, order, act, rows=None):
+    x = w["x"] if rows is None else w["x"][rows]
+    return oracle.mlp(x, w["W1_R"], w["W1_L"], w["b1"], w["W2_R"], w["W2_L"], w["b2"], nb=nb, order=order, act=act)
+
+
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("act", [0, 1, 2])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_small_ragged(mm, order, act, bf16):
+    announce("mlp small", order, act, "bf16" if bf16 else "fp32")
+    w = workloads.mlp_inputs(37, 24, 96, 4, order, seed=order * 10 + act, bf16=bf16, std=0.3)
+    y = _run(mm, w, 4, order, act, 96, bf16)
+    assert rel_l2(y, _oracle(w, 4, order, act)) <= (TOL_BF16 if bf16 else TOL_F32)
+
+
+def test_no_bias_and_single_block(mm):
+    announce("mlp nb=1 no bias")
+    w = workloads.mlp_inputs(10, 16, 64, 1, 1, seed=3, bf16=False, std=0.3, bias=False)
+    y = _run(mm, w, 1, 1, 2, 64, False)
+    assert rel_l2(y, _oracle(w, 1, 1, 2)) <= TOL_F32
+
+
+@pytest.mark.parametrize("order", [1, 2])
+def test_config3b(mm, order):
+    # 4096 tokens, 768 -> 3072 -> 768, 4 blocks, GELU, bf16; oracle on a seeded 512-token sample.
+    announce("mlp c3b order", order)
+    c = workloads.CONFIGS["c3b_mlp"]
+    w = workloads.mlp_inputs(c["tokens"], c["d"], c["d_hidden"], c["nb"], order, c["seed"], bf16=True)
+    y = _run(mm, w, c["nb"], order, 2, c["d_hidden"], True)
+    rows = np.sort(np.random.default_rng(0).choice(c["tokens"], size=512, replace=False))
+    rows[0] = 0; rows[-1] = c["tokens"] - 1
+    assert rel_l2(y[rows], _oracle(w, c["nb"], order, 2, rows)) <= TOL_BF16
+
+
+@pytest.mark.parametrize("order", [1, 2])
+def test_config5b_sampled(mm, order):
+    # 65536 tokens, 1024 -> 4096 -> 1024, 16 blocks; oracle on a seeded 256-token sample.
+    announce("mlp c5b order", order)
+    c = workloads.CONFIGS["c5b_mlp"]
+    w = workloads.mlp_inputs(c["tokens"], c["d"], c["d_hidden"], c["nb"], order, c["seed"], bf16=True)
+    y = _run(mm, w, c["nb"], order, 2, c["d_hidden"], True)
+    rows = np.sort(np.random.default_rng(1).choice(c["tokens"], size=256, replace=False))
+    rows[0] = 0; rows[-1] = c["tokens"] - 1
+    assert rel_l2(y[rows], _oracle(w, c["nb"], order, 2, rows)) <= TOL_BF16
+
+
+def test_zero_tokens(mm):
+    announce("mlp zero tokens")
+    w = workloads.mlp_inputs(1, 24, 96, 4, 1, seed=0, bf16=True)
+    x = torch.empty((0, 24), device="cuda", dtype=torch.bfloat16)
+    y = mm.monarch_mlp(x, dev(w["W1_R"], True), None, None, dev(w["W2_R"], True), None, None, 4, 1, 2, 96)
+    assert y.shape == (0, 24)

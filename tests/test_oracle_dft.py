@@ -113,3 +113,13 @@ def test_order3_random_blocks_against_digitwise_application():
     y = v.transpose(2, 1, 0).ravel()                          # P^R: [m2,m1,m0]
     M = oracle.monarch3_dense(*B)
     assert np.abs(M @ x - y).max() < 1e-12
+
+
+def test_selected_bins_match_full_transform_and_library():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((2, 4096)) + 1j * rng.standard_normal((2, 4096))
+    bins = [0, 1, 17, 2048, 4095]
+    Xb = oracle.dft_bins(x, bins)
+    assert np.abs(Xb - (4096 * np.fft.ifft(x, axis=-1))[:, bins]).max() < 1e-8
+    y = rng.standard_normal((1, 64)) + 0j
+    assert np.array_equal(oracle.dft_bins(y, np.arange(64)), oracle.dft(y))
