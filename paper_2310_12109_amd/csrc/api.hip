@@ -242,11 +242,19 @@ static int conv_check(int B, int H, int n, int klen, int nfft, const int *factor
     return MONARCH_OK;
 }
 
+// Which fused kernel serves this shape: 0 = none (multi-pass generic path), 1 = 64 x 32 MFMA.
+// With n, klen <= nfft/2 the circular and the causal form coincide, so `causal` does not matter.
+static int conv_fused_path(int n, int klen, const int *factors, int nf, monarch_dtype dt)
+{
+    if (factors && conv_mfma_2048_supported(n, klen, factors, nf, dt)) return 1;
+    return 0;
+}
+
 size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nfft,
                                            const int *factors, int nf, monarch_dtype dt)
 {
-    (void)n; (void)klen; (void)factors; (void)nf; (void)dt;
     if (B <= 0 || H <= 0 || nfft <= 0) return 0;
+    if (conv_fused_path(n, klen, factors, nf, dt)) return 0;   // fused kernels keep everything on chip
     const size_t rows = (size_t)B * H;
     const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
     const size_t kf = align_up((size_t)H * nfft * sizeof(float2), 256);
@@ -275,6 +283,9 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
     if (need && (!ws || ws_bytes < need))
         return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
     hipStream_t s = (hipStream_t)stream;
+
+    if (conv_fused_path(n, klen, factors, nf, dt) == 1)
+        return launch_conv_mfma_2048(u, k, g_in, g_out, y, B, H, n, klen, s);
 
     const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
     void *bufs[2] = {ws, (char *)ws + buf};

@@ -37,4 +37,11 @@ struct FftPass {
 };
 int launch_fft_pass(const FftPass &p, hipStream_t s);
 
+// ---- fused bf16 MFMA kernels ---------------------------------------------------------------
+
+// nfft = 2048 = 64 x 32, n <= 1024, klen <= 1024 (both multiples of 8), bf16 I/O.
+bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
+int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                          int B, int H, int n, int klen, hipStream_t s);
+
 }  // namespace monarch

@@ -67,8 +67,8 @@ def conv_inputs(B, H, n, seed, gates="projected", bf16=False, two_sided_nfft=Non
     if gates == "projected":
         W1 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float32)
         W2 = (rng.standard_normal((H, H)) / np.sqrt(H)).astype(np.float32)
-        g_in = np.einsum("bhn,hg->bgn", u, W1)
-        g_out = np.einsum("bhn,hg->bgn", u, W2)
+        g_in = np.matmul(W1.T[None], u)      # g[b,:,t] = W^T u[b,:,t]: a dense projection over channels
+        g_out = np.matmul(W2.T[None], u)
     elif gates == "normal":
         g_in = rng.standard_normal((B, H, n)).astype(np.float32)
         g_out = rng.standard_normal((B, H, n)).astype(np.float32)
