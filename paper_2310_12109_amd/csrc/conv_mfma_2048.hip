@@ -1,20 +1,25 @@
 // Fused gated causal Monarch-FFT convolution, nfft = 2048 = 64 x 32, bf16 I/O, fp32 accumulate.
 //
-// One workgroup (4 waves) owns one channel h.  It first turns k[h] into its spectrum k_f
-// (kept in LDS), then every wave takes PAIRS of batch rows of that channel and runs the whole
-// chain  pad -> Monarch DFT -> (.) k_f -> inverse Monarch DFT -> truncate -> gate  in registers:
+// A workgroup (4 waves) takes a work item (channel h, chunk of batch pairs): it first turns k[h]
+// into its spectrum k_f (one quarter per wave, kept in LDS), then every wave takes PAIRS of batch
+// rows of that channel and runs the whole chain
+//   pad -> Monarch DFT -> (.) k_f -> inverse Monarch DFT -> truncate -> gate
+// in registers:
 //
 //   * two real rows ride as one complex row z = x0 + i x1 (the kernel is real, so the
 //     convolution of z is conv(x0) + i conv(x1)): half the transforms;
 //   * the row is the N1 x N2 = 64 x 32 matrix x[c*32 + a]; the Monarch factors are
 //     R = I (x) F_64 (contract c), twiddle w_2048^(i a), L = F_32 blocks (contract a);
 //     the zero-padded half (c >= 32) is never multiplied and only outputs c < 32 are formed;
-//   * every factor is a bf16 MFMA (32x32x16) with the constant DFT matrix as one operand and
-//     the previous stage's accumulators, re-rounded to bf16, as the other.  An accumulator
-//     tile (rows in registers, columns on lanes) is a valid B operand (contract its rows,
-//     keep columns on lanes) and equally a valid A operand (contract its rows, its lane index
-//     becomes the new row index), so no stage needs a transpose: the permutations P of
-//     M = P L P R P never exist as data movement, not even in LDS;
+//   * every factor is a bf16 MFMA (16x16x32) with the constant DFT matrix as one operand and
+//     the previous stage's accumulators, re-rounded to bf16, as the other.  Two stacked
+//     accumulator tiles (32 rows in registers, 16 columns on lanes) are a valid B operand
+//     (contract the rows, keep the columns on lanes) and equally a valid A operand (contract the
+//     rows, the lane index becomes the new row index), so no stage needs a transpose: the
+//     permutations P of M = P L P R P never exist as data movement, not even in LDS;
+//   * the spectrum is walked in four chunks of 16 columns, which keeps the live fp32 tiles small
+//     enough for three waves per SIMD: all workgroups of the benchmark shape are resident at
+//     once and hide each other's MFMA, LDS and HBM latencies;
 //   * twiddles, the spectrum product and the gates are fp32 on the accumulators.
 //
 // Appendix DFT corollary (Monarch form of F_N), Sec. 3.2 Eq. 2 with gating, Thm 3 (padding).
@@ -23,27 +28,31 @@
 namespace monarch {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace c2048 {
 
 constexpr int N1 = 64, N2 = 32, NFFT = 2048, NHALF = 1024;
-constexpr int TW_LD = 34;   // padded row length (complex) of the twiddle table
+constexpr int TW_LD = 34;        // padded row length (complex) of the twiddle table
+#ifndef MONARCH_C2048_WAVES
+#define MONARCH_C2048_WAVES 3
+#endif
+constexpr int WAVES_PER_SIMD = MONARCH_C2048_WAVES;   // the register budget (512 / 3) the kernel is written for
 
 struct Smem {
-    float2 tw[N1][TW_LD];          // w_2048^(i*a), i < 64, a < 32
-    float4 kf_re[2][4][64];        // k_f / NFFT in accumulator layout [tile][quad][lane]
-    float4 kf_im[2][4][64];
-    uint32_t stage[4][NHALF];      // per wave: (re bf16 | im bf16 << 16) at [c*32 + a]
+    float2 tw[N1][TW_LD];        // w_2048^(i*a), i < 64, a < 32
+    float4 kf_re[4][2][64];      // k_f / NFFT in accumulator layout [chunk][row tile][lane]
+    float4 kf_im[4][2][64];
+    uint32_t stage[4][NHALF];    // per wave: (re bf16 | im bf16 << 16) at [c*32 + a]
+    float2 w64[64];              // w_64^e, source of the constant operands
 };
 
 union Pack8 {
     bf16x8 v;
     uint32_t d[4];
-    uint4 q;
 };
 
-struct COp { bf16x8 r, i, ni; };   // constant complex operand: real, imag, -imag
+struct COp { bf16x8 r, i; };     // constant complex operand: real and imaginary parts
 
 // cos/sin of 2*pi*e/N through the hardware units (argument in revolutions, 0 <= e < N).
 __device__ __forceinline__ float2 hw_omega(int e, int N)
@@ -62,27 +71,43 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 __device__ __forceinline__ float bf16_lo(uint32_t d) { return __uint_as_float(d << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t d) { return __uint_as_float(d & 0xffff0000u); }
 
-// Contraction index carried by operand slot (kstep s, lane group g, element j) when the operand
-// is made from accumulator registers 8s..8s+7: the accumulator row 8*(r/4) + 4*g + r%4.
-__device__ __forceinline__ int slot_index(int s, int g, int j) { return 16 * s + 8 * (j >> 2) + 4 * g + (j & 3); }
+// Contraction index carried by operand slot j of lane group kg when the operand is made from two
+// stacked 16x16 accumulator tiles: tile j/4, register j%4 holds row 16*(j/4) + 4*kg + j%4.
+__device__ __forceinline__ int slot_index(int kg, int j) { return 16 * (j >> 2) + 4 * kg + (j & 3); }
 
-__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ bf16x8 pack_acc(const f32x16 &v, int s)
+// Sign flips on packed bf16 operands (bit 15 of each half is the sign).
+__device__ __forceinline__ bf16x8 flip(bf16x8 v, uint32_t mask)
 {
     Pack8 p;
+    p.v = v;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) p.d[jj] = pack_bf16(v[8 * s + 2 * jj], v[8 * s + 2 * jj + 1]);
+    for (int jj = 0; jj < 4; ++jj) p.d[jj] ^= mask;
+    return p.v;
+}
+__device__ __forceinline__ bf16x8 neg_all(bf16x8 v) { return flip(v, 0x80008000u); }
+
+// Two stacked accumulator tiles -> one bf16 operand (slot 4*t + r <- tile t, register r).
+__device__ __forceinline__ bf16x8 pack_tiles(const f32x4 &t0, const f32x4 &t1)
+{
+    Pack8 p;
+    p.d[0] = pack_bf16(t0[0], t0[1]);
+    p.d[1] = pack_bf16(t0[2], t0[3]);
+    p.d[2] = pack_bf16(t1[0], t1[1]);
+    p.d[3] = pack_bf16(t1[2], t1[3]);
     return p.v;
 }
 
-// 8 consecutive bf16 of a row (chunk ch), zero past the end of the row.
+// 8 consecutive bf16 of a row (chunk ch), zero past the end of the row.  FULL: the row has all
+// 128 chunks, so the load is unconditional (no exec-mask branch per load).
+template <bool FULL>
 __device__ __forceinline__ uint4 load_chunk(const bf16_t *row, int ch, int len)
 {
-    if (ch * 8 < len) return *reinterpret_cast<const uint4 *>(row + ch * 8);
+    if (FULL || ch * 8 < len) return *reinterpret_cast<const uint4 *>(row + ch * 8);
     return make_uint4(0u, 0u, 0u, 0u);
 }
 
@@ -91,276 +116,345 @@ __device__ __forceinline__ uint32_t mul_pack(uint32_t a, uint32_t b)
     return pack_bf16(bf16_lo(a) * bf16_lo(b), bf16_hi(a) * bf16_hi(b));
 }
 
-// Writes rows x0 (real part) and x1 (imaginary part, may be absent) of one pair into the
-// wave's staging tile, gated by g0/g1 when given.  Lane handles chunks lane and lane+64.
-__device__ __forceinline__ void stage_pair(uint32_t *stage, int lane, const bf16_t *x0, const bf16_t *x1,
-                                           const bf16_t *g0, const bf16_t *g1, int len)
+// Raw rows as loaded: chunks lane and lane+64 of two rows (the second may be absent).
+struct RowLoad { uint4 a[2], b[2]; };
+
+template <bool FULL>
+__device__ __forceinline__ void load_rows(RowLoad &ld, int lane, const bf16_t *r0, const bf16_t *r1, int len)
+{
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int ch = lane + 64 * half;
+        ld.a[half] = r0 ? load_chunk<FULL>(r0, ch, len) : zero;
+        ld.b[half] = r1 ? load_chunk<FULL>(r1, ch, len) : zero;
+    }
+}
+
+// (lo | hi << 16) interleave of two packed rows: element e of each into word e.
+__device__ __forceinline__ void interleave_store(uint32_t *dst, const uint32_t (&r)[4], const uint32_t (&m)[4])
+{
+    uint4 o0, o1;
+    o0.x = __builtin_amdgcn_perm(m[0], r[0], 0x05040100u); o0.y = __builtin_amdgcn_perm(m[0], r[0], 0x07060302u);
+    o0.z = __builtin_amdgcn_perm(m[1], r[1], 0x05040100u); o0.w = __builtin_amdgcn_perm(m[1], r[1], 0x07060302u);
+    o1.x = __builtin_amdgcn_perm(m[2], r[2], 0x05040100u); o1.y = __builtin_amdgcn_perm(m[2], r[2], 0x07060302u);
+    o1.z = __builtin_amdgcn_perm(m[3], r[3], 0x05040100u); o1.w = __builtin_amdgcn_perm(m[3], r[3], 0x07060302u);
+    reinterpret_cast<uint4 *>(dst)[0] = o0;
+    reinterpret_cast<uint4 *>(dst)[1] = o1;
+}
+
+// Writes two rows into the wave's staging tile as (row a | row b << 16) words at [c*32 + a'],
+// multiplied elementwise by the gate rows when `gated`.
+__device__ __forceinline__ void stage_rows(uint32_t *stage, int lane, const RowLoad &x, const RowLoad &gt, bool gated)
 {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int ch = lane + 64 * half;
-        uint4 re = load_chunk(x0, ch, len);
-        uint4 im = x1 ? load_chunk(x1, ch, len) : make_uint4(0u, 0u, 0u, 0u);
-        if (g0) {
-            const uint4 ga = load_chunk(g0, ch, len);
-            re.x = mul_pack(re.x, ga.x); re.y = mul_pack(re.y, ga.y);
-            re.z = mul_pack(re.z, ga.z); re.w = mul_pack(re.w, ga.w);
-            if (x1) {
-                const uint4 gb = load_chunk(g1, ch, len);
-                im.x = mul_pack(im.x, gb.x); im.y = mul_pack(im.y, gb.y);
-                im.z = mul_pack(im.z, gb.z); im.w = mul_pack(im.w, gb.w);
+        uint32_t r[4] = {x.a[half].x, x.a[half].y, x.a[half].z, x.a[half].w};
+        uint32_t m[4] = {x.b[half].x, x.b[half].y, x.b[half].z, x.b[half].w};
+        if (gated) {
+            const uint32_t ga[4] = {gt.a[half].x, gt.a[half].y, gt.a[half].z, gt.a[half].w};
+            const uint32_t gb[4] = {gt.b[half].x, gt.b[half].y, gt.b[half].z, gt.b[half].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                r[q] = mul_pack(r[q], ga[q]);
+                m[q] = mul_pack(m[q], gb[q]);
             }
         }
-        const uint32_t r[4] = {re.x, re.y, re.z, re.w}, m[4] = {im.x, im.y, im.z, im.w};
-        uint4 o0, o1;
-        // element e: (re_e | im_e << 16)
-        o0.x = __builtin_amdgcn_perm(m[0], r[0], 0x05040100u); o0.y = __builtin_amdgcn_perm(m[0], r[0], 0x07060302u);
-        o0.z = __builtin_amdgcn_perm(m[1], r[1], 0x05040100u); o0.w = __builtin_amdgcn_perm(m[1], r[1], 0x07060302u);
-        o1.x = __builtin_amdgcn_perm(m[2], r[2], 0x05040100u); o1.y = __builtin_amdgcn_perm(m[2], r[2], 0x07060302u);
-        o1.z = __builtin_amdgcn_perm(m[3], r[3], 0x05040100u); o1.w = __builtin_amdgcn_perm(m[3], r[3], 0x07060302u);
-        uint4 *dst = reinterpret_cast<uint4 *>(stage + ch * 8);
-        dst[0] = o0;
-        dst[1] = o1;
+        interleave_store(stage + ch * 8, r, m);
     }
 }
 
-// A operands of the first factor: lane (a = lane%32, g) holds x[c][a] for the 8 c of each kstep.
-__device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int il, int g, bf16x8 (&xr)[2], bf16x8 (&xi)[2])
+// A operands of the first factor: for row tile m, lane (a = 16m + lane%16, kg) holds x[c][a]
+// for the 8 contraction indices c = slot_index(kg, j).
+__device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int l16, int kg, bf16x8 (&xr)[2], bf16x8 (&xi)[2])
 {
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    for (int m = 0; m < 2; ++m) {
         Pack8 pr, pi;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            const uint32_t d0 = stage[slot_index(s, g, 2 * jj) * 32 + il];
-            const uint32_t d1 = stage[slot_index(s, g, 2 * jj + 1) * 32 + il];
+            const int c0 = slot_index(kg, 2 * jj);
+            const uint32_t d0 = stage[c0 * 32 + 16 * m + l16];
+            const uint32_t d1 = stage[(c0 + 1) * 32 + 16 * m + l16];
             pr.d[jj] = __builtin_amdgcn_perm(d1, d0, 0x05040100u);
             pi.d[jj] = __builtin_amdgcn_perm(d1, d0, 0x07060302u);
         }
-        xr[s] = pr.v;
-        xi[s] = pi.v;
+        xr[m] = pr.v;
+        xi[m] = pi.v;
     }
 }
 
-// Forward transform of tile t (spectrum columns i = 32t + lane%32):
+// Forward transform of spectrum columns i = 16*CH + lane%16:
 //   Z1[a,i] = sum_c x[c,a] F64[c,i];  Z1 *= w_2048^(i a);  Z2[k,i] = sum_a F32[k,a] Z1[a,i].
-// Result rows k sit in registers (accumulator layout), columns i on lanes.
-template <bool HAS_IM>
-__device__ __forceinline__ void forward_tile(const Smem &sm, int t, int il, int g, const bf16x8 (&xr)[2],
-                                             const bf16x8 (&xi)[2], const COp (&Fb)[2], const COp (&G)[2],
-                                             f32x16 &z2r, f32x16 &z2i)
+// F holds F64[c][16*(CH%2) + lane%16]; columns 32..63 differ from it by (-1)^c (odd slots).
+// Result: rows k = 16m + 4kg + r in registers (z2[m][r]), column i on the lane.
+template <int CH, bool HAS_IM>
+__device__ __forceinline__ void forward_chunk(const Smem &sm, int l16, int kg, const bf16x8 (&xr)[2],
+                                              const bf16x8 (&xi)[2], const COp &F, const COp (&G)[2],
+                                              f32x4 (&z2r)[2], f32x4 (&z2i)[2])
 {
-    f32x16 zr = {0}, zi = {0};
+    constexpr uint32_t odd = CH >= 2 ? 0x80000000u : 0u;   // (-1)^c on the constant's odd slots
+    const bf16x8 fr = flip(F.r, odd), fi = flip(F.i, odd), nfi = flip(F.i, odd ^ 0x80008000u);
+    f32x4 zr[2], zi[2];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        zr = mfma(xr[s], Fb[s].r, zr);
-        zi = mfma(xr[s], Fb[s].i, zi);
+    for (int m = 0; m < 2; ++m) {
+        zr[m] = mfma(xr[m], fr, (f32x4){0, 0, 0, 0});
+        zi[m] = mfma(xr[m], fi, (f32x4){0, 0, 0, 0});
         if (HAS_IM) {
-            zr = mfma(xi[s], Fb[s].ni, zr);
-            zi = mfma(xi[s], Fb[s].r, zi);
+            zr[m] = mfma(xi[m], nfi, zr[m]);
+            zi[m] = mfma(xi[m], fr, zi[m]);
         }
     }
-    // twiddle: rows a = 8q + 4g + rr in registers, column i on the lane
-    const float2 *trow = sm.tw[32 * t + il];
+    // twiddle: rows a = 16m + 4kg + r in registers, column i on the lane
+    const float2 *trow = sm.tw[16 * CH + l16] + 4 * kg;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const float4 t01 = *reinterpret_cast<const float4 *>(trow + 8 * q + 4 * g);
-        const float4 t23 = *reinterpret_cast<const float4 *>(trow + 8 * q + 4 * g + 2);
+    for (int m = 0; m < 2; ++m) {
+        const float4 t01 = *reinterpret_cast<const float4 *>(trow + 16 * m);
+        const float4 t23 = *reinterpret_cast<const float4 *>(trow + 16 * m + 2);
         const float tr[4] = {t01.x, t01.z, t23.x, t23.z}, ti[4] = {t01.y, t01.w, t23.y, t23.w};
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const float a = zr[4 * q + rr], b = zi[4 * q + rr];
-            zr[4 * q + rr] = a * tr[rr] - b * ti[rr];
-            zi[4 * q + rr] = a * ti[rr] + b * tr[rr];
+        for (int r = 0; r < 4; ++r) {
+            const float a = zr[m][r], b = zi[m][r];
+            zr[m][r] = a * tr[r] - b * ti[r];
+            zi[m][r] = a * ti[r] + b * tr[r];
         }
     }
-    z2r = (f32x16){0};
-    z2i = (f32x16){0};
+    const bf16x8 br = pack_tiles(zr[0], zr[1]), bi = pack_tiles(zi[0], zi[1]);
+    const bf16x8 nbi = neg_all(bi);
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const bf16x8 br = pack_acc(zr, s), bi = pack_acc(zi, s);
-        z2r = mfma(G[s].r, br, z2r);
-        z2r = mfma(G[s].ni, bi, z2r);
-        z2i = mfma(G[s].i, br, z2i);
-        z2i = mfma(G[s].r, bi, z2i);
+    for (int m = 0; m < 2; ++m) {
+        z2r[m] = mfma(G[m].r, br, (f32x4){0, 0, 0, 0});
+        z2i[m] = mfma(G[m].i, br, (f32x4){0, 0, 0, 0});
+        z2r[m] = mfma(G[m].i, nbi, z2r[m]);
+        z2i[m] = mfma(G[m].r, bi, z2i[m]);
     }
 }
 
-__global__ __launch_bounds__(256) void conv2048_bf16_kernel(
+// Spectrum product, third factor and conjugate twiddle for columns i = 16*CH + ...; writes this
+// chunk's 16 contraction rows into the last factor's B operands (half of each operand).
+template <int CH>
+__device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16, int kg, f32x4 (&zr)[2],
+                                              f32x4 (&zi)[2], const COp (&G)[2], Pack8 (&wr_op)[2], Pack8 (&wi_op)[2])
+{
+    // Y = Z2 (.) k_f   (rows k in registers, column i on the lane)
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const float4 kr = sm.kf_re[CH][m][lane], ki = sm.kf_im[CH][m][lane];
+        const float kre[4] = {kr.x, kr.y, kr.z, kr.w}, kim[4] = {ki.x, ki.y, ki.z, ki.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float a = zr[m][r], b = zi[m][r];
+            zr[m][r] = a * kre[r] - b * kim[r];
+            zi[m][r] = a * kim[r] + b * kre[r];
+        }
+    }
+    // third factor: W[i,a] = sum_k Y[i,k] conj(F32)[k,a]; Y's lane index i becomes the row index
+    const bf16x8 ar = pack_tiles(zr[0], zr[1]), ai = pack_tiles(zi[0], zi[1]);
+    const bf16x8 nar = neg_all(ar);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        f32x4 wr = mfma(ar, G[nt].r, (f32x4){0, 0, 0, 0});
+        f32x4 wi = mfma(ai, G[nt].r, (f32x4){0, 0, 0, 0});
+        wr = mfma(ai, G[nt].i, wr);
+        wi = mfma(nar, G[nt].i, wi);
+        // conjugate twiddle: rows i = 16*CH + 4kg + r in registers, column a = 16nt + lane%16
+        const float2 *tcol = &sm.tw[16 * CH + 4 * kg][16 * nt + l16];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float2 w = tcol[r * TW_LD];
+            const float a = wr[r], b = wi[r];
+            wr[r] = a * w.x + b * w.y;
+            wi[r] = b * w.x - a * w.y;
+        }
+        // contraction rows 32*(CH/2) + 16*(CH%2) + 4kg + r  ->  slots 4*(CH%2) + r of kstep CH/2
+        wr_op[nt].d[2 * (CH & 1)] = pack_bf16(wr[0], wr[1]);
+        wr_op[nt].d[2 * (CH & 1) + 1] = pack_bf16(wr[2], wr[3]);
+        wi_op[nt].d[2 * (CH & 1)] = pack_bf16(wi[0], wi[1]);
+        wi_op[nt].d[2 * (CH & 1) + 1] = pack_bf16(wi[2], wi[3]);
+    }
+}
+
+template <bool FULL>
+__global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     const bf16_t *__restrict__ u, const bf16_t *__restrict__ k, const bf16_t *__restrict__ g_in,
     const bf16_t *__restrict__ g_out, bf16_t *__restrict__ y, int B, int H, int n, int klen)
 {
     __shared__ Smem sm;
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, il = lane & 31, g = lane >> 5;
-    const int h = blockIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
     uint32_t *stage = sm.stage[wave];
+    // work item = (channel h, group of 4 pairs); wave w of the group takes pair 4*group + w
+    const int h = blockIdx.x % H;
+    const int p = 4 * (blockIdx.x / H) + wave;
+    const int b0 = 2 * p;
+    const bool active = b0 < B, two = b0 + 1 < B;
+    const size_t row0 = ((size_t)b0 * H + h) * n, row1 = ((size_t)(b0 + 1) * H + h) * n;
 
-    // twiddle table w_2048^(i*a); i*a <= 63*31 < 2048
+    // Everything this wave needs from HBM is requested before any set-up work.
+    RowLoad ldk, ldx, ldg, ldo;
+    load_rows<FULL>(ldk, lane, k + (size_t)h * klen, nullptr, klen);
+    if (active) {
+        load_rows<FULL>(ldx, lane, u + row0, two ? u + row1 : nullptr, n);
+        if (g_in) load_rows<FULL>(ldg, lane, g_in + row0, two ? g_in + row1 : nullptr, n);
+        if (g_out) load_rows<FULL>(ldo, lane, g_out + row0, two ? g_out + row1 : nullptr, n);
+    }
+
+    // tables: w_2048^(i*a) (i*a <= 63*31 < 2048) and w_64^e
     for (int idx = tid; idx < N1 * N2; idx += 256) {
         const int i = idx >> 5, a = idx & 31;
         sm.tw[i][a] = hw_omega(i * a, NFFT);
     }
+    if (tid < 64) sm.w64[tid] = hw_omega(tid, 64);
+    __syncthreads();
 
-    // per-lane constant operands
-    COp Fb[2][2];   // F64[c][i], c = slot, i = 32t + il         (first factor, B operand; last factor t=0, A operand)
-    COp Hb[2];      // F64[il][32 + slot]                        (last factor, A operand, contraction rows 32..63)
-    COp G[2];       // F32[il][slot]                             (second factor A operand / third factor B operand)
+    // per-lane constant operands: F64[slot][16t + l16] (= F64[16t + l16][slot]) and F32[16t + l16][slot]
+    COp F[2], G[2];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        Pack8 fr[2], fi[2], fn[2], hr, hi, hn, gr, gi, gn;
+    for (int t = 0; t < 2; ++t) {
+        Pack8 fr, fi, gr, gi;
+        const int row = 16 * t + l16;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            float2 w[2][2], wh[2], wg[2];
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int cm = slot_index(s, g, 2 * jj + e);
-                w[0][e] = hw_omega((cm * il) & 63, 64);
-                w[1][e] = hw_omega((cm * (32 + il)) & 63, 64);
-                wh[e] = hw_omega((il * (32 + cm)) & 63, 64);
-                wg[e] = hw_omega((il * cm) & 31, 32);
-            }
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                fr[t].d[jj] = pack_bf16(w[t][0].x, w[t][1].x);
-                fi[t].d[jj] = pack_bf16(w[t][0].y, w[t][1].y);
-                fn[t].d[jj] = pack_bf16(-w[t][0].y, -w[t][1].y);
-            }
-            hr.d[jj] = pack_bf16(wh[0].x, wh[1].x);
-            hi.d[jj] = pack_bf16(wh[0].y, wh[1].y);
-            hn.d[jj] = pack_bf16(-wh[0].y, -wh[1].y);
-            gr.d[jj] = pack_bf16(wg[0].x, wg[1].x);
-            gi.d[jj] = pack_bf16(wg[0].y, wg[1].y);
-            gn.d[jj] = pack_bf16(-wg[0].y, -wg[1].y);
+            const int s0 = slot_index(kg, 2 * jj);
+            const float2 f0 = sm.w64[(s0 * row) & 63], f1 = sm.w64[((s0 + 1) * row) & 63];
+            const float2 g0 = sm.w64[(2 * s0 * row) & 63], g1 = sm.w64[(2 * (s0 + 1) * row) & 63];
+            fr.d[jj] = pack_bf16(f0.x, f1.x);
+            fi.d[jj] = pack_bf16(f0.y, f1.y);
+            gr.d[jj] = pack_bf16(g0.x, g1.x);
+            gi.d[jj] = pack_bf16(g0.y, g1.y);
         }
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            Fb[t][s].r = fr[t].v; Fb[t][s].i = fi[t].v; Fb[t][s].ni = fn[t].v;
-        }
-        Hb[s].r = hr.v; Hb[s].i = hi.v; Hb[s].ni = hn.v;
-        G[s].r = gr.v; G[s].i = gi.v; G[s].ni = gn.v;
+        F[t].r = fr.v; F[t].i = fi.v;
+        G[t].r = gr.v; G[t].i = gi.v;
     }
-    __syncthreads();   // twiddle table complete
+    const uint32_t lane_sign = (l16 & 1) ? 0x80008000u : 0u;   // (-1)^(row of this lane) on every slot
 
-    // spectrum of the kernel: waves 0 and 1 take one tile of spectrum columns each
-    if (wave < 2) {
-        stage_pair(stage, lane, k + (size_t)h * klen, nullptr, nullptr, nullptr, klen);
+    // spectrum of the kernel: wave w transforms spectrum columns 16w .. 16w+15
+    {
+        stage_rows(stage, lane, ldk, ldk, false);
         __builtin_amdgcn_wave_barrier();
         bf16x8 xr[2], xi[2];
-        read_stage_operands(stage, il, g, xr, xi);
-        f32x16 zr, zi;
-        if (wave == 0) forward_tile<false>(sm, 0, il, g, xr, xi, Fb[0], G, zr, zi);
-        else forward_tile<false>(sm, 1, il, g, xr, xi, Fb[1], G, zr, zi);
+        read_stage_operands(stage, l16, kg, xr, xi);
+        f32x4 zr[2], zi[2];
+        switch (wave) {
+        case 0: forward_chunk<0, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
+        case 1: forward_chunk<1, false>(sm, l16, kg, xr, xi, F[1], G, zr, zi); break;
+        case 2: forward_chunk<2, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
+        default: forward_chunk<3, false>(sm, l16, kg, xr, xi, F[1], G, zr, zi); break;
+        }
         const float inv = 1.0f / (float)NFFT;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            sm.kf_re[wave][q][lane] = make_float4(zr[4 * q] * inv, zr[4 * q + 1] * inv, zr[4 * q + 2] * inv, zr[4 * q + 3] * inv);
-            sm.kf_im[wave][q][lane] = make_float4(zi[4 * q] * inv, zi[4 * q + 1] * inv, zi[4 * q + 2] * inv, zi[4 * q + 3] * inv);
+        for (int m = 0; m < 2; ++m) {
+            sm.kf_re[wave][m][lane] = make_float4(zr[m][0] * inv, zr[m][1] * inv, zr[m][2] * inv, zr[m][3] * inv);
+            sm.kf_im[wave][m][lane] = make_float4(zi[m][0] * inv, zi[m][1] * inv, zi[m][2] * inv, zi[m][3] * inv);
         }
     }
-    __syncthreads();   // k_f complete; staging tiles of waves 0/1 free again
+    __syncthreads();   // k_f complete
+    if (!active) return;
 
-    const int npairs = (B + 1) >> 1;
-    for (int p = wave; p < npairs; p += 4) {
-        const int b0 = 2 * p;
-        const bool two = b0 + 1 < B;
-        const size_t row0 = ((size_t)b0 * H + h) * n, row1 = ((size_t)(b0 + 1) * H + h) * n;
-        __builtin_amdgcn_wave_barrier();
-        stage_pair(stage, lane, u + row0, two ? u + row1 : nullptr, g_in ? g_in + row0 : nullptr,
-                   g_in ? g_in + row1 : nullptr, n);
-        __builtin_amdgcn_wave_barrier();
-        bf16x8 xr[2], xi[2];
-        read_stage_operands(stage, il, g, xr, xi);
+    {
+        {
+            __builtin_amdgcn_wave_barrier();
+            stage_rows(stage, lane, ldx, ldg, g_in != nullptr);
+            __builtin_amdgcn_wave_barrier();
+            bf16x8 xr[2], xi[2];
+            read_stage_operands(stage, l16, kg, xr, xi);
+            __builtin_amdgcn_wave_barrier();
+            // the tile is free again: park the output gates in it, same word layout
+            if (g_out) stage_rows(stage, lane, ldo, ldo, false);
 
-        // forward transform and spectrum product, then third factor, per tile of columns i
-        bf16x8 wr_op[2][2], wi_op[2][2];   // [tile][kstep] operands of the last factor
+            // B operands of the last factor: [kstep = contraction rows 32ks..32ks+31][column tile nt]
+            Pack8 wr_op[2][2], wi_op[2][2];
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                f32x4 zr[2], zi[2];
+                forward_chunk<0, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
+                inverse_chunk<0>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                f32x4 zr[2], zi[2];
+                forward_chunk<1, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
+                inverse_chunk<1>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                f32x4 zr[2], zi[2];
+                forward_chunk<2, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
+                inverse_chunk<2>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                f32x4 zr[2], zi[2];
+                forward_chunk<3, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
+                inverse_chunk<3>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // last factor: y[c,a] = sum_i conj(F64)[c,i] W[i,a], c < 32 only (truncation to n).
+            // Contraction rows i >= 32 use F64[c][32+i'] = (-1)^c F64[c][i'], c being this lane's row.
+            f32x4 yr[2][2], yi[2][2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            f32x16 zr, zi;
-            forward_tile<true>(sm, t, il, g, xr, xi, Fb[t], G, zr, zi);
-            // Y = Z2 (.) k_f   (rows k in registers, column i on the lane)
+            for (int mt = 0; mt < 2; ++mt) {
+                const bf16x8 hr = flip(F[mt].r, lane_sign), hi = flip(F[mt].i, lane_sign);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 kr = sm.kf_re[t][q][lane], ki = sm.kf_im[t][q][lane];
-                const float kre[4] = {kr.x, kr.y, kr.z, kr.w}, kim[4] = {ki.x, ki.y, ki.z, ki.w};
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const float a = zr[4 * q + rr], b = zi[4 * q + rr];
-                    zr[4 * q + rr] = a * kre[rr] - b * kim[rr];
-                    zi[4 * q + rr] = a * kim[rr] + b * kre[rr];
+                for (int nt = 0; nt < 2; ++nt) {
+                    f32x4 ar = mfma(F[mt].r, wr_op[0][nt].v, (f32x4){0, 0, 0, 0});
+                    f32x4 ai = mfma(F[mt].r, wi_op[0][nt].v, (f32x4){0, 0, 0, 0});
+                    ar = mfma(F[mt].i, wi_op[0][nt].v, ar);
+                    ai = mfma(F[mt].i, neg_all(wr_op[0][nt].v), ai);
+                    ar = mfma(hr, wr_op[1][nt].v, ar);
+                    ai = mfma(hr, wi_op[1][nt].v, ai);
+                    ar = mfma(hi, wi_op[1][nt].v, ar);
+                    ai = mfma(hi, neg_all(wr_op[1][nt].v), ai);
+                    yr[mt][nt] = ar;
+                    yi[mt][nt] = ai;
                 }
             }
-            // third factor: W[i,a] = sum_k Y[i,k] conj(F32)[k,a]; Y's lane index i becomes the row index
-            f32x16 wr = {0}, wi = {0};
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const bf16x8 ar = pack_acc(zr, s), ai = pack_acc(zi, s);
-                wr = mfma(ar, G[s].r, wr);
-                wr = mfma(ai, G[s].i, wr);
-                wi = mfma(ar, G[s].ni, wi);
-                wi = mfma(ai, G[s].r, wi);
-            }
-            // conjugate twiddle: rows i = 32t + 8q + 4g + rr in registers, column a on the lane
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int i = 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
-                const float2 w = sm.tw[i][il];
-                const float a = wr[r], b = wi[r];
-                wr[r] = a * w.x + b * w.y;
-                wi[r] = b * w.x - a * w.y;
-            }
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                wr_op[t][s] = pack_acc(wr, s);
-                wi_op[t][s] = pack_acc(wi, s);
-            }
-        }
-        // last factor: y[c,a] = sum_i conj(F64)[c,i] W[i,a], c < 32 only (truncation to n)
-        f32x16 yr = {0}, yi = {0};
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            yr = mfma(Fb[0][s].r, wr_op[0][s], yr);
-            yr = mfma(Fb[0][s].i, wi_op[0][s], yr);
-            yi = mfma(Fb[0][s].r, wi_op[0][s], yi);
-            yi = mfma(Fb[0][s].ni, wr_op[0][s], yi);
-            yr = mfma(Hb[s].r, wr_op[1][s], yr);
-            yr = mfma(Hb[s].i, wi_op[1][s], yr);
-            yi = mfma(Hb[s].r, wi_op[1][s], yi);
-            yi = mfma(Hb[s].ni, wr_op[1][s], yi);
-        }
-        // rows c = 8q + 4g + rr, column a = il  ->  staging tile, then coalesced gated stores
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int c = 8 * (r >> 2) + 4 * g + (r & 3);
-            stage[c * 32 + il] = pack_bf16(yr[r], yi[r]);
-        }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int ch = lane + 64 * half;
-            if (ch * 8 >= n) continue;
-            const uint4 *src = reinterpret_cast<const uint4 *>(stage + ch * 8);
-            const uint4 s0 = src[0], s1 = src[1];
-            const uint32_t d[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-            uint32_t re[4], im[4];
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                re[jj] = __builtin_amdgcn_perm(d[2 * jj + 1], d[2 * jj], 0x05040100u);
-                im[jj] = __builtin_amdgcn_perm(d[2 * jj + 1], d[2 * jj], 0x07060302u);
-            }
+            // rows c = 16mt + 4kg + r, column a = 16nt + l16: gate in fp32, round once, park in the
+            // staging tile (all gate words are read before the first result is written)
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_wave_barrier();
+            uint32_t gw[2][2][4];
             if (g_out) {
-                const uint4 ga = load_chunk(g_out + row0, ch, n);
-                re[0] = mul_pack(re[0], ga.x); re[1] = mul_pack(re[1], ga.y);
-                re[2] = mul_pack(re[2], ga.z); re[3] = mul_pack(re[3], ga.w);
-                if (two) {
-                    const uint4 gb = load_chunk(g_out + row1, ch, n);
-                    im[0] = mul_pack(im[0], gb.x); im[1] = mul_pack(im[1], gb.y);
-                    im[2] = mul_pack(im[2], gb.z); im[3] = mul_pack(im[3], gb.w);
-                }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) gw[mt][nt][r] = stage[(16 * mt + 4 * kg + r) * 32 + 16 * nt + l16];
             }
-            *reinterpret_cast<uint4 *>(y + row0 + ch * 8) = make_uint4(re[0], re[1], re[2], re[3]);
-            if (two) *reinterpret_cast<uint4 *>(y + row1 + ch * 8) = make_uint4(im[0], im[1], im[2], im[3]);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float v0 = yr[mt][nt][r], v1 = yi[mt][nt][r];
+                        if (g_out) {
+                            v0 *= bf16_lo(gw[mt][nt][r]);
+                            v1 *= bf16_hi(gw[mt][nt][r]);
+                        }
+                        stage[(16 * mt + 4 * kg + r) * 32 + 16 * nt + l16] = pack_bf16(v0, v1);
+                    }
+            __builtin_amdgcn_wave_barrier();
+            // coalesced stores: lane takes chunks lane and lane+64 of both rows
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int ch = lane + 64 * half;
+                if (!FULL && ch * 8 >= n) continue;
+                const uint4 *src = reinterpret_cast<const uint4 *>(stage + ch * 8);
+                const uint4 s0 = src[0], s1 = src[1];
+                const uint32_t d[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+                uint32_t re[4], im[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    re[jj] = __builtin_amdgcn_perm(d[2 * jj + 1], d[2 * jj], 0x05040100u);
+                    im[jj] = __builtin_amdgcn_perm(d[2 * jj + 1], d[2 * jj], 0x07060302u);
+                }
+                *reinterpret_cast<uint4 *>(y + row0 + ch * 8) = make_uint4(re[0], re[1], re[2], re[3]);
+                if (two) *reinterpret_cast<uint4 *>(y + row1 + ch * 8) = make_uint4(im[0], im[1], im[2], im[3]);
+            }
         }
     }
 }
@@ -376,8 +470,16 @@ bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monar
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                           int B, int H, int n, int klen, hipStream_t s)
 {
-    hipLaunchKernelGGL(c2048::conv2048_bf16_kernel, dim3((unsigned)H), dim3(256), 0, s, (const bf16_t *)u,
-                       (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen);
+    // One workgroup per (channel, group of 4 batch pairs); with B <= 8 that is one per channel.
+    const int64_t groups = ((B + 1) / 2 + 3) / 4;
+    const int64_t grid = (int64_t)H * groups;
+    if (grid > 0x7fffffffLL) return fail(MONARCH_ESHAPE, "B*H too large for one launch");
+    if (n == c2048::NHALF && klen == c2048::NHALF)
+        hipLaunchKernelGGL(c2048::conv2048_bf16_kernel<true>, dim3((unsigned)grid), dim3(256), 0, s, (const bf16_t *)u,
+                           (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen);
+    else
+        hipLaunchKernelGGL(c2048::conv2048_bf16_kernel<false>, dim3((unsigned)grid), dim3(256), 0, s, (const bf16_t *)u,
+                           (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
