@@ -32,6 +32,19 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace c2048 {
 
+// Phase clocks for kernel tuning; compiled out unless MONARCH_PHASE_CLOCKS is defined.
+#ifdef MONARCH_PHASE_CLOCKS
+static __device__ long long *g_phase_clocks;   // [workgroup][wave][16]
+#define MONARCH_PHASE_MARK(slot)                                                                       \
+    do {                                                                                               \
+        if ((threadIdx.x & 63) == 0 && g_phase_clocks)                                                 \
+            g_phase_clocks[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (slot)] =              \
+                (slot) >= 14 ? (long long)wall_clock64() : (long long)__builtin_readcyclecounter();    \
+    } while (0)
+#else
+#define MONARCH_PHASE_MARK(slot)
+#endif
+
 constexpr int N1 = 64, N2 = 32, NFFT = 2048, NHALF = 1024;
 constexpr int TW_LD = 34;        // padded row length (complex) of the twiddle table
 #ifndef MONARCH_C2048_WAVES
@@ -39,27 +52,85 @@ constexpr int TW_LD = 34;        // padded row length (complex) of the twiddle t
 #endif
 constexpr int WAVES_PER_SIMD = MONARCH_C2048_WAVES;   // the register budget (512 / 3) the kernel is written for
 
+constexpr int ST_LD = 36;        // padded row length (words) of a staging tile: lane groups 4 rows
+                                 // apart fall on different LDS banks
+
 struct Smem {
     float2 tw[N1][TW_LD];        // w_2048^(i*a), i < 64, a < 32
     float4 kf_re[4][2][64];      // k_f / NFFT in accumulator layout [chunk][row tile][lane]
     float4 kf_im[4][2][64];
-    uint32_t stage[4][NHALF];    // per wave: (re bf16 | im bf16 << 16) at [c*32 + a]
-    float2 w64[64];              // w_64^e, source of the constant operands
+    uint32_t stage[4][32 * ST_LD];   // per wave: (re bf16 | im bf16 << 16) at [c*ST_LD + a]
 };
+
+// ---- constant tables, evaluated by the compiler --------------------------------------------
+// cos / sin of 2*pi*e/N for integer e, exact octant handling plus a Taylor series on [0, pi/4].
+constexpr double kTwoPi = 6.283185307179586476925286766559;
+constexpr double taylor_sin(double x) { double t = x, s = x; for (int k = 1; k < 12; ++k) { t *= -x * x / ((2 * k) * (2 * k + 1)); s += t; } return s; }
+constexpr double taylor_cos(double x) { double t = 1, s = 1; for (int k = 1; k < 12; ++k) { t *= -x * x / ((2 * k - 1) * (2 * k)); s += t; } return s; }
+struct CosSin { double c, s; };
+constexpr CosSin unit_root(int e, int N)   // N divisible by 8
+{
+    e %= N;
+    const int quadrant = e / (N / 4), r = e % (N / 4);
+    // first quadrant: angle r, mirrored around N/8 so that the series argument is <= pi/4
+    const bool mirror = r > N / 8;
+    const double x = kTwoPi * (mirror ? N / 4 - r : r) / N;
+    const double c0 = mirror ? taylor_sin(x) : taylor_cos(x), s0 = mirror ? taylor_cos(x) : taylor_sin(x);
+    switch (quadrant) {
+    case 0: return {c0, s0};
+    case 1: return {-s0, c0};
+    case 2: return {-c0, -s0};
+    default: return {s0, -c0};
+    }
+}
+constexpr uint32_t bf16_bits(double v)     // round to nearest even
+{
+    const uint32_t x = __builtin_bit_cast(uint32_t, (float)v);
+    return (x + 0x7fffu + ((x >> 16) & 1u)) >> 16;
+}
+constexpr int cslot(int kg, int j) { return 16 * (j >> 2) + 4 * kg + (j & 3); }
+
+struct TwiddleTable { float v[N1][TW_LD][2]; };
+constexpr TwiddleTable make_twiddles()
+{
+    TwiddleTable t{};
+    for (int i = 0; i < N1; ++i)
+        for (int a = 0; a < N2; ++a) {
+            const CosSin w = unit_root(i * a, NFFT);
+            t.v[i][a][0] = (float)w.c;
+            t.v[i][a][1] = (float)w.s;
+        }
+    return t;
+}
+// Per-lane constant MFMA operands, 8 x 16 bytes per lane:
+//   [2t], [2t+1]: real / imaginary part of F64[slot][16t + lane%16]  (= F64[16t + lane%16][slot])
+//   [4+2t], [5+2t]: real / imaginary part of F32[16t + lane%16][slot]
+struct OperandTable { uint32_t v[64][8][4]; };
+constexpr OperandTable make_operands()
+{
+    OperandTable t{};
+    for (int lane = 0; lane < 64; ++lane)
+        for (int tile = 0; tile < 2; ++tile)
+            for (int jj = 0; jj < 4; ++jj) {
+                const int row = 16 * tile + (lane & 15), s0 = cslot(lane >> 4, 2 * jj);
+                const CosSin f0 = unit_root(s0 * row, 64), f1 = unit_root((s0 + 1) * row, 64);
+                const CosSin g0 = unit_root(s0 * row, 32), g1 = unit_root((s0 + 1) * row, 32);
+                t.v[lane][2 * tile][jj] = bf16_bits(f0.c) | (bf16_bits(f1.c) << 16);
+                t.v[lane][2 * tile + 1][jj] = bf16_bits(f0.s) | (bf16_bits(f1.s) << 16);
+                t.v[lane][4 + 2 * tile][jj] = bf16_bits(g0.c) | (bf16_bits(g1.c) << 16);
+                t.v[lane][5 + 2 * tile][jj] = bf16_bits(g0.s) | (bf16_bits(g1.s) << 16);
+            }
+    return t;
+}
+__device__ const TwiddleTable g_twiddles = make_twiddles();
+__device__ const OperandTable g_operands = make_operands();
 
 union Pack8 {
     bf16x8 v;
     uint32_t d[4];
 };
 
-struct COp { bf16x8 r, i; };     // constant complex operand: real and imaginary parts
-
-// cos/sin of 2*pi*e/N through the hardware units (argument in revolutions, 0 <= e < N).
-__device__ __forceinline__ float2 hw_omega(int e, int N)
-{
-    const float x = (float)e / (float)N;
-    return make_float2(__builtin_amdgcn_cosf(x), __builtin_amdgcn_sinf(x));
-}
+struct COp { bf16x8 r, i, ni; }; // constant complex operand: real part, imaginary part and its negative
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
@@ -119,15 +190,27 @@ __device__ __forceinline__ uint32_t mul_pack(uint32_t a, uint32_t b)
 // Raw rows as loaded: chunks lane and lane+64 of two rows (the second may be absent).
 struct RowLoad { uint4 a[2], b[2]; };
 
+// Both pointers must be valid rows (no null checks: the loads stay free of branches).
 template <bool FULL>
 __device__ __forceinline__ void load_rows(RowLoad &ld, int lane, const bf16_t *r0, const bf16_t *r1, int len)
+{
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int ch = lane + 64 * half;
+        ld.a[half] = load_chunk<FULL>(r0, ch, len);
+        ld.b[half] = load_chunk<FULL>(r1, ch, len);
+    }
+}
+
+// One row only; the second row of the pair is zero.
+template <bool FULL>
+__device__ __forceinline__ void load_row(RowLoad &ld, int lane, const bf16_t *r0, int len)
 {
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        const int ch = lane + 64 * half;
-        ld.a[half] = r0 ? load_chunk<FULL>(r0, ch, len) : zero;
-        ld.b[half] = r1 ? load_chunk<FULL>(r1, ch, len) : zero;
+        ld.a[half] = load_chunk<FULL>(r0, lane + 64 * half, len);
+        ld.b[half] = zero;
     }
 }
 
@@ -143,7 +226,7 @@ __device__ __forceinline__ void interleave_store(uint32_t *dst, const uint32_t (
     reinterpret_cast<uint4 *>(dst)[1] = o1;
 }
 
-// Writes two rows into the wave's staging tile as (row a | row b << 16) words at [c*32 + a'],
+// Writes two rows into the wave's staging tile as (row a | row b << 16) words at [c*ST_LD + a'],
 // multiplied elementwise by the gate rows when `gated`.
 __device__ __forceinline__ void stage_rows(uint32_t *stage, int lane, const RowLoad &x, const RowLoad &gt, bool gated)
 {
@@ -161,7 +244,7 @@ __device__ __forceinline__ void stage_rows(uint32_t *stage, int lane, const RowL
                 m[q] = mul_pack(m[q], gb[q]);
             }
         }
-        interleave_store(stage + ch * 8, r, m);
+        interleave_store(stage + (ch >> 2) * ST_LD + (ch & 3) * 8, r, m);
     }
 }
 
@@ -175,8 +258,8 @@ __device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int l
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int c0 = slot_index(kg, 2 * jj);
-            const uint32_t d0 = stage[c0 * 32 + 16 * m + l16];
-            const uint32_t d1 = stage[(c0 + 1) * 32 + 16 * m + l16];
+            const uint32_t d0 = stage[c0 * ST_LD + 16 * m + l16];
+            const uint32_t d1 = stage[(c0 + 1) * ST_LD + 16 * m + l16];
             pr.d[jj] = __builtin_amdgcn_perm(d1, d0, 0x05040100u);
             pi.d[jj] = __builtin_amdgcn_perm(d1, d0, 0x07060302u);
         }
@@ -187,23 +270,22 @@ __device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int l
 
 // Forward transform of spectrum columns i = 16*CH + lane%16:
 //   Z1[a,i] = sum_c x[c,a] F64[c,i];  Z1 *= w_2048^(i a);  Z2[k,i] = sum_a F32[k,a] Z1[a,i].
-// F holds F64[c][16*(CH%2) + lane%16]; columns 32..63 differ from it by (-1)^c (odd slots).
+// F holds F64[c][16*(CH%2) + lane%16]; columns 32..63 differ from it by (-1)^c, which the caller
+// has applied to the data operands (odd slots negated) for CH >= 2.
 // Result: rows k = 16m + 4kg + r in registers (z2[m][r]), column i on the lane.
 template <int CH, bool HAS_IM>
 __device__ __forceinline__ void forward_chunk(const Smem &sm, int l16, int kg, const bf16x8 (&xr)[2],
                                               const bf16x8 (&xi)[2], const COp &F, const COp (&G)[2],
                                               f32x4 (&z2r)[2], f32x4 (&z2i)[2])
 {
-    constexpr uint32_t odd = CH >= 2 ? 0x80000000u : 0u;   // (-1)^c on the constant's odd slots
-    const bf16x8 fr = flip(F.r, odd), fi = flip(F.i, odd), nfi = flip(F.i, odd ^ 0x80008000u);
     f32x4 zr[2], zi[2];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
-        zr[m] = mfma(xr[m], fr, (f32x4){0, 0, 0, 0});
-        zi[m] = mfma(xr[m], fi, (f32x4){0, 0, 0, 0});
+        zr[m] = mfma(xr[m], F.r, (f32x4){0, 0, 0, 0});
+        zi[m] = mfma(xr[m], F.i, (f32x4){0, 0, 0, 0});
         if (HAS_IM) {
-            zr[m] = mfma(xi[m], nfi, zr[m]);
-            zi[m] = mfma(xi[m], fr, zi[m]);
+            zr[m] = mfma(xi[m], F.ni, zr[m]);
+            zi[m] = mfma(xi[m], F.r, zi[m]);
         }
     }
     // twiddle: rows a = 16m + 4kg + r in registers, column i on the lane
@@ -221,12 +303,11 @@ __device__ __forceinline__ void forward_chunk(const Smem &sm, int l16, int kg, c
         }
     }
     const bf16x8 br = pack_tiles(zr[0], zr[1]), bi = pack_tiles(zi[0], zi[1]);
-    const bf16x8 nbi = neg_all(bi);
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         z2r[m] = mfma(G[m].r, br, (f32x4){0, 0, 0, 0});
         z2i[m] = mfma(G[m].i, br, (f32x4){0, 0, 0, 0});
-        z2r[m] = mfma(G[m].i, nbi, z2r[m]);
+        z2r[m] = mfma(G[m].ni, bi, z2r[m]);
         z2i[m] = mfma(G[m].r, bi, z2i[m]);
     }
 }
@@ -251,13 +332,12 @@ __device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16,
     }
     // third factor: W[i,a] = sum_k Y[i,k] conj(F32)[k,a]; Y's lane index i becomes the row index
     const bf16x8 ar = pack_tiles(zr[0], zr[1]), ai = pack_tiles(zi[0], zi[1]);
-    const bf16x8 nar = neg_all(ar);
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         f32x4 wr = mfma(ar, G[nt].r, (f32x4){0, 0, 0, 0});
         f32x4 wi = mfma(ai, G[nt].r, (f32x4){0, 0, 0, 0});
         wr = mfma(ai, G[nt].i, wr);
-        wi = mfma(nar, G[nt].i, wi);
+        wi = mfma(ar, G[nt].ni, wi);
         // conjugate twiddle: rows i = 16*CH + 4kg + r in registers, column a = 16nt + lane%16
         const float2 *tcol = &sm.tw[16 * CH + 4 * kg][16 * nt + l16];
 #pragma unroll
@@ -275,7 +355,10 @@ __device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16,
     }
 }
 
-template <bool FULL>
+// FULL: n == klen == 1024, every row load is unconditional.  GIN / GOUT: the gates are present.
+// Keeping the loads free of branches lets the compiler wait for exactly the load it needs
+// (k first, then u and g_in, g_out last) instead of draining all of them at once.
+template <bool FULL, bool GIN, bool GOUT>
 __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     const bf16_t *__restrict__ u, const bf16_t *__restrict__ k, const bf16_t *__restrict__ g_in,
     const bf16_t *__restrict__ g_out, bf16_t *__restrict__ y, int B, int H, int n, int klen)
@@ -288,54 +371,63 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     // work item = (channel h, group of 4 pairs); wave w of the group takes pair 4*group + w
     const int h = blockIdx.x % H;
     const int p = 4 * (blockIdx.x / H) + wave;
-    const int b0 = 2 * p;
-    const bool active = b0 < B, two = b0 + 1 < B;
-    const size_t row0 = ((size_t)b0 * H + h) * n, row1 = ((size_t)(b0 + 1) * H + h) * n;
+    const bool active = 2 * p < B, two = 2 * p + 1 < B;
+    // rows of this wave's pair; a missing row is replaced by a valid one so that the loads need no
+    // branch (its data is ignored: the imaginary part is forced to zero, the store is skipped)
+    const int b0 = active ? 2 * p : 0, b1 = two ? 2 * p + 1 : b0;
+    const size_t row0 = ((size_t)b0 * H + h) * n, row1 = ((size_t)b1 * H + h) * n;
 
-    // Everything this wave needs from HBM is requested before any set-up work.
-    RowLoad ldk, ldx, ldg, ldo;
-    load_rows<FULL>(ldk, lane, k + (size_t)h * klen, nullptr, klen);
-    if (active) {
-        load_rows<FULL>(ldx, lane, u + row0, two ? u + row1 : nullptr, n);
-        if (g_in) load_rows<FULL>(ldg, lane, g_in + row0, two ? g_in + row1 : nullptr, n);
-        if (g_out) load_rows<FULL>(ldo, lane, g_out + row0, two ? g_out + row1 : nullptr, n);
-    }
-
-    // tables: w_2048^(i*a) (i*a <= 63*31 < 2048) and w_64^e
-    for (int idx = tid; idx < N1 * N2; idx += 256) {
-        const int i = idx >> 5, a = idx & 31;
-        sm.tw[i][a] = hw_omega(i * a, NFFT);
-    }
-    if (tid < 64) sm.w64[tid] = hw_omega(tid, 64);
-    __syncthreads();
-
-    // per-lane constant operands: F64[slot][16t + l16] (= F64[16t + l16][slot]) and F32[16t + l16][slot]
+    MONARCH_PHASE_MARK(14);
+    MONARCH_PHASE_MARK(0);
+    // Constant tables first (they come from L2 and gate everything else), then the rows.
+    static_assert(sizeof(TwiddleTable) == (4 * 256 + 64) * sizeof(uint4), "twiddle copy assumes 1088 pieces");
+    const uint4 *tw_src = reinterpret_cast<const uint4 *>(&g_twiddles);
+    const uint4 tw0 = tw_src[tid], tw1 = tw_src[tid + 256], tw2 = tw_src[tid + 512], tw3 = tw_src[tid + 768];
+    const uint4 tw4 = tw_src[1024 + (tid & 63)];   // every wave fetches the same tail; wave 0 stores it
     COp F[2], G[2];
+    {
+        const uint4 *ops = reinterpret_cast<const uint4 *>(g_operands.v[lane]);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            F[t].r = __builtin_bit_cast(bf16x8, ops[2 * t]);
+            F[t].i = __builtin_bit_cast(bf16x8, ops[2 * t + 1]);
+            G[t].r = __builtin_bit_cast(bf16x8, ops[4 + 2 * t]);
+            G[t].i = __builtin_bit_cast(bf16x8, ops[5 + 2 * t]);
+        }
+    }
+    RowLoad ldk, ldx, ldg, ldo;
+    load_row<FULL>(ldk, lane, k + (size_t)h * klen, klen);
+    load_rows<FULL>(ldx, lane, u + row0, u + row1, n);
+
+    MONARCH_PHASE_MARK(1);
+    if (GIN) load_rows<FULL>(ldg, lane, g_in + row0, g_in + row1, n);
+    {
+        uint4 *dst = reinterpret_cast<uint4 *>(&sm.tw[0][0]);
+        dst[tid] = tw0;
+        dst[tid + 256] = tw1;
+        dst[tid + 512] = tw2;
+        dst[tid + 768] = tw3;
+        if (wave == 0) dst[1024 + lane] = tw4;
+    }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        Pack8 fr, fi, gr, gi;
-        const int row = 16 * t + l16;
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int s0 = slot_index(kg, 2 * jj);
-            const float2 f0 = sm.w64[(s0 * row) & 63], f1 = sm.w64[((s0 + 1) * row) & 63];
-            const float2 g0 = sm.w64[(2 * s0 * row) & 63], g1 = sm.w64[(2 * (s0 + 1) * row) & 63];
-            fr.d[jj] = pack_bf16(f0.x, f1.x);
-            fi.d[jj] = pack_bf16(f0.y, f1.y);
-            gr.d[jj] = pack_bf16(g0.x, g1.x);
-            gi.d[jj] = pack_bf16(g0.y, g1.y);
-        }
-        F[t].r = fr.v; F[t].i = fi.v;
-        G[t].r = gr.v; G[t].i = gi.v;
+        F[t].ni = neg_all(F[t].i);
+        G[t].ni = neg_all(G[t].i);
     }
+    __syncthreads();   // twiddle table complete
     const uint32_t lane_sign = (l16 & 1) ? 0x80008000u : 0u;   // (-1)^(row of this lane) on every slot
 
+    MONARCH_PHASE_MARK(2);
     // spectrum of the kernel: wave w transforms spectrum columns 16w .. 16w+15
     {
         stage_rows(stage, lane, ldk, ldk, false);
         __builtin_amdgcn_wave_barrier();
         bf16x8 xr[2], xi[2];
         read_stage_operands(stage, l16, kg, xr, xi);
+        if (wave >= 2) {   // spectrum columns 32..63: (-1)^c on the data (odd slots)
+            xr[0] = flip(xr[0], 0x80000000u);
+            xr[1] = flip(xr[1], 0x80000000u);
+        }
         f32x4 zr[2], zi[2];
         switch (wave) {
         case 0: forward_chunk<0, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
@@ -350,19 +442,28 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
             sm.kf_im[wave][m][lane] = make_float4(zi[m][0] * inv, zi[m][1] * inv, zi[m][2] * inv, zi[m][3] * inv);
         }
     }
+    MONARCH_PHASE_MARK(3);
+    if (GOUT) load_rows<FULL>(ldo, lane, g_out + row0, g_out + row1, n);
     __syncthreads();   // k_f complete
+    MONARCH_PHASE_MARK(4);
     if (!active) return;
+    if (!two) {   // single row: its partner's data was only a placeholder
+        const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+        ldx.b[0] = ldx.b[1] = zero;
+    }
 
     {
         {
             __builtin_amdgcn_wave_barrier();
-            stage_rows(stage, lane, ldx, ldg, g_in != nullptr);
+            stage_rows(stage, lane, ldx, ldg, GIN);
             __builtin_amdgcn_wave_barrier();
             bf16x8 xr[2], xi[2];
             read_stage_operands(stage, l16, kg, xr, xi);
             __builtin_amdgcn_wave_barrier();
             // the tile is free again: park the output gates in it, same word layout
-            if (g_out) stage_rows(stage, lane, ldo, ldo, false);
+            MONARCH_PHASE_MARK(5);
+            if (GOUT) stage_rows(stage, lane, ldo, ldo, false);
+            MONARCH_PHASE_MARK(6);
 
             // B operands of the last factor: [kstep = contraction rows 32ks..32ks+31][column tile nt]
             Pack8 wr_op[2][2], wi_op[2][2];
@@ -372,11 +473,18 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                 forward_chunk<0, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
                 inverse_chunk<0>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
             }
+            MONARCH_PHASE_MARK(7);
             __builtin_amdgcn_sched_barrier(0);
             {
                 f32x4 zr[2], zi[2];
                 forward_chunk<1, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
                 inverse_chunk<1>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
+            }
+            // spectrum columns 32..63 see F64[c][32 + i'] = (-1)^c F64[c][i']: negate the odd slots of the data
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                xr[m] = flip(xr[m], 0x80000000u);
+                xi[m] = flip(xi[m], 0x80000000u);
             }
             __builtin_amdgcn_sched_barrier(0);
             {
@@ -390,39 +498,41 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                 forward_chunk<3, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
                 inverse_chunk<3>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
             }
+            MONARCH_PHASE_MARK(8);
             __builtin_amdgcn_sched_barrier(0);
             // last factor: y[c,a] = sum_i conj(F64)[c,i] W[i,a], c < 32 only (truncation to n).
             // Contraction rows i >= 32 use F64[c][32+i'] = (-1)^c F64[c][i'], c being this lane's row.
             f32x4 yr[2][2], yi[2][2];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-                const bf16x8 hr = flip(F[mt].r, lane_sign), hi = flip(F[mt].i, lane_sign);
+                const bf16x8 hr = flip(F[mt].r, lane_sign), hi = flip(F[mt].i, lane_sign), nhi = flip(F[mt].ni, lane_sign);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
                     f32x4 ar = mfma(F[mt].r, wr_op[0][nt].v, (f32x4){0, 0, 0, 0});
                     f32x4 ai = mfma(F[mt].r, wi_op[0][nt].v, (f32x4){0, 0, 0, 0});
                     ar = mfma(F[mt].i, wi_op[0][nt].v, ar);
-                    ai = mfma(F[mt].i, neg_all(wr_op[0][nt].v), ai);
+                    ai = mfma(F[mt].ni, wr_op[0][nt].v, ai);
                     ar = mfma(hr, wr_op[1][nt].v, ar);
                     ai = mfma(hr, wi_op[1][nt].v, ai);
                     ar = mfma(hi, wi_op[1][nt].v, ar);
-                    ai = mfma(hi, neg_all(wr_op[1][nt].v), ai);
+                    ai = mfma(nhi, wr_op[1][nt].v, ai);
                     yr[mt][nt] = ar;
                     yi[mt][nt] = ai;
                 }
             }
+            MONARCH_PHASE_MARK(9);
             // rows c = 16mt + 4kg + r, column a = 16nt + l16: gate in fp32, round once, park in the
             // staging tile (all gate words are read before the first result is written)
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_wave_barrier();
             uint32_t gw[2][2][4];
-            if (g_out) {
+            if (GOUT) {
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) gw[mt][nt][r] = stage[(16 * mt + 4 * kg + r) * 32 + 16 * nt + l16];
+                        for (int r = 0; r < 4; ++r) gw[mt][nt][r] = stage[(16 * mt + 4 * kg + r) * ST_LD + 16 * nt + l16];
             }
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
@@ -431,19 +541,20 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float v0 = yr[mt][nt][r], v1 = yi[mt][nt][r];
-                        if (g_out) {
+                        if (GOUT) {
                             v0 *= bf16_lo(gw[mt][nt][r]);
                             v1 *= bf16_hi(gw[mt][nt][r]);
                         }
-                        stage[(16 * mt + 4 * kg + r) * 32 + 16 * nt + l16] = pack_bf16(v0, v1);
+                        stage[(16 * mt + 4 * kg + r) * ST_LD + 16 * nt + l16] = pack_bf16(v0, v1);
                     }
             __builtin_amdgcn_wave_barrier();
+            MONARCH_PHASE_MARK(10);
             // coalesced stores: lane takes chunks lane and lane+64 of both rows
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int ch = lane + 64 * half;
                 if (!FULL && ch * 8 >= n) continue;
-                const uint4 *src = reinterpret_cast<const uint4 *>(stage + ch * 8);
+                const uint4 *src = reinterpret_cast<const uint4 *>(stage + (ch >> 2) * ST_LD + (ch & 3) * 8);
                 const uint4 s0 = src[0], s1 = src[1];
                 const uint32_t d[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
                 uint32_t re[4], im[4];
@@ -455,11 +566,20 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                 *reinterpret_cast<uint4 *>(y + row0 + ch * 8) = make_uint4(re[0], re[1], re[2], re[3]);
                 if (two) *reinterpret_cast<uint4 *>(y + row1 + ch * 8) = make_uint4(im[0], im[1], im[2], im[3]);
             }
+            MONARCH_PHASE_MARK(11);
+            MONARCH_PHASE_MARK(15);
         }
     }
 }
 
 }  // namespace c2048
+
+#ifdef MONARCH_PHASE_CLOCKS
+extern "C" int monarch_debug_set_phase_clocks(long long *buf)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(c2048::g_phase_clocks), &buf, sizeof(buf));
+}
+#endif
 
 bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt)
 {
@@ -474,12 +594,22 @@ int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const 
     const int64_t groups = ((B + 1) / 2 + 3) / 4;
     const int64_t grid = (int64_t)H * groups;
     if (grid > 0x7fffffffLL) return fail(MONARCH_ESHAPE, "B*H too large for one launch");
-    if (n == c2048::NHALF && klen == c2048::NHALF)
-        hipLaunchKernelGGL(c2048::conv2048_bf16_kernel<true>, dim3((unsigned)grid), dim3(256), 0, s, (const bf16_t *)u,
-                           (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen);
-    else
-        hipLaunchKernelGGL(c2048::conv2048_bf16_kernel<false>, dim3((unsigned)grid), dim3(256), 0, s, (const bf16_t *)u,
-                           (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen);
+    const bool full = n == c2048::NHALF && klen == c2048::NHALF;
+#define MONARCH_LAUNCH_C2048(FULLV, GINV, GOUTV)                                                                  \
+    hipLaunchKernelGGL((c2048::conv2048_bf16_kernel<FULLV, GINV, GOUTV>), dim3((unsigned)grid), dim3(256), 0, s,  \
+                       (const bf16_t *)u, (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out,        \
+                       (bf16_t *)y, B, H, n, klen)
+    switch ((full ? 4 : 0) | (g_in ? 2 : 0) | (g_out ? 1 : 0)) {
+    case 7: MONARCH_LAUNCH_C2048(true, true, true); break;
+    case 6: MONARCH_LAUNCH_C2048(true, true, false); break;
+    case 5: MONARCH_LAUNCH_C2048(true, false, true); break;
+    case 4: MONARCH_LAUNCH_C2048(true, false, false); break;
+    case 3: MONARCH_LAUNCH_C2048(false, true, true); break;
+    case 2: MONARCH_LAUNCH_C2048(false, true, false); break;
+    case 1: MONARCH_LAUNCH_C2048(false, false, true); break;
+    default: MONARCH_LAUNCH_C2048(false, false, false); break;
+    }
+#undef MONARCH_LAUNCH_C2048
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
