@@ -1,0 +1,37 @@
+"""The fused convolution launched from a replayed HIP graph gives the eager result every time."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import announce, dev
+from paper_2310_12109_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def test_graph_replays_match_eager():
+    from paper_2310_12109_amd import binding
+    announce("conv graph replay")
+    w = workloads.conv_inputs(4, 16, 1024, seed=3, gates="normal", bf16=True)
+    t = {k: dev(v, True) for k, v in w.items()}
+    eager = binding.monarch_causal_conv(t["u"], t["k"], t["g_in"], t["g_out"], (64, 32))
+    torch.cuda.synchronize()
+    want = eager.clone()
+    out = torch.empty_like(eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.monarch_causal_conv(t["u"], t["k"], t["g_in"], t["g_out"], (64, 32), out=out)   # warm up on this stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.monarch_causal_conv(t["u"], t["k"], t["g_in"], t["g_out"], (64, 32), out=out)
+    for rep in range(4):
+        out.zero_()
+        # eager work and a synchronisation between the replays
+        other = binding.monarch_causal_conv(t["g_in"], t["k"], None, None, (64, 32))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep} differs from the eager result"
+        assert other.shape == want.shape
