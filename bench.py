@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the timed kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what
+# the same counter reads for a plain copy (0.5 and 1.0): profiles/conv2048_bf16_c2_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = int((19388.5 / 0.5 + 12288.0 / 1.0) * 1024)
 WORKLOAD = "c2_conv"
 
 
@@ -110,7 +113,7 @@ def main():
                    "B": B, "H": H, "n": n, "nfft": int(np.prod(factors)), "factors": list(factors),
                    "buffer_sets": nsets, "launch": "hip graph of %d steps, replayed" % nsets, "sequence_tokens_per_s": B * n / (ms_per_step * 1e-3)},
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
                      "kernel": "conv2048_bf16_kernel", "algorithmic_bytes_per_launch": bytes_per_step,
                      "executed_tflops": flops / (ms_per_step * 1e-3) / 1e12},
         "host_wall_ms_per_step": wall_ms / args.steps,
