@@ -385,8 +385,9 @@ static int mlp_check(int64_t tokens, int d, int d_hidden, int nb, int order, int
 size_t monarch_mlp_workspace_bytes(int64_t tokens, int d, int d_hidden, int nb, int order,
                                    int mid1, int mid2, monarch_dtype dt)
 {
-    (void)d; (void)nb; (void)order; (void)mid1; (void)mid2; (void)dt;
+    (void)mid1; (void)mid2;
     if (tokens <= 0 || d_hidden <= 0) return 0;
+    if (order == 1 && nb > 0 && mlp_mfma_order1_supported(d, d_hidden, nb, dt)) return 0;   // hidden stays on chip
     return align_up((size_t)tokens * d_hidden * sizeof(float), 256);   // hidden activations, fp32
 }
 
@@ -412,6 +413,9 @@ int monarch_mlp(const void *x, void *y, int64_t tokens, int d, int d_hidden, int
     if (need && (!ws || ws_bytes < need))
         return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
     hipStream_t s = (hipStream_t)stream;
+
+    if (order == 1 && mlp_mfma_order1_supported(d, d_hidden, nb, dt))
+        return launch_mlp_mfma_order1(x, y, tokens, d, d_hidden, nb, W1_R, b1, W2_R, b2, act, s);
 
     // Layer 1 writes the activated hidden vector (fp32) to the workspace, layer 2 reads it.
     if (order == 1) {

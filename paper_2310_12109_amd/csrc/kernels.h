@@ -44,4 +44,10 @@ bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monar
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                           int B, int H, int n, int klen, hipStream_t s);
 
+// Block-diagonal MLP (order 1), bf16, d/nb a multiple of 32 up to 192, d_hidden/nb a multiple of 32.
+bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt);
+int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb,
+                           const void *W1, const void *b1, const void *W2, const void *b2, int act,
+                           hipStream_t s);
+
 }  // namespace monarch

@@ -1,0 +1,243 @@
+// Fused block-diagonal MLP (order 1: the M2-BERT dimension mixer), bf16 I/O, fp32 accumulate:
+//   y[t, blk] = W2_blk * act(W1_blk * x[t, blk] + b1_blk) + b2_blk        (Sec. 3.2, Eq. 3)
+//
+// One workgroup (4 waves, one per SIMD, up to 512 registers each) takes 64 tokens of one block.
+// Everything is computed transposed so that tokens sit on the MFMA column (lane) index:
+//   H^T[hidden, token] = W1[hidden, din] * X^T[din, token]      A = W1 rows, B = x rows
+//   Y^T[out,    token] = W2[out, hidden] * H^T[hidden, token]   A = W2 rows, B = the accumulators of H^T
+// Both weight operands and the x operand are plain 16-byte global loads (8 consecutive inputs of one
+// row), and the activated hidden tile re-enters the second GEMM straight from the accumulators (two
+// stacked 16x16 tiles = one K=32 operand), so the hidden vector never exists in LDS or HBM.
+// The waves split the hidden units (chunks of 32, wave w takes chunks w, w+4, ...): every weight is
+// fetched once per workgroup; the four partial Y tiles are summed with LDS float atomics, then written
+// with coalesced 16-byte stores.
+#include "kernels.h"
+
+namespace monarch {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+namespace mlp1 {
+
+constexpr int TOK = 64;   // tokens per workgroup (4 column tiles of 16)
+
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    bf16x2 p = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+union Pack8 {
+    bf16x8 v;
+    uint32_t d[4];
+    uint4 q;
+};
+
+// GELU(z) = z * Phi(z) with Phi(z) - 1/2 = z * q(z^2) fitted on |z| <= 4 (|error of Phi| < 1.3e-4,
+// far below bf16 resolution of the result); beyond 4 the argument is clamped (Phi = 1 or 0 to 3e-5).
+__device__ __forceinline__ float gelu_fast(float z)
+{
+    const float zc = fminf(fmaxf(z, -4.0f), 4.0f);
+    const float s = zc * zc;
+    float q = 2.68676641e-08f;
+    q = fmaf(q, s, -1.82473021e-06f);
+    q = fmaf(q, s, 5.284952499e-05f);
+    q = fmaf(q, s, -0.0008661364928f);
+    q = fmaf(q, s, 0.009053180024f);
+    q = fmaf(q, s, -0.06526927028f);
+    q = fmaf(q, s, 0.3984592387f);
+    return z * fmaf(zc, q, 0.5f);
+}
+
+template <int ACT>
+__device__ __forceinline__ float act_fast(float z)
+{
+    if (ACT == 2) return gelu_fast(z);
+    if (ACT == 1) return fmaxf(z, 0.0f);
+    return z;
+}
+
+// KS = din / 32 (K steps of the first GEMM); din / 16 row tiles of the second GEMM.
+template <int KS, int ACT>
+__global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
+    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
+    const bf16_t *__restrict__ b2)
+{
+    constexpr int DIN = 32 * KS, MT = 2 * KS, LD = DIN + 1;   // LD: padded row of the reduction tile
+    extern __shared__ float ytile[];                             // [TOK][LD]
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int blk = blockIdx.y;
+    const int64_t t0 = (int64_t)blockIdx.x * TOK;
+    const int dh = d_hidden / nb;   // hidden units of this block
+
+    for (int idx = tid; idx < TOK * LD; idx += 256) ytile[idx] = 0.0f;
+
+    // B operands of the first GEMM: lane (token 16nt + l16, kg) holds x[token][blk*DIN + 32ks + 8kg .. +7]
+    Pack8 xop[4][KS];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        int64_t t = t0 + 16 * nt + l16;
+        if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
+        const bf16_t *row = x + t * d + blk * DIN + 8 * kg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xop[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
+    }
+    f32x4 acc[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f32x4){0, 0, 0, 0};
+
+    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    // Row r of accumulator tile mt in lane group kg is accumulator row 16mt + 4kg + r.  The hidden unit
+    // given to first-GEMM row (mt, l16) is chosen so that the 8 operand slots of a lane group are 8
+    // consecutive hidden units (one 16-byte load of W2): unit(mt, row) = 8*(row/4) + 4*mt + row%4.
+    const int unit_of_lane[2] = {8 * (l16 >> 2) + (l16 & 3), 8 * (l16 >> 2) + 4 + (l16 & 3)};
+
+    for (int j = wave; j < dh / 32; j += 4) {
+        const int h0 = 32 * j;   // first hidden unit of the chunk
+        // Everything the chunk needs is requested up front: biases of the 8 hidden units this lane
+        // group's accumulator rows carry (h0 + 8kg .. +7), both W1 row tiles, all W2 row tiles.
+        uint4 braw = make_uint4(0u, 0u, 0u, 0u);
+        if (b1) braw = *reinterpret_cast<const uint4 *>(b1 + (size_t)blk * dh + h0 + 8 * kg);
+        Pack8 w1[2][KS], w2[MT];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const bf16_t *wrow = W1b + (size_t)(h0 + unit_of_lane[mt]) * DIN + 8 * kg;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) w1[mt][ks].q = *reinterpret_cast<const uint4 *>(wrow + 32 * ks);
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            w2[mt].q = *reinterpret_cast<const uint4 *>(W2b + (size_t)(16 * mt + l16) * dh + h0 + 8 * kg);
+
+        // first GEMM: H^T chunk (32 hidden x 64 tokens)
+        f32x4 hacc[2][4];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                f32x4 a = {0, 0, 0, 0};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) a = mfma(w1[mt][ks].v, xop[nt][ks].v, a);
+                hacc[mt][nt] = a;
+            }
+        // bias + activation on accumulator rows: tile mt, register r of lane group kg is hidden unit
+        // h0 + 8kg + 4mt + r; then two stacked tiles become one K=32 operand (slot 4mt + r)
+        Pack8 hop[4];
+        {
+            const uint32_t bw[4] = {braw.x, braw.y, braw.z, braw.w};
+            float bias[2][4];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t w = bw[2 * mt + (r >> 1)];
+                    bias[mt][r] = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+                }
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = act_fast<ACT>(hacc[mt][nt][r] + bias[mt][r]);
+                    hop[nt].d[2 * mt] = pack_bf16(v[0], v[1]);
+                    hop[nt].d[2 * mt + 1] = pack_bf16(v[2], v[3]);
+                }
+        }
+        // second GEMM: Y^T += W2[:, chunk] * H^T chunk; A operand = 8 consecutive hidden units of one output row
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
+    }
+
+    // sum the four waves' partial tiles: ytile[token][out] += acc (row = out feature 16mt + 4kg + r)
+    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                atomicAdd(&ytile[(16 * nt + l16) * LD + 16 * mt + 4 * kg + r], acc[mt][nt][r]);
+    __syncthreads();
+
+    // bias, rounding, coalesced stores: 8 consecutive features per thread
+    constexpr int PIECES = DIN / 8;   // 16-byte pieces per token
+    for (int idx = tid; idx < TOK * PIECES; idx += 256) {
+        const int t = idx / PIECES, o0 = (idx - t * PIECES) * 8;
+        if (t0 + t >= tokens) continue;
+        uint4 b2raw = make_uint4(0u, 0u, 0u, 0u);
+        if (b2) b2raw = *reinterpret_cast<const uint4 *>(b2 + (size_t)blk * DIN + o0);
+        const uint32_t b2w[4] = {b2raw.x, b2raw.y, b2raw.z, b2raw.w};
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t w = b2w[e >> 1];
+            v[e] = ytile[t * LD + o0 + e] + __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+        }
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]);
+        o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]);
+        o.w = pack_bf16(v[6], v[7]);
+        *reinterpret_cast<uint4 *>(y + (t0 + t) * d + blk * DIN + o0) = o;
+    }
+}
+
+}  // namespace mlp1
+
+bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
+{
+    if (dt != MONARCH_BF16 || d % nb || d_hidden % nb) return false;
+    const int din = d / nb, dh = d_hidden / nb;
+    return din % 32 == 0 && din >= 32 && din <= 192 && dh % 32 == 0 && d % 8 == 0;
+}
+
+int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb,
+                           const void *W1, const void *b1, const void *W2, const void *b2, int act,
+                           hipStream_t s)
+{
+    const int din = d / nb;
+    const int64_t tiles = (tokens + mlp1::TOK - 1) / mlp1::TOK;
+    if (tiles > 0x7fffffffLL || nb > 65535) return fail(MONARCH_ESHAPE, "too many tokens or blocks for one launch");
+    const dim3 grid((unsigned)tiles, (unsigned)nb);
+    const size_t lds = (size_t)mlp1::TOK * (din + 1) * sizeof(float);
+#define MONARCH_LAUNCH_MLP1(KSV, ACTV)                                                                          \
+    hipLaunchKernelGGL((mlp1::mlp_order1_kernel<KSV, ACTV>), grid, dim3(256), lds, s, (const bf16_t *)x,        \
+                       (bf16_t *)y, tokens, d, d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1,           \
+                       (const bf16_t *)W2, (const bf16_t *)b2)
+#define MONARCH_LAUNCH_MLP1_ACT(KSV)                     \
+    do {                                                 \
+        if (act == 2) MONARCH_LAUNCH_MLP1(KSV, 2);       \
+        else if (act == 1) MONARCH_LAUNCH_MLP1(KSV, 1);  \
+        else MONARCH_LAUNCH_MLP1(KSV, 0);                \
+    } while (0)
+    switch (din / 32) {
+    case 1: MONARCH_LAUNCH_MLP1_ACT(1); break;
+    case 2: MONARCH_LAUNCH_MLP1_ACT(2); break;
+    case 3: MONARCH_LAUNCH_MLP1_ACT(3); break;
+    case 4: MONARCH_LAUNCH_MLP1_ACT(4); break;
+    case 5: MONARCH_LAUNCH_MLP1_ACT(5); break;
+    default: MONARCH_LAUNCH_MLP1_ACT(6); break;
+    }
+#undef MONARCH_LAUNCH_MLP1_ACT
+#undef MONARCH_LAUNCH_MLP1
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+}  // namespace monarch
