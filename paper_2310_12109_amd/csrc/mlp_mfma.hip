@@ -9,8 +9,9 @@
 // row), and the activated hidden tile re-enters the second GEMM straight from the accumulators (two
 // stacked 16x16 tiles = one K=32 operand), so the hidden vector never exists in LDS or HBM.
 // The waves split the hidden units (chunks of 32, wave w takes chunks w, w+4, ...): every weight is
-// fetched once per workgroup; the four partial Y tiles are summed with LDS float atomics, then written
-// with coalesced 16-byte stores.
+// fetched once per workgroup; the four partial Y tiles are summed through LDS in two rounds of plain
+// 16-byte stores and loads (waves 2,3 -> 0,1, then 1 -> 0; LDS float atomics are an order of magnitude
+// slower), then written with coalesced 16-byte stores.
 #include "kernels.h"
 
 namespace monarch {
@@ -71,16 +72,17 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
     const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
     const bf16_t *__restrict__ b2)
 {
-    constexpr int DIN = 32 * KS, MT = 2 * KS, LD = DIN + 1;   // LD: padded row of the reduction tile
-    extern __shared__ float ytile[];                             // [TOK][LD]
+    constexpr int DIN = 32 * KS, MT = 2 * KS, LD = DIN + 1;   // LD: padded row of the output tile
+    constexpr int PART = MT * 4 * 64;                            // f32x4 pieces of one wave's partial tile
+    extern __shared__ f32x4 lds_raw[];
+    f32x4 *part = lds_raw;                                       // [2][PART] partial tiles, [piece][lane]
+    float *ytile = reinterpret_cast<float *>(lds_raw + 2 * PART);   // [TOK][LD] summed tile
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
     const int blk = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * TOK;
     const int dh = d_hidden / nb;   // hidden units of this block
-
-    for (int idx = tid; idx < TOK * LD; idx += 256) ytile[idx] = 0.0f;
 
     // B operands of the first GEMM: lane (token 16nt + l16, kg) holds x[token][blk*DIN + 32ks + 8kg .. +7]
     Pack8 xop[4][KS];
@@ -164,15 +166,35 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
             for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
     }
 
-    // sum the four waves' partial tiles: ytile[token][out] += acc (row = out feature 16mt + 4kg + r)
+    // Sum the four waves' partial tiles.  Piece (mt, nt) of a wave sits at part[slot][(mt*4+nt)*64 + lane].
+    auto spill = [&](int slot) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) part[slot * PART + (mt * 4 + nt) * 64 + lane] = acc[mt][nt];
+    };
+    auto absorb = [&](int slot) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] += part[slot * PART + (mt * 4 + nt) * 64 + lane];
+    };
+    if (wave >= 2) spill(wave - 2);
     __syncthreads();
+    if (wave < 2) absorb(wave);
+    __syncthreads();
+    if (wave == 1) spill(0);
+    __syncthreads();
+    if (wave == 0) {
+        absorb(0);
+        // row = out feature 16mt + 4kg + r, column = token 16nt + l16  ->  ytile[token][feature]
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+            for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                atomicAdd(&ytile[(16 * nt + l16) * LD + 16 * mt + 4 * kg + r], acc[mt][nt][r]);
+                for (int r = 0; r < 4; ++r) ytile[(16 * nt + l16) * LD + 16 * mt + 4 * kg + r] = acc[mt][nt][r];
+    }
     __syncthreads();
 
     // bias, rounding, coalesced stores: 8 consecutive features per thread
@@ -215,11 +237,17 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
     const int64_t tiles = (tokens + mlp1::TOK - 1) / mlp1::TOK;
     if (tiles > 0x7fffffffLL || nb > 65535) return fail(MONARCH_ESHAPE, "too many tokens or blocks for one launch");
     const dim3 grid((unsigned)tiles, (unsigned)nb);
-    const size_t lds = (size_t)mlp1::TOK * (din + 1) * sizeof(float);
+    // two partial tiles (din/16 row tiles x 4 column tiles x 64 lanes x 16 B) + the summed [64][din+1] tile
+    const size_t lds = (size_t)2 * (din / 16) * 4 * 64 * 16 + (size_t)mlp1::TOK * (din + 1) * sizeof(float);
 #define MONARCH_LAUNCH_MLP1(KSV, ACTV)                                                                          \
-    hipLaunchKernelGGL((mlp1::mlp_order1_kernel<KSV, ACTV>), grid, dim3(256), lds, s, (const bf16_t *)x,        \
-                       (bf16_t *)y, tokens, d, d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1,           \
-                       (const bf16_t *)W2, (const bf16_t *)b2)
+    do {                                                                                                        \
+        auto kern = mlp1::mlp_order1_kernel<KSV, ACTV>;                                                         \
+        if (lds > 64 * 1024)                                                                                    \
+            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                  (int)lds));                                                   \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d, d_hidden,  \
+                           nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2, (const bf16_t *)b2);  \
+    } while (0)
 #define MONARCH_LAUNCH_MLP1_ACT(KSV)                     \
     do {                                                 \
         if (act == 2) MONARCH_LAUNCH_MLP1(KSV, 2);       \
