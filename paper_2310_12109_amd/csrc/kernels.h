@@ -37,6 +37,12 @@ struct FftPass {
 };
 int launch_fft_pass(const FftPass &p, hipStream_t s);
 
+// ---- fp32 MFMA Monarch multiply --------------------------------------------------------------
+
+// Square order-2 Monarch with 16 blocks of 16 x 16 (N = 256), fp32 storage and arithmetic.
+bool matmul_mfma_b16_supported(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in, monarch_dtype dt);
+int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y, int64_t batch, hipStream_t s);
+
 // ---- fused bf16 MFMA kernels ---------------------------------------------------------------
 
 // nfft = 2048 = 64 x 32, n <= 1024, klen <= 1024 (both multiples of 8), bf16 I/O.
