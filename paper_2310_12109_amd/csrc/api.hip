@@ -176,6 +176,9 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
     const size_t buf = align_up(spec_bytes, 256);
     void *bufs[2] = {ws, (char *)ws + buf};
     const void *cur = src;
+    // bf16 transforms with MFMA-sized factors run on the matrix cores and keep the rows packed as
+    // bf16 pairs between passes; everything else takes the fp32 passes.
+    const bool mf = fft_mfma_supported(N, factors, nf, dt);
     for (int q = 0; q < nf; ++q) {
         FftPass p = blank_pass();
         set_pass_geometry(p, N, factors, nf, q);
@@ -186,7 +189,7 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
         if (q == 0)
             p.load = inverse ? LD_C32_CONJ : (is_real ? LD_REAL : LD_CPLX);
         else
-            p.load = LD_C32;
+            p.load = mf ? LD_C16 : LD_C32;
         if (q == nf - 1) {
             p.out = dst;
             if (!inverse) p.store = ST_C32_NATURAL;
@@ -196,9 +199,9 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
             }
         } else {
             p.out = bufs[q & 1];
-            p.store = ST_C32;
+            p.store = mf ? ST_C16 : ST_C32;
         }
-        rc = launch_fft_pass(p, s);
+        rc = mf ? launch_fft_pass_mfma(p, s) : launch_fft_pass(p, s);
         if (rc) return rc;
         cur = p.out;
     }
@@ -263,6 +266,80 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
     return 2 * buf + kf;
 }
 
+// Multi-pass convolution on the matrix cores (bf16, factors 16..128).  The kernel is real, so two
+// real rows of the same channel are transformed as one complex row (re = batch 2 b2, im = batch
+// 2 b2 + 1): conv(a + i b, k) = conv(a, k) + i conv(b, k).  Rows travel between passes as packed
+// bf16 pairs; the spectrum of k is kept in fp32.
+static int conv_passes_mfma(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                            int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                            void *const bufs[2], float2 *kf, hipStream_t s)
+{
+    const bool paired = B >= 2;
+    const int64_t crows = paired ? (int64_t)((B + 1) / 2) * H : (int64_t)B * H;
+    const void *cur = nullptr;
+    int rc;
+    for (int which = 0; which < 2; ++which) {   // 0: k_f = F k', 1: u_f = F (g_in o u)'
+        cur = which == 0 ? k : u;
+        for (int q = 0; q < nf; ++q) {
+            FftPass p = blank_pass();
+            set_pass_geometry(p, nfft, factors, nf, q);
+            p.rows = which == 0 ? H : crows;
+            p.dt = MONARCH_BF16;
+            p.in = cur;
+            p.H = H;
+            p.real_rows = (int64_t)B * H;
+            if (q == 0) {
+                p.load = which == 1 && paired ? LD_REAL_PAIR : LD_REAL;
+                p.n_valid = which == 0 ? klen : n;
+                p.gate = which == 0 ? nullptr : g_in;
+            } else {
+                p.load = LD_C16;
+            }
+            if (q == nf - 1) {
+                p.store = which == 0 ? ST_C32_NATURAL : ST_C16_NATURAL;
+                p.out = which == 0 ? (void *)kf : bufs[q & 1];
+            } else {
+                p.store = ST_C16;
+                p.out = bufs[q & 1];
+            }
+            rc = launch_fft_pass_mfma(p, s);
+            if (rc) return rc;
+            cur = p.out;
+        }
+    }
+    // y = Re / Im of F^-1 (k_f o u_f), first n entries, times g_out:  F^-1 z = conj(F conj(z)) / N.
+    const int first_out = (cur == bufs[0]) ? 1 : 0;
+    for (int q = 0; q < nf; ++q) {
+        FftPass p = blank_pass();
+        set_pass_geometry(p, nfft, factors, nf, q);
+        p.rows = crows;
+        p.dt = MONARCH_BF16;
+        p.in = cur;
+        p.H = H;
+        p.real_rows = (int64_t)B * H;
+        if (q == 0) {
+            p.load = LD_C16_CONJ_MULK;
+            p.kf = kf;
+        } else {
+            p.load = LD_C16;
+        }
+        if (q == nf - 1) {
+            p.store = paired ? ST_REAL_PAIR : ST_REAL_SCALE_GATE;
+            p.out = y;
+            p.gate = g_out;
+            p.n_valid = n;
+            p.scale = 1.0f / (float)nfft;
+        } else {
+            p.store = ST_C16;
+            p.out = bufs[(first_out + q) & 1];
+        }
+        rc = launch_fft_pass_mfma(p, s);
+        if (rc) return rc;
+        cur = p.out;
+    }
+    return MONARCH_OK;
+}
+
 int monarch_causal_conv(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                         int B, int H, int n, int klen, int nfft, const int *factors, int nf,
                         int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
@@ -292,6 +369,9 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
     const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
     void *bufs[2] = {ws, (char *)ws + buf};
     float2 *kf = (float2 *)((char *)ws + 2 * buf);
+
+    if (fft_mfma_supported(nfft, factors, nf, dt))
+        return conv_passes_mfma(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, bufs, kf, s);
 
     // 1. k_f = F k'  (H rows), staged through the row buffers.
     // 2. u_f = F (g_in o u)'  (B*H rows), left in natural order in one of the row buffers.

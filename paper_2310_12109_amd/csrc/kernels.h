@@ -16,8 +16,12 @@ int launch_matmul_generic(const void *x, const void *R, const void *L, const voi
 // Largest d_in/d_out + d_mid the generic kernel can hold on chip.
 bool matmul_generic_fits(int d_in, int d_mid, int d_out);
 
-enum FftLoad { LD_C32 = 0, LD_C32_CONJ = 1, LD_C32_CONJ_MULK = 2, LD_REAL = 3, LD_CPLX = 4 };
-enum FftStore { ST_C32 = 0, ST_C32_NATURAL = 1, ST_CPLX_CONJ_SCALE = 2, ST_REAL_SCALE_GATE = 3 };
+// C32: complex fp32 (re, im); C16: complex as a packed bf16 pair (MFMA passes only); REAL / CPLX: the
+// caller's element type.  *_PAIR: two real rows of one channel travel as one complex row (MFMA only).
+enum FftLoad { LD_C32 = 0, LD_C32_CONJ = 1, LD_C32_CONJ_MULK = 2, LD_REAL = 3, LD_CPLX = 4,
+               LD_C16 = 5, LD_C16_CONJ_MULK = 6, LD_REAL_PAIR = 7 };
+enum FftStore { ST_C32 = 0, ST_C32_NATURAL = 1, ST_CPLX_CONJ_SCALE = 2, ST_REAL_SCALE_GATE = 3,
+                ST_C16 = 4, ST_C16_NATURAL = 5, ST_REAL_PAIR = 6 };
 
 struct FftPass {
     const void *in;      // see FftLoad
@@ -30,12 +34,18 @@ struct FftPass {
     int nf;              // number of factors of the whole transform and the factors themselves
     int factors[3];
     int n_valid;         // LD_REAL: entries at positions >= n_valid are zero; ST_REAL: only t < n_valid is stored
-    int H;               // LD_C32_CONJ_MULK: row r uses kf row r % H
+    int H;               // *_CONJ_MULK: row r uses kf row r % H; *_PAIR: complex row b2*H + h packs real rows (2 b2)*H + h, (2 b2 + 1)*H + h
+    int64_t real_rows;   // *_PAIR: number of real rows (the last complex rows may have no second member)
     float scale;         // store scale (1/N for the inverse)
     int load, store;
     monarch_dtype dt;    // element type of typed loads/stores
 };
 int launch_fft_pass(const FftPass &p, hipStream_t s);
+
+// Same pass on the matrix cores: bf16 operands, fp32 accumulation, factors 16/32/64/128, every pass
+// but the last storing ST_C16 and every pass but the first loading LD_C16.
+bool fft_mfma_supported(int N, const int *factors, int nf, monarch_dtype dt);
+int launch_fft_pass_mfma(const FftPass &p, hipStream_t s);
 
 // ---- fp32 MFMA Monarch multiply --------------------------------------------------------------
 

@@ -108,7 +108,8 @@ def test_conv_rejects_bad_arguments(lib):
     assert call(klen=4096, causal=0) == ESHAPE
     assert call(causal=2) == EINVAL
     assert call(dt=2) == EDTYPE
-    assert call(ws=None, wsb=0) == EWORKSPACE
+    # order 2 keeps the hidden activations in the workspace (the fused order-1 kernel needs none)
+    assert call(order=2, w1l=FAKE, w2l=FAKE, ws=None, wsb=0) == EWORKSPACE
     assert call(wsb=64) == EWORKSPACE
     assert call(y=FAKE) == EINVAL                        # y aliases u
     assert lib.monarch_causal_conv_workspace_bytes(8, 4, 1024, 1024, 2048, fac, 2, 0) > 0
@@ -130,6 +131,7 @@ def test_mlp_rejects_bad_arguments(lib):
     assert call(order=1, w1l=FAKE) == EINVAL
     assert call(order=2, w1l=FAKE, w2l=FAKE, mid1=770) == ESHAPE
     assert call(dt=2) == EDTYPE
-    assert call(ws=None, wsb=0) == EWORKSPACE
+    # order 2 keeps the hidden activations in the workspace (the fused order-1 kernel needs none)
+    assert call(order=2, w1l=FAKE, w2l=FAKE, ws=None, wsb=0) == EWORKSPACE
     assert call(y=FAKE) == EINVAL
-    assert lib.monarch_mlp_workspace_bytes(16, 768, 3072, 4, 1, 0, 0, 1) >= 16 * 3072 * 4
+    assert lib.monarch_mlp_workspace_bytes(16, 768, 3072, 4, 2, 0, 0, 1) >= 16 * 3072 * 4

@@ -79,6 +79,27 @@ def test_ragged_shapes_fp32(mm, B, H, n, klen, factors, gates):
     assert rel_l2(y, _oracle(w, nfft)) <= TOL_F32
 
 
+@pytest.mark.parametrize("B,H,n,klen,factors,gates", [
+    (3, 5, 100, 37, (16, 16), "normal"),          # odd batch: the last row of each channel travels alone
+    (1, 3, 128, 128, (16, 16), "normal"),         # B = 1: no pairing
+    (2, 3, 1000, 999, (32, 64), "none"),
+    (5, 2, 2048, 2048, (64, 64), "normal"),
+    (4, 3, 1024, 300, (128, 16), "normal"),
+    (3, 2, 2000, 2000, (16, 16, 16), "normal"),   # three factors
+    (2, 2, 4096, 4096, (32, 16, 64), "normal"),   # nfft = 8n
+])
+def test_ragged_shapes_bf16_matrix_core_passes(mm, B, H, n, klen, factors, gates):
+    announce("conv bf16 mfma passes", B, H, n, klen, factors, gates)
+    nfft = int(np.prod(factors))
+    w = workloads.conv_inputs(B, H, n, seed=n + klen + 1, gates=gates, bf16=True)
+    w["k"] = np.ascontiguousarray(w["k"][:, :klen])
+    y = _run(mm, w, factors, True)
+    want = _oracle(w, nfft)
+    assert rel_l2(y, want) <= TOL_BF16
+    num = np.linalg.norm((y - want).reshape(-1, n), axis=1)
+    assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_BF16
+
+
 def test_single_gate_and_bf16_odd_batch(mm):
     announce("conv one gate, odd B, bf16")
     w = workloads.conv_inputs(3, 4, 1024, seed=8, gates="normal", bf16=True)

@@ -69,6 +69,50 @@ def test_bf16_input(mm):
     assert rel_l2(X, oracle.dft(x.astype(np.float64))) <= TOL_BF16
 
 
+MFMA_FACTORS = [(16, 16), (64, 32), (32, 64), (128, 16), (16, 128), (16, 16, 16), (32, 16, 64)]
+
+
+@pytest.mark.parametrize("factors", MFMA_FACTORS)
+@pytest.mark.parametrize("real_input", [True, False])
+def test_bf16_fft_matrix_core_passes(mm, factors, real_input):
+    # bf16 data with factors of 16..128 take the MFMA passes (bf16 operands, fp32 accumulation)
+    announce("fft bf16 mfma", factors, "real" if real_input else "complex")
+    N = int(np.prod(factors))
+    rows = 3
+    rng = np.random.default_rng(N + 11)
+    xr = workloads.round_to_bf16(rng.standard_normal((rows, N)).astype(np.float32))
+    xi = workloads.round_to_bf16(rng.standard_normal((rows, N)).astype(np.float32))
+    if real_input:
+        X = _cplx(mm.monarch_fft(dev(xr, True), factors, True))
+        want = oracle.dft(xr.astype(np.float64))
+    else:
+        X = _cplx(mm.monarch_fft(dev(np.stack([xr, xi], -1), True), factors, False))
+        want = oracle.dft(xr.astype(np.float64) + 1j * xi.astype(np.float64))
+    assert rel_l2(X, want) <= TOL_BF16
+    # no row may hide behind the others
+    num = np.linalg.norm(X - want, axis=1)
+    assert (num / np.linalg.norm(want, axis=1)).max() <= TOL_BF16
+
+
+@pytest.mark.parametrize("factors", [(16, 16), (64, 32), (128, 128), (16, 32, 16)])
+def test_bf16_ifft_matrix_core_passes(mm, factors):
+    announce("ifft bf16 mfma", factors)
+    N = int(np.prod(factors))
+    rng = np.random.default_rng(N + 12)
+    Xr = rng.standard_normal((2, N)).astype(np.float32)
+    Xi = rng.standard_normal((2, N)).astype(np.float32)
+    Xd = dev(np.stack([Xr, Xi], -1))
+    spec = Xr.astype(np.float64) + 1j * Xi.astype(np.float64)
+    if N <= 4096:
+        want = oracle.idft(spec)
+    else:   # library routine for the long rows; the paper's forward sign is +, so its inverse is numpy's forward / N
+        want = np.fft.fft(spec, axis=-1) / N
+    x = _cplx(mm.monarch_ifft(Xd, factors, False, dtype=torch.bfloat16))
+    assert rel_l2(x, want) <= TOL_BF16
+    xre = host(mm.monarch_ifft(Xd, factors, True, dtype=torch.bfloat16))
+    assert rel_l2(xre, want.real) <= TOL_BF16
+
+
 def test_unit_vector_gives_dft_column(mm):
     announce("fft delta")
     N = 256
