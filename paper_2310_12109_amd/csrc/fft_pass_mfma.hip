@@ -10,9 +10,10 @@
 // Between passes a row is stored as packed bf16 pairs (re, im): the next pass would round its
 // operands to bf16 anyway, so this halves the traffic at no cost in accuracy.
 //
-// Column tiles: when S >= 16 a tile is 16 consecutive s (loads and stores are 16-lane contiguous
-// runs); the last pass (S = 1) takes 16 consecutive *natural output* positions, so that its
-// stores are contiguous, and each lane reads its own contiguous run of f inputs.
+// Column tiles: when S >= 16 a tile is 16 or 32 consecutive s (loads and stores are 16-lane
+// contiguous runs of one or two elements per lane); the last pass (S = 1) takes 16 or 32 consecutive
+// *natural output* positions, so that its stores are contiguous, and each lane reads its own
+// contiguous run of f inputs per column.
 #include "kernels.h"
 
 namespace monarch {
@@ -41,56 +42,131 @@ __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
 // complex row b2 * H + h holds real rows (2 b2) * H + h and (2 b2 + 1) * H + h.
 __device__ __forceinline__ int64_t pair_first_row(const FftPass &p, int64_t rc) { return rc + (rc / p.H) * p.H; }
 
-// One input element as a complex number, with the load mode's conjugation / gating / spectrum
-// product applied.  pos is the position inside the row.
-template <int LOAD>
-__device__ __forceinline__ float2 load_value(const FftPass &p, int64_t rc, int pos)
+// NT adjacent 32-bit words / bf16 values with one access (NT = 1 or 2; the callers guarantee the
+// natural alignment of the wider access).
+template <int NT>
+__device__ __forceinline__ void load_words(const uint32_t *src, uint32_t (&w)[NT])
+{
+    if constexpr (NT == 1) w[0] = src[0];
+    else {
+        const uint2 v = *(const uint2 *)src;
+        w[0] = v.x;
+        w[1] = v.y;
+    }
+}
+template <int NT>
+__device__ __forceinline__ void store_words(uint32_t *dst, const uint32_t (&w)[NT])
+{
+    if constexpr (NT == 1) dst[0] = w[0];
+    else *(uint2 *)dst = make_uint2(w[0], w[1]);
+}
+template <int NT>
+__device__ __forceinline__ void load_bf16s(const bf16_t *src, float (&v)[NT])
+{
+    if constexpr (NT == 1) v[0] = (float)src[0];
+    else {
+        const uint32_t w = *(const uint32_t *)src;
+        v[0] = lo_f32(w);
+        v[1] = hi_f32(w);
+    }
+}
+template <int NT>
+__device__ __forceinline__ void store_bf16s(bf16_t *dst, const float (&v)[NT])
+{
+    if constexpr (NT == 1) dst[0] = (bf16_t)v[0];
+    else *(uint32_t *)dst = pack2(v[0], v[1]);
+}
+
+// NT adjacent input elements as complex numbers, with the load mode's conjugation / gating /
+// spectrum product applied.  pos is the position of the first one inside the row.
+template <int LOAD, int NT>
+__device__ __forceinline__ void load_values(const FftPass &p, int64_t rc, int pos, float (&re)[NT], float (&im)[NT])
 {
     typedef bf16_t T;
     if constexpr (LOAD == LD_C32_CONJ) {
-        const float2 v = ((const float2 *)p.in)[rc * p.N + pos];
-        return make_float2(v.x, -v.y);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {   // adjacent 8-byte loads: merged by the compiler
+            const float2 v = ((const float2 *)p.in)[rc * p.N + pos + t];
+            re[t] = v.x;
+            im[t] = -v.y;
+        }
     } else if constexpr (LOAD == LD_CPLX) {
-        const uint32_t w = ((const uint32_t *)p.in)[rc * p.N + pos];
-        return make_float2(lo_f32(w), hi_f32(w));
+        uint32_t w[NT];
+        load_words<NT>((const uint32_t *)p.in + rc * p.N + pos, w);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            re[t] = lo_f32(w[t]);
+            im[t] = hi_f32(w[t]);
+        }
     } else if constexpr (LOAD == LD_C16_CONJ_MULK) {
-        const uint32_t w = ((const uint32_t *)p.in)[rc * p.N + pos];
-        const float2 k = p.kf[(rc % p.H) * (int64_t)p.N + pos];
-        const float2 m = cmul(make_float2(lo_f32(w), hi_f32(w)), k);
-        return make_float2(m.x, -m.y);
+        uint32_t w[NT];
+        load_words<NT>((const uint32_t *)p.in + rc * p.N + pos, w);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const float2 k = p.kf[(rc % p.H) * (int64_t)p.N + pos + t];
+            const float2 m = cmul(make_float2(lo_f32(w[t]), hi_f32(w[t])), k);
+            re[t] = m.x;
+            im[t] = -m.y;
+        }
     } else if constexpr (LOAD == LD_REAL) {
-        const bool ok = pos < p.n_valid;
+        const bool ok = pos < p.n_valid;   // NT = 2: pos and n_valid are even
         const int64_t at = rc * p.n_valid + (ok ? pos : 0);
-        float v = to_f32(((const T *)p.in)[at]);
-        if (p.gate) v *= to_f32(((const T *)p.gate)[at]);
-        return make_float2(ok ? v : 0.0f, 0.0f);
+        float v[NT], g[NT];
+        load_bf16s<NT>((const T *)p.in + at, v);
+        if (p.gate) {
+            load_bf16s<NT>((const T *)p.gate + at, g);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) v[t] *= g[t];
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            re[t] = ok ? v[t] : 0.0f;
+            im[t] = 0.0f;
+        }
     } else {  // LD_REAL_PAIR
         const bool ok = pos < p.n_valid;
         const int64_t ra = pair_first_row(p, rc);
         const bool okb = ok && ra + p.H < p.real_rows;
         const int64_t at = ra * p.n_valid + (ok ? pos : 0);
         const int64_t bt = okb ? at + (int64_t)p.H * p.n_valid : at;
-        float va = to_f32(((const T *)p.in)[at]), vb = to_f32(((const T *)p.in)[bt]);
+        float va[NT], vb[NT], ga[NT], gb[NT];
+        load_bf16s<NT>((const T *)p.in + at, va);
+        load_bf16s<NT>((const T *)p.in + bt, vb);
         if (p.gate) {
-            va *= to_f32(((const T *)p.gate)[at]);
-            vb *= to_f32(((const T *)p.gate)[bt]);
+            load_bf16s<NT>((const T *)p.gate + at, ga);
+            load_bf16s<NT>((const T *)p.gate + bt, gb);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                va[t] *= ga[t];
+                vb[t] *= gb[t];
+            }
         }
-        return make_float2(ok ? va : 0.0f, okb ? vb : 0.0f);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            re[t] = ok ? va[t] : 0.0f;
+            im[t] = okb ? vb[t] : 0.0f;
+        }
     }
 }
 
-template <int F, int LOAD, int STORE, bool CONTIG>
-__global__ __launch_bounds__(256, 2) void fft_pass_mfma_kernel(const FftPass p)
+// NT column tiles per wave: lane l16 owns the adjacent columns col0 + t, t < NT, so that NT = 2
+// doubles the width of every global access and halves the operand reads from LDS.
+template <int F, int LOAD, int STORE, bool CONTIG, int NT>
+__global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pass_mfma_kernel(const FftPass p)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32;
+    constexpr int THREADS = F == 128 ? 512 : 256, WAVES = THREADS / 64;   // the 64 KB table of f = 128 is shared by 8 waves
+    constexpr int COLS = 16 * NT;
+    constexpr bool REAL_IN = LOAD == LD_REAL || LOAD == LD_REAL_PAIR;
+    constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
     constexpr bool REAL_B = LOAD == LD_REAL;                   // imaginary part of the input is zero
     constexpr bool REAL_D = STORE == ST_REAL_SCALE_GATE;       // only the real part is kept
     extern __shared__ __attribute__((aligned(16))) u32x4 ftab[];   // [JT][KS][re, im][lane]
     __shared__ float2 roots[F];
-    for (int e = threadIdx.x; e < F; e += 256) roots[e] = omega(e, F);
+    for (int e = threadIdx.x; e < F; e += THREADS) roots[e] = omega(e, F);
     __syncthreads();
     // A operand of row tile jt, k-step ks: lane (row l16, group kg) holds F[16 jt + l16][32 ks + 8 kg + e]
-    for (int idx = threadIdx.x; idx < JT * KS * 64; idx += 256) {
+    for (int idx = threadIdx.x; idx < JT * KS * 64; idx += THREADS) {
         const int ln = idx & 63, ks = (idx >> 6) % KS, jt = idx / (64 * KS);
         const int j = 16 * jt + (ln & 15), c0 = 32 * ks + 8 * (ln >> 4);
         u32x4 re, im;
@@ -110,149 +186,204 @@ __global__ __launch_bounds__(256, 2) void fft_pass_mfma_kernel(const FftPass p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
     const int S = p.S, O = p.O;
-    const int tiles_per_unit = CONTIG ? O / 16 : S / 16;           // unit: a row (CONTIG) or one (row, o)
+    const int tiles_per_unit = (CONTIG ? O : S) / COLS;           // unit: a row (CONTIG) or one (row, o)
     const int64_t ntiles = p.rows * (CONTIG ? 1 : O) * tiles_per_unit;
     const float inv_fs = 1.0f / (float)((int64_t)F * S);
 
-    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
+    for (int64_t tile = (int64_t)blockIdx.x * WAVES + wave; tile < ntiles; tile += (int64_t)gridDim.x * WAVES) {
         int64_t rc;
-        int col, base;   // col: s (S >= 16) or natural low index rho (S == 1); base: position of (o, c = 0, s)
+        int col0;       // first of this lane's columns: s (S >= 16) or natural low index rho (S == 1)
+        int base[NT];   // CONTIG: position of (o(col0 + t), c = 0); else base[0]: position of (o, c = 0, s = col0)
         if constexpr (CONTIG) {
             rc = tile / tiles_per_unit;
-            col = (int)(tile - rc * tiles_per_unit) * 16 + l16;
-            int o = col;   // two factors: the digit itself; three: swap the two digits already produced
-            if (p.nf == 3) o = (col % p.factors[0]) * p.factors[1] + col / p.factors[0];
-            base = o * F;
+            col0 = (int)(tile - rc * tiles_per_unit) * COLS + NT * l16;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                int o = col0 + t;   // two factors: the digit itself; three: swap the two digits already produced
+                if (p.nf == 3) o = ((col0 + t) % p.factors[0]) * p.factors[1] + (col0 + t) / p.factors[0];
+                base[t] = o * F;
+            }
         } else {
             const int64_t unit = tile / tiles_per_unit;
-            col = (int)(tile - unit * tiles_per_unit) * 16 + l16;
+            col0 = (int)(tile - unit * tiles_per_unit) * COLS + NT * l16;
             rc = unit / O;
-            base = (int)(unit - rc * O) * F * S + col;
+            base[0] = (int)(unit - rc * O) * F * S + col0;
         }
 
         // ---- B operands: k-step ks, slot e  <->  c = 32 ks + 8 kg + e
-        u32x4 br[KS], bi[KS], nbi[KS];
+        u32x4 br[NT][KS], bi[NT][KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int c0 = 32 * ks + 8 * kg;
-            if constexpr (CONTIG) {   // packed bf16 pairs, 8 consecutive elements per lane
-                u32x4 w0 = {0, 0, 0, 0}, w1 = w0;
-                if (c0 < F) {
-                    const u32x4 *src = (const u32x4 *)((const uint32_t *)p.in + rc * p.N + base + c0);
-                    w0 = src[0];
-                    w1 = src[1];
-                }
+            if constexpr (CONTIG) {   // packed bf16 pairs, 8 consecutive elements per lane and column
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    br[ks][h] = (w0[2 * h] & 0xffffu) | (w0[2 * h + 1] << 16);
-                    bi[ks][h] = (w0[2 * h] >> 16) | (w0[2 * h + 1] & 0xffff0000u);
-                    br[ks][2 + h] = (w1[2 * h] & 0xffffu) | (w1[2 * h + 1] << 16);
-                    bi[ks][2 + h] = (w1[2 * h] >> 16) | (w1[2 * h + 1] & 0xffff0000u);
+                for (int t = 0; t < NT; ++t) {
+                    u32x4 w0 = {0, 0, 0, 0}, w1 = w0;
+                    if (c0 < F) {
+                        const u32x4 *src = (const u32x4 *)((const uint32_t *)p.in + rc * p.N + base[t] + c0);
+                        w0 = src[0];
+                        w1 = src[1];
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        br[t][ks][h] = (w0[2 * h] & 0xffffu) | (w0[2 * h + 1] << 16);
+                        bi[t][ks][h] = (w0[2 * h] >> 16) | (w0[2 * h + 1] & 0xffff0000u);
+                        br[t][ks][2 + h] = (w1[2 * h] & 0xffffu) | (w1[2 * h + 1] << 16);
+                        bi[t][ks][2 + h] = (w1[2 * h] >> 16) | (w1[2 * h + 1] & 0xffff0000u);
+                    }
                 }
             } else if constexpr (LOAD == LD_C16) {
-                uint32_t w[8];
+                uint32_t w[8][NT];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const bool ok = c0 + e < F;
-                    const uint32_t v = ((const uint32_t *)p.in)[rc * p.N + base + (ok ? (c0 + e) * S : 0)];
-                    w[e] = ok ? v : 0u;
+                    load_words<NT>((const uint32_t *)p.in + rc * p.N + base[0] + (ok ? (c0 + e) * S : 0), w[e]);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) w[e][t] = ok ? w[e][t] : 0u;
                 }
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    br[ks][h] = (w[2 * h] & 0xffffu) | (w[2 * h + 1] << 16);
-                    bi[ks][h] = (w[2 * h] >> 16) | (w[2 * h + 1] & 0xffff0000u);
-                }
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        br[t][ks][h] = (w[2 * h][t] & 0xffffu) | (w[2 * h + 1][t] << 16);
+                        bi[t][ks][h] = (w[2 * h][t] >> 16) | (w[2 * h + 1][t] & 0xffff0000u);
+                    }
             } else {
                 // inputs past n_valid are zero: a k-step wholly past it is skipped (wave-uniform)
-                const bool live = !(LOAD == LD_REAL || LOAD == LD_REAL_PAIR) || (int64_t)32 * ks * S < p.n_valid;
-                float2 v[8];
+                const bool live = !REAL_IN || (int64_t)32 * ks * S < p.n_valid;
+                float vr[8][NT], vi[8][NT];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    v[e] = make_float2(0.0f, 0.0f);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) vr[e][t] = vi[e][t] = 0.0f;
                     if (live) {
                         const bool ok = c0 + e < F;
-                        const float2 t = load_value<LOAD>(p, rc, base + (ok ? (c0 + e) * S : 0));
-                        if (ok) v[e] = t;
+                        float re[NT], im[NT];
+                        load_values<LOAD, NT>(p, rc, base[0] + (ok ? (c0 + e) * S : 0), re, im);
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            vr[e][t] = ok ? re[t] : 0.0f;
+                            vi[e][t] = ok ? im[t] : 0.0f;
+                        }
                     }
                 }
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    br[ks][h] = pack2(v[2 * h].x, v[2 * h + 1].x);
-                    bi[ks][h] = pack2(v[2 * h].y, v[2 * h + 1].y);
-                }
-            }
+                for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int h = 0; h < 4; ++h) nbi[ks][h] = bi[ks][h] ^ 0x80008000u;
+                    for (int h = 0; h < 4; ++h) {
+                        br[t][ks][h] = pack2(vr[2 * h][t], vr[2 * h + 1][t]);
+                        bi[t][ks][h] = pack2(vi[2 * h][t], vi[2 * h + 1][t]);
+                    }
+            }
         }
 
         // ---- twiddle seeds: omega_(fS)^(j s) for j = 4 kg + r, stepped by omega_(fS)^(16 s) per row tile
-        float2 tw[4], step;
+        float2 tw[NT][4], step[NT];
         if constexpr (!CONTIG) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float rev = (float)((4 * kg + r) * col) * inv_fs;   // exact: j s < f S <= 2^24
-                tw[r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float rev = (float)((4 * kg + r) * (col0 + t)) * inv_fs;   // exact: j s < f S <= 2^24
+                    tw[t][r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+                }
+                const float rev = (float)(16 * (col0 + t)) * inv_fs;
+                step[t] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
             }
-            const float rev = (float)(16 * col) * inv_fs;
-            step = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
         }
 
         // ---- row tiles of the output digit j (kept as a loop: unrolled, the operand reads of all
         // tiles are hoisted and the register file overflows)
 #pragma unroll 1
         for (int jt = 0; jt < JT; ++jt) {
-            const bool wanted = !(STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR) || (int64_t)16 * jt * O < p.n_valid;
+            const bool wanted = !REAL_OUT || (int64_t)16 * jt * O < p.n_valid;
             if (wanted) {
-                f32x4 dr = {0, 0, 0, 0}, di = {0, 0, 0, 0};
+                f32x4 dr[NT], di[NT];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) dr[t] = di[t] = f32x4{0, 0, 0, 0};
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bool live = !(LOAD == LD_REAL || LOAD == LD_REAL_PAIR) || (int64_t)32 * ks * S < p.n_valid;
+                    const bool live = !REAL_IN || (int64_t)32 * ks * S < p.n_valid;
                     if (live) {
                         const u32x4 ar = ftab[(jt * KS + ks) * 128 + lane], ai = ftab[(jt * KS + ks) * 128 + 64 + lane];
-                        dr = mfma(ar, br[ks], dr);
-                        if constexpr (!REAL_B) dr = mfma(ai, nbi[ks], dr);
-                        if constexpr (!REAL_D) {
-                            di = mfma(ai, br[ks], di);
-                            if constexpr (!REAL_B) di = mfma(ar, bi[ks], di);
+                        const u32x4 nai = ai ^ 0x80008000u;
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            dr[t] = mfma(ar, br[t][ks], dr[t]);
+                            if constexpr (!REAL_B) dr[t] = mfma(nai, bi[t][ks], dr[t]);
+                            if constexpr (!REAL_D) {
+                                di[t] = mfma(ai, br[t][ks], di[t]);
+                                if constexpr (!REAL_B) di[t] = mfma(ar, bi[t][ks], di[t]);
+                            }
                         }
                     }
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int j = 16 * jt + 4 * kg + r;
-                    float2 z = make_float2(dr[r], di[r]);
-                    if constexpr (!CONTIG) {
-                        z = cmul(z, tw[r]);
-                        const int64_t at = rc * p.N + base + (int64_t)j * S;
-                        if constexpr (STORE == ST_C16) ((uint32_t *)p.out)[at] = pack2(z.x, z.y);
-                        else ((float2 *)p.out)[at] = z;   // ST_C32
+                    float zr[NT], zi[NT];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        zr[t] = dr[t][r];
+                        zi[t] = di[t][r];
+                    }
+                    if constexpr (!CONTIG) {   // ST_C16
+                        uint32_t w[NT];
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            const float2 z = cmul(make_float2(zr[t], zi[t]), tw[t][r]);
+                            w[t] = pack2(z.x, z.y);
+                        }
+                        store_words<NT>((uint32_t *)p.out + rc * p.N + base[0] + (int64_t)j * S, w);
                     } else {
-                        const int m = j * O + col;   // natural output index
+                        const int m = j * O + col0;   // natural output index of the first column
                         if constexpr (STORE == ST_C32_NATURAL) {
-                            ((float2 *)p.out)[rc * p.N + m] = z;
-                        } else if constexpr (STORE == ST_C16_NATURAL) {
-                            ((uint32_t *)p.out)[rc * p.N + m] = pack2(z.x, z.y);
-                        } else if constexpr (STORE == ST_CPLX_CONJ_SCALE) {
-                            ((uint32_t *)p.out)[rc * p.N + m] = pack2(z.x * p.scale, -z.y * p.scale);
+#pragma unroll
+                            for (int t = 0; t < NT; ++t) ((float2 *)p.out)[rc * p.N + m + t] = make_float2(zr[t], zi[t]);
+                        } else if constexpr (STORE == ST_C16_NATURAL || STORE == ST_CPLX_CONJ_SCALE) {
+                            uint32_t w[NT];
+#pragma unroll
+                            for (int t = 0; t < NT; ++t)
+                                w[t] = STORE == ST_C16_NATURAL ? pack2(zr[t], zi[t]) : pack2(zr[t] * p.scale, -zi[t] * p.scale);
+                            store_words<NT>((uint32_t *)p.out + rc * p.N + m, w);
                         } else if constexpr (STORE == ST_REAL_SCALE_GATE) {
-                            if (m < p.n_valid) {
+                            if (m < p.n_valid) {   // NT = 2: m and n_valid are even
                                 const int64_t at = rc * p.n_valid + m;
-                                float v = z.x * p.scale;
-                                if (p.gate) v *= to_f32(((const bf16_t *)p.gate)[at]);
-                                ((bf16_t *)p.out)[at] = (bf16_t)v;
+                                float v[NT], g[NT];
+#pragma unroll
+                                for (int t = 0; t < NT; ++t) v[t] = zr[t] * p.scale;
+                                if (p.gate) {
+                                    load_bf16s<NT>((const bf16_t *)p.gate + at, g);
+#pragma unroll
+                                    for (int t = 0; t < NT; ++t) v[t] *= g[t];
+                                }
+                                store_bf16s<NT>((bf16_t *)p.out + at, v);
                             }
                         } else {   // ST_REAL_PAIR: F^-1 = conj(F conj(.)) / N, so the second row is -Im
                             if (m < p.n_valid) {
                                 const int64_t ra = pair_first_row(p, rc);
                                 const int64_t at = ra * p.n_valid + m, bt = at + (int64_t)p.H * p.n_valid;
                                 const bool hasb = ra + p.H < p.real_rows;
-                                float va = z.x * p.scale, vb = -z.y * p.scale;
-                                if (p.gate) {
-                                    va *= to_f32(((const bf16_t *)p.gate)[at]);
-                                    if (hasb) vb *= to_f32(((const bf16_t *)p.gate)[bt]);
+                                float va[NT], vb[NT], g[NT];
+#pragma unroll
+                                for (int t = 0; t < NT; ++t) {
+                                    va[t] = zr[t] * p.scale;
+                                    vb[t] = -zi[t] * p.scale;
                                 }
-                                ((bf16_t *)p.out)[at] = (bf16_t)va;
-                                if (hasb) ((bf16_t *)p.out)[bt] = (bf16_t)vb;
+                                if (p.gate) {
+                                    load_bf16s<NT>((const bf16_t *)p.gate + at, g);
+#pragma unroll
+                                    for (int t = 0; t < NT; ++t) va[t] *= g[t];
+                                }
+                                store_bf16s<NT>((bf16_t *)p.out + at, va);
+                                if (hasb) {
+                                    if (p.gate) {
+                                        load_bf16s<NT>((const bf16_t *)p.gate + bt, g);
+#pragma unroll
+                                        for (int t = 0; t < NT; ++t) vb[t] *= g[t];
+                                    }
+                                    store_bf16s<NT>((bf16_t *)p.out + bt, vb);
+                                }
                             }
                         }
                     }
@@ -260,30 +391,44 @@ __global__ __launch_bounds__(256, 2) void fft_pass_mfma_kernel(const FftPass p)
             }
             if constexpr (!CONTIG) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tw[r] = cmul(tw[r], step);
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) tw[t][r] = cmul(tw[t][r], step[t]);
             }
         }
     }
 }
 
-template <int F, int LOAD, int STORE, bool CONTIG>
-static int launch_one(const FftPass &p, hipStream_t s)
+template <int F, int LOAD, int STORE, bool CONTIG, int NT>
+static int launch_nt(const FftPass &p, hipStream_t s)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32;
     const size_t lds = (size_t)JT * KS * 2 * 64 * 16;
     int dev = 0, ncu = 0;
     MONARCH_HIP_CHECK(hipGetDevice(&dev));
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
-    const int64_t ntiles = p.rows * (int64_t)p.N / F / 16;
-    int64_t grid = (ntiles + 3) / 4;
-    const int64_t cap = (int64_t)ncu * (F == 128 ? 2 : 4);
+    const int64_t ntiles = p.rows * (int64_t)p.N / F / (16 * NT);
+    constexpr int THREADS = F == 128 ? 512 : 256, WAVES = THREADS / 64;
+    int64_t grid = (ntiles + WAVES - 1) / WAVES;
+    const int64_t cap = (int64_t)ncu * (F == 128 ? 2 : 4);   // 16 waves per compute unit
     if (grid > cap) grid = cap;
-    auto kern = fft_pass_mfma_kernel<F, LOAD, STORE, CONTIG>;
+    auto kern = fft_pass_mfma_kernel<F, LOAD, STORE, CONTIG, NT>;
     if (lds > 48 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, p);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
+}
+
+// Two column tiles per wave whenever the wider accesses are aligned: an even run of columns and,
+// for real rows, an even row length.
+template <int F, int LOAD, int STORE, bool CONTIG>
+static int launch_one(const FftPass &p, hipStream_t s)
+{
+    const bool real_rows = LOAD == LD_REAL || LOAD == LD_REAL_PAIR || STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
+    // (f = 128 with strided columns runs at 128 registers per lane, where two tiles would spill)
+    const bool wide = (CONTIG ? p.O : p.S) % 32 == 0 && (!real_rows || p.n_valid % 2 == 0) && (CONTIG || F < 128);
+    return wide ? launch_nt<F, LOAD, STORE, CONTIG, 2>(p, s) : launch_nt<F, LOAD, STORE, CONTIG, 1>(p, s);
 }
 
 template <int F>
