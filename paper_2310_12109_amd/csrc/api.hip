@@ -464,12 +464,26 @@ static int mlp_check(int64_t tokens, int d, int d_hidden, int nb, int order, int
     return MONARCH_OK;
 }
 
+// Order 2 on the matrix cores: W1 = P L1 P R1 P and W2 = P L2 P R2 P meet at the hidden vector, where
+// block k of L1 feeds exactly block k of R2, so [L1, bias, activation, R2] is a block-diagonal MLP
+// whose hidden vector stays on chip; R1 and L2 with the permutations around them are one launch each.
+static bool mlp_order2_mfma_supported(int d, int d_hidden, int nb, int mid1, int mid2, monarch_dtype dt)
+{
+    if (nb < 1 || mid1 < 1 || mid1 != mid2 || d % nb || mid1 % nb || d_hidden % nb) return false;
+    return factor_mfma_supported(nb, mid1 / nb, d / nb, dt) && mlp_mfma_order1_supported(mid1, d_hidden, nb, dt) &&
+           factor_mfma_supported(nb, d / nb, mid2 / nb, dt);
+}
+
 size_t monarch_mlp_workspace_bytes(int64_t tokens, int d, int d_hidden, int nb, int order,
                                    int mid1, int mid2, monarch_dtype dt)
 {
-    (void)mid1; (void)mid2;
     if (tokens <= 0 || d_hidden <= 0) return 0;
     if (order == 1 && nb > 0 && mlp_mfma_order1_supported(d, d_hidden, nb, dt)) return 0;   // hidden stays on chip
+    if (order == 2) {
+        const int m1 = mid1 > 0 ? mid1 : d, m2 = mid2 > 0 ? mid2 : d;   // same defaults as the call itself
+        if (mlp_order2_mfma_supported(d, d_hidden, nb, m1, m2, dt))   // the two d_mid-wide intermediates, bf16
+            return 2 * align_up((size_t)tokens * m1 * sizeof(bf16_t), 256);
+    }
     return align_up((size_t)tokens * d_hidden * sizeof(float), 256);   // hidden activations, fp32
 }
 
@@ -497,7 +511,16 @@ int monarch_mlp(const void *x, void *y, int64_t tokens, int d, int d_hidden, int
     hipStream_t s = (hipStream_t)stream;
 
     if (order == 1 && mlp_mfma_order1_supported(d, d_hidden, nb, dt))
-        return launch_mlp_mfma_order1(x, y, tokens, d, d_hidden, nb, W1_R, b1, W2_R, b2, act, s);
+        return launch_mlp_mfma_order1(x, y, tokens, d, d_hidden, nb, W1_R, b1, W2_R, b2, act, 0, s);
+    if (order == 2 && mlp_order2_mfma_supported(d, d_hidden, nb, mid1, mid2, dt)) {
+        void *t2 = ws, *u1 = (char *)ws + align_up((size_t)tokens * mid1 * sizeof(bf16_t), 256);
+        rc = launch_factor_mfma(x, t2, tokens, nb, mid1 / nb, d / nb, W1_R, nullptr, 0, s);
+        if (rc) return rc;
+        // hidden unit h of block k is position h nb + k of the hidden vector: that is where its bias sits
+        rc = launch_mlp_mfma_order1(t2, u1, tokens, mid1, d_hidden, nb, W1_L, b1, W2_R, nullptr, act, 1, s);
+        if (rc) return rc;
+        return launch_factor_mfma(u1, y, tokens, nb, d / nb, mid2 / nb, W2_L, b2, 2, s);
+    }
 
     // Layer 1 writes the activated hidden vector (fp32) to the workspace, layer 2 reads it.
     if (order == 1) {

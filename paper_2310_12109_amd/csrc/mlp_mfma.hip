@@ -70,7 +70,7 @@ template <int KS, int ACT>
 __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
     const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
     const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
-    const bf16_t *__restrict__ b2)
+    const bf16_t *__restrict__ b2, int b1_interleaved)
 {
     constexpr int DIN = 32 * KS, MT = 2 * KS, LD = DIN + 1;   // LD: padded row of the output tile
     constexpr int PART = MT * 4 * 64;                            // f32x4 pieces of one wave's partial tile
@@ -111,8 +111,19 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
         const int h0 = 32 * j;   // first hidden unit of the chunk
         // Everything the chunk needs is requested up front: biases of the 8 hidden units this lane
         // group's accumulator rows carry (h0 + 8kg .. +7), both W1 row tiles, all W2 row tiles.
+        // (b1_interleaved: hidden unit h of block blk sits at b1[h nb + blk], the layout an order-2
+        // Monarch leaves its outputs in; otherwise at b1[blk dh + h])
         uint4 braw = make_uint4(0u, 0u, 0u, 0u);
-        if (b1) braw = *reinterpret_cast<const uint4 *>(b1 + (size_t)blk * dh + h0 + 8 * kg);
+        if (b1) {
+            if (!b1_interleaved) braw = *reinterpret_cast<const uint4 *>(b1 + (size_t)blk * dh + h0 + 8 * kg);
+            else {
+                const uint16_t *bsrc = reinterpret_cast<const uint16_t *>(b1) + (size_t)(h0 + 8 * kg) * nb + blk;
+                uint32_t w[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e] = bsrc[(size_t)e * nb];
+                braw = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+            }
+        }
         Pack8 w1[2][KS], w2[MT];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
@@ -231,7 +242,7 @@ bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
 
 int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb,
                            const void *W1, const void *b1, const void *W2, const void *b2, int act,
-                           hipStream_t s)
+                           int b1_interleaved, hipStream_t s)
 {
     const int din = d / nb;
     const int64_t tiles = (tokens + mlp1::TOK - 1) / mlp1::TOK;
@@ -246,7 +257,8 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
             MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                   (int)lds));                                                   \
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d, d_hidden,  \
-                           nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2, (const bf16_t *)b2);  \
+                           nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2, (const bf16_t *)b2,   \
+                           b1_interleaved);                                                                     \
     } while (0)
 #define MONARCH_LAUNCH_MLP1_ACT(KSV)                     \
     do {                                                 \

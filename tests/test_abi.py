@@ -134,4 +134,6 @@ def test_mlp_rejects_bad_arguments(lib):
     # order 2 keeps the hidden activations in the workspace (the fused order-1 kernel needs none)
     assert call(order=2, w1l=FAKE, w2l=FAKE, ws=None, wsb=0) == EWORKSPACE
     assert call(y=FAKE) == EINVAL
-    assert lib.monarch_mlp_workspace_bytes(16, 768, 3072, 4, 2, 0, 0, 1) >= 16 * 3072 * 4
+    # order 2, bf16: the two d_mid-wide intermediates; fp32: the hidden activations
+    assert lib.monarch_mlp_workspace_bytes(16, 768, 3072, 4, 2, 0, 0, 1) >= 2 * 16 * 768 * 2
+    assert lib.monarch_mlp_workspace_bytes(16, 768, 3072, 4, 2, 0, 0, 0) >= 16 * 3072 * 4

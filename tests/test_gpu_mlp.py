@@ -39,6 +39,25 @@ def test_small_ragged(mm, order, act, bf16):
     assert rel_l2(y, _oracle(w, 4, order, act)) <= (TOL_BF16 if bf16 else TOL_F32)
 
 
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("tokens,d,dh,nb,act,bias", [
+    (45, 128, 256, 4, 2, True),       # ragged token tile, blocks of 32
+    (130, 256, 1024, 4, 1, True),     # blocks of 64 -> 256
+    (33, 384, 768, 2, 0, False),      # blocks of 192 (the widest), no bias, no activation
+    (64, 512, 512, 16, 2, True),      # many small blocks, d_hidden = d
+])
+def test_matrix_core_shapes_bf16(mm, order, tokens, d, dh, nb, act, bias):
+    # bf16 shapes with blocks that are multiples of 32: the MFMA kernels (fused block MLP; for order 2
+    # also the two outer Monarch factors with their permutations)
+    announce("mlp mfma", order, tokens, d, dh, nb, act, bias)
+    w = workloads.mlp_inputs(tokens, d, dh, nb, order, seed=tokens + d, bf16=True, std=0.08, bias=bias)
+    y = _run(mm, w, nb, order, act, dh, True)
+    want = _oracle(w, nb, order, act)
+    assert rel_l2(y, want) <= TOL_BF16
+    num = np.linalg.norm(y - want, axis=1)
+    assert (num / np.linalg.norm(want, axis=1)).max() <= 2.5 * TOL_BF16
+
+
 def test_no_bias_and_single_block(mm):
     announce("mlp nb=1 no bias")
     w = workloads.mlp_inputs(10, 16, 64, 1, 1, seed=3, bf16=False, std=0.3, bias=False)
