@@ -231,6 +231,152 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
     }
 }
 
+
+// ---- variant for small blocks and many tokens -------------------------------------------------
+// When both weight matrices of a block fit in LDS (64 KB) they are staged there once, already in
+// MFMA operand order, by a persistent workgroup that then walks over tiles of 256 tokens of that
+// block: wave w owns tokens 64 w .. 64 w + 63 of the tile and the whole hidden vector, so nothing is
+// summed across waves and every weight byte leaves L2 once per workgroup instead of once per 64 tokens.
+// The next tile's x operands are requested before the current tile is computed.
+template <int KS, int ACT>
+__global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
+    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
+    const bf16_t *__restrict__ b2, int b1_interleaved, int wgs_per_block)
+{
+    constexpr int DIN = 32 * KS, MT = 2 * KS, OPS = 4 * KS;   // operand pieces (64 lanes x 16 B) per hidden chunk
+    extern __shared__ uint4 lds_ops[];                          // [chunk][OPS][lane], then the bias [dh] as bf16
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int blk = blockIdx.x % nb, slot = blockIdx.x / nb;
+    const int dh = d_hidden / nb, nch = dh / 32;
+    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_ops + (size_t)nch * OPS * 64);
+
+    // stage the block's weights: piece (chunk j, op o, lane) is exactly the 16-byte operand that lane
+    // will feed to the MFMA (same row / slot assignment as mlp_order1_kernel)
+    for (int idx = tid; idx < nch * OPS * 64; idx += 256) {
+        const int ln = idx & 63, q = idx >> 6, j = q / OPS, o = q - j * OPS;
+        const int r16 = ln & 15, g = ln >> 4;
+        const bf16_t *src;
+        if (o < 2 * KS) {
+            const int mt = o / KS, ks = o - mt * KS;
+            const int unit = 8 * (r16 >> 2) + 4 * mt + (r16 & 3);
+            src = W1b + (size_t)(32 * j + unit) * DIN + 32 * ks + 8 * g;
+        } else {
+            src = W2b + (size_t)(16 * (o - 2 * KS) + r16) * dh + 32 * j + 8 * g;
+        }
+        lds_ops[idx] = *reinterpret_cast<const uint4 *>(src);
+    }
+    for (int h = tid; h < dh; h += 256) {
+        uint16_t v = 0;
+        if (b1) v = reinterpret_cast<const uint16_t *>(b1)[b1_interleaved ? (size_t)h * nb + blk : (size_t)blk * dh + h];
+        bias_lds[h] = v;
+    }
+    // output bias of the rows this lane's accumulators carry: features 16 mt + 4 kg + r
+    float bias2[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bias2[mt][r] = b2 ? (float)b2[(size_t)blk * DIN + 16 * mt + 4 * kg + r] : 0.0f;
+    __syncthreads();
+
+    const int64_t ntiles = (tokens + 255) / 256;
+    Pack8 xnext[4][KS];
+    auto request = [&](int64_t tile) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            int64_t t = tile * 256 + 64 * wave + 16 * nt + l16;
+            if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
+            const bf16_t *row = x + t * d + blk * DIN + 8 * kg;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xnext[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
+        }
+    };
+    if (slot < ntiles) request(slot);
+    for (int64_t tile = slot; tile < ntiles; tile += wgs_per_block) {
+        Pack8 xop[4][KS];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xop[nt][ks] = xnext[nt][ks];
+        const int64_t after = tile + wgs_per_block;
+        request(after < ntiles ? after : tile);
+
+        f32x4 acc[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f32x4){0, 0, 0, 0};
+        for (int j = 0; j < nch; ++j) {
+            const uint4 *ops = lds_ops + (size_t)j * OPS * 64 + lane;
+            Pack8 w1[2][KS], w2[MT];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) w1[mt][ks].q = ops[(mt * KS + ks) * 64];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) w2[mt].q = ops[(2 * KS + mt) * 64];
+            const uint4 braw = *reinterpret_cast<const uint4 *>(bias_lds + 32 * j + 8 * kg);
+
+            f32x4 hacc[2][4];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    f32x4 a = {0, 0, 0, 0};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) a = mfma(w1[mt][ks].v, xop[nt][ks].v, a);
+                    hacc[mt][nt] = a;
+                }
+            Pack8 hop[4];
+            {
+                const uint32_t bw[4] = {braw.x, braw.y, braw.z, braw.w};
+                float bias[2][4];
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const uint32_t w = bw[2 * mt + (r >> 1)];
+                        bias[mt][r] = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+                    }
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt) {
+                        float v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = act_fast<ACT>(hacc[mt][nt][r] + bias[mt][r]);
+                        hop[nt].d[2 * mt] = pack_bf16(v[0], v[1]);
+                        hop[nt].d[2 * mt + 1] = pack_bf16(v[2], v[3]);
+                    }
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
+        }
+        // accumulator rows 4 kg .. 4 kg + 3 of tile mt are 4 consecutive features of token 16 nt + l16:
+        // one 8-byte store per tile and lane (the four lane groups of a token fill a 32-byte run)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int64_t t = tile * 256 + 64 * wave + 16 * nt + l16;
+            if (t < tokens) {
+                bf16_t *dst = y + t * d + blk * DIN + 4 * kg;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    uint2 o;
+                    o.x = pack_bf16(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
+                    o.y = pack_bf16(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
+                    *reinterpret_cast<uint2 *>(dst + 16 * mt) = o;
+                }
+            }
+        }
+    }
+}
+
 }  // namespace mlp1
 
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
@@ -245,6 +391,43 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
                            int b1_interleaved, hipStream_t s)
 {
     const int din = d / nb;
+    // small blocks, many tokens: weights resident in LDS, persistent workgroups
+    const int dh_blk = d_hidden / nb;
+    const size_t res_lds = (size_t)dh_blk * din * 4 + (size_t)dh_blk * 2;
+    if (din <= 64 && res_lds <= 72 * 1024 && tokens >= 2048) {
+        int dev = 0, ncu = 0;
+        MONARCH_HIP_CHECK(hipGetDevice(&dev));
+        MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+        const int64_t ntiles = (tokens + 255) / 256;
+        int64_t per_block = (2 * (int64_t)ncu + nb - 1) / nb;   // two workgroups per compute unit
+        if (per_block < 1) per_block = 1;
+        if (per_block > ntiles) per_block = ntiles;
+        const dim3 rgrid((unsigned)(per_block * nb));
+#define MONARCH_LAUNCH_RES(KSV, ACTV)                                                                           \
+    do {                                                                                                        \
+        auto kern = mlp1::mlp_order1_resident_kernel<KSV, ACTV>;                                                \
+        if (res_lds > 48 * 1024)                                                                                \
+            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                  (int)res_lds));                                               \
+        hipLaunchKernelGGL(kern, rgrid, dim3(256), res_lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d,       \
+                           d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2,            \
+                           (const bf16_t *)b2, b1_interleaved, (int)per_block);                                 \
+    } while (0)
+#define MONARCH_LAUNCH_RES_ACT(KSV)                     \
+    do {                                                \
+        if (act == 2) MONARCH_LAUNCH_RES(KSV, 2);       \
+        else if (act == 1) MONARCH_LAUNCH_RES(KSV, 1);  \
+        else MONARCH_LAUNCH_RES(KSV, 0);                \
+    } while (0)
+        switch (din / 32) {
+        case 1: MONARCH_LAUNCH_RES_ACT(1); break;
+        default: MONARCH_LAUNCH_RES_ACT(2); break;
+        }
+#undef MONARCH_LAUNCH_RES_ACT
+#undef MONARCH_LAUNCH_RES
+        MONARCH_HIP_CHECK(hipGetLastError());
+        return MONARCH_OK;
+    }
     const int64_t tiles = (tokens + mlp1::TOK - 1) / mlp1::TOK;
     if (tiles > 0x7fffffffLL || nb > 65535) return fail(MONARCH_ESHAPE, "too many tokens or blocks for one launch");
     const dim3 grid((unsigned)tiles, (unsigned)nb);

@@ -58,6 +58,24 @@ def test_matrix_core_shapes_bf16(mm, order, tokens, d, dh, nb, act, bias):
     assert (num / np.linalg.norm(want, axis=1)).max() <= 2.5 * TOL_BF16
 
 
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("tokens,d,dh,nb,act,bias", [
+    (2300, 128, 512, 4, 2, True),     # blocks of 32 -> 128, ragged last tile of 256 tokens
+    (2049, 256, 512, 4, 1, False),    # blocks of 64 -> 128, one token past a tile
+    (4096, 512, 2048, 8, 0, True),    # blocks of 64 -> 256
+])
+def test_resident_weight_kernel_bf16(mm, order, tokens, d, dh, nb, act, bias):
+    # small blocks and >= 2048 tokens: the block's weights stay in LDS while a workgroup walks over
+    # token tiles; checked on every token
+    announce("mlp resident", order, tokens, d, dh, nb, act, bias)
+    w = workloads.mlp_inputs(tokens, d, dh, nb, order, seed=tokens + dh, bf16=True, std=0.08, bias=bias)
+    y = _run(mm, w, nb, order, act, dh, True)
+    want = _oracle(w, nb, order, act)
+    assert rel_l2(y, want) <= TOL_BF16
+    num = np.linalg.norm(y - want, axis=1)
+    assert (num / np.linalg.norm(want, axis=1)).max() <= 2.5 * TOL_BF16
+
+
 def test_no_bias_and_single_block(mm):
     announce("mlp nb=1 no bias")
     w = workloads.mlp_inputs(10, 16, 64, 1, 1, seed=3, bf16=False, std=0.3, bias=False)
