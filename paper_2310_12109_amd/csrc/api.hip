@@ -247,11 +247,12 @@ static int conv_check(int B, int H, int n, int klen, int nfft, const int *factor
     return MONARCH_OK;
 }
 
-// Which fused kernel serves this shape: 0 = none (multi-pass generic path), 1 = 64 x 32 MFMA.
+// Which fused kernel serves this shape: 0 = none (multi-pass path), 1 = 64 x 32 MFMA, 2 = 16 x 16 MFMA.
 // With n, klen <= nfft/2 the circular and the causal form coincide, so `causal` does not matter.
 static int conv_fused_path(int n, int klen, const int *factors, int nf, monarch_dtype dt)
 {
     if (factors && conv_mfma_2048_supported(n, klen, factors, nf, dt)) return 1;
+    if (factors && conv_mfma_256_supported(n, klen, factors, nf, dt)) return 2;
     return 0;
 }
 
@@ -363,8 +364,9 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
         return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
     hipStream_t s = (hipStream_t)stream;
 
-    if (conv_fused_path(n, klen, factors, nf, dt) == 1)
-        return launch_conv_mfma_2048(u, k, g_in, g_out, y, B, H, n, klen, s);
+    const int fused = conv_fused_path(n, klen, factors, nf, dt);
+    if (fused == 1) return launch_conv_mfma_2048(u, k, g_in, g_out, y, B, H, n, klen, s);
+    if (fused == 2) return launch_conv_mfma_256(u, k, g_in, g_out, y, B, H, n, klen, s);
 
     const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
     void *bufs[2] = {ws, (char *)ws + buf};

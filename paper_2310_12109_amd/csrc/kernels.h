@@ -60,6 +60,11 @@ bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monar
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                           int B, int H, int n, int klen, hipStream_t s);
 
+// nfft = 256 = 16 x 16, n <= 128, klen <= 256, bf16 I/O; no workspace.
+bool conv_mfma_256_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
+int launch_conv_mfma_256(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                         int B, int H, int n, int klen, hipStream_t s);
+
 // Block-diagonal MLP (order 1), bf16, d/nb a multiple of 32 up to 192, d_hidden/nb a multiple of 32.
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt);
 // b1_interleaved: hidden unit h of block k reads b1[h nb + k] instead of b1[k (d_hidden / nb) + h].
