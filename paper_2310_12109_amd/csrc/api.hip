@@ -179,6 +179,7 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
     // bf16 transforms with MFMA-sized factors run on the matrix cores and keep the rows packed as
     // bf16 pairs between passes; everything else takes the fp32 passes.
     const bool mf = fft_mfma_supported(N, factors, nf, dt);
+    const bool mf32 = fft_mfma_f32_supported(N, factors, nf, dt);   // fp32 MFMA, rows stay complex fp32
     for (int q = 0; q < nf; ++q) {
         FftPass p = blank_pass();
         set_pass_geometry(p, N, factors, nf, q);
@@ -201,7 +202,7 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
             p.out = bufs[q & 1];
             p.store = mf ? ST_C16 : ST_C32;
         }
-        rc = mf ? launch_fft_pass_mfma(p, s) : launch_fft_pass(p, s);
+        rc = mf ? launch_fft_pass_mfma(p, s) : mf32 ? launch_fft_pass_mfma_f32(p, s) : launch_fft_pass(p, s);
         if (rc) return rc;
         cur = p.out;
     }
@@ -267,14 +268,18 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
     return 2 * buf + kf;
 }
 
-// Multi-pass convolution on the matrix cores (bf16, factors 16..128).  The kernel is real, so two
+// Multi-pass convolution on the matrix cores (bf16 or fp32, factors 16..128).  The kernel is real, so two
 // real rows of the same channel are transformed as one complex row (re = batch 2 b2, im = batch
 // 2 b2 + 1): conv(a + i b, k) = conv(a, k) + i conv(b, k).  Rows travel between passes as packed
 // bf16 pairs; the spectrum of k is kept in fp32.
 static int conv_passes_mfma(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                             int B, int H, int n, int klen, int nfft, const int *factors, int nf,
-                            void *const bufs[2], float2 *kf, hipStream_t s)
+                            void *const bufs[2], float2 *kf, monarch_dtype dt, hipStream_t s)
 {
+    // bf16: packed bf16 pairs between passes; fp32 (16x16x4 MFMA): complex fp32 between passes
+    const bool half = dt == MONARCH_BF16;
+    const int ld_mid = half ? LD_C16 : LD_C32, st_mid = half ? ST_C16 : ST_C32;
+    auto launch = [&](const FftPass &p) { return half ? launch_fft_pass_mfma(p, s) : launch_fft_pass_mfma_f32(p, s); };
     const bool paired = B >= 2;
     const int64_t crows = paired ? (int64_t)((B + 1) / 2) * H : (int64_t)B * H;
     const void *cur = nullptr;
@@ -285,7 +290,7 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
             FftPass p = blank_pass();
             set_pass_geometry(p, nfft, factors, nf, q);
             p.rows = which == 0 ? H : crows;
-            p.dt = MONARCH_BF16;
+            p.dt = dt;
             p.in = cur;
             p.H = H;
             p.real_rows = (int64_t)B * H;
@@ -294,16 +299,16 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
                 p.n_valid = which == 0 ? klen : n;
                 p.gate = which == 0 ? nullptr : g_in;
             } else {
-                p.load = LD_C16;
+                p.load = ld_mid;
             }
             if (q == nf - 1) {
-                p.store = which == 0 ? ST_C32_NATURAL : ST_C16_NATURAL;
+                p.store = which == 0 || !half ? ST_C32_NATURAL : ST_C16_NATURAL;
                 p.out = which == 0 ? (void *)kf : bufs[q & 1];
             } else {
-                p.store = ST_C16;
+                p.store = st_mid;
                 p.out = bufs[q & 1];
             }
-            rc = launch_fft_pass_mfma(p, s);
+            rc = launch(p);
             if (rc) return rc;
             cur = p.out;
         }
@@ -314,15 +319,15 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
         FftPass p = blank_pass();
         set_pass_geometry(p, nfft, factors, nf, q);
         p.rows = crows;
-        p.dt = MONARCH_BF16;
+        p.dt = dt;
         p.in = cur;
         p.H = H;
         p.real_rows = (int64_t)B * H;
         if (q == 0) {
-            p.load = LD_C16_CONJ_MULK;
+            p.load = half ? LD_C16_CONJ_MULK : LD_C32_CONJ_MULK;
             p.kf = kf;
         } else {
-            p.load = LD_C16;
+            p.load = ld_mid;
         }
         if (q == nf - 1) {
             p.store = paired ? ST_REAL_PAIR : ST_REAL_SCALE_GATE;
@@ -331,10 +336,10 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
             p.n_valid = n;
             p.scale = 1.0f / (float)nfft;
         } else {
-            p.store = ST_C16;
+            p.store = st_mid;
             p.out = bufs[(first_out + q) & 1];
         }
-        rc = launch_fft_pass_mfma(p, s);
+        rc = launch(p);
         if (rc) return rc;
         cur = p.out;
     }
@@ -372,8 +377,8 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
     void *bufs[2] = {ws, (char *)ws + buf};
     float2 *kf = (float2 *)((char *)ws + 2 * buf);
 
-    if (fft_mfma_supported(nfft, factors, nf, dt))
-        return conv_passes_mfma(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, bufs, kf, s);
+    if (fft_mfma_supported(nfft, factors, nf, dt) || fft_mfma_f32_supported(nfft, factors, nf, dt))
+        return conv_passes_mfma(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, bufs, kf, dt, s);
 
     // 1. k_f = F k'  (H rows), staged through the row buffers.
     // 2. u_f = F (g_in o u)'  (B*H rows), left in natural order in one of the row buffers.

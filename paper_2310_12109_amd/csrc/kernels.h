@@ -46,6 +46,9 @@ int launch_fft_pass(const FftPass &p, hipStream_t s);
 // but the last storing ST_C16 and every pass but the first loading LD_C16.
 bool fft_mfma_supported(int N, const int *factors, int nf, monarch_dtype dt);
 int launch_fft_pass_mfma(const FftPass &p, hipStream_t s);
+// The fp32 version (16x16x4 MFMA): rows stay complex fp32 (LD_C32 / ST_C32) between passes.
+bool fft_mfma_f32_supported(int N, const int *factors, int nf, monarch_dtype dt);
+int launch_fft_pass_mfma_f32(const FftPass &p, hipStream_t s);
 
 // ---- fp32 MFMA Monarch multiply --------------------------------------------------------------
 
