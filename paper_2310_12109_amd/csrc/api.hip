@@ -69,6 +69,7 @@ static FftPass blank_pass()
     memset(&p, 0, sizeof(p));
     p.scale = 1.0f;
     p.H = 1;
+    p.pair_stride = 1;
     return p;
 }
 
@@ -280,8 +281,13 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
     const bool half = dt == MONARCH_BF16;
     const int ld_mid = half ? LD_C16 : LD_C32, st_mid = half ? ST_C16 : ST_C32;
     auto launch = [&](const FftPass &p) { return half ? launch_fft_pass_mfma(p, s) : launch_fft_pass_mfma_f32(p, s); };
-    const bool paired = B >= 2;
-    const int64_t crows = paired ? (int64_t)((B + 1) / 2) * H : (int64_t)B * H;
+    // B >= 2: batch entries 2 b2, 2 b2 + 1 of a channel share a complex row (same kernel, so the spectra just
+    // multiply).  B = 1 (one long sequence per channel), bf16: neighbouring channels share a complex row, the
+    // kernels are paired the same way and the first inverse pass separates the Hermitian halves.
+    const bool by_channel = half && B == 1 && H >= 2;
+    const bool paired = B >= 2 || by_channel;
+    const int pair_stride = by_channel ? 1 : H;
+    const int64_t crows = by_channel ? (H + 1) / 2 : paired ? (int64_t)((B + 1) / 2) * H : (int64_t)B * H;
     const void *cur = nullptr;
     int rc;
     for (int which = 0; which < 2; ++which) {   // 0: k_f = F k', 1: u_f = F (g_in o u)'
@@ -289,20 +295,21 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
         for (int q = 0; q < nf; ++q) {
             FftPass p = blank_pass();
             set_pass_geometry(p, nfft, factors, nf, q);
-            p.rows = which == 0 ? H : crows;
+            p.rows = which == 0 && !by_channel ? H : crows;
             p.dt = dt;
             p.in = cur;
             p.H = H;
+            p.pair_stride = pair_stride;
             p.real_rows = (int64_t)B * H;
             if (q == 0) {
-                p.load = which == 1 && paired ? LD_REAL_PAIR : LD_REAL;
+                p.load = (which == 1 && paired) || by_channel ? LD_REAL_PAIR : LD_REAL;
                 p.n_valid = which == 0 ? klen : n;
                 p.gate = which == 0 ? nullptr : g_in;
             } else {
                 p.load = ld_mid;
             }
             if (q == nf - 1) {
-                p.store = which == 0 || !half ? ST_C32_NATURAL : ST_C16_NATURAL;
+                p.store = (which == 0 && !by_channel) || !half ? ST_C32_NATURAL : ST_C16_NATURAL;
                 p.out = which == 0 ? (void *)kf : bufs[q & 1];
             } else {
                 p.store = st_mid;
@@ -322,9 +329,10 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
         p.dt = dt;
         p.in = cur;
         p.H = H;
+        p.pair_stride = pair_stride;
         p.real_rows = (int64_t)B * H;
         if (q == 0) {
-            p.load = half ? LD_C16_CONJ_MULK : LD_C32_CONJ_MULK;
+            p.load = by_channel ? LD_C16_HERM_MULK : half ? LD_C16_CONJ_MULK : LD_C32_CONJ_MULK;
             p.kf = kf;
         } else {
             p.load = ld_mid;

@@ -38,9 +38,11 @@ __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// Real rows of complex row rc when two real rows of the same channel are packed as (re, im):
-// complex row b2 * H + h holds real rows (2 b2) * H + h and (2 b2 + 1) * H + h.
-__device__ __forceinline__ int64_t pair_first_row(const FftPass &p, int64_t rc) { return rc + (rc / p.H) * p.H; }
+// First of the two real rows packed as (re, im) in complex row rc; the second is pair_stride rows on.
+__device__ __forceinline__ int64_t pair_first_row(const FftPass &p, int64_t rc)
+{
+    return rc + (rc / p.pair_stride) * p.pair_stride;   // (rc / ps) * 2 ps + rc % ps
+}
 
 // NT adjacent 32-bit words / bf16 values with one access (NT = 1 or 2; the callers guarantee the
 // natural alignment of the wider access).
@@ -108,6 +110,24 @@ __device__ __forceinline__ void load_values(const FftPass &p, int64_t rc, int po
             re[t] = m.x;
             im[t] = -m.y;
         }
+    } else if constexpr (LOAD == LD_C16_HERM_MULK) {
+        // z = a + i b with a, b real: A[m] = (Z[m] + conj Z[N-m]) / 2, B[m] = (Z[m] - conj Z[N-m]) / 2i; same for
+        // the kernels.  Wanted: conj(A Ka + i B Kb), the spectrum of conv(a, ka) + i conv(b, kb), conjugated.
+        const uint32_t *zrow = (const uint32_t *)p.in + rc * p.N, *krow = (const uint32_t *)p.kf + rc * p.N;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int m = pos + t, mr = (p.N - m) & (p.N - 1);   // N is a power of two here
+            const uint32_t z0 = zrow[m], z1 = zrow[mr], k0 = krow[m], k1 = krow[mr];
+            const float2 za = make_float2(lo_f32(z0), hi_f32(z0)), zb = make_float2(lo_f32(z1), -hi_f32(z1));
+            const float2 ka = make_float2(lo_f32(k0), hi_f32(k0)), kb = make_float2(lo_f32(k1), -hi_f32(k1));
+            const float2 A = make_float2(0.5f * (za.x + zb.x), 0.5f * (za.y + zb.y));
+            const float2 Bv = make_float2(0.5f * (za.y - zb.y), -0.5f * (za.x - zb.x));   // (za - zb) / 2i
+            const float2 Ka = make_float2(0.5f * (ka.x + kb.x), 0.5f * (ka.y + kb.y));
+            const float2 Kb = make_float2(0.5f * (ka.y - kb.y), -0.5f * (ka.x - kb.x));
+            const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);
+            re[t] = pa.x - pb.y;          // Re(pa + i pb)
+            im[t] = -(pa.y + pb.x);       // -Im(pa + i pb)
+        }
     } else if constexpr (LOAD == LD_REAL) {
         const bool ok = pos < p.n_valid;   // NT = 2: pos and n_valid are even
         const int64_t at = rc * p.n_valid + (ok ? pos : 0);
@@ -126,9 +146,9 @@ __device__ __forceinline__ void load_values(const FftPass &p, int64_t rc, int po
     } else {  // LD_REAL_PAIR
         const bool ok = pos < p.n_valid;
         const int64_t ra = pair_first_row(p, rc);
-        const bool okb = ok && ra + p.H < p.real_rows;
+        const bool okb = ok && ra + p.pair_stride < p.real_rows;
         const int64_t at = ra * p.n_valid + (ok ? pos : 0);
-        const int64_t bt = okb ? at + (int64_t)p.H * p.n_valid : at;
+        const int64_t bt = okb ? at + (int64_t)p.pair_stride * p.n_valid : at;
         float va[NT], vb[NT], ga[NT], gb[NT];
         load_bf16s<NT>((const T *)p.in + at, va);
         load_bf16s<NT>((const T *)p.in + bt, vb);
@@ -362,8 +382,8 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
                         } else {   // ST_REAL_PAIR: F^-1 = conj(F conj(.)) / N, so the second row is -Im
                             if (m < p.n_valid) {
                                 const int64_t ra = pair_first_row(p, rc);
-                                const int64_t at = ra * p.n_valid + m, bt = at + (int64_t)p.H * p.n_valid;
-                                const bool hasb = ra + p.H < p.real_rows;
+                                const int64_t at = ra * p.n_valid + m, bt = at + (int64_t)p.pair_stride * p.n_valid;
+                                const bool hasb = ra + p.pair_stride < p.real_rows;
                                 float va[NT], vb[NT], g[NT];
 #pragma unroll
                                 for (int t = 0; t < NT; ++t) {
@@ -447,6 +467,7 @@ static int launch_f(const FftPass &p, hipStream_t s)
         switch (p.load) {
         case LD_C16: return launch_one<F, LD_C16, ST_C16, false>(p, s);
         case LD_C16_CONJ_MULK: return launch_one<F, LD_C16_CONJ_MULK, ST_C16, false>(p, s);
+        case LD_C16_HERM_MULK: return launch_one<F, LD_C16_HERM_MULK, ST_C16, false>(p, s);
         case LD_C32_CONJ: return launch_one<F, LD_C32_CONJ, ST_C16, false>(p, s);
         case LD_REAL: return launch_one<F, LD_REAL, ST_C16, false>(p, s);
         case LD_REAL_PAIR: return launch_one<F, LD_REAL_PAIR, ST_C16, false>(p, s);

@@ -20,8 +20,11 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// complex row b2 * H + h packs real rows (2 b2) * H + h and (2 b2 + 1) * H + h
-__device__ __forceinline__ int64_t pair_first_row(const FftPass &p, int64_t rc) { return rc + (rc / p.H) * p.H; }
+// first of the two real rows packed as (re, im) in complex row rc; the second is pair_stride rows on
+__device__ __forceinline__ int64_t pair_first_row(const FftPass &p, int64_t rc)
+{
+    return rc + (rc / p.pair_stride) * p.pair_stride;   // (rc / ps) * 2 ps + rc % ps
+}
 
 template <int LOAD>
 __device__ __forceinline__ float2 load_value(const FftPass &p, int64_t rc, int pos)
@@ -46,9 +49,9 @@ __device__ __forceinline__ float2 load_value(const FftPass &p, int64_t rc, int p
     } else {  // LD_REAL_PAIR
         const bool ok = pos < p.n_valid;
         const int64_t ra = pair_first_row(p, rc);
-        const bool okb = ok && ra + p.H < p.real_rows;
+        const bool okb = ok && ra + p.pair_stride < p.real_rows;
         const int64_t at = ra * p.n_valid + (ok ? pos : 0);
-        const int64_t bt = okb ? at + (int64_t)p.H * p.n_valid : at;
+        const int64_t bt = okb ? at + (int64_t)p.pair_stride * p.n_valid : at;
         float va = ((const float *)p.in)[at], vb = ((const float *)p.in)[bt];
         if (p.gate) {
             va *= ((const float *)p.gate)[at];
@@ -168,8 +171,8 @@ __global__ __launch_bounds__(256, 2) void fft_pass_f32_kernel(const FftPass p)
                         } else {   // ST_REAL_PAIR: F^-1 = conj(F conj(.)) / N, so the second row is -Im
                             if (m < p.n_valid) {
                                 const int64_t ra = pair_first_row(p, rc);
-                                const int64_t at = ra * p.n_valid + m, bt = at + (int64_t)p.H * p.n_valid;
-                                const bool hasb = ra + p.H < p.real_rows;
+                                const int64_t at = ra * p.n_valid + m, bt = at + (int64_t)p.pair_stride * p.n_valid;
+                                const bool hasb = ra + p.pair_stride < p.real_rows;
                                 float va = z.x * p.scale, vb = -z.y * p.scale;
                                 if (p.gate) {
                                     va *= ((const float *)p.gate)[at];

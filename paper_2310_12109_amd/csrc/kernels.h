@@ -17,9 +17,11 @@ int launch_matmul_generic(const void *x, const void *R, const void *L, const voi
 bool matmul_generic_fits(int d_in, int d_mid, int d_out);
 
 // C32: complex fp32 (re, im); C16: complex as a packed bf16 pair (MFMA passes only); REAL / CPLX: the
-// caller's element type.  *_PAIR: two real rows of one channel travel as one complex row (MFMA only).
+// caller's element type.  *_PAIR: two real rows travel as one complex row (MFMA only).
+// LD_C16_HERM_MULK: rows and kernels were both paired across channels (z = a + i b, kz = ka + i kb, natural
+// order, packed bf16, kz in `kf`): the Hermitian halves are separated on load, A Ka + i B Kb is formed and conjugated.
 enum FftLoad { LD_C32 = 0, LD_C32_CONJ = 1, LD_C32_CONJ_MULK = 2, LD_REAL = 3, LD_CPLX = 4,
-               LD_C16 = 5, LD_C16_CONJ_MULK = 6, LD_REAL_PAIR = 7 };
+               LD_C16 = 5, LD_C16_CONJ_MULK = 6, LD_REAL_PAIR = 7, LD_C16_HERM_MULK = 8 };
 enum FftStore { ST_C32 = 0, ST_C32_NATURAL = 1, ST_CPLX_CONJ_SCALE = 2, ST_REAL_SCALE_GATE = 3,
                 ST_C16 = 4, ST_C16_NATURAL = 5, ST_REAL_PAIR = 6 };
 
@@ -34,7 +36,9 @@ struct FftPass {
     int nf;              // number of factors of the whole transform and the factors themselves
     int factors[3];
     int n_valid;         // LD_REAL: entries at positions >= n_valid are zero; ST_REAL: only t < n_valid is stored
-    int H;               // *_CONJ_MULK: row r uses kf row r % H; *_PAIR: complex row b2*H + h packs real rows (2 b2)*H + h, (2 b2 + 1)*H + h
+    int H;               // *_CONJ_MULK: row r uses kf row r % H
+    int pair_stride;     // *_PAIR: complex row rc packs real rows first = (rc / ps) * 2 ps + rc % ps (re) and first + ps (im):
+                         // ps = H pairs batch entries 2 b2, 2 b2 + 1 of a channel, ps = 1 pairs neighbouring rows
     int64_t real_rows;   // *_PAIR: number of real rows (the last complex rows may have no second member)
     float scale;         // store scale (1/N for the inverse)
     int load, store;

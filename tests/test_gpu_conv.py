@@ -87,6 +87,9 @@ def test_ragged_shapes_fp32(mm, B, H, n, klen, factors, gates):
     (4, 3, 1024, 300, (128, 16), "normal"),
     (3, 2, 2000, 2000, (16, 16, 16), "normal"),   # three factors
     (2, 2, 4096, 4096, (32, 16, 64), "normal"),   # nfft = 8n
+    (1, 5, 1000, 999, (32, 64), "normal"),        # B = 1: neighbouring channels share a complex row; H odd
+    (1, 4, 2048, 2048, (16, 16, 16), "normal"),   # the same with three factors
+    (1, 2, 3000, 17, (128, 64), "none"),          # short kernel, no gates
 ])
 def test_ragged_shapes_bf16_matrix_core_passes(mm, B, H, n, klen, factors, gates):
     announce("conv bf16 mfma passes", B, H, n, klen, factors, gates)
