@@ -1,0 +1,129 @@
+"""Times every configuration of the hot path through the binding and prints one line per case:
+`python -m paper_2310_12109_amd.measure_configs [c1 c2 c3a c3b c4 c5a c5b]`.
+
+Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
+rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
+Cache cannot serve a working set that is smaller than it; time = HIP events around `reps` back-to-back
+launches (replayed from a HIP graph), divided by their number.  Rates are algorithmic: bytes every implementation must move and the
+textbook FLOPs of the method (costmodel.py), over the measured time.
+"""
+import sys
+
+import torch
+
+from . import binding, costmodel
+
+HBM_PEAK_GBS = 8000.0
+
+
+def _sets(make, bytes_per_set):
+    n = max(1, min(24, int(512e6 // max(bytes_per_set, 1)) + 1))
+    return [make() for _ in range(n)]
+
+
+def _time(calls, reps):
+    """One pass over every buffer set is captured into a HIP graph and replayed, so that a kernel of a
+    few microseconds is not timed at the rate the interpreter can launch it."""
+    for c in calls:   # warm-up
+        c()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in calls:
+            c()
+    graph.replay()
+    torch.cuda.synchronize()
+    rounds = max(1, reps // len(calls))
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(rounds):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / (rounds * len(calls))   # microseconds per call
+
+
+def _rnd(*shape, dt=torch.bfloat16, scale=1.0):
+    return (torch.randn(*shape, device="cuda") * scale).to(dt)
+
+
+def _report(name, us, nbytes, flops, nsets):
+    gbs = nbytes / us / 1e3
+    print(f"{name:42s} {us:9.1f} us  {gbs:8.1f} GB/s ({gbs / HBM_PEAK_GBS:5.3f} of HBM)  {flops / us / 1e6:8.1f} TFLOP/s  "
+          f"[{nsets} buffer sets]", flush=True)
+
+
+def matmul_c1(batch, reps):
+    nbytes = 2 * batch * 256 * 4 + 2 * 16 * 256 * 4
+    R, L = _rnd(16, 16, 16, dt=torch.float32, scale=.25), _rnd(16, 16, 16, dt=torch.float32, scale=.25)
+
+    def make():
+        x = _rnd(batch, 256, dt=torch.float32)
+        y = torch.empty_like(x)
+        return lambda: binding.monarch_matmul(x, R, L, out=y)
+    calls = _sets(make, nbytes)
+    _report(f"c1 matmul fp32 16x16 blocks, batch {batch}", _time(calls, reps), nbytes, batch * 4 * 256 * 16, len(calls))
+
+
+def conv(name, B, H, n, factors, dt, reps):
+    es = 2 if dt == torch.bfloat16 else 4
+    code = binding.BF16 if dt == torch.bfloat16 else binding.F32
+    nbytes = costmodel.conv_algorithmic_bytes(B, H, n, n, es)
+    ws = torch.empty(max(16, binding.monarch_causal_conv_workspace_bytes(B, H, n, n, factors, code)), dtype=torch.uint8, device="cuda")
+
+    def make():
+        u, gi, go = _rnd(B, H, n, dt=dt), _rnd(B, H, n, dt=dt), _rnd(B, H, n, dt=dt)
+        k = _rnd(H, n, dt=dt, scale=.1)
+        y = torch.empty_like(u)
+        return lambda: binding.monarch_causal_conv(u, k, gi, go, factors, ws=ws, out=y)
+    calls = _sets(make, nbytes)
+    _report(name, _time(calls, reps), nbytes, costmodel.conv_textbook_flops(B, H, factors), len(calls))
+
+
+def mlp(name, tokens, d, dh, nb, order, reps):
+    nbytes = costmodel.mlp_algorithmic_bytes(tokens, d, dh, nb, order)
+    std = 0.02
+    if order == 1:
+        w = dict(W1_R=_rnd(nb, dh // nb, d // nb, scale=std), W1_L=None, W2_R=_rnd(nb, d // nb, dh // nb, scale=std), W2_L=None)
+    else:
+        w = dict(W1_R=_rnd(nb, d // nb, d // nb, scale=std), W1_L=_rnd(nb, dh // nb, d // nb, scale=std),
+                 W2_R=_rnd(nb, d // nb, dh // nb, scale=std), W2_L=_rnd(nb, d // nb, d // nb, scale=std))
+    b1, b2 = _rnd(dh, scale=std), _rnd(d, scale=std)
+    ws = torch.empty(max(16, binding.monarch_mlp_workspace_bytes(tokens, d, dh, nb, order)), dtype=torch.uint8, device="cuda")
+
+    def make():
+        x = _rnd(tokens, d)
+        y = torch.empty_like(x)
+        return lambda: binding.monarch_mlp(x, w["W1_R"], w["W1_L"], b1, w["W2_R"], w["W2_L"], b2, nb, order, 2, dh, ws=ws, out=y)
+    calls = _sets(make, nbytes)
+    _report(name, _time(calls, reps), nbytes, costmodel.mlp_flops(tokens, d, dh, nb, order), len(calls))
+
+
+def main():
+    only = sys.argv[1:]
+
+    def want(name):
+        return not only or name in only
+    torch.manual_seed(0)
+    if want("c1"):
+        matmul_c1(64, 200)
+        matmul_c1(1 << 20, 10)
+    if want("c2"):
+        conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
+        conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)
+    if want("c3a"):
+        conv("c3a conv bf16 B=32 H=768 n=128 16x16", 32, 768, 128, (16, 16), torch.bfloat16, 200)
+    if want("c3b"):
+        mlp("c3b mlp bf16 4096x768->3072 nb=4 order 1", 4096, 768, 3072, 4, 1, 100)
+        mlp("c3b mlp bf16 4096x768->3072 nb=4 order 2", 4096, 768, 3072, 4, 2, 100)
+    if want("c4"):
+        conv("c4 conv bf16 B=4 H=768 n=8192 128x128", 4, 768, 8192, (128, 128), torch.bfloat16, 20)
+    if want("c5a"):
+        conv("c5a conv bf16 B=1 H=256 n=131072 64^3", 1, 256, 131072, (64, 64, 64), torch.bfloat16, 10)
+    if want("c5b"):
+        mlp("c5b mlp bf16 65536x1024->4096 nb=16 order 1", 65536, 1024, 4096, 16, 1, 20)
+        mlp("c5b mlp bf16 65536x1024->4096 nb=16 order 2", 65536, 1024, 4096, 16, 2, 20)
+
+
+if __name__ == "__main__":
+    main()
