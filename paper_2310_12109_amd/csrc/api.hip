@@ -269,6 +269,59 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
     return 2 * buf + kf;
 }
 
+// Two-factor convolution with each transform done in one kernel on LDS-resident rows (bf16): the kernel's
+// spectrum, the spectrum of the (paired) rows, and the inverse: three launches, no strided pass.
+static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                           int B, int H, int n, int klen, int nfft, const int *factors,
+                           void *const bufs[2], float2 *kf, hipStream_t s)
+{
+    Fft2Args a;
+    memset(&a, 0, sizeof(a));
+    a.N = nfft;
+    a.O = 1;
+    a.f1 = factors[0];
+    a.f2 = factors[1];
+    a.H = H;
+    a.pair_stride = H;
+    a.real_rows = (int64_t)B * H;
+    a.scale = 1.0f;
+    // k_f = F k'
+    Fft2Args p = a;
+    p.in = k;
+    p.out = kf;
+    p.rows = H;
+    p.n_valid = klen;
+    p.load = LD_REAL;
+    p.store = ST_C16;
+    int rc = launch_fft2_lds(p, s);
+    if (rc) return rc;
+    // u_f = F (g_in o u)', two batch entries of a channel per complex row
+    const int64_t crows = (int64_t)((B + 1) / 2) * H;
+    p = a;
+    p.in = u;
+    p.gate = g_in;
+    p.out = bufs[0];
+    p.rows = crows;
+    p.n_valid = n;
+    p.load = LD_REAL_PAIR;
+    p.store = ST_C16;
+    rc = launch_fft2_lds(p, s);
+    if (rc) return rc;
+    // y = F^-1 (k_f o u_f), truncated, times g_out
+    p = a;
+    p.in = bufs[0];
+    p.kf = kf;
+    p.gate = g_out;
+    p.out = y;
+    p.rows = crows;
+    p.n_valid = n;
+    p.inverse = 1;
+    p.load = LD_C16_CONJ_MULK;
+    p.store = ST_REAL_PAIR;
+    p.scale = 1.0f / (float)nfft;
+    return launch_fft2_lds(p, s);
+}
+
 // Multi-pass convolution on the matrix cores (bf16 or fp32, factors 16..128).  The kernel is real, so two
 // real rows of the same channel are transformed as one complex row (re = batch 2 b2, im = batch
 // 2 b2 + 1): conv(a + i b, k) = conv(a, k) + i conv(b, k).  Rows travel between passes as packed
@@ -385,6 +438,8 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
     void *bufs[2] = {ws, (char *)ws + buf};
     float2 *kf = (float2 *)((char *)ws + 2 * buf);
 
+    if (nf == 2 && B >= 2 && fft2_lds_supported(factors[0], factors[1], dt))
+        return conv_chunks_lds(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, bufs, kf, s);
     if (fft_mfma_supported(nfft, factors, nf, dt) || fft_mfma_f32_supported(nfft, factors, nf, dt))
         return conv_passes_mfma(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, bufs, kf, dt, s);
 

@@ -1,0 +1,509 @@
+// Two factors of the Monarch DFT (appendix, DFT corollary) in one kernel, on a chunk of f1 x f2
+// complex numbers held in LDS: bf16 operands, fp32 accumulation, f1, f2 in {16, 32, 64, 128}.
+//
+// The chunk is the last two digits [c1][c2] of a row (the whole row for two factors).  It is read
+// from global memory once with coalesced 16-byte accesses, both block-diagonal factors and the
+// twiddle diagonal between them are applied in place in LDS, and it is written back once:
+//   forward:  X: contract c1 -> j1, times omega_(f1 f2)^(j1 c2);   Y: contract c2 -> j2
+//   inverse (as conj o F o conj, factors in the opposite order):
+//             Y: contract j2 -> c2, times omega_(f1 f2)^(j1 c2);   X: contract j1 -> c1
+// so the spectrum stays in the order the forward leaves it in, position [j1][j2] holding frequency
+// j2 f1 + j1: the element-wise product with the kernel's spectrum needs no reordering, and neither
+// transform ever stores with a stride.  Stage X reads operands down the columns of the tile
+// (8 x 4 bytes per k-step), stage Y along its rows (2 x 16 bytes per k-step); each wave owns whole
+// column tiles (X) or row tiles (Y), so a stage works in place and one barrier separates the stages.
+#include "kernels.h"
+
+namespace monarch {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+namespace f2l {
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    bf16x2 v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float lo_f32(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float hi_f32(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+__device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+constexpr int pitch_of(int f2) { return f2 + 4; }              // words per tile row: 16-byte aligned, 4 banks off
+constexpr int table_words(int f) { return (f / 16) * ((f + 31) / 32) * 2 * 64 * 4; }
+
+// A-operand table of F_f in MFMA operand order: piece ((jt * KS + ks) * 2 + part) * 64 + lane
+template <int F, int THREADS>
+__device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    for (int e = threadIdx.x; e < F; e += THREADS) roots[e] = omega(e, F);
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < JT * KS * 64; idx += THREADS) {
+        const int ln = idx & 63, ks = (idx >> 6) % KS, jt = idx / (64 * KS);
+        const int j = 16 * jt + (ln & 15), c0 = 32 * ks + 8 * (ln >> 4);
+        u32x4 re, im;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            float2 w0 = make_float2(0.0f, 0.0f), w1 = w0;
+            if (c0 + 2 * h < F) w0 = roots[(j * (c0 + 2 * h)) % F];
+            if (c0 + 2 * h + 1 < F) w1 = roots[(j * (c0 + 2 * h + 1)) % F];
+            re[h] = pack2(w0.x, w1.x);
+            im[h] = pack2(w0.y, w1.y);
+        }
+        tab[(idx >> 6) * 128 + ln] = re;
+        tab[(idx >> 6) * 128 + 64 + ln] = im;
+    }
+    __syncthreads();
+}
+
+// One stage on one tile of 16 columns.  STRIDED: element (c, col) at tile[c * PITCH + col] (stage X);
+// otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: row
+// tiles of the output that are needed.  TW: multiply output (j, col) by omega_(mod)^(j col).
+template <int F, int PITCH, bool STRIDED, bool TW>
+__device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int col, int lane, int live_ks, int want_jt,
+                                           float inv_mod)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    const int kg = lane >> 4;
+    u32x4 br[KS], bi[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const int c0 = 32 * ks + 8 * kg;
+        uint32_t w[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = 0u;
+        if (ks < live_ks && c0 < F) {
+            if constexpr (STRIDED) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e] = tile[(c0 + e) * PITCH + col];
+            } else {
+                const u32x4 v0 = *reinterpret_cast<const u32x4 *>(tile + col * PITCH + c0);
+                const u32x4 v1 = *reinterpret_cast<const u32x4 *>(tile + col * PITCH + c0 + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    w[e] = v0[e];
+                    w[4 + e] = v1[e];
+                }
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            br[ks][h] = (w[2 * h] & 0xffffu) | (w[2 * h + 1] << 16);
+            bi[ks][h] = (w[2 * h] >> 16) | (w[2 * h + 1] & 0xffff0000u);
+        }
+    }
+    float2 tw[4], step;
+    if constexpr (TW) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float rev = (float)((4 * kg + r) * col) * inv_mod;   // exact: j col < modulus <= 2^24
+            tw[r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+        }
+        const float rev = (float)(16 * col) * inv_mod;
+        step = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+    }
+#pragma unroll 1
+    for (int jt = 0; jt < JT; ++jt) {
+        if (jt < want_jt) {
+            f32x4 dr = {0, 0, 0, 0}, di = {0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks < live_ks) {
+                    const u32x4 ar = tab[(jt * KS + ks) * 128 + lane], ai = tab[(jt * KS + ks) * 128 + 64 + lane];
+                    const u32x4 nai = ai ^ 0x80008000u;
+                    dr = mfma(ar, br[ks], dr);
+                    dr = mfma(nai, bi[ks], dr);
+                    di = mfma(ai, br[ks], di);
+                    di = mfma(ar, bi[ks], di);
+                }
+            }
+            uint32_t o[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float2 z = make_float2(dr[r], di[r]);
+                if constexpr (TW) z = cmul(z, tw[r]);
+                o[r] = pack2(z.x, z.y);
+            }
+            if constexpr (STRIDED) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tile[(16 * jt + 4 * kg + r) * PITCH + col] = o[r];
+            } else {
+                *reinterpret_cast<u32x4 *>(tile + col * PITCH + 16 * jt + 4 * kg) = u32x4{o[0], o[1], o[2], o[3]};
+            }
+        }
+        if constexpr (TW) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tw[r] = cmul(tw[r], step);
+        }
+    }
+}
+
+__device__ __forceinline__ int64_t pair_first_row(const Fft2Args &p, int64_t rc)
+{
+    return rc + (rc / p.pair_stride) * p.pair_stride;
+}
+
+// 8 bf16 values of a 16-byte piece as floats
+__device__ __forceinline__ void unpack8(const u32x4 &w, float (&v)[8])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        v[2 * t] = lo_f32(w[t]);
+        v[2 * t + 1] = hi_f32(w[t]);
+    }
+}
+
+// VEC: real rows are read and written 16 bytes (8 elements) at a time, which needs n_valid % 8 == 0; all
+// global loads of a chunk are issued together, those of the next chunk (and the output gates of this one)
+// before the stages of the current one, so that they are in flight while the matrix cores work.
+template <int F1, int F2, bool INVERSE, int LOAD, int STORE, bool VEC>
+__global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_kernel(const Fft2Args p)
+{
+    constexpr int THREADS = F1 >= 128 || F2 >= 128 ? 512 : 256, WAVES = THREADS / 64;
+    constexpr int PITCH = pitch_of(F2), CH = F1 * F2;
+    constexpr bool REAL_IN = LOAD == LD_REAL || LOAD == LD_REAL_PAIR;
+    constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
+    constexpr bool MULK = LOAD == LD_C16_CONJ_MULK;
+    constexpr int NIT4 = (CH + 4 * THREADS - 1) / (4 * THREADS);   // steps of 4 complex elements per thread
+    constexpr int NIT8 = (CH + 8 * THREADS - 1) / (8 * THREADS);   // steps of 8 real elements per thread
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    uint32_t *tile = lds;                                                   // [F1][PITCH] packed bf16 pairs
+    u32x4 *tab1 = reinterpret_cast<u32x4 *>(lds + F1 * PITCH);              // F_f1 operands
+    u32x4 *tab2 = F1 == F2 ? tab1 : tab1 + table_words(F1) / 4;             // F_f2 operands
+    __shared__ float2 roots[F1 > F2 ? F1 : F2];
+    build_table<F1, THREADS>(tab1, roots);
+    if constexpr (F1 != F2) build_table<F2, THREADS>(tab2, roots);
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t nchunks = p.rows * p.O;
+    const float inv_mod = 1.0f / (float)CH;
+    // rows of the tile that hold input (forward, zero-padded real rows) or wanted output (inverse, truncated)
+    const int real_rows_of_tile = (p.n_valid + F2 - 1) / F2;
+    const int live_x = REAL_IN ? (real_rows_of_tile + 31) / 32 : (F1 + 31) / 32;   // k-steps of stage X with input
+    const int want_x = REAL_OUT ? (real_rows_of_tile + 15) / 16 : F1 / 16;         // row tiles of stage X wanted
+    const int lim = REAL_IN ? (live_x * 32 * F2 < CH ? live_x * 32 * F2 : CH) : CH;   // tile elements stage X reads
+    auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
+
+    // staged inputs of one chunk
+    u32x4 za[REAL_IN ? NIT8 : NIT4], zb[REAL_IN ? NIT8 : NIT4], zc[REAL_IN ? NIT8 : 1], zd[REAL_IN ? NIT8 : 1];
+    auto request = [&](int64_t q) {
+        const int64_t rc = q / p.O;
+        if constexpr (REAL_IN) {
+            if constexpr (VEC) {
+                const int64_t ra = LOAD == LD_REAL_PAIR ? pair_first_row(p, rc) : rc;
+                const bool hasb = LOAD == LD_REAL_PAIR && ra + p.pair_stride < p.real_rows;
+                const bf16_t *ua = (const bf16_t *)p.in + ra * p.n_valid, *ub = hasb ? ua + (int64_t)p.pair_stride * p.n_valid : ua;
+                const bf16_t *ga = p.gate ? (const bf16_t *)p.gate + ra * p.n_valid : ua;
+                const bf16_t *gb = p.gate && hasb ? ga + (int64_t)p.pair_stride * p.n_valid : ga;
+#pragma unroll
+                for (int it = 0; it < NIT8; ++it) {
+                    const int e = 8 * (tid + it * THREADS);
+                    const int ee = e < p.n_valid ? e : 0;   // past the row: any valid address, the value is dropped
+                    if (it * 8 * THREADS < lim) {
+                        za[it] = *reinterpret_cast<const u32x4 *>(ua + ee);
+                        zc[it] = *reinterpret_cast<const u32x4 *>(ga + ee);
+                        if (LOAD == LD_REAL_PAIR) {
+                            zb[it] = *reinterpret_cast<const u32x4 *>(ub + ee);
+                            zd[it] = *reinterpret_cast<const u32x4 *>(gb + ee);
+                        }
+                    }
+                }
+            }
+        } else {
+            const int64_t at0 = rc * p.N + (q - rc * p.O) * CH;
+            const uint32_t *src = (const uint32_t *)p.in + at0;
+            const uint32_t *ksrc = MULK ? (const uint32_t *)p.kf + (rc % p.H) * (int64_t)p.N + (q - rc * p.O) * CH : src;
+#pragma unroll
+            for (int it = 0; it < NIT4; ++it) {
+                const int e = 4 * (tid + it * THREADS);
+                if (e < CH) {
+                    za[it] = *reinterpret_cast<const u32x4 *>(src + e);
+                    if (MULK) zb[it] = *reinterpret_cast<const u32x4 *>(ksrc + e);
+                }
+            }
+        }
+    };
+    auto deposit = [&](int64_t q) {   // staged inputs -> tile (natural order of the chunk)
+        if constexpr (REAL_IN) {
+            const int64_t rc = q / p.O;
+            const int64_t ra = LOAD == LD_REAL_PAIR ? pair_first_row(p, rc) : rc;
+            const bool hasb = LOAD == LD_REAL_PAIR && ra + p.pair_stride < p.real_rows;
+            if constexpr (VEC) {
+#pragma unroll
+                for (int it = 0; it < NIT8; ++it) {
+                    const int e = 8 * (tid + it * THREADS);
+                    if (e < lim) {
+                        float a[8], b[8], g[8];
+                        const bool ok = e < p.n_valid;
+                        unpack8(za[it], a);
+                        if (p.gate) {
+                            unpack8(zc[it], g);
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) a[t] *= g[t];
+                        }
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) b[t] = 0.0f;
+                        if (LOAD == LD_REAL_PAIR && hasb) {
+                            unpack8(zb[it], b);
+                            if (p.gate) {
+                                unpack8(zd[it], g);
+#pragma unroll
+                                for (int t = 0; t < 8; ++t) b[t] *= g[t];
+                            }
+                        }
+                        u32x4 w0, w1;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            w0[t] = ok ? pack2(a[t], b[t]) : 0u;
+                            w1[t] = ok ? pack2(a[4 + t], b[4 + t]) : 0u;
+                        }
+                        *reinterpret_cast<u32x4 *>(tile + tix(e)) = w0;
+                        *reinterpret_cast<u32x4 *>(tile + tix(e + 4)) = w1;
+                    }
+                }
+            } else {   // any row length: element by element
+                const bf16_t *ua = (const bf16_t *)p.in + ra * p.n_valid, *ub = ua + (int64_t)p.pair_stride * p.n_valid;
+                const bf16_t *ga = p.gate ? (const bf16_t *)p.gate + ra * p.n_valid : nullptr;
+                const bf16_t *gb = ga ? ga + (int64_t)p.pair_stride * p.n_valid : nullptr;
+                for (int e = 4 * tid; e < lim; e += 4 * THREADS) {
+                    u32x4 w;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const bool ok = e + t < p.n_valid;
+                        float re = ok ? (float)ua[e + t] : 0.0f, im = ok && hasb ? (float)ub[e + t] : 0.0f;
+                        if (ga) {
+                            re *= ok ? (float)ga[e + t] : 0.0f;
+                            im *= ok && hasb ? (float)gb[e + t] : 0.0f;
+                        }
+                        w[t] = pack2(re, im);
+                    }
+                    *reinterpret_cast<u32x4 *>(tile + tix(e)) = w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < NIT4; ++it) {
+                const int e = 4 * (tid + it * THREADS);
+                if (e < CH) {
+                    u32x4 w = za[it];
+                    if constexpr (MULK) {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float2 m = cmul(make_float2(lo_f32(w[t]), hi_f32(w[t])),
+                                                  make_float2(lo_f32(zb[it][t]), hi_f32(zb[it][t])));
+                            w[t] = pack2(m.x, -m.y);
+                        }
+                    }
+                    *reinterpret_cast<u32x4 *>(tile + tix(e)) = w;
+                }
+            }
+        }
+    };
+
+    if (blockIdx.x < nchunks) request(blockIdx.x);
+    for (int64_t q = blockIdx.x; q < nchunks; q += gridDim.x) {
+        const int64_t rc = q / p.O;
+        deposit(q);
+        __syncthreads();
+        if (q + gridDim.x < nchunks) request(q + gridDim.x);
+
+        // output gates of this chunk, requested before the stages
+        const int64_t ra = STORE == ST_REAL_PAIR ? pair_first_row(p, rc) : rc;
+        const bool hasb = STORE == ST_REAL_PAIR && ra + p.pair_stride < p.real_rows;
+        u32x4 oga[REAL_OUT && VEC ? NIT8 : 1], ogb[REAL_OUT && VEC ? NIT8 : 1];
+        if constexpr (REAL_OUT && VEC) {
+            if (p.gate) {
+                const bf16_t *ga = (const bf16_t *)p.gate + ra * p.n_valid, *gb = hasb ? ga + (int64_t)p.pair_stride * p.n_valid : ga;
+#pragma unroll
+                for (int it = 0; it < NIT8; ++it) {
+                    const int e = 8 * (tid + it * THREADS);
+                    if (e < p.n_valid) {
+                        oga[it] = *reinterpret_cast<const u32x4 *>(ga + e);
+                        if (STORE == ST_REAL_PAIR) ogb[it] = *reinterpret_cast<const u32x4 *>(gb + e);
+                    }
+                }
+            }
+        }
+
+        // ---- the two stages
+        if constexpr (!INVERSE) {
+            for (int t = wave; t < F2 / 16; t += WAVES)
+                stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, live_x, F1 / 16, inv_mod);
+            __syncthreads();
+            for (int t = wave; t < F1 / 16; t += WAVES)
+                stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, inv_mod);
+        } else {
+            for (int t = wave; t < F1 / 16; t += WAVES)
+                stage_tile<F2, PITCH, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, inv_mod);
+            __syncthreads();
+            for (int t = wave; t < F2 / 16; t += WAVES)
+                stage_tile<F1, PITCH, true, false>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, inv_mod);
+        }
+        __syncthreads();
+
+        // ---- tile -> global
+        if constexpr (!REAL_OUT) {
+            uint32_t *dst = (uint32_t *)p.out + rc * p.N + (q - rc * p.O) * CH;
+#pragma unroll
+            for (int it = 0; it < NIT4; ++it) {
+                const int e = 4 * (tid + it * THREADS);
+                if (e < CH) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+            }
+        } else {
+            // F^-1 = conj(F conj(.)) / N: first member = Re / N, second = -Im / N, times the output gate
+            bf16_t *ya = (bf16_t *)p.out + ra * p.n_valid, *yb = ya + (int64_t)p.pair_stride * p.n_valid;
+            if constexpr (VEC) {
+#pragma unroll
+                for (int it = 0; it < NIT8; ++it) {
+                    const int e = 8 * (tid + it * THREADS);
+                    if (e < p.n_valid) {
+                        const u32x4 w0 = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+                        const u32x4 w1 = *reinterpret_cast<const u32x4 *>(tile + tix(e + 4));
+                        float va[8], vb[8], g[8];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            va[t] = lo_f32(w0[t]) * p.scale;
+                            vb[t] = -hi_f32(w0[t]) * p.scale;
+                            va[4 + t] = lo_f32(w1[t]) * p.scale;
+                            vb[4 + t] = -hi_f32(w1[t]) * p.scale;
+                        }
+                        if (p.gate) {
+                            unpack8(oga[it], g);
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) va[t] *= g[t];
+                        }
+                        *reinterpret_cast<u32x4 *>(ya + e) =
+                            u32x4{pack2(va[0], va[1]), pack2(va[2], va[3]), pack2(va[4], va[5]), pack2(va[6], va[7])};
+                        if (STORE == ST_REAL_PAIR && hasb) {
+                            if (p.gate) {
+                                unpack8(ogb[it], g);
+#pragma unroll
+                                for (int t = 0; t < 8; ++t) vb[t] *= g[t];
+                            }
+                            *reinterpret_cast<u32x4 *>(yb + e) =
+                                u32x4{pack2(vb[0], vb[1]), pack2(vb[2], vb[3]), pack2(vb[4], vb[5]), pack2(vb[6], vb[7])};
+                        }
+                    }
+                }
+            } else {
+                const bf16_t *ga = p.gate ? (const bf16_t *)p.gate + ra * p.n_valid : nullptr;
+                const bf16_t *gb = ga ? ga + (int64_t)p.pair_stride * p.n_valid : nullptr;
+                for (int e = 4 * tid; e < p.n_valid; e += 4 * THREADS) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        if (e + t < p.n_valid) {
+                            float va = lo_f32(w[t]) * p.scale, vb = -hi_f32(w[t]) * p.scale;
+                            if (ga) va *= (float)ga[e + t];
+                            ya[e + t] = (bf16_t)va;
+                            if (hasb) {
+                                if (gb) vb *= (float)gb[e + t];
+                                yb[e + t] = (bf16_t)vb;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+static size_t lds_bytes(int f1, int f2)
+{
+    return ((size_t)f1 * pitch_of(f2) + table_words(f1) + (f1 == f2 ? 0 : table_words(f2))) * 4;
+}
+
+template <int F1, int F2, bool INVERSE, int LOAD, int STORE, bool VEC>
+static int launch_vec(const Fft2Args &p, hipStream_t s)
+{
+    constexpr int THREADS = F1 >= 128 || F2 >= 128 ? 512 : 256;
+    const size_t lds = lds_bytes(F1, F2);
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int per_cu = (int)((160 * 1024) / (lds + 1024));
+    const int64_t nchunks = p.rows * p.O;
+    int64_t grid = (int64_t)ncu * (per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu);
+    if (grid > nchunks) grid = nchunks;
+    auto kern = fft2_lds_kernel<F1, F2, INVERSE, LOAD, STORE, VEC>;
+    if (lds > 48 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, p);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+template <int F1, int F2, bool INVERSE, int LOAD, int STORE>
+static int launch_one(const Fft2Args &p, hipStream_t s)
+{
+    constexpr bool real_rows = LOAD == LD_REAL || LOAD == LD_REAL_PAIR || STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
+    if (!real_rows || p.n_valid % 8 == 0) return launch_vec<F1, F2, INVERSE, LOAD, STORE, true>(p, s);
+    return launch_vec<F1, F2, INVERSE, LOAD, STORE, false>(p, s);
+}
+
+template <int F1, int F2>
+static int launch_modes(const Fft2Args &p, hipStream_t s)
+{
+    if (!p.inverse) {
+        if (p.store != ST_C16) return fail(MONARCH_EINVAL, "internal: forward chunk kernel stores packed pairs only");
+        switch (p.load) {
+        case LD_REAL: return launch_one<F1, F2, false, LD_REAL, ST_C16>(p, s);
+        case LD_REAL_PAIR: return launch_one<F1, F2, false, LD_REAL_PAIR, ST_C16>(p, s);
+        case LD_C16: return launch_one<F1, F2, false, LD_C16, ST_C16>(p, s);
+        default: break;
+        }
+    } else if (p.load == LD_C16_CONJ_MULK) {
+        switch (p.store) {
+        case ST_REAL_SCALE_GATE: return launch_one<F1, F2, true, LD_C16_CONJ_MULK, ST_REAL_SCALE_GATE>(p, s);
+        case ST_REAL_PAIR: return launch_one<F1, F2, true, LD_C16_CONJ_MULK, ST_REAL_PAIR>(p, s);
+        case ST_C16: return launch_one<F1, F2, true, LD_C16_CONJ_MULK, ST_C16>(p, s);
+        default: break;
+        }
+    }
+    return fail(MONARCH_EINVAL, "internal: chunk kernel modes %d/%d not built", p.load, p.store);
+}
+
+}  // namespace f2l
+
+// the chunk shapes that are instantiated below
+static bool chunk_built(int f1, int f2)
+{
+    static const int shapes[][2] = {{128, 128}, {64, 64}, {64, 32}, {32, 64}, {32, 32}, {16, 16}, {128, 64}, {64, 128}};
+    for (const auto &sh : shapes)
+        if (sh[0] == f1 && sh[1] == f2) return true;
+    return false;
+}
+
+bool fft2_lds_supported(int f1, int f2, monarch_dtype dt)
+{
+    return dt == MONARCH_BF16 && chunk_built(f1, f2) && f2l::lds_bytes(f1, f2) + 1024 <= 160 * 1024;
+}
+
+int launch_fft2_lds(const Fft2Args &p, hipStream_t s)
+{
+    if (p.rows == 0) return MONARCH_OK;
+    if ((int64_t)p.O * p.f1 * p.f2 != p.N) return fail(MONARCH_EINVAL, "internal: chunk geometry does not multiply to N");
+#define MONARCH_F2L(A, B) \
+    if (p.f1 == A && p.f2 == B) return f2l::launch_modes<A, B>(p, s)
+    MONARCH_F2L(128, 128);
+    MONARCH_F2L(64, 64);
+    MONARCH_F2L(64, 32);
+    MONARCH_F2L(32, 64);
+    MONARCH_F2L(32, 32);
+    MONARCH_F2L(16, 16);
+    MONARCH_F2L(128, 64);
+    MONARCH_F2L(64, 128);
+#undef MONARCH_F2L
+    return fail(MONARCH_EINVAL, "internal: chunk %d x %d not built", p.f1, p.f2);
+}
+
+}  // namespace monarch

@@ -60,6 +60,27 @@ int launch_fft_pass_mfma_f32(const FftPass &p, hipStream_t s);
 bool matmul_mfma_b16_supported(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in, monarch_dtype dt);
 int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y, int64_t batch, hipStream_t s);
 
+// Two factors at once on chunks of f1 x f2 complex numbers held in LDS (bf16; see fft2_lds.hip).  The
+// spectrum is left in the forward's in-place order (position [j1][j2] = frequency j2 f1 + j1) and the
+// inverse consumes that order.  Loads: LD_REAL / LD_REAL_PAIR (whole rows, two factors) or LD_C16 forward,
+// LD_C16_CONJ_MULK inverse (kf: packed bf16 pairs in the same order, row r % H); stores: ST_C16, or
+// ST_REAL_SCALE_GATE / ST_REAL_PAIR for the inverse of a two-factor transform.
+struct Fft2Args {
+    const void *in;
+    void *out;
+    const void *gate;
+    const void *kf;
+    int64_t rows;        // complex rows
+    int N, O, f1, f2;    // row length, chunks per row, chunk = f1 x f2
+    int n_valid;         // real rows: their length (zero padded / truncated)
+    int H, pair_stride;
+    int64_t real_rows;
+    float scale;
+    int load, store, inverse;
+};
+bool fft2_lds_supported(int f1, int f2, monarch_dtype dt);
+int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
+
 // ---- fused bf16 MFMA kernels ---------------------------------------------------------------
 
 // nfft = 2048 = 64 x 32, n <= 1024, klen <= 1024 (both multiples of 8), bf16 I/O.
