@@ -269,57 +269,112 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
     return 2 * buf + kf;
 }
 
-// Two-factor convolution with each transform done in one kernel on LDS-resident rows (bf16): the kernel's
-// spectrum, the spectrum of the (paired) rows, and the inverse: three launches, no strided pass.
+// Convolution with the last two factors of every transform done in one kernel on LDS-resident chunks (bf16).
+// Two factors: three launches (spectrum of k, spectrum of the paired rows, inverse), no strided pass.
+// Three factors: the first factor is a strided pass before the chunk kernel (forward) and after it (inverse,
+// whose factors run in the opposite order), six launches.  Spectra stay in the order the forward leaves them in.
+static bool conv_chunks_supported(const int *factors, int nf, monarch_dtype dt)
+{
+    if (nf == 2) return fft2_lds_supported(factors[0], factors[1], dt);
+    const int f0 = factors[0];
+    return nf == 3 && (f0 == 16 || f0 == 32 || f0 == 64 || f0 == 128) && fft2_lds_supported(factors[1], factors[2], dt);
+}
+
 static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
-                           int B, int H, int n, int klen, int nfft, const int *factors,
+                           int B, int H, int n, int klen, int nfft, const int *factors, int nf,
                            void *const bufs[2], float2 *kf, hipStream_t s)
 {
+    // rows that share a complex row: two batch entries of a channel, or (one sequence per channel) two
+    // neighbouring channels, then with the kernels paired alike and separated again before the inverse
+    const bool by_channel = B == 1 && H >= 2;
+    const bool paired = B >= 2 || by_channel;
+    const int pair_stride = by_channel ? 1 : H;
+    const int64_t crows = by_channel ? (H + 1) / 2 : paired ? (int64_t)((B + 1) / 2) * H : (int64_t)B * H;
+    const int f1 = factors[nf - 2], f2 = factors[nf - 1], O = nf == 3 ? factors[0] : 1;
+
     Fft2Args a;
     memset(&a, 0, sizeof(a));
     a.N = nfft;
-    a.O = 1;
-    a.f1 = factors[0];
-    a.f2 = factors[1];
+    a.O = O;
+    a.f1 = f1;
+    a.f2 = f2;
     a.H = H;
-    a.pair_stride = H;
+    a.pair_stride = pair_stride;
     a.real_rows = (int64_t)B * H;
     a.scale = 1.0f;
-    // k_f = F k'
+    FftPass first = blank_pass();   // the strided pass of a three-factor transform
+    if (nf == 3) {
+        set_pass_geometry(first, nfft, factors, nf, 0);
+        first.dt = MONARCH_BF16;
+        first.H = H;
+        first.pair_stride = pair_stride;
+        first.real_rows = (int64_t)B * H;
+    }
+    int rc;
+    for (int which = 0; which < 2; ++which) {   // 0: spectrum of k (into kf), 1: spectrum of g_in o u (into bufs[1])
+        const bool pair_here = which == 0 ? by_channel : paired;
+        const int64_t rows = which == 0 ? (by_channel ? crows : H) : crows;
+        const void *src = which == 0 ? k : u;
+        const void *gate = which == 0 ? nullptr : g_in;
+        const int valid = which == 0 ? klen : n;
+        void *dst = which == 0 ? (void *)kf : bufs[1];
+        Fft2Args p = a;
+        p.rows = rows;
+        p.out = dst;
+        p.store = ST_C16;
+        if (nf == 2) {
+            p.in = src;
+            p.gate = gate;
+            p.n_valid = valid;
+            p.load = pair_here ? LD_REAL_PAIR : LD_REAL;
+        } else {
+            FftPass q = first;
+            q.rows = rows;
+            q.in = src;
+            q.gate = gate;
+            q.n_valid = valid;
+            q.load = pair_here ? LD_REAL_PAIR : LD_REAL;
+            q.out = bufs[0];
+            q.store = ST_C16;
+            rc = launch_fft_pass_mfma(q, s);
+            if (rc) return rc;
+            p.in = bufs[0];
+            p.load = LD_C16;
+        }
+        rc = launch_fft2_lds(p, s);
+        if (rc) return rc;
+    }
+    // inverse: product of the spectra on load, chunk factors, then (three factors) the strided factor
     Fft2Args p = a;
-    p.in = k;
-    p.out = kf;
-    p.rows = H;
-    p.n_valid = klen;
-    p.load = LD_REAL;
-    p.store = ST_C16;
-    int rc = launch_fft2_lds(p, s);
-    if (rc) return rc;
-    // u_f = F (g_in o u)', two batch entries of a channel per complex row
-    const int64_t crows = (int64_t)((B + 1) / 2) * H;
-    p = a;
-    p.in = u;
-    p.gate = g_in;
-    p.out = bufs[0];
     p.rows = crows;
-    p.n_valid = n;
-    p.load = LD_REAL_PAIR;
+    p.in = bufs[1];
+    p.kf = kf;
+    p.inverse = 1;
+    p.load = by_channel ? LD_C16_HERM_MULK : LD_C16_CONJ_MULK;
+    const int real_store = paired ? ST_REAL_PAIR : ST_REAL_SCALE_GATE;
+    if (nf == 2) {
+        p.gate = g_out;
+        p.out = y;
+        p.n_valid = n;
+        p.store = real_store;
+        p.scale = 1.0f / (float)nfft;
+        return launch_fft2_lds(p, s);
+    }
+    p.out = bufs[0];
     p.store = ST_C16;
+    p.tw_outer = 1;
     rc = launch_fft2_lds(p, s);
     if (rc) return rc;
-    // y = F^-1 (k_f o u_f), truncated, times g_out
-    p = a;
-    p.in = bufs[0];
-    p.kf = kf;
-    p.gate = g_out;
-    p.out = y;
-    p.rows = crows;
-    p.n_valid = n;
-    p.inverse = 1;
-    p.load = LD_C16_CONJ_MULK;
-    p.store = ST_REAL_PAIR;
-    p.scale = 1.0f / (float)nfft;
-    return launch_fft2_lds(p, s);
+    FftPass q = first;
+    q.rows = crows;
+    q.in = bufs[0];
+    q.load = LD_C16;
+    q.out = y;
+    q.gate = g_out;
+    q.n_valid = n;
+    q.store = real_store;
+    q.scale = 1.0f / (float)nfft;
+    return launch_fft_pass_mfma(q, s);
 }
 
 // Multi-pass convolution on the matrix cores (bf16 or fp32, factors 16..128).  The kernel is real, so two
@@ -438,8 +493,8 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
     void *bufs[2] = {ws, (char *)ws + buf};
     float2 *kf = (float2 *)((char *)ws + 2 * buf);
 
-    if (nf == 2 && B >= 2 && fft2_lds_supported(factors[0], factors[1], dt))
-        return conv_chunks_lds(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, bufs, kf, s);
+    if (conv_chunks_supported(factors, nf, dt))
+        return conv_chunks_lds(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, bufs, kf, s);
     if (fft_mfma_supported(nfft, factors, nf, dt) || fft_mfma_f32_supported(nfft, factors, nf, dt))
         return conv_passes_mfma(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, bufs, kf, dt, s);
 

@@ -65,10 +65,11 @@ __device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
 
 // One stage on one tile of 16 columns.  STRIDED: element (c, col) at tile[c * PITCH + col] (stage X);
 // otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: row
-// tiles of the output that are needed.  TW: multiply output (j, col) by omega_(mod)^(j col).
+// tiles of the output that are needed.  TW: multiply output row j by omega_(mod)^(alpha j + beta)
+// (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors).
 template <int F, int PITCH, bool STRIDED, bool TW>
 __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int col, int lane, int live_ks, int want_jt,
-                                           float inv_mod)
+                                           int alpha, int beta, float inv_mod)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32;
     const int kg = lane >> 4;
@@ -103,10 +104,10 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
     if constexpr (TW) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float rev = (float)((4 * kg + r) * col) * inv_mod;   // exact: j col < modulus <= 2^24
+            const float rev = (float)((4 * kg + r) * alpha + beta) * inv_mod;   // exact: the phase stays below the modulus <= 2^24
             tw[r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
         }
-        const float rev = (float)(16 * col) * inv_mod;
+        const float rev = (float)(16 * alpha) * inv_mod;
         step = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
     }
 #pragma unroll 1
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     constexpr int PITCH = pitch_of(F2), CH = F1 * F2;
     constexpr bool REAL_IN = LOAD == LD_REAL || LOAD == LD_REAL_PAIR;
     constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
-    constexpr bool MULK = LOAD == LD_C16_CONJ_MULK;
+    constexpr bool MULK = LOAD == LD_C16_CONJ_MULK, HERM = LOAD == LD_C16_HERM_MULK;
     constexpr int NIT4 = (CH + 4 * THREADS - 1) / (4 * THREADS);   // steps of 4 complex elements per thread
     constexpr int NIT8 = (CH + 8 * THREADS - 1) / (8 * THREADS);   // steps of 8 real elements per thread
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
 
     // staged inputs of one chunk
-    u32x4 za[REAL_IN ? NIT8 : NIT4], zb[REAL_IN ? NIT8 : NIT4], zc[REAL_IN ? NIT8 : 1], zd[REAL_IN ? NIT8 : 1];
+    u32x4 za[REAL_IN ? NIT8 : NIT4], zb[REAL_IN ? NIT8 : NIT4], zc[REAL_IN ? NIT8 : HERM ? NIT4 : 1], zd[REAL_IN ? NIT8 : HERM ? NIT4 : 1];
     auto request = [&](int64_t q) {
         const int64_t rc = q / p.O;
         if constexpr (REAL_IN) {
@@ -220,13 +221,42 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         } else {
             const int64_t at0 = rc * p.N + (q - rc * p.O) * CH;
             const uint32_t *src = (const uint32_t *)p.in + at0;
-            const uint32_t *ksrc = MULK ? (const uint32_t *)p.kf + (rc % p.H) * (int64_t)p.N + (q - rc * p.O) * CH : src;
+            const uint32_t *ksrc = MULK ? (const uint32_t *)p.kf + (rc % p.H) * (int64_t)p.N + (q - rc * p.O) * CH
+                                   : HERM ? (const uint32_t *)p.kf + at0 : src;
 #pragma unroll
             for (int it = 0; it < NIT4; ++it) {
                 const int e = 4 * (tid + it * THREADS);
                 if (e < CH) {
                     za[it] = *reinterpret_cast<const u32x4 *>(src + e);
-                    if (MULK) zb[it] = *reinterpret_cast<const u32x4 *>(ksrc + e);
+                    if (MULK || HERM) zb[it] = *reinterpret_cast<const u32x4 *>(ksrc + e);
+                }
+            }
+            if constexpr (HERM) {
+                // Frequency of chunk o, position (j1, j2) is m = j2 f0 f1 + j1 f0 + o; its mirror N - m sits in
+                // chunk (f0 - o) mod f0.  For o > 0 the mirror of position e is position CH - 1 - e: one 16-byte
+                // piece read backwards.  For o = 0: j1' = (f1 - j1) mod f1, j2' = f2 - 1 - j2 (j1 > 0) or (f2 - j2) mod f2.
+                const int o = (int)(q - rc * p.O), om = o ? p.O - o : 0;
+                const uint32_t *zm = (const uint32_t *)p.in + rc * p.N + (int64_t)om * CH;
+                const uint32_t *km = (const uint32_t *)p.kf + rc * p.N + (int64_t)om * CH;
+#pragma unroll
+                for (int it = 0; it < NIT4; ++it) {
+                    const int e = 4 * (tid + it * THREADS);
+                    if (e < CH) {
+                        if (o) {
+                            const u32x4 a = *reinterpret_cast<const u32x4 *>(zm + CH - 4 - e);
+                            const u32x4 b = *reinterpret_cast<const u32x4 *>(km + CH - 4 - e);
+                            zc[it] = u32x4{a[3], a[2], a[1], a[0]};
+                            zd[it] = u32x4{b[3], b[2], b[1], b[0]};
+                        } else {
+                            const int j1 = e / F2, j1m = (F1 - j1) % F1;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const int j2 = e % F2 + t, j2m = j1 ? F2 - 1 - j2 : (F2 - j2) % F2;
+                                zc[it][t] = zm[j1m * F2 + j2m];
+                                zd[it][t] = km[j1m * F2 + j2m];
+                            }
+                        }
+                    }
                 }
             }
         }
@@ -294,6 +324,23 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                 const int e = 4 * (tid + it * THREADS);
                 if (e < CH) {
                     u32x4 w = za[it];
+                    if constexpr (HERM) {
+                        // z = a + i b, kz = ka + i kb (a, b, ka, kb real): A = (Z + conj Z') / 2, B = (Z - conj Z') / 2i,
+                        // the same for the kernels; wanted: conj(A Ka + i B Kb)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float2 z0 = make_float2(lo_f32(w[t]), hi_f32(w[t]));
+                            const float2 z1 = make_float2(lo_f32(zc[it][t]), -hi_f32(zc[it][t]));
+                            const float2 k0 = make_float2(lo_f32(zb[it][t]), hi_f32(zb[it][t]));
+                            const float2 k1 = make_float2(lo_f32(zd[it][t]), -hi_f32(zd[it][t]));
+                            const float2 A = make_float2(0.5f * (z0.x + z1.x), 0.5f * (z0.y + z1.y));
+                            const float2 Bv = make_float2(0.5f * (z0.y - z1.y), -0.5f * (z0.x - z1.x));
+                            const float2 Ka = make_float2(0.5f * (k0.x + k1.x), 0.5f * (k0.y + k1.y));
+                            const float2 Kb = make_float2(0.5f * (k0.y - k1.y), -0.5f * (k0.x - k1.x));
+                            const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);
+                            w[t] = pack2(pa.x - pb.y, -(pa.y + pb.x));
+                        }
+                    }
                     if constexpr (MULK) {
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
@@ -336,16 +383,23 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         // ---- the two stages
         if constexpr (!INVERSE) {
             for (int t = wave; t < F2 / 16; t += WAVES)
-                stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, live_x, F1 / 16, inv_mod);
+                stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, live_x, F1 / 16, 16 * t + l16, 0, inv_mod);
             __syncthreads();
             for (int t = wave; t < F1 / 16; t += WAVES)
-                stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, inv_mod);
+                stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod);
         } else {
             for (int t = wave; t < F1 / 16; t += WAVES)
-                stage_tile<F2, PITCH, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, inv_mod);
+                stage_tile<F2, PITCH, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * t + l16, 0, inv_mod);
             __syncthreads();
-            for (int t = wave; t < F2 / 16; t += WAVES)
-                stage_tile<F1, PITCH, true, false>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, inv_mod);
+            if (p.tw_outer) {   // three factors: the diagonal omega_N^(o (f2 c1 + c2)) that precedes the first factor's inverse
+                const int o = (int)(q - rc * p.O);
+                for (int t = wave; t < F2 / 16; t += WAVES)
+                    stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, o * F2,
+                                                      o * (16 * t + l16), 1.0f / (float)p.N);
+            } else {
+                for (int t = wave; t < F2 / 16; t += WAVES)
+                    stage_tile<F1, PITCH, true, false>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, 0, 0, inv_mod);
+            }
         }
         __syncthreads();
 
@@ -468,6 +522,9 @@ static int launch_modes(const Fft2Args &p, hipStream_t s)
         case ST_C16: return launch_one<F1, F2, true, LD_C16_CONJ_MULK, ST_C16>(p, s);
         default: break;
         }
+    } else if (p.load == LD_C16_HERM_MULK) {
+        if (p.store == ST_C16) return launch_one<F1, F2, true, LD_C16_HERM_MULK, ST_C16>(p, s);
+        if (p.store == ST_REAL_PAIR) return launch_one<F1, F2, true, LD_C16_HERM_MULK, ST_REAL_PAIR>(p, s);
     }
     return fail(MONARCH_EINVAL, "internal: chunk kernel modes %d/%d not built", p.load, p.store);
 }

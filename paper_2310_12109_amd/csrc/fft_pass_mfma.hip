@@ -316,7 +316,7 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
         // tiles are hoisted and the register file overflows)
 #pragma unroll 1
         for (int jt = 0; jt < JT; ++jt) {
-            const bool wanted = !REAL_OUT || (int64_t)16 * jt * O < p.n_valid;
+            const bool wanted = !REAL_OUT || (int64_t)16 * jt * (CONTIG ? O : S) < p.n_valid;
             if (wanted) {
                 f32x4 dr[NT], di[NT];
 #pragma unroll
@@ -347,7 +347,7 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
                         zr[t] = dr[t][r];
                         zi[t] = di[t][r];
                     }
-                    if constexpr (!CONTIG) {   // ST_C16
+                    if constexpr (!CONTIG && !REAL_OUT) {   // ST_C16
                         uint32_t w[NT];
 #pragma unroll
                         for (int t = 0; t < NT; ++t) {
@@ -355,6 +355,35 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
                             w[t] = pack2(z.x, z.y);
                         }
                         store_words<NT>((uint32_t *)p.out + rc * p.N + base[0] + (int64_t)j * S, w);
+                    } else if constexpr (!CONTIG) {
+                        // Last pass of an inverse whose factors run in the opposite order (the first digit is
+                        // contracted last, O = 1): no twiddle follows, outputs are in time order j S + s.
+                        const int m = j * S + col0;
+                        if (m < p.n_valid) {
+                            const int64_t ra = STORE == ST_REAL_PAIR ? pair_first_row(p, rc) : rc;
+                            const int64_t at = ra * p.n_valid + m, bt = at + (int64_t)p.pair_stride * p.n_valid;
+                            const bool hasb = STORE == ST_REAL_PAIR && ra + p.pair_stride < p.real_rows;
+                            float va[NT], vb[NT], g[NT];
+#pragma unroll
+                            for (int t = 0; t < NT; ++t) {
+                                va[t] = zr[t] * p.scale;
+                                vb[t] = -zi[t] * p.scale;
+                            }
+                            if (p.gate) {
+                                load_bf16s<NT>((const bf16_t *)p.gate + at, g);
+#pragma unroll
+                                for (int t = 0; t < NT; ++t) va[t] *= g[t];
+                            }
+                            store_bf16s<NT>((bf16_t *)p.out + at, va);
+                            if (hasb) {
+                                if (p.gate) {
+                                    load_bf16s<NT>((const bf16_t *)p.gate + bt, g);
+#pragma unroll
+                                    for (int t = 0; t < NT; ++t) vb[t] *= g[t];
+                                }
+                                store_bf16s<NT>((bf16_t *)p.out + bt, vb);
+                            }
+                        }
                     } else {
                         const int m = j * O + col0;   // natural output index of the first column
                         if constexpr (STORE == ST_C32_NATURAL) {
@@ -464,6 +493,8 @@ static int launch_f(const FftPass &p, hipStream_t s)
         default: break;
         }
     } else {
+        if (p.store == ST_REAL_PAIR) return launch_one<F, LD_C16, ST_REAL_PAIR, false>(p, s);
+        if (p.store == ST_REAL_SCALE_GATE) return launch_one<F, LD_C16, ST_REAL_SCALE_GATE, false>(p, s);
         switch (p.load) {
         case LD_C16: return launch_one<F, LD_C16, ST_C16, false>(p, s);
         case LD_C16_CONJ_MULK: return launch_one<F, LD_C16_CONJ_MULK, ST_C16, false>(p, s);
@@ -493,7 +524,9 @@ int launch_fft_pass_mfma(const FftPass &p, hipStream_t s)
     if (p.rows == 0) return MONARCH_OK;
     // shapes the kernel's indexing relies on
     const bool last = p.S == 1;
-    if (last ? (p.O % 16 != 0 || p.load != LD_C16) : (p.S % 16 != 0 || p.store != ST_C16))
+    const bool real_out = p.store == ST_REAL_PAIR || p.store == ST_REAL_SCALE_GATE;
+    if (last ? (p.O % 16 != 0 || p.load != LD_C16)
+             : (p.S % 16 != 0 || (real_out ? (p.O != 1 || p.load != LD_C16) : p.store != ST_C16)))
         return fail(MONARCH_EINVAL, "internal: MFMA pass geometry O=%d f=%d S=%d load=%d store=%d", p.O, p.f, p.S, p.load, p.store);
     if ((int64_t)p.O * p.f * p.S != p.N) return fail(MONARCH_EINVAL, "internal: pass geometry does not multiply to N");
     switch (p.f) {

@@ -63,7 +63,7 @@ int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y,
 // Two factors at once on chunks of f1 x f2 complex numbers held in LDS (bf16; see fft2_lds.hip).  The
 // spectrum is left in the forward's in-place order (position [j1][j2] = frequency j2 f1 + j1) and the
 // inverse consumes that order.  Loads: LD_REAL / LD_REAL_PAIR (whole rows, two factors) or LD_C16 forward,
-// LD_C16_CONJ_MULK inverse (kf: packed bf16 pairs in the same order, row r % H); stores: ST_C16, or
+// LD_C16_CONJ_MULK / LD_C16_HERM_MULK inverse (kf: packed bf16 pairs in the same order); stores: ST_C16, or
 // ST_REAL_SCALE_GATE / ST_REAL_PAIR for the inverse of a two-factor transform.
 struct Fft2Args {
     const void *in;
@@ -77,6 +77,7 @@ struct Fft2Args {
     int64_t real_rows;
     float scale;
     int load, store, inverse;
+    int tw_outer;        // inverse of a three-factor transform: times omega_N^(o (f2 j + col)) after the chunk, o = chunk index
 };
 bool fft2_lds_supported(int f1, int f2, monarch_dtype dt);
 int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
