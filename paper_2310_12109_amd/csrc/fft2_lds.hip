@@ -355,12 +355,31 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         }
     };
 
-    if (blockIdx.x < nchunks) request(blockIdx.x);
-    for (int64_t q = blockIdx.x; q < nchunks; q += gridDim.x) {
+    // The i-th chunk of this workgroup, or -1 past the end.  Normally chunk blockIdx + i grid.  With the
+    // Hermitian separation a chunk also reads its mirror chunk, so a workgroup takes the two of a mirror
+    // pair back to back (the second finds the data in L2): slots 2 b, 2 b + 1, then 2 (b + grid), ... and
+    // slot t of a row is chunk 0, O/2, 1, O-1, 2, O-2, ...
+    auto chunk_at = [&](int64_t i) -> int64_t {
+        if constexpr (!HERM) {
+            const int64_t q = blockIdx.x + i * gridDim.x;
+            return q < nchunks ? q : -1;
+        } else {
+            const int64_t slot = 2 * ((int64_t)blockIdx.x + (i >> 1) * gridDim.x) + (i & 1);
+            if (slot >= nchunks) return -1;
+            const int64_t row = slot / p.O;
+            const int t = (int)(slot - row * p.O), k2 = t >> 1;
+            const int o = t < 2 ? (t ? p.O / 2 : 0) : ((t & 1) ? p.O - k2 : k2);
+            return row * p.O + (p.O > 1 ? o : 0);
+        }
+    };
+    int64_t q = chunk_at(0);
+    if (q >= 0) request(q);
+    for (int64_t i = 0; q >= 0; ++i) {
         const int64_t rc = q / p.O;
+        const int64_t qnext = chunk_at(i + 1);
         deposit(q);
         __syncthreads();
-        if (q + gridDim.x < nchunks) request(q + gridDim.x);
+        if (qnext >= 0) request(qnext);
 
         // output gates of this chunk, requested before the stages
         const int64_t ra = STORE == ST_REAL_PAIR ? pair_first_row(p, rc) : rc;
@@ -468,6 +487,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             }
         }
         __syncthreads();
+        q = qnext;
     }
 }
 
@@ -488,6 +508,7 @@ static int launch_vec(const Fft2Args &p, hipStream_t s)
     const int64_t nchunks = p.rows * p.O;
     int64_t grid = (int64_t)ncu * (per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu);
     if (grid > nchunks) grid = nchunks;
+    if (LOAD == LD_C16_HERM_MULK && grid > (nchunks + 1) / 2) grid = (nchunks + 1) / 2;   // two chunks per turn
     auto kern = fft2_lds_kernel<F1, F2, INVERSE, LOAD, STORE, VEC>;
     if (lds > 48 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
