@@ -311,7 +311,9 @@ static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const
         first.real_rows = (int64_t)B * H;
     }
     int rc;
-    for (int which = 0; which < 2; ++which) {   // 0: spectrum of k (into kf), 1: spectrum of g_in o u (into bufs[1])
+    // two factors, rows of a multiple of 8 elements, kernels not paired: the rows never leave the chip
+    const bool one_kernel = nf == 2 && !by_channel && n % 8 == 0;
+    for (int which = 0; which < (one_kernel ? 1 : 2); ++which) {   // 0: spectrum of k (into kf), 1: spectrum of g_in o u (into bufs[1])
         const bool pair_here = which == 0 ? by_channel : paired;
         const int64_t rows = which == 0 ? (by_channel ? crows : H) : crows;
         const void *src = which == 0 ? k : u;
@@ -343,6 +345,20 @@ static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const
         }
         rc = launch_fft2_lds(p, s);
         if (rc) return rc;
+    }
+    if (one_kernel) {
+        Fft2Args p = a;
+        p.rows = crows;
+        p.in = u;
+        p.gate = g_in;
+        p.gate_out = g_out;
+        p.kf = kf;
+        p.out = y;
+        p.n_valid = n;
+        p.load = paired ? LD_REAL_PAIR : LD_REAL;
+        p.store = paired ? ST_REAL_PAIR : ST_REAL_SCALE_GATE;
+        p.scale = 1.0f / (float)nfft;
+        return launch_fft2_lds(p, s);
     }
     // inverse: product of the spectra on load, chunk factors, then (three factors) the strided factor
     Fft2Args p = a;

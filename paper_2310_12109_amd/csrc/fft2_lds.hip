@@ -172,6 +172,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     constexpr bool REAL_IN = LOAD == LD_REAL || LOAD == LD_REAL_PAIR;
     constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
     constexpr bool MULK = LOAD == LD_C16_CONJ_MULK, HERM = LOAD == LD_C16_HERM_MULK;
+    constexpr bool FUSED = REAL_IN && REAL_OUT;   // whole convolution of a two-factor row: forward, times kf, inverse
     constexpr int NIT4 = (CH + 4 * THREADS - 1) / (4 * THREADS);   // steps of 4 complex elements per thread
     constexpr int NIT8 = (CH + 8 * THREADS - 1) / (8 * THREADS);   // steps of 8 real elements per thread
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -384,10 +385,19 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         // output gates of this chunk, requested before the stages
         const int64_t ra = STORE == ST_REAL_PAIR ? pair_first_row(p, rc) : rc;
         const bool hasb = STORE == ST_REAL_PAIR && ra + p.pair_stride < p.real_rows;
-        u32x4 oga[REAL_OUT && VEC ? NIT8 : 1], ogb[REAL_OUT && VEC ? NIT8 : 1];
+        const void *out_gate = FUSED ? p.gate_out : p.gate;
+        u32x4 oga[REAL_OUT && VEC ? NIT8 : 1], ogb[REAL_OUT && VEC ? NIT8 : 1], kfr[FUSED ? NIT4 : 1];
+        if constexpr (FUSED) {   // this chunk's kernel spectrum, multiplied in between the two transforms
+            const uint32_t *ksrc = (const uint32_t *)p.kf + (rc % p.H) * (int64_t)p.N;
+#pragma unroll
+            for (int it = 0; it < NIT4; ++it) {
+                const int e = 4 * (tid + it * THREADS);
+                if (e < CH) kfr[it] = *reinterpret_cast<const u32x4 *>(ksrc + e);
+            }
+        }
         if constexpr (REAL_OUT && VEC) {
-            if (p.gate) {
-                const bf16_t *ga = (const bf16_t *)p.gate + ra * p.n_valid, *gb = hasb ? ga + (int64_t)p.pair_stride * p.n_valid : ga;
+            if (out_gate) {
+                const bf16_t *ga = (const bf16_t *)out_gate + ra * p.n_valid, *gb = hasb ? ga + (int64_t)p.pair_stride * p.n_valid : ga;
 #pragma unroll
                 for (int it = 0; it < NIT8; ++it) {
                     const int e = 8 * (tid + it * THREADS);
@@ -406,7 +416,26 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             __syncthreads();
             for (int t = wave; t < F1 / 16; t += WAVES)
                 stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod);
-        } else {
+        }
+        if constexpr (FUSED) {
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < NIT4; ++it) {   // tile <- conj(tile o kf)
+                const int e = 4 * (tid + it * THREADS);
+                if (e < CH) {
+                    u32x4 w = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float2 m = cmul(make_float2(lo_f32(w[t]), hi_f32(w[t])),
+                                              make_float2(lo_f32(kfr[it][t]), hi_f32(kfr[it][t])));
+                        w[t] = pack2(m.x, -m.y);
+                    }
+                    *reinterpret_cast<u32x4 *>(tile + tix(e)) = w;
+                }
+            }
+            __syncthreads();
+        }
+        if constexpr (INVERSE || FUSED) {
             for (int t = wave; t < F1 / 16; t += WAVES)
                 stage_tile<F2, PITCH, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * t + l16, 0, inv_mod);
             __syncthreads();
@@ -438,6 +467,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                 for (int it = 0; it < NIT8; ++it) {
                     const int e = 8 * (tid + it * THREADS);
                     if (e < p.n_valid) {
+                        const bool gated = out_gate != nullptr;
                         const u32x4 w0 = *reinterpret_cast<const u32x4 *>(tile + tix(e));
                         const u32x4 w1 = *reinterpret_cast<const u32x4 *>(tile + tix(e + 4));
                         float va[8], vb[8], g[8];
@@ -448,7 +478,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                             va[4 + t] = lo_f32(w1[t]) * p.scale;
                             vb[4 + t] = -hi_f32(w1[t]) * p.scale;
                         }
-                        if (p.gate) {
+                        if (gated) {
                             unpack8(oga[it], g);
 #pragma unroll
                             for (int t = 0; t < 8; ++t) va[t] *= g[t];
@@ -456,7 +486,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                         *reinterpret_cast<u32x4 *>(ya + e) =
                             u32x4{pack2(va[0], va[1]), pack2(va[2], va[3]), pack2(va[4], va[5]), pack2(va[6], va[7])};
                         if (STORE == ST_REAL_PAIR && hasb) {
-                            if (p.gate) {
+                            if (gated) {
                                 unpack8(ogb[it], g);
 #pragma unroll
                                 for (int t = 0; t < 8; ++t) vb[t] *= g[t];
@@ -467,7 +497,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                     }
                 }
             } else {
-                const bf16_t *ga = p.gate ? (const bf16_t *)p.gate + ra * p.n_valid : nullptr;
+                const bf16_t *ga = out_gate ? (const bf16_t *)out_gate + ra * p.n_valid : nullptr;
                 const bf16_t *gb = ga ? ga + (int64_t)p.pair_stride * p.n_valid : nullptr;
                 for (int e = 4 * tid; e < p.n_valid; e += 4 * THREADS) {
                     const u32x4 w = *reinterpret_cast<const u32x4 *>(tile + tix(e));
@@ -528,8 +558,13 @@ static int launch_one(const Fft2Args &p, hipStream_t s)
 template <int F1, int F2>
 static int launch_modes(const Fft2Args &p, hipStream_t s)
 {
+    if (!p.inverse && p.store != ST_C16) {   // whole convolution in one kernel
+        if (p.n_valid % 8) return fail(MONARCH_EINVAL, "internal: the fused chunk convolution needs rows of a multiple of 8 elements");
+        if (p.load == LD_REAL_PAIR && p.store == ST_REAL_PAIR) return launch_vec<F1, F2, false, LD_REAL_PAIR, ST_REAL_PAIR, true>(p, s);
+        if (p.load == LD_REAL && p.store == ST_REAL_SCALE_GATE) return launch_vec<F1, F2, false, LD_REAL, ST_REAL_SCALE_GATE, true>(p, s);
+        return fail(MONARCH_EINVAL, "internal: fused chunk convolution modes %d/%d not built", p.load, p.store);
+    }
     if (!p.inverse) {
-        if (p.store != ST_C16) return fail(MONARCH_EINVAL, "internal: forward chunk kernel stores packed pairs only");
         switch (p.load) {
         case LD_REAL: return launch_one<F1, F2, false, LD_REAL, ST_C16>(p, s);
         case LD_REAL_PAIR: return launch_one<F1, F2, false, LD_REAL_PAIR, ST_C16>(p, s);

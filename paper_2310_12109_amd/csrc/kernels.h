@@ -64,11 +64,13 @@ int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y,
 // spectrum is left in the forward's in-place order (position [j1][j2] = frequency j2 f1 + j1) and the
 // inverse consumes that order.  Loads: LD_REAL / LD_REAL_PAIR (whole rows, two factors) or LD_C16 forward,
 // LD_C16_CONJ_MULK / LD_C16_HERM_MULK inverse (kf: packed bf16 pairs in the same order); stores: ST_C16, or
-// ST_REAL_SCALE_GATE / ST_REAL_PAIR for the inverse of a two-factor transform.
+// ST_REAL_SCALE_GATE / ST_REAL_PAIR for the inverse of a two-factor transform.  A real load together with a
+// real store runs the whole convolution of a two-factor row in one kernel: forward, times kf, inverse.
 struct Fft2Args {
     const void *in;
     void *out;
     const void *gate;
+    const void *gate_out;   // fused convolution (real load and real store): gate = input gate, gate_out = output gate
     const void *kf;
     int64_t rows;        // complex rows
     int N, O, f1, f2;    // row length, chunks per row, chunk = f1 x f2
