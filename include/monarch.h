@@ -71,7 +71,7 @@ int monarch_permutation_index(int b, int N, int32_t *host_out);
  * square case has all six sizes equal to b = sqrt(N).
  * x: (batch, d_in), y: (batch, d_out), R, L, x, y all of type dt.
  * Errors: EINVAL, ESHAPE (d_mid mismatch, sizes < 1, a row too large for the
- * on-chip tile: d_in + d_mid or d_out beyond 8192), EDTYPE, EHIP.
+ * on-chip tile: (max(d_in, d_out) + d_mid) * 4 bytes beyond 160 KB), EDTYPE, EHIP.
  */
 int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t batch,
                    int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
@@ -133,8 +133,9 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
  *            inner widths mid1, mid2 (0 means d):
  *            W1_R: [nb][mid1/nb][d/nb], W1_L: [nb][d_hidden/nb][mid1/nb],
  *            W2_R: [nb][mid2/nb][d_hidden/nb], W2_L: [nb][d/nb][mid2/nb].
- * act: 0 none, 1 ReLU, 2 GELU (exact, erf form).  b1 (d_hidden) and b2 (d) may
- * be NULL.  x, y: (tokens, d); everything of type dt.
+ * act: 0 none, 1 ReLU, 2 GELU (erf form: z * Phi(z); the bf16 kernels evaluate
+ * Phi by a polynomial with |error| <= 2.4e-4, below bf16 resolution).  b1
+ * (d_hidden) and b2 (d) may be NULL.  x, y: (tokens, d); everything of type dt.
  * Errors: EINVAL, ESHAPE (nb does not divide the widths, order not 1 or 2,
  * widths beyond the on-chip tile), EDTYPE, EWORKSPACE, EHIP.
  */
