@@ -59,9 +59,15 @@ struct Quad {
 };
 __device__ __forceinline__ Quad dft_quad(int row, int col0)
 {
+    // hardware sine / cosine of an exact fraction of a turn (error ~1e-6, far below bf16 resolution);
+    // the library sincospif would cost more instructions here than the five transforms of the wave
     float c[4], s[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) sincospif((float)((row * (col0 + e)) & 15) * 0.125f, &s[e], &c[e]);
+    for (int e = 0; e < 4; ++e) {
+        const float turn = (float)((row * (col0 + e)) & 15) * 0.0625f;
+        s[e] = __builtin_amdgcn_sinf(turn);
+        c[e] = __builtin_amdgcn_cosf(turn);
+    }
     Quad q;
     q.re = u32x2{pack2(c[0], c[1]), pack2(c[2], c[3])};
     q.im = u32x2{pack2(s[0], s[1]), pack2(s[2], s[3])};
@@ -127,9 +133,8 @@ __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restr
     float2 tw[4];   // omega_256^((4 kg + r) l16)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        float s, c;
-        sincospif((float)(((4 * kg + r) * l16) & 255) * (1.0f / 128.0f), &s, &c);
-        tw[r] = make_float2(c, s);
+        const float turn = (float)(((4 * kg + r) * l16) & 255) * (1.0f / 256.0f);
+        tw[r] = make_float2(__builtin_amdgcn_cosf(turn), __builtin_amdgcn_sinf(turn));
     }
     const f32x4 zero = {0, 0, 0, 0};
 
