@@ -164,7 +164,9 @@ __device__ __forceinline__ void unpack8(const u32x4 &w, float (&v)[8])
 // VEC: real rows are read and written 16 bytes (8 elements) at a time, which needs n_valid % 8 == 0; all
 // global loads of a chunk are issued together, those of the next chunk (and the output gates of this one)
 // before the stages of the current one, so that they are in flight while the matrix cores work.
-template <int F1, int F2, bool INVERSE, int LOAD, int STORE, bool VEC>
+// TWO (Hermitian separation, three factors): a workgroup takes a chunk o and its mirror chunk O - o in one turn,
+// in two tiles: each loaded word and each separated product serves both.
+template <int F1, int F2, bool INVERSE, int LOAD, int STORE, bool VEC, bool TWO>
 __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_kernel(const Fft2Args p)
 {
     constexpr int THREADS = F1 >= 128 || F2 >= 128 ? 512 : 256, WAVES = THREADS / 64;
@@ -177,7 +179,8 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     constexpr int NIT8 = (CH + 8 * THREADS - 1) / (8 * THREADS);   // steps of 8 real elements per thread
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     uint32_t *tile = lds;                                                   // [F1][PITCH] packed bf16 pairs
-    u32x4 *tab1 = reinterpret_cast<u32x4 *>(lds + F1 * PITCH);              // F_f1 operands
+    uint32_t *tile2 = lds + F1 * PITCH;                                     // TWO: the mirror chunk
+    u32x4 *tab1 = reinterpret_cast<u32x4 *>(lds + (TWO ? 2 : 1) * F1 * PITCH);   // F_f1 operands
     u32x4 *tab2 = F1 == F2 ? tab1 : tab1 + table_words(F1) / 4;             // F_f2 operands
     __shared__ float2 roots[F1 > F2 ? F1 : F2];
     build_table<F1, THREADS>(tab1, roots);
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             }
         }
     };
-    auto deposit = [&](int64_t q) {   // staged inputs -> tile (natural order of the chunk)
+    auto deposit = [&](int64_t q, bool paired) {   // staged inputs -> tile (natural order of the chunk)
         if constexpr (REAL_IN) {
             const int64_t rc = q / p.O;
             const int64_t ra = LOAD == LD_REAL_PAIR ? pair_first_row(p, rc) : rc;
@@ -324,10 +327,11 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             for (int it = 0; it < NIT4; ++it) {
                 const int e = 4 * (tid + it * THREADS);
                 if (e < CH) {
-                    u32x4 w = za[it];
+                    u32x4 w = za[it], w2 = za[it];
                     if constexpr (HERM) {
                         // z = a + i b, kz = ka + i kb (a, b, ka, kb real): A = (Z + conj Z') / 2, B = (Z - conj Z') / 2i,
-                        // the same for the kernels; wanted: conj(A Ka + i B Kb)
+                        // the same for the kernels; wanted: conj(A Ka + i B Kb), and for the mirror frequency
+                        // conj(conj(A Ka) + i conj(B Kb)) = A Ka - i B Kb
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const float2 z0 = make_float2(lo_f32(w[t]), hi_f32(w[t]));
@@ -340,7 +344,9 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                             const float2 Kb = make_float2(0.5f * (k0.y - k1.y), -0.5f * (k0.x - k1.x));
                             const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);
                             w[t] = pack2(pa.x - pb.y, -(pa.y + pb.x));
+                            w2[3 - t] = pack2(pa.x + pb.y, pa.y - pb.x);
                         }
+                        if (TWO && paired) *reinterpret_cast<u32x4 *>(tile2 + tix(CH - 4 - e)) = w2;   // mirror of e + t is CH - 1 - e - t
                     }
                     if constexpr (MULK) {
 #pragma unroll
@@ -360,8 +366,16 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     // Hermitian separation a chunk also reads its mirror chunk, so a workgroup takes the two of a mirror
     // pair back to back (the second finds the data in L2): slots 2 b, 2 b + 1, then 2 (b + grid), ... and
     // slot t of a row is chunk 0, O/2, 1, O-1, 2, O-2, ...
+    // TWO: a row has O/2 + 1 turns: chunk 0 and chunk O/2 alone (they are their own mirrors), chunk t with O - t.
+    const int turns_per_row = TWO ? p.O / 2 + 1 : p.O;
+    const int64_t nturns = TWO ? p.rows * turns_per_row : nchunks;
     auto chunk_at = [&](int64_t i) -> int64_t {
-        if constexpr (!HERM) {
+        if constexpr (TWO) {
+            const int64_t turn = blockIdx.x + i * gridDim.x;
+            if (turn >= nturns) return -1;
+            const int64_t row = turn / turns_per_row;
+            return row * p.O + (turn - row * turns_per_row);
+        } else if constexpr (!HERM) {
             const int64_t q = blockIdx.x + i * gridDim.x;
             return q < nchunks ? q : -1;
         } else {
@@ -377,8 +391,11 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     if (q >= 0) request(q);
     for (int64_t i = 0; q >= 0; ++i) {
         const int64_t rc = q / p.O;
+        const int o_here = (int)(q - rc * p.O);
+        const bool paired = TWO && o_here != 0 && 2 * o_here != p.O;   // this turn also carries chunk O - o
+        const int ntile = paired ? 2 : 1;
         const int64_t qnext = chunk_at(i + 1);
-        deposit(q);
+        deposit(q, paired);
         __syncthreads();
         if (qnext >= 0) request(qnext);
 
@@ -436,14 +453,20 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             __syncthreads();
         }
         if constexpr (INVERSE || FUSED) {
-            for (int t = wave; t < F1 / 16; t += WAVES)
-                stage_tile<F2, PITCH, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * t + l16, 0, inv_mod);
+            // (tile index ti = 1 is the mirror chunk O - o of a paired turn)
+            for (int t = wave; t < ntile * (F1 / 16); t += WAVES) {
+                const int ti = t / (F1 / 16), tt = t - ti * (F1 / 16);
+                stage_tile<F2, PITCH, false, true>(ti ? tile2 : tile, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
+                                                   16 * tt + l16, 0, inv_mod);
+            }
             __syncthreads();
             if (p.tw_outer) {   // three factors: the diagonal omega_N^(o (f2 c1 + c2)) that precedes the first factor's inverse
-                const int o = (int)(q - rc * p.O);
-                for (int t = wave; t < F2 / 16; t += WAVES)
-                    stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, o * F2,
-                                                      o * (16 * t + l16), 1.0f / (float)p.N);
+                for (int t = wave; t < ntile * (F2 / 16); t += WAVES) {
+                    const int ti = t / (F2 / 16), tt = t - ti * (F2 / 16);
+                    const int o = ti ? p.O - o_here : o_here;
+                    stage_tile<F1, PITCH, true, true>(ti ? tile2 : tile, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, want_x, o * F2,
+                                                      o * (16 * tt + l16), 1.0f / (float)p.N);
+                }
             } else {
                 for (int t = wave; t < F2 / 16; t += WAVES)
                     stage_tile<F1, PITCH, true, false>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, 0, 0, inv_mod);
@@ -458,6 +481,14 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             for (int it = 0; it < NIT4; ++it) {
                 const int e = 4 * (tid + it * THREADS);
                 if (e < CH) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+            }
+            if (TWO && paired) {
+                uint32_t *dst2 = (uint32_t *)p.out + rc * p.N + (int64_t)(p.O - o_here) * CH;
+#pragma unroll
+                for (int it = 0; it < NIT4; ++it) {
+                    const int e = 4 * (tid + it * THREADS);
+                    if (e < CH) *reinterpret_cast<u32x4 *>(dst2 + e) = *reinterpret_cast<const u32x4 *>(tile2 + tix(e));
+                }
             }
         } else {
             // F^-1 = conj(F conj(.)) / N: first member = Re / N, second = -Im / N, times the output gate
@@ -521,25 +552,25 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     }
 }
 
-static size_t lds_bytes(int f1, int f2)
+static size_t lds_bytes(int f1, int f2, int tiles = 1)
 {
-    return ((size_t)f1 * pitch_of(f2) + table_words(f1) + (f1 == f2 ? 0 : table_words(f2))) * 4;
+    return ((size_t)tiles * f1 * pitch_of(f2) + table_words(f1) + (f1 == f2 ? 0 : table_words(f2))) * 4;
 }
 
-template <int F1, int F2, bool INVERSE, int LOAD, int STORE, bool VEC>
+template <int F1, int F2, bool INVERSE, int LOAD, int STORE, bool VEC, bool TWO = false>
 static int launch_vec(const Fft2Args &p, hipStream_t s)
 {
     constexpr int THREADS = F1 >= 128 || F2 >= 128 ? 512 : 256;
-    const size_t lds = lds_bytes(F1, F2);
+    const size_t lds = lds_bytes(F1, F2, TWO ? 2 : 1);
     int dev = 0, ncu = 0;
     MONARCH_HIP_CHECK(hipGetDevice(&dev));
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     const int per_cu = (int)((160 * 1024) / (lds + 1024));
-    const int64_t nchunks = p.rows * p.O;
+    const int64_t nchunks = TWO ? p.rows * (p.O / 2 + 1) : p.rows * p.O;   // turns of a workgroup
     int64_t grid = (int64_t)ncu * (per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu);
     if (grid > nchunks) grid = nchunks;
-    if (LOAD == LD_C16_HERM_MULK && grid > (nchunks + 1) / 2) grid = (nchunks + 1) / 2;   // two chunks per turn
-    auto kern = fft2_lds_kernel<F1, F2, INVERSE, LOAD, STORE, VEC>;
+    if (!TWO && LOAD == LD_C16_HERM_MULK && grid > (nchunks + 1) / 2) grid = (nchunks + 1) / 2;   // two chunks per turn
+    auto kern = fft2_lds_kernel<F1, F2, INVERSE, LOAD, STORE, VEC, TWO>;
     if (lds > 48 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, p);
@@ -579,7 +610,12 @@ static int launch_modes(const Fft2Args &p, hipStream_t s)
         default: break;
         }
     } else if (p.load == LD_C16_HERM_MULK) {
-        if (p.store == ST_C16) return launch_one<F1, F2, true, LD_C16_HERM_MULK, ST_C16>(p, s);
+        if (p.store == ST_C16) {
+            // three factors and room for two tiles: mirror chunks together
+            if (p.O >= 2 && p.O % 2 == 0 && lds_bytes(F1, F2, 2) + 1024 <= 80 * 1024)
+                return launch_vec<F1, F2, true, LD_C16_HERM_MULK, ST_C16, true, true>(p, s);
+            return launch_one<F1, F2, true, LD_C16_HERM_MULK, ST_C16>(p, s);
+        }
         if (p.store == ST_REAL_PAIR) return launch_one<F1, F2, true, LD_C16_HERM_MULK, ST_REAL_PAIR>(p, s);
     }
     return fail(MONARCH_EINVAL, "internal: chunk kernel modes %d/%d not built", p.load, p.store);
