@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 c2 c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -80,6 +80,34 @@ def conv(name, B, H, n, factors, dt, reps):
     _report(name, _time(calls, reps), nbytes, costmodel.conv_textbook_flops(B, H, factors), len(calls))
 
 
+def fft(name, rows, factors, dt, reps):
+    """Forward real-input transform and its inverse (complex spectrum, fp32 pairs, natural order)."""
+    N = 1
+    for f in factors:
+        N *= f
+    es = 2 if dt == torch.bfloat16 else 4
+    nbytes = rows * N * (es + 8)
+    flops = 0   # (the transforms are reported by their traffic only)
+
+    def make_fwd():
+        x = _rnd(rows, N, dt=dt)
+        X = torch.empty((rows, N, 2), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(16, binding.monarch_fft_workspace_bytes(rows, N, factors, binding.BF16 if dt == torch.bfloat16 else binding.F32)),
+                         dtype=torch.uint8, device="cuda")
+        return lambda: binding.monarch_fft(x, factors, True, ws=ws, out=X)
+
+    def make_inv():
+        X = torch.randn((rows, N, 2), dtype=torch.float32, device="cuda")
+        x = torch.empty((rows, N), dtype=dt, device="cuda")
+        ws = torch.empty(max(16, binding.monarch_fft_workspace_bytes(rows, N, factors, binding.BF16 if dt == torch.bfloat16 else binding.F32)),
+                         dtype=torch.uint8, device="cuda")
+        return lambda: binding.monarch_ifft(X, factors, True, dtype=dt, ws=ws, out=x)
+    calls = _sets(make_fwd, 2 * nbytes)
+    _report(name + " forward", _time(calls, reps), nbytes, flops, len(calls))
+    calls = _sets(make_inv, 2 * nbytes)
+    _report(name + " inverse", _time(calls, reps), nbytes, flops, len(calls))
+
+
 def mlp(name, tokens, d, dh, nb, order, reps):
     nbytes = costmodel.mlp_algorithmic_bytes(tokens, d, dh, nb, order)
     std = 0.02
@@ -111,6 +139,10 @@ def main():
     if want("c2"):
         conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
         conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)
+    if want("fft"):
+        fft("fft bf16 real, 6144 rows of 2048 = 64x32", 6144, (64, 32), torch.bfloat16, 50)
+        fft("fft fp32 real, 6144 rows of 2048 = 64x32", 6144, (64, 32), torch.float32, 30)
+        fft("fft bf16 real, 1536 rows of 16384 = 128x128", 1536, (128, 128), torch.bfloat16, 20)
     if want("c3a"):
         conv("c3a conv bf16 B=32 H=768 n=128 16x16", 32, 768, 128, (16, 16), torch.bfloat16, 200)
     if want("c3b"):
