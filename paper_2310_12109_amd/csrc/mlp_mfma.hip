@@ -378,6 +378,177 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
     }
 }
 
+
+// ---- variant for large blocks ---------------------------------------------------------------------
+// One workgroup takes 64 tokens of one block, wave w the tokens 16 w .. 16 w + 15 and the whole hidden
+// vector (nothing is summed across waves).  The weights of one chunk of 32 hidden units (both matrices, in
+// MFMA operand order, 4 KS KB) go from L2 straight into a ring of LDS slots (direct-to-LDS 16-byte loads:
+// the 64 lanes of a wave fill one 1 KB operand piece) and are read from there by all four waves: a quarter
+// of the L2 traffic of mlp_order1_kernel, and requests RING - 1 chunks ahead of their use without holding
+// registers.  One barrier per chunk: it publishes chunk j and frees the slot chunk j - 1 was read from.
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// Direct-to-LDS load: each lane's 16 bytes at src go to lds_piece + 16 * lane (lds_piece wave-uniform).  Written
+// as assembly so that the compiler does not put its own wait-for-everything in front of every later LDS read:
+// the kernel below waits for these loads by count and publishes them with a barrier itself.
+__device__ __forceinline__ void dma_16(const void *src, void *lds_piece)
+{
+    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lptr_t)lds_piece);
+    uint32_t saved_m0;   // M0 carries the LDS address of the load; whatever the compiler keeps there is put back
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "s"(dst), "v"(src)
+                 : "memory");
+}
+
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt and lgkmcnt left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vm_at_most()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// slots of the weight ring: as many chunks of 4 KS KB as fit in 148 KB, at most 8
+constexpr int ring_slots(int ks) { return 148 / (4 * ks) < 8 ? 148 / (4 * ks) : 8; }
+
+template <int KS, int ACT, int NT>
+__global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
+    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
+    const bf16_t *__restrict__ b2, int b1_interleaved)
+{
+    constexpr int DIN = 32 * KS, MT = 2 * KS, OPS = 4 * KS;   // operand pieces (64 lanes x 16 B) per hidden chunk
+    constexpr int ring = ring_slots(KS);
+    extern __shared__ __attribute__((aligned(16))) uint4 lds_ring[];   // [ring][OPS * 64], then the hidden bias [dh]
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int blk = blockIdx.y;
+    const int64_t t0 = (int64_t)blockIdx.x * (64 * NT) + 16 * NT * wave;   // NT column tiles of 16 tokens per wave
+    const int dh = d_hidden / nb, nch = dh / 32;
+    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_ring + (size_t)ring * OPS * 64);
+
+    // Wave w fetches the pieces o = w, w + 4, ... of a chunk (KS of them); lane ln of piece o supplies the 16
+    // bytes that lane will feed to MFMA o (rows / slots as in mlp_order1_kernel: W1 rows in hidden-unit order
+    // 8 (r/4) + 4 mt + r%4, W2 rows = output features).  Past the last chunk the last one is fetched again, so
+    // that every iteration issues the same number of loads and the wait below can count them.
+    int src_off[KS], src_step[KS];   // element offset of this lane's pieces in chunk 0, and per chunk
+#pragma unroll
+    for (int u = 0; u < KS; ++u) {
+        const int o = wave + 4 * u;
+        if (o < 2 * KS) {
+            const int mt = o / KS, ks = o - mt * KS;
+            src_off[u] = (8 * (l16 >> 2) + 4 * mt + (l16 & 3)) * DIN + 32 * ks + 8 * kg;
+            src_step[u] = 32 * DIN;
+        } else {
+            src_off[u] = (int)((W2b - W1b) + (16 * (o - 2 * KS) + l16) * dh + 8 * kg);
+            src_step[u] = 32;
+        }
+    }
+    auto request = [&](int j) {
+        const int jj = j < nch ? j : nch - 1;
+        uint4 *slot = lds_ring + (size_t)(j % ring) * OPS * 64;
+#pragma unroll
+        for (int u = 0; u < KS; ++u) dma_16(W1b + src_off[u] + jj * src_step[u], slot + (wave + 4 * u) * 64);
+    };
+    for (int a = 0; a < ring - 1; ++a) request(a);
+
+    for (int h = tid; h < dh; h += 256) {
+        uint16_t v = 0;
+        if (b1) v = reinterpret_cast<const uint16_t *>(b1)[b1_interleaved ? (size_t)h * nb + blk : (size_t)blk * dh + h];
+        bias_lds[h] = v;
+    }
+    Pack8 xop[NT][KS];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        int64_t t = t0 + 16 * nt + l16;
+        if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
+        const bf16_t *row = x + t * d + blk * DIN + 8 * kg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xop[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
+    }
+    float bias2[MT][4];   // output bias of the rows this lane's accumulators carry
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bias2[mt][r] = b2 ? (float)b2[(size_t)blk * DIN + 16 * mt + 4 * kg + r] : 0.0f;
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0, 0, 0, 0};
+    // (x, the biases and the first ring - 1 chunks are in flight; the loop below waits by count)
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    for (int j = 0; j < nch; ++j) {
+        // the barrier that ended the previous iteration published chunk j and guaranteed that chunk j - 1 has
+        // been read by every wave: its slot is the one the next request overwrites
+        request(j + ring - 1);
+        // bias of the 8 hidden units this lane group's accumulator rows carry: 32 j + 8 kg .. + 7
+        f32x4 bias[2];
+        {
+            const uint4 braw = *reinterpret_cast<const uint4 *>(bias_lds + 32 * j + 8 * kg);
+            const uint32_t bw[4] = {braw.x, braw.y, braw.z, braw.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) bias[e >> 2][e & 3] = __uint_as_float((e & 1) ? (bw[e >> 1] & 0xffff0000u) : (bw[e >> 1] << 16));
+        }
+        const uint4 *ops = lds_ring + (size_t)(j % ring) * OPS * 64 + lane;
+        Pack8 hop[NT];
+        {
+            Pack8 w1[2][KS];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) w1[mt][ks].q = ops[(mt * KS + ks) * 64];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    f32x4 a = bias[mt];
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) a = mfma(w1[mt][ks].v, xop[nt][ks].v, a);
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = act_fast<ACT>(a[r]);
+                    hop[nt].d[2 * mt] = pack_bf16(v[0], v[1]);
+                    hop[nt].d[2 * mt + 1] = pack_bf16(v[2], v[3]);
+                }
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            Pack8 w2;
+            w2.q = ops[(2 * KS + mt) * 64];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma(w2.v, hop[nt].v, acc[mt][nt]);
+        }
+        // own pieces of chunk j + 1 landed (the KS (ring - 2) requests after them may still be in flight)
+        wait_vm_at_most<KS * (ring - 2)>();
+        __syncthreads();
+    }
+
+    // accumulator rows 4 kg .. 4 kg + 3 of tile mt are 4 consecutive features of a token: 8-byte stores
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int64_t t = t0 + 16 * nt + l16;
+        if (t < tokens) {
+            bf16_t *dst = y + t * d + blk * DIN + 4 * kg;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                uint2 o;
+                o.x = pack_bf16(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
+                o.y = pack_bf16(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
+                *reinterpret_cast<uint2 *>(dst + 16 * mt) = o;
+            }
+        }
+    }
+}
+
 }  // namespace mlp1
 
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
@@ -432,6 +603,51 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
     const int64_t tiles = (tokens + mlp1::TOK - 1) / mlp1::TOK;
     if (tiles > 0x7fffffffLL || nb > 65535) return fail(MONARCH_ESHAPE, "too many tokens or blocks for one launch");
     const dim3 grid((unsigned)tiles, (unsigned)nb);
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (tokens * nb >= (int64_t)256 * ncu) {
+        // Enough tokens for wider tiles: weights streamed through an LDS ring, 64 NT tokens per workgroup (less
+        // weight traffic out of L2 per token, which is what bounds the 64-token kernel below): the largest NT
+        // that still gives every compute unit a workgroup.
+        const int ntv = tokens * nb >= (int64_t)512 * ncu ? 4 : 2;
+        const int64_t wtiles = (tokens + 64 * ntv - 1) / (64 * ntv);
+        const dim3 sgrid((unsigned)wtiles, (unsigned)nb);
+        const size_t str_lds = (size_t)mlp1::ring_slots(din / 32) * (din / 8) * 1024 + (size_t)dh_blk * 2;
+#define MONARCH_LAUNCH_STR(KSV, ACTV, NTV)                                                                       \
+    do {                                                                                                         \
+        auto kern = mlp1::mlp_order1_stream_kernel<KSV, ACTV, NTV>;                                              \
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                              (int)str_lds));                                                    \
+        hipLaunchKernelGGL(kern, sgrid, dim3(256), str_lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d,        \
+                           d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2,             \
+                           (const bf16_t *)b2, b1_interleaved);                                                  \
+    } while (0)
+#define MONARCH_LAUNCH_STR_NT(KSV, ACTV)                      \
+    do {                                                      \
+        if (ntv == 4) MONARCH_LAUNCH_STR(KSV, ACTV, 4);       \
+        else MONARCH_LAUNCH_STR(KSV, ACTV, 2);                \
+    } while (0)
+#define MONARCH_LAUNCH_STR_ACT(KSV)                        \
+    do {                                                   \
+        if (act == 2) MONARCH_LAUNCH_STR_NT(KSV, 2);       \
+        else if (act == 1) MONARCH_LAUNCH_STR_NT(KSV, 1);  \
+        else MONARCH_LAUNCH_STR_NT(KSV, 0);                \
+    } while (0)
+        switch (din / 32) {
+        case 1: MONARCH_LAUNCH_STR_ACT(1); break;
+        case 2: MONARCH_LAUNCH_STR_ACT(2); break;
+        case 3: MONARCH_LAUNCH_STR_ACT(3); break;
+        case 4: MONARCH_LAUNCH_STR_ACT(4); break;
+        case 5: MONARCH_LAUNCH_STR_ACT(5); break;
+        default: MONARCH_LAUNCH_STR_ACT(6); break;
+        }
+#undef MONARCH_LAUNCH_STR_ACT
+#undef MONARCH_LAUNCH_STR_NT
+#undef MONARCH_LAUNCH_STR
+        MONARCH_HIP_CHECK(hipGetLastError());
+        return MONARCH_OK;
+    }
     // two partial tiles (din/16 row tiles x 4 column tiles x 64 lanes x 16 B) + the summed [64][din+1] tile
     const size_t lds = (size_t)2 * (din / 16) * 4 * 64 * 16 + (size_t)mlp1::TOK * (din + 1) * sizeof(float);
 #define MONARCH_LAUNCH_MLP1(KSV, ACTV)                                                                          \

@@ -76,6 +76,25 @@ def test_resident_weight_kernel_bf16(mm, order, tokens, d, dh, nb, act, bias):
     assert (num / np.linalg.norm(want, axis=1)).max() <= 2.5 * TOL_BF16
 
 
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("tokens,d,dh,nb,act", [
+    (32768 + 100, 384, 768, 2, 2),    # blocks of 192, 128 tokens per workgroup, ragged last tile
+    (33000, 512, 1024, 4, 1),         # blocks of 128, 256 tokens per workgroup
+])
+def test_streamed_weight_kernel_bf16(mm, order, tokens, d, dh, nb, act):
+    # large blocks and many tokens: weights go through an LDS ring by direct-to-LDS loads; oracle on sampled tokens
+    announce("mlp streamed", order, tokens, d, dh, nb, act)
+    w = workloads.mlp_inputs(tokens, d, dh, nb, order, seed=tokens + dh, bf16=True, std=0.08)
+    y = _run(mm, w, nb, order, act, dh, True)
+    rows = np.sort(np.random.default_rng(3).choice(tokens, size=300, replace=False))
+    rows[0] = 0; rows[-1] = tokens - 1; rows[1:9] = tokens - 1 - np.arange(1, 9) * 13
+    rows = np.unique(rows)
+    want = _oracle(w, nb, order, act, rows)
+    assert rel_l2(y[rows], want) <= TOL_BF16
+    num = np.linalg.norm(y[rows] - want, axis=1)
+    assert (num / np.linalg.norm(want, axis=1)).max() <= 2.5 * TOL_BF16
+
+
 def test_no_bias_and_single_block(mm):
     announce("mlp nb=1 no bias")
     w = workloads.mlp_inputs(10, 16, 64, 1, 1, seed=3, bf16=False, std=0.3, bias=False)
