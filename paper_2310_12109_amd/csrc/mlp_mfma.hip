@@ -12,6 +12,7 @@
 // fetched once per workgroup; the four partial Y tiles are summed through LDS in two rounds of plain
 // 16-byte stores and loads (waves 2,3 -> 0,1, then 1 -> 0; LDS float atomics are an order of magnitude
 // slower), then written with coalesced 16-byte stores.
+#include <type_traits>
 #include "kernels.h"
 
 namespace monarch {
@@ -432,20 +433,26 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
     const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
     uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_ring + (size_t)ring * OPS * 64);
 
-    // Wave w fetches the pieces o = w, w + 4, ... of a chunk (KS of them); lane ln of piece o supplies the 16
-    // bytes that lane will feed to MFMA o (rows / slots as in mlp_order1_kernel: W1 rows in hidden-unit order
+    // Wave w fetches the pieces o = w, w + 4, ... of a chunk (KS of them); piece o holds the 64 x 16 bytes that
+    // feed MFMA o (rows / slots as in mlp_order1_kernel: W1 rows in hidden-unit order
     // 8 (r/4) + 4 mt + r%4, W2 rows = output features).  Past the last chunk the last one is fetched again, so
     // that every iteration issues the same number of loads and the wait below can count them.
+    // The lane that FETCHES operand entry (row, lane group) is 4 row + group, not the lane that uses it
+    // (row + 16 group): four neighbouring lanes then fetch one 64-byte run of a row and the vector cache looks
+    // up one line for them instead of four (measured: 45 against 15 bytes per clock and compute unit).  A piece
+    // therefore sits in LDS in fetch order, and lane (l16, kg) reads entry 4 l16 + kg of it (free of bank
+    // conflicts, as measured).
+    const int frow = lane >> 2, fkg = lane & 3;
     int src_off[KS], src_step[KS];   // element offset of this lane's pieces in chunk 0, and per chunk
 #pragma unroll
     for (int u = 0; u < KS; ++u) {
         const int o = wave + 4 * u;
         if (o < 2 * KS) {
             const int mt = o / KS, ks = o - mt * KS;
-            src_off[u] = (8 * (l16 >> 2) + 4 * mt + (l16 & 3)) * DIN + 32 * ks + 8 * kg;
+            src_off[u] = (8 * (frow >> 2) + 4 * mt + (frow & 3)) * DIN + 32 * ks + 8 * fkg;
             src_step[u] = 32 * DIN;
         } else {
-            src_off[u] = (int)((W2b - W1b) + (16 * (o - 2 * KS) + l16) * dh + 8 * kg);
+            src_off[u] = (int)((W2b - W1b) + (16 * (o - 2 * KS) + frow) * dh + 8 * fkg);
             src_step[u] = 32;
         }
     }
@@ -497,7 +504,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
 #pragma unroll
             for (int e = 0; e < 8; ++e) bias[e >> 2][e & 3] = __uint_as_float((e & 1) ? (bw[e >> 1] & 0xffff0000u) : (bw[e >> 1] << 16));
         }
-        const uint4 *ops = lds_ring + (size_t)(j % ring) * OPS * 64 + lane;
+        const uint4 *ops = lds_ring + (size_t)(j % ring) * OPS * 64 + 4 * l16 + kg;
         Pack8 hop[NT];
         {
             Pack8 w1[2][KS];
@@ -549,7 +556,341 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
     }
 }
 
+
+// ---- variant for large blocks and few tokens --------------------------------------------------------
+// Same decomposition as mlp_order1_kernel (64 tokens of one block per workgroup, the waves split the hidden
+// units, partial tiles summed at the end), fed differently.  Measured on that kernel: a wave-wide 16-byte
+// load whose 16 rows are 16 different cache lines per lane quad costs the vector cache about 69 cycles, a
+// load whose lane quads each stay inside one line about 20; with every weight fetched in the first form the
+// compute unit spent most of its time in those look-ups.  Here
+//   * a wave brings the weights of its chunks into a private ring of three LDS slots with direct-to-LDS
+//     loads in the cheap lane order (lane 4 row + group fetches entry (row, group)), alternating the W1
+//     part and the W2 part of a chunk (2 KS KB each), ahead of their use, and reads each 1 KB operand from
+//     there once for all four column tiles.  The ring is private, so the main loop has no
+//     barrier: a wave waits on its own load counter only;
+//   * x goes through LDS once in the same way (each wave fetches a quarter of the tile);
+//   * at the end every wave owns the row tiles mt = wave (mod 4): the other waves' partial tiles go through
+//     LDS in one exchange (one barrier), the owner adds them, applies the output bias and stores.
+// Load accounting: direct-to-LDS loads and ordinary loads share the counter and complete in order; between
+// the prologue and the epilogue the only loads are the ring's, 2 KS per part.
+// Phase clocks for kernel tuning; compiled out unless MONARCH_MLP_CLOCKS is defined.
+#ifdef MONARCH_MLP_CLOCKS
+__device__ long long g_mlp_clk[4][64];
+#define MLP_MARK(i)                                                                                       \
+    do {                                                                                                  \
+        if (blockIdx.x == 1 && blockIdx.y == 1 && lane == 0) g_mlp_clk[wave][(i)] = __builtin_readcyclecounter(); \
+    } while (0)
+#else
+#define MLP_MARK(i)
+#endif
+
+// Two direct-to-LDS loads into consecutive 1 KB pieces with one save / restore of M0.  The LDS address is
+// passed as a number (wave-uniform, in a scalar register).
+__device__ __forceinline__ uint32_t lds_address(const void *p) { return (uint32_t)(size_t)(lptr_t)p; }
+__device__ __forceinline__ void dma_16_pair(const void *src0, const void *src1, uint32_t lds_first)
+{
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\tglobal_load_lds_dwordx4 %3, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "s"(lds_first), "v"(src0), "v"(src1)
+                 : "memory", "scc");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_at_most()   // also a compiler barrier: no LDS read moves above it
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds_reads()   // every LDS read issued so far has returned
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
+constexpr size_t split_lds_bytes(int ks, int dh) { return (size_t)24 * ks * 1024 + (size_t)dh * 2; }
+
+template <int KS, int ACT>
+__global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
+    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
+    const bf16_t *__restrict__ b2, int b1_interleaved)
+{
+    constexpr int DIN = 32 * KS, MT = 2 * KS, ITEM = 2 * KS;   // ITEM: 1 KB pieces of one ring part
+    extern __shared__ __attribute__((aligned(16))) uint4 lds_split[];   // [3 slots][4 waves][ITEM * 64], bias [dh]
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int frow = lane >> 2, fkg = lane & 3;   // the operand entry this lane fetches
+    const int rd = 4 * l16 + kg;                  // where the entry this lane uses sits in a piece
+    const int blk = blockIdx.y;
+    const int64_t t0 = (int64_t)blockIdx.x * TOK;
+    const int dh = d_hidden / nb, nch = dh / 32;
+    const int nmine = wave < nch ? (nch - wave + 3) / 4 : 0;   // chunks wave, wave + 4, ...
+    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_split + (size_t)12 * ITEM * 64);
+    auto slot_ptr = [&](int slot) { return lds_split + ((size_t)slot * 4 + wave) * ITEM * 64; };
+
+    // Parts of this wave, in the order they are needed: part 0 = W1 rows of its first chunk, then for
+    // jj = 0, 1, ...: part 2 jj + 1 = W1 rows of chunk jj + 1, part 2 jj + 2 = W2 columns of chunk jj (chunk jj
+    // of the wave is chunk wave + 4 jj of the block).  Part i lives in slot i % 3.  Past the wave's last chunk
+    // the last chunk is fetched again (never read), so that every request issues ITEM loads.
+    const bf16_t *w1_lane = W1b + (size_t)(8 * (frow >> 2) + (frow & 3)) * DIN + 8 * fkg;
+    const bf16_t *w2_lane = W2b + (size_t)frow * dh + 8 * fkg;
+    const uint32_t ring_addr = lds_address(lds_split) + (uint32_t)wave * ITEM * 1024;
+    auto request = [&](int i) {
+        const bool w1_part = i == 0 || (i & 1);
+        int c = i == 0 ? 0 : (i & 1) ? (i + 1) >> 1 : (i - 2) >> 1;
+        if (c > nmine - 1) c = nmine - 1;
+        const int h0 = 32 * (wave + 4 * c);
+        const uint32_t dst = ring_addr + (uint32_t)(i % 3) * 4 * ITEM * 1024;
+        if (w1_part) {
+            const bf16_t *src = w1_lane + (size_t)h0 * DIN;
+#pragma unroll
+            for (int o = 0; o < 2 * KS; o += 2)
+                dma_16_pair(src + 4 * (o / KS) * DIN + 32 * (o % KS), src + 4 * ((o + 1) / KS) * DIN + 32 * ((o + 1) % KS),
+                            dst + o * 1024);
+        } else {
+            const bf16_t *src = w2_lane + h0;
+#pragma unroll
+            for (int mt = 0; mt < MT; mt += 2)
+                dma_16_pair(src + (size_t)16 * mt * dh, src + (size_t)16 * (mt + 1) * dh, dst + mt * 1024);
+        }
+    };
+
+    // Prologue: the biases, then x (a quarter of the tile per wave) into the third slot's area and the first
+    // two parts into the first two slots.
+    MLP_MARK(0);
+    uint4 b1piece = make_uint4(0u, 0u, 0u, 0u);   // hidden bias, 8 units per thread (the usual layout)
+    const bool b1_vec = b1 && !b1_interleaved && dh <= 2048;
+    if (b1_vec && tid < dh / 8) b1piece = *reinterpret_cast<const uint4 *>(b1 + (size_t)blk * dh + 8 * tid);
+    uint2 b2raw[(MT + 3) / 4];                    // output bias of the row tiles this wave owns (mt = wave + 4 q)
+#pragma unroll
+    for (int q = 0; q < (MT + 3) / 4; ++q) {
+        b2raw[q] = make_uint2(0u, 0u);
+        if (b2 && wave + 4 * q < MT) b2raw[q] = *reinterpret_cast<const uint2 *>(b2 + (size_t)blk * DIN + 16 * (wave + 4 * q) + 4 * kg);
+    }
+    uint4 *xstage = lds_split + (size_t)2 * 4 * ITEM * 64;   // 4 KS pieces: piece (nt, ks) at (nt * KS + ks) * 64
+    {
+        int64_t t = t0 + 16 * wave + frow;   // wave w fetches the column tile nt = w
+        if (t >= tokens) t = tokens - 1;     // clamp: the column is computed but never stored
+        const bf16_t *row = x + t * d + blk * DIN + 8 * fkg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) dma_16(row + 32 * ks, xstage + (wave * KS + ks) * 64);
+    }
+    if (nmine > 0) {
+        request(0);
+        request(1);
+    }
+    if (b1_vec) {
+        if (tid < dh / 8) reinterpret_cast<uint4 *>(bias_lds)[tid] = b1piece;
+    } else {
+        for (int h = tid; h < dh; h += 256) {
+            uint16_t v = 0;
+            if (b1) v = reinterpret_cast<const uint16_t *>(b1)[b1_interleaved ? (size_t)h * nb + blk : (size_t)blk * dh + h];
+            bias_lds[h] = v;
+        }
+    }
+    // (x was requested before the two parts: at most those, 2 ITEM loads, may still be in flight)
+    MLP_MARK(1);
+    if (nmine > 0) wait_loads_at_most<2 * ITEM>();
+    else wait_loads_at_most<0>();
+    MLP_MARK(2);
+    __syncthreads();
+    Pack8 xop[4][KS];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xop[nt][ks].q = xstage[(nt * KS + ks) * 64 + rd];
+    wait_lds_reads();
+    __syncthreads();   // everybody holds x: the third slot is free
+    if (nmine > 0) request(2);
+    MLP_MARK(3);
+
+    f32x4 acc[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f32x4){0, 0, 0, 0};
+
+    // Tile mt, register r of lane group kg of the first GEMM is hidden unit h0 + 8 kg + 4 mt + r, the same for
+    // every token: the accumulators start from the bias.
+    auto start_from_bias = [&](f32x4 (&h)[2][4], int h0) {
+        const uint4 braw = *reinterpret_cast<const uint4 *>(bias_lds + h0 + 8 * kg);
+        const uint32_t bw[4] = {braw.x, braw.y, braw.z, braw.w};
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f32x4 b;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t w = bw[2 * mt + (r >> 1)];
+                b[r] = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+            }
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) h[mt][nt] = b;
+        }
+    };
+    auto first_gemm = [&](f32x4 (&h)[2][4], const Pack8 (&w1)[2][KS]) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) h[mt][nt] = mfma(w1[mt][ks].v, xop[nt][ks].v, h[mt][nt]);
+    };
+    auto read_piece_set = [&](Pack8 *dst, int slot) {
+        const uint4 *ops = slot_ptr(slot) + rd;
+#pragma unroll
+        for (int o = 0; o < ITEM; ++o) dst[o].q = ops[o * 64];
+    };
+
+    // The loop is software-pipelined so that the matrix core and the vector ALU of the SIMD (which has this one
+    // wave) work at the same time: while the activation of chunk jj runs on the vector ALU, the first GEMM of
+    // the wave's next chunk runs on the matrix core, one MFMA issued between slices of the activation (the
+    // order is pinned with scheduling barriers: left alone the compiler issues the MFMAs back to back, and a
+    // wave cannot issue anything while its next MFMA waits for the pipe); then the second GEMM of chunk jj.
+    // Load accounting of a step: when its W1 part is needed the two parts requested after it may be in flight,
+    // and the same holds for its W2 part: 2 ITEM loads at most.
+    constexpr int NM = 8 * KS;   // MFMAs of a first GEMM
+    f32x4 hacc[2][4];
+    auto step = [&](int jj, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value;
+        const int p = 2 * jj + 1;   // this step's parts: p (W1 of the next chunk), p + 1 (W2 of this chunk)
+        if (jj < 6) MLP_MARK(4 + 6 * jj);
+        if (!LAST && jj > 0) {
+            wait_lds_reads();   // (the previous step's W2 operands are long in registers)
+            request(p + 2);     // into the slot they came from
+        }
+        Pack8 w1[2][KS];
+        f32x4 hnext[2][4];
+        if (!LAST) {
+            if (jj < 6) MLP_MARK(5 + 6 * jj);
+            wait_loads_at_most<2 * ITEM>();
+            if (jj < 6) MLP_MARK(6 + 6 * jj);
+            read_piece_set(&w1[0][0], p % 3);
+            wait_lds_reads();
+            request(p + 3);
+            start_from_bias(hnext, 32 * (wave + 4 * (jj + 1)));
+        }
+        // activation on the accumulators; two stacked tiles become one K=32 operand (slot 4mt + r)
+        Pack8 hop[4];
+        float hv[32];   // value v = 8 nt + 4 mt + r
+        if (jj < 6) MLP_MARK(7 + 6 * jj);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < NM; ++u) {
+            if (!LAST) {
+                const int ks = u / 8, mt = (u / 4) % 2, nt = u % 4;
+                hnext[mt][nt] = mfma(w1[mt][ks].v, xop[nt][ks].v, hnext[mt][nt]);
+            }
+#pragma unroll
+            for (int v = (u * 32) / NM; v < ((u + 1) * 32) / NM; ++v) {
+                hv[v] = act_fast<ACT>(hacc[(v >> 2) & 1][v >> 3][v & 3]);
+                if (v & 1) hop[v >> 3].d[(v >> 1) & 3] = pack_bf16(hv[v - 1], hv[v]);
+            }
+        }
+        if (!LAST) {
+#pragma unroll
+            for (int u = 0; u < NM; ++u) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, (336 + NM - 1) / NM, 0);   // its share of the activation
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (jj < 6) MLP_MARK(8 + 6 * jj);
+        // second GEMM: Y^T += W2[:, chunk] * H^T chunk (the last step requested nothing: it waits for all)
+        if (LAST) wait_loads_at_most<0>();
+        else wait_loads_at_most<2 * ITEM>();
+        if (jj < 6) MLP_MARK(9 + 6 * jj);
+        Pack8 w2[MT];
+        read_piece_set(w2, (p + 1) % 3);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
+        // operand reads run four row tiles ahead of the MFMAs that use them
+        __builtin_amdgcn_sched_group_barrier(0x100, MT < 4 ? MT : 4, 1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
+            if (mt + 4 < MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (!LAST) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) hacc[mt][nt] = hnext[mt][nt];
+        }
+    };
+    if (nmine > 0) {
+        wait_loads_at_most<2 * ITEM>();   // part 0 has landed
+        Pack8 w1[2][KS];
+        read_piece_set(&w1[0][0], 0);
+        wait_lds_reads();
+        request(3);
+        start_from_bias(hacc, 32 * wave);
+        first_gemm(hacc, w1);
+        MLP_MARK(46);
+#pragma unroll 1
+        for (int jj = 0; jj < nmine - 1; ++jj) step(jj, std::false_type{});
+        step(nmine - 1, std::true_type{});
+    }
+
+    // Exchange: tile mt belongs to wave mt % 4; the three other waves park their partial of it at
+    // [mt][(wave - owner - 1) mod 4][nt][lane].  The ring is dead, but its last (repeated) requests may still
+    // be landing: they are waited for before the area is reused.
+    MLP_MARK(40);
+    wait_loads_at_most<0>();
+    MLP_MARK(41);
+    __syncthreads();
+    MLP_MARK(42);
+    f32x4 *part = reinterpret_cast<f32x4 *>(lds_split);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int owner = mt & 3;
+        if (wave != owner) {
+            f32x4 *dst = part + ((size_t)(mt * 3 + ((wave - owner - 1) & 3)) * 4) * 64 + lane;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) dst[nt * 64] = acc[mt][nt];
+        }
+    }
+    MLP_MARK(43);
+    __syncthreads();
+    MLP_MARK(44);
+    // accumulator rows 4 kg .. 4 kg + 3 of tile mt are 4 consecutive features of a token: 8-byte stores
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if (wave != (mt & 3)) continue;
+        const uint2 braw = b2raw[mt >> 2];
+        const float bias2[4] = {__uint_as_float(braw.x << 16), __uint_as_float(braw.x & 0xffff0000u),
+                                __uint_as_float(braw.y << 16), __uint_as_float(braw.y & 0xffff0000u)};
+        const f32x4 *src = part + (size_t)mt * 3 * 4 * 64 + lane;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            f32x4 v = acc[mt][nt];
+#pragma unroll
+            for (int q = 0; q < 3; ++q) v += src[(q * 4 + nt) * 64];
+            const int64_t t = t0 + 16 * nt + l16;
+            if (t < tokens) {
+                uint2 o;
+                o.x = pack_bf16(v[0] + bias2[0], v[1] + bias2[1]);
+                o.y = pack_bf16(v[2] + bias2[2], v[3] + bias2[3]);
+                *reinterpret_cast<uint2 *>(y + t * d + blk * DIN + 16 * mt + 4 * kg) = o;
+            }
+        }
+    }
+    MLP_MARK(45);
+}
+
 }  // namespace mlp1
+
+#ifdef MONARCH_MLP_CLOCKS
+extern "C" int monarch_debug_mlp_clocks(long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mlp1::g_mlp_clk), sizeof(long long) * 4 * 64);
+}
+#endif
 
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
 {
@@ -645,6 +986,37 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
 #undef MONARCH_LAUNCH_STR_ACT
 #undef MONARCH_LAUNCH_STR_NT
 #undef MONARCH_LAUNCH_STR
+        MONARCH_HIP_CHECK(hipGetLastError());
+        return MONARCH_OK;
+    }
+    const size_t split_lds = mlp1::split_lds_bytes(din / 32, dh_blk);
+    if (split_lds <= 160 * 1024) {
+#define MONARCH_LAUNCH_SPL(KSV, ACTV)                                                                            \
+    do {                                                                                                         \
+        auto kern = mlp1::mlp_order1_split_kernel<KSV, ACTV>;                                                    \
+        if (split_lds > 48 * 1024)                                                                               \
+            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                  (int)split_lds));                                              \
+        hipLaunchKernelGGL(kern, grid, dim3(256), split_lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d,       \
+                           d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2,             \
+                           (const bf16_t *)b2, b1_interleaved);                                                  \
+    } while (0)
+#define MONARCH_LAUNCH_SPL_ACT(KSV)                     \
+    do {                                                \
+        if (act == 2) MONARCH_LAUNCH_SPL(KSV, 2);       \
+        else if (act == 1) MONARCH_LAUNCH_SPL(KSV, 1);  \
+        else MONARCH_LAUNCH_SPL(KSV, 0);                \
+    } while (0)
+        switch (din / 32) {
+        case 1: MONARCH_LAUNCH_SPL_ACT(1); break;
+        case 2: MONARCH_LAUNCH_SPL_ACT(2); break;
+        case 3: MONARCH_LAUNCH_SPL_ACT(3); break;
+        case 4: MONARCH_LAUNCH_SPL_ACT(4); break;
+        case 5: MONARCH_LAUNCH_SPL_ACT(5); break;
+        default: MONARCH_LAUNCH_SPL_ACT(6); break;
+        }
+#undef MONARCH_LAUNCH_SPL_ACT
+#undef MONARCH_LAUNCH_SPL
         MONARCH_HIP_CHECK(hipGetLastError());
         return MONARCH_OK;
     }

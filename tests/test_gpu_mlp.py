@@ -45,6 +45,8 @@ def test_small_ragged(mm, order, act, bf16):
     (130, 256, 1024, 4, 1, True),     # blocks of 64 -> 256
     (33, 384, 768, 2, 0, False),      # blocks of 192 (the widest), no bias, no activation
     (64, 512, 512, 16, 2, True),      # many small blocks, d_hidden = d
+    (70, 480, 800, 5, 2, True),       # blocks of 96 -> 160: five hidden chunks over four waves
+    (100, 320, 448, 2, 2, True),      # blocks of 160 -> 224: seven hidden chunks
 ])
 def test_matrix_core_shapes_bf16(mm, order, tokens, d, dh, nb, act, bias):
     # bf16 shapes with blocks that are multiples of 32: the MFMA kernels (fused block MLP; for order 2
