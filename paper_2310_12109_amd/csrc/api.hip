@@ -174,6 +174,30 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
     if (overlaps(src, inverse ? spec_bytes : typed_bytes, dst, inverse ? typed_bytes : spec_bytes))
         return fail(MONARCH_EINVAL, "output overlaps input");
 
+    // Real bf16 rows, two factors that fit an LDS-resident chunk: the whole transform in one kernel, the row read
+    // once and the spectrum written once (forward) or the other way round.
+    if (nf == 2 && is_real && fft2_lds_supported(factors[0], factors[1], dt)) {
+        Fft2Args a;
+        a.in = src;
+        a.out = dst;
+        a.gate = a.gate_out = a.kf = nullptr;
+        a.rows = rows;
+        a.N = N;
+        a.O = 1;
+        a.f1 = factors[0];
+        a.f2 = factors[1];
+        a.n_valid = N;
+        a.H = 1;
+        a.pair_stride = 1;
+        a.real_rows = rows;
+        a.scale = 1.0f / (float)N;
+        a.load = inverse ? LD_C32_CONJ : LD_REAL;
+        a.store = inverse ? ST_REAL_SCALE_GATE : ST_C32_NATURAL;
+        a.inverse = inverse;
+        a.tw_outer = 0;
+        return launch_fft2_lds(a, s);
+    }
+
     const size_t buf = align_up(spec_bytes, 256);
     void *bufs[2] = {ws, (char *)ws + buf};
     const void *cur = src;

@@ -67,9 +67,11 @@ __device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
 // otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: row
 // tiles of the output that are needed.  TW: multiply output row j by omega_(mod)^(alpha j + beta)
 // (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors).
-template <int F, int PITCH, bool STRIDED, bool TW>
+// GOUT (only with !STRIDED): the results do not go back into the tile but, unrounded, to gout[j * gstride + col]
+// as complex fp32 (the natural order of a two-factor transform: frequency j f1 + col).
+template <int F, int PITCH, bool STRIDED, bool TW, bool GOUT = false>
 __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int col, int lane, int live_ks, int want_jt,
-                                           int alpha, int beta, float inv_mod)
+                                           int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32;
     const int kg = lane >> 4;
@@ -131,8 +133,10 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
                 float2 z = make_float2(dr[r] - ds[r], di[r]);
                 if constexpr (TW) z = cmul(z, tw[r]);
                 o[r] = pack2(z.x, z.y);
+                if constexpr (GOUT) gout[(int64_t)(16 * jt + 4 * kg + r) * gstride + col] = z;
             }
-            if constexpr (STRIDED) {
+            if constexpr (GOUT) {
+            } else if constexpr (STRIDED) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) tile[(16 * jt + 4 * kg + r) * PITCH + col] = o[r];
             } else {
@@ -175,7 +179,20 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
     constexpr bool MULK = LOAD == LD_C16_CONJ_MULK, HERM = LOAD == LD_C16_HERM_MULK;
     constexpr bool FUSED = REAL_IN && REAL_OUT;   // whole convolution of a two-factor row: forward, times kf, inverse
+    constexpr bool NAT_IN = LOAD == LD_C32_CONJ;        // complex fp32 rows in natural order (monarch_ifft's input)
+    constexpr bool NAT_OUT = STORE == ST_C32_NATURAL;   // complex fp32 rows in natural order (monarch_fft's output)
     constexpr int NIT4 = (CH + 4 * THREADS - 1) / (4 * THREADS);   // steps of 4 complex elements per thread
+    constexpr int NIT2 = (CH + 2 * THREADS - 1) / (2 * THREADS);   // steps of 2 complex elements per thread
+    // Natural order: frequency m = j2 F1 + j1 sits at tile position (j1, j2).  Step idx of a thread moves the two
+    // neighbours m = 2 idx', 2 idx' + 1 (16 bytes); within a wave 16 (8 if F1 = 16) lanes run along j1 and the
+    // rest along j2, which spreads the tile words over the LDS banks.
+    constexpr int NAT_A = F1 / 2 < 16 ? F1 / 2 : 16, NAT_G = 64 / NAT_A;
+    auto nat_pos = [](int idx, int &j1, int &j2) {
+        const int a = idx % NAT_A, g = (idx / NAT_A) % NAT_G, blk = idx / 64;
+        constexpr int BJ1 = (F1 / 2) / NAT_A;
+        j1 = 2 * ((blk % BJ1) * NAT_A + a);
+        j2 = (blk / BJ1) * NAT_G + g;
+    };
     constexpr int NIT8 = (CH + 8 * THREADS - 1) / (8 * THREADS);   // steps of 8 real elements per thread
     extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     uint32_t *tile = lds;                                                   // [F1][PITCH] packed bf16 pairs
@@ -198,10 +215,22 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
 
     // staged inputs of one chunk
-    u32x4 za[REAL_IN ? NIT8 : NIT4], zb[REAL_IN ? NIT8 : NIT4], zc[REAL_IN ? NIT8 : HERM ? NIT4 : 1], zd[REAL_IN ? NIT8 : HERM ? NIT4 : 1];
+    u32x4 za[REAL_IN ? NIT8 : NAT_IN ? NIT2 : NIT4], zb[REAL_IN ? NIT8 : NAT_IN ? 1 : NIT4], zc[REAL_IN ? NIT8 : HERM ? NIT4 : 1],
+        zd[REAL_IN ? NIT8 : HERM ? NIT4 : 1];
     auto request = [&](int64_t q) {
         const int64_t rc = q / p.O;
-        if constexpr (REAL_IN) {
+        if constexpr (NAT_IN) {
+            const float *src = (const float *)p.in + 2 * rc * (int64_t)p.N;
+#pragma unroll
+            for (int it = 0; it < NIT2; ++it) {
+                const int idx = tid + it * THREADS;
+                if (2 * idx < CH) {
+                    int j1, j2;
+                    nat_pos(idx, j1, j2);
+                    za[it] = *reinterpret_cast<const u32x4 *>(src + 2 * (j2 * F1 + j1));
+                }
+            }
+        } else if constexpr (REAL_IN) {
             if constexpr (VEC) {
                 const int64_t ra = LOAD == LD_REAL_PAIR ? pair_first_row(p, rc) : rc;
                 const bool hasb = LOAD == LD_REAL_PAIR && ra + p.pair_stride < p.real_rows;
@@ -266,7 +295,19 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         }
     };
     auto deposit = [&](int64_t q, bool paired) {   // staged inputs -> tile (natural order of the chunk)
-        if constexpr (REAL_IN) {
+        if constexpr (NAT_IN) {   // conjugated: the inverse is conj(F conj(.)) / N
+#pragma unroll
+            for (int it = 0; it < NIT2; ++it) {
+                const int idx = tid + it * THREADS;
+                if (2 * idx < CH) {
+                    int j1, j2;
+                    nat_pos(idx, j1, j2);
+                    const u32x4 w = za[it];
+                    tile[j1 * PITCH + j2] = pack2(__uint_as_float(w[0]), -__uint_as_float(w[1]));
+                    tile[(j1 + 1) * PITCH + j2] = pack2(__uint_as_float(w[2]), -__uint_as_float(w[3]));
+                }
+            }
+        } else if constexpr (REAL_IN) {
             const int64_t rc = q / p.O;
             const int64_t ra = LOAD == LD_REAL_PAIR ? pair_first_row(p, rc) : rc;
             const bool hasb = LOAD == LD_REAL_PAIR && ra + p.pair_stride < p.real_rows;
@@ -431,8 +472,15 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             for (int t = wave; t < F2 / 16; t += WAVES)
                 stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, live_x, F1 / 16, 16 * t + l16, 0, inv_mod);
             __syncthreads();
-            for (int t = wave; t < F1 / 16; t += WAVES)
-                stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod);
+            if constexpr (NAT_OUT) {
+                float2 *gout = (float2 *)p.out + rc * (int64_t)p.N;
+                for (int t = wave; t < F1 / 16; t += WAVES)
+                    stage_tile<F2, PITCH, false, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod,
+                                                              gout, F1);
+            } else {
+                for (int t = wave; t < F1 / 16; t += WAVES)
+                    stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod);
+            }
         }
         if constexpr (FUSED) {
             __syncthreads();
@@ -475,7 +523,9 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         __syncthreads();
 
         // ---- tile -> global
-        if constexpr (!REAL_OUT) {
+        if constexpr (NAT_OUT) {
+            // (written by the second stage)
+        } else if constexpr (!REAL_OUT) {
             uint32_t *dst = (uint32_t *)p.out + rc * p.N + (q - rc * p.O) * CH;
 #pragma unroll
             for (int it = 0; it < NIT4; ++it) {
@@ -589,6 +639,10 @@ static int launch_one(const Fft2Args &p, hipStream_t s)
 template <int F1, int F2>
 static int launch_modes(const Fft2Args &p, hipStream_t s)
 {
+    if (p.O == 1 && !p.inverse && p.load == LD_REAL && p.store == ST_C32_NATURAL)   // monarch_fft, real rows
+        return launch_one<F1, F2, false, LD_REAL, ST_C32_NATURAL>(p, s);
+    if (p.O == 1 && p.inverse && p.load == LD_C32_CONJ && p.store == ST_REAL_SCALE_GATE)   // monarch_ifft, real rows
+        return launch_one<F1, F2, true, LD_C32_CONJ, ST_REAL_SCALE_GATE>(p, s);
     if (!p.inverse && p.store != ST_C16) {   // whole convolution in one kernel
         if (p.n_valid % 8) return fail(MONARCH_EINVAL, "internal: the fused chunk convolution needs rows of a multiple of 8 elements");
         if (p.load == LD_REAL_PAIR && p.store == ST_REAL_PAIR) return launch_vec<F1, F2, false, LD_REAL_PAIR, ST_REAL_PAIR, true>(p, s);

@@ -113,6 +113,29 @@ def test_bf16_ifft_matrix_core_passes(mm, factors):
     assert rel_l2(xre, want.real) <= TOL_BF16
 
 
+@pytest.mark.parametrize("factors,rows", [((64, 32), 1300), ((32, 32), 700), ((64, 64), 600), ((128, 64), 300)])
+def test_bf16_real_rows_one_kernel_many_rows(mm, factors, rows):
+    # real bf16 rows with two LDS-sized factors: one kernel per transform, workgroups walk over several rows;
+    # checked against the library FFT (paper's sign: forward = conj of numpy's forward for real input)
+    announce("fft/ifft bf16 one kernel", factors, rows)
+    N = int(np.prod(factors))
+    rng = np.random.default_rng(N + rows)
+    x = workloads.round_to_bf16(rng.standard_normal((rows, N)).astype(np.float32))
+    X = _cplx(mm.monarch_fft(dev(x, True), factors, True))
+    want = np.conj(np.fft.fft(x.astype(np.float64), axis=-1))
+    num = np.linalg.norm(X - want, axis=1)
+    assert (num / np.linalg.norm(want, axis=1)).max() <= TOL_BF16
+    # a few rows against the oracle's own sum as well
+    for r in (0, rows // 2, rows - 1):
+        assert rel_l2(X[r:r + 1], oracle.dft(x[r:r + 1].astype(np.float64))) <= TOL_BF16
+    Xr = rng.standard_normal((rows, N)).astype(np.float32)
+    Xi = rng.standard_normal((rows, N)).astype(np.float32)
+    back = host(mm.monarch_ifft(dev(np.stack([Xr, Xi], -1)), factors, True, dtype=torch.bfloat16))
+    want = (np.fft.fft(Xr.astype(np.float64) + 1j * Xi.astype(np.float64), axis=-1) / N).real
+    num = np.linalg.norm(back - want, axis=1)
+    assert (num / np.linalg.norm(want, axis=1)).max() <= TOL_BF16
+
+
 def test_unit_vector_gives_dft_column(mm):
     announce("fft delta")
     N = 256
