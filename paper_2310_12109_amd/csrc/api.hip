@@ -174,9 +174,10 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
     if (overlaps(src, inverse ? spec_bytes : typed_bytes, dst, inverse ? typed_bytes : spec_bytes))
         return fail(MONARCH_EINVAL, "output overlaps input");
 
-    // Real bf16 rows, two factors that fit an LDS-resident chunk: the whole transform in one kernel, the row read
-    // once and the spectrum written once (forward) or the other way round.
-    if (nf == 2 && is_real && fft2_lds_supported(factors[0], factors[1], dt)) {
+    // bf16 rows, two factors that fit an LDS-resident chunk: the whole transform in one kernel, the row read once
+    // and the spectrum written once (forward) or the other way round.  (Complex bf16 rows are interleaved pairs:
+    // the packed form the kernel keeps its tile in.)
+    if (nf == 2 && fft2_lds_supported(factors[0], factors[1], dt)) {
         Fft2Args a;
         a.in = src;
         a.out = dst;
@@ -191,8 +192,8 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
         a.pair_stride = 1;
         a.real_rows = rows;
         a.scale = 1.0f / (float)N;
-        a.load = inverse ? LD_C32_CONJ : LD_REAL;
-        a.store = inverse ? ST_REAL_SCALE_GATE : ST_C32_NATURAL;
+        a.load = inverse ? LD_C32_CONJ : is_real ? LD_REAL : LD_C16;
+        a.store = !inverse ? ST_C32_NATURAL : is_real ? ST_REAL_SCALE_GATE : ST_CPLX_CONJ_SCALE;
         a.inverse = inverse;
         a.tw_outer = 0;
         return launch_fft2_lds(a, s);

@@ -530,7 +530,14 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
 #pragma unroll
             for (int it = 0; it < NIT4; ++it) {
                 const int e = 4 * (tid + it * THREADS);
-                if (e < CH) *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+                if (e < CH) {
+                    u32x4 w = *reinterpret_cast<const u32x4 *>(tile + tix(e));
+                    if constexpr (STORE == ST_CPLX_CONJ_SCALE) {   // the inverse's result: conj(tile) / N, as bf16 pairs
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) w[t] = pack2(lo_f32(w[t]) * p.scale, -hi_f32(w[t]) * p.scale);
+                    }
+                    *reinterpret_cast<u32x4 *>(dst + e) = w;
+                }
             }
             if (TWO && paired) {
                 uint32_t *dst2 = (uint32_t *)p.out + rc * p.N + (int64_t)(p.O - o_here) * CH;
@@ -643,6 +650,10 @@ static int launch_modes(const Fft2Args &p, hipStream_t s)
         return launch_one<F1, F2, false, LD_REAL, ST_C32_NATURAL>(p, s);
     if (p.O == 1 && p.inverse && p.load == LD_C32_CONJ && p.store == ST_REAL_SCALE_GATE)   // monarch_ifft, real rows
         return launch_one<F1, F2, true, LD_C32_CONJ, ST_REAL_SCALE_GATE>(p, s);
+    if (p.O == 1 && !p.inverse && p.load == LD_C16 && p.store == ST_C32_NATURAL)   // monarch_fft, complex bf16 rows
+        return launch_one<F1, F2, false, LD_C16, ST_C32_NATURAL>(p, s);
+    if (p.O == 1 && p.inverse && p.load == LD_C32_CONJ && p.store == ST_CPLX_CONJ_SCALE)   // monarch_ifft, complex bf16 rows
+        return launch_one<F1, F2, true, LD_C32_CONJ, ST_CPLX_CONJ_SCALE>(p, s);
     if (!p.inverse && p.store != ST_C16) {   // whole convolution in one kernel
         if (p.n_valid % 8) return fail(MONARCH_EINVAL, "internal: the fused chunk convolution needs rows of a multiple of 8 elements");
         if (p.load == LD_REAL_PAIR && p.store == ST_REAL_PAIR) return launch_vec<F1, F2, false, LD_REAL_PAIR, ST_REAL_PAIR, true>(p, s);
