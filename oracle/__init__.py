@@ -93,6 +93,22 @@ def matmul(x, R, L):
     return y
 
 
+def matmul_backward(x, R, L, dy):
+    """(dx, dR, dL) of S = sum_v <dy[v], M x[v]>, M = P3 L P2 R P1, by the chain rule through the five steps."""
+    x, R, L, dy = _f64(x), _f64(R), _f64(L), _f64(dy)
+    nbR, r_out, r_in = R.shape
+    nbL, l_out, l_in = L.shape
+    batch = x.shape[0]
+    assert x.shape[1] == nbR * r_in and dy.shape == (batch, nbL * l_out)
+    dx, dR, dL = np.empty_like(x), np.empty_like(R), np.empty_like(L)
+    rc = lib().oracle_matmul_backward(_p(x), _p(R), _p(L), _p(dy), _p(dx), _p(dR), _p(dL), ctypes.c_int64(batch),
+                                      ctypes.c_int(nbR), ctypes.c_int(r_out), ctypes.c_int(r_in),
+                                      ctypes.c_int(nbL), ctypes.c_int(l_out), ctypes.c_int(l_in))
+    if rc != 0:
+        raise ValueError("inconsistent Monarch factor shapes")
+    return dx, dR, dL
+
+
 def dft(x):
     """X[r,m] = sum_j x[r,j] omega_N^(m j), omega_N = exp(+2 pi i / N); O(N^2) per row."""
     x = _c128(x)

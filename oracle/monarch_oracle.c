@@ -226,6 +226,81 @@ int oracle_matmul(const double *x, const double *R, const double *L, double *y, 
     return 0;
 }
 
+/*
+ * Gradients of S = sum_v <dy[v,:], M x[v,:]> with M = P3 L P2 R P1 (Sec. 3.1), by the chain rule through the
+ * five steps of the product, each step's adjoint written out (own derivation; the paper states the forward
+ * product only):
+ *   forward   t0 = P1 x,  t1 = R t0,  t2 = P2 t1,  t3 = L t2,  y = P3 t3
+ *   backward  g3 = P3^T dy,  dL_k += g3_k t2_k^T,  g2 = L^T g3,  g1 = P2^T g2,  dR_k += g1_k t0_k^T,
+ *             g0 = R^T g1,  dx = P1^T g0
+ * x: batch x d_in, dy: batch x d_out, dx: batch x d_in, dR: like R, dL: like L (sums over the batch).
+ * Any of dx, dR, dL may be NULL.  Returns 0, -1 on inconsistent sizes.
+ */
+int oracle_matmul_backward(const double *x, const double *R, const double *L, const double *dy,
+                           double *dx, double *dR, double *dL, int64_t batch,
+                           int nbR, int r_out, int r_in, int nbL, int l_out, int l_in)
+{
+    if (nbR <= 0 || r_out <= 0 || r_in <= 0 || nbL <= 0 || l_out <= 0 || l_in <= 0) return -1;
+    if ((int64_t)nbR * r_out != (int64_t)nbL * l_in) return -1;
+    int d_in = nbR * r_in, d_mid = nbR * r_out, d_out = nbL * l_out;
+    int32_t *s1 = (int32_t *)malloc(sizeof(int32_t) * (size_t)d_in);
+    int32_t *s2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)d_mid);
+    int32_t *s3 = (int32_t *)malloc(sizeof(int32_t) * (size_t)d_out);
+    oracle_perm(r_in, d_in, s1);    /* (P1 x)[i] = x[s1[i]] */
+    oracle_perm(nbR, d_mid, s2);
+    oracle_perm(nbL, d_out, s3);
+    if (dR) memset(dR, 0, sizeof(double) * (size_t)nbR * r_out * r_in);
+    if (dL) memset(dL, 0, sizeof(double) * (size_t)nbL * l_out * l_in);
+    double *t0 = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *t1 = (double *)malloc(sizeof(double) * (size_t)d_mid);
+    double *t2 = (double *)malloc(sizeof(double) * (size_t)d_mid);
+    double *g3 = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *g2 = (double *)malloc(sizeof(double) * (size_t)d_mid);
+    double *g1 = (double *)malloc(sizeof(double) * (size_t)d_mid);
+    double *g0 = (double *)malloc(sizeof(double) * (size_t)d_in);
+    for (int64_t v = 0; v < batch; ++v) {   /* (serial: the parameter gradients are sums over v) */
+        const double *xv = x + (size_t)v * d_in, *dyv = dy + (size_t)v * d_out;
+        for (int i = 0; i < d_in; ++i) t0[i] = xv[s1[i]];
+        for (int k = 0; k < nbR; ++k)
+            for (int r = 0; r < r_out; ++r) {
+                double acc = 0.0;
+                for (int c = 0; c < r_in; ++c) acc += R[((size_t)k * r_out + r) * r_in + c] * t0[k * r_in + c];
+                t1[k * r_out + r] = acc;
+            }
+        for (int i = 0; i < d_mid; ++i) t2[i] = t1[s2[i]];
+        /* g3 = P3^T dy:  y[i] = t3[s3[i]]  =>  g3[s3[i]] = dy[i] */
+        for (int i = 0; i < d_out; ++i) g3[s3[i]] = dyv[i];
+        for (int k = 0; k < nbL; ++k)
+            for (int r = 0; r < l_out; ++r)
+                for (int a = 0; a < l_in; ++a)
+                    if (dL) dL[((size_t)k * l_out + r) * l_in + a] += g3[k * l_out + r] * t2[k * l_in + a];
+        for (int k = 0; k < nbL; ++k)
+            for (int a = 0; a < l_in; ++a) {
+                double acc = 0.0;
+                for (int r = 0; r < l_out; ++r) acc += L[((size_t)k * l_out + r) * l_in + a] * g3[k * l_out + r];
+                g2[k * l_in + a] = acc;
+            }
+        /* g1 = P2^T g2:  t2[i] = t1[s2[i]]  =>  g1[s2[i]] = g2[i] */
+        for (int i = 0; i < d_mid; ++i) g1[s2[i]] = g2[i];
+        for (int k = 0; k < nbR; ++k)
+            for (int r = 0; r < r_out; ++r)
+                for (int c = 0; c < r_in; ++c)
+                    if (dR) dR[((size_t)k * r_out + r) * r_in + c] += g1[k * r_out + r] * t0[k * r_in + c];
+        if (dx) {
+            for (int k = 0; k < nbR; ++k)
+                for (int c = 0; c < r_in; ++c) {
+                    double acc = 0.0;
+                    for (int r = 0; r < r_out; ++r) acc += R[((size_t)k * r_out + r) * r_in + c] * g1[k * r_out + r];
+                    g0[k * r_in + c] = acc;
+                }
+            /* dx = P1^T g0:  t0[i] = x[s1[i]]  =>  dx[s1[i]] = g0[i] */
+            for (int i = 0; i < d_in; ++i) dx[(size_t)v * d_in + s1[i]] = g0[i];
+        }
+    }
+    free(s1); free(s2); free(s3); free(t0); free(t1); free(t2); free(g3); free(g2); free(g1); free(g0);
+    return 0;
+}
+
 /* ------------------------------------------------------------------------- */
 /* DFT by its definition (Appendix: F_N[m,j] = omega_N^(m j))                */
 /* ------------------------------------------------------------------------- */
