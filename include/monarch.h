@@ -80,6 +80,24 @@ size_t monarch_matmul_workspace_bytes(int64_t batch, int nbR, int r_out, int r_i
                                       int nbL, int l_out, int l_in, monarch_dtype dt);
 
 /*
+ * Gradients of monarch_matmul (Sec. 3.1, M = P L P R P; the chain rule through the five factors of the
+ * product), for a training step: with S = sum_v <dy[v,:], y[v,:]>,
+ *   dx[v,:] = M^T dy[v,:]                       (batch, d_in), type dt
+ *   dR[k][r][c] = dS / dR[k][r][c],  dL alike   shaped like R and L, always float32 (sums over the batch)
+ * x, R, L as in monarch_matmul; dy: (batch, d_out) of type dt.  Any of dx, dR, dL may be NULL (not computed);
+ * dR and dL are overwritten, not accumulated into.  The sums over the batch are formed with floating-point
+ * atomic adds, so their last bits depend on the order in which workgroups finish.
+ * Errors: EINVAL (null x, R, L, dy with batch > 0; misalignment; an output overlapping an input), ESHAPE (as
+ * monarch_matmul; rows of (d_in + d_out + 2 d_mid) * 4 bytes beyond 160 KB), EDTYPE, EHIP.
+ */
+int monarch_matmul_backward(const void *x, const void *R, const void *L, const void *dy,
+                            void *dx, float *dR, float *dL, int64_t batch,
+                            int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
+                            monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_matmul_backward_workspace_bytes(int64_t batch, int nbR, int r_out, int r_in,
+                                               int nbL, int l_out, int l_in, monarch_dtype dt);
+
+/*
  * Monarch-factored DFT (appendix, DFT corollary; order 3 per the p-variate
  * section):  X[r,:] = F_N x[r,:],  F_N[m,j] = omega_N^(m j), unnormalised,
  * natural output order.  N = factors[0]*...*factors[nf-1], nf in {2,3}; the

@@ -32,6 +32,9 @@ _lib.monarch_permutation_index.argtypes = [_i, _i, _vp]
 _lib.monarch_matmul.argtypes = [_vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_matmul_workspace_bytes.restype = _sz
 _lib.monarch_matmul_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
+_lib.monarch_matmul_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_matmul_backward_workspace_bytes.restype = _sz
+_lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
 _lib.monarch_fft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_ifft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_fft_workspace_bytes.restype = _sz
@@ -46,6 +49,7 @@ _lib.monarch_mlp_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
 EXPORTS = [
     "monarch_strerror", "monarch_last_error", "monarch_permutation_index",
     "monarch_matmul", "monarch_matmul_workspace_bytes",
+    "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
     "monarch_mlp", "monarch_mlp_workspace_bytes",
@@ -120,6 +124,19 @@ def monarch_matmul(x, R, L, out=None):
     _check(_lib.monarch_matmul(_ptr(x), _ptr(R), _ptr(L), _ptr(y), batch, nbR, r_out, r_in, nbL, l_out, l_in,
                                _dt(x), None, 0, _stream()))
     return y
+
+
+def monarch_matmul_backward(x, R, L, dy, need_dx=True, need_dR=True, need_dL=True):
+    """(dx, dR, dL) of sum <dy, monarch_matmul(x, R, L)>; dR, dL are float32.  Skipped outputs are None."""
+    nbR, r_out, r_in = R.shape
+    nbL, l_out, l_in = L.shape
+    batch = x.shape[0]
+    dx = torch.empty_like(x) if need_dx else None
+    dR = torch.empty(R.shape, dtype=torch.float32, device=x.device) if need_dR else None
+    dL = torch.empty(L.shape, dtype=torch.float32, device=x.device) if need_dL else None
+    _check(_lib.monarch_matmul_backward(_ptr(x), _ptr(R), _ptr(L), _ptr(dy), _ptr(dx), _ptr(dR), _ptr(dL), batch,
+                                        nbR, r_out, r_in, nbL, l_out, l_in, _dt(x), None, 0, _stream()))
+    return dx, dR, dL
 
 
 def monarch_fft_workspace_bytes(rows, N, factors, dt=F32):

@@ -141,6 +141,52 @@ int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t
                                  dt, dt, dt, (hipStream_t)stream);
 }
 
+size_t monarch_matmul_backward_workspace_bytes(int64_t, int, int, int, int, int, int, monarch_dtype) { return 0; }
+
+int monarch_matmul_backward(const void *x, const void *R, const void *L, const void *dy,
+                            void *dx, float *dR, float *dL, int64_t batch,
+                            int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
+                            monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    (void)ws; (void)ws_bytes;
+    clear_error();
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (batch < 0) return fail(MONARCH_ESHAPE, "negative batch");
+    if (nbR < 1 || r_out < 1 || r_in < 1 || nbL < 1 || l_out < 1 || l_in < 1)
+        return fail(MONARCH_ESHAPE, "all block counts and block sizes must be >= 1");
+    if ((int64_t)nbR * r_out != (int64_t)nbL * l_in)
+        return fail(MONARCH_ESHAPE, "d_mid mismatch: nbR*r_out=%lld but nbL*l_in=%lld",
+                    (long long)nbR * r_out, (long long)nbL * l_in);
+    const int64_t d_in = (int64_t)nbR * r_in, d_mid = (int64_t)nbR * r_out, d_out = (int64_t)nbL * l_out;
+    if (d_in > 65536 || d_mid > 65536 || d_out > 65536 || !matmul_backward_fits(nbR, r_out, r_in, nbL, l_out, l_in))
+        return fail(MONARCH_ESHAPE, "row widths %lld/%lld/%lld exceed the on-chip tile",
+                    (long long)d_in, (long long)d_mid, (long long)d_out);
+    if (!dx && !dR && !dL) return MONARCH_OK;
+    const size_t es = dtype_size(dt);
+    const size_t nR = (size_t)nbR * r_out * r_in, nL = (size_t)nbL * l_out * l_in;
+    if ((dR || dL) && (!R || !L)) return fail(MONARCH_EINVAL, "R and L must be non-NULL");
+    if (misaligned(x) || misaligned(R) || misaligned(L) || misaligned(dy) || misaligned(dx) || misaligned(dR) || misaligned(dL))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    if (batch > 0) {
+        if (!x || !R || !L || !dy) return fail(MONARCH_EINVAL, "x, R, L and dy must be non-NULL");
+        const void *ins[4] = {x, dy, R, L};
+        const size_t in_bytes[4] = {(size_t)batch * d_in * es, (size_t)batch * d_out * es, nR * es, nL * es};
+        const void *outs[3] = {dx, dR, dL};
+        const size_t out_bytes[3] = {(size_t)batch * d_in * es, nR * sizeof(float), nL * sizeof(float)};
+        for (int o = 0; o < 3; ++o) {
+            if (!outs[o]) continue;
+            for (int i = 0; i < 4; ++i)
+                if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return fail(MONARCH_EINVAL, "an output overlaps an input");
+            for (int q = o + 1; q < 3; ++q)
+                if (outs[q] && overlaps(outs[o], out_bytes[o], outs[q], out_bytes[q])) return fail(MONARCH_EINVAL, "outputs overlap");
+        }
+    }
+    // (batch == 0: the parameter gradients are zero; the launcher clears them and runs no tile)
+    return launch_matmul_backward(x, R, L, dy, dx, dR, dL, batch, nbR, r_out, r_in, nbL, l_out, l_in, dt,
+                                  (hipStream_t)stream);
+}
+
 // ---------------------------------------------------------------------------------------------
 // monarch_fft / monarch_ifft
 // ---------------------------------------------------------------------------------------------

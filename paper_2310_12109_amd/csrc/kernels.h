@@ -81,6 +81,11 @@ struct Fft2Args {
     int load, store, inverse;
     int tw_outer;        // inverse of a three-factor transform: times omega_N^(o (f2 j + col)) after the chunk, o = chunk index
 };
+// gradients of the order-2 product (csrc/matmul_backward.hip); any of dx, dR, dL may be null
+bool matmul_backward_fits(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in);
+int launch_matmul_backward(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR,
+                           float *dL, int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
+                           monarch_dtype dt, hipStream_t s);
 bool fft2_lds_supported(int f1, int f2, monarch_dtype dt);
 int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
 

@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 c1b c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -63,6 +63,19 @@ def matmul_c1(batch, reps):
         return lambda: binding.monarch_matmul(x, R, L, out=y)
     calls = _sets(make, nbytes)
     _report(f"c1 matmul fp32 16x16 blocks, batch {batch}", _time(calls, reps), nbytes, batch * 4 * 256 * 16, len(calls))
+
+
+def matmul_backward_c1(batch, reps):
+    """Gradients of the config-1 product: reads x and dy, writes dx (3 KB per vector); dR, dL are 32 KB."""
+    nbytes = 3 * batch * 256 * 4 + 4 * 16 * 256 * 4
+    R, L = _rnd(16, 16, 16, dt=torch.float32, scale=.25), _rnd(16, 16, 16, dt=torch.float32, scale=.25)
+
+    def make():
+        x, dy = _rnd(batch, 256, dt=torch.float32), _rnd(batch, 256, dt=torch.float32)
+        return lambda: binding.monarch_matmul_backward(x, R, L, dy)
+    calls = _sets(make, nbytes)
+    # 5 block-diagonal products of 2 * 256 * 16 FLOP per vector (t1, g2, g0, dR, dL)
+    _report(f"c1 matmul backward fp32, batch {batch}", _time(calls, reps), nbytes, batch * 5 * 2 * 256 * 16, len(calls))
 
 
 def conv(name, B, H, n, factors, dt, reps):
@@ -136,6 +149,9 @@ def main():
     if want("c1"):
         matmul_c1(64, 200)
         matmul_c1(1 << 20, 10)
+    if want("c1b"):
+        matmul_backward_c1(64, 100)
+        matmul_backward_c1(1 << 18, 5)
     if want("c2"):
         conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
         conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)

@@ -73,6 +73,24 @@ def test_matmul_rejects_bad_arguments(lib):
     assert lib.monarch_strerror(ESHAPE) and lib.monarch_last_error()
 
 
+def test_matmul_backward_rejects_bad_arguments(lib):
+    f = lib.monarch_matmul_backward
+    f.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int64] + [ctypes.c_int] * 7 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    A, B, C, D, E, F, G = (FAKE * m for m in (1, 16, 32, 48, 64, 80, 96))   # 64 KB apart: no overlap at batch 4
+    sq = (16, 16, 16, 16, 16, 16)
+    assert f(None, B, C, D, E, F, G, 4, *sq, 0, None, 0, None) == EINVAL            # x missing
+    assert f(A, B, C, None, E, F, G, 4, *sq, 0, None, 0, None) == EINVAL            # dy missing
+    assert f(A, B, C, D, E, F, G, 4, 16, 16, 16, 8, 16, 16, 0, None, 0, None) == ESHAPE   # d_mid mismatch
+    assert f(A, B, C, D, E, F, G, 4, *sq, 2, None, 0, None) == EDTYPE
+    assert f(A, B, C, D, E, F, G, -1, *sq, 0, None, 0, None) == ESHAPE
+    assert f(A + 4, B, C, D, E, F, G, 4, *sq, 0, None, 0, None) == EINVAL           # misaligned
+    assert f(A, B, C, D, A, F, G, 4, *sq, 0, None, 0, None) == EINVAL               # dx aliases x
+    assert f(A, B, C, D, E, B, G, 4, *sq, 0, None, 0, None) == EINVAL               # dR aliases R
+    assert f(A, B, C, D, E, F, F, 4, *sq, 0, None, 0, None) == EINVAL               # dR aliases dL
+    assert f(A, B, C, D, None, None, None, 4, *sq, 0, None, 0, None) == 0           # nothing asked for
+    assert f(A, B, C, D, E, F, G, 4, 256, 256, 256, 256, 256, 256, 0, None, 0, None) == ESHAPE   # too wide
+
+
 def test_fft_rejects_bad_arguments(lib):
     fac = (ctypes.c_int * 3)(64, 32, 1)
     bad = (ctypes.c_int * 2)(64, 31)

@@ -1,0 +1,95 @@
+"""GPU parity: monarch_matmul_backward (gradients of the order-2 Monarch product, Sec. 3.1) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL_BF16, TOL_F32, announce, dev, host, rel_l2
+from paper_2310_12109_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2310_12109_amd import binding
+    return binding
+
+
+def _dy(batch, d_out, seed, bf16=False):
+    dy = np.random.default_rng(seed).standard_normal((batch, d_out)).astype(np.float32)
+    return workloads.round_to_bf16(dy) if bf16 else dy
+
+
+def _check(mm, w, dy, tol, bf16=False):
+    dx, dR, dL = mm.monarch_matmul_backward(dev(w["x"], bf16), dev(w["R"], bf16), dev(w["L"], bf16), dev(dy, bf16))
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    assert dR.dtype == torch.float32 and dL.dtype == torch.float32
+    assert rel_l2(host(dx), wdx) <= tol
+    assert rel_l2(host(dR), wdR) <= tol
+    assert rel_l2(host(dL), wdL) <= tol
+
+
+@pytest.mark.parametrize("batch", [64, 67, 1, 1000, 5000])
+def test_config1_square_fp32(mm, batch):
+    # several tiles, a ragged last tile, more tiles than workgroups (batch 5000)
+    announce("matmul backward c1 fp32 batch", batch)
+    w = workloads.monarch_matmul_inputs(batch=batch, b=16, seed=0)
+    _check(mm, w, _dy(batch, 256, batch), TOL_F32)
+
+
+@pytest.mark.parametrize("b", [2, 8, 32, 64])
+def test_square_other_block_sizes(mm, b):
+    announce("matmul backward square b", b)
+    w = workloads.monarch_matmul_inputs(batch=19, b=b, seed=b)
+    _check(mm, w, _dy(19, b * b, b), TOL_F32)
+
+
+@pytest.mark.parametrize("shape", [(4, 3, 2, 2, 5, 6), (4, 192, 192, 4, 768, 192), (16, 64, 64, 16, 256, 64), (3, 7, 5, 7, 2, 3)])
+def test_rectangular_fp32(mm, shape):
+    announce("matmul backward rect", shape)
+    nbR, r_out, r_in, nbL, l_out, l_in = shape
+    w = workloads.monarch_matmul_rect_inputs(37, *shape, seed=11)
+    _check(mm, w, _dy(37, nbL * l_out, 12), TOL_F32)
+
+
+def test_bf16_inputs(mm):
+    announce("matmul backward bf16")
+    w = workloads.monarch_matmul_inputs(batch=130, b=16, seed=3, bf16=True)
+    _check(mm, w, _dy(130, 256, 4, bf16=True), TOL_BF16, bf16=True)
+
+
+def test_outputs_can_be_skipped_and_are_overwritten(mm):
+    announce("matmul backward partial outputs")
+    w = workloads.monarch_matmul_inputs(batch=40, b=16, seed=5)
+    dy = _dy(40, 256, 6)
+    x, R, L, g = dev(w["x"]), dev(w["R"]), dev(w["L"]), dev(dy)
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dR=False, need_dL=False)
+    assert dR is None and dL is None and rel_l2(host(dx), wdx) <= TOL_F32
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dx=False)
+    assert dx is None and rel_l2(host(dR), wdR) <= TOL_F32 and rel_l2(host(dL), wdL) <= TOL_F32
+    # a second call into the same (non-zero) buffers gives the same result: overwritten, not accumulated
+    again = mm.monarch_matmul_backward(x, R, L, g, need_dx=False)
+    assert rel_l2(host(again[1]), wdR) <= TOL_F32
+
+
+def test_identity_blocks_give_the_transposed_permutation_exactly(mm):
+    announce("matmul backward identity")
+    b = 16
+    eye = np.broadcast_to(np.eye(b, dtype=np.float32), (b, b, b)).copy()
+    x = np.random.default_rng(7).standard_normal((33, b * b)).astype(np.float32)
+    dy = _dy(33, b * b, 8)
+    dx, _, _ = mm.monarch_matmul_backward(dev(x), dev(eye), dev(eye), dev(dy), need_dR=False, need_dL=False)
+    s = oracle.perm(b, b * b)
+    want = np.zeros_like(dy)
+    want[:, s] = dy
+    assert np.array_equal(host(dx), want.astype(np.float64))
+
+
+def test_empty_batch_gives_zero_parameter_gradients(mm):
+    announce("matmul backward empty")
+    w = workloads.monarch_matmul_inputs(batch=1, b=16, seed=0)
+    x = torch.empty((0, 256), device="cuda")
+    dx, dR, dL = mm.monarch_matmul_backward(x, dev(w["R"]), dev(w["L"]), torch.empty((0, 256), device="cuda"))
+    assert dx.shape == (0, 256) and float(dR.abs().max()) == 0.0 and float(dL.abs().max()) == 0.0
