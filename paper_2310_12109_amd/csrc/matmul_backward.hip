@@ -9,6 +9,7 @@
 // thread's share of the entries is at most EPT, else added to memory after every tile) and leave with one
 // floating-point atomic add per entry.  The caller's dR / dL are cleared by a fill kernel first.
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace monarch {
 
@@ -197,6 +198,183 @@ static int launch_typed(const void *x, const void *R, const void *L, const void 
 
 }  // namespace mmb
 
+// ---- square case b = 16 (N = 256), fp32, on the matrix cores -------------------------------------------
+// With x[v][16 c + a] and dy[v][16 k + i] (Sec. 3.1; blocks R_a, L_i of 16 x 16):
+//   T_a[i, v]  = sum_c R_a[i, c] x[v][16 c + a]          first factor, recomputed
+//   G_i[a, v]  = sum_k L_i[k, a] dy[v][16 k + i]         gradient of T_a[i, v]
+//   dL_i[k, a] = sum_v dy[v][16 k + i] T_a[i, v]
+//   dR_a[i, c] = sum_v G_i[a, v] x[v][16 c + a]
+//   dx[v][16 c + a] = sum_i R_a[i, c] G_i[a, v]
+// all of them 16x16x4 fp32 MFMAs.  A workgroup (4 waves) takes one tile of 16 vectors at a time; wave w owns the
+// blocks 4 w .. 4 w + 3 of every product, so its share of the weights (and of dR, dL, accumulated over all the
+// workgroup's tiles) stays in registers.  The rows of x and dy come in by direct-to-LDS loads (one vector,
+// 1 KB, per wave instruction); T and G cross between the waves through two LDS tiles whose index maps are the
+// middle permutation; dx leaves through LDS as whole rows.  Products over the vectors of a tile need their
+// operands transposed (a lane per feature, vectors on the contraction index): those are the reads of the x /
+// dy rows at [vector][feature] and of the T / G tiles along their other index.
+namespace mmb16 {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int B = 16, N = 256, TV = 16;
+constexpr int LDX = N + 4;                 // row pitch of the x / dy tiles: 16-byte aligned, one 16-byte slot off
+constexpr int RS = 18, LD = B * RS + 3;    // T / G tiles: element (v, p, q) at v LD + p RS + q
+constexpr size_t LDS_BYTES = sizeof(float) * (2 * TV * LDX + 2 * TV * LD);
+
+__device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
+    const float *__restrict__ x, const float *__restrict__ R, const float *__restrict__ L,
+    const float *__restrict__ dy, float *__restrict__ dx, float *__restrict__ dR, float *__restrict__ dL,
+    int64_t batch)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float *xs = smem;                      // [TV][LDX]
+    float *gs = xs + TV * LDX;             // [TV][LDX]  dy rows, later the dx rows
+    float *tt = gs + TV * LDX;             // T: (v, i, a)
+    float *gt = tt + TV * LD;              // G: (v, a, i)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
+    const int b0 = 4 * wave;   // this wave's blocks
+
+    // k-step s of an MFMA contracts the index 4 kg + s
+    float Rw[4][4], Rt[4][4], Lt[4][4];   // [block - b0][s]: R_a[l16][4kg+s], R_a[4kg+s][l16], L_i[4kg+s][l16]
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            Rw[q][s] = R[((b0 + q) * B + l16) * B + 4 * kg + s];
+            Rt[q][s] = R[((b0 + q) * B + 4 * kg + s) * B + l16];
+            Lt[q][s] = L[((b0 + q) * B + 4 * kg + s) * B + l16];
+        }
+    f32x4 accL[4], accR[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) accL[q] = accR[q] = f32x4{0, 0, 0, 0};
+
+    const int64_t ntiles = (batch + TV - 1) / TV;
+    const uint32_t xs_addr = lds_address(xs), gs_addr = lds_address(gs);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t v0 = tile * TV;
+        // rows in: wave w fetches vectors 4 w .. 4 w + 3 of x and of dy (rows past the batch: the last one)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int64_t v = v0 + b0 + q;
+            if (v >= batch) v = batch - 1;
+            dma_16_at(x + v * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            dma_16_at(dy + v * N + 4 * lane, gs_addr + (uint32_t)(b0 + q) * LDX * 4);
+        }
+        wait_loads_at_most<0>();
+        if (v0 + TV > batch) {   // ragged tile: the missing vectors must not reach dR, dL
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < TV * N; idx += 256) {
+                const int v = idx / N;
+                if (v0 + v >= batch) gs[v * LDX + (idx - v * N)] = 0.0f;
+            }
+        }
+        __syncthreads();
+
+        // T_a (blocks a of this wave) and G_i (blocks i of this wave); the lane is vector v = l16
+        {
+            f32x4 xq[4], gq[4];   // [s]: features 16 (4 kg + s) + b0 .. + 3
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                xq[s] = *reinterpret_cast<const f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + s) + b0);
+                gq[s] = *reinterpret_cast<const f32x4 *>(gs + l16 * LDX + 16 * (4 * kg + s) + b0);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 t = {0, 0, 0, 0}, g = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    t = mfma(Rw[q][s], xq[s][q], t);   // rows i = 4 kg + r
+                    g = mfma(Lt[q][s], gq[s][q], g);   // rows a = 4 kg + r
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    tt[l16 * LD + (4 * kg + r) * RS + b0 + q] = t[r];   // (v, i, a = b0 + q)
+                    gt[l16 * LD + (4 * kg + r) * RS + b0 + q] = g[r];   // (v, a, i = b0 + q)
+                }
+            }
+        }
+        __syncthreads();
+
+        // dL_i += dy_i T_i^T and dR_a += G_a x_a^T over the 16 vectors: k-step s contracts v = 4 kg + s
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int v = 4 * kg + s;
+            const f32x4 ga = *reinterpret_cast<const f32x4 *>(gs + v * LDX + 16 * l16 + b0);   // dy[v][16 k + i], k = l16
+            const f32x4 xb = *reinterpret_cast<const f32x4 *>(xs + v * LDX + 16 * l16 + b0);   // x[v][16 c + a], c = l16
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                accL[q] = mfma(ga[q], tt[v * LD + (b0 + q) * RS + l16], accL[q]);   // B: T_a[i][v], a = l16
+                accR[q] = mfma(gt[v * LD + (b0 + q) * RS + l16], xb[q], accR[q]);   // A: G_i[a][v], i = l16
+            }
+        }
+        // dx_a[c, v] = sum_i R_a[i, c] G_i[a, v]: rows c = 4 kg + r, column v = l16
+        f32x4 dxa[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc = mfma(Rt[q][s], gt[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
+            dxa[q] = acc;
+        }
+        __syncthreads();   // every wave is done with the dy rows: they become the dx rows
+        if (dx) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                *reinterpret_cast<f32x4 *>(gs + l16 * LDX + 16 * (4 * kg + r) + b0) = f32x4{dxa[0][r], dxa[1][r], dxa[2][r], dxa[3][r]};
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t v = v0 + b0 + q;
+                if (v < batch) *reinterpret_cast<f32x4 *>(dx + v * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(gs + (b0 + q) * LDX + 4 * lane);
+            }
+            __syncthreads();   // before the next tile's rows land
+        }
+    }
+    // accL[q][r] = dL_i[k = 4 kg + r][a = l16], accR[q][r] = dR_a[i = 4 kg + r][c = l16]
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (dL) atomicAdd(dL + ((b0 + q) * B + 4 * kg + r) * B + l16, accL[q][r]);
+            if (dR) atomicAdd(dR + ((b0 + q) * B + 4 * kg + r) * B + l16, accR[q][r]);
+        }
+}
+
+}  // namespace mmb16
+
+bool matmul_backward_b16_supported(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in, monarch_dtype dt)
+{
+    return dt == MONARCH_F32 && nbR == 16 && r_out == 16 && r_in == 16 && nbL == 16 && l_out == 16 && l_in == 16;
+}
+
+static int launch_matmul_backward_b16(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR,
+                                      float *dL, int64_t batch, hipStream_t s)
+{
+    if (dR || dL) {
+        hipLaunchKernelGGL(mmb::fill_zero_kernel, dim3(16), dim3(256), 0, s, dR, dR ? (size_t)4096 : 0, dL, dL ? (size_t)4096 : 0);
+        MONARCH_HIP_CHECK(hipGetLastError());
+    }
+    const int64_t ntiles = (batch + mmb16::TV - 1) / mmb16::TV;
+    if (ntiles == 0) return MONARCH_OK;
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    int64_t grid = 2 * (int64_t)ncu;   // two workgroups (69 KB of LDS each) per compute unit
+    if (grid > ntiles) grid = ntiles;
+    MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mmb16::matmul_backward_b16_kernel,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)mmb16::LDS_BYTES));
+    hipLaunchKernelGGL(mmb16::matmul_backward_b16_kernel, dim3((unsigned)grid), dim3(256), mmb16::LDS_BYTES, s,
+                       (const float *)x, (const float *)R, (const float *)L, (const float *)dy, (float *)dx, dR, dL, batch);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
 bool matmul_backward_fits(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in)
 {
     const mmb::Dims d = {nbR, r_out, r_in, nbL, l_out, l_in};
@@ -207,6 +385,8 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
                            float *dL, int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
                            monarch_dtype dt, hipStream_t s)
 {
+    if (matmul_backward_b16_supported(nbR, r_out, r_in, nbL, l_out, l_in, dt))
+        return launch_matmul_backward_b16(x, R, L, dy, dx, dR, dL, batch, s);
     const mmb::Dims d = {nbR, r_out, r_in, nbL, l_out, l_in};
     if (dt == MONARCH_F32) return mmb::launch_typed<float>(x, R, L, dy, dx, dR, dL, batch, d, s);
     return mmb::launch_typed<bf16_t>(x, R, L, dy, dx, dR, dL, batch, d, s);

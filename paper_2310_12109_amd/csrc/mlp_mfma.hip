@@ -14,6 +14,7 @@
 // slower), then written with coalesced 16-byte stores.
 #include <type_traits>
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace monarch {
 
@@ -387,30 +388,6 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
 // the 64 lanes of a wave fill one 1 KB operand piece) and are read from there by all four waves: a quarter
 // of the L2 traffic of mlp_order1_kernel, and requests RING - 1 chunks ahead of their use without holding
 // registers.  One barrier per chunk: it publishes chunk j and frees the slot chunk j - 1 was read from.
-typedef __attribute__((address_space(1))) const void *gptr_t;
-typedef __attribute__((address_space(3))) void *lptr_t;
-
-// Direct-to-LDS load: each lane's 16 bytes at src go to lds_piece + 16 * lane (lds_piece wave-uniform).  Written
-// as assembly so that the compiler does not put its own wait-for-everything in front of every later LDS read:
-// the kernel below waits for these loads by count and publishes them with a barrier itself.
-__device__ __forceinline__ void dma_16(const void *src, void *lds_piece)
-{
-    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lptr_t)lds_piece);
-    uint32_t saved_m0;   // M0 carries the LDS address of the load; whatever the compiler keeps there is put back
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0)
-                 : "s"(dst), "v"(src)
-                 : "memory");
-}
-
-// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt and lgkmcnt left at their maxima)
-template <int N>
-__device__ __forceinline__ void wait_vm_at_most()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
 // slots of the weight ring: as many chunks of 4 KS KB as fit in 148 KB, at most 8
 constexpr int ring_slots(int ks) { return 148 / (4 * ks) < 8 ? 148 / (4 * ks) : 8; }
 
@@ -583,29 +560,6 @@ __device__ long long g_mlp_clk[4][64];
 #else
 #define MLP_MARK(i)
 #endif
-
-// Two direct-to-LDS loads into consecutive 1 KB pieces with one save / restore of M0.  The LDS address is
-// passed as a number (wave-uniform, in a scalar register).
-__device__ __forceinline__ uint32_t lds_address(const void *p) { return (uint32_t)(size_t)(lptr_t)p; }
-__device__ __forceinline__ void dma_16_pair(const void *src0, const void *src1, uint32_t lds_first)
-{
-    uint32_t saved_m0;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\t"
-                 "s_add_u32 m0, m0, 0x400\n\tglobal_load_lds_dwordx4 %3, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0)
-                 : "s"(lds_first), "v"(src0), "v"(src1)
-                 : "memory", "scc");
-}
-template <int N>
-__device__ __forceinline__ void wait_loads_at_most()   // also a compiler barrier: no LDS read moves above it
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void wait_lds_reads()   // every LDS read issued so far has returned
-{
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-}
 
 constexpr size_t split_lds_bytes(int ks, int dh) { return (size_t)24 * ks * 1024 + (size_t)dh * 2; }
 

@@ -151,7 +151,7 @@ def main():
         matmul_c1(1 << 20, 10)
     if want("c1b"):
         matmul_backward_c1(64, 100)
-        matmul_backward_c1(1 << 18, 5)
+        matmul_backward_c1(1 << 20, 5)
     if want("c2"):
         conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
         conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)
