@@ -193,8 +193,8 @@ int monarch_matmul_backward(const void *x, const void *R, const void *L, const v
 
 size_t monarch_fft_workspace_bytes(int64_t rows, int N, const int *factors, int nf, monarch_dtype dt)
 {
-    (void)factors; (void)dt;
     if (rows <= 0 || N <= 0) return 0;
+    if (nf == 2 && factors && fft2_lds_supported(factors[0], factors[1], dt)) return 0;   // one kernel, rows stay on chip
     const size_t buf = align_up((size_t)rows * N * sizeof(float2), 256);
     return nf >= 3 ? 2 * buf : buf;
 }

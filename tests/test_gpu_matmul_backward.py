@@ -38,6 +38,15 @@ def test_config1_square_fp32(mm, batch):
     _check(mm, w, _dy(batch, 256, batch), TOL_F32)
 
 
+def test_config1_more_tiles_than_workgroups(mm):
+    # 1251 tiles of 16 vectors on at most 512 workgroups: every workgroup walks over several tiles and keeps its
+    # share of dR, dL in registers across them; the last tile is ragged
+    batch = 20011
+    announce("matmul backward c1 fp32 batch", batch)
+    w = workloads.monarch_matmul_inputs(batch=batch, b=16, seed=1)
+    _check(mm, w, _dy(batch, 256, 2), TOL_F32)
+
+
 @pytest.mark.parametrize("b", [2, 8, 32, 64])
 def test_square_other_block_sizes(mm, b):
     announce("matmul backward square b", b)
