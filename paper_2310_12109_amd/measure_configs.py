@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 c1b c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -63,6 +63,19 @@ def matmul_c1(batch, reps):
         return lambda: binding.monarch_matmul(x, R, L, out=y)
     calls = _sets(make, nbytes)
     _report(f"c1 matmul fp32 16x16 blocks, batch {batch}", _time(calls, reps), nbytes, batch * 4 * 256 * 16, len(calls))
+
+
+def plain_copy(mbytes, reps):
+    """A device-to-device copy of `mbytes` MB (read + written: twice that) with torch's copy kernel: what this
+    machine's memory system gives a kernel with no arithmetic, as a yardstick beside the 8 TB/s of the data sheet."""
+    n = int(mbytes * 1e6) // 16 * 16
+
+    def make():
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty(n, dtype=torch.uint8, device="cuda")
+        return lambda: b.copy_(a)
+    calls = _sets(make, 2 * n)
+    _report(f"plain copy, {2 * n / 1e6:.0f} MB moved", _time(calls, reps), 2 * n, 0, len(calls))
 
 
 def matmul_backward_c1(batch, reps):
@@ -149,6 +162,9 @@ def main():
     if want("c1"):
         matmul_c1(64, 200)
         matmul_c1(1 << 20, 10)
+    if want("copy"):
+        for mb in (12.6, 25.2, 50.4, 201, 805):
+            plain_copy(mb, 100 if mb < 100 else 20)
     if want("c1b"):
         matmul_backward_c1(64, 100)
         matmul_backward_c1(1 << 20, 5)
