@@ -35,3 +35,27 @@ def test_graph_replays_match_eager():
         torch.cuda.synchronize()
         assert torch.equal(out, want), f"replay {rep} differs from the eager result"
         assert other.shape == want.shape
+
+
+def test_graph_replays_of_the_matmul_gradients_match_eager():
+    # dR / dL are cleared by a fill kernel inside the call (no memset node) and summed with atomics: every replay
+    # must start from zero again and agree with the eager result to rounding
+    from paper_2310_12109_amd import binding
+    announce("matmul backward graph replay")
+    w = workloads.monarch_matmul_inputs(batch=3000, b=16, seed=4)
+    x, R, L = dev(w["x"]), dev(w["R"]), dev(w["L"])
+    dy = dev(np.random.default_rng(5).standard_normal((3000, 256)).astype(np.float32))
+    _, wantR, wantL = binding.monarch_matmul_backward(x, R, L, dy, need_dx=False)
+    torch.cuda.synchronize()
+    outs = {}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        outs["dx"], outs["dR"], outs["dL"] = binding.monarch_matmul_backward(x, R, L, dy)
+    for rep in range(3):
+        binding.monarch_matmul(x, R, L)   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in ((outs["dR"], wantR), (outs["dL"], wantL)):
+            err = float((got - want).norm() / want.norm())
+            assert err <= 1e-5, f"replay {rep}: {err}"
