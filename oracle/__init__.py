@@ -109,6 +109,24 @@ def matmul_backward(x, R, L, dy):
     return dx, dR, dL
 
 
+def mixer(u, K, g_in, g_out, R1, L1, R2, L2):
+    """y = g_out o M2 (K[h] o M1 (g_in o u)) with two general square order-2 Monarch matrices (Sec. 3.2 Eq. 2).
+    u, gates: (B, H, N); K: (H, N); factors (b, b, b), N = b*b."""
+    u, K = _f64(u), _f64(K)
+    B, H, N = u.shape
+    b = R1.shape[0]
+    assert N == b * b and K.shape == (H, N)
+    R1, L1, R2, L2 = _f64(R1), _f64(L1), _f64(R2), _f64(L2)
+    gi = _f64(g_in) if g_in is not None else None
+    go = _f64(g_out) if g_out is not None else None
+    y = np.empty_like(u)
+    rc = lib().oracle_mixer(_p(u), _p(K), _p(gi) if gi is not None else None, _p(go) if go is not None else None,
+                            _p(R1), _p(L1), _p(R2), _p(L2), _p(y), ctypes.c_int64(B * H), ctypes.c_int(H), ctypes.c_int(b))
+    if rc != 0:
+        raise ValueError("inconsistent mixer shapes")
+    return y
+
+
 def dft(x):
     """X[r,m] = sum_j x[r,j] omega_N^(m j), omega_N = exp(+2 pi i / N); O(N^2) per row."""
     x = _c128(x)

@@ -301,6 +301,51 @@ int oracle_matmul_backward(const double *x, const double *R, const double *L, co
     return 0;
 }
 
+/*
+ * Sequence mixer with two general (learned) order-2 Monarch matrices, Sec. 3.2 Eq. 2 and its gated form:
+ *   y[b,h,:] = g_out[b,h,:] o ( M2 ( K[h,:] o ( M1 ( g_in[b,h,:] o u[b,h,:] ) ) ) ),   o = elementwise product,
+ * M1 = P L1 P R1 P and M2 = P L2 P R2 P square of size N = nb*nb... in general M1: d_in -> d_mid1 given by
+ * its factor shapes; here both are N x N with blocks [bs][bs][bs], N = bs*bs, shared by all channels; K is
+ * the kernel in the transform domain, one row per channel.  With M1 the DFT and M2 its inverse this is the
+ * convolution; here the matrices are arbitrary.  u, g_in, g_out, y: rows x N with row = b*H + h; K: H x N.
+ * g_in / g_out may be NULL (= 1).  Both matrices are materialised densely.
+ */
+int oracle_mixer(const double *u, const double *K, const double *g_in, const double *g_out,
+                 const double *R1, const double *L1, const double *R2, const double *L2,
+                 double *y, int64_t rows, int H, int bs)
+{
+    if (bs <= 0 || H <= 0) return -1;
+    int N = bs * bs;
+    double *M1 = (double *)malloc(sizeof(double) * (size_t)N * N);
+    double *M2 = (double *)malloc(sizeof(double) * (size_t)N * N);
+    int rc = oracle_monarch_dense(R1, L1, bs, bs, bs, bs, bs, bs, M1);
+    if (rc == 0) rc = oracle_monarch_dense(R2, L2, bs, bs, bs, bs, bs, bs, M2);
+    if (rc != 0) { free(M1); free(M2); return rc; }
+#pragma omp parallel
+    {
+        double *a = (double *)malloc(sizeof(double) * (size_t)N);
+        double *t = (double *)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(static)
+        for (int64_t r = 0; r < rows; ++r) {
+            const int h = (int)(r % H);
+            for (int j = 0; j < N; ++j) a[j] = u[(size_t)r * N + j] * (g_in ? g_in[(size_t)r * N + j] : 1.0);
+            for (int i = 0; i < N; ++i) {
+                double s = 0.0;
+                for (int j = 0; j < N; ++j) s += M1[(size_t)i * N + j] * a[j];
+                t[i] = s * K[(size_t)h * N + i];
+            }
+            for (int i = 0; i < N; ++i) {
+                double s = 0.0;
+                for (int j = 0; j < N; ++j) s += M2[(size_t)i * N + j] * t[j];
+                y[(size_t)r * N + i] = s * (g_out ? g_out[(size_t)r * N + i] : 1.0);
+            }
+        }
+        free(a); free(t);
+    }
+    free(M1); free(M2);
+    return 0;
+}
+
 /* ------------------------------------------------------------------------- */
 /* DFT by its definition (Appendix: F_N[m,j] = omega_N^(m j))                */
 /* ------------------------------------------------------------------------- */
