@@ -98,6 +98,24 @@ size_t monarch_matmul_backward_workspace_bytes(int64_t batch, int nbR, int r_out
                                                int nbL, int l_out, int l_in, monarch_dtype dt);
 
 /*
+ * Sequence mixer with two general (learned) square order-2 Monarch matrices (Sec. 3.2, Eq. 2, in its gated
+ * form): for every sequence b in [0, B) and channel h in [0, H)
+ *   y[b,h,:] = g_out[b,h,:] o ( M2 ( K[h,:] o ( M1 ( g_in[b,h,:] o u[b,h,:] ) ) ) ),
+ * M1 = P L1 P R1 P and M2 = P L2 P R2 P as in monarch_matmul with all six sizes equal to bs, N = bs^2,
+ * both shared by all channels; o is the elementwise product.  With M1 the DFT and M2 its inverse this is the
+ * convolution of monarch_causal_conv; here the matrices are arbitrary real ones and K lives in M1's range.
+ * u, g_in, g_out, y: (B, H, N); K: (H, N); R1, L1, R2, L2: [bs][bs][bs]; all device memory of type dt, the
+ * arithmetic is float32.  g_in and / or g_out may be NULL (no gate).  Nothing is written outside y; a row
+ * stays on chip from its load to its store.
+ * Errors: EINVAL (a null required pointer with B * H > 0, misalignment, y overlapping an input), ESHAPE
+ * (B < 0, H < 1, bs < 1, 2 * bs^2 * 4 bytes beyond 160 KB), EDTYPE, EHIP.
+ */
+int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_out,
+                  const void *R1, const void *L1, const void *R2, const void *L2, void *y,
+                  int64_t B, int H, int bs, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_mixer_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt);
+
+/*
  * Monarch-factored DFT (appendix, DFT corollary; order 3 per the p-variate
  * section):  X[r,:] = F_N x[r,:],  F_N[m,j] = omega_N^(m j), unnormalised,
  * natural output order.  N = factors[0]*...*factors[nf-1], nf in {2,3}; the

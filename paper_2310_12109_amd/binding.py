@@ -35,6 +35,9 @@ _lib.monarch_matmul_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i
 _lib.monarch_matmul_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_matmul_backward_workspace_bytes.restype = _sz
 _lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
+_lib.monarch_mixer.argtypes = [_vp] * 9 + [_i64, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_mixer_workspace_bytes.restype = _sz
+_lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
 _lib.monarch_fft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_ifft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_fft_workspace_bytes.restype = _sz
@@ -50,6 +53,7 @@ EXPORTS = [
     "monarch_strerror", "monarch_last_error", "monarch_permutation_index",
     "monarch_matmul", "monarch_matmul_workspace_bytes",
     "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
+    "monarch_mixer", "monarch_mixer_workspace_bytes",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
     "monarch_mlp", "monarch_mlp_workspace_bytes",
@@ -137,6 +141,16 @@ def monarch_matmul_backward(x, R, L, dy, need_dx=True, need_dR=True, need_dL=Tru
     _check(_lib.monarch_matmul_backward(_ptr(x), _ptr(R), _ptr(L), _ptr(dy), _ptr(dx), _ptr(dR), _ptr(dL), batch,
                                         nbR, r_out, r_in, nbL, l_out, l_in, _dt(x), None, 0, _stream()))
     return dx, dR, dL
+
+
+def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):
+    """y = g_out * M2(K[h] * M1(g_in * u)) with M = P L P R P square; u, gates, y: (B, H, N); K: (H, N)."""
+    B, H, N = u.shape
+    bs = R1.shape[0]
+    y = out if out is not None else torch.empty_like(u)
+    _check(_lib.monarch_mixer(_ptr(u), _ptr(K), _ptr(g_in), _ptr(g_out), _ptr(R1), _ptr(L1), _ptr(R2), _ptr(L2), _ptr(y),
+                              B, H, bs, _dt(u), None, 0, _stream()))
+    return y
 
 
 def monarch_fft_workspace_bytes(rows, N, factors, dt=F32):

@@ -188,6 +188,37 @@ int monarch_matmul_backward(const void *x, const void *R, const void *L, const v
 }
 
 // ---------------------------------------------------------------------------------------------
+// monarch_mixer
+// ---------------------------------------------------------------------------------------------
+
+size_t monarch_mixer_workspace_bytes(int64_t, int, int, monarch_dtype) { return 0; }
+
+int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_out,
+                  const void *R1, const void *L1, const void *R2, const void *L2, void *y,
+                  int64_t B, int H, int bs, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    (void)ws; (void)ws_bytes;
+    clear_error();
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (B < 0 || H < 1) return fail(MONARCH_ESHAPE, "B must be >= 0 and H >= 1");
+    if (bs < 1 || !mixer_fits(bs)) return fail(MONARCH_ESHAPE, "block size %d: a row of bs^2 elements must fit in LDS twice", bs);
+    if (B > INT64_MAX / H) return fail(MONARCH_ESHAPE, "B * H overflows");
+    const int64_t rows = B * H, N = (int64_t)bs * bs;
+    if (rows == 0) return MONARCH_OK;
+    if (!u || !K || !R1 || !L1 || !R2 || !L2 || !y) return fail(MONARCH_EINVAL, "u, K, R1, L1, R2, L2 and y must be non-NULL");
+    if (misaligned(u) || misaligned(K) || misaligned(g_in) || misaligned(g_out) || misaligned(R1) || misaligned(L1) ||
+        misaligned(R2) || misaligned(L2) || misaligned(y))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt), act = (size_t)rows * N * es, wb = (size_t)N * bs * es;
+    const void *ins[8] = {u, g_in, g_out, K, R1, L1, R2, L2};
+    const size_t in_bytes[8] = {act, act, act, (size_t)H * N * es, wb, wb, wb, wb};
+    for (int i = 0; i < 8; ++i)
+        if (ins[i] && overlaps(y, act, ins[i], in_bytes[i])) return fail(MONARCH_EINVAL, "y overlaps an input");
+    return launch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, dt, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
 // monarch_fft / monarch_ifft
 // ---------------------------------------------------------------------------------------------
 

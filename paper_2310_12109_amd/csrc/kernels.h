@@ -86,6 +86,10 @@ bool matmul_backward_fits(int nbR, int r_out, int r_in, int nbL, int l_out, int 
 int launch_matmul_backward(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR,
                            float *dL, int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
                            monarch_dtype dt, hipStream_t s);
+// sequence mixer with two general square order-2 Monarch matrices (csrc/mixer.hip); g_in, g_out may be null
+bool mixer_fits(int bs);
+int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
+                 const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
 bool fft2_lds_supported(int f1, int f2, monarch_dtype dt);
 int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
 

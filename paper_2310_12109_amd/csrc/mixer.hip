@@ -1,0 +1,305 @@
+// Sequence mixer with two general (learned) order-2 Monarch matrices, Sec. 3.2 Eq. 2 and its gated form:
+//   y[b,h,:] = g_out[b,h,:] o ( M2 ( K[h,:] o ( M1 ( g_in[b,h,:] o u[b,h,:] ) ) ) )
+// M1 = P L1 P R1 P, M2 = P L2 P R2 P (Sec. 3.1), square, N = bs^2, factors [bs][bs][bs] shared by all channels;
+// K is the kernel in the transform domain, one row per channel.  (With M1 the DFT and M2 its inverse this is
+// the convolution of monarch_causal_conv; here the matrices are arbitrary real ones.)  A row never leaves the
+// chip between its load and its store: both products, the kernel product and the gates are fused.
+#include "kernels.h"
+#include "lds_dma.h"
+
+namespace monarch {
+
+// ---- any block size: fp32 arithmetic on tiles of rows in LDS ------------------------------------------
+namespace mixg {
+
+constexpr int THREADS = 256;
+
+// One block-diagonal factor W [bs][bs][bs] on TV rows: block k reads in[v][k * ks_in + c * cs_in] and writes
+// out[v][r * rs_out + k * ks_out] (the stride pairs realise the permutations of M = P L P R P).
+template <typename T, int TV>
+__device__ __forceinline__ void factor(const float *in, float *out, int N, int bs, const T *W, int cs_in, int ks_in,
+                                       int rs_out, int ks_out)
+{
+    for (int o = threadIdx.x; o < N; o += THREADS) {   // o = k bs + r
+        const int k = o / bs, r = o - k * bs;
+        float acc[TV];
+#pragma unroll
+        for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
+        const T *w = W + (size_t)o * bs;
+        for (int c = 0; c < bs; ++c) {
+            const float wv = to_f32(w[c]);
+#pragma unroll
+            for (int v = 0; v < TV; ++v) acc[v] = fmaf(wv, in[v * N + k * ks_in + c * cs_in], acc[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < TV; ++v) out[v * N + r * rs_out + k * ks_out] = acc[v];
+    }
+}
+
+template <typename T, int TV>
+__global__ __launch_bounds__(THREADS) void mixer_kernel(const T *__restrict__ u, const T *__restrict__ K,
+                                                        const T *__restrict__ g_in, const T *__restrict__ g_out,
+                                                        const T *__restrict__ R1, const T *__restrict__ L1,
+                                                        const T *__restrict__ R2, const T *__restrict__ L2,
+                                                        T *__restrict__ y, int64_t rows, int H, int bs)
+{
+    extern __shared__ float lds[];
+    const int N = bs * bs;
+    float *a = lds, *t = lds + TV * N;
+    const int64_t ntiles = (rows + TV - 1) / TV;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t r0 = tile * TV;
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            float x = 0.0f;
+            if (r0 + v < rows) {
+                x = to_f32(u[(r0 + v) * N + j]);
+                if (g_in) x *= to_f32(g_in[(r0 + v) * N + j]);
+            }
+            a[idx] = x;
+        }
+        __syncthreads();
+        factor<T, TV>(a, t, N, bs, R1, bs, 1, bs, 1);   // block k reads a[c bs + k], writes t[r bs + k]
+        __syncthreads();
+        factor<T, TV>(t, a, N, bs, L1, 1, bs, bs, 1);   // block k reads t[k bs + a'], writes a[r bs + k]
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            if (r0 + v < rows) a[idx] *= to_f32(K[((r0 + v) % H) * (int64_t)N + j]);
+        }
+        __syncthreads();
+        factor<T, TV>(a, t, N, bs, R2, bs, 1, bs, 1);
+        __syncthreads();
+        factor<T, TV>(t, a, N, bs, L2, 1, bs, bs, 1);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            if (r0 + v < rows) {
+                float o = a[idx];
+                if (g_out) o *= to_f32(g_out[(r0 + v) * N + j]);
+                y[(r0 + v) * N + j] = from_f32<T>(o);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+static int launch_typed(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
+                        const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, hipStream_t s)
+{
+    const int N = bs * bs;
+    int tv = 8;
+    while (tv > 1 && (size_t)2 * tv * N * sizeof(float) > 64 * 1024) tv >>= 1;
+    const size_t lds = (size_t)2 * tv * N * sizeof(float);
+    if (lds > 160 * 1024) return fail(MONARCH_ESHAPE, "a row of %d elements does not fit in LDS twice", N);
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t ntiles = (rows + tv - 1) / tv;
+    int64_t grid = (int64_t)ncu * (lds <= 40 * 1024 ? 4 : lds <= 80 * 1024 ? 2 : 1);
+    if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_MIXG(TVV)                                                                                    \
+    do {                                                                                                            \
+        auto kern = mixer_kernel<T, TVV>;                                                                           \
+        if (lds > 64 * 1024)                                                                                        \
+            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+                                                  (int)lds));                                                       \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)u, (const T *)K,           \
+                           (const T *)g_in, (const T *)g_out, (const T *)R1, (const T *)L1, (const T *)R2,          \
+                           (const T *)L2, (T *)y, rows, H, bs);                                                     \
+    } while (0)
+    switch (tv) {
+    case 8: MONARCH_LAUNCH_MIXG(8); break;
+    case 4: MONARCH_LAUNCH_MIXG(4); break;
+    case 2: MONARCH_LAUNCH_MIXG(2); break;
+    default: MONARCH_LAUNCH_MIXG(1); break;
+    }
+#undef MONARCH_LAUNCH_MIXG
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+}  // namespace mixg
+
+// ---- bs = 16 (N = 256), fp32, on the matrix cores -------------------------------------------------------
+// Four block-diagonal products of 16x16x4 fp32 MFMAs per row, rows on the MFMA column index.  A workgroup (4
+// waves) takes a tile of 16 rows; wave w owns the blocks 4 w .. 4 w + 3 of every factor (64 registers of
+// weights for the whole kernel).  Rows of u, g_in and g_out come in by direct-to-LDS loads (a row = 1 KB = one
+// wave instruction); between the factors of a Monarch matrix the rows cross between the waves through an LDS
+// tile whose index map is the middle permutation; between the two matrices they sit as plain rows.
+//   S1: T_a[i, v]  = sum_c R1_a[i, c] (g_in u)[v][16 c + a]          -> tile (v, i, a)
+//   S2: z[v][16 k + i] = K[h_v][16 k + i] sum_a L1_i[k, a] T_a[i, v]  -> rows
+//   S3, S4: the same with R2, L2 and g_out in place of K              -> rows, stored with 16-byte accesses
+namespace mix16 {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int B = 16, N = 256, TV = 16;
+constexpr int LDX = N + 4;                 // pitch of the row buffers
+constexpr int RS = 18, LD = B * RS + 3;    // tile: element (v, p, q) at v LD + p RS + q
+constexpr size_t LDS_BYTES = sizeof(float) * (2 * TV * LDX + TV * LD);
+
+__device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+template <bool GIN, bool GOUT>
+__global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restrict__ u, const float *__restrict__ K,
+                                                           const float *__restrict__ g_in, const float *__restrict__ g_out,
+                                                           const float *__restrict__ R1, const float *__restrict__ L1,
+                                                           const float *__restrict__ R2, const float *__restrict__ L2,
+                                                           float *__restrict__ y, int64_t rows, int H)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float *xs = smem;                  // [TV][LDX]  rows of u, at the end the rows of y
+    float *zs = xs + TV * LDX;         // [TV][LDX]  rows of g_in, then the rows between M1 and M2, then g_out
+    float *tt = zs + TV * LDX;         // tile between the two factors of a matrix: (v, i, a)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
+    const int b0 = 4 * wave;
+
+    // A operands: k-step s of block q holds W[b0 + q][row l16][4 kg + s]
+    float R1w[4][4], L1w[4][4], R2w[4][4], L2w[4][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int at = ((b0 + q) * B + l16) * B + 4 * kg + s;
+            R1w[q][s] = R1[at];
+            L1w[q][s] = L1[at];
+            R2w[q][s] = R2[at];
+            L2w[q][s] = L2[at];
+        }
+
+    const int64_t ntiles = (rows + TV - 1) / TV;
+    const uint32_t xs_addr = lds_address(xs), zs_addr = lds_address(zs);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t r0 = tile * TV;
+        // rows in: wave w fetches rows 4 w .. 4 w + 3 (rows past the end: the last one, never stored)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int64_t r = r0 + b0 + q;
+            if (r >= rows) r = rows - 1;
+            dma_16_at(u + r * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            if (GIN) dma_16_at(g_in + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
+        }
+        // the kernel entries this lane multiplies in S2: K[h_v][16 (4 kg + r) + b0 .. + 3], v = l16
+        f32x4 kq[4];
+        {
+            int64_t r = r0 + l16;
+            if (r >= rows) r = rows - 1;
+            const float *krow = K + (r % H) * (int64_t)N + b0;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) kq[rr] = *reinterpret_cast<const f32x4 *>(krow + 16 * (4 * kg + rr));
+        }
+        wait_loads_at_most<0>();
+        __syncthreads();
+
+        auto first_factor = [&](const float *rows_in, const float (&W)[4][4], bool gated) {
+            f32x4 xq[4];   // [s]: elements 16 (4 kg + s) + b0 .. + 3 of row v = l16
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                xq[s] = *reinterpret_cast<const f32x4 *>(rows_in + l16 * LDX + 16 * (4 * kg + s) + b0);
+                if (gated) xq[s] *= *reinterpret_cast<const f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + s) + b0);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 t = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) t = mfma(W[q][s], xq[s][q], t);   // rows i = 4 kg + r of block a = b0 + q
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tt[l16 * LD + (4 * kg + r) * RS + b0 + q] = t[r];   // (v, i, a)
+            }
+        };
+        auto second_factor = [&](const float (&W)[4][4], f32x4 (&out)[4]) {
+            // block i = b0 + q contracts a = 4 kg + s of tile row i; result rows k = 4 kg + r: element 16 k + i
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) acc = mfma(W[q][s], tt[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
+                out[q] = acc;
+            }
+        };
+
+        first_factor(xs, R1w, GIN);
+        __syncthreads();
+        f32x4 z[4];
+        second_factor(L1w, z);
+        // rows between the matrices: z[v][16 (4 kg + r) + b0 + q], times the kernel of the row's channel
+        // (zs held g_in, which every wave has consumed before the barrier above)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            *reinterpret_cast<f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0) =
+                f32x4{z[0][r] * kq[r][0], z[1][r] * kq[r][1], z[2][r] * kq[r][2], z[3][r] * kq[r][3]};
+        __syncthreads();
+        first_factor(zs, R2w, false);
+        __syncthreads();   // zs is free: the output gates land there while the last factor runs
+        if (GOUT) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int64_t r = r0 + b0 + q;
+                if (r >= rows) r = rows - 1;
+                dma_16_at(g_out + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            }
+        }
+        second_factor(L2w, z);
+        if (GOUT) {
+            wait_loads_at_most<0>();
+            __syncthreads();
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            f32x4 o = {z[0][r], z[1][r], z[2][r], z[3][r]};
+            if (GOUT) o *= *reinterpret_cast<const f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0);
+            *reinterpret_cast<f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0) = o;   // (u was consumed by the first factor)
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t r = r0 + b0 + q;
+            if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(xs + (b0 + q) * LDX + 4 * lane);
+        }
+        __syncthreads();   // before the next tile's rows land
+    }
+}
+
+}  // namespace mix16
+
+bool mixer_fits(int bs) { return bs >= 1 && (size_t)2 * bs * bs * sizeof(float) <= 160 * 1024; }
+
+int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
+                 const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s)
+{
+    if (rows == 0) return MONARCH_OK;
+    if (bs == 16 && dt == MONARCH_F32) {
+        int dev = 0, ncu = 0;
+        MONARCH_HIP_CHECK(hipGetDevice(&dev));
+        MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+        const int64_t ntiles = (rows + mix16::TV - 1) / mix16::TV;
+        int64_t grid = 2 * (int64_t)ncu;
+        if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_MIX16(GI, GO)                                                                               \
+    do {                                                                                                           \
+        auto kern = mix16::mixer_b16_kernel<GI, GO>;                                                               \
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
+                                              (int)mix16::LDS_BYTES));                                             \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), mix16::LDS_BYTES, s, (const float *)u,           \
+                           (const float *)K, (const float *)g_in, (const float *)g_out, (const float *)R1,         \
+                           (const float *)L1, (const float *)R2, (const float *)L2, (float *)y, rows, H);          \
+    } while (0)
+        if (g_in && g_out) MONARCH_LAUNCH_MIX16(true, true);
+        else if (g_in) MONARCH_LAUNCH_MIX16(true, false);
+        else if (g_out) MONARCH_LAUNCH_MIX16(false, true);
+        else MONARCH_LAUNCH_MIX16(false, false);
+#undef MONARCH_LAUNCH_MIX16
+        MONARCH_HIP_CHECK(hipGetLastError());
+        return MONARCH_OK;
+    }
+    if (dt == MONARCH_F32) return mixg::launch_typed<float>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, s);
+    return mixg::launch_typed<bf16_t>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, s);
+}
+
+}  // namespace monarch

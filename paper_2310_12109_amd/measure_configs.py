@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mixer c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -91,6 +91,22 @@ def matmul_backward_c1(batch, reps):
     _report(f"c1 matmul backward fp32, batch {batch}", _time(calls, reps), nbytes, batch * 5 * 2 * 256 * 16, len(calls))
 
 
+def mixer(B, H, reps):
+    """Learned-Monarch sequence mixer at N = 256, fp32: u, both gates read and y written (4 KB per row)."""
+    rows = B * H
+    nbytes = 4 * rows * 256 * 4 + H * 256 * 4 + 4 * 16 * 256 * 4
+    K = _rnd(H, 256, dt=torch.float32)
+    f = [_rnd(16, 16, 16, dt=torch.float32, scale=.25) for _ in range(4)]
+
+    def make():
+        u, gi, go = (_rnd(B, H, 256, dt=torch.float32) for _ in range(3))
+        y = torch.empty_like(u)
+        return lambda: binding.monarch_mixer(u, K, gi, go, *f, out=y)
+    calls = _sets(make, nbytes)
+    # four block-diagonal products of 2 * 256 * 16 FLOP per row
+    _report(f"mixer fp32 N=256, B={B} H={H}", _time(calls, reps), nbytes, rows * 4 * 2 * 256 * 16, len(calls))
+
+
 def conv(name, B, H, n, factors, dt, reps):
     es = 2 if dt == torch.bfloat16 else 4
     code = binding.BF16 if dt == torch.bfloat16 else binding.F32
@@ -168,6 +184,9 @@ def main():
     if want("c1b"):
         matmul_backward_c1(64, 100)
         matmul_backward_c1(1 << 20, 5)
+    if want("mixer"):
+        mixer(8, 768, 100)
+        mixer(1024, 768, 5)
     if want("c2"):
         conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
         conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)

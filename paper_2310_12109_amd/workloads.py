@@ -45,6 +45,19 @@ def monarch_matmul_rect_inputs(batch, nbR, r_out, r_in, nbL, l_out, l_in, seed=0
     return _finish({"x": x, "R": R, "L": L}, bf16)
 
 
+def mixer_inputs(B, H, b, seed=0, gates=(True, True), bf16=False):
+    """Learned-Monarch sequence mixer: u, gates ~ N(0, 1) of shape (B, H, b*b), kernel K ~ N(0, 1) of shape
+    (H, b*b) in the transform domain, four factors ~ N(0, 1/b) of shape (b, b, b)."""
+    rng = np.random.default_rng(seed)
+    N = b * b
+    d = {"u": rng.standard_normal((B, H, N)), "K": rng.standard_normal((H, N))}
+    d["g_in"] = rng.standard_normal((B, H, N)) if gates[0] else None
+    d["g_out"] = rng.standard_normal((B, H, N)) if gates[1] else None
+    for name in ("R1", "L1", "R2", "L2"):
+        d[name] = rng.standard_normal((b, b, b)) / np.sqrt(b)
+    return _finish(d, bf16)
+
+
 def decaying_kernel(rng, H, klen, rate=0.01, two_sided=False, nfft=None):
     """k[h,t] = N(0,1) * exp(-rate*t).  two_sided: length nfft, lag -l stored at nfft-l."""
     if not two_sided:

@@ -91,6 +91,25 @@ def test_matmul_backward_rejects_bad_arguments(lib):
     assert f(A, B, C, D, E, F, G, 4, 256, 256, 256, 256, 256, 256, 0, None, 0, None) == ESHAPE   # too wide
 
 
+def test_mixer_rejects_bad_arguments(lib):
+    f = lib.monarch_mixer
+    f.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    u, K, gi, go, R1, L1, R2, L2, y = (FAKE * m for m in (1, 16, 32, 48, 64, 65, 66, 67, 80))   # >= 64 KB apart
+    assert f(None, K, gi, go, R1, L1, R2, L2, y, 2, 4, 16, 0, None, 0, None) == EINVAL      # u missing
+    assert f(u, K, gi, go, R1, None, R2, L2, y, 2, 4, 16, 0, None, 0, None) == EINVAL       # a factor missing
+    assert f(u, K, None, None, R1, L1, R2, L2, None, 2, 4, 16, 0, None, 0, None) == EINVAL  # y missing
+    assert f(u, K, gi, go, R1, L1, R2, L2, u, 2, 4, 16, 0, None, 0, None) == EINVAL         # y aliases u
+    assert f(u, K, gi, go, R1, L1, R2, L2, go, 2, 4, 16, 0, None, 0, None) == EINVAL        # y aliases a gate
+    assert f(u + 8, K, gi, go, R1, L1, R2, L2, y, 2, 4, 16, 0, None, 0, None) == EINVAL     # misaligned
+    assert f(u, K, gi, go, R1, L1, R2, L2, y, -1, 4, 16, 0, None, 0, None) == ESHAPE
+    assert f(u, K, gi, go, R1, L1, R2, L2, y, 2, 0, 16, 0, None, 0, None) == ESHAPE
+    assert f(u, K, gi, go, R1, L1, R2, L2, y, 2, 4, 0, 0, None, 0, None) == ESHAPE
+    assert f(u, K, gi, go, R1, L1, R2, L2, y, 2, 4, 256, 0, None, 0, None) == ESHAPE        # a row beyond LDS
+    assert f(u, K, gi, go, R1, L1, R2, L2, y, 2, 4, 16, 2, None, 0, None) == EDTYPE
+    assert f(None, None, None, None, None, None, None, None, None, 0, 4, 16, 0, None, 0, None) == 0   # nothing to do
+    assert lib.monarch_mixer_workspace_bytes(8, 4, 16, 0) == 0
+
+
 def test_fft_rejects_bad_arguments(lib):
     fac = (ctypes.c_int * 3)(64, 32, 1)
     bad = (ctypes.c_int * 2)(64, 31)

@@ -1,0 +1,96 @@
+"""GPU parity: monarch_mixer (sequence mixer with two general order-2 Monarch matrices, Sec. 3.2 Eq. 2, gated)
+against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL_BF16, TOL_F32, announce, dev, host, rel_l2
+from paper_2310_12109_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2310_12109_amd import binding
+    return binding
+
+
+def _run(mm, w, bf16=False):
+    return mm.monarch_mixer(*(dev(w[k], bf16) for k in ("u", "K", "g_in", "g_out", "R1", "L1", "R2", "L2")))
+
+
+def _want(w):
+    return oracle.mixer(*(w[k] for k in ("u", "K", "g_in", "g_out", "R1", "L1", "R2", "L2")))
+
+
+@pytest.mark.parametrize("B,H", [(4, 16), (1, 1), (3, 7), (5, 13), (16, 96)])
+def test_n256_fp32(mm, B, H):
+    # tiles of 16 rows on the matrix cores: one tile, one row, ragged tiles whose rows change channel (3 x 7,
+    # 5 x 13), and 96 tiles
+    announce("mixer fp32 b=16 B,H", B, H)
+    w = workloads.mixer_inputs(B, H, 16, seed=B * 100 + H)
+    assert rel_l2(host(_run(mm, w)), _want(w)) <= TOL_F32
+
+
+@pytest.mark.parametrize("gates", [(True, False), (False, True), (False, False)])
+def test_n256_fp32_gates_absent(mm, gates):
+    announce("mixer fp32 b=16 gates", gates)
+    w = workloads.mixer_inputs(3, 11, 16, seed=7, gates=gates)
+    assert rel_l2(host(_run(mm, w)), _want(w)) <= TOL_F32
+
+
+def test_n256_fp32_more_tiles_than_workgroups(mm):
+    # 1251 tiles on at most 512 workgroups, the last tile ragged; the output must not depend on which workgroup
+    # and which of its iterations took a tile: checked against the oracle on a sample of rows from the whole range
+    B, H = 41, 488   # 20008 rows
+    announce("mixer fp32 b=16 B,H", B, H)
+    w = workloads.mixer_inputs(B, H, 16, seed=3)
+    y = host(_run(mm, w)).reshape(B * H, 256)
+    rows = np.unique(np.concatenate([np.arange(0, 40), np.arange(B * H - 40, B * H),
+                                     np.random.default_rng(0).integers(0, B * H, 400)]))
+    flat = {k: w[k].reshape(B * H, 256) for k in ("u", "g_in", "g_out")}
+    for r in rows:
+        h = r % H
+        want = oracle.mixer(flat["u"][r][None, None], w["K"][h][None], flat["g_in"][r][None, None], flat["g_out"][r][None, None],
+                            w["R1"], w["L1"], w["R2"], w["L2"])[0, 0]
+        assert rel_l2(y[r], want) <= TOL_F32, r
+    assert np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("b", [2, 3, 8, 32, 64])
+def test_other_block_sizes_fp32(mm, b):
+    announce("mixer fp32 b", b)
+    w = workloads.mixer_inputs(3, 5, b, seed=b)
+    assert rel_l2(host(_run(mm, w)), _want(w)) <= TOL_F32
+
+
+@pytest.mark.parametrize("b", [4, 16, 32])
+def test_bf16(mm, b):
+    announce("mixer bf16 b", b)
+    w = workloads.mixer_inputs(4, 9, b, seed=b, bf16=True)
+    y = _run(mm, w, bf16=True)
+    assert y.dtype == torch.bfloat16
+    assert rel_l2(host(y), _want(w)) <= TOL_BF16
+
+
+def test_identity_blocks_reduce_to_the_gated_product(mm):
+    # all four factors the identity: P P P = P for the involution P of a square Monarch matrix, so M = P and
+    # y = g_out o P (K o P (g_in o u)): an index identity, exact in fp32
+    announce("mixer identity blocks")
+    w = workloads.mixer_inputs(2, 3, 16, seed=1)
+    eye = np.broadcast_to(np.eye(16, dtype=np.float32), (16, 16, 16)).copy()
+    for k in ("R1", "L1", "R2", "L2"):
+        w[k] = eye
+    perm = oracle.perm(16, 256)
+    a = (w["g_in"] * w["u"]).astype(np.float32)
+    t = (a[..., perm] * w["K"][None]).astype(np.float32)
+    want = (t[..., perm] * w["g_out"]).astype(np.float32)
+    np.testing.assert_array_equal(host(_run(mm, w)).astype(np.float32), want)
+
+
+def test_empty_batch(mm):
+    w = workloads.mixer_inputs(1, 4, 16, seed=0)
+    w["u"] = w["u"][:0]; w["g_in"] = w["g_in"][:0]; w["g_out"] = w["g_out"][:0]
+    assert _run(mm, w).shape == (0, 4, 256)
