@@ -3,7 +3,8 @@
 TEST INFRASTRUCTURE ONLY: tests, the smoke check and the cpu_baseline leg of
 the benchmark call this; the product path never does.  The wrappers only
 marshal numpy arrays (float64 / complex128, C-contiguous) into the C
-functions; all arithmetic lives in the C file.
+functions; all arithmetic lives in the C file.  (oracle/blocky.py, plain numpy, holds the
+polynomial-parameterised Monarch matrices and their convolution.)
 """
 import ctypes
 import os

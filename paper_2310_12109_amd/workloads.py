@@ -58,6 +58,26 @@ def mixer_inputs(B, H, b, seed=0, gates=(True, True), bf16=False):
     return _finish(d, bf16)
 
 
+def blocky_inputs(B, H, n, b, seed=0, noise=0.05, klen=None, gates=True, bf16=False):
+    """Polynomial-parameterised Monarch convolution: coefficient matrices Lt, Rt (b*b, b) = the pattern that gives
+    the DFT (identity in every block of Rt and in the top block of Lt) plus N(0, noise^2) everywhere, a learned
+    perturbation of the Fourier transform; u, gates ~ N(0, 1) of shape (B, H, n); k (H, klen) with a decaying
+    envelope.  Parameters (Lt, Rt, k) stay float32; with bf16=True only u and the gates are rounded to bf16."""
+    rng = np.random.default_rng(seed)
+    N = b * b
+    klen = n if klen is None else klen
+    Lt = noise * rng.standard_normal((N, b))
+    Lt[:b, :] += np.eye(b)
+    Rt = noise * rng.standard_normal((N, b)) + np.tile(np.eye(b), (b, 1))
+    k = rng.standard_normal((H, klen)) * np.exp(-0.05 * np.arange(klen))[None, :]
+    par = _finish({"Lt": Lt, "Rt": Rt, "k": k}, False)
+    act = {"u": rng.standard_normal((B, H, n))}
+    act["g_in"] = rng.standard_normal((B, H, n)) if gates else None
+    act["g_out"] = rng.standard_normal((B, H, n)) if gates else None
+    par.update(_finish(act, bf16))
+    return par
+
+
 def decaying_kernel(rng, H, klen, rate=0.01, two_sided=False, nfft=None):
     """k[h,t] = N(0,1) * exp(-rate*t).  two_sided: length nfft, lag -l stored at nfft-l."""
     if not two_sided:
