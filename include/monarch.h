@@ -116,6 +116,36 @@ int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_
 size_t monarch_mixer_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt);
 
 /*
+ * Convolution with a polynomial-parameterised ("blocky") Monarch matrix (appendix: the blocky Monarch algorithm,
+ * the masking lemma for causality, the blocky Monarch convolution and its causality theorem).
+ *
+ * Parameters: coefficient matrices Lt, Rt (N x bs, row-major, float32, N = bs^2).  With w_m = exp(+2 pi i / m)
+ * they define the complex block-diagonal factors
+ *   R_{j1}[i0, j0] = sum_{a < bs} Rt[j1 bs + a, j0] w_bs^(i0 a),   L_{i0}[i1, j1] = sum_{a < N} Lt[a, j1] w_N^((i1 bs + i0) a),
+ * M = P L P R P as in monarch_matmul, and per sequence b and channel h
+ *   y[b,h,0:n] = g_out[b,h,:] o Re( M^-1 ( (M (k[h,:], 0)) o (M (g_in[b,h,:] o u[b,h,:], 0)) ) )[0:n],
+ * M^-1 = P R^-1 P L^-1 P with blockwise inverses.  Identity coefficients (every block of Rt and the top block of
+ * Lt the identity, the rest zero) give the DFT and the circular convolution of length N.  mask = 1 zeroes the
+ * coefficients the lemma zeroes (of Lt all but the entries [a, j1], j1 <= a < bs; of each block of Rt the entries
+ * [a, j0] with a < j0, and with a >= bs/2 in a column j0 < bs/2): then the map is causal in u for
+ * n, klen <= bs * floor(bs / 2).
+ *
+ * monarch_blocky_prepare (once per parameter update): evaluates the factors in float64, inverts the blocks
+ * (Gauss-Jordan, partial pivoting, float64), transforms the kernels k (H, klen; float32), and writes all of it as
+ * complex float32 into `state` (device memory of the caller, monarch_blocky_state_bytes(H, bs) bytes; its layout is
+ * private).  A singular block yields non-finite values in the state and in every later output.
+ * monarch_blocky_conv (per batch): u, g_in, g_out, y: (B, H, n) of type dt, n <= N; gates may be NULL; reads the
+ * state, writes nothing but y; complex float32 arithmetic, rows stay on chip from load to store.
+ * Errors: EINVAL (null or misaligned pointers, mask not 0 / 1, overlap), ESHAPE (bs outside [2, 64], klen or n
+ * beyond N, klen beyond bs * floor(bs / 2) with the mask), EWORKSPACE (state too small), EDTYPE, EHIP.
+ */
+size_t monarch_blocky_state_bytes(int H, int bs);
+int monarch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
+                           void *state, size_t state_bytes, monarch_stream_t stream);
+int monarch_blocky_conv(const void *u, const void *g_in, const void *g_out, const void *state, size_t state_bytes,
+                        void *y, int64_t B, int H, int n, int bs, monarch_dtype dt, monarch_stream_t stream);
+
+/*
  * Monarch-factored DFT (appendix, DFT corollary; order 3 per the p-variate
  * section):  X[r,:] = F_N x[r,:],  F_N[m,j] = omega_N^(m j), unnormalised,
  * natural output order.  N = factors[0]*...*factors[nf-1], nf in {2,3}; the

@@ -38,6 +38,10 @@ _lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _
 _lib.monarch_mixer.argtypes = [_vp] * 9 + [_i64, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_mixer_workspace_bytes.restype = _sz
 _lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
+_lib.monarch_blocky_state_bytes.restype = _sz
+_lib.monarch_blocky_state_bytes.argtypes = [_i, _i]
+_lib.monarch_blocky_prepare.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_blocky_conv.argtypes = [_vp, _vp, _vp, _vp, _sz, _vp, _i64, _i, _i, _i, _i, _vp]
 _lib.monarch_fft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_ifft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_fft_workspace_bytes.restype = _sz
@@ -54,6 +58,7 @@ EXPORTS = [
     "monarch_matmul", "monarch_matmul_workspace_bytes",
     "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
+    "monarch_blocky_state_bytes", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
     "monarch_mlp", "monarch_mlp_workspace_bytes",
@@ -151,6 +156,43 @@ def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):
     _check(_lib.monarch_mixer(_ptr(u), _ptr(K), _ptr(g_in), _ptr(g_out), _ptr(R1), _ptr(L1), _ptr(R2), _ptr(L2), _ptr(y),
                               B, H, bs, _dt(u), None, 0, _stream()))
     return y
+
+
+def monarch_blocky_prepare(Lt, Rt, k, mask=True, state=None):
+    """State (uint8 device tensor) of the polynomial-parameterised Monarch convolution: Lt, Rt (N, bs), k (H, klen),
+    all float32."""
+    N, bs = Lt.shape
+    H, klen = k.shape
+    need = _lib.monarch_blocky_state_bytes(H, bs)
+    if state is None:
+        state = torch.empty(max(need, 16), dtype=torch.uint8, device=Lt.device)
+    _check(_lib.monarch_blocky_prepare(_ptr(Lt), _ptr(Rt), _ptr(k), H, klen, bs, int(bool(mask)), _ptr(state),
+                                       state.numel(), _stream()))
+    return state
+
+
+def monarch_blocky_conv(u, g_in, g_out, state, bs, out=None):
+    B, H, n = u.shape
+    y = out if out is not None else torch.empty_like(u)
+    _check(_lib.monarch_blocky_conv(_ptr(u), _ptr(g_in), _ptr(g_out), _ptr(state), state.numel(), _ptr(y), B, H, n, bs,
+                                    _dt(u), _stream()))
+    return y
+
+
+def blocky_state_views(state, H, bs):
+    """The parts of a prepared state as complex64 tensors (R1, L1, R2, L2: (bs, bs, bs); Kf: (H, N)), for tests."""
+    N = bs * bs
+
+    def up(v):
+        return (v + 255) & ~255
+    f = up(N * bs * 8)
+    off = up(N * 16)
+    parts = []
+    for _ in range(4):
+        parts.append(state[off:off + N * bs * 8].view(torch.complex64).reshape(bs, bs, bs))
+        off += f
+    parts.append(state[off:off + H * N * 8].view(torch.complex64).reshape(H, N))
+    return parts
 
 
 def monarch_fft_workspace_bytes(rows, N, factors, dt=F32):

@@ -219,6 +219,60 @@ int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_
 }
 
 // ---------------------------------------------------------------------------------------------
+// monarch_blocky_prepare / monarch_blocky_conv
+// ---------------------------------------------------------------------------------------------
+
+size_t monarch_blocky_state_bytes(int H, int bs)
+{
+    if (H < 0 || !blocky_fits(bs)) return 0;
+    return blocky_state_bytes(H, bs);
+}
+
+int monarch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
+                           void *state, size_t state_bytes, monarch_stream_t stream)
+{
+    clear_error();
+    if (!blocky_fits(bs)) return fail(MONARCH_ESHAPE, "block size %d outside [2, 64]", bs);
+    const int N = bs * bs;
+    if (H < 0 || klen < 0 || klen > N) return fail(MONARCH_ESHAPE, "H must be >= 0 and klen in [0, N = %d]", N);
+    if (mask != 0 && mask != 1) return fail(MONARCH_EINVAL, "mask flag must be 0 or 1");
+    if (mask && klen > bs * (bs / 2))
+        return fail(MONARCH_ESHAPE, "with the causal mask the kernel may have at most bs * floor(bs / 2) = %d taps", bs * (bs / 2));
+    if (!Lt || !Rt || !state || (H > 0 && klen > 0 && !k)) return fail(MONARCH_EINVAL, "Lt, Rt, k and state must be non-NULL");
+    if (misaligned(Lt) || misaligned(Rt) || misaligned(k) || misaligned(state)) return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t need = blocky_state_bytes(H, bs);
+    if (state_bytes < need) return fail(MONARCH_EWORKSPACE, "state of %zu bytes needed, %zu given", need, state_bytes);
+    const size_t coeff = (size_t)N * bs * sizeof(float);
+    if (overlaps(state, need, Lt, coeff) || overlaps(state, need, Rt, coeff) ||
+        (k && overlaps(state, need, k, (size_t)H * klen * sizeof(float))))
+        return fail(MONARCH_EINVAL, "state overlaps an input");
+    return launch_blocky_prepare(Lt, Rt, k, H, klen, bs, mask, state, (hipStream_t)stream);
+}
+
+int monarch_blocky_conv(const void *u, const void *g_in, const void *g_out, const void *state, size_t state_bytes,
+                        void *y, int64_t B, int H, int n, int bs, monarch_dtype dt, monarch_stream_t stream)
+{
+    clear_error();
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (!blocky_fits(bs)) return fail(MONARCH_ESHAPE, "block size %d outside [2, 64]", bs);
+    if (B < 0 || H < 1 || n < 0 || n > bs * bs) return fail(MONARCH_ESHAPE, "B >= 0, H >= 1 and n in [0, bs^2] required");
+    if (B > INT64_MAX / H) return fail(MONARCH_ESHAPE, "B * H overflows");
+    const int64_t rows = B * H;
+    if (rows == 0 || n == 0) return MONARCH_OK;
+    if (!u || !y || !state) return fail(MONARCH_EINVAL, "u, y and state must be non-NULL");
+    if (misaligned(u) || misaligned(g_in) || misaligned(g_out) || misaligned(y) || misaligned(state))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t need = blocky_state_bytes(H, bs);
+    if (state_bytes < need) return fail(MONARCH_EWORKSPACE, "state of %zu bytes needed, %zu given", need, state_bytes);
+    const size_t act = (size_t)rows * n * dtype_size(dt);
+    if (overlaps(y, act, u, act) || (g_in && overlaps(y, act, g_in, act)) || (g_out && overlaps(y, act, g_out, act)) ||
+        overlaps(y, act, state, need))
+        return fail(MONARCH_EINVAL, "y overlaps an input");
+    return launch_blocky_conv(u, g_in, g_out, state, y, rows, H, n, bs, dt, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
 // monarch_fft / monarch_ifft
 // ---------------------------------------------------------------------------------------------
 

@@ -1,0 +1,332 @@
+// Polynomial-parameterised ("blocky") Monarch matrices and the convolution built on them (appendix: the blocky
+// Monarch algorithm, the masking lemma, the blocky Monarch convolution and its causality theorem).
+//
+// Parameters: coefficient matrices Lt, Rt (N x b, real, b = sqrt(N)).  They stand for complex block-diagonal
+// factors
+//   R_{j1}[i0, j0] = sum_{a<b} Rt[j1 b + a, j0] w_b^(i0 a),      L_{i0}[i1, j1] = sum_{a<N} Lt[a, j1] w_N^((i1 b + i0) a)
+// (w_m = exp(+2 pi i / m)), M = P L P R P, and the convolution is  f = M^-1 ( (M k) o (M u) )  with
+// M^-1 = P R^-1 P L^-1 P (blockwise inverses).  With the masks of the lemma applied to the coefficients the map
+// u -> f[0:n] is causal for n <= b floor(b/2).
+//
+// Two phases.  prepare (once per parameter update, O(N^1.5 .. N^2.5) work, float64 arithmetic): the factors, their
+// blockwise inverses and the kernel in the transform domain, written as complex float32 into a state buffer of the
+// caller.  conv (per batch): rows stay on chip from load to store, gates fused, complex float32 arithmetic.
+#include "kernels.h"
+
+namespace monarch {
+
+namespace blocky {
+
+struct cdouble {
+    double re, im;
+};
+__device__ __forceinline__ cdouble cmul(cdouble a, cdouble b) { return {a.re * b.re - a.im * b.im, a.re * b.im + a.im * b.re}; }
+__device__ __forceinline__ cdouble csub(cdouble a, cdouble b) { return {a.re - b.re, a.im - b.im}; }
+__device__ __forceinline__ cdouble cinv(cdouble a)
+{
+    const double d = a.re * a.re + a.im * a.im;   // 0 for a singular block: the inverse is then not finite
+    return {a.re / d, -a.im / d};
+}
+
+// layout of the state buffer (byte offsets, each part 256-byte aligned)
+struct Layout {
+    size_t tw, R1, L1, R2, L2, Kf, total;
+};
+__host__ __device__ inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+__host__ __device__ inline Layout layout(int H, int bs)
+{
+    const size_t N = (size_t)bs * bs, f = up256(N * bs * sizeof(float2));
+    Layout l;
+    l.tw = 0;
+    l.R1 = up256(N * sizeof(cdouble));
+    l.L1 = l.R1 + f;
+    l.R2 = l.L1 + f;
+    l.L2 = l.R2 + f;
+    l.Kf = l.L2 + f;
+    l.total = l.Kf + up256((size_t)H * N * sizeof(float2));
+    return l;
+}
+
+// w_N^e for e in [0, N), float64
+__global__ void twiddle_kernel(cdouble *tw, int N)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < N) {
+        double s, c;
+        sincospi(2.0 * (double)e / (double)N, &s, &c);
+        tw[e] = {c, s};
+    }
+}
+
+// masked coefficient reads (masking lemma); `a` is the degree, the second index the column
+__device__ __forceinline__ double coeff_L(const float *Lt, int bs, int a, int j1, bool mask)
+{
+    if (mask && (a >= bs || a < j1)) return 0.0;
+    return (double)Lt[(size_t)a * bs + j1];
+}
+__device__ __forceinline__ double coeff_R(const float *Rt, int bs, int j1, int a, int j0, bool mask)
+{
+    if (mask && (a < j0 || (a >= bs / 2 && j0 < bs / 2))) return 0.0;
+    return (double)Rt[((size_t)j1 * bs + a) * bs + j0];
+}
+
+// One workgroup per block: blocks [0, bs) are those of R, [bs, 2 bs) those of L.  The block is evaluated in
+// float64 into LDS, written out as complex float32, inverted in place (Gauss-Jordan, partial pivoting) and the
+// inverse written into the factor of M^-1 that it is: R^-1 -> L2, L^-1 -> R2.
+__global__ __launch_bounds__(256) void factor_kernel(const float *__restrict__ Lt, const float *__restrict__ Rt,
+                                                     const cdouble *__restrict__ tw, float2 *__restrict__ R1,
+                                                     float2 *__restrict__ L1, float2 *__restrict__ R2,
+                                                     float2 *__restrict__ L2, int bs, int mask)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
+    cdouble *A = reinterpret_cast<cdouble *>(raw);                      // [bs][bs]
+    int *swapped = reinterpret_cast<int *>(raw + (size_t)bs * bs * sizeof(cdouble));   // [bs] + 1
+    const int N = bs * bs, tid = threadIdx.x;
+    const bool is_L = blockIdx.x >= (unsigned)bs;
+    const int blk = is_L ? blockIdx.x - bs : blockIdx.x;
+    const int terms = is_L ? (mask ? bs : N) : bs;
+    for (int e = tid; e < N; e += blockDim.x) {
+        const int row = e / bs, col = e - row * bs;
+        cdouble acc = {0.0, 0.0};
+        // R: block j1 = blk, row i0, column j0: point w_b^i0 = w_N^(i0 b).  L: block i0 = blk, row i1, column j1:
+        // point w_N^(i1 b + i0)
+        const int point = is_L ? row * bs + blk : row * bs;
+        int ex = 0;   // (point * a) mod N
+        for (int a = 0; a < terms; ++a) {
+            const double c = is_L ? coeff_L(Lt, bs, a, col, mask) : coeff_R(Rt, bs, blk, a, col, mask);
+            const cdouble w = tw[ex];
+            acc.re += c * w.re;
+            acc.im += c * w.im;
+            ex += point;
+            if (ex >= N) ex -= N;
+        }
+        A[e] = acc;
+        (is_L ? L1 : R1)[(size_t)blk * N + e] = make_float2((float)acc.re, (float)acc.im);
+    }
+    __syncthreads();
+    for (int p = 0; p < bs; ++p) {
+        if (tid == 0) {
+            int best = p;
+            double bm = A[p * bs + p].re * A[p * bs + p].re + A[p * bs + p].im * A[p * bs + p].im;
+            for (int r = p + 1; r < bs; ++r) {
+                const cdouble v = A[r * bs + p];
+                const double m = v.re * v.re + v.im * v.im;
+                if (m > bm) { bm = m; best = r; }
+            }
+            swapped[p] = best;
+        }
+        __syncthreads();
+        const int piv = swapped[p];
+        if (piv != p)
+            for (int c = tid; c < bs; c += blockDim.x) {
+                const cdouble t = A[p * bs + c];
+                A[p * bs + c] = A[piv * bs + c];
+                A[piv * bs + c] = t;
+            }
+        __syncthreads();
+        const cdouble pinv = cinv(A[p * bs + p]);
+        __syncthreads();
+        for (int c = tid; c < bs; c += blockDim.x) A[p * bs + c] = c == p ? pinv : cmul(A[p * bs + c], pinv);
+        __syncthreads();
+        // eliminate column p from every other row; thread e owns entry (row, col), column p is handled last
+        for (int e = tid; e < N; e += blockDim.x) {
+            const int row = e / bs, col = e - row * bs;
+            if (row == p || col == p) continue;
+            A[e] = csub(A[e], cmul(A[row * bs + p], A[p * bs + col]));
+        }
+        __syncthreads();
+        for (int row = tid; row < bs; row += blockDim.x)
+            if (row != p) {
+                const cdouble f = A[row * bs + p];
+                const cdouble r = cmul(f, A[p * bs + p]);
+                A[row * bs + p] = {-r.re, -r.im};
+            }
+        __syncthreads();
+    }
+    // undo the row exchanges: they are column exchanges of the inverse, in reverse order
+    for (int p = bs - 1; p >= 0; --p) {
+        const int piv = swapped[p];
+        if (piv != p)
+            for (int r = tid; r < bs; r += blockDim.x) {
+                const cdouble t = A[r * bs + p];
+                A[r * bs + p] = A[r * bs + piv];
+                A[r * bs + piv] = t;
+            }
+        __syncthreads();
+    }
+    for (int e = tid; e < N; e += blockDim.x)
+        (is_L ? R2 : L2)[(size_t)blk * N + e] = make_float2((float)A[e].re, (float)A[e].im);
+}
+
+constexpr int THREADS = 256;
+
+// One complex block-diagonal factor W [bs][bs][bs] on TV rows held in LDS: block k reads in[v][k ks_in + c cs_in],
+// c < cmax, and writes out[v][r bs + k] for the rows r < rmax.  REAL_IN: the input has no imaginary part.
+template <int TV, bool REAL_IN>
+__device__ __forceinline__ void cfactor(const float2 *in, float2 *out, int N, int bs, const float2 *__restrict__ W,
+                                        int cs_in, int ks_in, int cmax, int rmax)
+{
+    for (int o = threadIdx.x; o < N; o += THREADS) {   // o = k bs + r
+        const int k = o / bs, r = o - k * bs;
+        if (r >= rmax) continue;
+        float2 acc[TV];
+#pragma unroll
+        for (int v = 0; v < TV; ++v) acc[v] = make_float2(0.0f, 0.0f);
+        const float2 *w = W + (size_t)o * bs;
+        for (int c = 0; c < cmax; ++c) {
+            const float2 wv = w[c];
+#pragma unroll
+            for (int v = 0; v < TV; ++v) {
+                const float2 x = in[v * N + k * ks_in + c * cs_in];
+                acc[v].x = fmaf(wv.x, x.x, acc[v].x);
+                acc[v].y = fmaf(wv.y, x.x, acc[v].y);
+                if (!REAL_IN) {
+                    acc[v].x = fmaf(-wv.y, x.y, acc[v].x);
+                    acc[v].y = fmaf(wv.x, x.y, acc[v].y);
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < TV; ++v) out[v * N + r * bs + k] = acc[v];
+    }
+}
+
+// Kf[h, :] = M (k[h, :], 0): one workgroup per channel
+__global__ __launch_bounds__(THREADS) void kf_kernel(const float *__restrict__ k, const float2 *__restrict__ R1,
+                                                     const float2 *__restrict__ L1, float2 *__restrict__ Kf, int klen,
+                                                     int bs)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
+    const int N = bs * bs, h = blockIdx.x;
+    float2 *a = reinterpret_cast<float2 *>(raw), *t = a + N;
+    for (int j = threadIdx.x; j < N; j += THREADS) a[j] = make_float2(j < klen ? k[(size_t)h * klen + j] : 0.0f, 0.0f);
+    __syncthreads();
+    cfactor<1, true>(a, t, N, bs, R1, bs, 1, (klen + bs - 1) / bs, bs);
+    __syncthreads();
+    cfactor<1, false>(t, a, N, bs, L1, 1, bs, bs, bs);
+    __syncthreads();
+    for (int j = threadIdx.x; j < N; j += THREADS) Kf[(size_t)h * N + j] = a[j];
+}
+
+// y[row, 0:n] = g_out o Re( M2 ( Kf[h] o ( M1 (g_in o u, 0) ) ) )[0:n], row = b H + h
+template <typename T, int TV>
+__global__ __launch_bounds__(THREADS) void conv_kernel(const T *__restrict__ u, const T *__restrict__ g_in,
+                                                       const T *__restrict__ g_out, const float2 *__restrict__ R1,
+                                                       const float2 *__restrict__ L1, const float2 *__restrict__ R2,
+                                                       const float2 *__restrict__ L2, const float2 *__restrict__ Kf,
+                                                       T *__restrict__ y, int64_t rows, int H, int n, int bs)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
+    const int N = bs * bs;
+    float2 *a = reinterpret_cast<float2 *>(raw), *t = a + (size_t)TV * N;
+    const int live = (n + bs - 1) / bs;   // leading indices c (of the input) and k (of the output) that matter
+    const int64_t ntiles = (rows + TV - 1) / TV;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t r0 = tile * TV;
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            float x = 0.0f;
+            if (r0 + v < rows && j < n) {
+                x = to_f32(u[(r0 + v) * n + j]);
+                if (g_in) x *= to_f32(g_in[(r0 + v) * n + j]);
+            }
+            a[idx] = make_float2(x, 0.0f);
+        }
+        __syncthreads();
+        cfactor<TV, true>(a, t, N, bs, R1, bs, 1, live, bs);
+        __syncthreads();
+        cfactor<TV, false>(t, a, N, bs, L1, 1, bs, bs, bs);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            int64_t r = r0 + v;
+            if (r >= rows) r = rows - 1;
+            const float2 kf = Kf[(r % H) * (int64_t)N + j], x = a[idx];
+            a[idx] = make_float2(x.x * kf.x - x.y * kf.y, x.x * kf.y + x.y * kf.x);
+        }
+        __syncthreads();
+        cfactor<TV, false>(a, t, N, bs, R2, bs, 1, bs, bs);
+        __syncthreads();
+        cfactor<TV, false>(t, a, N, bs, L2, 1, bs, bs, live);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            if (r0 + v < rows && j < n) {
+                float o = a[idx].x;
+                if (g_out) o *= to_f32(g_out[(r0 + v) * n + j]);
+                y[(r0 + v) * n + j] = from_f32<T>(o);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+static int launch_conv_typed(const void *u, const void *g_in, const void *g_out, const unsigned char *state, void *y,
+                             int64_t rows, int H, int n, int bs, hipStream_t s)
+{
+    const int N = bs * bs;
+    const Layout l = layout(H, bs);
+    int tv = 8;
+    while (tv > 1 && (size_t)2 * tv * N * sizeof(float2) > 64 * 1024) tv >>= 1;
+    const size_t lds = (size_t)2 * tv * N * sizeof(float2);
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t ntiles = (rows + tv - 1) / tv;
+    int64_t grid = (int64_t)ncu * (lds <= 32 * 1024 ? 4 : 2);
+    if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_BLOCKY(TVV)                                                                                \
+    hipLaunchKernelGGL((conv_kernel<T, TVV>), dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)u,          \
+                       (const T *)g_in, (const T *)g_out, (const float2 *)(state + l.R1),                         \
+                       (const float2 *)(state + l.L1), (const float2 *)(state + l.R2),                            \
+                       (const float2 *)(state + l.L2), (const float2 *)(state + l.Kf), (T *)y, rows, H, n, bs)
+    switch (tv) {
+    case 8: MONARCH_LAUNCH_BLOCKY(8); break;
+    case 4: MONARCH_LAUNCH_BLOCKY(4); break;
+    case 2: MONARCH_LAUNCH_BLOCKY(2); break;
+    default: MONARCH_LAUNCH_BLOCKY(1); break;
+    }
+#undef MONARCH_LAUNCH_BLOCKY
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+}  // namespace blocky
+
+bool blocky_fits(int bs) { return bs >= 2 && bs <= 64; }   // a row twice in LDS as complex float32: 64 KB at bs = 64
+
+size_t blocky_state_bytes(int H, int bs) { return blocky::layout(H, bs).total; }
+
+int launch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
+                          void *state, hipStream_t s)
+{
+    using namespace blocky;
+    const int N = bs * bs;
+    const Layout l = layout(H, bs);
+    unsigned char *st = static_cast<unsigned char *>(state);
+    cdouble *tw = reinterpret_cast<cdouble *>(st + l.tw);
+    float2 *R1 = reinterpret_cast<float2 *>(st + l.R1), *L1 = reinterpret_cast<float2 *>(st + l.L1);
+    float2 *R2 = reinterpret_cast<float2 *>(st + l.R2), *L2 = reinterpret_cast<float2 *>(st + l.L2);
+    hipLaunchKernelGGL(twiddle_kernel, dim3((N + 255) / 256), dim3(256), 0, s, tw, N);
+    const size_t lds_f = (size_t)N * sizeof(cdouble) + (bs + 1) * sizeof(int);
+    if (lds_f > 64 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)factor_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
+    hipLaunchKernelGGL(factor_kernel, dim3(2 * bs), dim3(256), lds_f, s, Lt, Rt, (const cdouble *)tw, R1, L1, R2, L2, bs, mask);
+    if (H > 0)
+        hipLaunchKernelGGL(kf_kernel, dim3(H), dim3(THREADS), (size_t)2 * N * sizeof(float2), s, k, (const float2 *)R1,
+                           (const float2 *)L1, reinterpret_cast<float2 *>(st + l.Kf), klen, bs);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const void *state, void *y, int64_t rows,
+                       int H, int n, int bs, monarch_dtype dt, hipStream_t s)
+{
+    if (rows == 0 || n == 0) return MONARCH_OK;
+    const unsigned char *st = static_cast<const unsigned char *>(state);
+    if (dt == MONARCH_F32) return blocky::launch_conv_typed<float>(u, g_in, g_out, st, y, rows, H, n, bs, s);
+    return blocky::launch_conv_typed<bf16_t>(u, g_in, g_out, st, y, rows, H, n, bs, s);
+}
+
+}  // namespace monarch

@@ -90,6 +90,13 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
 bool mixer_fits(int bs);
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                  const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
+// polynomial-parameterised Monarch convolution (csrc/blocky.hip): parameter phase and per-batch phase
+bool blocky_fits(int bs);
+size_t blocky_state_bytes(int H, int bs);
+int launch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
+                          void *state, hipStream_t s);
+int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const void *state, void *y, int64_t rows,
+                       int H, int n, int bs, monarch_dtype dt, hipStream_t s);
 bool fft2_lds_supported(int f1, int f2, monarch_dtype dt);
 int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
 

@@ -110,6 +110,37 @@ def test_mixer_rejects_bad_arguments(lib):
     assert lib.monarch_mixer_workspace_bytes(8, 4, 16, 0) == 0
 
 
+def test_blocky_rejects_bad_arguments(lib):
+    lib.monarch_blocky_state_bytes.restype = ctypes.c_size_t
+    lib.monarch_blocky_state_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
+    need = lib.monarch_blocky_state_bytes(4, 16)
+    assert need >= 256 * 16 + 4 * 4096 * 8 + 4 * 256 * 8
+    assert lib.monarch_blocky_state_bytes(4, 65) == 0
+    p = lib.monarch_blocky_prepare
+    p.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 4 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    Lt, Rt, k, st = FAKE, FAKE * 8, FAKE * 16, FAKE * 64
+    assert p(None, Rt, k, 4, 128, 16, 1, st, need, None) == EINVAL
+    assert p(Lt, Rt, k, 4, 128, 16, 1, None, need, None) == EINVAL
+    assert p(Lt, Rt, k, 4, 128, 16, 2, st, need, None) == EINVAL            # mask flag
+    assert p(Lt, Rt, k, 4, 128, 1, 1, st, need, None) == ESHAPE             # block size
+    assert p(Lt, Rt, k, 4, 128, 65, 1, st, 1 << 40, None) == ESHAPE
+    assert p(Lt, Rt, k, 4, 129, 16, 1, st, need, None) == ESHAPE            # more taps than the mask allows
+    assert p(Lt, Rt, k, 4, 257, 16, 0, st, need, None) == ESHAPE            # more taps than N
+    assert p(Lt, Rt, k, 4, 128, 16, 1, st, need - 1, None) == EWORKSPACE
+    assert p(Lt, Rt, k, 4, 128, 16, 1, Lt, need, None) == EINVAL            # state over the coefficients
+    c = lib.monarch_blocky_conv
+    c.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int64] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    u, gi, go, y = FAKE * 128, FAKE * 160, FAKE * 192, FAKE * 224
+    assert c(None, gi, go, st, need, y, 2, 4, 128, 16, 0, None) == EINVAL
+    assert c(u, gi, go, None, need, y, 2, 4, 128, 16, 0, None) == EINVAL
+    assert c(u, gi, go, st, need - 1, y, 2, 4, 128, 16, 0, None) == EWORKSPACE
+    assert c(u, gi, go, st, need, u, 2, 4, 128, 16, 0, None) == EINVAL       # y aliases u
+    assert c(u, gi, go, st, need, y, 2, 4, 257, 16, 0, None) == ESHAPE       # n beyond N
+    assert c(u, gi, go, st, need, y, 2, 0, 128, 16, 0, None) == ESHAPE
+    assert c(u, gi, go, st, need, y, 2, 4, 128, 16, 2, None) == EDTYPE
+    assert c(u, gi, go, st, need, y, 0, 4, 128, 16, 0, None) == 0            # nothing to do
+
+
 def test_fft_rejects_bad_arguments(lib):
     fac = (ctypes.c_int * 3)(64, 32, 1)
     bad = (ctypes.c_int * 2)(64, 31)
