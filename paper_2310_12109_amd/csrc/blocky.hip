@@ -12,6 +12,7 @@
 // blockwise inverses and the kernel in the transform domain, written as complex float32 into a state buffer of the
 // caller.  conv (per batch): rows stay on chip from load to store, gates fused, complex float32 arithmetic.
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace monarch {
 
@@ -294,6 +295,245 @@ static int launch_conv_typed(const void *u, const void *g_in, const void *g_out,
 
 }  // namespace blocky
 
+
+// ---- bs = 16 (N = 256), float32 rows, on the matrix cores ---------------------------------------------
+// The four complex block-diagonal products as 16x16x4 float32 MFMAs on real and imaginary parts, rows on the MFMA
+// column index.  A workgroup of 4 waves takes a tile of 16 rows; wave w owns blocks 4 w .. 4 w + 3 of every factor
+// (real and imaginary A operands: 128 registers for the kernel's lifetime).  The 16 rows of a tile are one
+// contiguous piece of memory and arrive by direct-to-LDS loads in chunks of 1 KB (LDS pitch 260 floats per chunk).
+//   S1  T_a[i, v]  = sum_c R1_a[i, c] (g_in u)[v][16 c + a]      real input; only the K steps with 16 c < n
+//   S2  z[v][16 k + i] = Kf[h_v][16 k + i] sum_a L1_i[k, a] T_a[i, v]
+//   S3, S4 the same with R2, L2; of S4 only the real part, of its rows only those with 16 k < n are stored
+// Inside a matrix the rows cross between the waves through two LDS tiles (real, imaginary) whose index map is the
+// middle permutation; between the matrices z sits as plain rows where u and g_in were.
+namespace blocky16 {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int B = 16, N = 256, TV = 16;
+constexpr int CH = 260;                    // LDS pitch of a 1 KB chunk (256 floats) of a tile, and of a row of z
+constexpr int RS = 18, LD = B * RS + 3;    // tiles between the factors: element (v, p, q) at v LD + p RS + q
+constexpr int ROWBUF = 16 * CH;            // 16 chunks, or 16 rows of z
+constexpr size_t LDS_BYTES = sizeof(float) * (2 * ROWBUF + 2 * TV * LD);
+
+__device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ int chunked(int flat) { return (flat >> 8) * CH + (flat & 255); }
+
+// KS1: K steps of S1 that can hold live input (2 for n <= 128, else 4); n is a multiple of 16
+template <int KS1>
+__global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restrict__ u, const float *__restrict__ g_in,
+                                                          const float *__restrict__ g_out, const float2 *__restrict__ R1,
+                                                          const float2 *__restrict__ L1, const float2 *__restrict__ R2,
+                                                          const float2 *__restrict__ L2, const float2 *__restrict__ Kf,
+                                                          float *__restrict__ y, int64_t rows, int H, int n)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float *xa = smem;              // u; then Re z; then g_out
+    float *xb = xa + ROWBUF;       // g_in; then Im z; then the rows of y
+    float *tr = xb + ROWBUF;       // Re, Im of the tile between the two factors of a matrix: (v, i, a)
+    float *ti = tr + TV * LD;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
+    const int b0 = 4 * wave;
+
+    // A operands.  S1: K step s, lane group kg holds column c = 4 s + kg (so that whole K steps are dead when n is
+    // short); the other three factors: column 4 kg + s.
+    float R1r[4][KS1], R1i[4][KS1], L1r[4][4], L1i[4][4], R2r[4][4], R2i[4][4], L2r[4][4], L2i[4][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int row = ((b0 + q) * B + l16) * B;
+            if (s < KS1) {
+                const float2 w = R1[row + 4 * s + kg];
+                R1r[q][s] = w.x;
+                R1i[q][s] = w.y;
+            }
+            const float2 a = L1[row + 4 * kg + s], b = R2[row + 4 * kg + s], c = L2[row + 4 * kg + s];
+            L1r[q][s] = a.x; L1i[q][s] = a.y;
+            R2r[q][s] = b.x; R2i[q][s] = b.y;
+            L2r[q][s] = c.x; L2i[q][s] = c.y;
+        }
+
+    const int64_t ntiles = (rows + TV - 1) / TV;
+    const int nchunks = n / 16;                 // 16 n floats per tile, 256 per chunk
+    const int64_t last_piece = rows * n - 4;
+    const uint32_t xa_addr = lds_address(xa), xb_addr = lds_address(xb);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t r0 = tile * TV, base = r0 * n;
+        for (int q = wave; q < nchunks; q += 4) {
+            int64_t at = base + 256 * q + 4 * lane;
+            if (at > last_piece) at = last_piece;   // (rows past the end of the batch: never stored)
+            dma_16_at(u + at, xa_addr + (uint32_t)q * CH * 4);
+            if (g_in) dma_16_at(g_in + at, xb_addr + (uint32_t)q * CH * 4);
+        }
+        wait_loads_at_most<0>();
+        __syncthreads();
+
+        // ---- S1: real input, complex R1
+        {
+            f32x4 xq[KS1];
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) {
+                const int j = 16 * (4 * s + kg) + b0;
+                const int at = chunked(l16 * n + j);
+                f32x4 v = *reinterpret_cast<const f32x4 *>(xa + at);
+                if (g_in) v *= *reinterpret_cast<const f32x4 *>(xb + at);
+                xq[s] = j < n ? v : f32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < KS1; ++s) {
+                    ar = mfma(R1r[q][s], xq[s][q], ar);
+                    ai = mfma(R1i[q][s], xq[s][q], ai);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    tr[l16 * LD + (4 * kg + r) * RS + b0 + q] = ar[r];
+                    ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[r];
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- S2: complex L1, then the kernel of the row's channel
+        {
+            int64_t row = r0 + l16;
+            if (row >= rows) row = rows - 1;
+            const float2 *kf = Kf + (row % H) * (int64_t)N + b0;
+            f32x4 zr[4], zi[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const float tre = tr[l16 * LD + (b0 + q) * RS + 4 * kg + s];
+                    const float tim = ti[l16 * LD + (b0 + q) * RS + 4 * kg + s];
+                    ar = mfma(L1r[q][s], tre, ar);
+                    ar = mfma(L1i[q][s], -tim, ar);
+                    ai = mfma(L1r[q][s], tim, ai);
+                    ai = mfma(L1i[q][s], tre, ai);
+                }
+                zr[q] = ar;
+                zi[q] = ai;
+            }
+            // rows k = 4 kg + r of blocks i = b0 .. b0 + 3: elements 16 k + i
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const f32x4 k01 = *reinterpret_cast<const f32x4 *>(kf + 16 * (4 * kg + r));       // (re, im) of i = b0, b0 + 1
+                const f32x4 k23 = *reinterpret_cast<const f32x4 *>(kf + 16 * (4 * kg + r) + 2);
+                const f32x4 kre = {k01[0], k01[2], k23[0], k23[2]}, kim = {k01[1], k01[3], k23[1], k23[3]};
+                const f32x4 a = {zr[0][r], zr[1][r], zr[2][r], zr[3][r]}, b = {zi[0][r], zi[1][r], zi[2][r], zi[3][r]};
+                *reinterpret_cast<f32x4 *>(xa + l16 * CH + 16 * (4 * kg + r) + b0) = a * kre - b * kim;
+                *reinterpret_cast<f32x4 *>(xb + l16 * CH + 16 * (4 * kg + r) + b0) = a * kim + b * kre;
+            }
+        }
+        __syncthreads();
+
+        // ---- S3: complex R2 on the rows of z
+        {
+            f32x4 xr[4], xi[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                xr[s] = *reinterpret_cast<const f32x4 *>(xa + l16 * CH + 16 * (4 * kg + s) + b0);
+                xi[s] = *reinterpret_cast<const f32x4 *>(xb + l16 * CH + 16 * (4 * kg + s) + b0);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    ar = mfma(R2r[q][s], xr[s][q], ar);
+                    ar = mfma(R2i[q][s], -xi[s][q], ar);
+                    ai = mfma(R2r[q][s], xi[s][q], ai);
+                    ai = mfma(R2i[q][s], xr[s][q], ai);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    tr[l16 * LD + (4 * kg + r) * RS + b0 + q] = ar[r];
+                    ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[r];
+                }
+            }
+        }
+        __syncthreads();   // z is consumed: the output gates land where Re z was while the last factor runs
+        if (g_out)
+            for (int q = wave; q < nchunks; q += 4) {
+                int64_t at = base + 256 * q + 4 * lane;
+                if (at > last_piece) at = last_piece;
+                dma_16_at(g_out + at, xa_addr + (uint32_t)q * CH * 4);
+            }
+
+        // ---- S4: real part of complex L2
+        f32x4 o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                acc = mfma(L2r[q][s], tr[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
+                acc = mfma(L2i[q][s], -ti[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
+            }
+            o[q] = acc;
+        }
+        if (g_out) {
+            wait_loads_at_most<0>();
+            __syncthreads();
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = 16 * (4 * kg + r) + b0;
+            if (j < n) {
+                const int at = chunked(l16 * n + j);
+                f32x4 v = {o[0][r], o[1][r], o[2][r], o[3][r]};
+                if (g_out) v *= *reinterpret_cast<const f32x4 *>(xa + at);
+                *reinterpret_cast<f32x4 *>(xb + at) = v;   // (Im z was consumed before the barrier after S3)
+            }
+        }
+        __syncthreads();
+        for (int q = wave; q < nchunks; q += 4) {
+            const int64_t at = base + 256 * q + 4 * lane;
+            if (at <= last_piece) *reinterpret_cast<f32x4 *>(y + at) = *reinterpret_cast<const f32x4 *>(xb + q * CH + 4 * lane);
+        }
+        __syncthreads();   // before the next tile's rows land
+    }
+}
+
+static bool supported(int bs, int n, monarch_dtype dt) { return bs == 16 && dt == MONARCH_F32 && n >= 16 && n % 16 == 0; }
+
+static int launch(const void *u, const void *g_in, const void *g_out, const unsigned char *state, void *y, int64_t rows,
+                  int H, int n, hipStream_t s)
+{
+    const blocky::Layout l = blocky::layout(H, 16);
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t ntiles = (rows + TV - 1) / TV;
+    int64_t grid = 2 * (int64_t)ncu;
+    if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_BLOCKY16(KS)                                                                                \
+    do {                                                                                                           \
+        auto kern = conv_b16_kernel<KS>;                                                                           \
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
+                                              (int)LDS_BYTES));                                                    \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), LDS_BYTES, s, (const float *)u,                  \
+                           (const float *)g_in, (const float *)g_out, (const float2 *)(state + l.R1),              \
+                           (const float2 *)(state + l.L1), (const float2 *)(state + l.R2),                         \
+                           (const float2 *)(state + l.L2), (const float2 *)(state + l.Kf), (float *)y, rows, H, n); \
+    } while (0)
+    if (n <= 128) MONARCH_LAUNCH_BLOCKY16(2);
+    else MONARCH_LAUNCH_BLOCKY16(4);
+#undef MONARCH_LAUNCH_BLOCKY16
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+}  // namespace blocky16
+
 bool blocky_fits(int bs) { return bs >= 2 && bs <= 64; }   // a row twice in LDS as complex float32: 64 KB at bs = 64
 
 size_t blocky_state_bytes(int H, int bs) { return blocky::layout(H, bs).total; }
@@ -325,6 +565,7 @@ int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const
 {
     if (rows == 0 || n == 0) return MONARCH_OK;
     const unsigned char *st = static_cast<const unsigned char *>(state);
+    if (blocky16::supported(bs, n, dt)) return blocky16::launch(u, g_in, g_out, st, y, rows, H, n, s);
     if (dt == MONARCH_F32) return blocky::launch_conv_typed<float>(u, g_in, g_out, st, y, rows, H, n, bs, s);
     return blocky::launch_conv_typed<bf16_t>(u, g_in, g_out, st, y, rows, H, n, bs, s);
 }

@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mixer c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mixer blocky c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -107,6 +107,26 @@ def mixer(B, H, reps):
     _report(f"mixer fp32 N=256, B={B} H={H}", _time(calls, reps), nbytes, rows * 4 * 2 * 256 * 16, len(calls))
 
 
+def blocky(B, H, reps):
+    """Causal convolution with a polynomial-parameterised Monarch matrix, N = 256, n = 128, fp32: u and both gates
+    read, y written (2 KB per row); 704 complex-arithmetic MFMAs of 2048 FLOP per 16 rows."""
+    from . import workloads
+    rows, n = B * H, 128
+    nbytes = 4 * rows * n * 4 + H * 256 * 8 + 4 * 4096 * 8
+    w = workloads.blocky_inputs(1, H, n, 16, seed=0)
+    par = [torch.from_numpy(w[k]).cuda() for k in ("Lt", "Rt", "k")]
+    state = binding.monarch_blocky_prepare(*par, mask=True)
+
+    def make():
+        u, gi, go = (_rnd(B, H, n, dt=torch.float32) for _ in range(3))
+        y = torch.empty_like(u)
+        return lambda: binding.monarch_blocky_conv(u, gi, go, state, 16, out=y)
+    calls = _sets(make, nbytes)
+    _report(f"blocky conv fp32 N=256 n=128, B={B} H={H}", _time(calls, reps), nbytes, rows / 16 * 704 * 2048, len(calls))
+    t = _time([lambda: binding.monarch_blocky_prepare(*par, mask=True, state=state)], 20)
+    print(f"blocky prepare (factors, blockwise inverses, {H} kernels transformed) {t:9.1f} us", flush=True)
+
+
 def conv(name, B, H, n, factors, dt, reps):
     es = 2 if dt == torch.bfloat16 else 4
     code = binding.BF16 if dt == torch.bfloat16 else binding.F32
@@ -187,6 +207,9 @@ def main():
     if want("mixer"):
         mixer(8, 768, 100)
         mixer(1024, 768, 5)
+    if want("blocky"):
+        blocky(8, 768, 100)
+        blocky(1024, 768, 5)
     if want("c2"):
         conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
         conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)

@@ -51,6 +51,33 @@ def test_causal_n128_fp32(mm, B, H):
     assert rel_l2(host(_conv(mm, w, 16)), _want(w)) <= TOL_F32
 
 
+@pytest.mark.parametrize("n", [16, 64, 112, 100, 36])
+def test_causal_b16_other_lengths(mm, n):
+    # multiples of 16 take the matrix-core kernel (dead K steps, partly filled tiles), the others the LDS-tile kernel
+    announce("blocky conv fp32 b=16 n", n)
+    w = workloads.blocky_inputs(3, 7, n, 16, seed=n)
+    assert rel_l2(host(_conv(mm, w, 16)), _want(w)) <= TOL_F32
+
+
+def test_causal_b16_more_tiles_than_workgroups(mm):
+    # 1251 tiles on at most 512 workgroups, the last one ragged
+    B, H = 41, 488
+    announce("blocky conv fp32 b=16 n=128 B,H", B, H)
+    w = workloads.blocky_inputs(B, H, 128, 16, seed=11)
+    got, want = host(_conv(mm, w, 16)), _want(w)
+    assert rel_l2(got, want) <= TOL_F32
+    err = np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 10 * TOL_F32      # no single row is off
+
+
+@pytest.mark.parametrize("gates", ["in", "out"])
+def test_causal_b16_one_gate(mm, gates):
+    announce("blocky conv fp32 b=16 gate", gates)
+    w = workloads.blocky_inputs(3, 7, 128, 16, seed=5)
+    w["g_out" if gates == "in" else "g_in"] = None
+    assert rel_l2(host(_conv(mm, w, 16)), _want(w)) <= TOL_F32
+
+
 @pytest.mark.parametrize("b,n", [(2, 2), (4, 8), (5, 10), (8, 20), (8, 32), (32, 512), (32, 300)])
 def test_causal_other_block_sizes_fp32(mm, b, n):
     announce("blocky conv fp32 b, n", b, n)
