@@ -31,7 +31,7 @@ __device__ __forceinline__ cdouble cinv(cdouble a)
 
 // layout of the state buffer (byte offsets, each part 256-byte aligned)
 struct Layout {
-    size_t tw, R1, L1, R2, L2, Kf, total;
+    size_t tw, R1, L1, R2, L2, Kf, Kq, total;
 };
 __host__ __device__ inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 __host__ __device__ inline Layout layout(int H, int bs)
@@ -44,7 +44,9 @@ __host__ __device__ inline Layout layout(int H, int bs)
     l.R2 = l.L1 + f;
     l.L2 = l.R2 + f;
     l.Kf = l.L2 + f;
-    l.total = l.Kf + up256((size_t)H * N * sizeof(float2));
+    l.Kq = l.Kf + up256((size_t)H * N * sizeof(float2));
+    // bs = 16 only: a second copy of Kf in the order in which the matrix-core kernel's lanes read it
+    l.total = l.Kq + (bs == 16 ? up256((size_t)((H + 3) / 4) * 4 * N * sizeof(float2)) : 0);
     return l;
 }
 
@@ -194,8 +196,8 @@ __device__ __forceinline__ void cfactor(const float2 *in, float2 *out, int N, in
 
 // Kf[h, :] = M (k[h, :], 0): one workgroup per channel
 __global__ __launch_bounds__(THREADS) void kf_kernel(const float *__restrict__ k, const float2 *__restrict__ R1,
-                                                     const float2 *__restrict__ L1, float2 *__restrict__ Kf, int klen,
-                                                     int bs)
+                                                     const float2 *__restrict__ L1, float2 *__restrict__ Kf,
+                                                     float4 *__restrict__ Kq, int klen, int bs)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
     const int N = bs * bs, h = blockIdx.x;
@@ -207,6 +209,15 @@ __global__ __launch_bounds__(THREADS) void kf_kernel(const float *__restrict__ k
     cfactor<1, false>(t, a, N, bs, L1, 1, bs, bs, bs);
     __syncthreads();
     for (int j = threadIdx.x; j < N; j += THREADS) Kf[(size_t)h * N + j] = a[j];
+    // bs = 16: the same values as pairs of complex numbers, in the order of blocky16::conv_b16_kernel's loads:
+    // piece ((w 4 + kg) 8 + 2 r + half) of channel h holds elements 16 (4 kg + r) + 4 w + 2 half and the next one;
+    // four consecutive channels are interleaved piece by piece, so that four neighbouring lanes read 64 bytes
+    if (Kq)
+        for (int idx = threadIdx.x; idx < N / 2; idx += THREADS) {
+            const int p = idx & 7, kg = (idx >> 3) & 3, w = idx >> 5;
+            const int j = 16 * (4 * kg + (p >> 1)) + 4 * w + 2 * (p & 1);
+            Kq[((size_t)(h >> 2) * (N / 2) + idx) * 4 + (h & 3)] = make_float4(a[j].x, a[j].y, a[j + 1].x, a[j + 1].y);
+        }
 }
 
 // y[row, 0:n] = g_out o Re( M2 ( Kf[h] o ( M1 (g_in o u, 0) ) ) )[0:n], row = b H + h
@@ -310,7 +321,7 @@ namespace blocky16 {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int B = 16, N = 256, TV = 16;
+constexpr int B = 16, TV = 16;
 constexpr int CH = 260;                    // LDS pitch of a 1 KB chunk (256 floats) of a tile, and of a row of z
 constexpr int RS = 18, LD = B * RS + 3;    // tiles between the factors: element (v, p, q) at v LD + p RS + q
 constexpr int ROWBUF = 16 * CH;            // 16 chunks, or 16 rows of z
@@ -322,12 +333,23 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
 }
 __device__ __forceinline__ int chunked(int flat) { return (flat >> 8) * CH + (flat & 255); }
 
+// Phase clocks for kernel tuning; compiled out unless MONARCH_BLOCKY_CLOCKS is defined.
+#ifdef MONARCH_BLOCKY_CLOCKS
+__device__ long long g_clk[4][32];
+#define BLK_MARK(i)                                                                                             \
+    do {                                                                                                        \
+        if (blockIdx.x == 1 && tile == 1 + 2 * (int64_t)gridDim.x && lane == 0) g_clk[wave][(i)] = __builtin_readcyclecounter(); \
+    } while (0)
+#else
+#define BLK_MARK(i)
+#endif
+
 // KS1: K steps of S1 that can hold live input (2 for n <= 128, else 4); n is a multiple of 16
 template <int KS1>
 __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restrict__ u, const float *__restrict__ g_in,
                                                           const float *__restrict__ g_out, const float2 *__restrict__ R1,
                                                           const float2 *__restrict__ L1, const float2 *__restrict__ R2,
-                                                          const float2 *__restrict__ L2, const float2 *__restrict__ Kf,
+                                                          const float2 *__restrict__ L2, const f32x4 *__restrict__ Kq,
                                                           float *__restrict__ y, int64_t rows, int H, int n)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
@@ -364,14 +386,32 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
     const uint32_t xa_addr = lds_address(xa), xb_addr = lds_address(xb);
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t r0 = tile * TV, base = r0 * n;
+        BLK_MARK(0);
+        // the kernel entries of S2, (re, im) of elements 16 (4 kg + r) + b0 .. + 3 of the row's channel, requested
+        // first: they are in registers long before S2 needs them
+        f32x4 k01[4], k23[4];
+        {
+            int64_t row = r0 + l16;
+            if (row >= rows) row = rows - 1;
+            const int h = (int)(row % H);
+            const f32x4 *kq = Kq + ((size_t)(h >> 2) * 128 + (wave * 4 + kg) * 8) * 4 + (h & 3);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                k01[r] = kq[(2 * r) * 4];
+                k23[r] = kq[(2 * r + 1) * 4];
+            }
+        }
         for (int q = wave; q < nchunks; q += 4) {
             int64_t at = base + 256 * q + 4 * lane;
             if (at > last_piece) at = last_piece;   // (rows past the end of the batch: never stored)
             dma_16_at(u + at, xa_addr + (uint32_t)q * CH * 4);
             if (g_in) dma_16_at(g_in + at, xb_addr + (uint32_t)q * CH * 4);
         }
+        BLK_MARK(1);
         wait_loads_at_most<0>();
+        BLK_MARK(2);
         __syncthreads();
+        BLK_MARK(3);
 
         // ---- S1: real input, complex R1
         {
@@ -399,13 +439,12 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
                 }
             }
         }
+        BLK_MARK(4);
         __syncthreads();
+        BLK_MARK(5);
 
         // ---- S2: complex L1, then the kernel of the row's channel
         {
-            int64_t row = r0 + l16;
-            if (row >= rows) row = rows - 1;
-            const float2 *kf = Kf + (row % H) * (int64_t)N + b0;
             f32x4 zr[4], zi[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -425,15 +464,15 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
             // rows k = 4 kg + r of blocks i = b0 .. b0 + 3: elements 16 k + i
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const f32x4 k01 = *reinterpret_cast<const f32x4 *>(kf + 16 * (4 * kg + r));       // (re, im) of i = b0, b0 + 1
-                const f32x4 k23 = *reinterpret_cast<const f32x4 *>(kf + 16 * (4 * kg + r) + 2);
-                const f32x4 kre = {k01[0], k01[2], k23[0], k23[2]}, kim = {k01[1], k01[3], k23[1], k23[3]};
+                const f32x4 kre = {k01[r][0], k01[r][2], k23[r][0], k23[r][2]}, kim = {k01[r][1], k01[r][3], k23[r][1], k23[r][3]};
                 const f32x4 a = {zr[0][r], zr[1][r], zr[2][r], zr[3][r]}, b = {zi[0][r], zi[1][r], zi[2][r], zi[3][r]};
                 *reinterpret_cast<f32x4 *>(xa + l16 * CH + 16 * (4 * kg + r) + b0) = a * kre - b * kim;
                 *reinterpret_cast<f32x4 *>(xb + l16 * CH + 16 * (4 * kg + r) + b0) = a * kim + b * kre;
             }
         }
+        BLK_MARK(6);
         __syncthreads();
+        BLK_MARK(7);
 
         // ---- S3: complex R2 on the rows of z
         {
@@ -460,6 +499,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
                 }
             }
         }
+        BLK_MARK(8);
         __syncthreads();   // z is consumed: the output gates land where Re z was while the last factor runs
         if (g_out)
             for (int q = wave; q < nchunks; q += 4) {
@@ -469,6 +509,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
             }
 
         // ---- S4: real part of complex L2
+        BLK_MARK(9);
         f32x4 o[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -480,10 +521,13 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
             }
             o[q] = acc;
         }
+        BLK_MARK(10);
         if (g_out) {
             wait_loads_at_most<0>();
+            BLK_MARK(11);
             __syncthreads();
         }
+        BLK_MARK(12);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int j = 16 * (4 * kg + r) + b0;
@@ -494,12 +538,16 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
                 *reinterpret_cast<f32x4 *>(xb + at) = v;   // (Im z was consumed before the barrier after S3)
             }
         }
+        BLK_MARK(13);
         __syncthreads();
+        BLK_MARK(14);
         for (int q = wave; q < nchunks; q += 4) {
             const int64_t at = base + 256 * q + 4 * lane;
             if (at <= last_piece) *reinterpret_cast<f32x4 *>(y + at) = *reinterpret_cast<const f32x4 *>(xb + q * CH + 4 * lane);
         }
+        BLK_MARK(15);
         __syncthreads();   // before the next tile's rows land
+        BLK_MARK(16);
     }
 }
 
@@ -523,7 +571,7 @@ static int launch(const void *u, const void *g_in, const void *g_out, const unsi
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), LDS_BYTES, s, (const float *)u,                  \
                            (const float *)g_in, (const float *)g_out, (const float2 *)(state + l.R1),              \
                            (const float2 *)(state + l.L1), (const float2 *)(state + l.R2),                         \
-                           (const float2 *)(state + l.L2), (const float2 *)(state + l.Kf), (float *)y, rows, H, n); \
+                           (const float2 *)(state + l.L2), (const f32x4 *)(state + l.Kq), (float *)y, rows, H, n); \
     } while (0)
     if (n <= 128) MONARCH_LAUNCH_BLOCKY16(2);
     else MONARCH_LAUNCH_BLOCKY16(4);
@@ -533,6 +581,13 @@ static int launch(const void *u, const void *g_in, const void *g_out, const unsi
 }
 
 }  // namespace blocky16
+
+#ifdef MONARCH_BLOCKY_CLOCKS
+extern "C" int monarch_debug_blocky_clocks(long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(blocky16::g_clk), sizeof(long long) * 4 * 32);
+}
+#endif
 
 bool blocky_fits(int bs) { return bs >= 2 && bs <= 64; }   // a row twice in LDS as complex float32: 64 KB at bs = 64
 
@@ -555,7 +610,8 @@ int launch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int 
     hipLaunchKernelGGL(factor_kernel, dim3(2 * bs), dim3(256), lds_f, s, Lt, Rt, (const cdouble *)tw, R1, L1, R2, L2, bs, mask);
     if (H > 0)
         hipLaunchKernelGGL(kf_kernel, dim3(H), dim3(THREADS), (size_t)2 * N * sizeof(float2), s, k, (const float2 *)R1,
-                           (const float2 *)L1, reinterpret_cast<float2 *>(st + l.Kf), klen, bs);
+                           (const float2 *)L1, reinterpret_cast<float2 *>(st + l.Kf),
+                           bs == 16 ? reinterpret_cast<float4 *>(st + l.Kq) : (float4 *)nullptr, klen, bs);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
