@@ -424,20 +424,24 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
                 if (g_in) v *= *reinterpret_cast<const f32x4 *>(xb + at);
                 xq[s] = j < n ? v : f32x4{0, 0, 0, 0};
             }
+            // (eight accumulators in turn: an MFMA never waits for the one issued just before it)
+            f32x4 ar[4], ai[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0};
+            for (int q = 0; q < 4; ++q) ar[q] = ai[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
-                for (int s = 0; s < KS1; ++s) {
-                    ar = mfma(R1r[q][s], xq[s][q], ar);
-                    ai = mfma(R1i[q][s], xq[s][q], ai);
+            for (int s = 0; s < KS1; ++s)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    ar[q] = mfma(R1r[q][s], xq[s][q], ar[q]);
+                    ai[q] = mfma(R1i[q][s], xq[s][q], ai[q]);
                 }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    tr[l16 * LD + (4 * kg + r) * RS + b0 + q] = ar[r];
-                    ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[r];
+                    tr[l16 * LD + (4 * kg + r) * RS + b0 + q] = ar[q][r];
+                    ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[q][r];
                 }
-            }
         }
         BLK_MARK(4);
         __syncthreads();
@@ -447,19 +451,25 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
         {
             f32x4 zr[4], zi[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0};
+            for (int q = 0; q < 4; ++q) zr[q] = zi[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const float tre = tr[l16 * LD + (b0 + q) * RS + 4 * kg + s];
-                    const float tim = ti[l16 * LD + (b0 + q) * RS + 4 * kg + s];
-                    ar = mfma(L1r[q][s], tre, ar);
-                    ar = mfma(L1i[q][s], -tim, ar);
-                    ai = mfma(L1r[q][s], tim, ai);
-                    ai = mfma(L1i[q][s], tre, ai);
+            for (int s = 0; s < 4; ++s) {
+                float tre[4], tim[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    tre[q] = tr[l16 * LD + (b0 + q) * RS + 4 * kg + s];
+                    tim[q] = ti[l16 * LD + (b0 + q) * RS + 4 * kg + s];
                 }
-                zr[q] = ar;
-                zi[q] = ai;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    zr[q] = mfma(L1r[q][s], tre[q], zr[q]);
+                    zi[q] = mfma(L1r[q][s], tim[q], zi[q]);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    zr[q] = mfma(L1i[q][s], -tim[q], zr[q]);
+                    zi[q] = mfma(L1i[q][s], tre[q], zi[q]);
+                }
             }
             // rows k = 4 kg + r of blocks i = b0 .. b0 + 3: elements 16 k + i
 #pragma unroll
@@ -482,22 +492,29 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
                 xr[s] = *reinterpret_cast<const f32x4 *>(xa + l16 * CH + 16 * (4 * kg + s) + b0);
                 xi[s] = *reinterpret_cast<const f32x4 *>(xb + l16 * CH + 16 * (4 * kg + s) + b0);
             }
+            f32x4 ar[4], ai[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0};
+            for (int q = 0; q < 4; ++q) ar[q] = ai[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    ar = mfma(R2r[q][s], xr[s][q], ar);
-                    ar = mfma(R2i[q][s], -xi[s][q], ar);
-                    ai = mfma(R2r[q][s], xi[s][q], ai);
-                    ai = mfma(R2i[q][s], xr[s][q], ai);
+            for (int s = 0; s < 4; ++s) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    ar[q] = mfma(R2r[q][s], xr[s][q], ar[q]);
+                    ai[q] = mfma(R2r[q][s], xi[s][q], ai[q]);
                 }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    tr[l16 * LD + (4 * kg + r) * RS + b0 + q] = ar[r];
-                    ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[r];
+                for (int q = 0; q < 4; ++q) {
+                    ar[q] = mfma(R2i[q][s], -xi[s][q], ar[q]);
+                    ai[q] = mfma(R2i[q][s], xr[s][q], ai[q]);
                 }
             }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    tr[l16 * LD + (4 * kg + r) * RS + b0 + q] = ar[q][r];
+                    ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[q][r];
+                }
         }
         BLK_MARK(8);
         __syncthreads();   // z is consumed: the output gates land where Re z was while the last factor runs
@@ -512,14 +529,13 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
         BLK_MARK(9);
         f32x4 o[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            f32x4 acc = {0, 0, 0, 0};
+        for (int q = 0; q < 4; ++q) o[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                acc = mfma(L2r[q][s], tr[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
-                acc = mfma(L2i[q][s], -ti[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
-            }
-            o[q] = acc;
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = mfma(L2r[q][s], tr[l16 * LD + (b0 + q) * RS + 4 * kg + s], o[q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = mfma(L2i[q][s], -ti[l16 * LD + (b0 + q) * RS + 4 * kg + s], o[q]);
         }
         BLK_MARK(10);
         if (g_out) {
