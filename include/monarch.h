@@ -98,6 +98,28 @@ size_t monarch_matmul_backward_workspace_bytes(int64_t batch, int nbR, int r_out
                                                int nbL, int l_out, int l_in, monarch_dtype dt);
 
 /*
+ * General (learned) order-3 Monarch product and its gradients (Sec. 3.1: higher-order Monarch matrices; appendix
+ * definition of order-p Monarch matrices, p = 3).  N = b^3; B1, B2, B3: [b*b blocks][b][b], B1 applied first;
+ *   M = P^R B3 P_(b,b^2,N) B2 P_(b^2,b^3,N) B1 P^R,   P^R the reversal of the three base-b digits of an index.
+ * With j = j2 b^2 + j1 b + j0 (input), m = m2 b^2 + m1 b + m0 (output) and block (p, q) = block p b + q:
+ *   t1[(j0,j1), m0] = sum_j2 B1[(j0,j1)][m0, j2] x[j]
+ *   t2[(m0,j0), m1] = sum_j1 B2[(m0,j0)][m1, j1] t1[(j0,j1), m0]
+ *   y[m]            = sum_j0 B3[(m0,m1)][m2, j0] t2[(m0,j0), m1]
+ * (the factors of the order-3 Monarch DFT of monarch_fft are of this form with complex blocks).
+ * monarch_matmul3: x, y: (batch, N); x, y and the factors of type dt, fp32 arithmetic.
+ * monarch_matmul3_backward: with S = sum_v <dy[v,:], y[v,:]>: dx = M^T dy (type dt) and dB1, dB2, dB3 = dS/dB
+ * (always float32, overwritten; sums over the batch by floating-point atomic adds: the last bits depend on the
+ * order of the additions).  Any of dx, dB1, dB2, dB3 may be NULL (not computed).
+ * Errors: EINVAL (null required pointer with batch > 0, misalignment, overlap), ESHAPE (batch < 0, b outside
+ * [1, 16]), EDTYPE, EHIP.
+ */
+int monarch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,
+                    monarch_dtype dt, monarch_stream_t stream);
+int monarch_matmul3_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
+                             float *dB1, float *dB2, float *dB3, int64_t batch, int b, monarch_dtype dt,
+                             monarch_stream_t stream);
+
+/*
  * Sequence mixer with two general (learned) square order-2 Monarch matrices (Sec. 3.2, Eq. 2, in its gated
  * form): for every sequence b in [0, B) and channel h in [0, H)
  *   y[b,h,:] = g_out[b,h,:] o ( M2 ( K[h,:] o ( M1 ( g_in[b,h,:] o u[b,h,:] ) ) ) ),

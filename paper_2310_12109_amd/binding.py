@@ -35,6 +35,8 @@ _lib.monarch_matmul_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i
 _lib.monarch_matmul_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_matmul_backward_workspace_bytes.restype = _sz
 _lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
+_lib.monarch_matmul3.argtypes = [_vp] * 5 + [_i64, _i, _i, _vp]
+_lib.monarch_matmul3_backward.argtypes = [_vp] * 9 + [_i64, _i, _i, _vp]
 _lib.monarch_mixer.argtypes = [_vp] * 9 + [_i64, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_mixer_workspace_bytes.restype = _sz
 _lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
@@ -57,6 +59,7 @@ EXPORTS = [
     "monarch_strerror", "monarch_last_error", "monarch_permutation_index",
     "monarch_matmul", "monarch_matmul_workspace_bytes",
     "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
+    "monarch_matmul3", "monarch_matmul3_backward",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
     "monarch_blocky_state_bytes", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
@@ -146,6 +149,24 @@ def monarch_matmul_backward(x, R, L, dy, need_dx=True, need_dR=True, need_dL=Tru
     _check(_lib.monarch_matmul_backward(_ptr(x), _ptr(R), _ptr(L), _ptr(dy), _ptr(dx), _ptr(dR), _ptr(dL), batch,
                                         nbR, r_out, r_in, nbL, l_out, l_in, _dt(x), None, 0, _stream()))
     return dx, dR, dL
+
+
+def monarch_matmul3(x, B1, B2, B3, out=None):
+    """y = M x for the order-3 Monarch matrix of the factors B1 (first), B2, B3: (b*b, b, b); x: (batch, b^3)."""
+    b = B1.shape[-1]
+    y = out if out is not None else torch.empty_like(x)
+    _check(_lib.monarch_matmul3(_ptr(x), _ptr(B1), _ptr(B2), _ptr(B3), _ptr(y), x.shape[0], b, _dt(x), _stream()))
+    return y
+
+
+def monarch_matmul3_backward(x, B1, B2, B3, dy, need_dx=True, need_dB=True):
+    """(dx, dB1, dB2, dB3) of sum <dy, monarch_matmul3(x, B1, B2, B3)>; the factor gradients are float32."""
+    b = B1.shape[-1]
+    dx = torch.empty_like(x) if need_dx else None
+    dB = [torch.empty(B1.shape, dtype=torch.float32, device=x.device) if need_dB else None for _ in range(3)]
+    _check(_lib.monarch_matmul3_backward(_ptr(x), _ptr(B1), _ptr(B2), _ptr(B3), _ptr(dy), _ptr(dx), _ptr(dB[0]),
+                                         _ptr(dB[1]), _ptr(dB[2]), x.shape[0], b, _dt(x), _stream()))
+    return (dx, *dB)
 
 
 def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):

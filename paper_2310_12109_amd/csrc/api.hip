@@ -188,6 +188,64 @@ int monarch_matmul_backward(const void *x, const void *R, const void *L, const v
 }
 
 // ---------------------------------------------------------------------------------------------
+// monarch_matmul3 / monarch_matmul3_backward
+// ---------------------------------------------------------------------------------------------
+
+static int check_matmul3(int64_t batch, int b, monarch_dtype dt)
+{
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (batch < 0) return fail(MONARCH_ESHAPE, "negative batch");
+    if (!matmul3_fits(b)) return fail(MONARCH_ESHAPE, "block size %d outside [1, 16] (four rows of b^3 floats must fit in LDS)", b);
+    return MONARCH_OK;
+}
+
+int monarch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,
+                    monarch_dtype dt, monarch_stream_t stream)
+{
+    clear_error();
+    int rc = check_matmul3(batch, b, dt);
+    if (rc) return rc;
+    if (batch == 0) return MONARCH_OK;
+    if (!x || !B1 || !B2 || !B3 || !y) return fail(MONARCH_EINVAL, "x, B1, B2, B3 and y must be non-NULL");
+    if (misaligned(x) || misaligned(B1) || misaligned(B2) || misaligned(B3) || misaligned(y))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt), N = (size_t)b * b * b, act = (size_t)batch * N * es, wb = N * b * es;
+    if (overlaps(y, act, x, act) || overlaps(y, act, B1, wb) || overlaps(y, act, B2, wb) || overlaps(y, act, B3, wb))
+        return fail(MONARCH_EINVAL, "y overlaps an input");
+    return launch_matmul3(x, B1, B2, B3, y, batch, b, dt, (hipStream_t)stream);
+}
+
+int monarch_matmul3_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
+                             float *dB1, float *dB2, float *dB3, int64_t batch, int b, monarch_dtype dt,
+                             monarch_stream_t stream)
+{
+    clear_error();
+    int rc = check_matmul3(batch, b, dt);
+    if (rc) return rc;
+    if (!dx && !dB1 && !dB2 && !dB3) return MONARCH_OK;
+    if (misaligned(x) || misaligned(B1) || misaligned(B2) || misaligned(B3) || misaligned(dy) || misaligned(dx) ||
+        misaligned(dB1) || misaligned(dB2) || misaligned(dB3))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt), N = (size_t)b * b * b, act = (size_t)batch * N * es, wn = N * b;
+    if (batch > 0) {
+        if (!x || !B1 || !B2 || !B3 || !dy) return fail(MONARCH_EINVAL, "x, B1, B2, B3 and dy must be non-NULL");
+        const void *ins[5] = {x, dy, B1, B2, B3};
+        const size_t in_bytes[5] = {act, act, wn * es, wn * es, wn * es};
+        const void *outs[4] = {dx, dB1, dB2, dB3};
+        const size_t out_bytes[4] = {act, wn * sizeof(float), wn * sizeof(float), wn * sizeof(float)};
+        for (int o = 0; o < 4; ++o) {
+            if (!outs[o]) continue;
+            for (int i = 0; i < 5; ++i)
+                if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return fail(MONARCH_EINVAL, "an output overlaps an input");
+            for (int q = o + 1; q < 4; ++q)
+                if (outs[q] && overlaps(outs[o], out_bytes[o], outs[q], out_bytes[q])) return fail(MONARCH_EINVAL, "outputs overlap");
+        }
+    }
+    return launch_matmul3_backward(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, b, dt, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
 // monarch_mixer
 // ---------------------------------------------------------------------------------------------
 

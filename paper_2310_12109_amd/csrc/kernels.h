@@ -90,6 +90,12 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
 bool mixer_fits(int bs);
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                  const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
+// general order-3 Monarch product and its gradients (csrc/matmul3.hip); any of dx, dB1, dB2, dB3 may be null
+bool matmul3_fits(int b);
+int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,
+                   monarch_dtype dt, hipStream_t s);
+int launch_matmul3_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
+                            float *dB1, float *dB2, float *dB3, int64_t batch, int b, monarch_dtype dt, hipStream_t s);
 // polynomial-parameterised Monarch convolution (csrc/blocky.hip): parameter phase and per-batch phase
 bool blocky_fits(int bs);
 size_t blocky_state_bytes(int H, int bs);

@@ -1,0 +1,233 @@
+// General (learned) order-3 Monarch product and its gradients (Sec. 3.1 and the appendix definition of order-p
+// Monarch matrices, p = 3).  N = b^3, three block-diagonal factors B1, B2, B3 of b^2 blocks of b x b, B1 applied
+// first:  M = P^R B3 P_(b,b^2,N) B2 P_(b^2,b^3,N) B1 P^R.  With the input index j = j2 b^2 + j1 b + j0 and the
+// output index m = m2 b^2 + m1 b + m0 (block (p, q) is block p b + q):
+//   t1[(j0,j1), m0] = sum_j2 B1[(j0,j1)][m0, j2] x[j2, j1, j0]
+//   t2[(m0,j0), m1] = sum_j1 B2[(m0,j0)][m1, j1] t1[(j0,j1), m0]
+//   y[m2, m1, m0]   = sum_j0 B3[(m0,m1)][m2, j0] t2[(m0,j0), m1]
+// The permutations are LDS index maps; rows stay on chip between the factors.  fp32 arithmetic on tiles of rows
+// in LDS (the order-3 counterpart of the shape-generic order-2 kernels).
+#include "kernels.h"
+
+namespace monarch {
+
+namespace mm3 {
+
+constexpr int THREADS = 256;
+
+// Where factor S (1, 2, 3) reads the element that meets column c of row (p, q, .) of its blocks.
+template <int S>
+__device__ __forceinline__ int in_index(int p, int q, int c, int b)
+{
+    if (S == 1) return (c * b + q) * b + p;   // x[j2 = c, j1 = q, j0 = p]
+    if (S == 2) return (q * b + c) * b + p;   // t1[(j0 = q, j1 = c), m0 = p]
+    return (p * b + c) * b + q;               // t2[(m0 = p, j0 = c), m1 = q]
+}
+
+// One factor on TV rows: out[v][(p, q, r)] = sum_c W[(p, q)][r, c] in[v][in_index(p, q, c)]; the last factor
+// writes y[r, q, p] instead.
+template <typename T, int TV, int S>
+__device__ __forceinline__ void factor(const float *in, float *out, int N, int b, const T *__restrict__ W)
+{
+    for (int o = threadIdx.x; o < N; o += THREADS) {
+        const int r = o % b, pq = o / b, q = pq % b, p = pq / b;
+        float acc[TV];
+#pragma unroll
+        for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
+        const T *w = W + (size_t)o * b;
+        for (int c = 0; c < b; ++c) {
+            const float wv = to_f32(w[c]);
+            const int at = in_index<S>(p, q, c, b);
+#pragma unroll
+            for (int v = 0; v < TV; ++v) acc[v] = fmaf(wv, in[v * N + at], acc[v]);
+        }
+        const int to = S == 3 ? (r * b + q) * b + p : o;
+#pragma unroll
+        for (int v = 0; v < TV; ++v) out[v * N + to] = acc[v];
+    }
+}
+
+template <typename T, int TV>
+__global__ __launch_bounds__(THREADS) void forward_kernel(const T *__restrict__ x, const T *__restrict__ B1,
+                                                          const T *__restrict__ B2, const T *__restrict__ B3,
+                                                          T *__restrict__ y, int64_t batch, int b)
+{
+    extern __shared__ float lds[];
+    const int N = b * b * b;
+    float *a = lds, *t = lds + TV * N;
+    const int64_t ntiles = (batch + TV - 1) / TV;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t v0 = tile * TV;
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N;
+            a[idx] = v0 + v < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
+        }
+        __syncthreads();
+        factor<T, TV, 1>(a, t, N, b, B1);
+        __syncthreads();
+        factor<T, TV, 2>(t, a, N, b, B2);
+        __syncthreads();
+        factor<T, TV, 3>(a, t, N, b, B3);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS)
+            if (v0 + idx / N < batch) y[v0 * N + idx] = from_f32<T>(t[idx]);
+        __syncthreads();
+    }
+}
+
+// Gradients, one row per pass of the loop (four rows of N floats in LDS: x, t1, t2 and the running gradient).
+// Adjoint of each step, last step first; every entry of dB1, dB2, dB3 receives one atomic add per row.
+template <typename T>
+__global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__ x, const T *__restrict__ B1,
+                                                           const T *__restrict__ B2, const T *__restrict__ B3,
+                                                           const T *__restrict__ dy, T *__restrict__ dx,
+                                                           float *__restrict__ dB1, float *__restrict__ dB2,
+                                                           float *__restrict__ dB3, int64_t batch, int b)
+{
+    extern __shared__ float lds[];
+    const int N = b * b * b;
+    float *xs = lds, *t1 = xs + N, *t2 = t1 + N, *g = t2 + N;
+    for (int64_t v = blockIdx.x; v < batch; v += gridDim.x) {
+        for (int j = threadIdx.x; j < N; j += THREADS) {
+            xs[j] = to_f32(x[v * N + j]);
+            // g3[(m0, m1), m2] = dy[m2, m1, m0]
+            const int m0 = j % b, m1 = (j / b) % b, m2 = j / (b * b);
+            g[(m0 * b + m1) * b + m2] = to_f32(dy[v * N + j]);
+        }
+        __syncthreads();
+        factor<T, 1, 1>(xs, t1, N, b, B1);
+        __syncthreads();
+        factor<T, 1, 2>(t1, t2, N, b, B2);
+        __syncthreads();
+        // dB3[(p, q)][r, c] += g3[(p, q), r] t2[(p, c), q]
+        if (dB3)
+            for (int e = threadIdx.x; e < N * b; e += THREADS) {
+                const int c = e % b, o = e / b, pq = o / b, q = pq % b, p = pq / b;
+                atomicAdd(dB3 + e, g[o] * t2[in_index<3>(p, q, c, b)]);
+            }
+        __syncthreads();
+        // g2[(p, c), q] = sum_r B3[(p, q)][r, c] g3[(p, q), r]   -> over t2
+        for (int o2 = threadIdx.x; o2 < N; o2 += THREADS) {
+            const int q = o2 % b, pc = o2 / b, c = pc % b, p = pc / b;
+            float acc = 0.0f;
+            for (int r = 0; r < b; ++r) acc = fmaf(to_f32(B3[(((size_t)p * b + q) * b + r) * b + c]), g[(p * b + q) * b + r], acc);
+            t2[o2] = acc;
+        }
+        __syncthreads();
+        // dB2[(p, q)][r, c] += g2[(p, q), r] t1[(q, c), p]
+        if (dB2)
+            for (int e = threadIdx.x; e < N * b; e += THREADS) {
+                const int c = e % b, o = e / b, pq = o / b, q = pq % b, p = pq / b;
+                atomicAdd(dB2 + e, t2[o] * t1[in_index<2>(p, q, c, b)]);
+            }
+        __syncthreads();
+        // g1[(q, c), p] = sum_r B2[(p, q)][r, c] g2[(p, q), r]   -> over g
+        for (int o1 = threadIdx.x; o1 < N; o1 += THREADS) {
+            const int p = o1 % b, qc = o1 / b, c = qc % b, q = qc / b;
+            float acc = 0.0f;
+            for (int r = 0; r < b; ++r) acc = fmaf(to_f32(B2[(((size_t)p * b + q) * b + r) * b + c]), t2[(p * b + q) * b + r], acc);
+            g[o1] = acc;
+        }
+        __syncthreads();
+        // dB1[(p, q)][r, c] += g1[(p, q), r] x[c, q, p]
+        if (dB1)
+            for (int e = threadIdx.x; e < N * b; e += THREADS) {
+                const int c = e % b, o = e / b, pq = o / b, q = pq % b, p = pq / b;
+                atomicAdd(dB1 + e, g[o] * xs[in_index<1>(p, q, c, b)]);
+            }
+        // dx[c, q, p] = sum_r B1[(p, q)][r, c] g1[(p, q), r]
+        if (dx)
+            for (int j = threadIdx.x; j < N; j += THREADS) {
+                const int p = j % b, q = (j / b) % b, c = j / (b * b);
+                float acc = 0.0f;
+                for (int r = 0; r < b; ++r) acc = fmaf(to_f32(B1[(((size_t)p * b + q) * b + r) * b + c]), g[(p * b + q) * b + r], acc);
+                dx[v * N + j] = from_f32<T>(acc);
+            }
+        __syncthreads();
+    }
+}
+
+__global__ void fill3_kernel(float *a, float *b, float *c, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        if (a) a[i] = 0.0f;
+        if (b) b[i] = 0.0f;
+        if (c) c[i] = 0.0f;
+    }
+}
+
+static int compute_units(int *ncu)
+{
+    int dev = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    return MONARCH_OK;
+}
+
+template <typename T>
+static int launch_forward(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,
+                          hipStream_t s)
+{
+    const int N = b * b * b;
+    int tv = 8;
+    while (tv > 1 && (size_t)2 * tv * N * sizeof(float) > 64 * 1024) tv >>= 1;
+    const size_t lds = (size_t)2 * tv * N * sizeof(float);
+    int ncu = 0;
+    if (int rc = compute_units(&ncu)) return rc;
+    const int64_t ntiles = (batch + tv - 1) / tv;
+    int64_t grid = (int64_t)ncu * (lds <= 32 * 1024 ? 4 : 2);
+    if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_MM3(TVV)                                                                                  \
+    hipLaunchKernelGGL((forward_kernel<T, TVV>), dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)x,      \
+                       (const T *)B1, (const T *)B2, (const T *)B3, (T *)y, batch, b)
+    switch (tv) {
+    case 8: MONARCH_LAUNCH_MM3(8); break;
+    case 4: MONARCH_LAUNCH_MM3(4); break;
+    case 2: MONARCH_LAUNCH_MM3(2); break;
+    default: MONARCH_LAUNCH_MM3(1); break;
+    }
+#undef MONARCH_LAUNCH_MM3
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+template <typename T>
+static int launch_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
+                           float *dB1, float *dB2, float *dB3, int64_t batch, int b, hipStream_t s)
+{
+    const int N = b * b * b;
+    if (dB1 || dB2 || dB3) hipLaunchKernelGGL(fill3_kernel, dim3(64), dim3(256), 0, s, dB1, dB2, dB3, (size_t)N * b);
+    if (batch > 0) {
+        int ncu = 0;
+        if (int rc = compute_units(&ncu)) return rc;
+        int64_t grid = 2 * (int64_t)ncu;
+        if (grid > batch) grid = batch;
+        hipLaunchKernelGGL((backward_kernel<T>), dim3((unsigned)grid), dim3(THREADS), (size_t)4 * N * sizeof(float), s,
+                           (const T *)x, (const T *)B1, (const T *)B2, (const T *)B3, (const T *)dy, (T *)dx, dB1, dB2,
+                           dB3, batch, b);
+    }
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+}  // namespace mm3
+
+bool matmul3_fits(int b) { return b >= 1 && b <= 16; }   // four rows of b^3 floats in 64 KB of LDS
+
+int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,
+                   monarch_dtype dt, hipStream_t s)
+{
+    if (batch == 0) return MONARCH_OK;
+    if (dt == MONARCH_F32) return mm3::launch_forward<float>(x, B1, B2, B3, y, batch, b, s);
+    return mm3::launch_forward<bf16_t>(x, B1, B2, B3, y, batch, b, s);
+}
+
+int launch_matmul3_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
+                            float *dB1, float *dB2, float *dB3, int64_t batch, int b, monarch_dtype dt, hipStream_t s)
+{
+    if (dt == MONARCH_F32) return mm3::launch_backward<float>(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, b, s);
+    return mm3::launch_backward<bf16_t>(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, b, s);
+}
+
+}  // namespace monarch

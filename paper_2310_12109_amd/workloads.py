@@ -45,6 +45,15 @@ def monarch_matmul_rect_inputs(batch, nbR, r_out, r_in, nbL, l_out, l_in, seed=0
     return _finish({"x": x, "R": R, "L": L}, bf16)
 
 
+def monarch_matmul3_inputs(batch, b, seed=0, bf16=False):
+    """General order-3 Monarch product, N = b^3: x, dy ~ N(0, 1); three factors of b*b blocks ~ N(0, 1/b)."""
+    rng = np.random.default_rng(seed)
+    d = {"x": rng.standard_normal((batch, b ** 3)), "dy": rng.standard_normal((batch, b ** 3))}
+    for name in ("B1", "B2", "B3"):
+        d[name] = rng.standard_normal((b * b, b, b)) / np.sqrt(b)
+    return _finish(d, bf16)
+
+
 def mixer_inputs(B, H, b, seed=0, gates=(True, True), bf16=False):
     """Learned-Monarch sequence mixer: u, gates ~ N(0, 1) of shape (B, H, b*b), kernel K ~ N(0, 1) of shape
     (H, b*b) in the transform domain, four factors ~ N(0, 1/b) of shape (b, b, b)."""

@@ -91,6 +91,30 @@ def test_matmul_backward_rejects_bad_arguments(lib):
     assert f(A, B, C, D, E, F, G, 4, 256, 256, 256, 256, 256, 256, 0, None, 0, None) == ESHAPE   # too wide
 
 
+def test_matmul3_rejects_bad_arguments(lib):
+    f = lib.monarch_matmul3
+    f.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    x, B1, B2, B3, y = (FAKE * m for m in (1, 64, 128, 192, 256))   # 256 KB apart
+    assert f(None, B1, B2, B3, y, 4, 8, 0, None) == EINVAL
+    assert f(x, B1, B2, None, y, 4, 8, 0, None) == EINVAL
+    assert f(x, B1, B2, B3, x, 4, 8, 0, None) == EINVAL        # y aliases x
+    assert f(x + 4, B1, B2, B3, y, 4, 8, 0, None) == EINVAL    # misaligned
+    assert f(x, B1, B2, B3, y, -1, 8, 0, None) == ESHAPE
+    assert f(x, B1, B2, B3, y, 4, 17, 0, None) == ESHAPE       # b^3 beyond the on-chip tile
+    assert f(x, B1, B2, B3, y, 4, 0, 0, None) == ESHAPE
+    assert f(x, B1, B2, B3, y, 4, 8, 2, None) == EDTYPE
+    assert f(None, None, None, None, None, 0, 8, 0, None) == 0
+    g = lib.monarch_matmul3_backward
+    g.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    dy, dx, d1, d2, d3 = (FAKE * m for m in (320, 384, 448, 512, 576))
+    assert g(x, B1, B2, B3, None, dx, d1, d2, d3, 4, 8, 0, None) == EINVAL       # dy missing
+    assert g(x, B1, B2, B3, dy, x, d1, d2, d3, 4, 8, 0, None) == EINVAL          # dx aliases x
+    assert g(x, B1, B2, B3, dy, dx, B1, d2, d3, 4, 8, 0, None) == EINVAL         # dB1 aliases B1
+    assert g(x, B1, B2, B3, dy, dx, d1, d1, d3, 4, 8, 0, None) == EINVAL         # dB1 aliases dB2
+    assert g(x, B1, B2, B3, dy, dx, d1, d2, d3, 4, 17, 0, None) == ESHAPE
+    assert g(x, B1, B2, B3, dy, None, None, None, None, 4, 8, 0, None) == 0      # nothing asked for
+
+
 def test_mixer_rejects_bad_arguments(lib):
     f = lib.monarch_mixer
     f.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
