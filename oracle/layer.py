@@ -1,0 +1,38 @@
+"""CPU oracle for the basic M2 layer (Sec. 3.2, Eq. 2 and its dimension-mixing counterpart, with the
+non-linearity, skip connection and layer normalisation of the paper's basic implementation).
+
+TEST INFRASTRUCTURE ONLY.  Plain numpy float64 with the four Monarch matrices materialised densely
+(oracle.monarch_dense), so that every step is a dense matrix product or an elementwise operation:
+    X~ = ( M2 act( K_n o (M1 X^T) ) )^T           mix along the sequence, one kernel row per feature
+    Y  = M4 act( k_d o (M3 X~) )                  mix along the features, one kernel shared by all positions
+    out = LayerNorm(Y + X~)                       over the features, biased variance, affine
+X: (B, n, d); M1, M2: n x n; M3, M4: d x d; K_n: (d, n); k_d: (d,).  Factor roles as in monarch_matmul: R is the
+factor applied first.
+"""
+import numpy as np
+
+from . import monarch_dense
+
+
+def _act(a, act):
+    if act == "relu":
+        return np.maximum(a, 0.0)
+    assert act == "none"
+    return a
+
+
+def m2_layer(x, seq, n_kernel, dim, d_kernel, gamma, beta, eps=1e-5, act="relu"):
+    """seq = (R1, L1, R2, L2), dim = (R3, L3, R4, L4).  Returns (out, X~)."""
+    x = np.asarray(x, dtype=np.float64)
+    M1, M2 = monarch_dense(seq[0], seq[1]), monarch_dense(seq[2], seq[3])
+    M3, M4 = monarch_dense(dim[0], dim[1]), monarch_dense(dim[2], dim[3])
+    Kn, kd = np.asarray(n_kernel, dtype=np.float64), np.asarray(d_kernel, dtype=np.float64)
+    xt = x.transpose(0, 2, 1)                                           # (B, d, n)
+    s = _act(np.einsum("ij,bhj->bhi", M1, xt) * Kn[None], act)
+    xtil = np.einsum("ij,bhj->bhi", M2, s).transpose(0, 2, 1)           # (B, n, d)
+    z = _act(np.einsum("ij,btj->bti", M3, xtil) * kd[None, None], act)
+    r = np.einsum("ij,btj->bti", M4, z) + xtil
+    mean = r.mean(axis=-1, keepdims=True)
+    var = ((r - mean) ** 2).mean(axis=-1, keepdims=True)
+    out = (r - mean) / np.sqrt(var + eps) * np.asarray(gamma, dtype=np.float64) + np.asarray(beta, dtype=np.float64)
+    return out, xtil

@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mixer blocky c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mm3 mixer blocky c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -107,6 +107,27 @@ def mixer(B, H, reps):
     _report(f"mixer fp32 N=256, B={B} H={H}", _time(calls, reps), nbytes, rows * 4 * 2 * 256 * 16, len(calls))
 
 
+def matmul3(b, batch, reps):
+    """General order-3 Monarch product and its gradients, fp32: 2 N floats per row forward, 3 N backward."""
+    N = b ** 3
+    f = [_rnd(b * b, b, b, dt=torch.float32, scale=b ** -0.5) for _ in range(3)]
+
+    def make_fwd():
+        x = _rnd(batch, N, dt=torch.float32)
+        y = torch.empty_like(x)
+        return lambda: binding.monarch_matmul3(x, *f, out=y)
+
+    def make_bwd():
+        x, dy = _rnd(batch, N, dt=torch.float32), _rnd(batch, N, dt=torch.float32)
+        return lambda: binding.monarch_matmul3_backward(x, *f, dy)
+    nb = 2 * batch * N * 4 + 3 * N * b * 4
+    calls = _sets(make_fwd, nb)
+    _report(f"order-3 matmul fp32 b={b} N={N}, batch {batch}", _time(calls, reps), nb, batch * 3 * 2 * N * b, len(calls))
+    nb = 3 * batch * N * 4 + 6 * N * b * 4
+    calls = _sets(make_bwd, nb)
+    _report(f"order-3 backward fp32 b={b} N={N}, batch {batch}", _time(calls, reps), nb, batch * 8 * 2 * N * b, len(calls))
+
+
 def blocky(B, H, reps):
     """Causal convolution with a polynomial-parameterised Monarch matrix, N = 256, n = 128, fp32: u and both gates
     read, y written (2 KB per row); 704 complex-arithmetic MFMAs of 2048 FLOP per 16 rows."""
@@ -207,6 +228,9 @@ def main():
     if want("mixer"):
         mixer(8, 768, 100)
         mixer(1024, 768, 5)
+    if want("mm3"):
+        matmul3(8, 16384, 10)
+        matmul3(16, 4096, 10)
     if want("blocky"):
         blocky(8, 768, 100)
         blocky(1024, 768, 5)

@@ -54,6 +54,20 @@ def monarch_matmul3_inputs(batch, b, seed=0, bf16=False):
     return _finish(d, bf16)
 
 
+def m2_layer_inputs(B, bn, bd, seed=0, bf16=False):
+    """Basic M2 layer: x ~ N(0, 1) of shape (B, n, d), n = bn^2, d = bd^2; eight factors ~ N(0, 1/block size);
+    kernels n_kernel (d, n), d_kernel (d,) ~ N(0, 1); layer-norm weight 1 + N(0, 0.1^2), bias N(0, 0.1^2)."""
+    rng = np.random.default_rng(seed)
+    n, d = bn * bn, bd * bd
+    w = {"x": rng.standard_normal((B, n, d)), "n_kernel": rng.standard_normal((d, n)), "d_kernel": rng.standard_normal(d),
+         "gamma": 1.0 + 0.1 * rng.standard_normal(d), "beta": 0.1 * rng.standard_normal(d)}
+    for name in ("R1", "L1", "R2", "L2"):
+        w[name] = rng.standard_normal((bn, bn, bn)) / np.sqrt(bn)
+    for name in ("R3", "L3", "R4", "L4"):
+        w[name] = rng.standard_normal((bd, bd, bd)) / np.sqrt(bd)
+    return _finish(w, bf16)
+
+
 def mixer_inputs(B, H, b, seed=0, gates=(True, True), bf16=False):
     """Learned-Monarch sequence mixer: u, gates ~ N(0, 1) of shape (B, H, b*b), kernel K ~ N(0, 1) of shape
     (H, b*b) in the transform domain, four factors ~ N(0, 1/b) of shape (b, b, b)."""
