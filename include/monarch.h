@@ -138,6 +138,27 @@ int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_
 size_t monarch_mixer_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt);
 
 /*
+ * The basic M2 layer (Sec. 3.2: Eq. 2 for the sequence axis and its counterpart for the feature axis, with the
+ * non-linearity, skip connection and layer normalisation of the paper's basic implementation):
+ *   X~ = ( M2 act( K_n o (M1 X^T) ) )^T           per sequence; K_n: (d, n), one kernel row per feature
+ *   Y  = M4 act( k_d o (M3 X~) )                  per position;  k_d: (d,)
+ *   y  = LayerNorm(Y + X~)                        over the features: biased variance, eps, weight gamma, bias beta
+ * x, y: (B, n, d), n = bn^2, d = bd^2.  M1, M2 = P L P R P with blocks [bn][bn][bn] (R applied first, as in
+ * monarch_matmul); M3, M4 with blocks [bd][bd][bd].  act: 0 none, 1 ReLU.  All tensors device memory of type dt,
+ * float32 arithmetic.  Two kernels: the sequence mixer reads x and writes X~ in (B, n, d) order directly (no
+ * transpose pass), the dimension mixer fuses the skip connection and the normalisation into its store.  ws holds
+ * X~: monarch_m2_layer_workspace_bytes(B, n, d, dt) bytes of device memory, owned by the caller.
+ * Errors: EINVAL (null or misaligned pointer, act, eps, overlap of x, y, ws), ESHAPE (B < 0, block sizes),
+ * EWORKSPACE, EDTYPE, EHIP.
+ */
+int monarch_m2_layer(const void *x, void *y, int64_t B, int bn, int bd,
+                     const void *R1, const void *L1, const void *R2, const void *L2, const void *n_kernel,
+                     const void *R3, const void *L3, const void *R4, const void *L4, const void *d_kernel,
+                     const void *ln_gamma, const void *ln_beta, float eps, int act,
+                     monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_m2_layer_workspace_bytes(int64_t B, int n, int d, monarch_dtype dt);
+
+/*
  * Convolution with a polynomial-parameterised ("blocky") Monarch matrix (appendix: the blocky Monarch algorithm,
  * the masking lemma for causality, the blocky Monarch convolution and its causality theorem).
  *

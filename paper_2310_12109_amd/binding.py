@@ -37,6 +37,9 @@ _lib.monarch_matmul_backward_workspace_bytes.restype = _sz
 _lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
 _lib.monarch_matmul3.argtypes = [_vp] * 5 + [_i64, _i, _i, _vp]
 _lib.monarch_matmul3_backward.argtypes = [_vp] * 9 + [_i64, _i, _i, _vp]
+_lib.monarch_m2_layer.argtypes = [_vp, _vp, _i64, _i, _i] + [_vp] * 12 + [ctypes.c_float, _i, _i, _vp, _sz, _vp]
+_lib.monarch_m2_layer_workspace_bytes.restype = _sz
+_lib.monarch_m2_layer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
 _lib.monarch_mixer.argtypes = [_vp] * 9 + [_i64, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_mixer_workspace_bytes.restype = _sz
 _lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
@@ -61,6 +64,7 @@ EXPORTS = [
     "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
     "monarch_matmul3", "monarch_matmul3_backward",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
+    "monarch_m2_layer", "monarch_m2_layer_workspace_bytes",
     "monarch_blocky_state_bytes", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
@@ -176,6 +180,20 @@ def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):
     y = out if out is not None else torch.empty_like(u)
     _check(_lib.monarch_mixer(_ptr(u), _ptr(K), _ptr(g_in), _ptr(g_out), _ptr(R1), _ptr(L1), _ptr(R2), _ptr(L2), _ptr(y),
                               B, H, bs, _dt(u), None, 0, _stream()))
+    return y
+
+
+def monarch_m2_layer(x, seq, n_kernel, dim, d_kernel, gamma, beta, eps=1e-5, act=1, ws=None, out=None):
+    """LayerNorm(M4 act(k_d * M3 X~) + X~), X~ = (M2 act(K_n * M1 x^T))^T; x: (B, n, d); seq = (R1, L1, R2, L2),
+    dim = (R3, L3, R4, L4)."""
+    B, n, d = x.shape
+    bn, bd = seq[0].shape[0], dim[0].shape[0]
+    y = out if out is not None else torch.empty_like(x)
+    need = _lib.monarch_m2_layer_workspace_bytes(B, n, d, _dt(x))
+    ws, wsb = _workspace(max(need, 16), ws, x.device)
+    _check(_lib.monarch_m2_layer(_ptr(x), _ptr(y), B, bn, bd, *(_ptr(t) for t in seq), _ptr(n_kernel),
+                                 *(_ptr(t) for t in dim), _ptr(d_kernel), _ptr(gamma), _ptr(beta), eps, act, _dt(x),
+                                 _ptr(ws), wsb, _stream()))
     return y
 
 

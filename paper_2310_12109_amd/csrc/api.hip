@@ -273,7 +273,60 @@ int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_
     const size_t in_bytes[8] = {act, act, act, (size_t)H * N * es, wb, wb, wb, wb};
     for (int i = 0; i < 8; ++i)
         if (ins[i] && overlaps(y, act, ins[i], in_bytes[i])) return fail(MONARCH_EINVAL, "y overlaps an input");
-    return launch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, dt, (hipStream_t)stream);
+    return launch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, dt, MixOpt(), (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// monarch_m2_layer
+// ---------------------------------------------------------------------------------------------
+
+size_t monarch_m2_layer_workspace_bytes(int64_t B, int n, int d, monarch_dtype dt)
+{
+    if (B <= 0 || n <= 0 || d <= 0 || (dt != MONARCH_F32 && dt != MONARCH_BF16)) return 0;
+    return align_up((size_t)B * n * d * dtype_size(dt), 256);
+}
+
+int monarch_m2_layer(const void *x, void *y, int64_t B, int bn, int bd,
+                     const void *R1, const void *L1, const void *R2, const void *L2, const void *n_kernel,
+                     const void *R3, const void *L3, const void *R4, const void *L4, const void *d_kernel,
+                     const void *ln_gamma, const void *ln_beta, float eps, int act,
+                     monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    clear_error();
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (B < 0) return fail(MONARCH_ESHAPE, "negative batch");
+    if (bn < 1 || bd < 1 || !mixer_fits(bn) || !mixer_fits(bd))
+        return fail(MONARCH_ESHAPE, "block sizes %d, %d: a row of bs^2 elements must fit in LDS twice", bn, bd);
+    if (act != 0 && act != 1) return fail(MONARCH_EINVAL, "activation must be 0 (none) or 1 (ReLU)");
+    if (!(eps >= 0.0f)) return fail(MONARCH_EINVAL, "eps must be >= 0");
+    if (B == 0) return MONARCH_OK;
+    const int n = bn * bn, d = bd * bd;
+    if (B > INT64_MAX / ((int64_t)n * d)) return fail(MONARCH_ESHAPE, "B * n * d overflows");
+    const void *req[15] = {x, y, R1, L1, R2, L2, n_kernel, R3, L3, R4, L4, d_kernel, ln_gamma, ln_beta, ws};
+    for (int i = 0; i < 15; ++i) {
+        if (!req[i]) return fail(MONARCH_EINVAL, "every pointer argument must be non-NULL");
+        if (misaligned(req[i])) return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    }
+    const size_t need = monarch_m2_layer_workspace_bytes(B, n, d, dt);
+    if (ws_bytes < need) return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    const size_t act_bytes = (size_t)B * n * d * dtype_size(dt);
+    if (overlaps(y, act_bytes, x, act_bytes) || overlaps(ws, need, x, act_bytes) || overlaps(ws, need, y, act_bytes))
+        return fail(MONARCH_EINVAL, "x, y and the workspace must not overlap");
+    // sequence mixer: rows (b, feature), positions along the row; reads x and writes X~ in (B, n, d) order
+    MixOpt seq;
+    seq.act = act;
+    seq.transposed = 1;
+    rc = launch_mixer(x, n_kernel, nullptr, nullptr, R1, L1, R2, L2, ws, B * d, d, bn, dt, seq, (hipStream_t)stream);
+    if (rc) return rc;
+    // dimension mixer: rows (b, position), one kernel row for all of them; skip connection and layer norm fused
+    MixOpt dim;
+    dim.act = act;
+    dim.layer_norm = 1;
+    dim.gamma = ln_gamma;
+    dim.beta = ln_beta;
+    dim.eps = eps;
+    return launch_mixer(ws, d_kernel, nullptr, nullptr, R3, L3, R4, L4, y, B * n, 1, bd, dt, dim, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------------------------

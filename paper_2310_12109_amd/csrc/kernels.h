@@ -87,9 +87,17 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
                            float *dL, int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
                            monarch_dtype dt, hipStream_t s);
 // sequence mixer with two general square order-2 Monarch matrices (csrc/mixer.hip); g_in, g_out may be null
+struct MixOpt {
+    int act = 0;             // between the kernel product and the second matrix: 0 none, 1 ReLU
+    int transposed = 0;      // u, gates and y are (B, N, H) instead of (B, H, N)
+    int layer_norm = 0;      // y = LayerNorm(result + u) over the row, with gamma, beta (type dt, N entries), eps
+    const void *gamma = nullptr, *beta = nullptr;
+    float eps = 0.0f;
+};
 bool mixer_fits(int bs);
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                 const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
+                 const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt,
+                 const MixOpt &opt, hipStream_t s);
 // general order-3 Monarch product and its gradients (csrc/matmul3.hip); any of dx, dB1, dB2, dB3 may be null
 bool matmul3_fits(int b);
 int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,

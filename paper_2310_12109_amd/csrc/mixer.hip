@@ -4,10 +4,17 @@
 // K is the kernel in the transform domain, one row per channel.  (With M1 the DFT and M2 its inverse this is
 // the convolution of monarch_causal_conv; here the matrices are arbitrary real ones.)  A row never leaves the
 // chip between its load and its store: both products, the kernel product and the gates are fused.
+//
+// Options (MixOpt) turn the same kernels into the two halves of the paper's basic M2 layer: an activation between
+// the kernel product and the second matrix; u and y addressed as (B, N, H) instead of (B, H, N), so that the
+// sequence mixer reads and writes the layer's (batch, position, feature) tensors without a transpose pass; and an
+// epilogue y = LayerNorm(result + u) over the row (skip connection and normalisation of the dimension mixer).
 #include "kernels.h"
 #include "lds_dma.h"
 
 namespace monarch {
+
+__device__ __forceinline__ float mix_act(float v, int act) { return act == 1 ? fmaxf(v, 0.0f) : v; }
 
 // ---- any block size: fp32 arithmetic on tiles of rows in LDS ------------------------------------------
 namespace mixg {
@@ -41,11 +48,14 @@ __global__ __launch_bounds__(THREADS) void mixer_kernel(const T *__restrict__ u,
                                                         const T *__restrict__ g_in, const T *__restrict__ g_out,
                                                         const T *__restrict__ R1, const T *__restrict__ L1,
                                                         const T *__restrict__ R2, const T *__restrict__ L2,
-                                                        T *__restrict__ y, int64_t rows, int H, int bs)
+                                                        T *__restrict__ y, int64_t rows, int H, int bs,
+                                                        const MixOpt opt)
 {
     extern __shared__ float lds[];
     const int N = bs * bs;
     float *a = lds, *t = lds + TV * N;
+    // element j of row r = b H + h: (B, H, N) or, transposed, (B, N, H)
+    auto at = [&](int64_t r, int j) -> int64_t { return opt.transposed ? ((r / H) * N + j) * H + r % H : r * N + j; };
     const int64_t ntiles = (rows + TV - 1) / TV;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t r0 = tile * TV;
@@ -53,8 +63,8 @@ __global__ __launch_bounds__(THREADS) void mixer_kernel(const T *__restrict__ u,
             const int v = idx / N, j = idx - v * N;
             float x = 0.0f;
             if (r0 + v < rows) {
-                x = to_f32(u[(r0 + v) * N + j]);
-                if (g_in) x *= to_f32(g_in[(r0 + v) * N + j]);
+                x = to_f32(u[at(r0 + v, j)]);
+                if (g_in) x *= to_f32(g_in[at(r0 + v, j)]);
             }
             a[idx] = x;
         }
@@ -65,19 +75,47 @@ __global__ __launch_bounds__(THREADS) void mixer_kernel(const T *__restrict__ u,
         __syncthreads();
         for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
             const int v = idx / N, j = idx - v * N;
-            if (r0 + v < rows) a[idx] *= to_f32(K[((r0 + v) % H) * (int64_t)N + j]);
+            if (r0 + v < rows) a[idx] = mix_act(a[idx] * to_f32(K[((r0 + v) % H) * (int64_t)N + j]), opt.act);
         }
         __syncthreads();
         factor<T, TV>(a, t, N, bs, R2, bs, 1, bs, 1);
         __syncthreads();
         factor<T, TV>(t, a, N, bs, L2, 1, bs, bs, 1);
         __syncthreads();
-        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
-            const int v = idx / N, j = idx - v * N;
-            if (r0 + v < rows) {
-                float o = a[idx];
-                if (g_out) o *= to_f32(g_out[(r0 + v) * N + j]);
-                y[(r0 + v) * N + j] = from_f32<T>(o);
+        if (opt.layer_norm) {
+            // rows of result + u; wave w normalises rows w, w + 4, ... (two passes: mean, then variance)
+            for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+                const int v = idx / N, j = idx - v * N;
+                if (r0 + v < rows) {
+                    float o = a[idx];
+                    if (g_out) o *= to_f32(g_out[at(r0 + v, j)]);
+                    a[idx] = o + to_f32(u[at(r0 + v, j)]);
+                }
+            }
+            __syncthreads();
+            const int lane = threadIdx.x & 63;
+            for (int v = threadIdx.x >> 6; v < TV; v += THREADS / 64) {
+                float sum = 0.0f;
+                for (int j = lane; j < N; j += 64) sum += a[v * N + j];
+                for (int m = 32; m; m >>= 1) sum += __shfl_xor(sum, m);
+                const float mean = sum / N;
+                float sq = 0.0f;
+                for (int j = lane; j < N; j += 64) sq += (a[v * N + j] - mean) * (a[v * N + j] - mean);
+                for (int m = 32; m; m >>= 1) sq += __shfl_xor(sq, m);
+                const float rstd = rsqrtf(sq / N + opt.eps);
+                if (r0 + v < rows)
+                    for (int j = lane; j < N; j += 64)
+                        y[at(r0 + v, j)] = from_f32<T>((a[v * N + j] - mean) * rstd * to_f32(((const T *)opt.gamma)[j]) +
+                                                       to_f32(((const T *)opt.beta)[j]));
+            }
+        } else {
+            for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+                const int v = idx / N, j = idx - v * N;
+                if (r0 + v < rows) {
+                    float o = a[idx];
+                    if (g_out) o *= to_f32(g_out[at(r0 + v, j)]);
+                    y[at(r0 + v, j)] = from_f32<T>(o);
+                }
             }
         }
         __syncthreads();
@@ -86,7 +124,8 @@ __global__ __launch_bounds__(THREADS) void mixer_kernel(const T *__restrict__ u,
 
 template <typename T>
 static int launch_typed(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                        const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, hipStream_t s)
+                        const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, const MixOpt &opt,
+                        hipStream_t s)
 {
     const int N = bs * bs;
     int tv = 8;
@@ -107,7 +146,7 @@ static int launch_typed(const void *u, const void *K, const void *g_in, const vo
                                                   (int)lds));                                                       \
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)u, (const T *)K,           \
                            (const T *)g_in, (const T *)g_out, (const T *)R1, (const T *)L1, (const T *)R2,          \
-                           (const T *)L2, (T *)y, rows, H, bs);                                                     \
+                           (const T *)L2, (T *)y, rows, H, bs, opt);                                                \
     } while (0)
     switch (tv) {
     case 8: MONARCH_LAUNCH_MIXG(8); break;
@@ -138,7 +177,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int B = 16, N = 256, TV = 16;
 constexpr int LDX = N + 4;                 // pitch of the row buffers
 constexpr int RS = 18, LD = B * RS + 3;    // tile: element (v, p, q) at v LD + p RS + q
-constexpr size_t LDS_BYTES = sizeof(float) * (2 * TV * LDX + TV * LD);
+constexpr int STATS = 4 * TV;              // per wave and row: a partial sum (layer norm)
+constexpr size_t LDS_BYTES = sizeof(float) * (2 * TV * LDX + TV * LD + STATS);
 
 __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
 {
@@ -150,12 +190,14 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
                                                            const float *__restrict__ g_in, const float *__restrict__ g_out,
                                                            const float *__restrict__ R1, const float *__restrict__ L1,
                                                            const float *__restrict__ R2, const float *__restrict__ L2,
-                                                           float *__restrict__ y, int64_t rows, int H)
+                                                           float *__restrict__ y, int64_t rows, int H,
+                                                           const MixOpt opt)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float *xs = smem;                  // [TV][LDX]  rows of u, at the end the rows of y
     float *zs = xs + TV * LDX;         // [TV][LDX]  rows of g_in, then the rows between M1 and M2, then g_out
     float *tt = zs + TV * LDX;         // tile between the two factors of a matrix: (v, i, a)
+    float *stats = tt + TV * LD;       // [4 waves][TV]
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
     const int b0 = 4 * wave;
@@ -177,13 +219,24 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
     const uint32_t xs_addr = lds_address(xs), zs_addr = lds_address(zs);
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t r0 = tile * TV;
-        // rows in: wave w fetches rows 4 w .. 4 w + 3 (rows past the end: the last one, never stored)
+        // (B, N, H) layout: the 16 rows of a tile are 16 neighbouring channels of one sequence (H is a multiple of
+        // 16), 64 contiguous bytes per position; lane (v = l16, kg) moves positions 4 t + kg of row v
+        const int64_t tbase = (r0 / H) * (int64_t)N * H + r0 % H;
+        if (opt.transposed) {
+            for (int t = wave; t < N / 4; t += 4) {
+                const int j = 4 * t + kg;
+                xs[l16 * LDX + j] = u[tbase + (int64_t)j * H + l16];
+                if (GIN) zs[l16 * LDX + j] = g_in[tbase + (int64_t)j * H + l16];
+            }
+        } else {
+            // rows in: wave w fetches rows 4 w .. 4 w + 3 (rows past the end: the last one, never stored)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            int64_t r = r0 + b0 + q;
-            if (r >= rows) r = rows - 1;
-            dma_16_at(u + r * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
-            if (GIN) dma_16_at(g_in + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            for (int q = 0; q < 4; ++q) {
+                int64_t r = r0 + b0 + q;
+                if (r >= rows) r = rows - 1;
+                dma_16_at(u + r * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
+                if (GIN) dma_16_at(g_in + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            }
         }
         // the kernel entries this lane multiplies in S2: K[h_v][16 (4 kg + r) + b0 .. + 3], v = l16
         f32x4 kq[4];
@@ -233,16 +286,24 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             *reinterpret_cast<f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0) =
-                f32x4{z[0][r] * kq[r][0], z[1][r] * kq[r][1], z[2][r] * kq[r][2], z[3][r] * kq[r][3]};
+                f32x4{mix_act(z[0][r] * kq[r][0], opt.act), mix_act(z[1][r] * kq[r][1], opt.act),
+                      mix_act(z[2][r] * kq[r][2], opt.act), mix_act(z[3][r] * kq[r][3], opt.act)};
         __syncthreads();
         first_factor(zs, R2w, false);
         __syncthreads();   // zs is free: the output gates land there while the last factor runs
         if (GOUT) {
+            if (opt.transposed) {
+                for (int t = wave; t < N / 4; t += 4) {
+                    const int j = 4 * t + kg;
+                    zs[l16 * LDX + j] = g_out[tbase + (int64_t)j * H + l16];
+                }
+            } else {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int64_t r = r0 + b0 + q;
-                if (r >= rows) r = rows - 1;
-                dma_16_at(g_out + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
+                for (int q = 0; q < 4; ++q) {
+                    int64_t r = r0 + b0 + q;
+                    if (r >= rows) r = rows - 1;
+                    dma_16_at(g_out + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
+                }
             }
         }
         second_factor(L2w, z);
@@ -250,17 +311,63 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
             wait_loads_at_most<0>();
             __syncthreads();
         }
+        f32x4 o[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            f32x4 o = {z[0][r], z[1][r], z[2][r], z[3][r]};
-            if (GOUT) o *= *reinterpret_cast<const f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0);
-            *reinterpret_cast<f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0) = o;   // (u was consumed by the first factor)
+            o[r] = f32x4{z[0][r], z[1][r], z[2][r], z[3][r]};
+            if (GOUT) o[r] *= *reinterpret_cast<const f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0);
         }
-        __syncthreads();
+        if (opt.layer_norm) {
+            // skip connection (u is still in xs: this lane's positions are read before it overwrites them), then the
+            // row's mean and variance in two passes: 16 values per lane, the 4 lane groups of a wave by shuffles,
+            // the 4 waves through LDS
+            float part = 0.0f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int64_t r = r0 + b0 + q;
-            if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(xs + (b0 + q) * LDX + 4 * lane);
+            for (int r = 0; r < 4; ++r) {
+                o[r] += *reinterpret_cast<const f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0);
+                part += o[r][0] + o[r][1] + o[r][2] + o[r][3];
+            }
+            part += __shfl_xor(part, 16);
+            part += __shfl_xor(part, 32);
+            if (kg == 0) stats[wave * TV + l16] = part;
+            __syncthreads();
+            const float mean = (stats[l16] + stats[TV + l16] + stats[2 * TV + l16] + stats[3 * TV + l16]) * (1.0f / N);
+            __syncthreads();
+            part = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                o[r] -= mean;
+                part += o[r][0] * o[r][0] + o[r][1] * o[r][1] + o[r][2] * o[r][2] + o[r][3] * o[r][3];
+            }
+            part += __shfl_xor(part, 16);
+            part += __shfl_xor(part, 32);
+            if (kg == 0) stats[wave * TV + l16] = part;
+            __syncthreads();
+            const float var = (stats[l16] + stats[TV + l16] + stats[2 * TV + l16] + stats[3 * TV + l16]) * (1.0f / N);
+            const float rstd = rsqrtf(var + opt.eps);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = 16 * (4 * kg + r) + b0;
+                o[r] = o[r] * rstd * *reinterpret_cast<const f32x4 *>((const float *)opt.gamma + j) +
+                       *reinterpret_cast<const f32x4 *>((const float *)opt.beta + j);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            *reinterpret_cast<f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0) = o[r];   // (u is consumed)
+        __syncthreads();
+        if (opt.transposed) {
+            if (r0 + l16 < rows)
+                for (int t = wave; t < N / 4; t += 4) {
+                    const int j = 4 * t + kg;
+                    y[tbase + (int64_t)j * H + l16] = xs[l16 * LDX + j];
+                }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t r = r0 + b0 + q;
+                if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(xs + (b0 + q) * LDX + 4 * lane);
+            }
         }
         __syncthreads();   // before the next tile's rows land
     }
@@ -271,10 +378,11 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 bool mixer_fits(int bs) { return bs >= 1 && (size_t)2 * bs * bs * sizeof(float) <= 160 * 1024; }
 
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                 const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s)
+                 const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt,
+                 const MixOpt &opt, hipStream_t s)
 {
     if (rows == 0) return MONARCH_OK;
-    if (bs == 16 && dt == MONARCH_F32) {
+    if (bs == 16 && dt == MONARCH_F32 && (!opt.transposed || H % 16 == 0)) {
         int dev = 0, ncu = 0;
         MONARCH_HIP_CHECK(hipGetDevice(&dev));
         MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
@@ -288,7 +396,7 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
                                               (int)mix16::LDS_BYTES));                                             \
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), mix16::LDS_BYTES, s, (const float *)u,           \
                            (const float *)K, (const float *)g_in, (const float *)g_out, (const float *)R1,         \
-                           (const float *)L1, (const float *)R2, (const float *)L2, (float *)y, rows, H);          \
+                           (const float *)L1, (const float *)R2, (const float *)L2, (float *)y, rows, H, opt);     \
     } while (0)
         if (g_in && g_out) MONARCH_LAUNCH_MIX16(true, true);
         else if (g_in) MONARCH_LAUNCH_MIX16(true, false);
@@ -298,8 +406,8 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
         MONARCH_HIP_CHECK(hipGetLastError());
         return MONARCH_OK;
     }
-    if (dt == MONARCH_F32) return mixg::launch_typed<float>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, s);
-    return mixg::launch_typed<bf16_t>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, s);
+    if (dt == MONARCH_F32) return mixg::launch_typed<float>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, opt, s);
+    return mixg::launch_typed<bf16_t>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, opt, s);
 }
 
 }  // namespace monarch

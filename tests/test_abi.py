@@ -134,6 +134,34 @@ def test_mixer_rejects_bad_arguments(lib):
     assert lib.monarch_mixer_workspace_bytes(8, 4, 16, 0) == 0
 
 
+def test_m2_layer_rejects_bad_arguments(lib):
+    f = lib.monarch_m2_layer
+    f.argtypes = ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int] + [ctypes.c_void_p] * 12 +
+                  [ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p])
+    lib.monarch_m2_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.monarch_m2_layer_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    need = lib.monarch_m2_layer_workspace_bytes(2, 256, 256, 0)
+    assert need >= 2 * 256 * 256 * 4
+    x, y, ws = FAKE * 1024, FAKE * 2048, FAKE * 4096          # 4 MB apart
+    p = [FAKE * (16 + i) for i in range(12)]
+
+    def call(x=x, y=y, B=2, bn=16, bd=16, p=p, eps=1e-5, act=1, dt=0, ws=ws, wsb=need):
+        return f(x, y, B, bn, bd, *p, eps, act, dt, ws, wsb, None)
+    assert call(x=None) == EINVAL
+    assert call(p=p[:5] + [None] + p[6:]) == EINVAL
+    assert call(y=x) == EINVAL                   # y aliases x
+    assert call(ws=x) == EINVAL                  # workspace aliases x
+    assert call(x=x + 8) == EINVAL               # misaligned
+    assert call(act=2) == EINVAL
+    assert call(eps=-1.0) == EINVAL
+    assert call(B=-1) == ESHAPE
+    assert call(bn=0) == ESHAPE
+    assert call(bd=200) == ESHAPE                # a row beyond LDS
+    assert call(dt=2) == EDTYPE
+    assert call(wsb=need - 1) == EWORKSPACE
+    assert call(B=0) == 0
+
+
 def test_blocky_rejects_bad_arguments(lib):
     lib.monarch_blocky_state_bytes.restype = ctypes.c_size_t
     lib.monarch_blocky_state_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
