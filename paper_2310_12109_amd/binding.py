@@ -183,6 +183,10 @@ def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):
     return y
 
 
+def monarch_m2_layer_workspace_bytes(B, n, d, dt=F32):
+    return _lib.monarch_m2_layer_workspace_bytes(B, n, d, dt)
+
+
 def monarch_m2_layer(x, seq, n_kernel, dim, d_kernel, gamma, beta, eps=1e-5, act=1, ws=None, out=None):
     """LayerNorm(M4 act(k_d * M3 X~) + X~), X~ = (M2 act(K_n * M1 x^T))^T; x: (B, n, d); seq = (R1, L1, R2, L2),
     dim = (R3, L3, R4, L4)."""

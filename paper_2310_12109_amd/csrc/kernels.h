@@ -90,6 +90,7 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
 struct MixOpt {
     int act = 0;             // between the kernel product and the second matrix: 0 none, 1 ReLU
     int transposed = 0;      // u, gates and y are (B, N, H) instead of (B, H, N)
+    int run = 1;             // (set by the launcher) neighbouring tiles a workgroup takes in a row, transposed access
     int layer_norm = 0;      // y = LayerNorm(result + u) over the row, with gamma, beta (type dt, N entries), eps
     const void *gamma = nullptr, *beta = nullptr;
     float eps = 0.0f;

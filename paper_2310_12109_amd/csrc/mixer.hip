@@ -177,6 +177,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int B = 16, N = 256, TV = 16;
 constexpr int LDX = N + 4;                 // pitch of the row buffers
 constexpr int RS = 18, LD = B * RS + 3;    // tile: element (v, p, q) at v LD + p RS + q
+constexpr int TRANSPOSED_RUN = 8;
 constexpr int STATS = 4 * TV;              // per wave and row: a partial sum (layer norm)
 constexpr size_t LDS_BYTES = sizeof(float) * (2 * TV * LDX + TV * LD + STATS);
 
@@ -217,16 +218,31 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 
     const int64_t ntiles = (rows + TV - 1) / TV;
     const uint32_t xs_addr = lds_address(xs), zs_addr = lds_address(zs);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // (B, N, H) layout: a tile covers 64 of the bytes of a position; a workgroup takes `run` neighbouring tiles one
+    // after the other, so that the other bytes of the lines it has fetched are used while they are still in its L2
+    const int run = opt.transposed ? opt.run : 1;
+    for (int64_t it = 0;; ++it) {
+        const int64_t tile = ((int64_t)blockIdx.x + (it / run) * gridDim.x) * run + it % run;
+        if (((int64_t)blockIdx.x + (it / run) * gridDim.x) * run >= ntiles) break;
+        if (tile >= ntiles) continue;
         const int64_t r0 = tile * TV;
         // (B, N, H) layout: the 16 rows of a tile are 16 neighbouring channels of one sequence (H is a multiple of
         // 16), 64 contiguous bytes per position; lane (v = l16, kg) moves positions 4 t + kg of row v
         const int64_t tbase = (r0 / H) * (int64_t)N * H + r0 % H;
         if (opt.transposed) {
-            for (int t = wave; t < N / 4; t += 4) {
-                const int j = 4 * t + kg;
-                xs[l16 * LDX + j] = u[tbase + (int64_t)j * H + l16];
-                if (GIN) zs[l16 * LDX + j] = g_in[tbase + (int64_t)j * H + l16];
+            // (all sixteen loads of an array are in flight before the first value is stored)
+            float a[16], g[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = 4 * (wave + 4 * i) + kg;
+                a[i] = u[tbase + (int64_t)j * H + l16];
+                if (GIN) g[i] = g_in[tbase + (int64_t)j * H + l16];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = 4 * (wave + 4 * i) + kg;
+                xs[l16 * LDX + j] = a[i];
+                if (GIN) zs[l16 * LDX + j] = g[i];
             }
         } else {
             // rows in: wave w fetches rows 4 w .. 4 w + 3 (rows past the end: the last one, never stored)
@@ -293,10 +309,11 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
         __syncthreads();   // zs is free: the output gates land there while the last factor runs
         if (GOUT) {
             if (opt.transposed) {
-                for (int t = wave; t < N / 4; t += 4) {
-                    const int j = 4 * t + kg;
-                    zs[l16 * LDX + j] = g_out[tbase + (int64_t)j * H + l16];
-                }
+                float g[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) g[i] = g_out[tbase + (int64_t)(4 * (wave + 4 * i) + kg) * H + l16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) zs[l16 * LDX + 4 * (wave + 4 * i) + kg] = g[i];
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -357,11 +374,13 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
             *reinterpret_cast<f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0) = o[r];   // (u is consumed)
         __syncthreads();
         if (opt.transposed) {
-            if (r0 + l16 < rows)
-                for (int t = wave; t < N / 4; t += 4) {
-                    const int j = 4 * t + kg;
+            if (r0 + l16 < rows) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int j = 4 * (wave + 4 * i) + kg;
                     y[tbase + (int64_t)j * H + l16] = xs[l16 * LDX + j];
                 }
+            }
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -387,8 +406,14 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
         MONARCH_HIP_CHECK(hipGetDevice(&dev));
         MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
         const int64_t ntiles = (rows + mix16::TV - 1) / mix16::TV;
+        // runs of neighbouring tiles only when there are tiles enough to keep every workgroup busy with whole runs
+        MixOpt o16 = opt;
+        o16.run = 1;
+        while (o16.run < mix16::TRANSPOSED_RUN && ntiles >= 2 * (int64_t)ncu * 2 * o16.run && (H / 16) % (2 * o16.run) == 0)
+            o16.run *= 2;
+        const int64_t nruns = opt.transposed ? (ntiles + o16.run - 1) / o16.run : ntiles;
         int64_t grid = 2 * (int64_t)ncu;
-        if (grid > ntiles) grid = ntiles;
+        if (grid > nruns) grid = nruns;
 #define MONARCH_LAUNCH_MIX16(GI, GO)                                                                               \
     do {                                                                                                           \
         auto kern = mix16::mixer_b16_kernel<GI, GO>;                                                               \
@@ -396,7 +421,7 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
                                               (int)mix16::LDS_BYTES));                                             \
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), mix16::LDS_BYTES, s, (const float *)u,           \
                            (const float *)K, (const float *)g_in, (const float *)g_out, (const float *)R1,         \
-                           (const float *)L1, (const float *)R2, (const float *)L2, (float *)y, rows, H, opt);     \
+                           (const float *)L1, (const float *)R2, (const float *)L2, (float *)y, rows, H, o16);     \
     } while (0)
         if (g_in && g_out) MONARCH_LAUNCH_MIX16(true, true);
         else if (g_in) MONARCH_LAUNCH_MIX16(true, false);

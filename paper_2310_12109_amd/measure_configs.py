@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mm3 mixer blocky c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mm3 mixer layer blocky c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -128,6 +128,25 @@ def matmul3(b, batch, reps):
     _report(f"order-3 backward fp32 b={b} N={N}, batch {batch}", _time(calls, reps), nb, batch * 8 * 2 * N * b, len(calls))
 
 
+def m2_layer(B, reps):
+    """The basic M2 layer at n = d = 256, fp32: x read, X~ written and read, y written (4 passes over B n d floats)."""
+    from . import workloads
+    w = workloads.m2_layer_inputs(1, 16, 16, seed=0)
+    par = {k: torch.from_numpy(v).cuda() for k, v in w.items() if k != "x"}
+    seq, dim = [par[k] for k in ("R1", "L1", "R2", "L2")], [par[k] for k in ("R3", "L3", "R4", "L4")]
+    nbytes = 4 * B * 256 * 256 * 4 + 2 * 256 * 256 * 4
+    ws = torch.empty(binding.monarch_m2_layer_workspace_bytes(B, 256, 256, binding.F32), dtype=torch.uint8, device="cuda")
+
+    def make():
+        x = _rnd(B, 256, 256, dt=torch.float32)
+        y = torch.empty_like(x)
+        return lambda: binding.monarch_m2_layer(x, seq, par["n_kernel"], dim, par["d_kernel"], par["gamma"], par["beta"],
+                                                ws=ws, out=y)
+    calls = _sets(make, nbytes)
+    # two mixers of four block-diagonal products each: 8 * 2 * 256 * 16 FLOP per row of 256
+    _report(f"m2 layer fp32 n=256 d=256, B={B}", _time(calls, reps), nbytes, B * 2 * 256 * 8 * 2 * 256 * 16, len(calls))
+
+
 def blocky(B, H, reps):
     """Causal convolution with a polynomial-parameterised Monarch matrix, N = 256, n = 128, fp32: u and both gates
     read, y written (2 KB per row); 704 complex-arithmetic MFMAs of 2048 FLOP per 16 rows."""
@@ -231,6 +250,9 @@ def main():
     if want("mm3"):
         matmul3(8, 16384, 10)
         matmul3(16, 4096, 10)
+    if want("layer"):
+        m2_layer(32, 50)
+        m2_layer(2048, 5)
     if want("blocky"):
         blocky(8, 768, 100)
         blocky(1024, 768, 5)
