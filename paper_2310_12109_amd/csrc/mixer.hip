@@ -186,14 +186,31 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-template <bool GIN, bool GOUT>
-__global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restrict__ u, const float *__restrict__ K,
-                                                           const float *__restrict__ g_in, const float *__restrict__ g_out,
-                                                           const float *__restrict__ R1, const float *__restrict__ L1,
-                                                           const float *__restrict__ R2, const float *__restrict__ L2,
-                                                           float *__restrict__ y, int64_t rows, int H,
+// four consecutive elements (16-byte aligned for float, 8-byte aligned for bf16) as floats, and back
+__device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ f32x4 ld4(const bf16_t *p)
+{
+    const uint2 w = *reinterpret_cast<const uint2 *>(p);
+    return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                 __uint_as_float(w.y & 0xffff0000u)};
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const bf16_t a = from_f32<bf16_t>(lo), b = from_f32<bf16_t>(hi);
+    return (uint32_t) * reinterpret_cast<const uint16_t *>(&a) | ((uint32_t) * reinterpret_cast<const uint16_t *>(&b) << 16);
+}
+
+// T: type of every tensor in memory.  float rows arrive by direct-to-LDS loads; bf16 rows (512 bytes, two per wave
+// instruction) pass through registers and are widened on the way into LDS: everything on chip is float.
+template <typename T, bool GIN, bool GOUT>
+__global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__ u, const T *__restrict__ K,
+                                                           const T *__restrict__ g_in, const T *__restrict__ g_out,
+                                                           const T *__restrict__ R1, const T *__restrict__ L1,
+                                                           const T *__restrict__ R2, const T *__restrict__ L2,
+                                                           T *__restrict__ y, int64_t rows, int H,
                                                            const MixOpt opt)
 {
+    constexpr bool F32 = sizeof(T) == 4;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float *xs = smem;                  // [TV][LDX]  rows of u, at the end the rows of y
     float *zs = xs + TV * LDX;         // [TV][LDX]  rows of g_in, then the rows between M1 and M2, then g_out
@@ -210,14 +227,41 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int at = ((b0 + q) * B + l16) * B + 4 * kg + s;
-            R1w[q][s] = R1[at];
-            L1w[q][s] = L1[at];
-            R2w[q][s] = R2[at];
-            L2w[q][s] = L2[at];
+            R1w[q][s] = to_f32(R1[at]);
+            L1w[q][s] = to_f32(L1[at]);
+            R2w[q][s] = to_f32(R2[at]);
+            L2w[q][s] = to_f32(L2[at]);
         }
 
     const int64_t ntiles = (rows + TV - 1) / TV;
     const uint32_t xs_addr = lds_address(xs), zs_addr = lds_address(zs);
+    // this wave's four rows (4 w .. 4 w + 3 of the tile; rows past the end: the last one, never stored) into LDS
+    auto fetch_rows = [&](const T *src, int64_t r0, float *dst, uint32_t dst_addr) {
+        if constexpr (F32) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int64_t r = r0 + b0 + q;
+                if (r >= rows) r = rows - 1;
+                dma_16_at(src + r * N + 4 * lane, dst_addr + (uint32_t)(b0 + q) * LDX * 4);
+            }
+        } else {
+            uint4 w[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {   // lanes 0..31: row 2 i, lanes 32..63: row 2 i + 1; 8 elements per lane
+                int64_t r = r0 + b0 + 2 * i + (lane >> 5);
+                if (r >= rows) r = rows - 1;
+                w[i] = *reinterpret_cast<const uint4 *>(src + r * N + 8 * (lane & 31));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                float *d = dst + (b0 + 2 * i + (lane >> 5)) * LDX + 8 * (lane & 31);
+                *reinterpret_cast<f32x4 *>(d) = f32x4{__uint_as_float(w[i].x << 16), __uint_as_float(w[i].x & 0xffff0000u),
+                                                      __uint_as_float(w[i].y << 16), __uint_as_float(w[i].y & 0xffff0000u)};
+                *reinterpret_cast<f32x4 *>(d + 4) = f32x4{__uint_as_float(w[i].z << 16), __uint_as_float(w[i].z & 0xffff0000u),
+                                                          __uint_as_float(w[i].w << 16), __uint_as_float(w[i].w & 0xffff0000u)};
+            }
+        }
+    };
     // (B, N, H) layout: a tile covers 64 of the bytes of a position; a workgroup takes `run` neighbouring tiles one
     // after the other, so that the other bytes of the lines it has fetched are used while they are still in its L2
     const int run = opt.transposed ? opt.run : 1;
@@ -235,8 +279,8 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int j = 4 * (wave + 4 * i) + kg;
-                a[i] = u[tbase + (int64_t)j * H + l16];
-                if (GIN) g[i] = g_in[tbase + (int64_t)j * H + l16];
+                a[i] = to_f32(u[tbase + (int64_t)j * H + l16]);
+                if (GIN) g[i] = to_f32(g_in[tbase + (int64_t)j * H + l16]);
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -245,23 +289,17 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
                 if (GIN) zs[l16 * LDX + j] = g[i];
             }
         } else {
-            // rows in: wave w fetches rows 4 w .. 4 w + 3 (rows past the end: the last one, never stored)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int64_t r = r0 + b0 + q;
-                if (r >= rows) r = rows - 1;
-                dma_16_at(u + r * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
-                if (GIN) dma_16_at(g_in + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
-            }
+            fetch_rows(u, r0, xs, xs_addr);
+            if (GIN) fetch_rows(g_in, r0, zs, zs_addr);
         }
         // the kernel entries this lane multiplies in S2: K[h_v][16 (4 kg + r) + b0 .. + 3], v = l16
         f32x4 kq[4];
         {
             int64_t r = r0 + l16;
             if (r >= rows) r = rows - 1;
-            const float *krow = K + (r % H) * (int64_t)N + b0;
+            const T *krow = K + (r % H) * (int64_t)N + b0;
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) kq[rr] = *reinterpret_cast<const f32x4 *>(krow + 16 * (4 * kg + rr));
+            for (int rr = 0; rr < 4; ++rr) kq[rr] = ld4(krow + 16 * (4 * kg + rr));
         }
         wait_loads_at_most<0>();
         __syncthreads();
@@ -311,16 +349,11 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
             if (opt.transposed) {
                 float g[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) g[i] = g_out[tbase + (int64_t)(4 * (wave + 4 * i) + kg) * H + l16];
+                for (int i = 0; i < 16; ++i) g[i] = to_f32(g_out[tbase + (int64_t)(4 * (wave + 4 * i) + kg) * H + l16]);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) zs[l16 * LDX + 4 * (wave + 4 * i) + kg] = g[i];
             } else {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    int64_t r = r0 + b0 + q;
-                    if (r >= rows) r = rows - 1;
-                    dma_16_at(g_out + r * N + 4 * lane, zs_addr + (uint32_t)(b0 + q) * LDX * 4);
-                }
+                fetch_rows(g_out, r0, zs, zs_addr);
             }
         }
         second_factor(L2w, z);
@@ -365,8 +398,7 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = 16 * (4 * kg + r) + b0;
-                o[r] = o[r] * rstd * *reinterpret_cast<const f32x4 *>((const float *)opt.gamma + j) +
-                       *reinterpret_cast<const f32x4 *>((const float *)opt.beta + j);
+                o[r] = o[r] * rstd * ld4((const T *)opt.gamma + j) + ld4((const T *)opt.beta + j);
             }
         }
 #pragma unroll
@@ -378,14 +410,26 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const float *__restri
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j = 4 * (wave + 4 * i) + kg;
-                    y[tbase + (int64_t)j * H + l16] = xs[l16 * LDX + j];
+                    y[tbase + (int64_t)j * H + l16] = from_f32<T>(xs[l16 * LDX + j]);
                 }
             }
         } else {
+            if constexpr (F32) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t r = r0 + b0 + q;
-                if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(xs + (b0 + q) * LDX + 4 * lane);
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t r = r0 + b0 + q;
+                    if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(xs + (b0 + q) * LDX + 4 * lane);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {   // two rows per instruction, 8 elements (16 bytes) per lane
+                    const int v = b0 + 2 * i + (lane >> 5);
+                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(xs + v * LDX + 8 * (lane & 31));
+                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(xs + v * LDX + 8 * (lane & 31) + 4);
+                    if (r0 + v < rows)
+                        *reinterpret_cast<uint4 *>(y + (r0 + v) * N + 8 * (lane & 31)) =
+                            uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+                }
             }
         }
         __syncthreads();   // before the next tile's rows land
@@ -401,7 +445,7 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
                  const MixOpt &opt, hipStream_t s)
 {
     if (rows == 0) return MONARCH_OK;
-    if (bs == 16 && dt == MONARCH_F32 && (!opt.transposed || H % 16 == 0)) {
+    if (bs == 16 && (!opt.transposed || H % 16 == 0)) {
         int dev = 0, ncu = 0;
         MONARCH_HIP_CHECK(hipGetDevice(&dev));
         MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
@@ -414,19 +458,25 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
         const int64_t nruns = opt.transposed ? (ntiles + o16.run - 1) / o16.run : ntiles;
         int64_t grid = 2 * (int64_t)ncu;
         if (grid > nruns) grid = nruns;
-#define MONARCH_LAUNCH_MIX16(GI, GO)                                                                               \
+#define MONARCH_LAUNCH_MIX16(T, GI, GO)                                                                            \
     do {                                                                                                           \
-        auto kern = mix16::mixer_b16_kernel<GI, GO>;                                                               \
+        auto kern = mix16::mixer_b16_kernel<T, GI, GO>;                                                            \
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
                                               (int)mix16::LDS_BYTES));                                             \
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), mix16::LDS_BYTES, s, (const float *)u,           \
-                           (const float *)K, (const float *)g_in, (const float *)g_out, (const float *)R1,         \
-                           (const float *)L1, (const float *)R2, (const float *)L2, (float *)y, rows, H, o16);     \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), mix16::LDS_BYTES, s, (const T *)u, (const T *)K, \
+                           (const T *)g_in, (const T *)g_out, (const T *)R1, (const T *)L1, (const T *)R2,         \
+                           (const T *)L2, (T *)y, rows, H, o16);                                                   \
     } while (0)
-        if (g_in && g_out) MONARCH_LAUNCH_MIX16(true, true);
-        else if (g_in) MONARCH_LAUNCH_MIX16(true, false);
-        else if (g_out) MONARCH_LAUNCH_MIX16(false, true);
-        else MONARCH_LAUNCH_MIX16(false, false);
+#define MONARCH_LAUNCH_MIX16_GATES(T)                                                                              \
+    do {                                                                                                           \
+        if (g_in && g_out) MONARCH_LAUNCH_MIX16(T, true, true);                                                    \
+        else if (g_in) MONARCH_LAUNCH_MIX16(T, true, false);                                                       \
+        else if (g_out) MONARCH_LAUNCH_MIX16(T, false, true);                                                      \
+        else MONARCH_LAUNCH_MIX16(T, false, false);                                                                \
+    } while (0)
+        if (dt == MONARCH_F32) MONARCH_LAUNCH_MIX16_GATES(float);
+        else MONARCH_LAUNCH_MIX16_GATES(bf16_t);
+#undef MONARCH_LAUNCH_MIX16_GATES
 #undef MONARCH_LAUNCH_MIX16
         MONARCH_HIP_CHECK(hipGetLastError());
         return MONARCH_OK;

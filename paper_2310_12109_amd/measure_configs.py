@@ -91,20 +91,21 @@ def matmul_backward_c1(batch, reps):
     _report(f"c1 matmul backward fp32, batch {batch}", _time(calls, reps), nbytes, batch * 5 * 2 * 256 * 16, len(calls))
 
 
-def mixer(B, H, reps):
-    """Learned-Monarch sequence mixer at N = 256, fp32: u, both gates read and y written (4 KB per row)."""
+def mixer(B, H, reps, dt=torch.float32):
+    """Learned-Monarch sequence mixer at N = 256: u, both gates read and y written (4 rows of 256 per row)."""
     rows = B * H
-    nbytes = 4 * rows * 256 * 4 + H * 256 * 4 + 4 * 16 * 256 * 4
-    K = _rnd(H, 256, dt=torch.float32)
-    f = [_rnd(16, 16, 16, dt=torch.float32, scale=.25) for _ in range(4)]
+    es = 4 if dt == torch.float32 else 2
+    nbytes = (4 * rows * 256 + H * 256 + 4 * 16 * 256) * es
+    K = _rnd(H, 256, dt=dt)
+    f = [_rnd(16, 16, 16, dt=dt, scale=.25) for _ in range(4)]
 
     def make():
-        u, gi, go = (_rnd(B, H, 256, dt=torch.float32) for _ in range(3))
+        u, gi, go = (_rnd(B, H, 256, dt=dt) for _ in range(3))
         y = torch.empty_like(u)
         return lambda: binding.monarch_mixer(u, K, gi, go, *f, out=y)
     calls = _sets(make, nbytes)
     # four block-diagonal products of 2 * 256 * 16 FLOP per row
-    _report(f"mixer fp32 N=256, B={B} H={H}", _time(calls, reps), nbytes, rows * 4 * 2 * 256 * 16, len(calls))
+    _report(f"mixer {'fp32' if es == 4 else 'bf16'} N=256, B={B} H={H}", _time(calls, reps), nbytes, rows * 4 * 2 * 256 * 16, len(calls))
 
 
 def matmul3(b, batch, reps):
@@ -247,6 +248,8 @@ def main():
     if want("mixer"):
         mixer(8, 768, 100)
         mixer(1024, 768, 5)
+        mixer(8, 768, 100, torch.bfloat16)
+        mixer(1024, 768, 5, torch.bfloat16)
     if want("mm3"):
         matmul3(8, 16384, 10)
         matmul3(16, 4096, 10)

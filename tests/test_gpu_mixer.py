@@ -75,6 +75,27 @@ def test_bf16(mm, b):
     assert rel_l2(host(y), _want(w)) <= TOL_BF16
 
 
+@pytest.mark.parametrize("gates", [(True, True), (False, False), (True, False)])
+def test_bf16_n256_many_tiles(mm, gates):
+    # bf16 rows through the matrix-core kernel (two rows per load instruction, widened into LDS): 143 tiles, ragged
+    announce("mixer bf16 b=16 many tiles, gates", gates)
+    w = workloads.mixer_inputs(13, 175, 16, seed=21, gates=gates, bf16=True)
+    assert rel_l2(host(_run(mm, w, bf16=True)), _want(w)) <= TOL_BF16
+
+
+def test_bf16_identity_blocks_are_exact_up_to_the_output_rounding(mm):
+    # identity blocks: the mixer is g_out o P(K o P(g_in o u)); fp32 products of bf16 values, one rounding at the store
+    announce("mixer bf16 identity blocks")
+    w = workloads.mixer_inputs(2, 5, 16, seed=22, bf16=True)
+    eye = np.broadcast_to(np.eye(16, dtype=np.float32), (16, 16, 16)).copy()
+    for k in ("R1", "L1", "R2", "L2"):
+        w[k] = eye
+    perm = oracle.perm(16, 256)
+    t = ((w["g_in"] * w["u"]).astype(np.float32)[..., perm] * w["K"][None]).astype(np.float32)
+    want = workloads.round_to_bf16((t[..., perm] * w["g_out"]).astype(np.float32))
+    np.testing.assert_array_equal(host(_run(mm, w, bf16=True)).astype(np.float32), want)
+
+
 def test_identity_blocks_reduce_to_the_gated_product(mm):
     # all four factors the identity: P P P = P for the involution P of a square Monarch matrix, so M = P and
     # y = g_out o P (K o P (g_in o u)): an index identity, exact in fp32
