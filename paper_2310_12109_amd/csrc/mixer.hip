@@ -179,12 +179,23 @@ constexpr int LDX = N + 4;                 // pitch of the row buffers
 constexpr int RS = 18, LD = B * RS + 3;    // tile: element (v, p, q) at v LD + p RS + q
 constexpr int TRANSPOSED_RUN = 8;
 constexpr int STATS = 4 * TV;              // per wave and row: a partial sum (layer norm)
-constexpr size_t LDS_BYTES = sizeof(float) * (2 * TV * LDX + TV * LD + STATS);
+constexpr size_t LDS_BYTES = sizeof(float) * (3 * TV * LDX + TV * LD + STATS);
 
 __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
+
+// Phase clocks for kernel tuning; compiled out unless MONARCH_MIXER_CLOCKS is defined.
+#ifdef MONARCH_MIXER_CLOCKS
+__device__ long long g_clk[4][32];
+#define MIX_MARK(i)                                                                                             \
+    do {                                                                                                        \
+        if (blockIdx.x == 1 && it == 2 && lane == 0) g_clk[wave][(i)] = __builtin_readcyclecounter();           \
+    } while (0)
+#else
+#define MIX_MARK(i)
+#endif
 
 // four consecutive elements (16-byte aligned for float, 8-byte aligned for bf16) as floats, and back
 __device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
@@ -200,8 +211,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return (uint32_t) * reinterpret_cast<const uint16_t *>(&a) | ((uint32_t) * reinterpret_cast<const uint16_t *>(&b) << 16);
 }
 
-// T: type of every tensor in memory.  float rows arrive by direct-to-LDS loads; bf16 rows (512 bytes, two per wave
-// instruction) pass through registers and are widened on the way into LDS: everything on chip is float.
+// T: type of every tensor in memory; everything on chip is float.
+//
+// Three row buffers.  Rows of u (and g_in) wait in two of them; the third takes z between the matrices, then the
+// output gates, then the rows of y (each lane overwrites the gate values it has just used).  As soon as the first
+// factor has consumed a tile's inputs, the inputs of the workgroup's next tile are requested into the buffers that
+// have become free (float: direct-to-LDS loads; bf16: into registers, widened into LDS after the third factor),
+// together with this tile's kernel entries and output gates (registers), so that no stage of a tile waits for
+// memory except the very first.  Without input gates u alternates between two buffers, which keeps this tile's u
+// for the skip connection of the layer-norm epilogue.  Not prefetched: the (B, N, H) access, and the layer-norm
+// epilogue combined with input gates.
 template <typename T, bool GIN, bool GOUT>
 __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__ u, const T *__restrict__ K,
                                                            const T *__restrict__ g_in, const T *__restrict__ g_out,
@@ -211,10 +230,12 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
                                                            const MixOpt opt)
 {
     constexpr bool F32 = sizeof(T) == 4;
+    constexpr int NW = F32 ? 4 : 2;    // registers' worth of 16-byte pieces a lane holds of an array of a tile
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    float *xs = smem;                  // [TV][LDX]  rows of u, at the end the rows of y
-    float *zs = xs + TV * LDX;         // [TV][LDX]  rows of g_in, then the rows between M1 and M2, then g_out
-    float *tt = zs + TV * LDX;         // tile between the two factors of a matrix: (v, i, a)
+    float *bufA = smem;                // [TV][LDX] each
+    float *bufB = bufA + TV * LDX;
+    float *bufC = bufB + TV * LDX;
+    float *tt = bufC + TV * LDX;       // tile between the two factors of a matrix: (v, i, a)
     float *stats = tt + TV * LD;       // [4 waves][TV]
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
@@ -234,26 +255,23 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         }
 
     const int64_t ntiles = (rows + TV - 1) / TV;
-    const uint32_t xs_addr = lds_address(xs), zs_addr = lds_address(zs);
-    // this wave's four rows (4 w .. 4 w + 3 of the tile; rows past the end: the last one, never stored) into LDS
-    auto fetch_rows = [&](const T *src, int64_t r0, float *dst, uint32_t dst_addr) {
-        if constexpr (F32) {
+    // This wave's four rows of a tile (4 w .. 4 w + 3; rows past the end: the last one, never stored) as 16-byte
+    // pieces: float: piece `lane` of row 4 w + i; bf16: piece lane % 32 of row 4 w + 2 i + lane / 32.
+    auto piece = [&](const T *src, int64_t r0, int i) -> const T * {
+        int64_t r = r0 + b0 + (F32 ? i : 2 * i + (lane >> 5));
+        if (r >= rows) r = rows - 1;
+        return src + r * N + (F32 ? 4 * lane : 8 * (lane & 31));
+    };
+    auto load_rows = [&](const T *src, int64_t r0, uint4 (&w)[NW]) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int64_t r = r0 + b0 + q;
-                if (r >= rows) r = rows - 1;
-                dma_16_at(src + r * N + 4 * lane, dst_addr + (uint32_t)(b0 + q) * LDX * 4);
-            }
-        } else {
-            uint4 w[2];
+        for (int i = 0; i < NW; ++i) w[i] = *reinterpret_cast<const uint4 *>(piece(src, r0, i));
+    };
+    auto park_rows = [&](const uint4 (&w)[NW], float *dst) {   // registers -> LDS rows, widened
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {   // lanes 0..31: row 2 i, lanes 32..63: row 2 i + 1; 8 elements per lane
-                int64_t r = r0 + b0 + 2 * i + (lane >> 5);
-                if (r >= rows) r = rows - 1;
-                w[i] = *reinterpret_cast<const uint4 *>(src + r * N + 8 * (lane & 31));
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NW; ++i) {
+            if constexpr (F32) {
+                *reinterpret_cast<uint4 *>(dst + (b0 + i) * LDX + 4 * lane) = w[i];
+            } else {
                 float *d = dst + (b0 + 2 * i + (lane >> 5)) * LDX + 8 * (lane & 31);
                 *reinterpret_cast<f32x4 *>(d) = f32x4{__uint_as_float(w[i].x << 16), __uint_as_float(w[i].x & 0xffff0000u),
                                                       __uint_as_float(w[i].y << 16), __uint_as_float(w[i].y & 0xffff0000u)};
@@ -262,16 +280,58 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             }
         }
     };
-    // (B, N, H) layout: a tile covers 64 of the bytes of a position; a workgroup takes `run` neighbouring tiles one
-    // after the other, so that the other bytes of the lines it has fetched are used while they are still in its L2
+    auto dma_rows = [&](const T *src, int64_t r0, float *dst) {   // float only: memory -> LDS rows directly
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds_address(dst));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            dma_16_at(piece(src, r0, i), __builtin_amdgcn_readfirstlane(base + (uint32_t)(b0 + i) * LDX * 4));
+    };
+    auto fetch_now = [&](const T *src, int64_t r0, float *dst) {
+        if constexpr (F32) {
+            dma_rows(src, r0, dst);
+        } else {
+            uint4 w[NW];
+            load_rows(src, r0, w);
+            park_rows(w, dst);
+        }
+    };
+    // tile number of this workgroup's it-th tile (-1: none).  (B, N, H) layout: a tile covers 64 of the bytes of a
+    // position; a workgroup takes `run` neighbouring tiles one after the other, so that the other bytes of the
+    // lines it has fetched are used while they are still in its L2
     const int run = opt.transposed ? opt.run : 1;
+    auto tile_of = [&](int64_t it) -> int64_t {
+        const int64_t first = ((int64_t)blockIdx.x + (it / run) * gridDim.x) * run;
+        if (first >= ntiles) return -2;               // past the end: stop
+        return first + it % run < ntiles ? first + it % run : -1;   // -1: a hole at the end of the last run
+    };
+
+    // (float rows are not prefetched: the compiler's own waits for the register loads of a tile count loads in
+    // issue order and would also wait for direct-to-LDS loads of the next tile issued before them; the float
+    // kernel runs at the rate of a plain copy as it is)
+    const bool prefetch = !F32 && !opt.transposed && !(opt.layer_norm && GIN);
+    // the kernel entries a lane multiplies in S2: K[h_v][16 (4 kg + r) + b0 .. + 3], v = l16
+    f32x4 kq[4];
+    auto load_kernel = [&](int64_t r0, f32x4 (&k)[4]) {
+        int64_t r = r0 + l16;
+        if (r >= rows) r = rows - 1;
+        const T *krow = K + (r % H) * (int64_t)N + b0;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) k[rr] = ld4(krow + 16 * (4 * kg + rr));
+    };
+    float *ub = bufA, *nb = bufB;      // rows of u of this tile; where the next tile's go when there are no input gates
+    if (prefetch && tile_of(0) >= 0) {
+        fetch_now(u, tile_of(0) * TV, ub);
+        if (GIN) fetch_now(g_in, tile_of(0) * TV, bufB);
+    }
     for (int64_t it = 0;; ++it) {
-        const int64_t tile = ((int64_t)blockIdx.x + (it / run) * gridDim.x) * run + it % run;
-        if (((int64_t)blockIdx.x + (it / run) * gridDim.x) * run >= ntiles) break;
-        if (tile >= ntiles) continue;
+        const int64_t tile = tile_of(it);
+        if (tile == -2) break;
+        if (tile < 0) continue;
         const int64_t r0 = tile * TV;
+        const int64_t next = prefetch ? tile_of(it + 1) : -1;   // (run = 1 whenever prefetch is on)
+        MIX_MARK(0);
         // (B, N, H) layout: the 16 rows of a tile are 16 neighbouring channels of one sequence (H is a multiple of
-        // 16), 64 contiguous bytes per position; lane (v = l16, kg) moves positions 4 t + kg of row v
+        // 16), 64 contiguous bytes per position; lane (v = l16, kg) moves positions 4 (wave + 4 i) + kg of row v
         const int64_t tbase = (r0 / H) * (int64_t)N * H + r0 % H;
         if (opt.transposed) {
             // (all sixteen loads of an array are in flight before the first value is stored)
@@ -285,31 +345,26 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int j = 4 * (wave + 4 * i) + kg;
-                xs[l16 * LDX + j] = a[i];
-                if (GIN) zs[l16 * LDX + j] = g[i];
+                ub[l16 * LDX + j] = a[i];
+                if (GIN) bufB[l16 * LDX + j] = g[i];
             }
-        } else {
-            fetch_rows(u, r0, xs, xs_addr);
-            if (GIN) fetch_rows(g_in, r0, zs, zs_addr);
+        } else if (!prefetch) {
+            fetch_now(u, r0, ub);
+            if (GIN) fetch_now(g_in, r0, bufB);
         }
-        // the kernel entries this lane multiplies in S2: K[h_v][16 (4 kg + r) + b0 .. + 3], v = l16
-        f32x4 kq[4];
-        {
-            int64_t r = r0 + l16;
-            if (r >= rows) r = rows - 1;
-            const T *krow = K + (r % H) * (int64_t)N + b0;
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) kq[rr] = ld4(krow + 16 * (4 * kg + rr));
-        }
-        wait_loads_at_most<0>();
+        load_kernel(r0, kq);
+        MIX_MARK(1);
+        if (F32) wait_loads_at_most<0>();   // the direct-to-LDS loads (bf16 rows pass through registers)
+        MIX_MARK(2);
         __syncthreads();
+        MIX_MARK(3);
 
         auto first_factor = [&](const float *rows_in, const float (&W)[4][4], bool gated) {
             f32x4 xq[4];   // [s]: elements 16 (4 kg + s) + b0 .. + 3 of row v = l16
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 xq[s] = *reinterpret_cast<const f32x4 *>(rows_in + l16 * LDX + 16 * (4 * kg + s) + b0);
-                if (gated) xq[s] *= *reinterpret_cast<const f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + s) + b0);
+                if (gated) xq[s] *= *reinterpret_cast<const f32x4 *>(bufB + l16 * LDX + 16 * (4 * kg + s) + b0);
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -331,50 +386,80 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             }
         };
 
-        first_factor(xs, R1w, GIN);
+        first_factor(ub, R1w, GIN);
+        MIX_MARK(4);
         __syncthreads();
+        MIX_MARK(5);
+
+        // requested here, to arrive while the next three stages run: this tile's output gates (bf16: rows, into
+        // registers; float rows come by direct-to-LDS loads once z is consumed) ...
+        uint4 gq[NW];
+        if (!F32 && GOUT && !opt.transposed) load_rows(g_out, r0, gq);
+        // ... and the next tile's inputs: the first factor has consumed the buffers they go to
+        float *u_next = GIN ? bufA : nb;
+        uint4 pu[NW], pg[NW];
+        if (next >= 0) {
+            if constexpr (F32) {
+                dma_rows(u, next * TV, u_next);
+                if (GIN) dma_rows(g_in, next * TV, bufB);
+            } else {
+                load_rows(u, next * TV, pu);
+                if (GIN) load_rows(g_in, next * TV, pg);
+            }
+        }
+
         f32x4 z[4];
         second_factor(L1w, z);
         // rows between the matrices: z[v][16 (4 kg + r) + b0 + q], times the kernel of the row's channel
-        // (zs held g_in, which every wave has consumed before the barrier above)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            *reinterpret_cast<f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0) =
+            *reinterpret_cast<f32x4 *>(bufC + l16 * LDX + 16 * (4 * kg + r) + b0) =
                 f32x4{mix_act(z[0][r] * kq[r][0], opt.act), mix_act(z[1][r] * kq[r][1], opt.act),
                       mix_act(z[2][r] * kq[r][2], opt.act), mix_act(z[3][r] * kq[r][3], opt.act)};
+        MIX_MARK(6);
         __syncthreads();
-        first_factor(zs, R2w, false);
-        __syncthreads();   // zs is free: the output gates land there while the last factor runs
+        MIX_MARK(7);
+        first_factor(bufC, R2w, false);
+        MIX_MARK(8);
+        __syncthreads();   // z is consumed: the output gates take its place
         if (GOUT) {
             if (opt.transposed) {
                 float g[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) g[i] = to_f32(g_out[tbase + (int64_t)(4 * (wave + 4 * i) + kg) * H + l16]);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) zs[l16 * LDX + 4 * (wave + 4 * i) + kg] = g[i];
+                for (int i = 0; i < 16; ++i) bufC[l16 * LDX + 4 * (wave + 4 * i) + kg] = g[i];
+            } else if constexpr (F32) {
+                dma_rows(g_out, r0, bufC);
             } else {
-                fetch_rows(g_out, r0, zs, zs_addr);
+                park_rows(gq, bufC);
             }
         }
+        if (!F32 && next >= 0) {
+            park_rows(pu, u_next);
+            if (GIN) park_rows(pg, bufB);
+        }
+        MIX_MARK(9);
         second_factor(L2w, z);
+        MIX_MARK(10);
         if (GOUT) {
-            wait_loads_at_most<0>();
+            if (F32) wait_loads_at_most<0>();
             __syncthreads();
         }
+        MIX_MARK(12);
         f32x4 o[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             o[r] = f32x4{z[0][r], z[1][r], z[2][r], z[3][r]};
-            if (GOUT) o[r] *= *reinterpret_cast<const f32x4 *>(zs + l16 * LDX + 16 * (4 * kg + r) + b0);
+            if (GOUT) o[r] *= *reinterpret_cast<const f32x4 *>(bufC + l16 * LDX + 16 * (4 * kg + r) + b0);
         }
         if (opt.layer_norm) {
-            // skip connection (u is still in xs: this lane's positions are read before it overwrites them), then the
-            // row's mean and variance in two passes: 16 values per lane, the 4 lane groups of a wave by shuffles,
-            // the 4 waves through LDS
+            // skip connection (this tile's u is still in its buffer), then the row's mean and variance in two
+            // passes: 16 values per lane, the 4 lane groups of a wave by shuffles, the 4 waves through LDS
             float part = 0.0f;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                o[r] += *reinterpret_cast<const f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0);
+                o[r] += *reinterpret_cast<const f32x4 *>(ub + l16 * LDX + 16 * (4 * kg + r) + b0);
                 part += o[r][0] + o[r][1] + o[r][2] + o[r][3];
             }
             part += __shfl_xor(part, 16);
@@ -401,42 +486,58 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
                 o[r] = o[r] * rstd * ld4((const T *)opt.gamma + j) + ld4((const T *)opt.beta + j);
             }
         }
+        // rows of y over the gates: every lane overwrites exactly the positions it has read
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            *reinterpret_cast<f32x4 *>(xs + l16 * LDX + 16 * (4 * kg + r) + b0) = o[r];   // (u is consumed)
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<f32x4 *>(bufC + l16 * LDX + 16 * (4 * kg + r) + b0) = o[r];
+        MIX_MARK(13);
         __syncthreads();
+        MIX_MARK(14);
         if (opt.transposed) {
             if (r0 + l16 < rows) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j = 4 * (wave + 4 * i) + kg;
-                    y[tbase + (int64_t)j * H + l16] = from_f32<T>(xs[l16 * LDX + j]);
+                    y[tbase + (int64_t)j * H + l16] = from_f32<T>(bufC[l16 * LDX + j]);
                 }
+            }
+        } else if constexpr (F32) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t r = r0 + b0 + q;
+                if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(bufC + (b0 + q) * LDX + 4 * lane);
             }
         } else {
-            if constexpr (F32) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t r = r0 + b0 + q;
-                    if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(xs + (b0 + q) * LDX + 4 * lane);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {   // two rows per instruction, 8 elements (16 bytes) per lane
-                    const int v = b0 + 2 * i + (lane >> 5);
-                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(xs + v * LDX + 8 * (lane & 31));
-                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(xs + v * LDX + 8 * (lane & 31) + 4);
-                    if (r0 + v < rows)
-                        *reinterpret_cast<uint4 *>(y + (r0 + v) * N + 8 * (lane & 31)) =
-                            uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
-                }
+            for (int i = 0; i < 2; ++i) {   // two rows per instruction, 8 elements (16 bytes) per lane
+                const int v = b0 + 2 * i + (lane >> 5);
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(bufC + v * LDX + 8 * (lane & 31));
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(bufC + v * LDX + 8 * (lane & 31) + 4);
+                if (r0 + v < rows)
+                    *reinterpret_cast<uint4 *>(y + (r0 + v) * N + 8 * (lane & 31)) =
+                        uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
             }
         }
-        __syncthreads();   // before the next tile's rows land
+        MIX_MARK(15);
+        // (no barrier here: the next tile's first barrier comes before anything of this tile's buffers is rewritten,
+        // except the inputs requested above into buffers that were free)
+        if (!GIN && next >= 0) {
+            float *t = ub;
+            ub = nb;
+            nb = t;
+        }
+
+        MIX_MARK(16);
     }
 }
 
 }  // namespace mix16
+
+#ifdef MONARCH_MIXER_CLOCKS
+extern "C" int monarch_debug_mixer_clocks(long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mix16::g_clk), sizeof(long long) * 4 * 32);
+}
+#endif
 
 bool mixer_fits(int bs) { return bs >= 1 && (size_t)2 * bs * bs * sizeof(float) <= 160 * 1024; }
 
