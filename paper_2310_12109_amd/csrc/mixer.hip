@@ -179,7 +179,7 @@ constexpr int LDX = N + 4;                 // pitch of the row buffers
 constexpr int RS = 18, LD = B * RS + 3;    // tile: element (v, p, q) at v LD + p RS + q
 constexpr int TRANSPOSED_RUN = 8;
 constexpr int STATS = 4 * TV;              // per wave and row: a partial sum (layer norm)
-constexpr size_t LDS_BYTES = sizeof(float) * (3 * TV * LDX + TV * LD + STATS);
+constexpr size_t LDS_BYTES = sizeof(float) * (3 * TV * LDX + TV * LD + STATS + 2 * N);
 
 __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
 {
@@ -237,6 +237,7 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
     float *bufC = bufB + TV * LDX;
     float *tt = bufC + TV * LDX;       // tile between the two factors of a matrix: (v, i, a)
     float *stats = tt + TV * LD;       // [4 waves][TV]
+    float *gb = stats + STATS;         // layer norm: weight [N], bias [N]
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
     const int b0 = 4 * wave;
@@ -253,6 +254,11 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             R2w[q][s] = to_f32(R2[at]);
             L2w[q][s] = to_f32(L2[at]);
         }
+
+    if (opt.layer_norm) {
+        gb[threadIdx.x] = to_f32(((const T *)opt.gamma)[threadIdx.x]);
+        gb[N + threadIdx.x] = to_f32(((const T *)opt.beta)[threadIdx.x]);   // (published by the first barrier of the loop)
+    }
 
     const int64_t ntiles = (rows + TV - 1) / TV;
     // This wave's four rows of a tile (4 w .. 4 w + 3; rows past the end: the last one, never stored) as 16-byte
@@ -295,6 +301,41 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             park_rows(w, dst);
         }
     };
+    // (B, N, H) layout: the 16 rows of a tile are 16 neighbouring channels of one sequence (H is a multiple of 16):
+    // 16 sizeof(T) contiguous bytes per position, i.e. TP 16-byte pieces of TE channels.  Lane l of instruction
+    // w + 4 i moves piece l % TP of position (w + 4 i) 64 / TP + l / TP; in LDS the values go to (channel, position)
+    // and back one by one (the banks of the 64 lanes differ).  All loads of an array are in flight before the first
+    // value is stored.  A tile never crosses the end of the batch in this layout.
+    constexpr int TP = (int)sizeof(T), TE = 16 / (int)sizeof(T);
+    auto tile_base = [&](int64_t r0) -> int64_t { return (r0 / H) * (int64_t)N * H + r0 % H; };
+    auto load_transposed = [&](const T *src, int64_t tbase, uint4 (&w)[TP]) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i) {
+            const int p = (wave + 4 * i) * (64 / TP) + lane / TP, c0 = (lane % TP) * TE;
+            w[i] = *reinterpret_cast<const uint4 *>(src + tbase + (int64_t)p * H + c0);
+        }
+    };
+    auto park_transposed = [&](const uint4 (&w)[TP], float *dst) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i) {
+            const int p = (wave + 4 * i) * (64 / TP) + lane / TP, c0 = (lane % TP) * TE;
+            float *d = dst + c0 * LDX + p;
+            if constexpr (F32) {
+                d[0] = __uint_as_float(w[i].x); d[LDX] = __uint_as_float(w[i].y);
+                d[2 * LDX] = __uint_as_float(w[i].z); d[3 * LDX] = __uint_as_float(w[i].w);
+            } else {
+                d[0] = __uint_as_float(w[i].x << 16); d[LDX] = __uint_as_float(w[i].x & 0xffff0000u);
+                d[2 * LDX] = __uint_as_float(w[i].y << 16); d[3 * LDX] = __uint_as_float(w[i].y & 0xffff0000u);
+                d[4 * LDX] = __uint_as_float(w[i].z << 16); d[5 * LDX] = __uint_as_float(w[i].z & 0xffff0000u);
+                d[6 * LDX] = __uint_as_float(w[i].w << 16); d[7 * LDX] = __uint_as_float(w[i].w & 0xffff0000u);
+            }
+        }
+    };
+    auto fetch_transposed = [&](const T *src, int64_t tbase, float *dst) {
+        uint4 w[TP];
+        load_transposed(src, tbase, w);
+        park_transposed(w, dst);
+    };
     // tile number of this workgroup's it-th tile (-1: none).  (B, N, H) layout: a tile covers 64 of the bytes of a
     // position; a workgroup takes `run` neighbouring tiles one after the other, so that the other bytes of the
     // lines it has fetched are used while they are still in its L2
@@ -305,10 +346,10 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         return first + it % run < ntiles ? first + it % run : -1;   // -1: a hole at the end of the last run
     };
 
-    // (float rows are not prefetched: the compiler's own waits for the register loads of a tile count loads in
+    // (float rows in the (B, H, N) layout are not prefetched: the compiler's own waits for the register loads of a tile count loads in
     // issue order and would also wait for direct-to-LDS loads of the next tile issued before them; the float
     // kernel runs at the rate of a plain copy as it is)
-    const bool prefetch = !F32 && !opt.transposed && !(opt.layer_norm && GIN);
+    const bool prefetch = (!F32 || opt.transposed) && !(opt.layer_norm && GIN);
     // the kernel entries a lane multiplies in S2: K[h_v][16 (4 kg + r) + b0 .. + 3], v = l16
     f32x4 kq[4];
     auto load_kernel = [&](int64_t r0, f32x4 (&k)[4]) {
@@ -320,35 +361,27 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
     };
     float *ub = bufA, *nb = bufB;      // rows of u of this tile; where the next tile's go when there are no input gates
     if (prefetch && tile_of(0) >= 0) {
-        fetch_now(u, tile_of(0) * TV, ub);
-        if (GIN) fetch_now(g_in, tile_of(0) * TV, bufB);
+        if (opt.transposed) {
+            fetch_transposed(u, tile_base(tile_of(0) * TV), ub);
+            if (GIN) fetch_transposed(g_in, tile_base(tile_of(0) * TV), bufB);
+        } else {
+            fetch_now(u, tile_of(0) * TV, ub);
+            if (GIN) fetch_now(g_in, tile_of(0) * TV, bufB);
+        }
     }
     for (int64_t it = 0;; ++it) {
         const int64_t tile = tile_of(it);
         if (tile == -2) break;
         if (tile < 0) continue;
         const int64_t r0 = tile * TV;
-        const int64_t next = prefetch ? tile_of(it + 1) : -1;   // (run = 1 whenever prefetch is on)
+        const int64_t next = prefetch ? tile_of(it + 1) : -1;
         MIX_MARK(0);
-        // (B, N, H) layout: the 16 rows of a tile are 16 neighbouring channels of one sequence (H is a multiple of
-        // 16), 64 contiguous bytes per position; lane (v = l16, kg) moves positions 4 (wave + 4 i) + kg of row v
-        const int64_t tbase = (r0 / H) * (int64_t)N * H + r0 % H;
-        if (opt.transposed) {
-            // (all sixteen loads of an array are in flight before the first value is stored)
-            float a[16], g[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int j = 4 * (wave + 4 * i) + kg;
-                a[i] = to_f32(u[tbase + (int64_t)j * H + l16]);
-                if (GIN) g[i] = to_f32(g_in[tbase + (int64_t)j * H + l16]);
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int j = 4 * (wave + 4 * i) + kg;
-                ub[l16 * LDX + j] = a[i];
-                if (GIN) bufB[l16 * LDX + j] = g[i];
-            }
-        } else if (!prefetch) {
+        const int64_t tbase = tile_base(r0);
+        if (prefetch) {
+        } else if (opt.transposed) {
+            fetch_transposed(u, tbase, ub);
+            if (GIN) fetch_transposed(g_in, tbase, bufB);
+        } else {
             fetch_now(u, r0, ub);
             if (GIN) fetch_now(g_in, r0, bufB);
         }
@@ -366,24 +399,27 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
                 xq[s] = *reinterpret_cast<const f32x4 *>(rows_in + l16 * LDX + 16 * (4 * kg + s) + b0);
                 if (gated) xq[s] *= *reinterpret_cast<const f32x4 *>(bufB + l16 * LDX + 16 * (4 * kg + s) + b0);
             }
+            // (the four blocks' accumulators in turn: an MFMA never waits for the one issued just before it)
+            f32x4 t[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f32x4 t = {0, 0, 0, 0};
+            for (int q = 0; q < 4; ++q) t[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) t = mfma(W[q][s], xq[s][q], t);   // rows i = 4 kg + r of block a = b0 + q
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tt[l16 * LD + (4 * kg + r) * RS + b0 + q] = t[r];   // (v, i, a)
-            }
+                for (int q = 0; q < 4; ++q) t[q] = mfma(W[q][s], xq[s][q], t[q]);   // rows i = 4 kg + r of block a = b0 + q
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tt[l16 * LD + (4 * kg + r) * RS + b0 + q] = t[q][r];   // (v, i, a)
         };
         auto second_factor = [&](const float (&W)[4][4], f32x4 (&out)[4]) {
             // block i = b0 + q contracts a = 4 kg + s of tile row i; result rows k = 4 kg + r: element 16 k + i
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f32x4 acc = {0, 0, 0, 0};
+            for (int q = 0; q < 4; ++q) out[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) acc = mfma(W[q][s], tt[l16 * LD + (b0 + q) * RS + 4 * kg + s], acc);
-                out[q] = acc;
-            }
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) out[q] = mfma(W[q][s], tt[l16 * LD + (b0 + q) * RS + 4 * kg + s], out[q]);
         };
 
         first_factor(ub, R1w, GIN);
@@ -391,20 +427,25 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         __syncthreads();
         MIX_MARK(5);
 
-        // requested here, to arrive while the next three stages run: this tile's output gates (bf16: rows, into
-        // registers; float rows come by direct-to-LDS loads once z is consumed) ...
+        // requested here, to arrive while the next three stages run: this tile's output gates (into registers; float
+        // rows in the (B, H, N) layout come by direct-to-LDS loads once z is consumed) ...
+        static_assert(NW == TP, "one register array serves both layouts");
         uint4 gq[NW];
-        if (!F32 && GOUT && !opt.transposed) load_rows(g_out, r0, gq);
+        if (GOUT) {
+            if (opt.transposed) load_transposed(g_out, tbase, gq);
+            else if (!F32) load_rows(g_out, r0, gq);
+        }
         // ... and the next tile's inputs: the first factor has consumed the buffers they go to
         float *u_next = GIN ? bufA : nb;
-        uint4 pu[NW], pg[NW];
+        constexpr int PW = NW > TP ? NW : TP;
+        uint4 pu[PW], pg[PW];
         if (next >= 0) {
-            if constexpr (F32) {
-                dma_rows(u, next * TV, u_next);
-                if (GIN) dma_rows(g_in, next * TV, bufB);
-            } else {
-                load_rows(u, next * TV, pu);
-                if (GIN) load_rows(g_in, next * TV, pg);
+            if (opt.transposed) {
+                load_transposed(u, tile_base(next * TV), reinterpret_cast<uint4(&)[TP]>(pu));
+                if (GIN) load_transposed(g_in, tile_base(next * TV), reinterpret_cast<uint4(&)[TP]>(pg));
+            } else if constexpr (!F32) {
+                load_rows(u, next * TV, reinterpret_cast<uint4(&)[NW]>(pu));
+                if (GIN) load_rows(g_in, next * TV, reinterpret_cast<uint4(&)[NW]>(pg));
             }
         }
 
@@ -424,20 +465,21 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         __syncthreads();   // z is consumed: the output gates take its place
         if (GOUT) {
             if (opt.transposed) {
-                float g[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) g[i] = to_f32(g_out[tbase + (int64_t)(4 * (wave + 4 * i) + kg) * H + l16]);
-#pragma unroll
-                for (int i = 0; i < 16; ++i) bufC[l16 * LDX + 4 * (wave + 4 * i) + kg] = g[i];
+                park_transposed(gq, bufC);
             } else if constexpr (F32) {
                 dma_rows(g_out, r0, bufC);
             } else {
                 park_rows(gq, bufC);
             }
         }
-        if (!F32 && next >= 0) {
-            park_rows(pu, u_next);
-            if (GIN) park_rows(pg, bufB);
+        if (next >= 0) {
+            if (opt.transposed) {
+                park_transposed(reinterpret_cast<uint4(&)[TP]>(pu), u_next);
+                if (GIN) park_transposed(reinterpret_cast<uint4(&)[TP]>(pg), bufB);
+            } else if constexpr (!F32) {
+                park_rows(reinterpret_cast<uint4(&)[NW]>(pu), u_next);
+                if (GIN) park_rows(reinterpret_cast<uint4(&)[NW]>(pg), bufB);
+            }
         }
         MIX_MARK(9);
         second_factor(L2w, z);
@@ -483,7 +525,7 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = 16 * (4 * kg + r) + b0;
-                o[r] = o[r] * rstd * ld4((const T *)opt.gamma + j) + ld4((const T *)opt.beta + j);
+                o[r] = o[r] * rstd * *reinterpret_cast<const f32x4 *>(gb + j) + *reinterpret_cast<const f32x4 *>(gb + N + j);
             }
         }
         // rows of y over the gates: every lane overwrites exactly the positions it has read
@@ -493,12 +535,15 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         __syncthreads();
         MIX_MARK(14);
         if (opt.transposed) {
-            if (r0 + l16 < rows) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int j = 4 * (wave + 4 * i) + kg;
-                    y[tbase + (int64_t)j * H + l16] = from_f32<T>(bufC[l16 * LDX + j]);
-                }
+            for (int i = 0; i < TP; ++i) {
+                const int p = (wave + 4 * i) * (64 / TP) + lane / TP, c0 = (lane % TP) * TE;
+                float v[TE];
+#pragma unroll
+                for (int e = 0; e < TE; ++e) v[e] = bufC[(c0 + e) * LDX + p];
+                T *dst = y + tbase + (int64_t)p * H + c0;
+                if constexpr (F32) *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+                else *reinterpret_cast<uint4 *>(dst) = uint4{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
             }
         } else if constexpr (F32) {
 #pragma unroll

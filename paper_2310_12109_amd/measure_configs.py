@@ -129,23 +129,25 @@ def matmul3(b, batch, reps):
     _report(f"order-3 backward fp32 b={b} N={N}, batch {batch}", _time(calls, reps), nb, batch * 8 * 2 * N * b, len(calls))
 
 
-def m2_layer(B, reps):
-    """The basic M2 layer at n = d = 256, fp32: x read, X~ written and read, y written (4 passes over B n d floats)."""
+def m2_layer(B, reps, dt=torch.float32):
+    """The basic M2 layer at n = d = 256: x read, X~ written and read, y written (4 passes over B n d elements)."""
     from . import workloads
     w = workloads.m2_layer_inputs(1, 16, 16, seed=0)
-    par = {k: torch.from_numpy(v).cuda() for k, v in w.items() if k != "x"}
+    par = {k: torch.from_numpy(v).cuda().to(dt) for k, v in w.items() if k != "x"}
+    es = 4 if dt == torch.float32 else 2
     seq, dim = [par[k] for k in ("R1", "L1", "R2", "L2")], [par[k] for k in ("R3", "L3", "R4", "L4")]
-    nbytes = 4 * B * 256 * 256 * 4 + 2 * 256 * 256 * 4
-    ws = torch.empty(binding.monarch_m2_layer_workspace_bytes(B, 256, 256, binding.F32), dtype=torch.uint8, device="cuda")
+    nbytes = (4 * B * 256 * 256 + 2 * 256 * 256) * es
+    ws = torch.empty(binding.monarch_m2_layer_workspace_bytes(B, 256, 256, binding.F32 if es == 4 else binding.BF16),
+                     dtype=torch.uint8, device="cuda")
 
     def make():
-        x = _rnd(B, 256, 256, dt=torch.float32)
+        x = _rnd(B, 256, 256, dt=dt)
         y = torch.empty_like(x)
         return lambda: binding.monarch_m2_layer(x, seq, par["n_kernel"], dim, par["d_kernel"], par["gamma"], par["beta"],
                                                 ws=ws, out=y)
     calls = _sets(make, nbytes)
     # two mixers of four block-diagonal products each: 8 * 2 * 256 * 16 FLOP per row of 256
-    _report(f"m2 layer fp32 n=256 d=256, B={B}", _time(calls, reps), nbytes, B * 2 * 256 * 8 * 2 * 256 * 16, len(calls))
+    _report(f"m2 layer {'fp32' if es == 4 else 'bf16'} n=256 d=256, B={B}", _time(calls, reps), nbytes, B * 2 * 256 * 8 * 2 * 256 * 16, len(calls))
 
 
 def blocky(B, H, reps):
@@ -256,6 +258,7 @@ def main():
     if want("layer"):
         m2_layer(32, 50)
         m2_layer(2048, 5)
+        m2_layer(2048, 5, torch.bfloat16)
     if want("blocky"):
         blocky(8, 768, 100)
         blocky(1024, 768, 5)
