@@ -344,14 +344,23 @@ __device__ long long g_clk[4][32];
 #define BLK_MARK(i)
 #endif
 
-// KS1: K steps of S1 that can hold live input (2 for n <= 128, else 4); n is a multiple of 16
-template <int KS1>
-__global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restrict__ u, const float *__restrict__ g_in,
-                                                          const float *__restrict__ g_out, const float2 *__restrict__ R1,
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const bf16_t a = from_f32<bf16_t>(lo), b = from_f32<bf16_t>(hi);
+    return (uint32_t) * reinterpret_cast<const uint16_t *>(&a) | ((uint32_t) * reinterpret_cast<const uint16_t *>(&b) << 16);
+}
+
+// KS1: K steps of S1 that can hold live input (2 for n <= 128, else 4); n is a multiple of 16.
+// T: type of u, the gates and y in memory.  float tiles arrive by direct-to-LDS loads; bf16 tiles pass through
+// registers (8 elements per lane and instruction) and are widened on the way into LDS: everything on chip is float.
+template <typename T, int KS1>
+__global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ u, const T *__restrict__ g_in,
+                                                          const T *__restrict__ g_out, const float2 *__restrict__ R1,
                                                           const float2 *__restrict__ L1, const float2 *__restrict__ R2,
                                                           const float2 *__restrict__ L2, const f32x4 *__restrict__ Kq,
-                                                          float *__restrict__ y, int64_t rows, int H, int n)
+                                                          T *__restrict__ y, int64_t rows, int H, int n)
 {
+    constexpr bool F32 = sizeof(T) == 4;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float *xa = smem;              // u; then Re z; then g_out
     float *xb = xa + ROWBUF;       // g_in; then Im z; then the rows of y
@@ -382,8 +391,34 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
 
     const int64_t ntiles = (rows + TV - 1) / TV;
     const int nchunks = n / 16;                 // 16 n floats per tile, 256 per chunk
-    const int64_t last_piece = rows * n - 4;
+    const int64_t last_piece = rows * n - (F32 ? 4 : 8);
     const uint32_t xa_addr = lds_address(xa), xb_addr = lds_address(xb);
+    // the 16 n contiguous elements of a tile of one array into an LDS row buffer (chunked layout); elements past
+    // the end of the batch repeat the last piece and are never stored
+    auto fetch_tile = [&](const T *src, int64_t base, float *dst, uint32_t dst_addr) {
+        if constexpr (F32) {
+            for (int q = wave; q < nchunks; q += 4) {
+                int64_t at = base + 256 * q + 4 * lane;
+                if (at > last_piece) at = last_piece;
+                dma_16_at(src + at, dst_addr + (uint32_t)q * CH * 4);
+            }
+        } else {
+            // instruction q moves elements 512 q + 8 lane .. + 7 of the tile (two chunks of 256)
+            for (int q = wave; 512 * q < 16 * n; q += 4) {
+                const int f = 512 * q + 8 * lane;
+                if (f < 16 * n) {
+                    int64_t at = base + f;
+                    if (at > last_piece) at = last_piece;
+                    const uint4 w = *reinterpret_cast<const uint4 *>(src + at);
+                    float *d = dst + chunked(f);
+                    *reinterpret_cast<f32x4 *>(d) = f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
+                                                          __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u)};
+                    *reinterpret_cast<f32x4 *>(d + 4) = f32x4{__uint_as_float(w.z << 16), __uint_as_float(w.z & 0xffff0000u),
+                                                              __uint_as_float(w.w << 16), __uint_as_float(w.w & 0xffff0000u)};
+                }
+            }
+        }
+    };
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t r0 = tile * TV, base = r0 * n;
         BLK_MARK(0);
@@ -401,12 +436,8 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
                 k23[r] = kq[(2 * r + 1) * 4];
             }
         }
-        for (int q = wave; q < nchunks; q += 4) {
-            int64_t at = base + 256 * q + 4 * lane;
-            if (at > last_piece) at = last_piece;   // (rows past the end of the batch: never stored)
-            dma_16_at(u + at, xa_addr + (uint32_t)q * CH * 4);
-            if (g_in) dma_16_at(g_in + at, xb_addr + (uint32_t)q * CH * 4);
-        }
+        fetch_tile(u, base, xa, xa_addr);
+        if (g_in) fetch_tile(g_in, base, xb, xb_addr);
         BLK_MARK(1);
         wait_loads_at_most<0>();
         BLK_MARK(2);
@@ -518,12 +549,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
         }
         BLK_MARK(8);
         __syncthreads();   // z is consumed: the output gates land where Re z was while the last factor runs
-        if (g_out)
-            for (int q = wave; q < nchunks; q += 4) {
-                int64_t at = base + 256 * q + 4 * lane;
-                if (at > last_piece) at = last_piece;
-                dma_16_at(g_out + at, xa_addr + (uint32_t)q * CH * 4);
-            }
+        if (g_out) fetch_tile(g_out, base, xa, xa_addr);
 
         // ---- S4: real part of complex L2
         BLK_MARK(9);
@@ -557,9 +583,21 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
         BLK_MARK(13);
         __syncthreads();
         BLK_MARK(14);
-        for (int q = wave; q < nchunks; q += 4) {
-            const int64_t at = base + 256 * q + 4 * lane;
-            if (at <= last_piece) *reinterpret_cast<f32x4 *>(y + at) = *reinterpret_cast<const f32x4 *>(xb + q * CH + 4 * lane);
+        if constexpr (F32) {
+            for (int q = wave; q < nchunks; q += 4) {
+                const int64_t at = base + 256 * q + 4 * lane;
+                if (at <= last_piece) *reinterpret_cast<f32x4 *>(y + at) = *reinterpret_cast<const f32x4 *>(xb + q * CH + 4 * lane);
+            }
+        } else {
+            for (int q = wave; 512 * q < 16 * n; q += 4) {
+                const int f = 512 * q + 8 * lane;
+                if (f < 16 * n && base + f <= last_piece) {
+                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(xb + chunked(f));
+                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(xb + chunked(f) + 4);
+                    *reinterpret_cast<uint4 *>(y + base + f) =
+                        uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+                }
+            }
         }
         BLK_MARK(15);
         __syncthreads();   // before the next tile's rows land
@@ -567,10 +605,10 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const float *__restric
     }
 }
 
-static bool supported(int bs, int n, monarch_dtype dt) { return bs == 16 && dt == MONARCH_F32 && n >= 16 && n % 16 == 0; }
+static bool supported(int bs, int n, monarch_dtype) { return bs == 16 && n >= 16 && n % 16 == 0; }
 
 static int launch(const void *u, const void *g_in, const void *g_out, const unsigned char *state, void *y, int64_t rows,
-                  int H, int n, hipStream_t s)
+                  int H, int n, monarch_dtype dt, hipStream_t s)
 {
     const blocky::Layout l = blocky::layout(H, 16);
     int dev = 0, ncu = 0;
@@ -579,18 +617,23 @@ static int launch(const void *u, const void *g_in, const void *g_out, const unsi
     const int64_t ntiles = (rows + TV - 1) / TV;
     int64_t grid = 2 * (int64_t)ncu;
     if (grid > ntiles) grid = ntiles;
-#define MONARCH_LAUNCH_BLOCKY16(KS)                                                                                \
+#define MONARCH_LAUNCH_BLOCKY16(T, KS)                                                                             \
     do {                                                                                                           \
-        auto kern = conv_b16_kernel<KS>;                                                                           \
+        auto kern = conv_b16_kernel<T, KS>;                                                                        \
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
                                               (int)LDS_BYTES));                                                    \
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), LDS_BYTES, s, (const float *)u,                  \
-                           (const float *)g_in, (const float *)g_out, (const float2 *)(state + l.R1),              \
-                           (const float2 *)(state + l.L1), (const float2 *)(state + l.R2),                         \
-                           (const float2 *)(state + l.L2), (const f32x4 *)(state + l.Kq), (float *)y, rows, H, n); \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), LDS_BYTES, s, (const T *)u, (const T *)g_in,     \
+                           (const T *)g_out, (const float2 *)(state + l.R1), (const float2 *)(state + l.L1),       \
+                           (const float2 *)(state + l.R2), (const float2 *)(state + l.L2),                         \
+                           (const f32x4 *)(state + l.Kq), (T *)y, rows, H, n);                                     \
     } while (0)
-    if (n <= 128) MONARCH_LAUNCH_BLOCKY16(2);
-    else MONARCH_LAUNCH_BLOCKY16(4);
+    if (dt == MONARCH_F32) {
+        if (n <= 128) MONARCH_LAUNCH_BLOCKY16(float, 2);
+        else MONARCH_LAUNCH_BLOCKY16(float, 4);
+    } else {
+        if (n <= 128) MONARCH_LAUNCH_BLOCKY16(bf16_t, 2);
+        else MONARCH_LAUNCH_BLOCKY16(bf16_t, 4);
+    }
 #undef MONARCH_LAUNCH_BLOCKY16
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
@@ -637,7 +680,7 @@ int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const
 {
     if (rows == 0 || n == 0) return MONARCH_OK;
     const unsigned char *st = static_cast<const unsigned char *>(state);
-    if (blocky16::supported(bs, n, dt)) return blocky16::launch(u, g_in, g_out, st, y, rows, H, n, s);
+    if (blocky16::supported(bs, n, dt)) return blocky16::launch(u, g_in, g_out, st, y, rows, H, n, dt, s);
     if (dt == MONARCH_F32) return blocky::launch_conv_typed<float>(u, g_in, g_out, st, y, rows, H, n, bs, s);
     return blocky::launch_conv_typed<bf16_t>(u, g_in, g_out, st, y, rows, H, n, bs, s);
 }

@@ -150,24 +150,26 @@ def m2_layer(B, reps, dt=torch.float32):
     _report(f"m2 layer {'fp32' if es == 4 else 'bf16'} n=256 d=256, B={B}", _time(calls, reps), nbytes, B * 2 * 256 * 8 * 2 * 256 * 16, len(calls))
 
 
-def blocky(B, H, reps):
-    """Causal convolution with a polynomial-parameterised Monarch matrix, N = 256, n = 128, fp32: u and both gates
-    read, y written (2 KB per row); 704 complex-arithmetic MFMAs of 2048 FLOP per 16 rows."""
+def blocky(B, H, reps, dt=torch.float32):
+    """Causal convolution with a polynomial-parameterised Monarch matrix, N = 256, n = 128: u and both gates
+    read, y written; 704 complex-arithmetic MFMAs of 2048 FLOP per 16 rows."""
     from . import workloads
     rows, n = B * H, 128
-    nbytes = 4 * rows * n * 4 + H * 256 * 8 + 4 * 4096 * 8
+    es = 4 if dt == torch.float32 else 2
+    nbytes = 4 * rows * n * es + H * 256 * 8 + 4 * 4096 * 8
     w = workloads.blocky_inputs(1, H, n, 16, seed=0)
     par = [torch.from_numpy(w[k]).cuda() for k in ("Lt", "Rt", "k")]
     state = binding.monarch_blocky_prepare(*par, mask=True)
 
     def make():
-        u, gi, go = (_rnd(B, H, n, dt=torch.float32) for _ in range(3))
+        u, gi, go = (_rnd(B, H, n, dt=dt) for _ in range(3))
         y = torch.empty_like(u)
         return lambda: binding.monarch_blocky_conv(u, gi, go, state, 16, out=y)
     calls = _sets(make, nbytes)
-    _report(f"blocky conv fp32 N=256 n=128, B={B} H={H}", _time(calls, reps), nbytes, rows / 16 * 704 * 2048, len(calls))
-    t = _time([lambda: binding.monarch_blocky_prepare(*par, mask=True, state=state)], 20)
-    print(f"blocky prepare (factors, blockwise inverses, {H} kernels transformed) {t:9.1f} us", flush=True)
+    _report(f"blocky conv {'fp32' if es == 4 else 'bf16'} N=256 n=128, B={B} H={H}", _time(calls, reps), nbytes, rows / 16 * 704 * 2048, len(calls))
+    if es == 4 and B <= 8:
+        t = _time([lambda: binding.monarch_blocky_prepare(*par, mask=True, state=state)], 20)
+        print(f"blocky prepare (factors, blockwise inverses, {H} kernels transformed) {t:9.1f} us", flush=True)
 
 
 def conv(name, B, H, n, factors, dt, reps):
@@ -262,6 +264,7 @@ def main():
     if want("blocky"):
         blocky(8, 768, 100)
         blocky(1024, 768, 5)
+        blocky(1024, 768, 5, torch.bfloat16)
     if want("c2"):
         conv("c2 conv bf16 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.bfloat16, 200)
         conv("c2 conv fp32 B=8 H=768 n=1024 64x32", 8, 768, 1024, (64, 32), torch.float32, 50)

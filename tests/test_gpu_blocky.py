@@ -124,6 +124,18 @@ def test_bf16(mm, b, n):
     assert rel_l2(host(y), _want(w)) <= TOL_BF16
 
 
+@pytest.mark.parametrize("n,B,H", [(128, 7, 93), (48, 3, 7), (256, 2, 5), (16, 3, 5)])
+def test_bf16_b16_matrix_core_kernel(mm, n, B, H):
+    # bf16 tiles through the matrix-core kernel: many ragged tiles; a tile that fills one and a half load
+    # instructions (n = 48); rows longer than 128 (no mask: the lemma allows at most 128 taps); the shortest rows
+    announce("blocky conv bf16 b=16 n, B, H", n, B, H)
+    mask = n <= 128
+    w = workloads.blocky_inputs(B, H, n, 16, seed=n + B, noise=0.05 if mask else 0.01, bf16=True)
+    y = _conv(mm, w, 16, mask=mask, bf16=True)
+    assert y.dtype == torch.bfloat16
+    assert rel_l2(host(y), _want(w, mask=mask)) <= TOL_BF16
+
+
 def test_output_is_causal_on_the_gpu(mm):
     announce("blocky conv causality")
     w = workloads.blocky_inputs(1, 3, 128, 16, seed=4)
