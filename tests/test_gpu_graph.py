@@ -59,3 +59,32 @@ def test_graph_replays_of_the_matmul_gradients_match_eager():
         for got, want in ((outs["dR"], wantR), (outs["dL"], wantL)):
             err = float((got - want).norm() / want.norm())
             assert err <= 1e-5, f"replay {rep}: {err}"
+
+
+def test_graph_replays_of_the_layer_and_the_blocky_convolution_match_eager():
+    # two-kernel entry points (layer: workspace between the kernels; blocky: prepared state) captured and replayed
+    from paper_2310_12109_amd import binding
+    announce("layer + blocky conv graph replay")
+    w = workloads.m2_layer_inputs(3, 16, 16, seed=6)
+    d = {k: dev(v) for k, v in w.items()}
+    seq, dim = [d[k] for k in ("R1", "L1", "R2", "L2")], [d[k] for k in ("R3", "L3", "R4", "L4")]
+    ws = torch.empty(binding.monarch_m2_layer_workspace_bytes(3, 256, 256, binding.F32), dtype=torch.uint8, device="cuda")
+    want_layer = binding.monarch_m2_layer(d["x"], seq, d["n_kernel"], dim, d["d_kernel"], d["gamma"], d["beta"], ws=ws).clone()
+    wb = workloads.blocky_inputs(3, 20, 128, 16, seed=7)
+    state = binding.monarch_blocky_prepare(dev(wb["Lt"]), dev(wb["Rt"]), dev(wb["k"]), mask=True)
+    u, gi, go = dev(wb["u"]), dev(wb["g_in"]), dev(wb["g_out"])
+    want_conv = binding.monarch_blocky_conv(u, gi, go, state, 16).clone()
+    torch.cuda.synchronize()
+    out_layer, out_conv = torch.empty_like(want_layer), torch.empty_like(want_conv)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.monarch_m2_layer(d["x"], seq, d["n_kernel"], dim, d["d_kernel"], d["gamma"], d["beta"], ws=ws, out=out_layer)
+        binding.monarch_blocky_conv(u, gi, go, state, 16, out=out_conv)
+    for rep in range(3):
+        out_layer.zero_(); out_conv.zero_(); ws.zero_()
+        binding.monarch_mixer(u.new_zeros(1, 4, 256), u.new_zeros(4, 256), None, None, *seq)   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_layer, want_layer), f"layer: replay {rep} differs from the eager result"
+        assert torch.equal(out_conv, want_conv), f"blocky conv: replay {rep} differs from the eager result"
