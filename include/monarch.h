@@ -175,14 +175,18 @@ size_t monarch_m2_layer_workspace_bytes(int64_t B, int n, int d, monarch_dtype d
  *
  * monarch_blocky_prepare (once per parameter update): evaluates the factors in float64, inverts the blocks
  * (Gauss-Jordan, partial pivoting, float64), transforms the kernels k (H, klen; float32), and writes all of it as
- * complex float32 into `state` (device memory of the caller, monarch_blocky_state_bytes(H, bs) bytes; its layout is
- * private).  A singular block yields non-finite values in the state and in every later output.
+ * complex float32 into `state` (device memory of the caller, monarch_blocky_state_bytes(H, bs) bytes; see
+ * monarch_blocky_state_offsets).  A singular block yields non-finite values in the state and in every later output.
  * monarch_blocky_conv (per batch): u, g_in, g_out, y: (B, H, n) of type dt, n <= N; gates may be NULL; reads the
  * state, writes nothing but y; complex float32 arithmetic, rows stay on chip from load to store.
  * Errors: EINVAL (null or misaligned pointers, mask not 0 / 1, overlap), ESHAPE (bs outside [2, 64], klen or n
  * beyond N, klen beyond bs * floor(bs / 2) with the mask), EWORKSPACE (state too small), EDTYPE, EHIP.
  */
 size_t monarch_blocky_state_bytes(int H, int bs);
+/* For inspection and tests: byte offsets, within a prepared state, of the complex float32 arrays R1, L1 (factors
+ * of M), R2, L2 (factors of M^-1, R2 = blockwise L^-1 applied first), each [bs][bs][bs], and Kf (H, N), written to
+ * host_out[0..4] (host memory). */
+int monarch_blocky_state_offsets(int H, int bs, size_t *host_out);
 int monarch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
                            void *state, size_t state_bytes, monarch_stream_t stream);
 int monarch_blocky_conv(const void *u, const void *g_in, const void *g_out, const void *state, size_t state_bytes,

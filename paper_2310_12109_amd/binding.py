@@ -45,6 +45,7 @@ _lib.monarch_mixer_workspace_bytes.restype = _sz
 _lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
 _lib.monarch_blocky_state_bytes.restype = _sz
 _lib.monarch_blocky_state_bytes.argtypes = [_i, _i]
+_lib.monarch_blocky_state_offsets.argtypes = [_i, _i, ctypes.POINTER(ctypes.c_size_t)]
 _lib.monarch_blocky_prepare.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_blocky_conv.argtypes = [_vp, _vp, _vp, _vp, _sz, _vp, _i64, _i, _i, _i, _i, _vp]
 _lib.monarch_fft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
@@ -65,7 +66,7 @@ EXPORTS = [
     "monarch_matmul3", "monarch_matmul3_backward",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
     "monarch_m2_layer", "monarch_m2_layer_workspace_bytes",
-    "monarch_blocky_state_bytes", "monarch_blocky_prepare", "monarch_blocky_conv",
+    "monarch_blocky_state_bytes", "monarch_blocky_state_offsets", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
     "monarch_mlp", "monarch_mlp_workspace_bytes",
@@ -225,16 +226,10 @@ def monarch_blocky_conv(u, g_in, g_out, state, bs, out=None):
 def blocky_state_views(state, H, bs):
     """The parts of a prepared state as complex64 tensors (R1, L1, R2, L2: (bs, bs, bs); Kf: (H, N)), for tests."""
     N = bs * bs
-
-    def up(v):
-        return (v + 255) & ~255
-    f = up(N * bs * 8)
-    off = up(N * 16)
-    parts = []
-    for _ in range(4):
-        parts.append(state[off:off + N * bs * 8].view(torch.complex64).reshape(bs, bs, bs))
-        off += f
-    parts.append(state[off:off + H * N * 8].view(torch.complex64).reshape(H, N))
+    off = (ctypes.c_size_t * 5)()
+    _check(_lib.monarch_blocky_state_offsets(H, bs, off))
+    parts = [state[off[i]:off[i] + N * bs * 8].view(torch.complex64).reshape(bs, bs, bs) for i in range(4)]
+    parts.append(state[off[4]:off[4] + H * N * 8].view(torch.complex64).reshape(H, N))
     return parts
 
 

@@ -339,6 +339,15 @@ size_t monarch_blocky_state_bytes(int H, int bs)
     return blocky_state_bytes(H, bs);
 }
 
+int monarch_blocky_state_offsets(int H, int bs, size_t *host_out)
+{
+    clear_error();
+    if (H < 0 || !blocky_fits(bs)) return fail(MONARCH_ESHAPE, "H must be >= 0 and the block size in [2, 64]");
+    if (!host_out) return fail(MONARCH_EINVAL, "host_out must be non-NULL");
+    blocky_state_offsets(H, bs, host_out);
+    return MONARCH_OK;
+}
+
 int monarch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
                            void *state, size_t state_bytes, monarch_stream_t stream)
 {

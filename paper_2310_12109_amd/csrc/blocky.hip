@@ -652,6 +652,16 @@ bool blocky_fits(int bs) { return bs >= 2 && bs <= 64; }   // a row twice in LDS
 
 size_t blocky_state_bytes(int H, int bs) { return blocky::layout(H, bs).total; }
 
+void blocky_state_offsets(int H, int bs, size_t out[5])
+{
+    const blocky::Layout l = blocky::layout(H, bs);
+    out[0] = l.R1;
+    out[1] = l.L1;
+    out[2] = l.R2;
+    out[3] = l.L2;
+    out[4] = l.Kf;
+}
+
 int launch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
                           void *state, hipStream_t s)
 {

@@ -108,6 +108,7 @@ int launch_matmul3_backward(const void *x, const void *B1, const void *B2, const
 // polynomial-parameterised Monarch convolution (csrc/blocky.hip): parameter phase and per-batch phase
 bool blocky_fits(int bs);
 size_t blocky_state_bytes(int H, int bs);
+void blocky_state_offsets(int H, int bs, size_t out[5]);   // byte offsets of R1, L1, R2, L2, Kf
 int launch_blocky_prepare(const float *Lt, const float *Rt, const float *k, int H, int klen, int bs, int mask,
                           void *state, hipStream_t s);
 int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const void *state, void *y, int64_t rows,

@@ -168,6 +168,13 @@ def test_blocky_rejects_bad_arguments(lib):
     need = lib.monarch_blocky_state_bytes(4, 16)
     assert need >= 256 * 16 + 4 * 4096 * 8 + 4 * 256 * 8
     assert lib.monarch_blocky_state_bytes(4, 65) == 0
+    off = (ctypes.c_size_t * 5)()
+    lib.monarch_blocky_state_offsets.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    assert lib.monarch_blocky_state_offsets(4, 16, off) == 0
+    assert list(off) == sorted(off) and off[0] >= 256 * 16 and off[4] + 4 * 256 * 8 <= need
+    assert all(o % 256 == 0 for o in off) and off[1] - off[0] >= 4096 * 8
+    assert lib.monarch_blocky_state_offsets(4, 65, off) == ESHAPE
+    assert lib.monarch_blocky_state_offsets(4, 16, None) == EINVAL
     p = lib.monarch_blocky_prepare
     p.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 4 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     Lt, Rt, k, st = FAKE, FAKE * 8, FAKE * 16, FAKE * 64
