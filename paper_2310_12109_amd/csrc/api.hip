@@ -136,7 +136,7 @@ int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t
     if (overlaps(y, (size_t)batch * d_out * es, x, (size_t)batch * d_in * es))
         return fail(MONARCH_EINVAL, "y overlaps x");
     if (matmul_mfma_b16_supported(nbR, r_out, r_in, nbL, l_out, l_in, dt))
-        return launch_matmul_mfma_b16(x, R, L, y, batch, (hipStream_t)stream);
+        return launch_matmul_mfma_b16(x, R, L, y, batch, dt, (hipStream_t)stream);
     return launch_matmul_generic(x, R, L, nullptr, y, batch, nbR, r_out, r_in, nbL, l_out, l_in, 2, 0,
                                  dt, dt, dt, (hipStream_t)stream);
 }

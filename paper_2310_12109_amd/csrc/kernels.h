@@ -58,7 +58,8 @@ int launch_fft_pass_mfma_f32(const FftPass &p, hipStream_t s);
 
 // Square order-2 Monarch with 16 blocks of 16 x 16 (N = 256), fp32 storage and arithmetic.
 bool matmul_mfma_b16_supported(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in, monarch_dtype dt);
-int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y, int64_t batch, hipStream_t s);
+int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y, int64_t batch, monarch_dtype dt,
+                           hipStream_t s);
 
 // Two factors at once on chunks of f1 x f2 complex numbers held in LDS (bf16; see fft2_lds.hip).  The
 // spectrum is left in the forward's in-place order (position [j1][j2] = frequency j2 f1 + j1) and the

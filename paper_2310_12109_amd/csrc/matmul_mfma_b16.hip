@@ -1,5 +1,5 @@
-// Order-2 Monarch matrix multiply y = P L P R P x for the square case b = 16 (N = 256), fp32
-// (Sec. 3.1).  HBM-bound: 2 KB of traffic and 16 KFLOP per vector.
+// Order-2 Monarch matrix multiply y = P L P R P x for the square case b = 16 (N = 256), fp32 or bf16
+// tensors, fp32 arithmetic (Sec. 3.1).  HBM-bound: 2 KB (fp32) of traffic and 16 KFLOP per vector.
 //
 // Persistent waves, each on its own tile of 16 vectors; vectors sit on the MFMA column index.
 //   stage 1, block a:  T_a[i, v] = sum_c R_a[i, c] x[v][16c + a]     (16x16x4 fp32 MFMA, 4 k-steps)
@@ -38,10 +38,26 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-__global__ __launch_bounds__(256, 2) void monarch_b16_f32_kernel(const float *__restrict__ x,
-                                                                 const float *__restrict__ R,
-                                                                 const float *__restrict__ L,
-                                                                 float *__restrict__ y, int64_t batch)
+// four consecutive elements as floats (float: 16-byte aligned; bf16: 8-byte aligned)
+__device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ f32x4 ld4(const bf16_t *p)
+{
+    const uint2 w = *reinterpret_cast<const uint2 *>(p);
+    return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                 __uint_as_float(w.y & 0xffff0000u)};
+}
+__device__ __forceinline__ void st4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+__device__ __forceinline__ void st4(bf16_t *p, f32x4 v)
+{
+    const bf16_t h[4] = {from_f32<bf16_t>(v[0]), from_f32<bf16_t>(v[1]), from_f32<bf16_t>(v[2]), from_f32<bf16_t>(v[3])};
+    *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(h);
+}
+
+// T: type of x, R, L and y in memory; registers, LDS and the arithmetic are float.
+template <typename T>
+__global__ __launch_bounds__(256, 2) void monarch_b16_kernel(const T *__restrict__ x, const T *__restrict__ R,
+                                                             const T *__restrict__ L, T *__restrict__ y,
+                                                             int64_t batch)
 {
     extern __shared__ __attribute__((aligned(16))) float tiles[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -52,8 +68,8 @@ __global__ __launch_bounds__(256, 2) void monarch_b16_f32_kernel(const float *__
     float Rw[B][4], Lw[B][4];
 #pragma unroll
     for (int m = 0; m < B; ++m) {
-        const f32x4 r = *reinterpret_cast<const f32x4 *>(R + (m * B + l16) * B + 4 * kg);
-        const f32x4 l = *reinterpret_cast<const f32x4 *>(L + (m * B + l16) * B + 4 * kg);
+        const f32x4 r = ld4(R + (m * B + l16) * B + 4 * kg);
+        const f32x4 l = ld4(L + (m * B + l16) * B + 4 * kg);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             Rw[m][s] = r[s];
@@ -72,11 +88,11 @@ __global__ __launch_bounds__(256, 2) void monarch_b16_f32_kernel(const float *__
     auto request = [&](int64_t tile_index) {
         int64_t v = tile_index * TV + l16;
         if (v >= batch) v = batch - 1;
-        const float *xrow = x + v * N + 64 * kg;
+        const T *xrow = x + v * N + 64 * kg;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) xq[s][q] = *reinterpret_cast<const f32x4 *>(xrow + 16 * s + 4 * q);
+            for (int q = 0; q < 4; ++q) xq[s][q] = ld4(xrow + 16 * s + 4 * q);
     };
     request(t);
 
@@ -106,14 +122,14 @@ __global__ __launch_bounds__(256, 2) void monarch_b16_f32_kernel(const float *__
         }
         wave_sync();
         // y[v][16k + i] = (v, row i, col k).  Lane -> (k = lane / 4, i = 4 (lane % 4) + e): one 16-byte
-        // store per lane, a whole vector (1 KB, contiguous) per instruction.
+        // (bf16: 8-byte) store per lane, a whole vector (contiguous) per instruction.
         const float *src = tile + (4 * (lane & 3)) * RS + (lane >> 2);
 #pragma unroll
         for (int vv = 0; vv < TV; ++vv) {
             f32x4 val;
 #pragma unroll
             for (int e = 0; e < 4; ++e) val[e] = src[vv * LD + e * RS];
-            if (v0 + vv < batch) *reinterpret_cast<f32x4 *>(y + (v0 + vv) * N + 4 * lane) = val;
+            if (v0 + vv < batch) st4(y + (v0 + vv) * N + 4 * lane, val);
         }
         wave_sync();
     }
@@ -123,10 +139,11 @@ __global__ __launch_bounds__(256, 2) void monarch_b16_f32_kernel(const float *__
 
 bool matmul_mfma_b16_supported(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in, monarch_dtype dt)
 {
-    return dt == MONARCH_F32 && nbR == 16 && r_out == 16 && r_in == 16 && nbL == 16 && l_out == 16 && l_in == 16;
+    return (dt == MONARCH_F32 || dt == MONARCH_BF16) && nbR == 16 && r_out == 16 && r_in == 16 && nbL == 16 && l_out == 16 && l_in == 16;
 }
 
-int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y, int64_t batch, hipStream_t s)
+int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y, int64_t batch, monarch_dtype dt,
+                           hipStream_t s)
 {
     int dev = 0, ncu = 0;
     MONARCH_HIP_CHECK(hipGetDevice(&dev));
@@ -135,10 +152,17 @@ int launch_matmul_mfma_b16(const void *x, const void *R, const void *L, void *y,
     const int64_t wgs_needed = (ntiles + mm16::WAVES - 1) / mm16::WAVES;
     const int64_t slots = 2 * (int64_t)ncu;   // two workgroups (8 waves) per compute unit
     const unsigned grid = (unsigned)(wgs_needed < slots ? wgs_needed : slots);
-    MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mm16::monarch_b16_f32_kernel,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)mm16::LDS_BYTES));
-    hipLaunchKernelGGL(mm16::monarch_b16_f32_kernel, dim3(grid), dim3(256), mm16::LDS_BYTES, s, (const float *)x, (const float *)R,
-                       (const float *)L, (float *)y, batch);
+    if (dt == MONARCH_F32) {
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mm16::monarch_b16_kernel<float>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)mm16::LDS_BYTES));
+        hipLaunchKernelGGL(mm16::monarch_b16_kernel<float>, dim3(grid), dim3(256), mm16::LDS_BYTES, s, (const float *)x,
+                           (const float *)R, (const float *)L, (float *)y, batch);
+    } else {
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mm16::monarch_b16_kernel<bf16_t>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)mm16::LDS_BYTES));
+        hipLaunchKernelGGL(mm16::monarch_b16_kernel<bf16_t>, dim3(grid), dim3(256), mm16::LDS_BYTES, s, (const bf16_t *)x,
+                           (const bf16_t *)R, (const bf16_t *)L, (bf16_t *)y, batch);
+    }
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }

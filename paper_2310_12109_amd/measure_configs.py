@@ -53,16 +53,17 @@ def _report(name, us, nbytes, flops, nsets):
           f"[{nsets} buffer sets]", flush=True)
 
 
-def matmul_c1(batch, reps):
-    nbytes = 2 * batch * 256 * 4 + 2 * 16 * 256 * 4
-    R, L = _rnd(16, 16, 16, dt=torch.float32, scale=.25), _rnd(16, 16, 16, dt=torch.float32, scale=.25)
+def matmul_c1(batch, reps, dt=torch.float32):
+    es = 4 if dt == torch.float32 else 2
+    nbytes = (2 * batch * 256 + 2 * 16 * 256) * es
+    R, L = _rnd(16, 16, 16, dt=dt, scale=.25), _rnd(16, 16, 16, dt=dt, scale=.25)
 
     def make():
-        x = _rnd(batch, 256, dt=torch.float32)
+        x = _rnd(batch, 256, dt=dt)
         y = torch.empty_like(x)
         return lambda: binding.monarch_matmul(x, R, L, out=y)
     calls = _sets(make, nbytes)
-    _report(f"c1 matmul fp32 16x16 blocks, batch {batch}", _time(calls, reps), nbytes, batch * 4 * 256 * 16, len(calls))
+    _report(f"c1 matmul {'fp32' if es == 4 else 'bf16'} 16x16 blocks, batch {batch}", _time(calls, reps), nbytes, batch * 4 * 256 * 16, len(calls))
 
 
 def plain_copy(mbytes, reps):
@@ -243,6 +244,7 @@ def main():
     if want("c1"):
         matmul_c1(64, 200)
         matmul_c1(1 << 20, 10)
+        matmul_c1(1 << 20, 10, torch.bfloat16)
     if want("copy"):
         for mb in (12.6, 25.2, 50.4, 201, 805):
             plain_copy(mb, 100 if mb < 100 else 20)

@@ -60,6 +60,25 @@ def test_bf16_inputs(mm, b):
     assert rel_l2(y, oracle.matmul(w["x"], w["R"], w["L"])) <= TOL_BF16
 
 
+@pytest.mark.parametrize("batch", [1, 16, 5000, 20011])
+def test_bf16_config1_shape_on_the_matrix_cores(mm, batch):
+    # bf16 tensors through the fp32 MFMA kernel of config 1: one vector, one tile, many ragged tiles, more tiles
+    # than waves
+    announce("matmul bf16 b=16 batch", batch)
+    w = workloads.monarch_matmul_inputs(batch=batch, b=16, seed=batch, bf16=True)
+    y = mm.monarch_matmul(dev(w["x"], True), dev(w["R"], True), dev(w["L"], True))
+    assert y.dtype == torch.bfloat16
+    assert rel_l2(host(y), oracle.matmul(w["x"], w["R"], w["L"])) <= TOL_BF16
+
+
+def test_bf16_identity_blocks_are_the_permutation_bit_exact(mm):
+    announce("matmul bf16 identity b=16")
+    eye = np.tile(np.eye(16, dtype=np.float32), (16, 1, 1))
+    x = workloads.round_to_bf16(np.random.default_rng(0).standard_normal((19, 256)).astype(np.float32))
+    y = host(mm.monarch_matmul(dev(x, True), dev(eye, True), dev(eye, True))).astype(np.float32)
+    np.testing.assert_array_equal(y, x[:, oracle.perm(16, 256)])
+
+
 @pytest.mark.parametrize("b", [4, 16])
 def test_identity_blocks_are_the_permutation_bit_exact(mm, b):
     # L = R = I  =>  M = P (the involution P_(b,b^2)); multiplying by 1 and adding 0 is exact.
