@@ -226,11 +226,21 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const bf16_t a = from_f32<bf16_t>(lo), b = from_f32<bf16_t>(hi);
+    return (uint32_t) * reinterpret_cast<const uint16_t *>(&a) | ((uint32_t) * reinterpret_cast<const uint16_t *>(&b) << 16);
+}
+
+// T: type of x, R, L, dy and dx in memory (dR, dL are always float).  float rows arrive by direct-to-LDS loads;
+// bf16 rows (512 bytes, two per wave instruction) pass through registers and are widened into LDS.
+template <typename T>
 __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
-    const float *__restrict__ x, const float *__restrict__ R, const float *__restrict__ L,
-    const float *__restrict__ dy, float *__restrict__ dx, float *__restrict__ dR, float *__restrict__ dL,
+    const T *__restrict__ x, const T *__restrict__ R, const T *__restrict__ L,
+    const T *__restrict__ dy, T *__restrict__ dx, float *__restrict__ dR, float *__restrict__ dL,
     int64_t batch)
 {
+    constexpr bool F32 = sizeof(T) == 4;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float *xs = smem;                      // [TV][LDX]
     float *gs = xs + TV * LDX;             // [TV][LDX]  dy rows, later the dx rows
@@ -246,9 +256,9 @@ __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
     for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            Rw[q][s] = R[((b0 + q) * B + l16) * B + 4 * kg + s];
-            Rt[q][s] = R[((b0 + q) * B + 4 * kg + s) * B + l16];
-            Lt[q][s] = L[((b0 + q) * B + 4 * kg + s) * B + l16];
+            Rw[q][s] = to_f32(R[((b0 + q) * B + l16) * B + 4 * kg + s]);
+            Rt[q][s] = to_f32(R[((b0 + q) * B + 4 * kg + s) * B + l16]);
+            Lt[q][s] = to_f32(L[((b0 + q) * B + 4 * kg + s) * B + l16]);
         }
     f32x4 accL[4], accR[4];
 #pragma unroll
@@ -259,14 +269,33 @@ __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t v0 = tile * TV;
         // rows in: wave w fetches vectors 4 w .. 4 w + 3 of x and of dy (rows past the batch: the last one)
+        if constexpr (F32) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            int64_t v = v0 + b0 + q;
-            if (v >= batch) v = batch - 1;
-            dma_16_at(x + v * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
-            dma_16_at(dy + v * N + 4 * lane, gs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            for (int q = 0; q < 4; ++q) {
+                int64_t v = v0 + b0 + q;
+                if (v >= batch) v = batch - 1;
+                dma_16_at(x + v * N + 4 * lane, xs_addr + (uint32_t)(b0 + q) * LDX * 4);
+                dma_16_at(dy + v * N + 4 * lane, gs_addr + (uint32_t)(b0 + q) * LDX * 4);
+            }
+            wait_loads_at_most<0>();
+        } else {
+            uint4 w[4];   // lanes 0..31: vector 2 i, lanes 32..63: vector 2 i + 1; 8 elements per lane
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                int64_t v = v0 + b0 + 2 * i + (lane >> 5);
+                if (v >= batch) v = batch - 1;
+                w[i] = *reinterpret_cast<const uint4 *>(x + v * N + 8 * (lane & 31));
+                w[2 + i] = *reinterpret_cast<const uint4 *>(dy + v * N + 8 * (lane & 31));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float *d = (i < 2 ? xs : gs) + (b0 + 2 * (i & 1) + (lane >> 5)) * LDX + 8 * (lane & 31);
+                *reinterpret_cast<f32x4 *>(d) = f32x4{__uint_as_float(w[i].x << 16), __uint_as_float(w[i].x & 0xffff0000u),
+                                                      __uint_as_float(w[i].y << 16), __uint_as_float(w[i].y & 0xffff0000u)};
+                *reinterpret_cast<f32x4 *>(d + 4) = f32x4{__uint_as_float(w[i].z << 16), __uint_as_float(w[i].z & 0xffff0000u),
+                                                          __uint_as_float(w[i].w << 16), __uint_as_float(w[i].w & 0xffff0000u)};
+            }
         }
-        wait_loads_at_most<0>();
         if (v0 + TV > batch) {   // ragged tile: the missing vectors must not reach dR, dL
             __syncthreads();
             for (int idx = threadIdx.x; idx < TV * N; idx += 256) {
@@ -328,10 +357,22 @@ __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
             for (int r = 0; r < 4; ++r)
                 *reinterpret_cast<f32x4 *>(gs + l16 * LDX + 16 * (4 * kg + r) + b0) = f32x4{dxa[0][r], dxa[1][r], dxa[2][r], dxa[3][r]};
             __syncthreads();
+            if constexpr (F32) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t v = v0 + b0 + q;
-                if (v < batch) *reinterpret_cast<f32x4 *>(dx + v * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(gs + (b0 + q) * LDX + 4 * lane);
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t v = v0 + b0 + q;
+                    if (v < batch) *reinterpret_cast<f32x4 *>(dx + v * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(gs + (b0 + q) * LDX + 4 * lane);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int vv = b0 + 2 * i + (lane >> 5);
+                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(gs + vv * LDX + 8 * (lane & 31));
+                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(gs + vv * LDX + 8 * (lane & 31) + 4);
+                    if (v0 + vv < batch)
+                        *reinterpret_cast<uint4 *>(dx + (v0 + vv) * N + 8 * (lane & 31)) =
+                            uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+                }
             }
             __syncthreads();   // before the next tile's rows land
         }
@@ -350,11 +391,12 @@ __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
 
 bool matmul_backward_b16_supported(int nbR, int r_out, int r_in, int nbL, int l_out, int l_in, monarch_dtype dt)
 {
-    return dt == MONARCH_F32 && nbR == 16 && r_out == 16 && r_in == 16 && nbL == 16 && l_out == 16 && l_in == 16;
+    return (dt == MONARCH_F32 || dt == MONARCH_BF16) && nbR == 16 && r_out == 16 && r_in == 16 && nbL == 16 && l_out == 16 &&
+           l_in == 16;
 }
 
 static int launch_matmul_backward_b16(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR,
-                                      float *dL, int64_t batch, hipStream_t s)
+                                      float *dL, int64_t batch, monarch_dtype dt, hipStream_t s)
 {
     if (dR || dL) {
         hipLaunchKernelGGL(mmb::fill_zero_kernel, dim3(16), dim3(256), 0, s, dR, dR ? (size_t)4096 : 0, dL, dL ? (size_t)4096 : 0);
@@ -367,10 +409,18 @@ static int launch_matmul_backward_b16(const void *x, const void *R, const void *
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     int64_t grid = 2 * (int64_t)ncu;   // two workgroups (69 KB of LDS each) per compute unit
     if (grid > ntiles) grid = ntiles;
-    MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mmb16::matmul_backward_b16_kernel,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)mmb16::LDS_BYTES));
-    hipLaunchKernelGGL(mmb16::matmul_backward_b16_kernel, dim3((unsigned)grid), dim3(256), mmb16::LDS_BYTES, s,
-                       (const float *)x, (const float *)R, (const float *)L, (const float *)dy, (float *)dx, dR, dL, batch);
+    if (dt == MONARCH_F32) {
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mmb16::matmul_backward_b16_kernel<float>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)mmb16::LDS_BYTES));
+        hipLaunchKernelGGL(mmb16::matmul_backward_b16_kernel<float>, dim3((unsigned)grid), dim3(256), mmb16::LDS_BYTES, s,
+                           (const float *)x, (const float *)R, (const float *)L, (const float *)dy, (float *)dx, dR, dL, batch);
+    } else {
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)mmb16::matmul_backward_b16_kernel<bf16_t>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)mmb16::LDS_BYTES));
+        hipLaunchKernelGGL(mmb16::matmul_backward_b16_kernel<bf16_t>, dim3((unsigned)grid), dim3(256), mmb16::LDS_BYTES, s,
+                           (const bf16_t *)x, (const bf16_t *)R, (const bf16_t *)L, (const bf16_t *)dy, (bf16_t *)dx, dR, dL,
+                           batch);
+    }
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
@@ -386,7 +436,7 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
                            monarch_dtype dt, hipStream_t s)
 {
     if (matmul_backward_b16_supported(nbR, r_out, r_in, nbL, l_out, l_in, dt))
-        return launch_matmul_backward_b16(x, R, L, dy, dx, dR, dL, batch, s);
+        return launch_matmul_backward_b16(x, R, L, dy, dx, dR, dL, batch, dt, s);
     const mmb::Dims d = {nbR, r_out, r_in, nbL, l_out, l_in};
     if (dt == MONARCH_F32) return mmb::launch_typed<float>(x, R, L, dy, dx, dR, dL, batch, d, s);
     return mmb::launch_typed<bf16_t>(x, R, L, dy, dx, dR, dL, batch, d, s);

@@ -79,17 +79,18 @@ def plain_copy(mbytes, reps):
     _report(f"plain copy, {2 * n / 1e6:.0f} MB moved", _time(calls, reps), 2 * n, 0, len(calls))
 
 
-def matmul_backward_c1(batch, reps):
-    """Gradients of the config-1 product: reads x and dy, writes dx (3 KB per vector); dR, dL are 32 KB."""
-    nbytes = 3 * batch * 256 * 4 + 4 * 16 * 256 * 4
-    R, L = _rnd(16, 16, 16, dt=torch.float32, scale=.25), _rnd(16, 16, 16, dt=torch.float32, scale=.25)
+def matmul_backward_c1(batch, reps, dt=torch.float32):
+    """Gradients of the config-1 product: reads x and dy, writes dx (3 rows of 256 per vector); dR, dL are 32 KB."""
+    es = 4 if dt == torch.float32 else 2
+    nbytes = 3 * batch * 256 * es + 2 * 16 * 256 * (es + 4)
+    R, L = _rnd(16, 16, 16, dt=dt, scale=.25), _rnd(16, 16, 16, dt=dt, scale=.25)
 
     def make():
-        x, dy = _rnd(batch, 256, dt=torch.float32), _rnd(batch, 256, dt=torch.float32)
+        x, dy = _rnd(batch, 256, dt=dt), _rnd(batch, 256, dt=dt)
         return lambda: binding.monarch_matmul_backward(x, R, L, dy)
     calls = _sets(make, nbytes)
     # 5 block-diagonal products of 2 * 256 * 16 FLOP per vector (t1, g2, g0, dR, dL)
-    _report(f"c1 matmul backward fp32, batch {batch}", _time(calls, reps), nbytes, batch * 5 * 2 * 256 * 16, len(calls))
+    _report(f"c1 matmul backward {'fp32' if es == 4 else 'bf16'}, batch {batch}", _time(calls, reps), nbytes, batch * 5 * 2 * 256 * 16, len(calls))
 
 
 def mixer(B, H, reps, dt=torch.float32):
@@ -251,6 +252,7 @@ def main():
     if want("c1b"):
         matmul_backward_c1(64, 100)
         matmul_backward_c1(1 << 20, 5)
+        matmul_backward_c1(1 << 20, 5, torch.bfloat16)
     if want("mixer"):
         mixer(8, 768, 100)
         mixer(1024, 768, 5)

@@ -62,6 +62,19 @@ def test_rectangular_fp32(mm, shape):
     _check(mm, w, _dy(37, nbL * l_out, 12), TOL_F32)
 
 
+@pytest.mark.parametrize("batch", [1, 67, 5000, 20011])
+def test_bf16_config1_shape_on_the_matrix_cores(mm, batch):
+    # bf16 tensors through the fp32 MFMA kernel: ragged tiles, more tiles than workgroups; dx is rounded to bf16,
+    # dR and dL are fp32 sums of products of bf16 values
+    announce("matmul backward bf16 b=16 batch", batch)
+    w = workloads.monarch_matmul_inputs(batch=batch, b=16, seed=batch, bf16=True)
+    dy = _dy(batch, 256, batch + 1, bf16=True)
+    dx, dR, dL = mm.monarch_matmul_backward(dev(w["x"], True), dev(w["R"], True), dev(w["L"], True), dev(dy, True))
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    assert dx.dtype == torch.bfloat16 and rel_l2(host(dx), wdx) <= TOL_BF16
+    assert rel_l2(host(dR), wdR) <= 10 * TOL_F32 and rel_l2(host(dL), wdL) <= 10 * TOL_F32
+
+
 def test_bf16_inputs(mm):
     announce("matmul backward bf16")
     w = workloads.monarch_matmul_inputs(batch=130, b=16, seed=3, bf16=True)
