@@ -36,3 +36,31 @@ def m2_layer(x, seq, n_kernel, dim, d_kernel, gamma, beta, eps=1e-5, act="relu")
     var = ((r - mean) ** 2).mean(axis=-1, keepdims=True)
     out = (r - mean) / np.sqrt(var + eps) * np.asarray(gamma, dtype=np.float64) + np.asarray(beta, dtype=np.float64)
     return out, xtil
+
+
+def mixer_backward(u, K, g_in, g_out, R1, L1, R2, L2, dy):
+    """Gradients of S = sum <dy, y>, y = g_out o M2 (K[h] o M1 (g_in o u)) (the sequence mixer of Sec. 3.2 Eq. 2 in
+    its gated form), by the chain rule through its five steps with the dense Monarch matrices; the gradients of the
+    block-diagonal factors come from the order-2 product's own oracle (oracle.matmul_backward).
+    Returns a dict: du, dK, dg_in, dg_out (None without the gate), dR1, dL1, dR2, dL2."""
+    from . import matmul_backward
+    u, K, dy = (np.asarray(t, dtype=np.float64) for t in (u, K, dy))
+    B, H, N = u.shape
+    gi = np.asarray(g_in, dtype=np.float64) if g_in is not None else None
+    go = np.asarray(g_out, dtype=np.float64) if g_out is not None else None
+    M1, M2 = monarch_dense(R1, L1), monarch_dense(R2, L2)
+    a = u * gi if gi is not None else u
+    s = a @ M1.T
+    t = s * K[None]
+    w = t @ M2.T
+    dw = dy * go if go is not None else dy
+    out = {"dg_out": dy * w if go is not None else None}
+    dt = dw @ M2
+    _, out["dR2"], out["dL2"] = matmul_backward(t.reshape(B * H, N), R2, L2, dw.reshape(B * H, N))
+    out["dK"] = (dt * s).sum(axis=0)
+    ds = dt * K[None]
+    da = ds @ M1
+    _, out["dR1"], out["dL1"] = matmul_backward(a.reshape(B * H, N), R1, L1, ds.reshape(B * H, N))
+    out["du"] = da * gi if gi is not None else da
+    out["dg_in"] = da * u if gi is not None else None
+    return out
