@@ -138,6 +138,26 @@ int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_
 size_t monarch_mixer_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt);
 
 /*
+ * Gradients of monarch_mixer (Sec. 3.2 Eq. 2, gated form; the chain rule through gate, M1, kernel product, M2,
+ * gate), for a training step: with S = sum <dy, y>,
+ *   du, dg_in, dg_out: (B, H, N), type dt;   dK: (H, N) float32 (a sum over the sequences);
+ *   dR1, dL1, dR2, dL2: [bs][bs][bs] float32 (sums over all rows, by floating-point atomic adds: the last bits depend
+ *   on the order of the additions).  All are overwritten.  Any of them may be NULL (not computed); dg_in / dg_out
+ *   need their gate.
+ * Composed from the order-2 product and its gradient kernels with elementwise kernels between them; the
+ * intermediate rows (type dt) travel through ws: monarch_mixer_backward_workspace_bytes(B, H, bs, dt) bytes of
+ * device memory of the caller (five arrays of the size of u).
+ * Errors: EINVAL (null required pointer with B * H > 0, a gate's gradient without the gate, misalignment, overlap),
+ * ESHAPE, EWORKSPACE, EDTYPE, EHIP.
+ */
+int monarch_mixer_backward(const void *u, const void *K, const void *g_in, const void *g_out,
+                           const void *R1, const void *L1, const void *R2, const void *L2, const void *dy,
+                           void *du, float *dK, void *dg_in, void *dg_out,
+                           float *dR1, float *dL1, float *dR2, float *dL2,
+                           int64_t B, int H, int bs, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_mixer_backward_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt);
+
+/*
  * The basic M2 layer (Sec. 3.2: Eq. 2 for the sequence axis and its counterpart for the feature axis, with the
  * non-linearity, skip connection and layer normalisation of the paper's basic implementation):
  *   X~ = ( M2 act( K_n o (M1 X^T) ) )^T           per sequence; K_n: (d, n), one kernel row per feature

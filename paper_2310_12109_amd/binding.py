@@ -37,6 +37,9 @@ _lib.monarch_matmul_backward_workspace_bytes.restype = _sz
 _lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
 _lib.monarch_matmul3.argtypes = [_vp] * 5 + [_i64, _i, _i, _vp]
 _lib.monarch_matmul3_backward.argtypes = [_vp] * 9 + [_i64, _i, _i, _vp]
+_lib.monarch_mixer_backward.argtypes = [_vp] * 17 + [_i64, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_mixer_backward_workspace_bytes.restype = _sz
+_lib.monarch_mixer_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i]
 _lib.monarch_m2_layer.argtypes = [_vp, _vp, _i64, _i, _i] + [_vp] * 12 + [ctypes.c_float, _i, _i, _vp, _sz, _vp]
 _lib.monarch_m2_layer_workspace_bytes.restype = _sz
 _lib.monarch_m2_layer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
@@ -65,6 +68,7 @@ EXPORTS = [
     "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
     "monarch_matmul3", "monarch_matmul3_backward",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
+    "monarch_mixer_backward", "monarch_mixer_backward_workspace_bytes",
     "monarch_m2_layer", "monarch_m2_layer_workspace_bytes",
     "monarch_blocky_state_bytes", "monarch_blocky_state_offsets", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
@@ -182,6 +186,25 @@ def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):
     _check(_lib.monarch_mixer(_ptr(u), _ptr(K), _ptr(g_in), _ptr(g_out), _ptr(R1), _ptr(L1), _ptr(R2), _ptr(L2), _ptr(y),
                               B, H, bs, _dt(u), None, 0, _stream()))
     return y
+
+
+def monarch_mixer_backward(u, K, g_in, g_out, R1, L1, R2, L2, dy, ws=None):
+    """Gradients of sum <dy, monarch_mixer(...)>: dict with du, dK, dg_in, dg_out (None without the gate), dR1, dL1,
+    dR2, dL2; dK and the factor gradients are float32."""
+    B, H, N = u.shape
+    bs = R1.shape[0]
+    f32 = dict(dtype=torch.float32, device=u.device)
+    g = {"du": torch.empty_like(u), "dK": torch.empty((H, N), **f32),
+         "dg_in": torch.empty_like(u) if g_in is not None else None,
+         "dg_out": torch.empty_like(u) if g_out is not None else None}
+    for name in ("dR1", "dL1", "dR2", "dL2"):
+        g[name] = torch.empty((bs, bs, bs), **f32)
+    ws, wsb = _workspace(_lib.monarch_mixer_backward_workspace_bytes(B, H, bs, _dt(u)), ws, u.device)
+    _check(_lib.monarch_mixer_backward(_ptr(u), _ptr(K), _ptr(g_in), _ptr(g_out), _ptr(R1), _ptr(L1), _ptr(R2), _ptr(L2),
+                                       _ptr(dy), _ptr(g["du"]), _ptr(g["dK"]), _ptr(g["dg_in"]), _ptr(g["dg_out"]),
+                                       _ptr(g["dR1"]), _ptr(g["dL1"]), _ptr(g["dR2"]), _ptr(g["dL2"]), B, H, bs, _dt(u),
+                                       _ptr(ws), wsb, _stream()))
+    return g
 
 
 def monarch_m2_layer_workspace_bytes(B, n, d, dt=F32):

@@ -277,6 +277,56 @@ int monarch_mixer(const void *u, const void *K, const void *g_in, const void *g_
 }
 
 // ---------------------------------------------------------------------------------------------
+// monarch_mixer_backward
+// ---------------------------------------------------------------------------------------------
+
+size_t monarch_mixer_backward_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt)
+{
+    if (B <= 0 || H <= 0 || bs <= 0 || (dt != MONARCH_F32 && dt != MONARCH_BF16)) return 0;
+    return mixer_backward_workspace_bytes(B, H, bs, dt);
+}
+
+int monarch_mixer_backward(const void *u, const void *K, const void *g_in, const void *g_out,
+                           const void *R1, const void *L1, const void *R2, const void *L2, const void *dy,
+                           void *du, float *dK, void *dg_in, void *dg_out,
+                           float *dR1, float *dL1, float *dR2, float *dL2,
+                           int64_t B, int H, int bs, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
+{
+    clear_error();
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (B < 0 || H < 1) return fail(MONARCH_ESHAPE, "B must be >= 0 and H >= 1");
+    if (bs < 1 || !mixer_fits(bs) || !matmul_backward_fits(bs, bs, bs, bs, bs, bs) || !matmul_generic_fits(bs * bs, bs * bs, bs * bs))
+        return fail(MONARCH_ESHAPE, "block size %d: rows of bs^2 elements exceed the on-chip tiles", bs);
+    if (B > INT64_MAX / H) return fail(MONARCH_ESHAPE, "B * H overflows");
+    if ((dg_in && !g_in) || (dg_out && !g_out)) return fail(MONARCH_EINVAL, "a gate's gradient was asked for without the gate");
+    const void *all[18] = {u, K, g_in, g_out, R1, L1, R2, L2, dy, du, dK, dg_in, dg_out, dR1, dL1, dR2, dL2, ws};
+    for (int i = 0; i < 18; ++i)
+        if (misaligned(all[i])) return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const int64_t rows = B * H;
+    const size_t es = dtype_size(dt), N = (size_t)bs * bs, act = (size_t)rows * N * es, wb = N * bs * es;
+    const size_t need = rows > 0 ? mixer_backward_workspace_bytes(B, H, bs, dt) : 0;
+    if (rows > 0) {
+        if (!u || !K || !R1 || !L1 || !R2 || !L2 || !dy) return fail(MONARCH_EINVAL, "u, K, the four factors and dy must be non-NULL");
+        if (!ws || ws_bytes < need) return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws ? ws_bytes : (size_t)0);
+    }
+    const void *ins[9] = {u, g_in, g_out, dy, K, R1, L1, R2, L2};
+    const size_t in_bytes[9] = {act, act, act, act, (size_t)H * N * es, wb, wb, wb, wb};
+    const void *outs[9] = {du, dg_in, dg_out, dK, dR1, dL1, dR2, dL2, rows > 0 ? ws : nullptr};
+    const size_t out_bytes[9] = {act, act, act, (size_t)H * N * 4, N * bs * 4, N * bs * 4, N * bs * 4, N * bs * 4, need};
+    for (int o = 0; o < 9; ++o) {
+        if (!outs[o]) continue;
+        for (int i = 0; i < 9; ++i)
+            if (ins[i] && rows > 0 && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i]))
+                return fail(MONARCH_EINVAL, "an output or the workspace overlaps an input");
+        for (int q = o + 1; q < 9; ++q)
+            if (outs[q] && overlaps(outs[o], out_bytes[o], outs[q], out_bytes[q])) return fail(MONARCH_EINVAL, "outputs overlap");
+    }
+    return launch_mixer_backward(u, K, g_in, g_out, R1, L1, R2, L2, dy, du, dK, dg_in, dg_out, dR1, dL1, dR2, dL2, B, H, bs, dt,
+                                 ws, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
 // monarch_m2_layer
 // ---------------------------------------------------------------------------------------------
 

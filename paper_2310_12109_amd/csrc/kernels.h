@@ -100,6 +100,12 @@ bool mixer_fits(int bs);
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                  const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt,
                  const MixOpt &opt, hipStream_t s);
+// gradients of the sequence mixer (csrc/mixer_backward.hip); ws: mixer_backward_workspace_bytes
+size_t mixer_backward_workspace_bytes(int64_t B, int H, int bs, monarch_dtype dt);
+int launch_mixer_backward(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1,
+                          const void *L1, const void *R2, const void *L2, const void *dy, void *du, float *dK, void *dg_in,
+                          void *dg_out, float *dR1, float *dL1, float *dR2, float *dL2, int64_t B, int H, int bs,
+                          monarch_dtype dt, void *ws, hipStream_t s);
 // general order-3 Monarch product and its gradients (csrc/matmul3.hip); any of dx, dB1, dB2, dB3 may be null
 bool matmul3_fits(int b);
 int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,

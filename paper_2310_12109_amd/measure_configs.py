@@ -1,5 +1,5 @@
 """Times every configuration of the hot path through the binding and prints one line per case:
-`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mm3 mixer layer blocky c2 fft c3a c3b c4 c5a c5b]`.
+`python -m paper_2310_12109_amd.measure_configs [c1 copy c1b mixerb mm3 mixer layer blocky c2 fft c3a c3b c4 c5a c5b]`.
 
 Inputs are random tensors of each configuration's shapes and dtypes, already resident in HBM.  Every case
 rotates over enough distinct buffer sets to exceed 512 MB (at most 24 sets), so that the 256 MB Infinity
@@ -174,6 +174,25 @@ def blocky(B, H, reps, dt=torch.float32):
         print(f"blocky prepare (factors, blockwise inverses, {H} kernels transformed) {t:9.1f} us", flush=True)
 
 
+def mixer_backward(B, H, reps, dt=torch.float32):
+    """Gradients of the learned-Monarch mixer at N = 256: u, gates, dy read; du, dg_in, dg_out written (7 arrays)."""
+    rows = B * H
+    es = 4 if dt == torch.float32 else 2
+    nbytes = 7 * rows * 256 * es
+    K = _rnd(H, 256, dt=dt)
+    f = [_rnd(16, 16, 16, dt=dt, scale=.25) for _ in range(4)]
+    ws = torch.empty(binding.raw().monarch_mixer_backward_workspace_bytes(B, H, 16, binding.F32 if es == 4 else binding.BF16),
+                     dtype=torch.uint8, device="cuda")
+
+    def make():
+        u, gi, go, dy = (_rnd(B, H, 256, dt=dt) for _ in range(4))
+        return lambda: binding.monarch_mixer_backward(u, K, gi, go, *f, dy, ws=ws)
+    calls = _sets(make, nbytes)
+    # forward again (2 products of 2 factors) and two gradient calls of 5 families each
+    _report(f"mixer backward {'fp32' if es == 4 else 'bf16'} N=256, B={B} H={H}", _time(calls, reps), nbytes,
+            rows * 14 * 2 * 256 * 16, len(calls))
+
+
 def conv(name, B, H, n, factors, dt, reps):
     es = 2 if dt == torch.bfloat16 else 4
     code = binding.BF16 if dt == torch.bfloat16 else binding.F32
@@ -258,6 +277,10 @@ def main():
         mixer(1024, 768, 5)
         mixer(8, 768, 100, torch.bfloat16)
         mixer(1024, 768, 5, torch.bfloat16)
+    if want("mixerb"):
+        mixer_backward(8, 768, 50)
+        mixer_backward(256, 768, 5)
+        mixer_backward(256, 768, 5, torch.bfloat16)
     if want("mm3"):
         matmul3(8, 16384, 10)
         matmul3(16, 4096, 10)

@@ -134,6 +134,39 @@ def test_mixer_rejects_bad_arguments(lib):
     assert lib.monarch_mixer_workspace_bytes(8, 4, 16, 0) == 0
 
 
+def test_mixer_backward_rejects_bad_arguments(lib):
+    f = lib.monarch_mixer_backward
+    f.argtypes = [ctypes.c_void_p] * 17 + [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.monarch_mixer_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.monarch_mixer_backward_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    need = lib.monarch_mixer_backward_workspace_bytes(2, 4, 16, 0)
+    assert need >= 5 * 2 * 4 * 256 * 4
+    p = [FAKE * (64 * (i + 1)) for i in range(17)]      # 256 KB apart
+    ws = FAKE * 4096
+
+    def call(p=p, B=2, H=4, bs=16, dt=0, ws=ws, wsb=need):
+        return f(*p, B, H, bs, dt, ws, wsb, None)
+
+    def with_(i, v):
+        q = list(p); q[i] = v
+        return q
+    assert call(with_(0, None)) == EINVAL                 # u missing
+    assert call(with_(8, None)) == EINVAL                 # dy missing
+    assert call(with_(2, None)) == EINVAL                 # dg_in asked for without g_in
+    assert call(with_(9, p[0])) == EINVAL                 # du aliases u
+    assert call(with_(13, p[4])) == EINVAL                # dR1 aliases R1
+    assert call(with_(14, p[13])) == EINVAL               # dL1 aliases dR1
+    assert call(with_(0, p[0] + 4)) == EINVAL             # misaligned
+    assert call(ws=p[0]) == EINVAL                        # workspace over u
+    assert call(wsb=need - 1) == EWORKSPACE
+    assert call(ws=None) == EWORKSPACE
+    assert call(B=-1) == ESHAPE
+    assert call(H=0) == ESHAPE
+    assert call(bs=0) == ESHAPE
+    assert call(bs=200) == ESHAPE
+    assert call(dt=2) == EDTYPE
+
+
 def test_m2_layer_rejects_bad_arguments(lib):
     f = lib.monarch_m2_layer
     f.argtypes = ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int] + [ctypes.c_void_p] * 12 +

@@ -1,0 +1,78 @@
+"""GPU parity: monarch_mixer_backward (gradients of the gated sequence mixer, Sec. 3.2 Eq. 2) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import TOL_BF16, TOL_F32, announce, dev, host, rel_l2
+from oracle import layer
+from paper_2310_12109_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+KEYS = ("u", "K", "g_in", "g_out", "R1", "L1", "R2", "L2")
+GRADS = ("du", "dK", "dg_in", "dg_out", "dR1", "dL1", "dR2", "dL2")
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2310_12109_amd import binding
+    return binding
+
+
+def _check(mm, w, dy, tol, bf16=False):
+    got = mm.monarch_mixer_backward(*(dev(w[k], bf16) for k in KEYS), dev(dy, bf16))
+    want = layer.mixer_backward(*(w[k] for k in KEYS), dy)
+    for name in GRADS:
+        if want[name] is None:
+            assert got[name] is None
+            continue
+        assert rel_l2(host(got[name]), want[name]) <= tol, name
+    for name in ("dK", "dR1", "dL1", "dR2", "dL2"):
+        assert got[name].dtype == torch.float32
+
+
+def _dy(w, seed, bf16=False):
+    dy = np.random.default_rng(seed).standard_normal(w["u"].shape).astype(np.float32)
+    return workloads.round_to_bf16(dy) if bf16 else dy
+
+
+@pytest.mark.parametrize("B,H", [(4, 16), (1, 1), (3, 7), (16, 96)])
+def test_n256_fp32(mm, B, H):
+    # the matrix-core kernels of the order-2 product and its gradients under the composition; ragged tiles
+    announce("mixer backward fp32 b=16 B,H", B, H)
+    w = workloads.mixer_inputs(B, H, 16, seed=B + H)
+    _check(mm, w, _dy(w, 1), TOL_F32)
+
+
+@pytest.mark.parametrize("gates", [(True, False), (False, True), (False, False)])
+def test_n256_fp32_gates_absent(mm, gates):
+    announce("mixer backward fp32 gates", gates)
+    w = workloads.mixer_inputs(3, 11, 16, seed=7, gates=gates)
+    _check(mm, w, _dy(w, 2), TOL_F32)
+
+
+@pytest.mark.parametrize("b", [2, 3, 8, 32])
+def test_other_block_sizes_fp32(mm, b):
+    announce("mixer backward fp32 b", b)
+    w = workloads.mixer_inputs(3, 5, b, seed=b)
+    _check(mm, w, _dy(w, 3), TOL_F32)
+
+
+@pytest.mark.parametrize("b", [4, 16])
+def test_bf16(mm, b):
+    # every intermediate row is rounded to bf16 between the kernels
+    announce("mixer backward bf16 b", b)
+    w = workloads.mixer_inputs(4, 9, b, seed=b, bf16=True)
+    _check(mm, w, _dy(w, 4, bf16=True), TOL_BF16, bf16=True)
+
+
+def test_empty_batch_clears_the_sums(mm):
+    announce("mixer backward empty batch")
+    w = workloads.mixer_inputs(1, 4, 16, seed=0)
+    for k in ("u", "g_in", "g_out"):
+        w[k] = w[k][:0]
+    got = mm.monarch_mixer_backward(*(dev(w[k]) for k in KEYS), dev(w["u"]))
+    torch.cuda.synchronize()
+    assert got["du"].shape == (0, 4, 256)
+    for name in ("dK", "dR1", "dL1", "dR2", "dL2"):
+        assert float(got[name].abs().max()) == 0.0
