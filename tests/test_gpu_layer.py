@@ -46,6 +46,17 @@ def test_fp32_many_tiles(mm):
     assert rel_l2(host(_run(mm, w)), _want(w)) <= TOL_F32
 
 
+def test_fp32_runs_of_neighbouring_tiles(mm):
+    # 2176 tiles in the sequence mixer: enough for the launcher to hand each workgroup runs of two neighbouring
+    # tiles of the (B, n, d) layout
+    announce("m2 layer fp32 16, 16, B=136")
+    w = workloads.m2_layer_inputs(136, 16, 16, seed=11)
+    got, want = host(_run(mm, w)), _want(w)
+    assert rel_l2(got, want) <= TOL_F32
+    err = np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 10 * TOL_F32      # no single row is off
+
+
 def test_no_activation(mm):
     announce("m2 layer fp32 no activation")
     w = workloads.m2_layer_inputs(2, 16, 16, seed=8)
