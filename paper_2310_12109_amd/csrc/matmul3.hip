@@ -75,9 +75,10 @@ __global__ __launch_bounds__(THREADS) void forward_kernel(const T *__restrict__ 
     }
 }
 
-// Gradients, one row per pass of the loop (four rows of N floats in LDS: x, t1, t2 and the running gradient).
-// Adjoint of each step, last step first; every entry of dB1, dB2, dB3 receives one atomic add per row.
-template <typename T>
+// Gradients on tiles of TV rows (four buffers of TV rows of N floats in LDS: x, t1, t2 and the running gradient).
+// Adjoint of each step, last step first; every entry of dB1, dB2, dB3 is summed over the rows of a tile in a
+// register and receives one atomic add per tile.
+template <typename T, int TV>
 __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__ x, const T *__restrict__ B1,
                                                            const T *__restrict__ B2, const T *__restrict__ B3,
                                                            const T *__restrict__ dy, T *__restrict__ dx,
@@ -86,62 +87,100 @@ __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__
 {
     extern __shared__ float lds[];
     const int N = b * b * b;
-    float *xs = lds, *t1 = xs + N, *t2 = t1 + N, *g = t2 + N;
-    for (int64_t v = blockIdx.x; v < batch; v += gridDim.x) {
-        for (int j = threadIdx.x; j < N; j += THREADS) {
-            xs[j] = to_f32(x[v * N + j]);
+    float *xs = lds, *t1 = xs + TV * N, *t2 = t1 + TV * N, *g = t2 + TV * N;
+    const int64_t ntiles = (batch + TV - 1) / TV;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t v0 = tile * TV;
+        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
+            const int v = idx / N, j = idx - v * N;
+            const bool live = v0 + v < batch;   // rows past the end are zero: they add nothing to the sums
+            xs[idx] = live ? to_f32(x[v0 * N + idx]) : 0.0f;
             // g3[(m0, m1), m2] = dy[m2, m1, m0]
             const int m0 = j % b, m1 = (j / b) % b, m2 = j / (b * b);
-            g[(m0 * b + m1) * b + m2] = to_f32(dy[v * N + j]);
+            g[v * N + (m0 * b + m1) * b + m2] = live ? to_f32(dy[v0 * N + idx]) : 0.0f;
         }
         __syncthreads();
-        factor<T, 1, 1>(xs, t1, N, b, B1);
+        factor<T, TV, 1>(xs, t1, N, b, B1);
         __syncthreads();
-        factor<T, 1, 2>(t1, t2, N, b, B2);
+        factor<T, TV, 2>(t1, t2, N, b, B2);
         __syncthreads();
         // dB3[(p, q)][r, c] += g3[(p, q), r] t2[(p, c), q]
         if (dB3)
             for (int e = threadIdx.x; e < N * b; e += THREADS) {
                 const int c = e % b, o = e / b, pq = o / b, q = pq % b, p = pq / b;
-                atomicAdd(dB3 + e, g[o] * t2[in_index<3>(p, q, c, b)]);
+                const int at = in_index<3>(p, q, c, b);
+                float acc = 0.0f;
+#pragma unroll
+                for (int v = 0; v < TV; ++v) acc = fmaf(g[v * N + o], t2[v * N + at], acc);
+                atomicAdd(dB3 + e, acc);
             }
         __syncthreads();
         // g2[(p, c), q] = sum_r B3[(p, q)][r, c] g3[(p, q), r]   -> over t2
         for (int o2 = threadIdx.x; o2 < N; o2 += THREADS) {
             const int q = o2 % b, pc = o2 / b, c = pc % b, p = pc / b;
-            float acc = 0.0f;
-            for (int r = 0; r < b; ++r) acc = fmaf(to_f32(B3[(((size_t)p * b + q) * b + r) * b + c]), g[(p * b + q) * b + r], acc);
-            t2[o2] = acc;
+            float acc[TV];
+#pragma unroll
+            for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
+            for (int r = 0; r < b; ++r) {
+                const float w = to_f32(B3[(((size_t)p * b + q) * b + r) * b + c]);
+#pragma unroll
+                for (int v = 0; v < TV; ++v) acc[v] = fmaf(w, g[v * N + (p * b + q) * b + r], acc[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < TV; ++v) t2[v * N + o2] = acc[v];
         }
         __syncthreads();
         // dB2[(p, q)][r, c] += g2[(p, q), r] t1[(q, c), p]
         if (dB2)
             for (int e = threadIdx.x; e < N * b; e += THREADS) {
                 const int c = e % b, o = e / b, pq = o / b, q = pq % b, p = pq / b;
-                atomicAdd(dB2 + e, t2[o] * t1[in_index<2>(p, q, c, b)]);
+                const int at = in_index<2>(p, q, c, b);
+                float acc = 0.0f;
+#pragma unroll
+                for (int v = 0; v < TV; ++v) acc = fmaf(t2[v * N + o], t1[v * N + at], acc);
+                atomicAdd(dB2 + e, acc);
             }
         __syncthreads();
         // g1[(q, c), p] = sum_r B2[(p, q)][r, c] g2[(p, q), r]   -> over g
         for (int o1 = threadIdx.x; o1 < N; o1 += THREADS) {
             const int p = o1 % b, qc = o1 / b, c = qc % b, q = qc / b;
-            float acc = 0.0f;
-            for (int r = 0; r < b; ++r) acc = fmaf(to_f32(B2[(((size_t)p * b + q) * b + r) * b + c]), t2[(p * b + q) * b + r], acc);
-            g[o1] = acc;
+            float acc[TV];
+#pragma unroll
+            for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
+            for (int r = 0; r < b; ++r) {
+                const float w = to_f32(B2[(((size_t)p * b + q) * b + r) * b + c]);
+#pragma unroll
+                for (int v = 0; v < TV; ++v) acc[v] = fmaf(w, t2[v * N + (p * b + q) * b + r], acc[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < TV; ++v) g[v * N + o1] = acc[v];
         }
         __syncthreads();
         // dB1[(p, q)][r, c] += g1[(p, q), r] x[c, q, p]
         if (dB1)
             for (int e = threadIdx.x; e < N * b; e += THREADS) {
                 const int c = e % b, o = e / b, pq = o / b, q = pq % b, p = pq / b;
-                atomicAdd(dB1 + e, g[o] * xs[in_index<1>(p, q, c, b)]);
+                const int at = in_index<1>(p, q, c, b);
+                float acc = 0.0f;
+#pragma unroll
+                for (int v = 0; v < TV; ++v) acc = fmaf(g[v * N + o], xs[v * N + at], acc);
+                atomicAdd(dB1 + e, acc);
             }
         // dx[c, q, p] = sum_r B1[(p, q)][r, c] g1[(p, q), r]
         if (dx)
             for (int j = threadIdx.x; j < N; j += THREADS) {
                 const int p = j % b, q = (j / b) % b, c = j / (b * b);
-                float acc = 0.0f;
-                for (int r = 0; r < b; ++r) acc = fmaf(to_f32(B1[(((size_t)p * b + q) * b + r) * b + c]), g[(p * b + q) * b + r], acc);
-                dx[v * N + j] = from_f32<T>(acc);
+                float acc[TV];
+#pragma unroll
+                for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
+                for (int r = 0; r < b; ++r) {
+                    const float w = to_f32(B1[(((size_t)p * b + q) * b + r) * b + c]);
+#pragma unroll
+                    for (int v = 0; v < TV; ++v) acc[v] = fmaf(w, g[v * N + (p * b + q) * b + r], acc[v]);
+                }
+#pragma unroll
+                for (int v = 0; v < TV; ++v)
+                    if (v0 + v < batch) dx[(v0 + v) * N + j] = from_f32<T>(acc[v]);
             }
         __syncthreads();
     }
@@ -201,11 +240,28 @@ static int launch_backward(const void *x, const void *B1, const void *B2, const 
     if (batch > 0) {
         int ncu = 0;
         if (int rc = compute_units(&ncu)) return rc;
-        int64_t grid = 2 * (int64_t)ncu;
-        if (grid > batch) grid = batch;
-        hipLaunchKernelGGL((backward_kernel<T>), dim3((unsigned)grid), dim3(THREADS), (size_t)4 * N * sizeof(float), s,
-                           (const T *)x, (const T *)B1, (const T *)B2, (const T *)B3, (const T *)dy, (T *)dx, dB1, dB2,
-                           dB3, batch, b);
+        int tv = 8;
+        while (tv > 1 && (size_t)4 * tv * N * sizeof(float) > 128 * 1024) tv >>= 1;
+        const size_t lds = (size_t)4 * tv * N * sizeof(float);
+        const int64_t ntiles = (batch + tv - 1) / tv;
+        int64_t grid = (int64_t)ncu * (lds <= 40 * 1024 ? 4 : lds <= 80 * 1024 ? 2 : 1);
+        if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_MM3B(TVV)                                                                                  \
+    do {                                                                                                          \
+        auto kern = backward_kernel<T, TVV>;                                                                      \
+        if (lds > 64 * 1024)                                                                                      \
+            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                  (int)lds));                                                     \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)x, (const T *)B1,        \
+                           (const T *)B2, (const T *)B3, (const T *)dy, (T *)dx, dB1, dB2, dB3, batch, b);        \
+    } while (0)
+        switch (tv) {
+        case 8: MONARCH_LAUNCH_MM3B(8); break;
+        case 4: MONARCH_LAUNCH_MM3B(4); break;
+        case 2: MONARCH_LAUNCH_MM3B(2); break;
+        default: MONARCH_LAUNCH_MM3B(1); break;
+        }
+#undef MONARCH_LAUNCH_MM3B
     }
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
