@@ -209,17 +209,24 @@ static int launch_forward(const void *x, const void *B1, const void *B2, const v
                           hipStream_t s)
 {
     const int N = b * b * b;
+    // (more rows per tile: every weight read from L2 serves more rows)
     int tv = 8;
-    while (tv > 1 && (size_t)2 * tv * N * sizeof(float) > 64 * 1024) tv >>= 1;
+    while (tv > 1 && (size_t)2 * tv * N * sizeof(float) > 128 * 1024) tv >>= 1;
     const size_t lds = (size_t)2 * tv * N * sizeof(float);
     int ncu = 0;
     if (int rc = compute_units(&ncu)) return rc;
     const int64_t ntiles = (batch + tv - 1) / tv;
-    int64_t grid = (int64_t)ncu * (lds <= 32 * 1024 ? 4 : 2);
+    int64_t grid = (int64_t)ncu * (lds <= 32 * 1024 ? 4 : lds <= 80 * 1024 ? 2 : 1);
     if (grid > ntiles) grid = ntiles;
 #define MONARCH_LAUNCH_MM3(TVV)                                                                                  \
-    hipLaunchKernelGGL((forward_kernel<T, TVV>), dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)x,      \
-                       (const T *)B1, (const T *)B2, (const T *)B3, (T *)y, batch, b)
+    do {                                                                                                         \
+        auto kern = forward_kernel<T, TVV>;                                                                      \
+        if (lds > 64 * 1024)                                                                                     \
+            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                  (int)lds));                                                    \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)x, (const T *)B1,       \
+                           (const T *)B2, (const T *)B3, (T *)y, batch, b);                                      \
+    } while (0)
     switch (tv) {
     case 8: MONARCH_LAUNCH_MM3(8); break;
     case 4: MONARCH_LAUNCH_MM3(4); break;
