@@ -276,12 +276,134 @@ static int launch_backward(const void *x, const void *B1, const void *B2, const 
 
 }  // namespace mm3
 
+// ---- b = 16 (N = 4096), forward, on the matrix cores ---------------------------------------------------
+// A workgroup of 8 waves holds a tile of 8 rows in LDS (a tile of 16 would not fit) and works in place: in every
+// stage a block reads the 16 elements of a row that it contracts and writes its 16 results to the same places
+// (element (d2, d1, d0) of a row sits at d2 S2 + d1 S1 + d0, the digits being (j2, j1, j0) before the first factor,
+// (m0, j1, j0), (m0, m1, j0) and (m0, m1, m2) after the first, second and third), so the permutations cost nothing
+// and only the store reverses the digits.  Rows sit on the MFMA column index (columns 8..15 repeat rows 0..7); the
+// weights, 3 x 256 KB, do not fit on chip: every block's 16 x 16 matrix is read from L2 as the A operand of four
+// 16x16x4 fp32 MFMAs by the wave that owns the block (32 blocks per wave and stage).  The strides S1 = 18,
+// S2 = 290 and the row pitch (1 mod 64) keep the operand reads of the first two stages free of bank conflicts.
+namespace mm3b16 {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int B = 16, N = 4096, TV = 8, THREADS = 512, WAVES = 8;
+constexpr int S1 = 18, S2 = 290, ROWP = 4673;
+constexpr size_t LDS_BYTES = sizeof(float) * TV * ROWP;
+
+__device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ f32x4 ld4(const bf16_t *p)
+{
+    const uint2 w = *reinterpret_cast<const uint2 *>(p);
+    return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                 __uint_as_float(w.y & 0xffff0000u)};
+}
+__device__ __forceinline__ void st4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+__device__ __forceinline__ void st4(bf16_t *p, f32x4 v)
+{
+    const bf16_t h[4] = {from_f32<bf16_t>(v[0]), from_f32<bf16_t>(v[1]), from_f32<bf16_t>(v[2]), from_f32<bf16_t>(v[3])};
+    *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(h);
+}
+
+// One factor in place.  Block (p, q) contracts the digit that has stride SK in the tile; its other two digits sit
+// at `at(p, q)`.  Lane (n = lane % 16, kg = lane / 16): row n % 8 of the tile, contraction indices 4 kg + s.
+template <typename T, int SK, typename At>
+__device__ __forceinline__ void stage(float *tile, const T *__restrict__ W, int wave, int lane, At at)
+{
+    const int l16 = lane & 15, kg = lane >> 4;
+    float *mine = tile + (l16 & 7) * ROWP;
+#pragma unroll 4
+    for (int i = 0; i < 256 / WAVES; ++i) {
+        const int blk = wave * (256 / WAVES) + i, p = blk >> 4, q = blk & 15;
+        const f32x4 w = ld4(W + ((size_t)blk * B + l16) * B + 4 * kg);   // W[blk][row l16][4 kg .. + 3]
+        float *e = mine + at(p, q);
+        f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc = mfma(w[s], e[(4 * kg + s) * SK], acc);
+        // rows 4 kg + r of the block's result, column = row n of the tile: back where the inputs were
+        if (l16 < TV) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) e[(4 * kg + r) * SK] = acc[r];
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(THREADS) void forward_kernel(const T *__restrict__ x, const T *__restrict__ B1,
+                                                          const T *__restrict__ B2, const T *__restrict__ B3,
+                                                          T *__restrict__ y, int64_t batch)
+{
+    extern __shared__ __attribute__((aligned(16))) float tile[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t ntiles = (batch + TV - 1) / TV;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t v0 = t * TV;
+        // rows in: 16 pieces of 4 elements per thread (a piece never crosses a digit d1)
+#pragma unroll 4
+        for (int it = 0; it < TV * N / 4 / THREADS; ++it) {
+            const int piece = it * THREADS + threadIdx.x, v = piece / (N / 4), j = 4 * (piece % (N / 4));
+            int64_t r = v0 + v;
+            if (r >= batch) r = batch - 1;   // (rows past the end: computed, never stored)
+            const f32x4 val = ld4(x + r * N + j);
+            float *d = tile + v * ROWP + (j >> 8) * S2 + ((j >> 4) & 15) * S1 + (j & 15);
+            d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+        }
+        __syncthreads();
+        // factor 1: block (j0, j1) contracts j2 (stride S2); m0 takes j2's place
+        stage<T, S2>(tile, B1, wave, lane, [](int p, int q) { return q * S1 + p; });
+        __syncthreads();
+        // factor 2: block (m0, j0) contracts j1 (stride S1); m1 takes j1's place
+        stage<T, S1>(tile, B2, wave, lane, [](int p, int q) { return p * S2 + q; });
+        __syncthreads();
+        // factor 3: block (m0, m1) contracts j0 (stride 1); m2 takes j0's place
+        stage<T, 1>(tile, B3, wave, lane, [](int p, int q) { return p * S2 + q * S1; });
+        __syncthreads();
+        // rows out: y[m2, m1, m0] sits at (m0, m1, m2); a thread stores m0 = 4 g .. 4 g + 3 of one (m2, m1)
+#pragma unroll 4
+        for (int it = 0; it < TV * N / 4 / THREADS; ++it) {
+            const int piece = it * THREADS + threadIdx.x, v = piece / (N / 4), j = 4 * (piece % (N / 4));
+            const int m2 = j >> 8, m1 = (j >> 4) & 15, m0 = j & 15;
+            const float *sp = tile + v * ROWP + m0 * S2 + m1 * S1 + m2;
+            if (v0 + v < batch) st4(y + (v0 + v) * N + j, f32x4{sp[0], sp[S2], sp[2 * S2], sp[3 * S2]});
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+static int launch(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, hipStream_t s)
+{
+    int ncu = 0;
+    if (int rc = mm3::compute_units(&ncu)) return rc;
+    const int64_t ntiles = (batch + TV - 1) / TV;
+    int64_t grid = ncu;   // one workgroup (150 KB of LDS) per compute unit
+    if (grid > ntiles) grid = ntiles;
+    auto kern = forward_kernel<T>;
+    MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES, s, (const T *)x, (const T *)B1, (const T *)B2,
+                       (const T *)B3, (T *)y, batch);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+}  // namespace mm3b16
+
 bool matmul3_fits(int b) { return b >= 1 && b <= 16; }   // four rows of b^3 floats in 64 KB of LDS
 
 int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3, void *y, int64_t batch, int b,
                    monarch_dtype dt, hipStream_t s)
 {
     if (batch == 0) return MONARCH_OK;
+    if (b == 16) {
+        if (dt == MONARCH_F32) return mm3b16::launch<float>(x, B1, B2, B3, y, batch, s);
+        return mm3b16::launch<bf16_t>(x, B1, B2, B3, y, batch, s);
+    }
     if (dt == MONARCH_F32) return mm3::launch_forward<float>(x, B1, B2, B3, y, batch, b, s);
     return mm3::launch_forward<bf16_t>(x, B1, B2, B3, y, batch, b, s);
 }

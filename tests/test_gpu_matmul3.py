@@ -30,6 +30,26 @@ def test_forward_fp32(mm, b, batch):
     assert rel_l2(host(mm.monarch_matmul3(*_f(w))), order3.matmul3(w["x"], w["B1"], w["B2"], w["B3"])) <= TOL_F32
 
 
+@pytest.mark.parametrize("batch", [8, 21, 2600])
+def test_forward_b16_on_the_matrix_cores(mm, batch):
+    # tiles of 8 rows worked in place in LDS: one tile, ragged tiles, more tiles than workgroups
+    announce("matmul3 fp32 b=16 batch", batch)
+    w = workloads.monarch_matmul3_inputs(batch, 16, seed=batch)
+    got, want = host(mm.monarch_matmul3(*_f(w))), order3.matmul3(w["x"], w["B1"], w["B2"], w["B3"])
+    assert rel_l2(got, want) <= TOL_F32
+    err = np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    assert err.max() <= 10 * TOL_F32      # no single row is off
+
+
+def test_forward_b16_identity_blocks_reverse_the_digits(mm):
+    announce("matmul3 identity blocks b=16")
+    b = 16
+    w = workloads.monarch_matmul3_inputs(5, b, seed=2)
+    eye = np.broadcast_to(np.eye(b, dtype=np.float32), (b * b, b, b)).copy()
+    y = host(mm.monarch_matmul3(dev(w["x"]), dev(eye), dev(eye), dev(eye))).astype(np.float32)
+    np.testing.assert_array_equal(y.reshape(5, b, b, b), w["x"].reshape(5, b, b, b).transpose(0, 3, 2, 1))
+
+
 def test_forward_against_the_dense_matrix(mm):
     # the same product through the oracle's dense matrix (dense permutations and block-diagonals)
     announce("matmul3 fp32 dense b=4")
