@@ -318,18 +318,36 @@ __device__ __forceinline__ void stage(float *tile, const T *__restrict__ W, int 
 {
     const int l16 = lane & 15, kg = lane >> 4;
     float *mine = tile + (l16 & 7) * ROWP;
-#pragma unroll 4
-    for (int i = 0; i < 256 / WAVES; ++i) {
-        const int blk = wave * (256 / WAVES) + i, p = blk >> 4, q = blk & 15;
-        const f32x4 w = ld4(W + ((size_t)blk * B + l16) * B + 4 * kg);   // W[blk][row l16][4 kg .. + 3]
-        float *e = mine + at(p, q);
-        f32x4 acc = {0, 0, 0, 0};
+    // the weights of the next eight blocks are requested while the current eight are multiplied: the latency of L2
+    // is paid once per stage, not once per block
+    constexpr int NB = 256 / WAVES, G = 8;
+    f32x4 w[2][G];
+    // (the pointer passes through an empty asm that also names the latest result, so that the compiler keeps each
+    // group's requests where they are written instead of hoisting all 32 to the top, which would need 128 registers)
+    float anchor = 0.0f;
+    auto request = [&](int g, f32x4 (&dst)[G]) {
+        const T *src = W;
+        asm volatile("" : "+s"(src) : "v"(anchor));
 #pragma unroll
-        for (int s = 0; s < 4; ++s) acc = mfma(w[s], e[(4 * kg + s) * SK], acc);
-        // rows 4 kg + r of the block's result, column = row n of the tile: back where the inputs were
-        if (l16 < TV) {
+        for (int u = 0; u < G; ++u) dst[u] = ld4(src + ((size_t)(wave * NB + g * G + u) * B + l16) * B + 4 * kg);   // W[blk][row l16][4 kg .. + 3]
+    };
+    request(0, w[0]);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) e[(4 * kg + r) * SK] = acc[r];
+    for (int g = 0; g < NB / G; ++g) {
+        if (g + 1 < NB / G) request(g + 1, w[(g + 1) & 1]);
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+            const int blk = wave * NB + g * G + u, p = blk >> 4, q = blk & 15;
+            float *e = mine + at(p, q);
+            f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc = mfma(w[g & 1][u][s], e[(4 * kg + s) * SK], acc);
+            // rows 4 kg + r of the block's result, column = row n of the tile: back where the inputs were
+            if (l16 < TV) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) e[(4 * kg + r) * SK] = acc[r];
+            }
+            anchor = acc[0];
         }
     }
 }

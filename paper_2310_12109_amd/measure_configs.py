@@ -284,6 +284,7 @@ def main():
     if want("mm3"):
         matmul3(8, 16384, 10)
         matmul3(16, 4096, 10)
+        matmul3(16, 65536, 2)
     if want("layer"):
         m2_layer(32, 50)
         m2_layer(2048, 5)
