@@ -289,7 +289,7 @@ namespace mm3b16 {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int B = 16, N = 4096, TV = 8, THREADS = 512, WAVES = 8;
+constexpr int B = 16, N = 4096, TV = 8, THREADS = 1024, WAVES = 16;
 constexpr int S1 = 18, S2 = 290, ROWP = 4673;
 constexpr size_t LDS_BYTES = sizeof(float) * TV * ROWP;
 
@@ -336,18 +336,30 @@ __device__ __forceinline__ void stage(float *tile, const T *__restrict__ W, int 
     for (int g = 0; g < NB / G; ++g) {
         if (g + 1 < NB / G) request(g + 1, w[(g + 1) & 1]);
 #pragma unroll
-        for (int u = 0; u < G; ++u) {
-            const int blk = wave * NB + g * G + u, p = blk >> 4, q = blk & 15;
-            float *e = mine + at(p, q);
-            f32x4 acc = {0, 0, 0, 0};
+        for (int u = 0; u < G; u += 2) {   // two blocks at a time: their accumulators take turns
+            const int blk = wave * NB + g * G + u;
+            float *e0 = mine + at(blk >> 4, blk & 15), *e1 = mine + at((blk + 1) >> 4, (blk + 1) & 15);
+            float b0v[4], b1v[4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc = mfma(w[g & 1][u][s], e[(4 * kg + s) * SK], acc);
-            // rows 4 kg + r of the block's result, column = row n of the tile: back where the inputs were
+            for (int s = 0; s < 4; ++s) {
+                b0v[s] = e0[(4 * kg + s) * SK];
+                b1v[s] = e1[(4 * kg + s) * SK];
+            }
+            f32x4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                acc0 = mfma(w[g & 1][u][s], b0v[s], acc0);
+                acc1 = mfma(w[g & 1][u + 1][s], b1v[s], acc1);
+            }
+            // rows 4 kg + r of each block's result, column = row n of the tile: back where the inputs were
             if (l16 < TV) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) e[(4 * kg + r) * SK] = acc[r];
+                for (int r = 0; r < 4; ++r) {
+                    e0[(4 * kg + r) * SK] = acc0[r];
+                    e1[(4 * kg + r) * SK] = acc1[r];
+                }
             }
-            anchor = acc[0];
+            anchor = acc1[0];
         }
     }
 }
