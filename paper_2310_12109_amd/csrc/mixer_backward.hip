@@ -14,27 +14,53 @@ namespace mixb {
 
 constexpr int THREADS = 256;
 
-// out[i] = p[i] * q[i] (q null: copy of p); out2[i] = p[i] * q2[i] if out2
-template <typename T>
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// four consecutive elements as floats and back (every array here starts 16-byte aligned and N = bs^2 elements per
+// row; the vector kernels run when N is a multiple of 4)
+__device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ f32x4 ld4(const bf16_t *p)
+{
+    const uint2 w = *reinterpret_cast<const uint2 *>(p);
+    return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                 __uint_as_float(w.y & 0xffff0000u)};
+}
+__device__ __forceinline__ void st4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+__device__ __forceinline__ void st4(bf16_t *p, f32x4 v)
+{
+    const bf16_t h[4] = {from_f32<bf16_t>(v[0]), from_f32<bf16_t>(v[1]), from_f32<bf16_t>(v[2]), from_f32<bf16_t>(v[3])};
+    *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(h);
+}
+
+// out[i] = p[i] * q[i] (q null: copy of p); out2[i] = p[i] * q2[i] if out2.  V: elements per thread and step (4 or 1)
+template <typename T, int V>
 __global__ void product_kernel(const T *__restrict__ p, const T *__restrict__ q, const T *__restrict__ q2,
                                T *__restrict__ out, T *__restrict__ out2, size_t n)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        const float v = to_f32(p[i]);
-        if (out) out[i] = from_f32<T>(q ? v * to_f32(q[i]) : v);
-        if (out2) out2[i] = from_f32<T>(v * to_f32(q2[i]));
+    const size_t stride = (size_t)gridDim.x * blockDim.x * V;
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * V; i < n; i += stride) {
+        if constexpr (V == 4) {
+            const f32x4 v = ld4(p + i);
+            if (out) st4(out + i, q ? v * ld4(q + i) : v);
+            if (out2) st4(out2 + i, v * ld4(q2 + i));
+        } else {
+            const float v = to_f32(p[i]);
+            if (out) out[i] = from_f32<T>(q ? v * to_f32(q[i]) : v);
+            if (out2) out2[i] = from_f32<T>(v * to_f32(q2[i]));
+        }
     }
 }
 
 // t[r, j] = K[r % H, j] * s[r, j]
-template <typename T>
+template <typename T, int V>
 __global__ void kernel_product_kernel(const T *__restrict__ s, const T *__restrict__ K, T *__restrict__ t, size_t n,
                                       size_t HN)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-        t[i] = from_f32<T>(to_f32(s[i]) * to_f32(K[i % HN]));
+    const size_t stride = (size_t)gridDim.x * blockDim.x * V;
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * V; i < n; i += stride) {
+        if constexpr (V == 4) st4(t + i, ld4(s + i) * ld4(K + i % HN));
+        else t[i] = from_f32<T>(to_f32(s[i]) * to_f32(K[i % HN]));
+    }
 }
 
 // One thread per kernel entry (h, j): dK[h, j] = sum_b dt[b, h, j] s[b, h, j] (no atomics: the sum over the
@@ -79,26 +105,31 @@ static int run(const void *u, const void *K, const void *g_in, const void *g_out
     const size_t arr = ((n * sizeof(T) + 255) / 256) * 256;
     unsigned char *w8 = static_cast<unsigned char *>(ws);
     T *a = (T *)w8, *s = (T *)(w8 + arr), *t = (T *)(w8 + 2 * arr), *w = (T *)(w8 + 3 * arr), *x1 = (T *)(w8 + 4 * arr);
-    const unsigned g = blocks_for(n);
+    const bool vec = N % 4 == 0;
+    const unsigned g = blocks_for(vec ? n / 4 : n);
+    auto launch_product = [&](const T *p, const T *q, const T *q2, T *out, T *out2) {
+        if (vec) hipLaunchKernelGGL((product_kernel<T, 4>), dim3(g), dim3(THREADS), 0, st, p, q, q2, out, out2, n);
+        else hipLaunchKernelGGL((product_kernel<T, 1>), dim3(g), dim3(THREADS), 0, st, p, q, q2, out, out2, n);
+    };
     int rc;
     // forward again (nothing to do for an empty batch: the gradient kernels below then only clear their sums)
     const T *a_in = (const T *)u;
     if (rows > 0 && g_in) {
-        hipLaunchKernelGGL(product_kernel<T>, dim3(g), dim3(THREADS), 0, st, (const T *)u, (const T *)g_in, (const T *)nullptr,
-                           a, (T *)nullptr, n);
+        launch_product((const T *)u, (const T *)g_in, (const T *)nullptr, a, (T *)nullptr);
         a_in = a;
     }
     if (rows > 0) {
         if ((rc = product(a_in, R1, L1, s, rows, bs, dt, st))) return rc;
-        hipLaunchKernelGGL(kernel_product_kernel<T>, dim3(g), dim3(THREADS), 0, st, (const T *)s, (const T *)K, t, n, HN);
+        if (vec) hipLaunchKernelGGL((kernel_product_kernel<T, 4>), dim3(g), dim3(THREADS), 0, st, (const T *)s, (const T *)K, t, n, HN);
+        else hipLaunchKernelGGL((kernel_product_kernel<T, 1>), dim3(g), dim3(THREADS), 0, st, (const T *)s, (const T *)K, t, n, HN);
     }
     const T *dw = (const T *)dy;
     if (rows > 0 && g_out) {
         if (dg_out)
             if ((rc = product(t, R2, L2, w, rows, bs, dt, st))) return rc;
         // dw = dy o g_out, dg_out = dy o w
-        hipLaunchKernelGGL(product_kernel<T>, dim3(g), dim3(THREADS), 0, st, (const T *)dy, (const T *)g_out,
-                           dg_out ? (const T *)w : (const T *)nullptr, x1, dg_out ? (T *)dg_out : (T *)nullptr, n);
+        launch_product((const T *)dy, (const T *)g_out, dg_out ? (const T *)w : (const T *)nullptr, x1,
+                       dg_out ? (T *)dg_out : (T *)nullptr);
         dw = x1;
     }
     // through M2: dt (into w's array), dR2, dL2
@@ -112,9 +143,8 @@ static int run(const void *u, const void *K, const void *g_in, const void *g_out
     if ((rc = launch_matmul_backward(a_in, R1, L1, w, need_da ? da : nullptr, dR1, dL1, rows, bs, bs, bs, bs, bs, bs, dt, st)))
         return rc;
     if (rows > 0 && g_in && need_da)
-        hipLaunchKernelGGL(product_kernel<T>, dim3(g), dim3(THREADS), 0, st, (const T *)da, du ? (const T *)g_in : (const T *)nullptr,
-                           dg_in ? (const T *)u : (const T *)nullptr, du ? (T *)du : (T *)nullptr,
-                           dg_in ? (T *)dg_in : (T *)nullptr, n);
+        launch_product((const T *)da, du ? (const T *)g_in : (const T *)nullptr, dg_in ? (const T *)u : (const T *)nullptr,
+                       du ? (T *)du : (T *)nullptr, dg_in ? (T *)dg_in : (T *)nullptr);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
