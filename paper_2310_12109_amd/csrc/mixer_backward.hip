@@ -65,21 +65,33 @@ __global__ void kernel_product_kernel(const T *__restrict__ s, const T *__restri
 
 // One thread per kernel entry (h, j): dK[h, j] = sum_b dt[b, h, j] s[b, h, j] (no atomics: the sum over the
 // batch runs inside the thread, neighbouring threads read neighbouring addresses); ds = dt o K in place.
-template <typename T>
+template <typename T, int V>
 __global__ void kernel_gradient_kernel(T *__restrict__ dt_ds, const T *__restrict__ s, const T *__restrict__ K,
                                        float *__restrict__ dK, int64_t B, size_t HN)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * V;
     if (e >= HN) return;
-    const float k = to_f32(K[e]);
-    float acc = 0.0f;
-    for (int64_t b = 0; b < B; ++b) {
-        const size_t at = (size_t)b * HN + e;
-        const float d = to_f32(dt_ds[at]);
-        acc = fmaf(d, to_f32(s[at]), acc);
-        dt_ds[at] = from_f32<T>(d * k);
+    if constexpr (V == 4) {
+        const f32x4 k = ld4(K + e);
+        f32x4 acc = {0, 0, 0, 0};
+        for (int64_t b = 0; b < B; ++b) {
+            const size_t at = (size_t)b * HN + e;
+            const f32x4 d = ld4(dt_ds + at);
+            acc += d * ld4(s + at);
+            st4(dt_ds + at, d * k);
+        }
+        if (dK) *reinterpret_cast<f32x4 *>(dK + e) = acc;
+    } else {
+        const float k = to_f32(K[e]);
+        float acc = 0.0f;
+        for (int64_t b = 0; b < B; ++b) {
+            const size_t at = (size_t)b * HN + e;
+            const float d = to_f32(dt_ds[at]);
+            acc = fmaf(d, to_f32(s[at]), acc);
+            dt_ds[at] = from_f32<T>(d * k);
+        }
+        if (dK) dK[e] = acc;
     }
-    if (dK) dK[e] = acc;
 }
 
 static unsigned blocks_for(size_t n)
@@ -135,8 +147,12 @@ static int run(const void *u, const void *K, const void *g_in, const void *g_out
     // through M2: dt (into w's array), dR2, dL2
     if ((rc = launch_matmul_backward(t, R2, L2, dw, w, dR2, dL2, rows, bs, bs, bs, bs, bs, bs, dt, st))) return rc;
     // dK and ds = dt o K (in place)
-    hipLaunchKernelGGL(kernel_gradient_kernel<T>, dim3((unsigned)((HN + THREADS - 1) / THREADS)), dim3(THREADS), 0, st, w,
-                       (const T *)s, (const T *)K, dK, B, HN);
+    if (vec)
+        hipLaunchKernelGGL((kernel_gradient_kernel<T, 4>), dim3((unsigned)((HN / 4 + 63) / 64)), dim3(64), 0, st, w, (const T *)s,
+                           (const T *)K, dK, B, HN);
+    else
+        hipLaunchKernelGGL((kernel_gradient_kernel<T, 1>), dim3((unsigned)((HN + THREADS - 1) / THREADS)), dim3(THREADS), 0, st, w,
+                           (const T *)s, (const T *)K, dK, B, HN);
     // through M1: da (into t's array, or straight into du without an input gate), dR1, dL1
     const bool need_da = du || dg_in;
     T *da = g_in ? t : (T *)du;
