@@ -333,17 +333,6 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
 }
 __device__ __forceinline__ int chunked(int flat) { return (flat >> 8) * CH + (flat & 255); }
 
-// Phase clocks for kernel tuning; compiled out unless MONARCH_BLOCKY_CLOCKS is defined.
-#ifdef MONARCH_BLOCKY_CLOCKS
-__device__ long long g_clk[4][32];
-#define BLK_MARK(i)                                                                                             \
-    do {                                                                                                        \
-        if (blockIdx.x == 1 && tile == 1 + 2 * (int64_t)gridDim.x && lane == 0) g_clk[wave][(i)] = __builtin_readcyclecounter(); \
-    } while (0)
-#else
-#define BLK_MARK(i)
-#endif
-
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
     const bf16_t a = from_f32<bf16_t>(lo), b = from_f32<bf16_t>(hi);
@@ -421,7 +410,6 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
     };
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t r0 = tile * TV, base = r0 * n;
-        BLK_MARK(0);
         // the kernel entries of S2, (re, im) of elements 16 (4 kg + r) + b0 .. + 3 of the row's channel, requested
         // first: they are in registers long before S2 needs them
         f32x4 k01[4], k23[4];
@@ -438,11 +426,8 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
         }
         fetch_tile(u, base, xa, xa_addr);
         if (g_in) fetch_tile(g_in, base, xb, xb_addr);
-        BLK_MARK(1);
         wait_loads_at_most<0>();
-        BLK_MARK(2);
         __syncthreads();
-        BLK_MARK(3);
 
         // ---- S1: real input, complex R1
         {
@@ -474,9 +459,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
                     ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[q][r];
                 }
         }
-        BLK_MARK(4);
         __syncthreads();
-        BLK_MARK(5);
 
         // ---- S2: complex L1, then the kernel of the row's channel
         {
@@ -511,9 +494,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
                 *reinterpret_cast<f32x4 *>(xb + l16 * CH + 16 * (4 * kg + r) + b0) = a * kim + b * kre;
             }
         }
-        BLK_MARK(6);
         __syncthreads();
-        BLK_MARK(7);
 
         // ---- S3: complex R2 on the rows of z
         {
@@ -547,12 +528,10 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
                     ti[l16 * LD + (4 * kg + r) * RS + b0 + q] = ai[q][r];
                 }
         }
-        BLK_MARK(8);
         __syncthreads();   // z is consumed: the output gates land where Re z was while the last factor runs
         if (g_out) fetch_tile(g_out, base, xa, xa_addr);
 
         // ---- S4: real part of complex L2
-        BLK_MARK(9);
         f32x4 o[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) o[q] = f32x4{0, 0, 0, 0};
@@ -563,13 +542,10 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
 #pragma unroll
             for (int q = 0; q < 4; ++q) o[q] = mfma(L2i[q][s], -ti[l16 * LD + (b0 + q) * RS + 4 * kg + s], o[q]);
         }
-        BLK_MARK(10);
         if (g_out) {
             wait_loads_at_most<0>();
-            BLK_MARK(11);
             __syncthreads();
         }
-        BLK_MARK(12);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int j = 16 * (4 * kg + r) + b0;
@@ -580,9 +556,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
                 *reinterpret_cast<f32x4 *>(xb + at) = v;   // (Im z was consumed before the barrier after S3)
             }
         }
-        BLK_MARK(13);
         __syncthreads();
-        BLK_MARK(14);
         if constexpr (F32) {
             for (int q = wave; q < nchunks; q += 4) {
                 const int64_t at = base + 256 * q + 4 * lane;
@@ -599,9 +573,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
                 }
             }
         }
-        BLK_MARK(15);
         __syncthreads();   // before the next tile's rows land
-        BLK_MARK(16);
     }
 }
 
@@ -640,13 +612,6 @@ static int launch(const void *u, const void *g_in, const void *g_out, const unsi
 }
 
 }  // namespace blocky16
-
-#ifdef MONARCH_BLOCKY_CLOCKS
-extern "C" int monarch_debug_blocky_clocks(long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(blocky16::g_clk), sizeof(long long) * 4 * 32);
-}
-#endif
 
 bool blocky_fits(int bs) { return bs >= 2 && bs <= 64; }   // a row twice in LDS as complex float32: 64 KB at bs = 64
 

@@ -32,19 +32,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace c2048 {
 
-// Phase clocks for kernel tuning; compiled out unless MONARCH_PHASE_CLOCKS is defined.
-#ifdef MONARCH_PHASE_CLOCKS
-static __device__ long long *g_phase_clocks;   // [workgroup][wave][16]
-#define MONARCH_PHASE_MARK(slot)                                                                       \
-    do {                                                                                               \
-        if ((threadIdx.x & 63) == 0 && g_phase_clocks)                                                 \
-            g_phase_clocks[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (slot)] =              \
-                (slot) >= 14 ? (long long)wall_clock64() : (long long)__builtin_readcyclecounter();    \
-    } while (0)
-#else
-#define MONARCH_PHASE_MARK(slot)
-#endif
-
 constexpr int N1 = 64, N2 = 32, NFFT = 2048, NHALF = 1024;
 constexpr int TW_LD = 34;        // padded row length (complex) of the twiddle table
 #ifndef MONARCH_C2048_WAVES
@@ -377,8 +364,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     const int b0 = active ? 2 * p : 0, b1 = two ? 2 * p + 1 : b0;
     const size_t row0 = ((size_t)b0 * H + h) * n, row1 = ((size_t)b1 * H + h) * n;
 
-    MONARCH_PHASE_MARK(14);
-    MONARCH_PHASE_MARK(0);
     // Constant tables first (they come from L2 and gate everything else), then the rows.
     static_assert(sizeof(TwiddleTable) == (4 * 256 + 64) * sizeof(uint4), "twiddle copy assumes 1088 pieces");
     const uint4 *tw_src = reinterpret_cast<const uint4 *>(&g_twiddles);
@@ -399,7 +384,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     load_row<FULL>(ldk, lane, k + (size_t)h * klen, klen);
     load_rows<FULL>(ldx, lane, u + row0, u + row1, n);
 
-    MONARCH_PHASE_MARK(1);
     if (GIN) load_rows<FULL>(ldg, lane, g_in + row0, g_in + row1, n);
     {
         uint4 *dst = reinterpret_cast<uint4 *>(&sm.tw[0][0]);
@@ -417,7 +401,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     __syncthreads();   // twiddle table complete
     const uint32_t lane_sign = (l16 & 1) ? 0x80008000u : 0u;   // (-1)^(row of this lane) on every slot
 
-    MONARCH_PHASE_MARK(2);
     // spectrum of the kernel: wave w transforms spectrum columns 16w .. 16w+15
     {
         stage_rows(stage, lane, ldk, ldk, false);
@@ -442,10 +425,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
             sm.kf_im[wave][m][lane] = make_float4(zi[m][0] * inv, zi[m][1] * inv, zi[m][2] * inv, zi[m][3] * inv);
         }
     }
-    MONARCH_PHASE_MARK(3);
     if (GOUT) load_rows<FULL>(ldo, lane, g_out + row0, g_out + row1, n);
     __syncthreads();   // k_f complete
-    MONARCH_PHASE_MARK(4);
     if (!active) return;
     if (!two) {   // single row: its partner's data was only a placeholder
         const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
@@ -461,9 +442,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
             read_stage_operands(stage, l16, kg, xr, xi);
             __builtin_amdgcn_wave_barrier();
             // the tile is free again: park the output gates in it, same word layout
-            MONARCH_PHASE_MARK(5);
             if (GOUT) stage_rows(stage, lane, ldo, ldo, false);
-            MONARCH_PHASE_MARK(6);
 
             // B operands of the last factor: [kstep = contraction rows 32ks..32ks+31][column tile nt]
             Pack8 wr_op[2][2], wi_op[2][2];
@@ -473,7 +452,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                 forward_chunk<0, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
                 inverse_chunk<0>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
             }
-            MONARCH_PHASE_MARK(7);
             __builtin_amdgcn_sched_barrier(0);
             {
                 f32x4 zr[2], zi[2];
@@ -498,7 +476,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                 forward_chunk<3, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
                 inverse_chunk<3>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
             }
-            MONARCH_PHASE_MARK(8);
             __builtin_amdgcn_sched_barrier(0);
             // last factor: y[c,a] = sum_i conj(F64)[c,i] W[i,a], c < 32 only (truncation to n).
             // Contraction rows i >= 32 use F64[c][32+i'] = (-1)^c F64[c][i'], c being this lane's row.
@@ -520,7 +497,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                     yi[mt][nt] = ai;
                 }
             }
-            MONARCH_PHASE_MARK(9);
             // rows c = 16mt + 4kg + r, column a = 16nt + l16: gate in fp32, round once, park in the
             // staging tile (all gate words are read before the first result is written)
             __builtin_amdgcn_sched_barrier(0);
@@ -548,7 +524,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                         stage[(16 * mt + 4 * kg + r) * ST_LD + 16 * nt + l16] = pack_bf16(v0, v1);
                     }
             __builtin_amdgcn_wave_barrier();
-            MONARCH_PHASE_MARK(10);
             // coalesced stores: lane takes chunks lane and lane+64 of both rows
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -566,20 +541,11 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                 *reinterpret_cast<uint4 *>(y + row0 + ch * 8) = make_uint4(re[0], re[1], re[2], re[3]);
                 if (two) *reinterpret_cast<uint4 *>(y + row1 + ch * 8) = make_uint4(im[0], im[1], im[2], im[3]);
             }
-            MONARCH_PHASE_MARK(11);
-            MONARCH_PHASE_MARK(15);
         }
     }
 }
 
 }  // namespace c2048
-
-#ifdef MONARCH_PHASE_CLOCKS
-extern "C" int monarch_debug_set_phase_clocks(long long *buf)
-{
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(c2048::g_phase_clocks), &buf, sizeof(buf));
-}
-#endif
 
 bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt)
 {

@@ -186,17 +186,6 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// Phase clocks for kernel tuning; compiled out unless MONARCH_MIXER_CLOCKS is defined.
-#ifdef MONARCH_MIXER_CLOCKS
-__device__ long long g_clk[4][32];
-#define MIX_MARK(i)                                                                                             \
-    do {                                                                                                        \
-        if (blockIdx.x == 1 && it == 2 && lane == 0) g_clk[wave][(i)] = __builtin_readcyclecounter();           \
-    } while (0)
-#else
-#define MIX_MARK(i)
-#endif
-
 // four consecutive elements (16-byte aligned for float, 8-byte aligned for bf16) as floats, and back
 __device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
 __device__ __forceinline__ f32x4 ld4(const bf16_t *p)
@@ -375,7 +364,6 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         if (tile < 0) continue;
         const int64_t r0 = tile * TV;
         const int64_t next = prefetch ? tile_of(it + 1) : -1;
-        MIX_MARK(0);
         const int64_t tbase = tile_base(r0);
         if (prefetch) {
         } else if (opt.transposed) {
@@ -386,11 +374,8 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             if (GIN) fetch_now(g_in, r0, bufB);
         }
         load_kernel(r0, kq);
-        MIX_MARK(1);
         if (F32) wait_loads_at_most<0>();   // the direct-to-LDS loads (bf16 rows pass through registers)
-        MIX_MARK(2);
         __syncthreads();
-        MIX_MARK(3);
 
         auto first_factor = [&](const float *rows_in, const float (&W)[4][4], bool gated) {
             f32x4 xq[4];   // [s]: elements 16 (4 kg + s) + b0 .. + 3 of row v = l16
@@ -423,9 +408,7 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         };
 
         first_factor(ub, R1w, GIN);
-        MIX_MARK(4);
         __syncthreads();
-        MIX_MARK(5);
 
         // requested here, to arrive while the next three stages run: this tile's output gates (into registers; float
         // rows in the (B, H, N) layout come by direct-to-LDS loads once z is consumed) ...
@@ -457,11 +440,8 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             *reinterpret_cast<f32x4 *>(bufC + l16 * LDX + 16 * (4 * kg + r) + b0) =
                 f32x4{mix_act(z[0][r] * kq[r][0], opt.act), mix_act(z[1][r] * kq[r][1], opt.act),
                       mix_act(z[2][r] * kq[r][2], opt.act), mix_act(z[3][r] * kq[r][3], opt.act)};
-        MIX_MARK(6);
         __syncthreads();
-        MIX_MARK(7);
         first_factor(bufC, R2w, false);
-        MIX_MARK(8);
         __syncthreads();   // z is consumed: the output gates take its place
         if (GOUT) {
             if (opt.transposed) {
@@ -481,14 +461,11 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
                 if (GIN) park_rows(reinterpret_cast<uint4(&)[NW]>(pg), bufB);
             }
         }
-        MIX_MARK(9);
         second_factor(L2w, z);
-        MIX_MARK(10);
         if (GOUT) {
             if (F32) wait_loads_at_most<0>();
             __syncthreads();
         }
-        MIX_MARK(12);
         f32x4 o[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -531,9 +508,7 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
         // rows of y over the gates: every lane overwrites exactly the positions it has read
 #pragma unroll
         for (int r = 0; r < 4; ++r) *reinterpret_cast<f32x4 *>(bufC + l16 * LDX + 16 * (4 * kg + r) + b0) = o[r];
-        MIX_MARK(13);
         __syncthreads();
-        MIX_MARK(14);
         if (opt.transposed) {
 #pragma unroll
             for (int i = 0; i < TP; ++i) {
@@ -562,7 +537,6 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
                         uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
             }
         }
-        MIX_MARK(15);
         // (no barrier here: the next tile's first barrier comes before anything of this tile's buffers is rewritten,
         // except the inputs requested above into buffers that were free)
         if (!GIN && next >= 0) {
@@ -571,18 +545,10 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
             nb = t;
         }
 
-        MIX_MARK(16);
     }
 }
 
 }  // namespace mix16
-
-#ifdef MONARCH_MIXER_CLOCKS
-extern "C" int monarch_debug_mixer_clocks(long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mix16::g_clk), sizeof(long long) * 4 * 32);
-}
-#endif
 
 bool mixer_fits(int bs) { return bs >= 1 && (size_t)2 * bs * bs * sizeof(float) <= 160 * 1024; }
 

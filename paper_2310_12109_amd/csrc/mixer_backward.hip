@@ -94,6 +94,12 @@ __global__ void kernel_gradient_kernel(T *__restrict__ dt_ds, const T *__restric
     }
 }
 
+__global__ void clear_kernel(float *p, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.0f;
+}
+
 static unsigned blocks_for(size_t n)
 {
     const size_t b = (n + THREADS - 1) / THREADS;
@@ -146,8 +152,10 @@ static int run(const void *u, const void *K, const void *g_in, const void *g_out
     }
     // through M2: dt (into w's array), dR2, dL2
     if ((rc = launch_matmul_backward(t, R2, L2, dw, w, dR2, dL2, rows, bs, bs, bs, bs, bs, bs, dt, st))) return rc;
-    // dK and ds = dt o K (in place)
-    if (vec)
+    // dK and ds = dt o K (in place).  An empty batch reads nothing (its inputs may be NULL): dK is only cleared.
+    if (rows == 0) {
+        if (dK) hipLaunchKernelGGL(clear_kernel, dim3(blocks_for(HN)), dim3(THREADS), 0, st, dK, HN);
+    } else if (vec)
         hipLaunchKernelGGL((kernel_gradient_kernel<T, 4>), dim3((unsigned)((HN / 4 + 63) / 64)), dim3(64), 0, st, w, (const T *)s,
                            (const T *)K, dK, B, HN);
     else

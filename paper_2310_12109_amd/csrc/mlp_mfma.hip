@@ -550,16 +550,6 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
 //     LDS in one exchange (one barrier), the owner adds them, applies the output bias and stores.
 // Load accounting: direct-to-LDS loads and ordinary loads share the counter and complete in order; between
 // the prologue and the epilogue the only loads are the ring's, 2 KS per part.
-// Phase clocks for kernel tuning; compiled out unless MONARCH_MLP_CLOCKS is defined.
-#ifdef MONARCH_MLP_CLOCKS
-__device__ long long g_mlp_clk[4][64];
-#define MLP_MARK(i)                                                                                       \
-    do {                                                                                                  \
-        if (blockIdx.x == 1 && blockIdx.y == 1 && lane == 0) g_mlp_clk[wave][(i)] = __builtin_readcyclecounter(); \
-    } while (0)
-#else
-#define MLP_MARK(i)
-#endif
 
 constexpr size_t split_lds_bytes(int ks, int dh) { return (size_t)24 * ks * 1024 + (size_t)dh * 2; }
 
@@ -614,7 +604,6 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
 
     // Prologue: the biases, then x (a quarter of the tile per wave) into the third slot's area and the first
     // two parts into the first two slots.
-    MLP_MARK(0);
     uint4 b1piece = make_uint4(0u, 0u, 0u, 0u);   // hidden bias, 8 units per thread (the usual layout)
     const bool b1_vec = b1 && !b1_interleaved && dh <= 2048;
     if (b1_vec && tid < dh / 8) b1piece = *reinterpret_cast<const uint4 *>(b1 + (size_t)blk * dh + 8 * tid);
@@ -646,10 +635,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
         }
     }
     // (x was requested before the two parts: at most those, 2 ITEM loads, may still be in flight)
-    MLP_MARK(1);
     if (nmine > 0) wait_loads_at_most<2 * ITEM>();
     else wait_loads_at_most<0>();
-    MLP_MARK(2);
     __syncthreads();
     Pack8 xop[4][KS];
 #pragma unroll
@@ -659,7 +646,6 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     wait_lds_reads();
     __syncthreads();   // everybody holds x: the third slot is free
     if (nmine > 0) request(2);
-    MLP_MARK(3);
 
     f32x4 acc[MT][4];
 #pragma unroll
@@ -710,7 +696,6 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     auto step = [&](int jj, auto last_tag) {
         constexpr bool LAST = decltype(last_tag)::value;
         const int p = 2 * jj + 1;   // this step's parts: p (W1 of the next chunk), p + 1 (W2 of this chunk)
-        if (jj < 6) MLP_MARK(4 + 6 * jj);
         if (!LAST && jj > 0) {
             wait_lds_reads();   // (the previous step's W2 operands are long in registers)
             request(p + 2);     // into the slot they came from
@@ -718,9 +703,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
         Pack8 w1[2][KS];
         f32x4 hnext[2][4];
         if (!LAST) {
-            if (jj < 6) MLP_MARK(5 + 6 * jj);
             wait_loads_at_most<2 * ITEM>();
-            if (jj < 6) MLP_MARK(6 + 6 * jj);
             read_piece_set(&w1[0][0], p % 3);
             wait_lds_reads();
             request(p + 3);
@@ -729,7 +712,6 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
         // activation on the accumulators; two stacked tiles become one K=32 operand (slot 4mt + r)
         Pack8 hop[4];
         float hv[32];   // value v = 8 nt + 4 mt + r
-        if (jj < 6) MLP_MARK(7 + 6 * jj);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < NM; ++u) {
@@ -751,11 +733,9 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (jj < 6) MLP_MARK(8 + 6 * jj);
         // second GEMM: Y^T += W2[:, chunk] * H^T chunk (the last step requested nothing: it waits for all)
         if (LAST) wait_loads_at_most<0>();
         else wait_loads_at_most<2 * ITEM>();
-        if (jj < 6) MLP_MARK(9 + 6 * jj);
         Pack8 w2[MT];
         read_piece_set(w2, (p + 1) % 3);
 #pragma unroll
@@ -785,7 +765,6 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
         request(3);
         start_from_bias(hacc, 32 * wave);
         first_gemm(hacc, w1);
-        MLP_MARK(46);
 #pragma unroll 1
         for (int jj = 0; jj < nmine - 1; ++jj) step(jj, std::false_type{});
         step(nmine - 1, std::true_type{});
@@ -794,11 +773,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     // Exchange: tile mt belongs to wave mt % 4; the three other waves park their partial of it at
     // [mt][(wave - owner - 1) mod 4][nt][lane].  The ring is dead, but its last (repeated) requests may still
     // be landing: they are waited for before the area is reused.
-    MLP_MARK(40);
     wait_loads_at_most<0>();
-    MLP_MARK(41);
     __syncthreads();
-    MLP_MARK(42);
     f32x4 *part = reinterpret_cast<f32x4 *>(lds_split);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -809,9 +785,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
             for (int nt = 0; nt < 4; ++nt) dst[nt * 64] = acc[mt][nt];
         }
     }
-    MLP_MARK(43);
     __syncthreads();
-    MLP_MARK(44);
     // accumulator rows 4 kg .. 4 kg + 3 of tile mt are 4 consecutive features of a token: 8-byte stores
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -834,17 +808,9 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
             }
         }
     }
-    MLP_MARK(45);
 }
 
 }  // namespace mlp1
-
-#ifdef MONARCH_MLP_CLOCKS
-extern "C" int monarch_debug_mlp_clocks(long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mlp1::g_mlp_clk), sizeof(long long) * 4 * 64);
-}
-#endif
 
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
 {

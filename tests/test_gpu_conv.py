@@ -115,6 +115,41 @@ def test_single_gate_and_bf16_odd_batch(mm):
     assert rel_l2(y2, _oracle(w2, 2048)) <= TOL_BF16
 
 
+@pytest.mark.parametrize("n,klen", [(1000, 1000), (1024, 504), (512, 512), (1024, 1024)])
+@pytest.mark.parametrize("gates", ["both", "in", "out", "none"])
+def test_fused_64x32_bf16_short_rows_and_each_gate(mm, n, klen, gates):
+    # the fused 64 x 32 kernel with rows or kernels shorter than 1024 (zero fill on load, stores past n skipped),
+    # with and without each gate; B = 5 leaves the third wave with a lone row and the fourth without work
+    announce("conv fused 64x32 bf16 short", n, klen, gates)
+    B, H = 5, 6
+    w = workloads.conv_inputs(B, H, n, seed=n + klen + len(gates), gates="normal", bf16=True)
+    w["k"] = np.ascontiguousarray(w["k"][:, :klen])
+    if gates in ("out", "none"):
+        w["g_in"] = None
+    if gates in ("in", "none"):
+        w["g_out"] = None
+    y = _run(mm, w, (64, 32), True)
+    want = _oracle(w, 2048)
+    assert rel_l2(y, want) <= TOL_BF16
+    num = np.linalg.norm((y - want).reshape(-1, n), axis=1)
+    assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_BF16
+
+
+@pytest.mark.parametrize("B", [9, 17, 24])
+@pytest.mark.parametrize("n,klen", [(1024, 1024), (1000, 1000), (512, 512)])
+def test_fused_64x32_bf16_many_batch_groups(mm, B, n, klen):
+    # more than eight batch entries: several workgroups per channel (groups of four row pairs), odd tails
+    announce("conv fused 64x32 bf16 groups", B, n, klen)
+    H = 5
+    w = workloads.conv_inputs(B, H, n, seed=B + n, gates="normal", bf16=True)
+    w["k"] = np.ascontiguousarray(w["k"][:, :klen])
+    y = _run(mm, w, (64, 32), True)
+    want = _oracle(w, 2048)
+    assert rel_l2(y, want) <= TOL_BF16
+    num = np.linalg.norm((y - want).reshape(-1, n), axis=1)
+    assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_BF16
+
+
 def test_delta_kernel_and_causality(mm):
     announce("conv delta / causality")
     B, H, n = 2, 3, 1024

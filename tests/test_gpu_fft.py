@@ -136,6 +136,32 @@ def test_bf16_real_rows_one_kernel_many_rows(mm, factors, rows):
     assert (num / np.linalg.norm(want, axis=1)).max() <= TOL_BF16
 
 
+@pytest.mark.parametrize("real_input", [True, False])
+def test_bf16_forward_128x128_many_rows(mm, real_input):
+    # forward transform of bf16 rows of 16384 = 128 x 128 in one kernel (natural-order spectrum store), more rows
+    # than workgroups so that each walks over several: sampled bins of sampled rows against the oracle's own sum,
+    # every row against the library FFT (the paper's forward sign is +: the conjugate of numpy's forward on
+    # conjugated input)
+    announce("fft bf16 128x128 forward", "real" if real_input else "complex")
+    N, rows = 16384, 530
+    rng = np.random.default_rng(N + rows + int(real_input))
+    xr = workloads.round_to_bf16(rng.standard_normal((rows, N)).astype(np.float32))
+    if real_input:
+        x64 = xr.astype(np.float64)
+        X = _cplx(mm.monarch_fft(dev(xr, True), (128, 128), True))
+    else:
+        xi = workloads.round_to_bf16(rng.standard_normal((rows, N)).astype(np.float32))
+        x64 = xr.astype(np.float64) + 1j * xi.astype(np.float64)
+        X = _cplx(mm.monarch_fft(dev(np.stack([xr, xi], -1), True), (128, 128), False))
+    bins = np.concatenate([[0, 1, 127, 128, N // 2, N - 1], rng.choice(N, size=26, replace=False)]).astype(np.int32)
+    for r in (0, 255, 256, rows - 1):
+        want = oracle.dft_bins(x64[r:r + 1], bins)
+        assert rel_l2(X[r:r + 1, bins], want) <= TOL_BF16
+    lib = np.conj(np.fft.fft(np.conj(x64), axis=-1))
+    num = np.linalg.norm(X - lib, axis=1)
+    assert (num / np.linalg.norm(lib, axis=1)).max() <= TOL_BF16
+
+
 def test_unit_vector_gives_dft_column(mm):
     announce("fft delta")
     N = 256

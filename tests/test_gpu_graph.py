@@ -3,7 +3,8 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import announce, dev
+import oracle
+from gpu_util import TOL_BF16, announce, dev, host, rel_l2
 from paper_2310_12109_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -35,6 +36,9 @@ def test_graph_replays_match_eager():
         torch.cuda.synchronize()
         assert torch.equal(out, want), f"replay {rep} differs from the eager result"
         assert other.shape == want.shape
+    # and the replayed result is the right one, not merely the repeated one: the oracle's direct sum
+    ref = oracle.causal_conv(w["u"], w["k"], w["g_in"], w["g_out"], nfft=2048)
+    assert rel_l2(host(out), ref) <= TOL_BF16
 
 
 def test_graph_replays_of_the_matmul_gradients_match_eager():

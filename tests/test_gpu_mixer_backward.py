@@ -76,3 +76,22 @@ def test_empty_batch_clears_the_sums(mm):
     assert got["du"].shape == (0, 4, 256)
     for name in ("dK", "dR1", "dL1", "dR2", "dL2"):
         assert float(got[name].abs().max()) == 0.0
+
+
+def test_empty_batch_with_null_inputs_through_the_raw_abi(mm):
+    # B = 0 through the C ABI with every input NULL (the header allows it): nothing may be read, and the sums that
+    # were asked for come back cleared
+    announce("mixer backward empty batch, NULL inputs, raw ABI")
+    H, bs = 4, 16
+    N = bs * bs
+    outs = {name: torch.full((n,), 7.0, device="cuda") for name, n in
+            (("dK", H * N), ("dR1", N * bs), ("dL1", N * bs), ("dR2", N * bs), ("dL2", N * bs))}
+    lib = mm.raw()
+    rc = lib.monarch_mixer_backward(None, None, None, None, None, None, None, None, None,
+                                    None, outs["dK"].data_ptr(), None, None,
+                                    outs["dR1"].data_ptr(), outs["dL1"].data_ptr(), outs["dR2"].data_ptr(), outs["dL2"].data_ptr(),
+                                    0, H, bs, mm.F32, None, 0, torch.cuda.current_stream().cuda_stream)
+    assert rc == 0, lib.monarch_last_error()
+    torch.cuda.synchronize()
+    for name, t in outs.items():
+        assert float(t.abs().max()) == 0.0, name

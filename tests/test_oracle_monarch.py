@@ -55,24 +55,31 @@ def test_entry_formula_in_block_terms(b):
 
 
 @pytest.mark.parametrize("b", [2, 4, 8])
-def test_against_reshape_einsum_semantics(b):
-    # The appendix listing computes the same map with reshape-transposes and a
-    # batched einsum; its first-applied factor is the R of the equation.
+def test_stepwise_application_with_explicit_loops(b):
+    # The product applied to a vector one step at a time, every step an explicit loop over (block, row):
+    # gather by P, block-diagonal R, gather by P, block-diagonal L, gather by P (Sec. 3.1; the basic layer of the
+    # appendix applies the same five steps, with its first-applied factor in the role of R here).
     rng = np.random.default_rng(7 + b)
     N = b * b
     R = rng.standard_normal((b, b, b))
     L = rng.standard_normal((b, b, b))
+    sigma = [(i % b) * b + i // b for i in range(N)]         # (P x)[i] = x[sigma(i)]
 
-    def rearr(x):                     # "(m n) -> (n m)" with n = b
-        return x.reshape(*x.shape[:-1], b, b).transpose(-1, -2).reshape(*x.shape)
+    def gather(v):
+        return [v[sigma[i]] for i in range(N)]
 
-    def bd(x, w):
-        return torch.einsum("bnm,...bm->...bn", w, x.view(*x.shape[:-1], b, b)).reshape(*x.shape)
+    def blocks(v, W):
+        out = [0.0] * N
+        for k in range(b):
+            for r in range(b):
+                out[k * b + r] = sum(W[k, r, c] * v[k * b + c] for c in range(b))
+        return out
 
-    x = torch.eye(N, dtype=torch.float64)
-    y = rearr(bd(rearr(bd(rearr(x), torch.from_numpy(R))), torch.from_numpy(L)))
-    M_listing = y.numpy().T           # row v of y is M e_v
-    assert np.abs(oracle.monarch_dense(R, L) - M_listing).max() < 1e-13
+    M = oracle.monarch_dense(R, L)
+    for col in range(N):
+        e = [1.0 if j == col else 0.0 for j in range(N)]
+        y = gather(blocks(gather(blocks(gather(e), R)), L))
+        assert np.abs(M[:, col] - np.array(y)).max() < 1e-13
 
 
 @pytest.mark.parametrize("b", [2, 3, 5, 16])
