@@ -256,6 +256,25 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
                                            const int *factors, int nf, monarch_dtype dt);
 
 /*
+ * monarch_causal_conv for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  Same arguments, results and errors as monarch_causal_conv
+ * without ws / ws_bytes; the scratch memory the multi-pass paths need (row
+ * buffers between the passes, the spectrum of k) is a static device array of
+ * MONARCH_STATIC_SCRATCH_BYTES inside the library, which every GPU the library
+ * runs on holds until the process ends.  The call allocates nothing and frees
+ * nothing.  A shape whose monarch_causal_conv_workspace_bytes exceeds
+ * MONARCH_STATIC_SCRATCH_BYTES returns MONARCH_EWORKSPACE (no device work).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, different threads) race and give undefined
+ * results; serialise them.  Nothing in the array needs to start at zero.
+ */
+#define MONARCH_STATIC_SCRATCH_BYTES (32u << 20)
+int monarch_causal_conv_static(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                               int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                               int causal, monarch_dtype dt, monarch_stream_t stream);
+
+/*
  * Monarch MLP, the dimension mixer (Sec. 3.2 Eq. 3):
  *   y[t,:] = W2 * act(W1 * x[t,:] + b1) + b2,   t in [0, tokens),
  * W1: d -> d_hidden, W2: d_hidden -> d.

@@ -56,6 +56,7 @@ _lib.monarch_ifft.argtypes = [_vp, _vp, _i64, _i, _ip, _i, _i, _i, _vp, _sz, _vp
 _lib.monarch_fft_workspace_bytes.restype = _sz
 _lib.monarch_fft_workspace_bytes.argtypes = [_i64, _i, _ip, _i, _i]
 _lib.monarch_causal_conv.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _ip, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_causal_conv_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _ip, _i, _i, _i, _vp]
 _lib.monarch_causal_conv_workspace_bytes.restype = _sz
 _lib.monarch_causal_conv_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _ip, _i, _i]
 _lib.monarch_mlp.argtypes = [_vp, _vp, _i64, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]
@@ -72,7 +73,7 @@ EXPORTS = [
     "monarch_m2_layer", "monarch_m2_layer_workspace_bytes",
     "monarch_blocky_state_bytes", "monarch_blocky_state_offsets", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
-    "monarch_causal_conv", "monarch_causal_conv_workspace_bytes",
+    "monarch_causal_conv", "monarch_causal_conv_workspace_bytes", "monarch_causal_conv_static",
     "monarch_mlp", "monarch_mlp_workspace_bytes",
 ]
 
@@ -308,6 +309,21 @@ def monarch_causal_conv(u, k, g_in, g_out, factors, causal=True, ws=None, out=No
     _check(_lib.monarch_causal_conv(_ptr(u), _ptr(k), _ptr(g_in), _ptr(g_out), _ptr(y), B, H, n, klen, nfft,
                                     f, nf, 1 if causal else 0, _dt(u), _ptr(ws), nbytes, _stream()))
     return y
+
+
+STATIC_SCRATCH_BYTES = 32 << 20   # MONARCH_STATIC_SCRATCH_BYTES of the header
+
+
+def monarch_causal_conv_static(u, k, g_in, g_out, factors, out, causal=True):
+    """The entry point that allocates nothing: the caller passes the output too; scratch is the library's own."""
+    B, H, n = u.shape
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    _check(_lib.monarch_causal_conv_static(_ptr(u), _ptr(k), _ptr(g_in), _ptr(g_out), _ptr(out), B, H, n, k.shape[1], nfft,
+                                           f, nf, 1 if causal else 0, _dt(u), _stream()))
+    return out
 
 
 def monarch_mlp_workspace_bytes(tokens, d, d_hidden, nb, order, mid1=0, mid2=0, dt=BF16):

@@ -2,6 +2,8 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "kernels.h"
 
 namespace monarch {
@@ -804,12 +806,10 @@ static int conv_passes_mfma(const void *u, const void *k, const void *g_in, cons
     return MONARCH_OK;
 }
 
-int monarch_causal_conv(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
-                        int B, int H, int n, int klen, int nfft, const int *factors, int nf,
-                        int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
-                        monarch_stream_t stream)
+static int conv_run(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                    int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                    int causal, monarch_dtype dt, void *ws, size_t ws_bytes, monarch_stream_t stream)
 {
-    clear_error();
     int rc = conv_check(B, H, n, klen, nfft, factors, nf, causal, dt);
     if (rc) return rc;
     if (B == 0 || H == 0) return MONARCH_OK;
@@ -900,6 +900,61 @@ int monarch_causal_conv(const void *u, const void *k, const void *g_in, const vo
         cur = p.out;
     }
     return MONARCH_OK;
+}
+
+int monarch_causal_conv(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                        int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                        int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
+                        monarch_stream_t stream)
+{
+    clear_error();
+    return conv_run(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, causal, dt, ws, ws_bytes, stream);
+}
+
+// The same convolution for callers that cannot allocate: the row buffers and the spectrum of k live in a
+// file-scope device array instead of a caller's workspace.  Every GPU the library runs on holds its own copy of
+// the array at its own address; host code never uses the array's name as an address (it is only a stand-in on the
+// host side) but the pointer looked up once per device below.
+static __device__ __align__(256) unsigned char scratch[MONARCH_STATIC_SCRATCH_BYTES];
+
+static const int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];          // per device: address of that device's copy, NULL until looked up
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+static int static_scratch(void **out)
+{
+    int dev = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MONARCH_EHIP, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        MONARCH_HIP_CHECK(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(MONARCH_EHIP, "the static scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MONARCH_OK;
+}
+
+int monarch_causal_conv_static(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                               int B, int H, int n, int klen, int nfft, const int *factors, int nf,
+                               int causal, monarch_dtype dt, monarch_stream_t stream)
+{
+    clear_error();
+    int rc = conv_check(B, H, n, klen, nfft, factors, nf, causal, dt);
+    if (rc) return rc;
+    const size_t need = monarch_causal_conv_workspace_bytes(B, H, n, klen, nfft, factors, nf, dt);
+    if (need > (size_t)MONARCH_STATIC_SCRATCH_BYTES)
+        return fail(MONARCH_EWORKSPACE, "this shape needs %zu bytes of scratch; the static array holds %zu "
+                    "(use monarch_causal_conv with a workspace)", need, (size_t)MONARCH_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    if (need) {
+        rc = static_scratch(&ptr);
+        if (rc) return rc;
+    }
+    return conv_run(u, k, g_in, g_out, y, B, H, n, klen, nfft, factors, nf, causal, dt, ptr, need, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
