@@ -221,6 +221,26 @@ def causal_conv(u, k, g_in=None, g_out=None, nfft=None, causal=True):
     return y
 
 
+def causal_conv_points(u, k, g_in, g_out, rows, ts, nfft=None, causal=True):
+    """Single outputs y[b, h, t] of causal_conv: rows[i] = b * H + h, ts[i] = t (for rows too long to sum whole)."""
+    u, k = _f64(u), _f64(k)
+    B, H, n = u.shape
+    klen = k.shape[1]
+    if nfft is None:
+        nfft = 2 * n
+    g_in = None if g_in is None else _f64(g_in)
+    g_out = None if g_out is None else _f64(g_out)
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    ts = np.ascontiguousarray(np.asarray(ts, dtype=np.int32))
+    assert rows.shape == ts.shape and rows.ndim == 1
+    assert rows.min(initial=0) >= 0 and rows.max(initial=0) < B * H and ts.min(initial=0) >= 0 and ts.max(initial=0) < n
+    out = np.empty(rows.shape[0], dtype=np.float64)
+    lib().oracle_causal_conv_points(_p(u), _p(k), _p(g_in), _p(g_out), _p(out), ctypes.c_int(B), ctypes.c_int(H),
+                                    ctypes.c_int(n), ctypes.c_int(klen), ctypes.c_int(nfft),
+                                    ctypes.c_int(1 if causal else 0), _p(rows), _p(ts), ctypes.c_int(rows.shape[0]))
+    return out
+
+
 def fft_conv_row(u, k, nfft):
     """(F^-1((F k') o (F u'))) over all nfft outputs for one row, via the naive DFT."""
     u, k = _f64(u), _f64(k)

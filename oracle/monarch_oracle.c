@@ -565,6 +565,38 @@ void oracle_causal_conv(const double *u, const double *k, const double *g_in, co
 }
 
 /*
+ * Single outputs of the same sums: y_pts[i] = y[row_i, t_i] with row_i = b*H + h, for sizes at which whole
+ * rows take too long (each output is one O(n) sum; same definition, same order of the additions).
+ */
+void oracle_causal_conv_points(const double *u, const double *k, const double *g_in, const double *g_out,
+                               double *y_pts, int B, int H, int n, int klen, int nfft, int causal,
+                               const int64_t *rows, const int *ts, int npts)
+{
+    (void)B;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int i = 0; i < npts; ++i) {
+        int64_t row = rows[i];
+        int t = ts[i];
+        int h = (int)(row % H);
+        const double *ur = u + (size_t)row * n;
+        const double *gi = g_in ? g_in + (size_t)row * n : NULL;
+        const double *kr = k + (size_t)h * klen;
+        double s = 0.0;
+        int last = causal ? t : n - 1;
+        for (int q = 0; q <= last; ++q) {
+            int lag = t - q;
+            if (!causal) {
+                lag %= nfft;
+                if (lag < 0) lag += nfft;
+            }
+            if (lag >= klen) continue;
+            s += kr[lag] * (gi ? gi[q] * ur[q] : ur[q]);
+        }
+        y_pts[i] = g_out ? g_out[(size_t)row * n + t] * s : s;
+    }
+}
+
+/*
  * The same map through the convolution theorem, exactly as the paper states
  * it: y = (F^-1 ((F k') o (F u')))[0:n], k' and u' zero-padded to nfft, with
  * the DFT of this file.  One row (no gates).  Used to pin the identity on

@@ -80,3 +80,31 @@ def test_monarch_convolution_with_dft_monarch():
     f = np.linalg.solve(M, (M @ k) * (M @ u))
     yd = oracle.causal_conv(u[None, None, :n], k[None, :n], nfft=N)[0, 0]
     assert np.abs(f[:n].real - yd).max() < 1e-11 and np.abs(f.imag).max() < 1e-11
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_single_outputs_against_library_convolve_and_a_toeplitz_product(causal):
+    # causal_conv_points: y[b, h, t] one output at a time.  Causal: the library's full convolution of the gated
+    # row, times the output gate.  Circular (two-sided kernel of length nfft): an explicit Toeplitz matrix
+    # T[t, s] = k[(t - s) mod nfft] built with numpy indexing.
+    rng = np.random.default_rng(5 + int(causal))
+    B, H, n, nfft = 3, 4, 37, 80
+    klen = 29 if causal else nfft
+    u, gi, go = rng.standard_normal((3, B, H, n))
+    k = rng.standard_normal((H, klen))
+    rows = rng.integers(0, B * H, size=60)
+    ts = rng.integers(0, n, size=60)
+    ts[:3] = (0, n - 1, klen % n)
+    got = oracle.causal_conv_points(u, k, gi, go, rows, ts, nfft=nfft, causal=causal)
+    for i, (row, t) in enumerate(zip(rows, ts)):
+        b, h = divmod(int(row), H)
+        if causal:
+            want = np.convolve(k[h], gi[b, h] * u[b, h])[t] * go[b, h, t]
+        else:
+            T = k[h][(np.arange(n)[:, None] - np.arange(n)[None, :]) % nfft]
+            want = (T @ (gi[b, h] * u[b, h]))[t] * go[b, h, t]
+        assert abs(got[i] - want) < 1e-12
+    # no gates; a planted off-by-one lag would be seen by the delta kernel
+    k1 = np.zeros((H, 5)); k1[:, 1] = 1.0
+    pts = oracle.causal_conv_points(u, k1, None, None, [0, 5], [0, 9], nfft=nfft, causal=True)
+    assert pts[0] == 0.0 and pts[1] == u[1, 1, 8]     # row 5 = (b 1, h 1)
