@@ -1,16 +1,27 @@
 #!/usr/bin/env python3
-"""Benchmark of the Monarch Mixer hot path on one MI355X.
+"""Benchmark of the Monarch Mixer hot path on one MI355X: the one measurement program of this repository.
 
-A step is one pass of the whole fused path (pad -> Monarch DFT -> (.) k_f -> inverse Monarch DFT
--> truncate, gates fused) over one batch of the configuration the metric is quoted on:
-the causal Monarch-FFT long convolution with B=8, H=768, n=1024 zero-padded to 2048 = 64 x 32,
-bf16 in / fp32 accumulate.  Inputs are seeded synthetic tensors already resident in HBM; the
-step rotates through enough distinct buffer sets (> 512 MB) that the 256 MB Infinity Cache
-cannot serve them.  Prints ONE JSON line.
+Headline (`value`, `ms_per_step`, `roofline`): a step is one pass of the whole fused path
+(pad -> Monarch DFT -> (.) k_f -> inverse Monarch DFT -> truncate, gates fused) over one batch of the
+configuration the metric is quoted on: the causal Monarch-FFT long convolution with B=8, H=768, n=1024
+zero-padded to 2048 = 64 x 32, bf16 in / fp32 accumulate.  `configs` carries the same measurement for every
+other named configuration (Monarch matmul at batch 2^20, the fp32 convolution, the M2-BERT-shaped convolution
+and MLP, the 128 x 128 and 64^3 long convolutions, the 16-block MLP).
+
+How a case is timed: inputs are seeded synthetic tensors already resident in HBM; a case rotates through
+enough distinct buffer sets (> 512 MB) that the 256 MB Infinity Cache cannot serve them; the launches of one
+pass over the sets are captured into a HIP graph; a timed region is exactly `steps` steps (replays of that graph
+plus one of a shorter graph for the remainder), bracketed by HIP events on the stream the kernels run on; the region is repeated until
+at least 50 ms have been timed and the median region is reported.  Prints ONE JSON line.
+
+  python bench.py                       headline + every configuration + oracle baseline
+  python bench.py --config c4_conv      one configuration only (what the rocprofv3 commands in profiles/ run)
+  python bench.py --copy-calibration 256   plain copies of 256 MiB (calibrates FETCH_SIZE / WRITE_SIZE)
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,124 +30,406 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per launch of the timed kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what
-# the same counter reads for a plain copy (0.5 and 1.0): profiles/conv2048_bf16_c2_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = int((19388.5 / 0.5 + 12288.0 / 1.0) * 1024)
-WORKLOAD = "c2_conv"
+MFMA_BF16_TFLOPS = 2500.0      # dense bf16 matrix peak, published
+MFMA_F32_TFLOPS = 157.3        # fp32 matrix peak, published
+HEADLINE = "c2_conv_bf16"
+MIN_TIMED_MS = 50.0
 
 
-def _make_set(torch, cfg, seed, canonical=None):
-    """One buffer set on the device.  Set 0 is the seeded numpy workload (also checked against
-    the oracle); the others are fresh draws of the same distributions made on the device."""
-    B, H, n = cfg["B"], cfg["H"], cfg["n"]
-    if canonical is not None:
-        return {k: (None if v is None else torch.from_numpy(v).cuda().to(torch.bfloat16)) for k, v in canonical.items()}
-    g = torch.Generator(device="cuda").manual_seed(1000 + seed)
-    u = torch.randn((B, H, n), device="cuda", generator=g)
-    t = torch.arange(n, device="cuda", dtype=torch.float32)
-    k = torch.randn((H, n), device="cuda", generator=g) * torch.exp(-0.01 * t)[None]
-    W1 = torch.randn((H, H), device="cuda", generator=g) / H ** 0.5
-    W2 = torch.randn((H, H), device="cuda", generator=g) / H ** 0.5
-    g_in = torch.matmul(W1.t()[None], u)
-    g_out = torch.matmul(W2.t()[None], u)
-    return {"u": u.bfloat16(), "k": k.bfloat16(), "g_in": g_in.bfloat16(), "g_out": g_out.bfloat16()}
+def traffic_from_profile(name):
+    """HBM bytes per launch of a case's dominant kernel as the counter run measured them: the line
+    `TRAFFIC <case> <bytes>` of profiles/hbm_traffic.txt (written from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
+    this program, each scaled by what the counter reads for a plain copy).  None when no such line exists."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*TRAFFIC\s+(\S+)\s+(\d+)", line)
+        if m and m.group(1) == name:
+            return int(m.group(2))
+    return None
+
+
+class Case:
+    """One configuration: buffer sets on the device, the call, the cost model, the parity sample."""
+    name = ""
+    workload = ""
+    dtype = "bf16"
+    kernel = ""
+
+    def build(self, torch, binding, workloads):      # -> list of zero-argument callables, one per buffer set
+        raise NotImplementedError
+
+    def elements(self):                              # the "(B*N*H)" unit of the metric
+        raise NotImplementedError
+
+    def algorithmic_bytes(self):
+        raise NotImplementedError
+
+    def executed_flops(self):
+        return 0.0
+
+    bound = "hbm"
+    mfma_peak = MFMA_BF16_TFLOPS
+
+    def parity(self, np, torch, oracle):             # -> (rel_l2, description) of buffer set 0 against the oracle
+        return None, ""
+
+    def roofline(self, ms):
+        t = ms * 1e-3
+        gbs = self.algorithmic_bytes() / t / 1e9
+        tf = self.executed_flops() / t / 1e12
+        r = {"bound": self.bound, "kernel": self.kernel, "algorithmic_bytes_per_step": self.algorithmic_bytes(),
+             "executed_flops_per_step": self.executed_flops(), "hbm_gbs": gbs, "executed_tflops": tf,
+             "traffic": traffic_from_profile(self.name)}
+        if self.bound == "hbm":
+            r.update(achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS)
+        else:
+            r.update(achieved=tf, peak=self.mfma_peak, unit="TFLOP/s", frac=tf / self.mfma_peak)
+        return r
+
+
+def _nsets(bytes_per_set, cap=24):
+    return max(2, min(cap, int(512e6 // max(bytes_per_set, 1)) + 2))
+
+
+def _rel(np, got, want):
+    return float(np.linalg.norm(np.asarray(got, dtype=np.float64) - want) / np.linalg.norm(want))
+
+
+class ConvCase(Case):
+    def __init__(self, name, cfg_key, bf16, kernel, bound="hbm", mfma_peak=MFMA_BF16_TFLOPS, launches=1):
+        self.name, self.cfg_key, self.bf16, self.kernel, self.bound, self.mfma_peak = name, cfg_key, bf16, kernel, bound, mfma_peak
+        self.dtype = "bf16" if bf16 else "f32"
+        self.launches = launches
+
+    def build(self, torch, binding, workloads):
+        from paper_2310_12109_amd import costmodel
+        self.costmodel = costmodel
+        c = workloads.CONFIGS[self.cfg_key]
+        self.B, self.H, self.n, self.factors, self.gates = c["B"], c["H"], c["n"], tuple(c["factors"]), c["gates"]
+        B, H, n = self.B, self.H, self.n
+        nfft = 1
+        for f in self.factors:
+            nfft *= f
+        self.nfft = nfft
+        self.workload = ("causal Monarch-FFT conv B=%d H=%d n=%d nfft=%d=%s, gates fused, %s" %
+                         (B, H, n, nfft, "x".join(map(str, self.factors)), "bf16 in / fp32 acc" if self.bf16 else "fp32"))
+        tdt = torch.bfloat16 if self.bf16 else torch.float32
+        self.canonical = workloads.conv_inputs(B, H, n, c["seed"], gates=self.gates, bf16=self.bf16)
+        first = {k: (None if v is None else torch.from_numpy(v).cuda().to(tdt)) for k, v in self.canonical.items()}
+        nsets = _nsets(self.algorithmic_bytes())
+        self.sets = [first]
+        t = torch.arange(n, device="cuda", dtype=torch.float32)
+        for s in range(1, nsets):
+            g = torch.Generator(device="cuda").manual_seed(1000 + s)
+            u = torch.randn((B, H, n), device="cuda", generator=g)
+            k = torch.randn((H, n), device="cuda", generator=g) * torch.exp(-0.01 * t)[None]
+            if self.gates == "projected":
+                W1 = torch.randn((H, H), device="cuda", generator=g) / H ** 0.5
+                W2 = torch.randn((H, H), device="cuda", generator=g) / H ** 0.5
+                g_in, g_out = torch.matmul(W1.t()[None], u), torch.matmul(W2.t()[None], u)
+            else:
+                g_in = torch.randn((B, H, n), device="cuda", generator=g)
+                g_out = torch.randn((B, H, n), device="cuda", generator=g)
+            self.sets.append({"u": u.to(tdt), "k": k.to(tdt), "g_in": g_in.to(tdt), "g_out": g_out.to(tdt)})
+            del u, k, g_in, g_out
+        self.outs = [torch.empty_like(s["u"]) for s in self.sets]
+        ws_bytes = binding.monarch_causal_conv_workspace_bytes(B, H, n, n, self.factors, binding.BF16 if self.bf16 else binding.F32)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+
+        def call(i):
+            s = self.sets[i]
+            return lambda: binding.monarch_causal_conv(s["u"], s["k"], s["g_in"], s["g_out"], self.factors, causal=True, ws=ws, out=self.outs[i])
+        return [call(i) for i in range(nsets)]
+
+    def elements(self):
+        return self.B * self.n * self.H
+
+    def algorithmic_bytes(self):
+        es = 2 if self.bf16 else 4
+        return (2 + 2) * self.B * self.H * self.n * es + self.H * self.n * es
+
+    def executed_flops(self):
+        return self.costmodel.conv_executed_flops(self.B, self.H, self.factors)
+
+    def parity(self, np, torch, oracle):
+        w = self.canonical
+        got = self.outs[0].float().cpu().numpy().astype(np.float64)
+        rows_total = self.B * self.H
+        if rows_total * self.n * self.n <= 2e10:       # the whole tensor by the direct sum
+            want = oracle.causal_conv(w["u"], w["k"], w["g_in"], w["g_out"], nfft=self.nfft)
+            return _rel(np, got, want), "every output, direct O(n^2) sum in fp64"
+        rng = np.random.default_rng(0)
+        npts = 4096
+        rows = rng.integers(0, rows_total, size=npts)
+        ts = rng.integers(0, self.n, size=npts)
+        ts[:4] = (0, 1, self.n // 2, self.n - 1)
+        want = oracle.causal_conv_points(w["u"], w["k"], w["g_in"], w["g_out"], rows, ts, nfft=self.nfft)
+        return _rel(np, got.reshape(rows_total, self.n)[rows, ts], want), "%d seeded outputs, direct O(n) sums in fp64" % npts
+
+
+class MatmulCase(Case):
+    name = "c1_matmul_f32_batch_2p20"
+    dtype = "f32"
+    kernel = "monarch_b16_kernel<float>"
+    batch = 1 << 20
+
+    def build(self, torch, binding, workloads):
+        self.workload = "order-2 Monarch matmul N=256 (16 blocks of 16x16), fp32, batch 2^20 (config 1's kernel at steady state)"
+        w = workloads.monarch_matmul_inputs(batch=4096, b=16, seed=0)
+        self.canonical = w
+        R, L = torch.from_numpy(w["R"]).cuda(), torch.from_numpy(w["L"]).cuda()
+        g = torch.Generator(device="cuda").manual_seed(7)
+        self.x = torch.randn((self.batch, 256), device="cuda", generator=g)
+        self.x[:4096] = torch.from_numpy(w["x"]).cuda()
+        self.y = torch.empty_like(self.x)
+        self.x2 = torch.randn((self.batch, 256), device="cuda", generator=g)
+        self.y2 = torch.empty_like(self.x2)
+        return [lambda: binding.monarch_matmul(self.x, R, L, out=self.y), lambda: binding.monarch_matmul(self.x2, R, L, out=self.y2)]
+
+    def elements(self):
+        return self.batch * 256
+
+    def algorithmic_bytes(self):
+        return (2 * self.batch * 256 + 2 * 16 * 256) * 4
+
+    def executed_flops(self):
+        return self.batch * 4.0 * 256 * 16
+
+    def parity(self, np, torch, oracle):
+        w = self.canonical
+        got = self.y[:4096].cpu().numpy()
+        return _rel(np, got, oracle.matmul(w["x"], w["R"], w["L"])), "the first 4096 vectors against the dense 256x256 product in fp64"
+
+
+class MlpCase(Case):
+    def __init__(self, name, cfg_key, order, kernel, bound):
+        self.name, self.cfg_key, self.order, self.kernel, self.bound = name, cfg_key, order, kernel, bound
+
+    def build(self, torch, binding, workloads):
+        from paper_2310_12109_amd import costmodel
+        self.costmodel = costmodel
+        c = workloads.CONFIGS[self.cfg_key]
+        self.tokens, self.d, self.dh, self.nb = c["tokens"], c["d"], c["d_hidden"], c["nb"]
+        self.workload = "Monarch MLP order %d, %d tokens, %d -> %d -> %d, %d blocks, GELU, bf16" % (
+            self.order, self.tokens, self.d, self.dh, self.d, self.nb)
+        w = workloads.mlp_inputs(self.tokens, self.d, self.dh, self.nb, self.order, c["seed"], bf16=True)
+        self.canonical = w
+        bf = lambda a: None if a is None else torch.from_numpy(a).cuda().to(torch.bfloat16)
+        wt = {k: bf(w[k]) for k in ("W1_R", "W1_L", "b1", "W2_R", "W2_L", "b2")}
+        nsets = _nsets(self.algorithmic_bytes())
+        g = torch.Generator(device="cuda").manual_seed(11)
+        self.xs = [bf(w["x"])] + [torch.randn((self.tokens, self.d), device="cuda", generator=g).to(torch.bfloat16) for _ in range(nsets - 1)]
+        self.ys = [torch.empty_like(x) for x in self.xs]
+        ws_bytes = binding.monarch_mlp_workspace_bytes(self.tokens, self.d, self.dh, self.nb, self.order, 0, 0, binding.BF16)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+
+        def call(i):
+            return lambda: binding.monarch_mlp(self.xs[i], wt["W1_R"], wt["W1_L"], wt["b1"], wt["W2_R"], wt["W2_L"], wt["b2"],
+                                               self.nb, self.order, 2, self.dh, ws=ws, out=self.ys[i])
+        return [call(i) for i in range(nsets)]
+
+    def elements(self):
+        return self.tokens * self.d
+
+    def algorithmic_bytes(self):
+        return self.costmodel.mlp_algorithmic_bytes(self.tokens, self.d, self.dh, self.nb, self.order)
+
+    def executed_flops(self):
+        return self.costmodel.mlp_flops(self.tokens, self.d, self.dh, self.nb, self.order)
+
+    def parity(self, np, torch, oracle):
+        w = self.canonical
+        rows = np.sort(np.random.default_rng(0).choice(self.tokens, size=128, replace=False))
+        rows[0], rows[-1] = 0, self.tokens - 1
+        want = oracle.mlp(w["x"][rows], w["W1_R"], w["W1_L"], w["b1"], w["W2_R"], w["W2_L"], w["b2"], nb=self.nb, order=self.order, act=2)
+        got = self.ys[0].float().cpu().numpy()[rows]
+        return _rel(np, got, want), "128 seeded tokens against the dense-materialised MLP in fp64"
+
+
+def all_cases():
+    return [
+        ConvCase("c2_conv_bf16", "c2_conv", True, "conv2048_bf16_kernel", "hbm"),
+        MatmulCase(),
+        ConvCase("c2_conv_f32", "c2_conv", False, "fft_pass_mfma_f32_kernel (6 launches)", "mfma", MFMA_F32_TFLOPS),
+        ConvCase("c3a_conv_bf16", "c3a_conv", True, "conv256_bf16_kernel", "hbm"),
+        MlpCase("c3b_mlp_order1", "c3b_mlp", 1, "mlp_order1_split_kernel", "mfma"),
+        MlpCase("c3b_mlp_order2", "c3b_mlp", 2, "factor_kernel + mlp_order1 + factor_kernel", "mfma"),
+        ConvCase("c4_conv_bf16", "c4_conv", True, "fft2_lds_kernel<128,128> (fused chunk convolution)", "mfma"),
+        ConvCase("c5a_conv_bf16", "c5a_conv", True, "fft_pass_mfma_kernel + fft2_lds_kernel<64,64> (6 launches)", "mfma"),
+        MlpCase("c5b_mlp_order1", "c5b_mlp", 1, "mlp_order1_resident_kernel", "hbm"),
+        MlpCase("c5b_mlp_order2", "c5b_mlp", 2, "factor_kernel + mlp_order1_resident_kernel + factor_kernel", "hbm"),
+    ]
+
+
+def time_case(torch, calls, steps, warmup):
+    """Median time of a region of exactly `steps` steps, in ms per step; regions repeat until >= MIN_TIMED_MS."""
+    nsets = len(calls)
+    for i in range(max(warmup, 1)):
+        calls[i % nsets]()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in calls:
+            c()
+    graph.replay()
+    rest = None                      # the steps of a region that do not fill a whole pass: a second graph
+    if steps % nsets:
+        rest = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(rest):
+            for c in calls[:steps % nsets]:
+                c()
+        rest.replay()
+    torch.cuda.synchronize()
+    regions, total_ms, host_ms = [], 0.0, 0.0
+    while (total_ms < MIN_TIMED_MS or len(regions) < 3) and len(regions) < 2000:
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        start.record()
+        for _ in range(steps // nsets):
+            graph.replay()
+        if rest is not None:
+            rest.replay()
+        end.record()
+        torch.cuda.synchronize()
+        host_ms += (time.perf_counter() - t0) * 1e3
+        regions.append(start.elapsed_time(end))
+        total_ms += regions[-1]
+    regions.sort()
+    med = regions[len(regions) // 2]
+    return {"ms_per_step": med / steps, "regions": len(regions), "region_ms_min": regions[0], "region_ms_max": regions[-1],
+            "host_wall_ms_per_step": host_ms / (len(regions) * steps), "buffer_sets": nsets}
+
+
+def run_case(torch, np, binding, workloads, oracle, case, steps, warmup, check):
+    calls = case.build(torch, binding, workloads)
+    t = time_case(torch, calls, steps, warmup)
+    ms = t["ms_per_step"]
+    rec = {"name": case.name, "workload": case.workload, "dtype": case.dtype, "steps": steps, "ms_per_step": ms,
+           "value": case.elements() / (ms * 1e-3), "unit": "elements/s", "roofline": case.roofline(ms)}
+    rec.update({k: t[k] for k in ("regions", "region_ms_min", "region_ms_max", "host_wall_ms_per_step", "buffer_sets")})
+    if check:
+        calls[0]()
+        torch.cuda.synchronize()
+        rel, how = case.parity(np, torch, oracle)
+        rec["rel_l2_vs_oracle"] = rel
+        rec["parity_sample"] = how
+    return rec
+
+
+def copy_calibration(mib):
+    """Plain device-to-device copies of a known size: what FETCH_SIZE / WRITE_SIZE read for known traffic."""
+    import torch
+    n = mib * (1 << 20)
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(8):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration_mib": mib, "copies": 8}))
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5500)
+    ap.add_argument("--steps", type=int, default=1100, help="steps of the headline case per timed region")
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--config", action="append", help="run only these cases (names as in the `configs` list); the first is the headline of the line")
+    ap.add_argument("--no-extra-configs", action="store_true", help="headline only")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle legs (parity samples and the oracle timing)")
+    ap.add_argument("--copy-calibration", type=int, metavar="MIB", help="only run plain copies of this size (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (rows are independent, so more GPUs "
               "would just split the batch); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.copy_calibration:
+        copy_calibration(args.copy_calibration)
+        return
 
     import numpy as np
     import torch
 
-    from paper_2310_12109_amd import binding, costmodel, workloads
+    from paper_2310_12109_amd import binding, workloads
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg = workloads.CONFIGS[WORKLOAD]
-    B, H, n, factors = cfg["B"], cfg["H"], cfg["n"], cfg["factors"]
-
-    canonical = workloads.conv_inputs(B, H, n, cfg["seed"], gates=cfg["gates"], bf16=True)
-    bytes_per_step = costmodel.conv_algorithmic_bytes(B, H, n, n, dtype_bytes=2, gates=2)
-    nsets = max(2, int(np.ceil(512e6 / bytes_per_step)) + 1)
-    sets = [_make_set(torch, cfg, 0, canonical)] + [_make_set(torch, cfg, s) for s in range(1, nsets)]
-    outs = [torch.empty_like(s["u"]) for s in sets]
-    ws_bytes = binding.monarch_causal_conv_workspace_bytes(B, H, n, n, factors, binding.BF16)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
-
-    def step(i):
-        s = sets[i % nsets]
-        binding.monarch_causal_conv(s["u"], s["k"], s["g_in"], s["g_out"], factors, causal=True, ws=ws, out=outs[i % nsets])
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    # One pass over all buffer sets is captured into a HIP graph (the step is a single ~15 us
-    # kernel: launching it from Python call by call would time the interpreter, not the GPU).
-    # The timed region replays it and runs the remainder eagerly: exactly `steps` steps.
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        for i in range(nsets):
-            step(i)
-    graph.replay()
-    torch.cuda.synchronize()
-    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    start.record()
-    for _ in range(args.steps // nsets):
-        graph.replay()
-    for i in range(args.steps % nsets):
-        step(i)
-    end.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ev_ms = start.elapsed_time(end)
-    ms_per_step = ev_ms / args.steps
-    value = B * n * H / (ms_per_step * 1e-3)
-
-    achieved_gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
-    flops = costmodel.conv_executed_flops(B, H, factors)
-
-    out = {
-        "metric": "M2 mixer tokens/s (B*N*H)", "value": value, "unit": "elements/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "causal Monarch-FFT conv B=8 H=768 n=1024 nfft=2048=64x32, gates fused, bf16 in / fp32 acc",
-                   "B": B, "H": H, "n": n, "nfft": int(np.prod(factors)), "factors": list(factors),
-                   "buffer_sets": nsets, "launch": "hip graph of %d steps, replayed" % nsets, "sequence_tokens_per_s": B * n / (ms_per_step * 1e-3)},
-        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "conv2048_bf16_kernel", "algorithmic_bytes_per_launch": bytes_per_step,
-                     "executed_tflops": flops / (ms_per_step * 1e-3) / 1e12},
-        "host_wall_ms_per_step": wall_ms / args.steps,
-    }
-
-    # parity of the timed configuration against the oracle, and the oracle's own speed
+    oracle = None
     if not args.no_cpu_baseline:
         import oracle
+
+    cases = {c.name: c for c in all_cases()}
+    if args.config:
+        unknown = [n for n in args.config if n not in cases]
+        if unknown:
+            sys.exit("bench.py: unknown case(s) %s; known: %s" % (unknown, ", ".join(cases)))
+        order = args.config
+    else:
+        order = [HEADLINE] + ([] if args.no_extra_configs else [n for n in cases if n != HEADLINE])
+
+    head_case = cases[order[0]]
+    head = run_case(torch, np, binding, workloads, oracle, head_case, args.steps, args.warmup, oracle is not None)
+    out = {
+        "metric": "M2 mixer tokens/s (B*N*H)", "value": head["value"], "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head_case.dtype, "data": "synthetic",
+        "config": {"workload": head["workload"], "case": head["name"], "buffer_sets": head["buffer_sets"],
+                   "launch": "hip graph of one pass over the buffer sets, replayed; %d regions of %d steps, median" % (head["regions"], args.steps),
+                   "region_ms_min": head["region_ms_min"], "region_ms_max": head["region_ms_max"]},
+        "roofline": head["roofline"],
+        "host_wall_ms_per_step": head["host_wall_ms_per_step"],
+    }
+    if hasattr(head_case, "B"):
+        out["config"]["sequence_tokens_per_s"] = head_case.B * head_case.n / (head["ms_per_step"] * 1e-3)
+    if "rel_l2_vs_oracle" in head:
+        out["rel_l2_vs_oracle"] = head["rel_l2_vs_oracle"]
+
+    # the oracle's own speed on the headline workload (a reported baseline, not a target)
+    if oracle is not None and isinstance(head_case, ConvCase):
+        w = head_case.canonical
+        rows_total = head_case.B * head_case.H
+        sample_rows = max(1, min(rows_total, int(2e11 // (head_case.n * head_case.n))))    # bounds the CPU work
+        b_rows = max(1, sample_rows // head_case.H)
+        sub = {k: (None if w[k] is None else w[k][:b_rows]) for k in ("u", "g_in", "g_out")}
         reps = []
-        want = None
         for _ in range(3):
             t1 = time.perf_counter()
-            want = oracle.causal_conv(canonical["u"], canonical["k"], canonical["g_in"], canonical["g_out"], nfft=2048)
+            oracle.causal_conv(sub["u"], w["k"], sub["g_in"], sub["g_out"], nfft=head_case.nfft)
             reps.append(time.perf_counter() - t1)
         cpu_s = sorted(reps)[1]
-        step(0)
-        torch.cuda.synchronize()
-        got = outs[0].float().cpu().numpy().astype(np.float64)
-        out["rel_l2_vs_oracle"] = float(np.linalg.norm(got - want) / np.linalg.norm(want))
-        out["cpu_baseline"] = {"value": B * n * H / cpu_s, "unit": "elements/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "the full batch (8 x 768 rows of 1024), direct O(n^2) sum in "
-                               "fp64, median of 3 runs (%.2f s each)" % cpu_s}
+        out["cpu_baseline"] = {"value": b_rows * head_case.H * head_case.n / cpu_s, "unit": "elements/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "%d of %d batch entries (%d rows of %d), direct O(n^2) sum in fp64, "
+                               "median of 3 runs (%.2f s each)" % (b_rows, head_case.B, b_rows * head_case.H, head_case.n, cpu_s)}
+    del head_case
+    cases[order[0]] = None
+    torch.cuda.empty_cache()
+
+    extra = []
+    for name in order[1:]:
+        case = cases[name]
+        try:
+            extra.append(run_case(torch, np, binding, workloads, oracle, case, _steps_for(case), min(args.warmup, 5), oracle is not None))
+        finally:
+            cases[name] = None
+            del case
+            torch.cuda.empty_cache()
+    if extra:
+        out["configs"] = extra
     print(json.dumps(out))
+
+
+def _steps_for(case):
+    """Steps per timed region of a non-headline case: short kernels get more so that a region is not a handful
+    of microseconds; every region is still repeated until 50 ms have been timed."""
+    if isinstance(case, ConvCase) and case.cfg_key == "c3a_conv":
+        return 440
+    if isinstance(case, MlpCase) and case.cfg_key == "c3b_mlp":
+        return 240
+    if isinstance(case, ConvCase) and case.cfg_key == "c2_conv":
+        return 100
+    return 12
 
 
 if __name__ == "__main__":

@@ -23,13 +23,23 @@ def conv_algorithmic_bytes(B, H, n, klen, dtype_bytes, gates=2):
 
 
 def conv_executed_flops(B, H, factors):
-    """FLOPs the fused order-2 kernel actually issues: two real rows share one complex transform,
-    the zero-padded half of the first factor and the discarded half of the last are skipped."""
-    N1, N2 = factors
-    N = N1 * N2
-    per_pair = 4.0 * N * N1 + 8.0 * N * N2 + 8.0 * N * N2 + 4.0 * N * N1 + 3 * 6.0 * N
-    per_kernel_row = 2.0 * N * N1 + 8.0 * N * N2 + 6.0 * N
-    return math.ceil(B / 2) * H * per_pair + H * per_kernel_row
+    """FLOPs the convolution kernels actually issue, for two or three factors f0, f1[, f2] (N their product):
+    two real rows share one complex transform (two batch entries of a channel; with B = 1 two neighbouring
+    channels, the kernels paired alike), the zero-padded half of the first factor's input and the discarded
+    half of its output in the inverse are skipped, and a real kernel row costs half a complex one in the first
+    factor.  A complex DFT factor of size f over N points is four real GEMMs: 8 N f."""
+    N = 1
+    for f in factors:
+        N *= f
+    f0, rest = factors[0], sum(factors[1:])
+    diagonals = 6.0 * N * (len(factors) - 1)
+    row_forward = 4.0 * N * f0 + 8.0 * N * rest + diagonals             # complex row, half of the input zero
+    row_inverse = 8.0 * N * rest + 4.0 * N * f0 + diagonals + 6.0 * N   # times k_f; half of the output dropped
+    if B == 1 and H >= 2:
+        crows = math.ceil(H / 2)
+        return crows * (2 * row_forward + row_inverse)
+    kernel_row = 2.0 * N * f0 + 8.0 * N * rest + diagonals              # real input
+    return math.ceil(B / 2) * H * (row_forward + row_inverse) + H * kernel_row
 
 
 def conv_textbook_flops(B, H, factors):
