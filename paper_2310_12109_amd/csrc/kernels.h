@@ -130,6 +130,11 @@ bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monar
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                           int B, int H, int n, int klen, hipStream_t s);
 
+// nfft = 16384 = 128 x 128, n <= 8192, klen <= 8192 (both multiples of 8), bf16 I/O; no workspace.
+bool conv_mfma_16k_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
+int launch_conv_mfma_16k(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                         int B, int H, int n, int klen, hipStream_t s);
+
 // nfft = 256 = 16 x 16, n <= 128, klen <= 256, bf16 I/O; no workspace.
 bool conv_mfma_256_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
 int launch_conv_mfma_256(const void *u, const void *k, const void *g_in, const void *g_out, void *y,

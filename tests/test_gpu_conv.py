@@ -150,6 +150,30 @@ def test_fused_64x32_bf16_many_batch_groups(mm, B, n, klen):
     assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_BF16
 
 
+@pytest.mark.parametrize("B,H,n,klen,gates", [
+    (3, 5, 8192, 8192, "both"),     # odd batch: the last pair of every channel has one row
+    (4, 3, 8000, 8000, "none"),     # rows that end inside a tile row
+    (1, 4, 4096, 1000, "in"),       # one sequence per channel, short kernel
+    (2, 300, 8192, 512, "out"),     # more channels than compute units: workgroups walk over several
+    (6, 2, 128, 8, "both"),         # a single tile row of input
+])
+def test_fused_128x128_bf16(mm, B, H, n, klen, gates):
+    # nfft = 16384 = 128 x 128 with rows of a multiple of 8 elements: the fused kernel (spectrum of k in registers,
+    # row pairs through one LDS tile); every output against the direct sum
+    announce("conv fused 128x128 bf16", B, H, n, klen, gates)
+    w = workloads.conv_inputs(B, H, n, seed=B + H + n + klen, gates="normal", bf16=True)
+    w["k"] = np.ascontiguousarray(w["k"][:, :klen])
+    if gates in ("out", "none"):
+        w["g_in"] = None
+    if gates in ("in", "none"):
+        w["g_out"] = None
+    y = _run(mm, w, (128, 128), True)
+    want = _oracle(w, 16384)
+    assert rel_l2(y, want) <= TOL_BF16
+    num = np.linalg.norm((y - want).reshape(-1, n), axis=1)
+    assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_BF16
+
+
 def test_delta_kernel_and_causality(mm):
     announce("conv delta / causality")
     B, H, n = 2, 3, 1024
