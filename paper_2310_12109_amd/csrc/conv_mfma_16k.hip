@@ -76,9 +76,12 @@ __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// Column of the tile word (row, col): the 16-column groups of rows with bit 3 set are swapped, so that the four
-// lane groups of a strided read (rows 8 apart) fall on different banks; runs of 16 columns stay contiguous.
-__device__ __forceinline__ int swz(int row, int col) { return col ^ ((row & 8) << 1); }
+// Column of the tile word (row, col): the 16-column groups of a row are swapped when bits 3 and 4 of the row differ.
+// The four lane groups of a strided access read rows 8 apart: 8 rows are 32 banks, so with the swap they fall on
+// four different sets of 16 banks, whether the LDS has 32 banks (two lane groups per pass) or 64; runs of 16
+// columns stay contiguous for the 16-byte accesses along a row.
+__device__ __forceinline__ int swz_bit(int row) { return (((row >> 3) ^ (row >> 4)) & 1) << 4; }
+__device__ __forceinline__ int swz(int row, int col) { return col ^ swz_bit(row); }
 
 struct Ops { u32x4 re[4], im[4]; };     // the whole F_128 as this lane's A operands: 32 registers (rows j < 64)
 template <int T> __device__ __forceinline__ u32x4 half_rows(const u32x4 &a)   // rows j + 64 T of the same tile
@@ -213,10 +216,10 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
 
     // stage X / X': this wave's 16 columns; this lane's words sit at xbase + row' * PITCH, row' = row - 8 kg
     const int xcol = 16 * wave + l16;
-    const int xbase = 8 * kg * PITCH + (xcol ^ ((kg & 1) << 4));
+    const int xbase = 8 * kg * PITCH + (xcol ^ swz_bit(8 * kg));
     // stage Y / Y': this wave's 16 rows
     const int yrow = 16 * wave + l16;
-    const int yswz = (yrow & 8) << 1;
+    const int yswz = swz_bit(yrow);
     const uint32_t *yline = tile + yrow * PITCH;
 
     // job g of this workgroup: channel blockIdx.x + (g / jobs_per_channel) * gridDim.x, step g % jobs_per_channel
@@ -263,30 +266,26 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
         }
     };
 
-    int g = 0;
-    request(g);
-    for (;; ++g) {
-        const int h = job_channel(g), s = g % jobs_per_channel;
-        if (h >= H) break;
-        const bool is_kernel = s == 0;
-        const int b0 = 2 * (s - 1);
-        const bool hasb = !is_kernel && b0 + 1 < B;
-        const int len = is_kernel ? klen : n;
-
-        // ---- rows -> tile (rows c1 < 64; zero past the end of the row)
+    // Rows of job g (as requested) -> tile rows c1 < 64, zero past the end of the row.  Every thread writes the same
+    // tile words that it reads in the last pass of a pair job, so no barrier is needed between that pass and this.
+    auto deposit = [&](int g) {
+        const int s = g % jobs_per_channel;
+        const bool isk = s == 0;
+        const bool two = !isk && 2 * (s - 1) + 1 < B;
+        const int len = isk ? klen : n;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int e = 8 * (tid + it * THREADS), row = e >> 7, col = e & 127;
             float a[8], bb[8], gt[8];
             unpack8(in.a[it], a);
-            if (GIN && !is_kernel) {
+            if (GIN && !isk) {
                 unpack8(in.ga[it], gt);
 #pragma unroll
                 for (int t = 0; t < 8; ++t) a[t] *= gt[t];
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) bb[t] = 0.0f;
-            if (hasb) {
+            if (two) {
                 unpack8(in.b[it], bb);
                 if (GIN) {
                     unpack8(in.gb[it], gt);
@@ -305,7 +304,18 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
             *reinterpret_cast<u32x4 *>(dst) = w0;
             *reinterpret_cast<u32x4 *>(dst + 4) = w1;
         }
-        __syncthreads();
+    };
+
+    request(0);
+    deposit(0);
+    __syncthreads();
+    for (int g = 0;; ++g) {
+        const int h = job_channel(g), s = g % jobs_per_channel;
+        if (h >= H) break;
+        const bool is_kernel = s == 0;
+        const int b0 = 2 * (s - 1);
+        const bool hasb = !is_kernel && b0 + 1 < B;
+        const bool more = job_channel(g + 1) < H;   // another job follows
         request(g + 1);   // the next job's rows travel while this one is transformed
 
         // ---- stage X: contract c1 down this wave's columns (rows >= 64 are padding: two blocks), twiddle
@@ -362,7 +372,9 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
             MONARCH_C16K_K_TILE(0, 0) MONARCH_C16K_K_TILE(0, 1) MONARCH_C16K_K_TILE(0, 2) MONARCH_C16K_K_TILE(0, 3)
             MONARCH_C16K_K_TILE(1, 0) MONARCH_C16K_K_TILE(1, 1) MONARCH_C16K_K_TILE(1, 2) MONARCH_C16K_K_TILE(1, 3)
 #undef MONARCH_C16K_K_TILE
-            __syncthreads();   // every wave has read its rows: the next job may overwrite the tile
+            __syncthreads();   // every wave has read its rows: the next job's rows may overwrite the tile
+            deposit(g + 1);    // (a pair job always follows a kernel job)
+            __syncthreads();
             continue;
         }
 
@@ -479,6 +491,9 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
             yb[it] = u32x4{pack2(vb[0], vb[1]), pack2(vb[2], vb[3]), pack2(vb[4], vb[5]), pack2(vb[6], vb[7])};
         }
         asm volatile("" : "+v"(ya[0]), "+v"(ya[1]), "+v"(yb[0]), "+v"(yb[1]));   // computed here, not inside the tests
+        // the next job's rows go into the tile words this thread has just read; the stores come last, so that
+        // nothing waits for them
+        if (more) deposit(g + 1);
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int e = 8 * (tid + it * THREADS);
@@ -487,7 +502,7 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
                 if (hasb) *reinterpret_cast<u32x4 *>(y + rb + e) = yb[it];
             }
         }
-        __syncthreads();   // the tile is free for the next job's rows
+        __syncthreads();   // the next job's rows are in the tile
     }
 }
 
