@@ -17,6 +17,7 @@ at least 50 ms have been timed and the median region is reported.  Prints ONE JS
   python bench.py                       headline + every configuration + oracle baseline
   python bench.py --config c4_conv      one configuration only (what the rocprofv3 commands in profiles/ run)
   python bench.py --copy-calibration 256   plain copies of 256 MiB (calibrates FETCH_SIZE / WRITE_SIZE)
+  python bench.py --summarize-profile DIR [--kernel NAME]   medians of a rocprofv3 output folder (no GPU needed)
 """
 import argparse
 import json
@@ -248,6 +249,176 @@ class MlpCase(Case):
         return _rel(np, got, want), "128 seeded tokens against the dense-materialised MLP in fp64"
 
 
+class RandomCase(Case):
+    """A case of the widening rows (learned mixer, gradients, order 3, the basic layer, the blocky convolution, the
+    plain transforms): random tensors of the stated shapes, timed like every other case; their parity with the
+    oracle is the business of tests/, so no sample is checked here.  `make(torch, binding, rnd)` returns a function
+    that builds one buffer set and returns its call."""
+    def __init__(self, name, workload, dtype, kernel, nbytes, flops, elements, make, bound="hbm", mfma_peak=MFMA_F32_TFLOPS):
+        self.name, self.workload, self.dtype, self.kernel = name, workload, dtype, kernel
+        self._bytes, self._flops, self._elements, self._make = nbytes, flops, elements, make
+        self.bound, self.mfma_peak = bound, mfma_peak
+
+    def build(self, torch, binding, workloads):
+        def rnd(*shape, dt=torch.float32, scale=1.0):
+            return (torch.randn(*shape, device="cuda") * scale).to(dt)
+        one = self._make(torch, binding, workloads, rnd)
+        return [one() for _ in range(_nsets(self._bytes))]
+
+    def elements(self):
+        return self._elements
+
+    def algorithmic_bytes(self):
+        return self._bytes
+
+    def executed_flops(self):
+        return self._flops
+
+
+def widening_cases():
+    """Cases that only run when named with --config (what the rocprofv3 commands of profiles/ use)."""
+    cases = []
+
+    def add(*a, **k):
+        cases.append(RandomCase(*a, **k))
+
+    def tdt(torch, name):
+        return torch.bfloat16 if name == "bf16" else torch.float32
+
+    for batch in (64, 1 << 20):
+        for dn in ("f32", "bf16"):
+            es = 4 if dn == "f32" else 2
+
+            def mk_fwd(torch, binding, workloads, rnd, batch=batch, dn=dn):
+                dt = tdt(torch, dn)
+                R, L = rnd(16, 16, 16, dt=dt, scale=.25), rnd(16, 16, 16, dt=dt, scale=.25)
+
+                def one():
+                    x = rnd(batch, 256, dt=dt)
+                    y = torch.empty_like(x)
+                    return lambda: binding.monarch_matmul(x, R, L, out=y)
+                return one
+
+            def mk_bwd(torch, binding, workloads, rnd, batch=batch, dn=dn):
+                dt = tdt(torch, dn)
+                R, L = rnd(16, 16, 16, dt=dt, scale=.25), rnd(16, 16, 16, dt=dt, scale=.25)
+
+                def one():
+                    x, dy = rnd(batch, 256, dt=dt), rnd(batch, 256, dt=dt)
+                    return lambda: binding.monarch_matmul_backward(x, R, L, dy)
+                return one
+            add("c1_matmul_%s_batch_%d" % (dn, batch), "order-2 Monarch matmul N=256, %s, batch %d" % (dn, batch), dn,
+                "monarch_b16_kernel", (2 * batch * 256 + 2 * 4096) * es, batch * 4.0 * 256 * 16, batch * 256, mk_fwd)
+            add("c1_backward_%s_batch_%d" % (dn, batch), "gradients of the order-2 Monarch matmul N=256, %s, batch %d" % (dn, batch), dn,
+                "matmul_backward_b16_kernel", 3 * batch * 256 * es + 2 * 4096 * (es + 4), batch * 10.0 * 256 * 16, batch * 256, mk_bwd)
+
+    for B in (8, 1024):
+        for dn in ("f32", "bf16"):
+            es = 4 if dn == "f32" else 2
+            rows = B * 768
+
+            def mk_mixer(torch, binding, workloads, rnd, B=B, dn=dn):
+                dt = tdt(torch, dn)
+                K = rnd(768, 256, dt=dt)
+                f = [rnd(16, 16, 16, dt=dt, scale=.25) for _ in range(4)]
+
+                def one():
+                    u, gi, go = (rnd(B, 768, 256, dt=dt) for _ in range(3))
+                    y = torch.empty_like(u)
+                    return lambda: binding.monarch_mixer(u, K, gi, go, *f, out=y)
+                return one
+
+            def mk_blocky(torch, binding, workloads, rnd, B=B, dn=dn):
+                dt = tdt(torch, dn)
+                w = workloads.blocky_inputs(1, 768, 128, 16, seed=0)
+                state = binding.monarch_blocky_prepare(*(torch.from_numpy(w[k]).cuda() for k in ("Lt", "Rt", "k")), mask=True)
+
+                def one():
+                    u, gi, go = (rnd(B, 768, 128, dt=dt) for _ in range(3))
+                    y = torch.empty_like(u)
+                    return lambda: binding.monarch_blocky_conv(u, gi, go, state, 16, out=y)
+                return one
+            add("mixer_%s_B%d" % (dn, B), "learned-Monarch sequence mixer N=256, B=%d H=768, %s" % (B, dn), dn, "mixer_b16_kernel",
+                (4 * rows * 256 + 768 * 256 + 4 * 4096) * es, rows * 8.0 * 256 * 16, rows * 256, mk_mixer)
+            add("blocky_conv_%s_B%d" % (dn, B), "polynomial-parameterised Monarch causal conv N=256 n=128, B=%d H=768, %s" % (B, dn), dn,
+                "blocky16::conv_b16_kernel", 4 * rows * 128 * es + 768 * 256 * 8 + 4 * 4096 * 8, rows / 16 * 704 * 2048.0, rows * 128,
+                mk_blocky, bound="mfma")
+
+    for B, dn in ((8, "f32"), (256, "f32"), (256, "bf16")):
+        es = 4 if dn == "f32" else 2
+
+        def mk_mixb(torch, binding, workloads, rnd, B=B, dn=dn):
+            dt = tdt(torch, dn)
+            K = rnd(768, 256, dt=dt)
+            f = [rnd(16, 16, 16, dt=dt, scale=.25) for _ in range(4)]
+            ws = torch.empty(binding.raw().monarch_mixer_backward_workspace_bytes(B, 768, 16, binding.F32 if dn == "f32" else binding.BF16),
+                             dtype=torch.uint8, device="cuda")
+
+            def one():
+                u, gi, go, dy = (rnd(B, 768, 256, dt=dt) for _ in range(4))
+                return lambda: binding.monarch_mixer_backward(u, K, gi, go, *f, dy, ws=ws)
+            return one
+        add("mixer_backward_%s_B%d" % (dn, B), "gradients of the learned mixer N=256, B=%d H=768, %s" % (B, dn), dn, "composition (9 launches)",
+            7 * B * 768 * 256 * es, B * 768 * 28.0 * 256 * 16, B * 768 * 256, mk_mixb)
+
+    for B, dn in ((32, "f32"), (2048, "f32"), (2048, "bf16")):
+        es = 4 if dn == "f32" else 2
+
+        def mk_layer(torch, binding, workloads, rnd, B=B, dn=dn):
+            dt = tdt(torch, dn)
+            w = workloads.m2_layer_inputs(1, 16, 16, seed=0)
+            par = {k: torch.from_numpy(v).cuda().to(dt) for k, v in w.items() if k != "x"}
+            seq, dim = [par[k] for k in ("R1", "L1", "R2", "L2")], [par[k] for k in ("R3", "L3", "R4", "L4")]
+            ws = torch.empty(binding.monarch_m2_layer_workspace_bytes(B, 256, 256, binding.F32 if dn == "f32" else binding.BF16),
+                             dtype=torch.uint8, device="cuda")
+
+            def one():
+                x = rnd(B, 256, 256, dt=dt)
+                y = torch.empty_like(x)
+                return lambda: binding.monarch_m2_layer(x, seq, par["n_kernel"], dim, par["d_kernel"], par["gamma"], par["beta"], ws=ws, out=y)
+            return one
+        add("m2_layer_%s_B%d" % (dn, B), "basic M2 layer n=d=256, B=%d, %s" % (B, dn), dn, "mixer_b16_kernel (2 launches)",
+            (4 * B * 65536 + 2 * 65536) * es, B * 512 * 16.0 * 256 * 16, B * 65536, mk_layer)
+
+    for b, batch in ((8, 16384), (16, 4096), (16, 65536)):
+        N = b ** 3
+
+        def mk_mm3(torch, binding, workloads, rnd, b=b, batch=batch, N=N, backward=False):
+            f = [rnd(b * b, b, b, scale=b ** -0.5) for _ in range(3)]
+
+            def one():
+                x = rnd(batch, N)
+                if backward:
+                    dy = rnd(batch, N)
+                    return lambda: binding.monarch_matmul3_backward(x, *f, dy)
+                y = torch.empty_like(x)
+                return lambda: binding.monarch_matmul3(x, *f, out=y)
+            return one
+        add("matmul3_f32_b%d_batch_%d" % (b, batch), "general order-3 Monarch product N=%d, fp32, batch %d" % (N, batch), "f32",
+            "mm3 forward", 2 * batch * N * 4 + 3 * N * b * 4, batch * 6.0 * N * b, batch * N, mk_mm3)
+        if batch <= 16384:
+            add("matmul3_backward_f32_b%d_batch_%d" % (b, batch), "gradients of the order-3 Monarch product N=%d, fp32, batch %d" % (N, batch), "f32",
+                "mm3 backward", 3 * batch * N * 4 + 6 * N * b * 4, batch * 16.0 * N * b, batch * N,
+                lambda torch, binding, workloads, rnd, f=mk_mm3: f(torch, binding, workloads, rnd, backward=True))
+
+    for rows, factors in ((6144, (64, 32)), (1536, (128, 128))):
+        N = factors[0] * factors[1]
+        for inverse in (False, True):
+            def mk_fft(torch, binding, workloads, rnd, rows=rows, factors=factors, N=N, inverse=inverse):
+                def one():
+                    if inverse:
+                        X = torch.randn((rows, N, 2), dtype=torch.float32, device="cuda")
+                        x = torch.empty((rows, N), dtype=torch.bfloat16, device="cuda")
+                        return lambda: binding.monarch_ifft(X, factors, True, dtype=torch.bfloat16, out=x)
+                    x = rnd(rows, N, dt=torch.bfloat16)
+                    X = torch.empty((rows, N, 2), dtype=torch.float32, device="cuda")
+                    return lambda: binding.monarch_fft(x, factors, True, out=X)
+                return one
+            add("%s_bf16_%dx%d" % ("ifft" if inverse else "fft", rows, N), "Monarch %s, %d real bf16 rows of %d = %dx%d, fp32 spectrum" % (
+                "inverse DFT" if inverse else "DFT", rows, N, factors[0], factors[1]), "bf16", "fft2_lds_kernel", rows * N * 10, 0.0, rows * N, mk_fft)
+    return cases
+
+
 def all_cases():
     return [
         ConvCase("c2_conv_bf16", "c2_conv", True, "conv2048_bf16_kernel", "hbm"),
@@ -331,6 +502,32 @@ def copy_calibration(mib):
     print(json.dumps({"copy_calibration_mib": mib, "copies": 8}))
 
 
+def summarize_profile(directory, kernel_filter):
+    """Prints what the text files under profiles/ quote from a rocprofv3 output folder: per kernel whose name
+    contains `kernel_filter`, the median and mean per dispatch of every collected counter
+    (*_counter_collection.csv) and the rows of the kernel statistics (*_kernel_stats.csv)."""
+    import collections
+    import csv
+    import glob
+    for path in sorted(glob.glob(os.path.join(directory, "**", "*_counter_collection.csv"), recursive=True)):
+        acc = collections.defaultdict(lambda: collections.defaultdict(list))
+        with open(path, newline="") as f:
+            for row in csv.DictReader(f):
+                if kernel_filter in row["Kernel_Name"]:
+                    acc[row["Kernel_Name"]][row["Counter_Name"]].append(float(row["Counter_Value"]))
+        for name, counters in acc.items():
+            print("%s\n  %s" % (path, name[:120]))
+            for cname, v in sorted(counters.items()):
+                v.sort()
+                print("    %-32s dispatches %5d  median %16.1f  mean %16.1f" % (cname, len(v), v[len(v) // 2], sum(v) / len(v)))
+    for path in sorted(glob.glob(os.path.join(directory, "**", "*_kernel_stats.csv"), recursive=True)):
+        with open(path, newline="") as f:
+            for row in csv.DictReader(f):
+                if kernel_filter in row["Name"]:
+                    print("%s\n  %s\n    calls %s  total ns %s  average ns %s  min %s  max %s" % (
+                        path, row["Name"][:120], row["Calls"], row["TotalDurationNs"], row["AverageNs"], row["MinNs"], row["MaxNs"]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -340,7 +537,12 @@ def main():
     ap.add_argument("--no-extra-configs", action="store_true", help="headline only")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle legs (parity samples and the oracle timing)")
     ap.add_argument("--copy-calibration", type=int, metavar="MIB", help="only run plain copies of this size (counter calibration)")
+    ap.add_argument("--summarize-profile", metavar="DIR", help="only print counter / kernel-trace summaries of a rocprofv3 output folder")
+    ap.add_argument("--kernel", default="monarch", help="with --summarize-profile: substring a kernel name must contain")
     args = ap.parse_args()
+    if args.summarize_profile:
+        summarize_profile(args.summarize_profile, args.kernel)
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (rows are independent, so more GPUs "
               "would just split the batch); run with --gpus 1", file=sys.stderr)
@@ -361,13 +563,15 @@ def main():
         import oracle
 
     cases = {c.name: c for c in all_cases()}
+    default_names = list(cases)
+    cases.update({c.name: c for c in widening_cases()})
     if args.config:
         unknown = [n for n in args.config if n not in cases]
         if unknown:
             sys.exit("bench.py: unknown case(s) %s; known: %s" % (unknown, ", ".join(cases)))
         order = args.config
     else:
-        order = [HEADLINE] + ([] if args.no_extra_configs else [n for n in cases if n != HEADLINE])
+        order = [HEADLINE] + ([] if args.no_extra_configs else [n for n in default_names if n != HEADLINE])
 
     head_case = cases[order[0]]
     head = run_case(torch, np, binding, workloads, oracle, head_case, args.steps, args.warmup, oracle is not None)
@@ -429,6 +633,8 @@ def _steps_for(case):
         return 240
     if isinstance(case, ConvCase) and case.cfg_key == "c2_conv":
         return 100
+    if isinstance(case, RandomCase) and case.algorithmic_bytes() < 64e6:
+        return 200
     return 12
 
 
