@@ -30,10 +30,11 @@ static bool overlaps(const void *a, size_t na, const void *b, size_t nb)
     return a0 < b0 + nb && b0 < a0 + na;
 }
 
-static int check_dtype(monarch_dtype dt)
+// fp16 I/O: the hot-path entry points (matmul, fft / ifft, causal_conv, mlp) take it; the others do not.
+static int check_dtype(monarch_dtype dt, bool f16_ok = false)
 {
     if (dt == MONARCH_F32 || dt == MONARCH_BF16) return MONARCH_OK;
-    if (dt == MONARCH_F16) return fail(MONARCH_EDTYPE, "fp16 I/O is reserved and not implemented");
+    if (dt == MONARCH_F16) return f16_ok ? MONARCH_OK : fail(MONARCH_EDTYPE, "this entry point does not take fp16 tensors");
     return fail(MONARCH_EDTYPE, "unknown element type %d", (int)dt);
 }
 
@@ -118,7 +119,7 @@ int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t
 {
     (void)ws; (void)ws_bytes;
     clear_error();
-    int rc = check_dtype(dt);
+    int rc = check_dtype(dt, true);
     if (rc) return rc;
     if (batch < 0) return fail(MONARCH_ESHAPE, "negative batch");
     if (nbR < 1 || r_out < 1 || r_in < 1 || nbL < 1 || l_out < 1 || l_in < 1)
@@ -460,7 +461,7 @@ static int fft_common(const void *src, void *dst, int64_t rows, int N, const int
                       int is_real, int inverse, monarch_dtype dt, void *ws, size_t ws_bytes,
                       hipStream_t s)
 {
-    int rc = check_dtype(dt);
+    int rc = check_dtype(dt, true);
     if (rc) return rc;
     rc = check_factors(N, factors, nf);
     if (rc) return rc;
@@ -559,7 +560,7 @@ int monarch_ifft(const void *X, void *x, int64_t rows, int N, const int *factors
 static int conv_check(int B, int H, int n, int klen, int nfft, const int *factors, int nf, int causal,
                       monarch_dtype dt)
 {
-    int rc = check_dtype(dt);
+    int rc = check_dtype(dt, true);
     if (rc) return rc;
     rc = check_factors(nfft, factors, nf);
     if (rc) return rc;
@@ -830,7 +831,7 @@ static int conv_run(const void *u, const void *k, const void *g_in, const void *
     hipStream_t s = (hipStream_t)stream;
 
     const int fused = conv_fused_path(n, klen, factors, nf, dt);
-    if (fused == 1) return launch_conv_mfma_2048(u, k, g_in, g_out, y, B, H, n, klen, s);
+    if (fused == 1) return launch_conv_mfma_2048(u, k, g_in, g_out, y, B, H, n, klen, dt, s);
     if (fused == 2) return launch_conv_mfma_256(u, k, g_in, g_out, y, B, H, n, klen, s);
     if (fused == 3) return launch_conv_mfma_16k(u, k, g_in, g_out, y, B, H, n, klen, s);
 
@@ -967,7 +968,7 @@ int monarch_causal_conv_static(const void *u, const void *k, const void *g_in, c
 static int mlp_check(int64_t tokens, int d, int d_hidden, int nb, int order, int &mid1, int &mid2,
                      int act, monarch_dtype dt)
 {
-    int rc = check_dtype(dt);
+    int rc = check_dtype(dt, true);
     if (rc) return rc;
     if (tokens < 0) return fail(MONARCH_ESHAPE, "negative token count");
     if (d < 1 || d_hidden < 1 || nb < 1) return fail(MONARCH_ESHAPE, "d, d_hidden and nb must be >= 1");

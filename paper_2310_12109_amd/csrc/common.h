@@ -10,6 +10,7 @@
 namespace monarch {
 
 typedef __bf16 bf16_t;
+typedef _Float16 f16_t;
 
 // Thread-local message of the last failing call; returns `code` for tail calls.
 int fail(int code, const char *fmt, ...);
@@ -24,10 +25,12 @@ void clear_error();
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+__device__ __forceinline__ float to_f32(f16_t v) { return (float)v; }
 
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) { return (f16_t)v; }
 
 // exp(+2*pi*i*e/N) for 0 <= e < N.  sincospif reduces its argument exactly, and
 // 2e/N is exact in fp32 whenever N is a power of two (N <= 2^24).

@@ -1,4 +1,4 @@
-// Fused gated causal Monarch-FFT convolution, nfft = 2048 = 64 x 32, bf16 I/O, fp32 accumulate.
+// Fused gated causal Monarch-FFT convolution, nfft = 2048 = 64 x 32, bf16 or fp16 I/O, fp32 accumulate.
 //
 // A workgroup (4 waves) takes a work item (channel h, chunk of batch pairs): it first turns k[h]
 // into its spectrum k_f (one quarter per wave, kept in LDS), then every wave takes PAIRS of batch
@@ -11,8 +11,8 @@
 //   * the row is the N1 x N2 = 64 x 32 matrix x[c*32 + a]; the Monarch factors are
 //     R = I (x) F_64 (contract c), twiddle w_2048^(i a), L = F_32 blocks (contract a);
 //     the zero-padded half (c >= 32) is never multiplied and only outputs c < 32 are formed;
-//   * every factor is a bf16 MFMA (16x16x32) with the constant DFT matrix as one operand and
-//     the previous stage's accumulators, re-rounded to bf16, as the other.  Two stacked
+//   * every factor is a 16-bit MFMA (16x16x32, bf16 or fp16) with the constant DFT matrix as one operand and
+//     the previous stage's accumulators, re-rounded to 16 bits, as the other.  Two stacked
 //     accumulator tiles (32 rows in registers, 16 columns on lanes) are a valid B operand
 //     (contract the rows, keep the columns on lanes) and equally a valid A operand (contract the
 //     rows, the lane index becomes the new row index), so no stage needs a transpose: the
@@ -29,7 +29,9 @@
 namespace monarch {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t op8;   // one MFMA operand: 8 packed 16-bit values of either type
 
 namespace c2048 {
 
@@ -56,6 +58,29 @@ using croots::bf16_bits;
 using croots::unit_root;
 constexpr int cslot(int kg, int j) { return 16 * (j >> 2) + 4 * kg + (j & 3); }
 
+// fp16 bits of a value of magnitude <= 1 (a cosine or sine): round to nearest even; the tables hold no value
+// between 0 and the smallest normal number (the smallest non-zero one is sin(2 pi / 2048)).
+constexpr uint32_t f16_bits(double v)
+{
+    if (v == 0.0) return 0u;
+    const uint32_t sign = v < 0 ? 0x8000u : 0u;
+    double a = v < 0 ? -v : v;
+    int e = 0;
+    while (a < 1.0) { a *= 2.0; --e; }
+    while (a >= 2.0) { a *= 0.5; ++e; }
+    // a in [1, 2): 10 fraction bits
+    double f = (a - 1.0) * 1024.0;
+    uint32_t m = (uint32_t)f;
+    const double rest = f - (double)m;
+    if (rest > 0.5 || (rest == 0.5 && (m & 1u))) ++m;
+    uint32_t ebits = (uint32_t)(e + 15);
+    if (m == 1024u) { m = 0u; ++ebits; }
+    return sign | (ebits << 10) | m;
+}
+template <typename E> constexpr uint32_t half_bits(double v);
+template <> constexpr uint32_t half_bits<bf16_t>(double v) { return bf16_bits(v); }
+template <> constexpr uint32_t half_bits<f16_t>(double v) { return f16_bits(v); }
+
 struct TwiddleTable { float v[N1][TW_LD][2]; };
 constexpr TwiddleTable make_twiddles()
 {
@@ -72,6 +97,7 @@ constexpr TwiddleTable make_twiddles()
 //   [2t], [2t+1]: real / imaginary part of F64[slot][16t + lane%16]  (= F64[16t + lane%16][slot])
 //   [4+2t], [5+2t]: real / imaginary part of F32[16t + lane%16][slot]
 struct OperandTable { uint32_t v[64][8][4]; };
+template <typename E>
 constexpr OperandTable make_operands()
 {
     OperandTable t{};
@@ -81,101 +107,106 @@ constexpr OperandTable make_operands()
                 const int row = 16 * tile + (lane & 15), s0 = cslot(lane >> 4, 2 * jj);
                 const CosSin f0 = unit_root(s0 * row, 64), f1 = unit_root((s0 + 1) * row, 64);
                 const CosSin g0 = unit_root(s0 * row, 32), g1 = unit_root((s0 + 1) * row, 32);
-                t.v[lane][2 * tile][jj] = bf16_bits(f0.c) | (bf16_bits(f1.c) << 16);
-                t.v[lane][2 * tile + 1][jj] = bf16_bits(f0.s) | (bf16_bits(f1.s) << 16);
-                t.v[lane][4 + 2 * tile][jj] = bf16_bits(g0.c) | (bf16_bits(g1.c) << 16);
-                t.v[lane][5 + 2 * tile][jj] = bf16_bits(g0.s) | (bf16_bits(g1.s) << 16);
+                t.v[lane][2 * tile][jj] = half_bits<E>(f0.c) | (half_bits<E>(f1.c) << 16);
+                t.v[lane][2 * tile + 1][jj] = half_bits<E>(f0.s) | (half_bits<E>(f1.s) << 16);
+                t.v[lane][4 + 2 * tile][jj] = half_bits<E>(g0.c) | (half_bits<E>(g1.c) << 16);
+                t.v[lane][5 + 2 * tile][jj] = half_bits<E>(g0.s) | (half_bits<E>(g1.s) << 16);
             }
     return t;
 }
 __device__ const TwiddleTable g_twiddles = make_twiddles();
-__device__ const OperandTable g_operands = make_operands();
+__device__ const OperandTable g_operands_bf16 = make_operands<bf16_t>();
+__device__ const OperandTable g_operands_f16 = make_operands<f16_t>();
+template <typename E> __device__ __forceinline__ const OperandTable &operands();
+template <> __device__ __forceinline__ const OperandTable &operands<bf16_t>() { return g_operands_bf16; }
+template <> __device__ __forceinline__ const OperandTable &operands<f16_t>() { return g_operands_f16; }
 
 union Pack8 {
-    bf16x8 v;
+    op8 v;
     uint32_t d[4];
 };
 
-struct COp { bf16x8 r, i, ni; }; // constant complex operand: real part, imaginary part and its negative
+struct COp { op8 r, i, ni; };    // constant complex operand: real part, imaginary part and its negative
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+// The element type E (bf16_t or f16_t) only shows in four places: rounding a pair of floats to a packed pair,
+// widening the halves of a packed pair, the matrix instruction, and the two-term dot product of the gating.
+template <typename E> __device__ __forceinline__ uint32_t pack16(float lo, float hi)
 {
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-    bf16x2 p = {(__bf16)lo, (__bf16)hi};
+    typedef __attribute__((ext_vector_type(2))) E pair_t;
+    pair_t p = {(E)lo, (E)hi};
     return __builtin_bit_cast(uint32_t, p);
 }
-
-__device__ __forceinline__ float bf16_lo(uint32_t d) { return __uint_as_float(d << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t d) { return __uint_as_float(d & 0xffff0000u); }
+template <typename E> __device__ __forceinline__ float lo32(uint32_t d);
+template <typename E> __device__ __forceinline__ float hi32(uint32_t d);
+template <> __device__ __forceinline__ float lo32<bf16_t>(uint32_t d) { return __uint_as_float(d << 16); }
+template <> __device__ __forceinline__ float hi32<bf16_t>(uint32_t d) { return __uint_as_float(d & 0xffff0000u); }
+template <> __device__ __forceinline__ float lo32<f16_t>(uint32_t d)
+{
+    typedef __attribute__((ext_vector_type(2))) f16_t pair_t;
+    return (float)__builtin_bit_cast(pair_t, d)[0];
+}
+template <> __device__ __forceinline__ float hi32<f16_t>(uint32_t d)
+{
+    typedef __attribute__((ext_vector_type(2))) f16_t pair_t;
+    return (float)__builtin_bit_cast(pair_t, d)[1];
+}
 
 // Contraction index carried by operand slot j of lane group kg when the operand is made from two
 // stacked 16x16 accumulator tiles: tile j/4, register j%4 holds row 16*(j/4) + 4*kg + j%4.
 __device__ __forceinline__ int slot_index(int kg, int j) { return 16 * (j >> 2) + 4 * kg + (j & 3); }
 
-__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
+template <typename E> __device__ __forceinline__ f32x4 mfma(op8 a, op8 b, f32x4 c);
+template <> __device__ __forceinline__ f32x4 mfma<bf16_t>(op8 a, op8 b, f32x4 c)
 {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4 mfma<f16_t>(op8 a, op8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// Sign flips on packed bf16 operands (bit 15 of each half is the sign).
-__device__ __forceinline__ bf16x8 flip(bf16x8 v, uint32_t mask)
-{
-    Pack8 p;
-    p.v = v;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) p.d[jj] ^= mask;
-    return p.v;
-}
-__device__ __forceinline__ bf16x8 neg_all(bf16x8 v) { return flip(v, 0x80008000u); }
+// Sign flips on packed 16-bit operands (bit 15 of each half is the sign in both types).
+__device__ __forceinline__ op8 flip(op8 v, uint32_t mask) { return v ^ mask; }
+__device__ __forceinline__ op8 neg_all(op8 v) { return flip(v, 0x80008000u); }
 
-// Two stacked accumulator tiles -> one bf16 operand (slot 4*t + r <- tile t, register r).
-__device__ __forceinline__ bf16x8 pack_tiles(const f32x4 &t0, const f32x4 &t1)
+// Two stacked accumulator tiles -> one 16-bit operand (slot 4*t + r <- tile t, register r).
+template <typename E> __device__ __forceinline__ op8 pack_tiles(const f32x4 &t0, const f32x4 &t1)
 {
-    Pack8 p;
-    p.d[0] = pack_bf16(t0[0], t0[1]);
-    p.d[1] = pack_bf16(t0[2], t0[3]);
-    p.d[2] = pack_bf16(t1[0], t1[1]);
-    p.d[3] = pack_bf16(t1[2], t1[3]);
-    return p.v;
+    return op8{pack16<E>(t0[0], t0[1]), pack16<E>(t0[2], t0[3]), pack16<E>(t1[0], t1[1]), pack16<E>(t1[2], t1[3])};
 }
 
 // 8 consecutive bf16 of a row (chunk ch), zero past the end of the row.  FULL: the row has all
 // 128 chunks, so the load is unconditional (no exec-mask branch per load).
-template <bool FULL>
-__device__ __forceinline__ uint4 load_chunk(const bf16_t *row, int ch, int len)
+template <bool FULL, typename E>
+__device__ __forceinline__ uint4 load_chunk(const E *row, int ch, int len)
 {
     if (FULL || ch * 8 < len) return *reinterpret_cast<const uint4 *>(row + ch * 8);
     return make_uint4(0u, 0u, 0u, 0u);
-}
-
-__device__ __forceinline__ uint32_t mul_pack(uint32_t a, uint32_t b)
-{
-    return pack_bf16(bf16_lo(a) * bf16_lo(b), bf16_hi(a) * bf16_hi(b));
 }
 
 // Raw rows as loaded: chunks lane and lane+64 of two rows (the second may be absent).
 struct RowLoad { uint4 a[2], b[2]; };
 
 // Both pointers must be valid rows (no null checks: the loads stay free of branches).
-template <bool FULL>
-__device__ __forceinline__ void load_rows(RowLoad &ld, int lane, const bf16_t *r0, const bf16_t *r1, int len)
+template <bool FULL, typename E>
+__device__ __forceinline__ void load_rows(RowLoad &ld, int lane, const E *r0, const E *r1, int len)
 {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int ch = lane + 64 * half;
-        ld.a[half] = load_chunk<FULL>(r0, ch, len);
-        ld.b[half] = load_chunk<FULL>(r1, ch, len);
+        ld.a[half] = load_chunk<FULL, E>(r0, ch, len);
+        ld.b[half] = load_chunk<FULL, E>(r1, ch, len);
     }
 }
 
 // One row only; the second row of the pair is zero.
-template <bool FULL>
-__device__ __forceinline__ void load_row(RowLoad &ld, int lane, const bf16_t *r0, int len)
+template <bool FULL, typename E>
+__device__ __forceinline__ void load_row(RowLoad &ld, int lane, const E *r0, int len)
 {
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        ld.a[half] = load_chunk<FULL>(r0, lane + 64 * half, len);
+        ld.a[half] = load_chunk<FULL, E>(r0, lane + 64 * half, len);
         ld.b[half] = zero;
     }
 }
@@ -192,31 +223,54 @@ __device__ __forceinline__ void interleave_store(uint32_t *dst, const uint32_t (
     reinterpret_cast<uint4 *>(dst)[1] = o1;
 }
 
+// x.lo * g.lo + x.hi * g.hi of two packed 16-bit pairs, in fp32 (exact when one of the products is zero).
+template <typename E> __device__ __forceinline__ float dot2(uint32_t x, uint32_t g);
+template <> __device__ __forceinline__ float dot2<bf16_t>(uint32_t x, uint32_t g)
+{
+    float d;
+    asm("v_dot2_f32_bf16 %0, %1, %2, 0" : "=v"(d) : "v"(x), "v"(g));
+    return d;
+}
+template <> __device__ __forceinline__ float dot2<f16_t>(uint32_t x, uint32_t g)
+{
+    float d;
+    asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(d) : "v"(x), "v"(g));
+    return d;
+}
+
 // Writes two rows into the wave's staging tile as (row a | row b << 16) words at [c*ST_LD + a'],
-// multiplied elementwise by the gate rows when `gated`.
+// multiplied elementwise by the gate rows when `gated`.  Gated: each product of two 16-bit values is one
+// two-term dot product against the gate word with its other half masked away (exact in fp32), and the
+// rounding of the products of the two rows to 16 bits is the instruction that interleaves them.
+template <typename E>
 __device__ __forceinline__ void stage_rows(uint32_t *stage, int lane, const RowLoad &x, const RowLoad &gt, bool gated)
 {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int ch = lane + 64 * half;
-        uint32_t r[4] = {x.a[half].x, x.a[half].y, x.a[half].z, x.a[half].w};
-        uint32_t m[4] = {x.b[half].x, x.b[half].y, x.b[half].z, x.b[half].w};
+        const uint32_t r[4] = {x.a[half].x, x.a[half].y, x.a[half].z, x.a[half].w};
+        const uint32_t m[4] = {x.b[half].x, x.b[half].y, x.b[half].z, x.b[half].w};
+        uint32_t *dst = stage + (ch >> 2) * ST_LD + (ch & 3) * 8;
         if (gated) {
             const uint32_t ga[4] = {gt.a[half].x, gt.a[half].y, gt.a[half].z, gt.a[half].w};
             const uint32_t gb[4] = {gt.b[half].x, gt.b[half].y, gt.b[half].z, gt.b[half].w};
+            uint32_t o[8];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                r[q] = mul_pack(r[q], ga[q]);
-                m[q] = mul_pack(m[q], gb[q]);
+                o[2 * q] = pack16<E>(dot2<E>(r[q], ga[q] & 0xffffu), dot2<E>(m[q], gb[q] & 0xffffu));
+                o[2 * q + 1] = pack16<E>(dot2<E>(r[q], ga[q] & 0xffff0000u), dot2<E>(m[q], gb[q] & 0xffff0000u));
             }
+            reinterpret_cast<uint4 *>(dst)[0] = make_uint4(o[0], o[1], o[2], o[3]);
+            reinterpret_cast<uint4 *>(dst)[1] = make_uint4(o[4], o[5], o[6], o[7]);
+        } else {
+            interleave_store(dst, r, m);
         }
-        interleave_store(stage + (ch >> 2) * ST_LD + (ch & 3) * 8, r, m);
     }
 }
 
 // A operands of the first factor: for row tile m, lane (a = 16m + lane%16, kg) holds x[c][a]
 // for the 8 contraction indices c = slot_index(kg, j).
-__device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int l16, int kg, bf16x8 (&xr)[2], bf16x8 (&xi)[2])
+__device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int l16, int kg, op8 (&xr)[2], op8 (&xi)[2])
 {
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
@@ -239,19 +293,19 @@ __device__ __forceinline__ void read_stage_operands(const uint32_t *stage, int l
 // F holds F64[c][16*(CH%2) + lane%16]; columns 32..63 differ from it by (-1)^c, which the caller
 // has applied to the data operands (odd slots negated) for CH >= 2.
 // Result: rows k = 16m + 4kg + r in registers (z2[m][r]), column i on the lane.
-template <int CH, bool HAS_IM>
-__device__ __forceinline__ void forward_chunk(const Smem &sm, int l16, int kg, const bf16x8 (&xr)[2],
-                                              const bf16x8 (&xi)[2], const COp &F, const COp (&G)[2],
+template <typename E, int CH, bool HAS_IM>
+__device__ __forceinline__ void forward_chunk(const Smem &sm, int l16, int kg, const op8 (&xr)[2],
+                                              const op8 (&xi)[2], const COp &F, const COp (&G)[2],
                                               f32x4 (&z2r)[2], f32x4 (&z2i)[2])
 {
     f32x4 zr[2], zi[2];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
-        zr[m] = mfma(xr[m], F.r, (f32x4){0, 0, 0, 0});
-        zi[m] = mfma(xr[m], F.i, (f32x4){0, 0, 0, 0});
+        zr[m] = mfma<E>(xr[m], F.r, (f32x4){0, 0, 0, 0});
+        zi[m] = mfma<E>(xr[m], F.i, (f32x4){0, 0, 0, 0});
         if (HAS_IM) {
-            zr[m] = mfma(xi[m], F.ni, zr[m]);
-            zi[m] = mfma(xi[m], F.r, zi[m]);
+            zr[m] = mfma<E>(xi[m], F.ni, zr[m]);
+            zi[m] = mfma<E>(xi[m], F.r, zi[m]);
         }
     }
     // twiddle: rows a = 16m + 4kg + r in registers, column i on the lane
@@ -268,19 +322,19 @@ __device__ __forceinline__ void forward_chunk(const Smem &sm, int l16, int kg, c
             zi[m][r] = a * ti[r] + b * tr[r];
         }
     }
-    const bf16x8 br = pack_tiles(zr[0], zr[1]), bi = pack_tiles(zi[0], zi[1]);
+    const op8 br = pack_tiles<E>(zr[0], zr[1]), bi = pack_tiles<E>(zi[0], zi[1]);
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
-        z2r[m] = mfma(G[m].r, br, (f32x4){0, 0, 0, 0});
-        z2i[m] = mfma(G[m].i, br, (f32x4){0, 0, 0, 0});
-        z2r[m] = mfma(G[m].ni, bi, z2r[m]);
-        z2i[m] = mfma(G[m].r, bi, z2i[m]);
+        z2r[m] = mfma<E>(G[m].r, br, (f32x4){0, 0, 0, 0});
+        z2i[m] = mfma<E>(G[m].i, br, (f32x4){0, 0, 0, 0});
+        z2r[m] = mfma<E>(G[m].ni, bi, z2r[m]);
+        z2i[m] = mfma<E>(G[m].r, bi, z2i[m]);
     }
 }
 
 // Spectrum product, third factor and conjugate twiddle for columns i = 16*CH + ...; writes this
 // chunk's 16 contraction rows into the last factor's B operands (half of each operand).
-template <int CH>
+template <typename E, int CH>
 __device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16, int kg, f32x4 (&zr)[2],
                                               f32x4 (&zi)[2], const COp (&G)[2], Pack8 (&wr_op)[2], Pack8 (&wi_op)[2])
 {
@@ -297,13 +351,13 @@ __device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16,
         }
     }
     // third factor: W[i,a] = sum_k Y[i,k] conj(F32)[k,a]; Y's lane index i becomes the row index
-    const bf16x8 ar = pack_tiles(zr[0], zr[1]), ai = pack_tiles(zi[0], zi[1]);
+    const op8 ar = pack_tiles<E>(zr[0], zr[1]), ai = pack_tiles<E>(zi[0], zi[1]);
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-        f32x4 wr = mfma(ar, G[nt].r, (f32x4){0, 0, 0, 0});
-        f32x4 wi = mfma(ai, G[nt].r, (f32x4){0, 0, 0, 0});
-        wr = mfma(ai, G[nt].i, wr);
-        wi = mfma(ar, G[nt].ni, wi);
+        f32x4 wr = mfma<E>(ar, G[nt].r, (f32x4){0, 0, 0, 0});
+        f32x4 wi = mfma<E>(ai, G[nt].r, (f32x4){0, 0, 0, 0});
+        wr = mfma<E>(ai, G[nt].i, wr);
+        wi = mfma<E>(ar, G[nt].ni, wi);
         // conjugate twiddle: rows i = 16*CH + 4kg + r in registers, column a = 16nt + lane%16
         const float2 *tcol = &sm.tw[16 * CH + 4 * kg][16 * nt + l16];
 #pragma unroll
@@ -314,20 +368,20 @@ __device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16,
             wi[r] = b * w.x - a * w.y;
         }
         // contraction rows 32*(CH/2) + 16*(CH%2) + 4kg + r  ->  slots 4*(CH%2) + r of kstep CH/2
-        wr_op[nt].d[2 * (CH & 1)] = pack_bf16(wr[0], wr[1]);
-        wr_op[nt].d[2 * (CH & 1) + 1] = pack_bf16(wr[2], wr[3]);
-        wi_op[nt].d[2 * (CH & 1)] = pack_bf16(wi[0], wi[1]);
-        wi_op[nt].d[2 * (CH & 1) + 1] = pack_bf16(wi[2], wi[3]);
+        wr_op[nt].d[2 * (CH & 1)] = pack16<E>(wr[0], wr[1]);
+        wr_op[nt].d[2 * (CH & 1) + 1] = pack16<E>(wr[2], wr[3]);
+        wi_op[nt].d[2 * (CH & 1)] = pack16<E>(wi[0], wi[1]);
+        wi_op[nt].d[2 * (CH & 1) + 1] = pack16<E>(wi[2], wi[3]);
     }
 }
 
 // FULL: n == klen == 1024, every row load is unconditional.  GIN / GOUT: the gates are present.
 // Keeping the loads free of branches lets the compiler wait for exactly the load it needs
 // (k first, then u and g_in, g_out last) instead of draining all of them at once.
-template <bool FULL, bool GIN, bool GOUT>
-__global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
-    const bf16_t *__restrict__ u, const bf16_t *__restrict__ k, const bf16_t *__restrict__ g_in,
-    const bf16_t *__restrict__ g_out, bf16_t *__restrict__ y, int B, int H, int n, int klen)
+template <typename E, bool FULL, bool GIN, bool GOUT>
+__global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
+    const E *__restrict__ u, const E *__restrict__ k, const E *__restrict__ g_in,
+    const E *__restrict__ g_out, E *__restrict__ y, int B, int H, int n, int klen)
 {
     __shared__ Smem sm;
     const int tid = threadIdx.x;
@@ -350,20 +404,20 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     const uint4 tw4 = tw_src[1024 + (tid & 63)];   // every wave fetches the same tail; wave 0 stores it
     COp F[2], G[2];
     {
-        const uint4 *ops = reinterpret_cast<const uint4 *>(g_operands.v[lane]);
+        const uint4 *ops = reinterpret_cast<const uint4 *>(operands<E>().v[lane]);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            F[t].r = __builtin_bit_cast(bf16x8, ops[2 * t]);
-            F[t].i = __builtin_bit_cast(bf16x8, ops[2 * t + 1]);
-            G[t].r = __builtin_bit_cast(bf16x8, ops[4 + 2 * t]);
-            G[t].i = __builtin_bit_cast(bf16x8, ops[5 + 2 * t]);
+            F[t].r = __builtin_bit_cast(op8, ops[2 * t]);
+            F[t].i = __builtin_bit_cast(op8, ops[2 * t + 1]);
+            G[t].r = __builtin_bit_cast(op8, ops[4 + 2 * t]);
+            G[t].i = __builtin_bit_cast(op8, ops[5 + 2 * t]);
         }
     }
     RowLoad ldk, ldx, ldg, ldo;
-    load_row<FULL>(ldk, lane, k + (size_t)h * klen, klen);
-    load_rows<FULL>(ldx, lane, u + row0, u + row1, n);
+    load_row<FULL, E>(ldk, lane, k + (size_t)h * klen, klen);
+    load_rows<FULL, E>(ldx, lane, u + row0, u + row1, n);
 
-    if (GIN) load_rows<FULL>(ldg, lane, g_in + row0, g_in + row1, n);
+    if (GIN) load_rows<FULL, E>(ldg, lane, g_in + row0, g_in + row1, n);
     {
         uint4 *dst = reinterpret_cast<uint4 *>(&sm.tw[0][0]);
         dst[tid] = tw0;
@@ -382,9 +436,9 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
 
     // spectrum of the kernel: wave w transforms spectrum columns 16w .. 16w+15
     {
-        stage_rows(stage, lane, ldk, ldk, false);
+        stage_rows<E>(stage, lane, ldk, ldk, false);
         __builtin_amdgcn_wave_barrier();
-        bf16x8 xr[2], xi[2];
+        op8 xr[2], xi[2];
         read_stage_operands(stage, l16, kg, xr, xi);
         if (wave >= 2) {   // spectrum columns 32..63: (-1)^c on the data (odd slots)
             xr[0] = flip(xr[0], 0x80000000u);
@@ -392,10 +446,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
         }
         f32x4 zr[2], zi[2];
         switch (wave) {
-        case 0: forward_chunk<0, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
-        case 1: forward_chunk<1, false>(sm, l16, kg, xr, xi, F[1], G, zr, zi); break;
-        case 2: forward_chunk<2, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
-        default: forward_chunk<3, false>(sm, l16, kg, xr, xi, F[1], G, zr, zi); break;
+        case 0: forward_chunk<E, 0, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
+        case 1: forward_chunk<E, 1, false>(sm, l16, kg, xr, xi, F[1], G, zr, zi); break;
+        case 2: forward_chunk<E, 2, false>(sm, l16, kg, xr, xi, F[0], G, zr, zi); break;
+        default: forward_chunk<E, 3, false>(sm, l16, kg, xr, xi, F[1], G, zr, zi); break;
         }
         const float inv = 1.0f / (float)NFFT;
 #pragma unroll
@@ -404,7 +458,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
             sm.kf_im[wave][m][lane] = make_float4(zi[m][0] * inv, zi[m][1] * inv, zi[m][2] * inv, zi[m][3] * inv);
         }
     }
-    if (GOUT) load_rows<FULL>(ldo, lane, g_out + row0, g_out + row1, n);
+    if (GOUT) load_rows<FULL, E>(ldo, lane, g_out + row0, g_out + row1, n);
     __syncthreads();   // k_f complete
     if (!active) return;
     if (!two) {   // single row: its partner's data was only a placeholder
@@ -415,27 +469,27 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
     {
         {
             __builtin_amdgcn_wave_barrier();
-            stage_rows(stage, lane, ldx, ldg, GIN);
+            stage_rows<E>(stage, lane, ldx, ldg, GIN);
             __builtin_amdgcn_wave_barrier();
-            bf16x8 xr[2], xi[2];
+            op8 xr[2], xi[2];
             read_stage_operands(stage, l16, kg, xr, xi);
             __builtin_amdgcn_wave_barrier();
             // the tile is free again: park the output gates in it, same word layout
-            if (GOUT) stage_rows(stage, lane, ldo, ldo, false);
+            if (GOUT) stage_rows<E>(stage, lane, ldo, ldo, false);
 
             // B operands of the last factor: [kstep = contraction rows 32ks..32ks+31][column tile nt]
             Pack8 wr_op[2][2], wi_op[2][2];
             __builtin_amdgcn_sched_barrier(0);
             {
                 f32x4 zr[2], zi[2];
-                forward_chunk<0, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
-                inverse_chunk<0>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
+                forward_chunk<E, 0, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
+                inverse_chunk<E, 0>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
             }
             __builtin_amdgcn_sched_barrier(0);
             {
                 f32x4 zr[2], zi[2];
-                forward_chunk<1, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
-                inverse_chunk<1>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
+                forward_chunk<E, 1, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
+                inverse_chunk<E, 1>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
             }
             // spectrum columns 32..63 see F64[c][32 + i'] = (-1)^c F64[c][i']: negate the odd slots of the data
 #pragma unroll
@@ -446,14 +500,14 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
             __builtin_amdgcn_sched_barrier(0);
             {
                 f32x4 zr[2], zi[2];
-                forward_chunk<2, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
-                inverse_chunk<2>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
+                forward_chunk<E, 2, true>(sm, l16, kg, xr, xi, F[0], G, zr, zi);
+                inverse_chunk<E, 2>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
             }
             __builtin_amdgcn_sched_barrier(0);
             {
                 f32x4 zr[2], zi[2];
-                forward_chunk<3, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
-                inverse_chunk<3>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
+                forward_chunk<E, 3, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
+                inverse_chunk<E, 3>(sm, lane, l16, kg, zr, zi, G, wr_op[1], wi_op[1]);
             }
             __builtin_amdgcn_sched_barrier(0);
             // last factor: y[c,a] = sum_i conj(F64)[c,i] W[i,a], c < 32 only (truncation to n).
@@ -461,17 +515,17 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
             f32x4 yr[2][2], yi[2][2];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-                const bf16x8 hr = flip(F[mt].r, lane_sign), hi = flip(F[mt].i, lane_sign), nhi = flip(F[mt].ni, lane_sign);
+                const op8 hr = flip(F[mt].r, lane_sign), hi = flip(F[mt].i, lane_sign), nhi = flip(F[mt].ni, lane_sign);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
-                    f32x4 ar = mfma(F[mt].r, wr_op[0][nt].v, (f32x4){0, 0, 0, 0});
-                    f32x4 ai = mfma(F[mt].r, wi_op[0][nt].v, (f32x4){0, 0, 0, 0});
-                    ar = mfma(F[mt].i, wi_op[0][nt].v, ar);
-                    ai = mfma(F[mt].ni, wr_op[0][nt].v, ai);
-                    ar = mfma(hr, wr_op[1][nt].v, ar);
-                    ai = mfma(hr, wi_op[1][nt].v, ai);
-                    ar = mfma(hi, wi_op[1][nt].v, ar);
-                    ai = mfma(nhi, wr_op[1][nt].v, ai);
+                    f32x4 ar = mfma<E>(F[mt].r, wr_op[0][nt].v, (f32x4){0, 0, 0, 0});
+                    f32x4 ai = mfma<E>(F[mt].r, wi_op[0][nt].v, (f32x4){0, 0, 0, 0});
+                    ar = mfma<E>(F[mt].i, wi_op[0][nt].v, ar);
+                    ai = mfma<E>(F[mt].ni, wr_op[0][nt].v, ai);
+                    ar = mfma<E>(hr, wr_op[1][nt].v, ar);
+                    ai = mfma<E>(hr, wi_op[1][nt].v, ai);
+                    ar = mfma<E>(hi, wi_op[1][nt].v, ar);
+                    ai = mfma<E>(nhi, wr_op[1][nt].v, ai);
                     yr[mt][nt] = ar;
                     yi[mt][nt] = ai;
                 }
@@ -497,10 +551,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
                     for (int r = 0; r < 4; ++r) {
                         float v0 = yr[mt][nt][r], v1 = yi[mt][nt][r];
                         if (GOUT) {
-                            v0 *= bf16_lo(gw[mt][nt][r]);
-                            v1 *= bf16_hi(gw[mt][nt][r]);
+                            v0 *= lo32<E>(gw[mt][nt][r]);
+                            v1 *= hi32<E>(gw[mt][nt][r]);
                         }
-                        stage[(16 * mt + 4 * kg + r) * ST_LD + 16 * nt + l16] = pack_bf16(v0, v1);
+                        stage[(16 * mt + 4 * kg + r) * ST_LD + 16 * nt + l16] = pack16<E>(v0, v1);
                     }
             __builtin_amdgcn_wave_barrier();
             // coalesced stores: lane takes chunks lane and lane+64 of both rows
@@ -528,12 +582,13 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_bf16_kernel(
 
 bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt)
 {
-    return dt == MONARCH_BF16 && nf == 2 && factors[0] == 64 && factors[1] == 32 && n <= 1024 && klen <= 1024 &&
-           n % 8 == 0 && klen % 8 == 0;
+    return (dt == MONARCH_BF16 || dt == MONARCH_F16) && nf == 2 && factors[0] == 64 && factors[1] == 32 && n <= 1024 &&
+           klen <= 1024 && n % 8 == 0 && klen % 8 == 0;
 }
 
-int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
-                          int B, int H, int n, int klen, hipStream_t s)
+template <typename E>
+static int launch_typed(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                        int B, int H, int n, int klen, hipStream_t s)
 {
     // One workgroup per (channel, group of 4 batch pairs); with B <= 8 that is one per channel.
     const int64_t groups = ((B + 1) / 2 + 3) / 4;
@@ -541,9 +596,8 @@ int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const 
     if (grid > 0x7fffffffLL) return fail(MONARCH_ESHAPE, "B*H too large for one launch");
     const bool full = n == c2048::NHALF && klen == c2048::NHALF;
 #define MONARCH_LAUNCH_C2048(FULLV, GINV, GOUTV)                                                                  \
-    hipLaunchKernelGGL((c2048::conv2048_bf16_kernel<FULLV, GINV, GOUTV>), dim3((unsigned)grid), dim3(256), 0, s,  \
-                       (const bf16_t *)u, (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out,        \
-                       (bf16_t *)y, B, H, n, klen)
+    hipLaunchKernelGGL((c2048::conv2048_kernel<E, FULLV, GINV, GOUTV>), dim3((unsigned)grid), dim3(256), 0, s,    \
+                       (const E *)u, (const E *)k, (const E *)g_in, (const E *)g_out, (E *)y, B, H, n, klen)
     switch ((full ? 4 : 0) | (g_in ? 2 : 0) | (g_out ? 1 : 0)) {
     case 7: MONARCH_LAUNCH_C2048(true, true, true); break;
     case 6: MONARCH_LAUNCH_C2048(true, true, false); break;
@@ -557,6 +611,13 @@ int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const 
 #undef MONARCH_LAUNCH_C2048
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
+}
+
+int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                          int B, int H, int n, int klen, monarch_dtype dt, hipStream_t s)
+{
+    if (dt == MONARCH_F16) return launch_typed<f16_t>(u, k, g_in, g_out, y, B, H, n, klen, s);
+    return launch_typed<bf16_t>(u, k, g_in, g_out, y, B, H, n, klen, s);
 }
 
 }  // namespace monarch

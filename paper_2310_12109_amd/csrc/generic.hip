@@ -147,6 +147,12 @@ int launch_matmul_generic(const void *x, const void *R, const void *L, const voi
         return launch_matmul_typed<bf16_t, bf16_t, float>(MONARCH_ARGS);
     if (dt_in == MONARCH_F32 && dt_w == MONARCH_BF16 && dt_out == MONARCH_BF16)
         return launch_matmul_typed<float, bf16_t, bf16_t>(MONARCH_ARGS);
+    if (dt_in == MONARCH_F16 && dt_w == MONARCH_F16 && dt_out == MONARCH_F16)
+        return launch_matmul_typed<f16_t, f16_t, f16_t>(MONARCH_ARGS);
+    if (dt_in == MONARCH_F16 && dt_w == MONARCH_F16 && dt_out == MONARCH_F32)
+        return launch_matmul_typed<f16_t, f16_t, float>(MONARCH_ARGS);
+    if (dt_in == MONARCH_F32 && dt_w == MONARCH_F16 && dt_out == MONARCH_F16)
+        return launch_matmul_typed<float, f16_t, f16_t>(MONARCH_ARGS);
 #undef MONARCH_ARGS
     return fail(MONARCH_EDTYPE, "unsupported element type combination");
 }
@@ -262,6 +268,8 @@ int launch_fft_pass(const FftPass &p, hipStream_t s)
     if (grid > 1 << 20) grid = 1 << 20;
     if (p.dt == MONARCH_F32)
         hipLaunchKernelGGL(fft_pass_kernel<float>, dim3((unsigned)grid), dim3(256), 0, s, p);
+    else if (p.dt == MONARCH_F16)
+        hipLaunchKernelGGL(fft_pass_kernel<f16_t>, dim3((unsigned)grid), dim3(256), 0, s, p);
     else
         hipLaunchKernelGGL(fft_pass_kernel<bf16_t>, dim3((unsigned)grid), dim3(256), 0, s, p);
     MONARCH_HIP_CHECK(hipGetLastError());

@@ -125,10 +125,10 @@ int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
 
 // ---- fused bf16 MFMA kernels ---------------------------------------------------------------
 
-// nfft = 2048 = 64 x 32, n <= 1024, klen <= 1024 (both multiples of 8), bf16 I/O.
+// nfft = 2048 = 64 x 32, n <= 1024, klen <= 1024 (both multiples of 8), bf16 or fp16 I/O.
 bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
-                          int B, int H, int n, int klen, hipStream_t s);
+                          int B, int H, int n, int klen, monarch_dtype dt, hipStream_t s);
 
 // nfft = 16384 = 128 x 128, n <= 8192, klen <= 8192 (both multiples of 8), bf16 I/O; no workspace.
 bool conv_mfma_16k_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);

@@ -64,7 +64,7 @@ def test_matmul_rejects_bad_arguments(lib):
     assert f(None, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == EINVAL
     assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 8, 16, 16, 0, None, 0, None) == ESHAPE   # d_mid mismatch
     assert f(FAKE, FAKE, FAKE, FAKE, 4, 0, 16, 16, 16, 16, 16, 0, None, 0, None) == ESHAPE
-    assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 2, None, 0, None) == EDTYPE   # fp16 reserved
+    assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 2, None, 0, None) == EINVAL   # fp16 is taken: y aliases x
     assert f(FAKE, FAKE, FAKE, FAKE, 4, 16, 16, 16, 16, 16, 16, 9, None, 0, None) == EDTYPE
     assert f(FAKE + 4, FAKE, FAKE, FAKE * 2, 4, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == EINVAL  # misaligned
     assert f(FAKE, FAKE * 4, FAKE * 8, FAKE, 4, 16, 16, 16, 16, 16, 16, 0, None, 0, None) == EINVAL  # y aliases x
@@ -164,7 +164,7 @@ def test_mixer_backward_rejects_bad_arguments(lib):
     assert call(H=0) == ESHAPE
     assert call(bs=0) == ESHAPE
     assert call(bs=200) == ESHAPE
-    assert call(dt=2) == EDTYPE
+    assert call(dt=9) == EDTYPE
 
 
 def test_m2_layer_rejects_bad_arguments(lib):
@@ -190,7 +190,7 @@ def test_m2_layer_rejects_bad_arguments(lib):
     assert call(B=-1) == ESHAPE
     assert call(bn=0) == ESHAPE
     assert call(bd=200) == ESHAPE                # a row beyond LDS
-    assert call(dt=2) == EDTYPE
+    assert call(dt=9) == EDTYPE
     assert call(wsb=need - 1) == EWORKSPACE
     assert call(B=0) == 0
 
@@ -246,7 +246,7 @@ def test_fft_rejects_bad_arguments(lib):
     assert f(FAKE, FAKE * 1024, 4, 2048, fac, 2, 1, 0, FAKE, 100, None) == EWORKSPACE
     assert f(FAKE, None, 4, 2048, fac, 2, 1, 0, FAKE, 1 << 30, None) == EINVAL
     assert f(FAKE, FAKE * 1024, 4, 2048, fac, 2, 7, 0, FAKE, 1 << 30, None) == EINVAL       # real flag
-    assert lib.monarch_ifft(FAKE, FAKE * 1024, 4, 2048, fac, 2, 1, 2, FAKE, 1 << 30, None) == EDTYPE
+    assert lib.monarch_ifft(FAKE, FAKE * 1024, 4, 2048, fac, 2, 1, 9, FAKE, 1 << 30, None) == EDTYPE
     need = lib.monarch_fft_workspace_bytes(4, 2048, fac, 2, 0)
     assert need >= 4 * 2048 * 8
 
@@ -267,7 +267,7 @@ def test_conv_rejects_bad_arguments(lib):
     assert call(klen=2000) == ESHAPE                    # causal kernel longer than the sequence
     assert call(klen=4096, causal=0) == ESHAPE
     assert call(causal=2) == EINVAL
-    assert call(dt=2) == EDTYPE
+    assert call(dt=9) == EDTYPE
     # order 2 keeps the hidden activations in the workspace (the fused order-1 kernel needs none)
     assert call(order=2, w1l=FAKE, w2l=FAKE, ws=None, wsb=0) == EWORKSPACE
     assert call(wsb=64) == EWORKSPACE
@@ -290,7 +290,7 @@ def test_mlp_rejects_bad_arguments(lib):
     assert call(order=2) == EINVAL                       # order 2 without the L factors
     assert call(order=1, w1l=FAKE) == EINVAL
     assert call(order=2, w1l=FAKE, w2l=FAKE, mid1=770) == ESHAPE
-    assert call(dt=2) == EDTYPE
+    assert call(dt=9) == EDTYPE
     # order 2 keeps the hidden activations in the workspace (the fused order-1 kernel needs none)
     assert call(order=2, w1l=FAKE, w2l=FAKE, ws=None, wsb=0) == EWORKSPACE
     assert call(y=FAKE) == EINVAL
