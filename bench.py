@@ -531,7 +531,7 @@ def summarize_profile(directory, kernel_filter):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1100, help="steps of the headline case per timed region")
+    ap.add_argument("--steps", type=int, default=3500, help="steps of the headline case per timed region")
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", action="append", help="run only these cases (names as in the `configs` list); the first is the headline of the line")
     ap.add_argument("--no-extra-configs", action="store_true", help="headline only")

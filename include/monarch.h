@@ -20,8 +20,11 @@
  *     shape checks happen before any device work, so a failing call has no side
  *     effect.  monarch_last_error() gives a thread-local message for the last
  *     failure.  The library never throws, aborts or prints.
- *   - I/O element types: MONARCH_F32 or MONARCH_BF16 (MONARCH_F16 is reserved
- *     and returns MONARCH_EDTYPE).  Arithmetic accumulates in fp32 always.
+ *   - I/O element types: MONARCH_F32, MONARCH_BF16 or MONARCH_F16 on the four
+ *     hot-path operations (monarch_matmul, monarch_fft / monarch_ifft,
+ *     monarch_causal_conv and its _static variant, monarch_mlp); the other entry
+ *     points take F32 and BF16 and return MONARCH_EDTYPE for F16.  Arithmetic
+ *     accumulates in fp32 always.
  *   - Index conventions: 0-based; omega_N = exp(+2*pi*i/N) (the paper's sign);
  *     sigma_(b,N)(i1*b+i0) = i0*(N/b)+i1 and (P_(b,N) x)[i] = x[sigma(i)]
  *     (appendix notation); block-diagonal factors are stored [block][out][in].
@@ -285,8 +288,10 @@ int monarch_causal_conv_static(const void *u, const void *k, const void *g_in, c
  *            inner widths mid1, mid2 (0 means d):
  *            W1_R: [nb][mid1/nb][d/nb], W1_L: [nb][d_hidden/nb][mid1/nb],
  *            W2_R: [nb][mid2/nb][d_hidden/nb], W2_L: [nb][d/nb][mid2/nb].
- * act: 0 none, 1 ReLU, 2 GELU (erf form: z * Phi(z); the bf16 kernels evaluate
- * Phi by a polynomial with |error| <= 2.4e-4, below bf16 resolution).  b1
+ * act: 0 none, 1 ReLU, 2 GELU (erf form: z * Phi(z); the 16-bit matrix-core
+ * kernels evaluate Phi by a polynomial in fp16 with |Phi error| <= 1e-3, an
+ * absolute bound: the result is within 1e-3 |z| of z Phi(z), and 0 below
+ * z = -3.25).  b1
  * (d_hidden) and b2 (d) may be NULL.  x, y: (tokens, d); everything of type dt.
  * Errors: EINVAL, ESHAPE (nb does not divide the widths, order not 1 or 2,
  * widths beyond the on-chip tile), EDTYPE, EWORKSPACE, EHIP.

@@ -1037,15 +1037,15 @@ int monarch_mlp(const void *x, void *y, int64_t tokens, int d, int d_hidden, int
     hipStream_t s = (hipStream_t)stream;
 
     if (order == 1 && mlp_mfma_order1_supported(d, d_hidden, nb, dt))
-        return launch_mlp_mfma_order1(x, y, tokens, d, d_hidden, nb, W1_R, b1, W2_R, b2, act, 0, s);
+        return launch_mlp_mfma_order1(x, y, tokens, d, d_hidden, nb, W1_R, b1, W2_R, b2, act, 0, dt, s);
     if (order == 2 && mlp_order2_mfma_supported(d, d_hidden, nb, mid1, mid2, dt)) {
         void *t2 = ws, *u1 = (char *)ws + align_up((size_t)tokens * mid1 * sizeof(bf16_t), 256);
-        rc = launch_factor_mfma(x, t2, tokens, nb, mid1 / nb, d / nb, W1_R, nullptr, 0, s);
+        rc = launch_factor_mfma(x, t2, tokens, nb, mid1 / nb, d / nb, W1_R, nullptr, 0, dt, s);
         if (rc) return rc;
         // hidden unit h of block k is position h nb + k of the hidden vector: that is where its bias sits
-        rc = launch_mlp_mfma_order1(t2, u1, tokens, mid1, d_hidden, nb, W1_L, b1, W2_R, nullptr, act, 1, s);
+        rc = launch_mlp_mfma_order1(t2, u1, tokens, mid1, d_hidden, nb, W1_L, b1, W2_R, nullptr, act, 1, dt, s);
         if (rc) return rc;
-        return launch_factor_mfma(u1, y, tokens, nb, d / nb, mid2 / nb, W2_L, b2, 2, s);
+        return launch_factor_mfma(u1, y, tokens, nb, d / nb, mid2 / nb, W2_L, b2, 2, dt, s);
     }
 
     // Layer 1 writes the activated hidden vector (fp32) to the workspace, layer 2 reads it.

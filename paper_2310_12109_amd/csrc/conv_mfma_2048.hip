@@ -24,14 +24,17 @@
 //
 // Appendix DFT corollary (Monarch form of F_N), Sec. 3.2 Eq. 2 with gating, Thm 3 (padding).
 #include "const_roots.h"
+#include "half16.h"
 #include "kernels.h"
 
 namespace monarch {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t op8;   // one MFMA operand: 8 packed 16-bit values of either type
+using h16::f32x4;
+using h16::hi32;
+using h16::lo32;
+using h16::mfma;
+using h16::op8;
+using h16::pack16;
 
 namespace c2048 {
 
@@ -128,42 +131,12 @@ union Pack8 {
 
 struct COp { op8 r, i, ni; };    // constant complex operand: real part, imaginary part and its negative
 
-// The element type E (bf16_t or f16_t) only shows in four places: rounding a pair of floats to a packed pair,
-// widening the halves of a packed pair, the matrix instruction, and the two-term dot product of the gating.
-template <typename E> __device__ __forceinline__ uint32_t pack16(float lo, float hi)
-{
-    typedef __attribute__((ext_vector_type(2))) E pair_t;
-    pair_t p = {(E)lo, (E)hi};
-    return __builtin_bit_cast(uint32_t, p);
-}
-template <typename E> __device__ __forceinline__ float lo32(uint32_t d);
-template <typename E> __device__ __forceinline__ float hi32(uint32_t d);
-template <> __device__ __forceinline__ float lo32<bf16_t>(uint32_t d) { return __uint_as_float(d << 16); }
-template <> __device__ __forceinline__ float hi32<bf16_t>(uint32_t d) { return __uint_as_float(d & 0xffff0000u); }
-template <> __device__ __forceinline__ float lo32<f16_t>(uint32_t d)
-{
-    typedef __attribute__((ext_vector_type(2))) f16_t pair_t;
-    return (float)__builtin_bit_cast(pair_t, d)[0];
-}
-template <> __device__ __forceinline__ float hi32<f16_t>(uint32_t d)
-{
-    typedef __attribute__((ext_vector_type(2))) f16_t pair_t;
-    return (float)__builtin_bit_cast(pair_t, d)[1];
-}
+// (The element type E, bf16_t or f16_t, only shows in the helpers of half16.h, the constant tables and the
+// two-term dot product of the gating.)
 
 // Contraction index carried by operand slot j of lane group kg when the operand is made from two
 // stacked 16x16 accumulator tiles: tile j/4, register j%4 holds row 16*(j/4) + 4*kg + j%4.
 __device__ __forceinline__ int slot_index(int kg, int j) { return 16 * (j >> 2) + 4 * kg + (j & 3); }
-
-template <typename E> __device__ __forceinline__ f32x4 mfma(op8 a, op8 b, f32x4 c);
-template <> __device__ __forceinline__ f32x4 mfma<bf16_t>(op8 a, op8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-template <> __device__ __forceinline__ f32x4 mfma<f16_t>(op8 a, op8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
 
 // Sign flips on packed 16-bit operands (bit 15 of each half is the sign in both types).
 __device__ __forceinline__ op8 flip(op8 v, uint32_t mask) { return v ^ mask; }

@@ -17,19 +17,20 @@
 // served by L2.  Tokens sit on the MFMA column index.  The workgroup has 16 waves and the (block,
 // row tile) units are dealt round-robin to them, each wave requesting the weights of its first units
 // before it waits for the token tile: one trip to HBM and one to L2 per workgroup, overlapped.
+#include "half16.h"
 #include "kernels.h"
 
 namespace monarch {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
+using h16::f32x4;
+using h16::op8;
 
 namespace fac {
 
 constexpr int THREADS = 1024, WAVES = THREADS / 64;
 
 union Pack8 {
-    bf16x8 v;
+    op8 v;
     uint32_t d[4];
     uint16_t h[8];
     uint4 q;
@@ -44,10 +45,10 @@ static inline size_t lds_bytes(int tok, int nb, int r_out, int r_in)
 }
 
 // KS = r_in / 32 k-steps; NTK column tiles of 16 tokens per workgroup.
-template <int KS, int MODE, int NTK>
-__global__ __launch_bounds__(1024) void factor_kernel(const bf16_t *__restrict__ in, bf16_t *__restrict__ out,
-                                                        int64_t tokens, int nb, int r_out, const bf16_t *__restrict__ W,
-                                                        const bf16_t *__restrict__ bias)
+template <typename E, int KS, int MODE, int NTK>
+__global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, E *__restrict__ out,
+                                                        int64_t tokens, int nb, int r_out, const E *__restrict__ W,
+                                                        const E *__restrict__ bias)
 {
     constexpr int RIN = 32 * KS, TOK = 16 * NTK;
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(1024) void factor_kernel(const bf16_t *__restrict__
             int u = u0 + b * WAVES;
             if (u >= units) u = u0;
             const int k = u / mts, mt = u - k * mts;
-            const bf16_t *wrow = W + ((size_t)k * r_out + 16 * mt + l16) * RIN + 8 * kg;
+            const E *wrow = W + ((size_t)k * r_out + 16 * mt + l16) * RIN + 8 * kg;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) a[b][ks].q = *reinterpret_cast<const uint4 *>(wrow + 32 * ks);
         }
@@ -133,14 +134,14 @@ __global__ __launch_bounds__(1024) void factor_kernel(const bf16_t *__restrict__
                     for (int ks = 0; ks < KS; ++ks) {
                         Pack8 xop;
                         xop.q = *reinterpret_cast<const uint4 *>(row + 16 * nt * ld_in + k * RIN + 32 * ks);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[b][ks].v, xop.v, acc, 0, 0, 0);
+                        acc = h16::mfma<E>(a[b][ks].v, xop.v, acc);
                     }
                     // rows r = 16 mt + 4 kg + i of block k, token 16 nt + l16  ->  output position r nb + k
                     // (rounded to bf16 here; the bias is added to that value at copy-out and the sum
                     // rounded again: at most half a bf16 ulp more than a single rounding)
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        tout[(16 * nt + l16) * ld_out + (16 * mt + 4 * kg + i) * nb + k] = __builtin_bit_cast(uint16_t, (__bf16)acc[i]);
+                        tout[(16 * nt + l16) * ld_out + (16 * mt + 4 * kg + i) * nb + k] = __builtin_bit_cast(uint16_t, (E)acc[i]);
                 }
             }
         }
@@ -167,9 +168,8 @@ __global__ __launch_bounds__(1024) void factor_kernel(const bf16_t *__restrict__
             if (bias) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float sum = __builtin_bit_cast(float, (uint32_t)v[u].h[e] << 16) +
-                                      __builtin_bit_cast(float, (uint32_t)bv[u].h[e] << 16);
-                    v[u].h[e] = __builtin_bit_cast(uint16_t, (__bf16)sum);
+                    const float sum = (float)__builtin_bit_cast(E, v[u].h[e]) + (float)__builtin_bit_cast(E, bv[u].h[e]);
+                    v[u].h[e] = __builtin_bit_cast(uint16_t, (E)sum);
                 }
             }
             *reinterpret_cast<uint4 *>(out + (t0 + t) * d_out + o) = v[u].q;
@@ -181,13 +181,16 @@ __global__ __launch_bounds__(1024) void factor_kernel(const bf16_t *__restrict__
 
 bool factor_mfma_supported(int nb, int r_out, int r_in, monarch_dtype dt)
 {
-    if (dt != MONARCH_BF16 || nb < 1) return false;
+    if ((dt != MONARCH_BF16 && dt != MONARCH_F16) || nb < 1) return false;
     if (r_in % 32 || r_in > 192 || r_out % 16) return false;
     return fac::lds_bytes(16, nb, r_out, r_in) <= 160 * 1024;
 }
 
-int launch_factor_mfma(const void *in, void *out, int64_t tokens, int nb, int r_out, int r_in, const void *W,
-                       const void *bias, int mode, hipStream_t s)
+namespace {
+
+template <typename E>
+int launch_typed(const void *in, void *out, int64_t tokens, int nb, int r_out, int r_in, const void *W,
+                 const void *bias, int mode, hipStream_t s)
 {
     if (tokens == 0) return MONARCH_OK;
     // 16 tokens per workgroup: measured faster than 32 (which halves the weight traffic out of L2
@@ -198,12 +201,12 @@ int launch_factor_mfma(const void *in, void *out, int64_t tokens, int nb, int r_
     const size_t lds = fac::lds_bytes(tok, nb, r_out, r_in);
 #define MONARCH_LAUNCH_FAC(KSV, MODEV, NTKV)                                                                            \
     do {                                                                                                          \
-        auto kern = fac::factor_kernel<KSV, MODEV, NTKV>;                                                             \
+        auto kern = fac::factor_kernel<E, KSV, MODEV, NTKV>;                                                             \
         if (lds > 48 * 1024)                                                                                      \
             MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
                                                   (int)lds));                                                     \
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(fac::THREADS), lds, s, (const bf16_t *)in, (bf16_t *)out, \
-                           tokens, nb, r_out, (const bf16_t *)W, (const bf16_t *)bias);                           \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(fac::THREADS), lds, s, (const E *)in, (E *)out, \
+                           tokens, nb, r_out, (const E *)W, (const E *)bias);                           \
     } while (0)
 #define MONARCH_LAUNCH_FAC_MODE(KSV)                                         \
     do {                                                                     \
@@ -229,6 +232,15 @@ int launch_factor_mfma(const void *in, void *out, int64_t tokens, int nb, int r_
 #undef MONARCH_LAUNCH_FAC
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
+}
+
+}  // namespace
+
+int launch_factor_mfma(const void *in, void *out, int64_t tokens, int nb, int r_out, int r_in, const void *W,
+                       const void *bias, int mode, monarch_dtype dt, hipStream_t s)
+{
+    if (dt == MONARCH_F16) return launch_typed<f16_t>(in, out, tokens, nb, r_out, r_in, W, bias, mode, s);
+    return launch_typed<bf16_t>(in, out, tokens, nb, r_out, r_in, W, bias, mode, s);
 }
 
 }  // namespace monarch

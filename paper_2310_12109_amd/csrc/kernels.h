@@ -140,12 +140,12 @@ bool conv_mfma_256_supported(int n, int klen, const int *factors, int nf, monarc
 int launch_conv_mfma_256(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                          int B, int H, int n, int klen, hipStream_t s);
 
-// Block-diagonal MLP (order 1), bf16, d/nb a multiple of 32 up to 192, d_hidden/nb a multiple of 32.
+// Block-diagonal MLP (order 1), bf16 or fp16, d/nb a multiple of 32 up to 192, d_hidden/nb a multiple of 32.
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt);
 // b1_interleaved: hidden unit h of block k reads b1[h nb + k] instead of b1[k (d_hidden / nb) + h].
 int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb,
                            const void *W1, const void *b1, const void *W2, const void *b2, int act,
-                           int b1_interleaved, hipStream_t s);
+                           int b1_interleaved, monarch_dtype dt, hipStream_t s);
 
 // One block-diagonal factor (nb blocks of r_out x r_in, r_in a multiple of 32 up to 192, r_out a
 // multiple of 16) of a rectangular order-2 Monarch with the permutations around it, bf16.
@@ -153,6 +153,6 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
 // 2: second factor on the previous factor's natural [block][row] output.  Writes out[r nb + k] (+ bias).
 bool factor_mfma_supported(int nb, int r_out, int r_in, monarch_dtype dt);
 int launch_factor_mfma(const void *in, void *out, int64_t tokens, int nb, int r_out, int r_in, const void *W,
-                       const void *bias, int mode, hipStream_t s);
+                       const void *bias, int mode, monarch_dtype dt, hipStream_t s);
 
 }  // namespace monarch

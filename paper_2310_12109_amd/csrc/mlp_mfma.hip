@@ -13,32 +13,26 @@
 // 16-byte stores and loads (waves 2,3 -> 0,1, then 1 -> 0; LDS float atomics are an order of magnitude
 // slower), then written with coalesced 16-byte stores.
 #include <type_traits>
+#include "half16.h"
 #include "kernels.h"
 #include "lds_dma.h"
 
 namespace monarch {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
+using h16::f32x4;
+using h16::op8;
 
 namespace mlp1 {
 
+using h16::hi32;
+using h16::lo32;
+using h16::mfma;
+using h16::pack16;
+
 constexpr int TOK = 64;   // tokens per workgroup (4 column tiles of 16)
 
-__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-    bf16x2 p = {(__bf16)lo, (__bf16)hi};
-    return __builtin_bit_cast(uint32_t, p);
-}
-
 union Pack8 {
-    bf16x8 v;
+    op8 v;
     uint32_t d[4];
     uint4 q;
 };
@@ -53,7 +47,7 @@ union Pack8 {
 // relative bound in the far negative tail (GELU(-3) = -0.004 may be off by 0.003; below z = -3.25 the result is 0).
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 __device__ __forceinline__ f16x2 splat16(float v) { return (f16x2){(_Float16)v, (_Float16)v}; }
-__device__ __forceinline__ uint32_t gelu_pack(float z0, float z1)
+template <typename E> __device__ __forceinline__ uint32_t gelu_pack(float z0, float z1)
 {
     const f16x2 h = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(z0, z1));
     f16x2 t = h * splat16(0.25f);
@@ -68,24 +62,24 @@ __device__ __forceinline__ uint32_t gelu_pack(float z0, float z1)
     float g0, g1;   // Phi (fp16, low / high half) times z (fp32)
     asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(g0) : "v"(w), "v"(z0));
     asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(g1) : "v"(w), "v"(z1));
-    return pack_bf16(g0, g1);
+    return pack16<E>(g0, g1);
 }
 
 // Activation of two neighbouring accumulator values, packed for the second GEMM.
-template <int ACT>
+template <typename E, int ACT>
 __device__ __forceinline__ uint32_t act_pack(float z0, float z1)
 {
-    if (ACT == 2) return gelu_pack(z0, z1);
-    if (ACT == 1) return pack_bf16(fmaxf(z0, 0.0f), fmaxf(z1, 0.0f));
-    return pack_bf16(z0, z1);
+    if (ACT == 2) return gelu_pack<E>(z0, z1);
+    if (ACT == 1) return pack16<E>(fmaxf(z0, 0.0f), fmaxf(z1, 0.0f));
+    return pack16<E>(z0, z1);
 }
 
 // KS = din / 32 (K steps of the first GEMM); din / 16 row tiles of the second GEMM.
-template <int KS, int ACT>
+template <typename E, int KS, int ACT>
 __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
-    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
-    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
-    const bf16_t *__restrict__ b2, int b1_interleaved)
+    const E *__restrict__ x, E *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const E *__restrict__ W1, const E *__restrict__ b1, const E *__restrict__ W2,
+    const E *__restrict__ b2, int b1_interleaved)
 {
     constexpr int DIN = 32 * KS, MT = 2 * KS, LD = DIN + 1;   // LD: padded row of the output tile
     constexpr int PART = MT * 4 * 64;                            // f32x4 pieces of one wave's partial tile
@@ -105,7 +99,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
     for (int nt = 0; nt < 4; ++nt) {
         int64_t t = t0 + 16 * nt + l16;
         if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
-        const bf16_t *row = x + t * d + blk * DIN + 8 * kg;
+        const E *row = x + t * d + blk * DIN + 8 * kg;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) xop[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
     }
@@ -115,8 +109,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f32x4){0, 0, 0, 0};
 
-    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
-    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    const E *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const E *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
     // Row r of accumulator tile mt in lane group kg is accumulator row 16mt + 4kg + r.  The hidden unit
     // given to first-GEMM row (mt, l16) is chosen so that the 8 operand slots of a lane group are 8
     // consecutive hidden units (one 16-byte load of W2): unit(mt, row) = 8*(row/4) + 4*mt + row%4.
@@ -142,7 +136,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
         Pack8 w1[2][KS], w2[MT];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            const bf16_t *wrow = W1b + (size_t)(h0 + unit_of_lane[mt]) * DIN + 8 * kg;
+            const E *wrow = W1b + (size_t)(h0 + unit_of_lane[mt]) * DIN + 8 * kg;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) w1[mt][ks].q = *reinterpret_cast<const uint4 *>(wrow + 32 * ks);
         }
@@ -160,7 +154,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const uint32_t w = bw[2 * mt + (r >> 1)];
-                    bias[mt][r] = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+                    bias[mt][r] = ((r & 1) ? hi32<E>(w) : lo32<E>(w));
                 }
         }
         f32x4 hacc[2][4];
@@ -170,7 +164,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
             for (int nt = 0; nt < 4; ++nt) {
                 f32x4 a = bias[mt];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) a = mfma(w1[mt][ks].v, xop[nt][ks].v, a);
+                for (int ks = 0; ks < KS; ++ks) a = mfma<E>(w1[mt][ks].v, xop[nt][ks].v, a);
                 hacc[mt][nt] = a;
             }
         // activation on the accumulators; two stacked tiles become one K=32 operand (slot 4mt + r)
@@ -179,14 +173,14 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-                hop[nt].d[2 * mt] = act_pack<ACT>(hacc[mt][nt][0], hacc[mt][nt][1]);
-                hop[nt].d[2 * mt + 1] = act_pack<ACT>(hacc[mt][nt][2], hacc[mt][nt][3]);
+                hop[nt].d[2 * mt] = act_pack<E, ACT>(hacc[mt][nt][0], hacc[mt][nt][1]);
+                hop[nt].d[2 * mt + 1] = act_pack<E, ACT>(hacc[mt][nt][2], hacc[mt][nt][3]);
             }
         // second GEMM: Y^T += W2[:, chunk] * H^T chunk; A operand = 8 consecutive hidden units of one output row
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma<E>(w2[mt].v, hop[nt].v, acc[mt][nt]);
     }
 
     // Sum the four waves' partial tiles.  Piece (mt, nt) of a wave sits at part[slot][(mt*4+nt)*64 + lane].
@@ -232,13 +226,13 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const uint32_t w = b2w[e >> 1];
-            v[e] = ytile[t * LD + o0 + e] + __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+            v[e] = ytile[t * LD + o0 + e] + ((e & 1) ? hi32<E>(w) : lo32<E>(w));
         }
         uint4 o;
-        o.x = pack_bf16(v[0], v[1]);
-        o.y = pack_bf16(v[2], v[3]);
-        o.z = pack_bf16(v[4], v[5]);
-        o.w = pack_bf16(v[6], v[7]);
+        o.x = pack16<E>(v[0], v[1]);
+        o.y = pack16<E>(v[2], v[3]);
+        o.z = pack16<E>(v[4], v[5]);
+        o.w = pack16<E>(v[6], v[7]);
         *reinterpret_cast<uint4 *>(y + (t0 + t) * d + blk * DIN + o0) = o;
     }
 }
@@ -250,11 +244,11 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
 // block: wave w owns tokens 64 w .. 64 w + 63 of the tile and the whole hidden vector, so nothing is
 // summed across waves and every weight byte leaves L2 once per workgroup instead of once per 64 tokens.
 // The next tile's x operands are requested before the current tile is computed.
-template <int KS, int ACT>
+template <typename E, int KS, int ACT>
 __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
-    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
-    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
-    const bf16_t *__restrict__ b2, int b1_interleaved, int wgs_per_block)
+    const E *__restrict__ x, E *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const E *__restrict__ W1, const E *__restrict__ b1, const E *__restrict__ W2,
+    const E *__restrict__ b2, int b1_interleaved, int wgs_per_block)
 {
     constexpr int DIN = 32 * KS, MT = 2 * KS, OPS = 4 * KS;   // operand pieces (64 lanes x 16 B) per hidden chunk
     extern __shared__ uint4 lds_ops[];                          // [chunk][OPS][lane], then the bias [dh] as bf16
@@ -263,8 +257,8 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
     const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
     const int blk = blockIdx.x % nb, slot = blockIdx.x / nb;
     const int dh = d_hidden / nb, nch = dh / 32;
-    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
-    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    const E *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const E *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
     uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_ops + (size_t)nch * OPS * 64);
 
     // stage the block's weights: piece (chunk j, op o, lane) is exactly the 16-byte operand that lane
@@ -272,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
     for (int idx = tid; idx < nch * OPS * 64; idx += 256) {
         const int ln = idx & 63, q = idx >> 6, j = q / OPS, o = q - j * OPS;
         const int r16 = ln & 15, g = ln >> 4;
-        const bf16_t *src;
+        const E *src;
         if (o < 2 * KS) {
             const int mt = o / KS, ks = o - mt * KS;
             const int unit = 8 * (r16 >> 2) + 4 * mt + (r16 & 3);
@@ -302,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
         for (int nt = 0; nt < 4; ++nt) {
             int64_t t = tile * 256 + 64 * wave + 16 * nt + l16;
             if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
-            const bf16_t *row = x + t * d + blk * DIN + 8 * kg;
+            const E *row = x + t * d + blk * DIN + 8 * kg;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) xnext[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
         }
@@ -341,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const uint32_t w = bw[2 * mt + (r >> 1)];
-                        bias[mt][r] = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+                        bias[mt][r] = ((r & 1) ? hi32<E>(w) : lo32<E>(w));
                     }
             }
             f32x4 hacc[2][4];
@@ -351,7 +345,7 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
                 for (int nt = 0; nt < 4; ++nt) {
                     f32x4 a = bias[mt];
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) a = mfma(w1[mt][ks].v, xop[nt][ks].v, a);
+                    for (int ks = 0; ks < KS; ++ks) a = mfma<E>(w1[mt][ks].v, xop[nt][ks].v, a);
                     hacc[mt][nt] = a;
                 }
             Pack8 hop[4];
@@ -359,13 +353,13 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
             for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt) {
-                    hop[nt].d[2 * mt] = act_pack<ACT>(hacc[mt][nt][0], hacc[mt][nt][1]);
-                    hop[nt].d[2 * mt + 1] = act_pack<ACT>(hacc[mt][nt][2], hacc[mt][nt][3]);
+                    hop[nt].d[2 * mt] = act_pack<E, ACT>(hacc[mt][nt][0], hacc[mt][nt][1]);
+                    hop[nt].d[2 * mt + 1] = act_pack<E, ACT>(hacc[mt][nt][2], hacc[mt][nt][3]);
                 }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
+                for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma<E>(w2[mt].v, hop[nt].v, acc[mt][nt]);
         }
         // accumulator rows 4 kg .. 4 kg + 3 of tile mt are 4 consecutive features of token 16 nt + l16:
         // one 8-byte store per tile and lane (the four lane groups of a token fill a 32-byte run)
@@ -373,12 +367,12 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
         for (int nt = 0; nt < 4; ++nt) {
             const int64_t t = tile * 256 + 64 * wave + 16 * nt + l16;
             if (t < tokens) {
-                bf16_t *dst = y + t * d + blk * DIN + 4 * kg;
+                E *dst = y + t * d + blk * DIN + 4 * kg;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     uint2 o;
-                    o.x = pack_bf16(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
-                    o.y = pack_bf16(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
+                    o.x = pack16<E>(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
+                    o.y = pack16<E>(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
                     *reinterpret_cast<uint2 *>(dst + 16 * mt) = o;
                 }
             }
@@ -397,11 +391,11 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
 // slots of the weight ring: as many chunks of 4 KS KB as fit in 148 KB, at most 8
 constexpr int ring_slots(int ks) { return 148 / (4 * ks) < 8 ? 148 / (4 * ks) : 8; }
 
-template <int KS, int ACT, int NT>
+template <typename E, int KS, int ACT, int NT>
 __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
-    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
-    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
-    const bf16_t *__restrict__ b2, int b1_interleaved)
+    const E *__restrict__ x, E *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const E *__restrict__ W1, const E *__restrict__ b1, const E *__restrict__ W2,
+    const E *__restrict__ b2, int b1_interleaved)
 {
     constexpr int DIN = 32 * KS, MT = 2 * KS, OPS = 4 * KS;   // operand pieces (64 lanes x 16 B) per hidden chunk
     constexpr int ring = ring_slots(KS);
@@ -412,8 +406,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
     const int blk = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * (64 * NT) + 16 * NT * wave;   // NT column tiles of 16 tokens per wave
     const int dh = d_hidden / nb, nch = dh / 32;
-    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
-    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    const E *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const E *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
     uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_ring + (size_t)ring * OPS * 64);
 
     // Wave w fetches the pieces o = w, w + 4, ... of a chunk (KS of them); piece o holds the 64 x 16 bytes that
@@ -457,7 +451,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
     for (int nt = 0; nt < NT; ++nt) {
         int64_t t = t0 + 16 * nt + l16;
         if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
-        const bf16_t *row = x + t * d + blk * DIN + 8 * kg;
+        const E *row = x + t * d + blk * DIN + 8 * kg;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) xop[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
     }
@@ -485,7 +479,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
             const uint4 braw = *reinterpret_cast<const uint4 *>(bias_lds + 32 * j + 8 * kg);
             const uint32_t bw[4] = {braw.x, braw.y, braw.z, braw.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) bias[e >> 2][e & 3] = __uint_as_float((e & 1) ? (bw[e >> 1] & 0xffff0000u) : (bw[e >> 1] << 16));
+            for (int e = 0; e < 8; ++e) bias[e >> 2][e & 3] = ((e & 1) ? hi32<E>(bw[e >> 1]) : lo32<E>(bw[e >> 1]));
         }
         const uint4 *ops = lds_ring + (size_t)(j % ring) * OPS * 64 + 4 * l16 + kg;
         Pack8 hop[NT];
@@ -501,9 +495,9 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
                 for (int mt = 0; mt < 2; ++mt) {
                     f32x4 a = bias[mt];
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) a = mfma(w1[mt][ks].v, xop[nt][ks].v, a);
-                    hop[nt].d[2 * mt] = act_pack<ACT>(a[0], a[1]);
-                    hop[nt].d[2 * mt + 1] = act_pack<ACT>(a[2], a[3]);
+                    for (int ks = 0; ks < KS; ++ks) a = mfma<E>(w1[mt][ks].v, xop[nt][ks].v, a);
+                    hop[nt].d[2 * mt] = act_pack<E, ACT>(a[0], a[1]);
+                    hop[nt].d[2 * mt + 1] = act_pack<E, ACT>(a[2], a[3]);
                 }
             }
         }
@@ -512,7 +506,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
             Pack8 w2;
             w2.q = ops[(2 * KS + mt) * 64];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma(w2.v, hop[nt].v, acc[mt][nt]);
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma<E>(w2.v, hop[nt].v, acc[mt][nt]);
         }
         // own pieces of chunk j + 1 landed (the KS (ring - 2) requests after them may still be in flight)
         wait_vm_at_most<KS * (ring - 2)>();
@@ -524,12 +518,12 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
     for (int nt = 0; nt < NT; ++nt) {
         const int64_t t = t0 + 16 * nt + l16;
         if (t < tokens) {
-            bf16_t *dst = y + t * d + blk * DIN + 4 * kg;
+            E *dst = y + t * d + blk * DIN + 4 * kg;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 uint2 o;
-                o.x = pack_bf16(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
-                o.y = pack_bf16(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
+                o.x = pack16<E>(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
+                o.y = pack16<E>(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
                 *reinterpret_cast<uint2 *>(dst + 16 * mt) = o;
             }
         }
@@ -556,11 +550,11 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_stream_kernel(
 
 constexpr size_t split_lds_bytes(int ks, int dh) { return (size_t)24 * ks * 1024 + (size_t)dh * 2; }
 
-template <int KS, int ACT>
+template <typename E, int KS, int ACT>
 __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
-    const bf16_t *__restrict__ x, bf16_t *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
-    const bf16_t *__restrict__ W1, const bf16_t *__restrict__ b1, const bf16_t *__restrict__ W2,
-    const bf16_t *__restrict__ b2, int b1_interleaved)
+    const E *__restrict__ x, E *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
+    const E *__restrict__ W1, const E *__restrict__ b1, const E *__restrict__ W2,
+    const E *__restrict__ b2, int b1_interleaved)
 {
     constexpr int DIN = 32 * KS, MT = 2 * KS, ITEM = 2 * KS;   // ITEM: 1 KB pieces of one ring part
     extern __shared__ __attribute__((aligned(16))) uint4 lds_split[];   // [3 slots][4 waves][ITEM * 64], bias [dh]
@@ -573,8 +567,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     const int64_t t0 = (int64_t)blockIdx.x * TOK;
     const int dh = d_hidden / nb, nch = dh / 32;
     const int nmine = wave < nch ? (nch - wave + 3) / 4 : 0;   // chunks wave, wave + 4, ...
-    const bf16_t *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
-    const bf16_t *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
+    const E *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
+    const E *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
     uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_split + (size_t)12 * ITEM * 64);
     auto slot_ptr = [&](int slot) { return lds_split + ((size_t)slot * 4 + wave) * ITEM * 64; };
 
@@ -582,8 +576,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     // jj = 0, 1, ...: part 2 jj + 1 = W1 rows of chunk jj + 1, part 2 jj + 2 = W2 columns of chunk jj (chunk jj
     // of the wave is chunk wave + 4 jj of the block).  Part i lives in slot i % 3.  Past the wave's last chunk
     // the last chunk is fetched again (never read), so that every request issues ITEM loads.
-    const bf16_t *w1_lane = W1b + (size_t)(8 * (frow >> 2) + (frow & 3)) * DIN + 8 * fkg;
-    const bf16_t *w2_lane = W2b + (size_t)frow * dh + 8 * fkg;
+    const E *w1_lane = W1b + (size_t)(8 * (frow >> 2) + (frow & 3)) * DIN + 8 * fkg;
+    const E *w2_lane = W2b + (size_t)frow * dh + 8 * fkg;
     const uint32_t ring_addr = lds_address(lds_split) + (uint32_t)wave * ITEM * 1024;
     auto request = [&](int i) {
         const bool w1_part = i == 0 || (i & 1);
@@ -592,13 +586,13 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
         const int h0 = 32 * (wave + 4 * c);
         const uint32_t dst = ring_addr + (uint32_t)(i % 3) * 4 * ITEM * 1024;
         if (w1_part) {
-            const bf16_t *src = w1_lane + (size_t)h0 * DIN;
+            const E *src = w1_lane + (size_t)h0 * DIN;
 #pragma unroll
             for (int o = 0; o < 2 * KS; o += 2)
                 dma_16_pair(src + 4 * (o / KS) * DIN + 32 * (o % KS), src + 4 * ((o + 1) / KS) * DIN + 32 * ((o + 1) % KS),
                             dst + o * 1024);
         } else {
-            const bf16_t *src = w2_lane + h0;
+            const E *src = w2_lane + h0;
 #pragma unroll
             for (int mt = 0; mt < MT; mt += 2)
                 dma_16_pair(src + (size_t)16 * mt * dh, src + (size_t)16 * (mt + 1) * dh, dst + mt * 1024);
@@ -620,7 +614,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     {
         int64_t t = t0 + 16 * wave + frow;   // wave w fetches the column tile nt = w
         if (t >= tokens) t = tokens - 1;     // clamp: the column is computed but never stored
-        const bf16_t *row = x + t * d + blk * DIN + 8 * fkg;
+        const E *row = x + t * d + blk * DIN + 8 * fkg;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) dma_16(row + 32 * ks, xstage + (wave * KS + ks) * 64);
     }
@@ -667,7 +661,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const uint32_t w = bw[2 * mt + (r >> 1)];
-                b[r] = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+                b[r] = ((r & 1) ? hi32<E>(w) : lo32<E>(w));
             }
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) h[mt][nt] = b;
@@ -679,7 +673,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) h[mt][nt] = mfma(w1[mt][ks].v, xop[nt][ks].v, h[mt][nt]);
+                for (int nt = 0; nt < 4; ++nt) h[mt][nt] = mfma<E>(w1[mt][ks].v, xop[nt][ks].v, h[mt][nt]);
     };
     auto read_piece_set = [&](Pack8 *dst, int slot) {
         const uint4 *ops = slot_ptr(slot) + rd;
@@ -719,11 +713,11 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
         for (int u = 0; u < NM; ++u) {
             if (!LAST) {
                 const int ks = u / 8, mt = (u / 4) % 2, nt = u % 4;
-                hnext[mt][nt] = mfma(w1[mt][ks].v, xop[nt][ks].v, hnext[mt][nt]);
+                hnext[mt][nt] = mfma<E>(w1[mt][ks].v, xop[nt][ks].v, hnext[mt][nt]);
             }
 #pragma unroll
             for (int v = (u * 16) / NM; v < ((u + 1) * 16) / NM; ++v)   // pair v: values 2v, 2v + 1 of 8 nt + 4 mt + r
-                hop[v >> 2].d[v & 3] = act_pack<ACT>(hacc[(v >> 1) & 1][v >> 2][2 * (v & 1)], hacc[(v >> 1) & 1][v >> 2][2 * (v & 1) + 1]);
+                hop[v >> 2].d[v & 3] = act_pack<E, ACT>(hacc[(v >> 1) & 1][v >> 2][2 * (v & 1)], hacc[(v >> 1) & 1][v >> 2][2 * (v & 1) + 1]);
         }
         if (!LAST) {
 #pragma unroll
@@ -741,7 +735,7 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma(w2[mt].v, hop[nt].v, acc[mt][nt]);
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma<E>(w2[mt].v, hop[nt].v, acc[mt][nt]);
         // operand reads run four row tiles ahead of the MFMAs that use them
         __builtin_amdgcn_sched_group_barrier(0x100, MT < 4 ? MT : 4, 1);
 #pragma unroll
@@ -791,8 +785,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
     for (int mt = 0; mt < MT; ++mt) {
         if (wave != (mt & 3)) continue;
         const uint2 braw = b2raw[mt >> 2];
-        const float bias2[4] = {__uint_as_float(braw.x << 16), __uint_as_float(braw.x & 0xffff0000u),
-                                __uint_as_float(braw.y << 16), __uint_as_float(braw.y & 0xffff0000u)};
+        const float bias2[4] = {lo32<E>(braw.x), hi32<E>(braw.x),
+                                lo32<E>(braw.y), hi32<E>(braw.y)};
         const f32x4 *src = part + (size_t)mt * 3 * 4 * 64 + lane;
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
@@ -802,8 +796,8 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
             const int64_t t = t0 + 16 * nt + l16;
             if (t < tokens) {
                 uint2 o;
-                o.x = pack_bf16(v[0] + bias2[0], v[1] + bias2[1]);
-                o.y = pack_bf16(v[2] + bias2[2], v[3] + bias2[3]);
+                o.x = pack16<E>(v[0] + bias2[0], v[1] + bias2[1]);
+                o.y = pack16<E>(v[2] + bias2[2], v[3] + bias2[3]);
                 *reinterpret_cast<uint2 *>(y + t * d + blk * DIN + 16 * mt + 4 * kg) = o;
             }
         }
@@ -814,14 +808,16 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_split_kernel(
 
 bool mlp_mfma_order1_supported(int d, int d_hidden, int nb, monarch_dtype dt)
 {
-    if (dt != MONARCH_BF16 || d % nb || d_hidden % nb) return false;
+    if ((dt != MONARCH_BF16 && dt != MONARCH_F16) || d % nb || d_hidden % nb) return false;
     const int din = d / nb, dh = d_hidden / nb;
     return din % 32 == 0 && din >= 32 && din <= 192 && dh % 32 == 0 && d % 8 == 0;
 }
 
-int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb,
-                           const void *W1, const void *b1, const void *W2, const void *b2, int act,
-                           int b1_interleaved, hipStream_t s)
+namespace {
+
+template <typename E>
+int launch_typed(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb, const void *W1,
+                 const void *b1, const void *W2, const void *b2, int act, int b1_interleaved, hipStream_t s)
 {
     const int din = d / nb;
     // small blocks, many tokens: weights resident in LDS, persistent workgroups
@@ -838,13 +834,13 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
         const dim3 rgrid((unsigned)(per_block * nb));
 #define MONARCH_LAUNCH_RES(KSV, ACTV)                                                                           \
     do {                                                                                                        \
-        auto kern = mlp1::mlp_order1_resident_kernel<KSV, ACTV>;                                                \
+        auto kern = mlp1::mlp_order1_resident_kernel<E, KSV, ACTV>;                                                \
         if (res_lds > 48 * 1024)                                                                                \
             MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                   (int)res_lds));                                               \
-        hipLaunchKernelGGL(kern, rgrid, dim3(256), res_lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d,       \
-                           d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2,            \
-                           (const bf16_t *)b2, b1_interleaved, (int)per_block);                                 \
+        hipLaunchKernelGGL(kern, rgrid, dim3(256), res_lds, s, (const E *)x, (E *)y, tokens, d,       \
+                           d_hidden, nb, (const E *)W1, (const E *)b1, (const E *)W2,            \
+                           (const E *)b2, b1_interleaved, (int)per_block);                                 \
     } while (0)
 #define MONARCH_LAUNCH_RES_ACT(KSV)                     \
     do {                                                \
@@ -877,12 +873,12 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
         const size_t str_lds = (size_t)mlp1::ring_slots(din / 32) * (din / 8) * 1024 + (size_t)dh_blk * 2;
 #define MONARCH_LAUNCH_STR(KSV, ACTV, NTV)                                                                       \
     do {                                                                                                         \
-        auto kern = mlp1::mlp_order1_stream_kernel<KSV, ACTV, NTV>;                                              \
+        auto kern = mlp1::mlp_order1_stream_kernel<E, KSV, ACTV, NTV>;                                              \
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,    \
                                               (int)str_lds));                                                    \
-        hipLaunchKernelGGL(kern, sgrid, dim3(256), str_lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d,        \
-                           d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2,             \
-                           (const bf16_t *)b2, b1_interleaved);                                                  \
+        hipLaunchKernelGGL(kern, sgrid, dim3(256), str_lds, s, (const E *)x, (E *)y, tokens, d,        \
+                           d_hidden, nb, (const E *)W1, (const E *)b1, (const E *)W2,             \
+                           (const E *)b2, b1_interleaved);                                                  \
     } while (0)
 #define MONARCH_LAUNCH_STR_NT(KSV, ACTV)                      \
     do {                                                      \
@@ -913,13 +909,13 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
     if (split_lds <= 160 * 1024) {
 #define MONARCH_LAUNCH_SPL(KSV, ACTV)                                                                            \
     do {                                                                                                         \
-        auto kern = mlp1::mlp_order1_split_kernel<KSV, ACTV>;                                                    \
+        auto kern = mlp1::mlp_order1_split_kernel<E, KSV, ACTV>;                                                    \
         if (split_lds > 48 * 1024)                                                                               \
             MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                   (int)split_lds));                                              \
-        hipLaunchKernelGGL(kern, grid, dim3(256), split_lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d,       \
-                           d_hidden, nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2,             \
-                           (const bf16_t *)b2, b1_interleaved);                                                  \
+        hipLaunchKernelGGL(kern, grid, dim3(256), split_lds, s, (const E *)x, (E *)y, tokens, d,       \
+                           d_hidden, nb, (const E *)W1, (const E *)b1, (const E *)W2,             \
+                           (const E *)b2, b1_interleaved);                                                  \
     } while (0)
 #define MONARCH_LAUNCH_SPL_ACT(KSV)                     \
     do {                                                \
@@ -944,12 +940,12 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
     const size_t lds = (size_t)2 * (din / 16) * 4 * 64 * 16 + (size_t)mlp1::TOK * (din + 1) * sizeof(float);
 #define MONARCH_LAUNCH_MLP1(KSV, ACTV)                                                                          \
     do {                                                                                                        \
-        auto kern = mlp1::mlp_order1_kernel<KSV, ACTV>;                                                         \
+        auto kern = mlp1::mlp_order1_kernel<E, KSV, ACTV>;                                                         \
         if (lds > 64 * 1024)                                                                                    \
             MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                   (int)lds));                                                   \
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, (const bf16_t *)x, (bf16_t *)y, tokens, d, d_hidden,  \
-                           nb, (const bf16_t *)W1, (const bf16_t *)b1, (const bf16_t *)W2, (const bf16_t *)b2,   \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, (const E *)x, (E *)y, tokens, d, d_hidden,  \
+                           nb, (const E *)W1, (const E *)b1, (const E *)W2, (const E *)b2,   \
                            b1_interleaved);                                                                     \
     } while (0)
 #define MONARCH_LAUNCH_MLP1_ACT(KSV)                     \
@@ -970,6 +966,17 @@ int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_
 #undef MONARCH_LAUNCH_MLP1
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
+}
+
+}  // namespace
+
+int launch_mlp_mfma_order1(const void *x, void *y, int64_t tokens, int d, int d_hidden, int nb,
+                           const void *W1, const void *b1, const void *W2, const void *b2, int act,
+                           int b1_interleaved, monarch_dtype dt, hipStream_t s)
+{
+    if (dt == MONARCH_F16)
+        return launch_typed<f16_t>(x, y, tokens, d, d_hidden, nb, W1, b1, W2, b2, act, b1_interleaved, s);
+    return launch_typed<bf16_t>(x, y, tokens, d, d_hidden, nb, W1, b1, W2, b2, act, b1_interleaved, s);
 }
 
 }  // namespace monarch

@@ -77,7 +77,10 @@ def test_causal_conv_f16_without_gates(mm):
 
 
 @pytest.mark.parametrize("order", [1, 2])
-@pytest.mark.parametrize("tokens,d,dh,nb", [(37, 24, 96, 4), (300, 256, 1024, 4), (2100, 128, 512, 4)])
+@pytest.mark.parametrize("tokens,d,dh,nb", [(37, 24, 96, 4),            # generic kernels
+                                            (300, 256, 1024, 4),         # matrix-core kernel, few tokens
+                                            (2100, 128, 512, 4),         # weights resident in LDS
+                                            (16500, 384, 768, 4)])       # weights streamed, wide token tiles
 def test_mlp_f16(mm, order, tokens, d, dh, nb):
     announce("mlp f16", order, tokens, d, dh, nb)
     w = workloads.mlp_inputs(tokens, d, dh, nb, order, seed=tokens, bf16=False, std=0.08)
