@@ -603,7 +603,8 @@ size_t monarch_causal_conv_workspace_bytes(int B, int H, int n, int klen, int nf
 // Convolution with the last two factors of every transform done in one kernel on LDS-resident chunks (bf16).
 // Two factors: three launches (spectrum of k, spectrum of the paired rows, inverse), no strided pass.
 // Three factors: the first factor is a strided pass before the chunk kernel (forward) and after it (inverse,
-// whose factors run in the opposite order), six launches.  Spectra stay in the order the forward leaves them in.
+// whose factors run in the opposite order), six launches; four when the rows pair two channels (one sequence per
+// channel): then one kernel does every chunk stage.  Spectra stay in the order the forward leaves them in.
 static bool conv_chunks_supported(const int *factors, int nf, monarch_dtype dt)
 {
     if (nf == 2) return fft2_lds_supported(factors[0], factors[1], dt);
@@ -644,6 +645,8 @@ static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const
     int rc;
     // two factors, rows of a multiple of 8 elements, kernels not paired: the rows never leave the chip
     const bool one_kernel = nf == 2 && !by_channel && n % 8 == 0;
+    // three factors, channels paired: four launches, the spectra never leave the chip
+    const bool fused_middle = nf == 3 && by_channel && conv3_middle_supported(O, f1, f2, MONARCH_BF16);
     for (int which = 0; which < (one_kernel ? 1 : 2); ++which) {   // 0: spectrum of k (into kf), 1: spectrum of g_in o u (into bufs[1])
         const bool pair_here = which == 0 ? by_channel : paired;
         const int64_t rows = which == 0 ? (by_channel ? crows : H) : crows;
@@ -667,10 +670,11 @@ static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const
             q.gate = gate;
             q.n_valid = valid;
             q.load = pair_here ? LD_REAL_PAIR : LD_REAL;
-            q.out = bufs[0];
+            q.out = fused_middle ? dst : bufs[0];
             q.store = ST_C16;
             rc = launch_fft_pass_mfma(q, s);
             if (rc) return rc;
+            if (fused_middle) continue;   // the chunk factors run in the middle kernel
             p.in = bufs[0];
             p.load = LD_C16;
         }
@@ -710,7 +714,7 @@ static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const
     p.out = bufs[0];
     p.store = ST_C16;
     p.tw_outer = 1;
-    rc = launch_fft2_lds(p, s);
+    rc = fused_middle ? launch_conv3_middle(p, s) : launch_fft2_lds(p, s);
     if (rc) return rc;
     FftPass q = first;
     q.rows = crows;

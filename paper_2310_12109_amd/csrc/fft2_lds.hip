@@ -609,6 +609,192 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     }
 }
 
+// Middle of a three-factor convolution whose complex rows pair two channels (one sequence per channel), in one
+// kernel: the chunk factors of the forward transform of the row and of its kernel row, the separation of the two
+// channels' spectra by Hermitian symmetry, their products, and the chunk factors of the inverse with the diagonal
+// that precedes the first factor's inverse.  in / kf: the rows of g_in o u and of k after the strided pass on
+// the first factor (packed bf16 pairs, chunk o of row r at (r N + o CH) words); out: the same layout, ready for
+// the strided inverse pass.
+// The spectrum at frequency m needs the one at N - m, which sits in chunk (O - o) mod O: a turn of a workgroup
+// takes chunk o and chunk O - o of a row together, four tiles in LDS (0: u chunk o, 1: u mirror chunk, 2 and 3
+// the same of k).  Chunks 0 and O / 2 mirror onto themselves and take a turn each with two tiles.  Nothing of the
+// spectra ever reaches HBM.
+template <int F1, int F2, int THREADS>
+__global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
+{
+    constexpr int WAVES = THREADS / 64, PITCH = pitch_of(F2), CH = F1 * F2, TILE = F1 * PITCH;
+    constexpr int NIT4 = (CH + 4 * THREADS - 1) / (4 * THREADS);   // steps of 4 complex elements per thread
+    constexpr int XT = F2 / 16, YT = F1 / 16;                     // column tiles of stage X, row tiles of stage Y
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    u32x4 *tab1 = reinterpret_cast<u32x4 *>(lds + 4 * TILE);
+    u32x4 *tab2 = F1 == F2 ? tab1 : tab1 + table_words(F1) / 4;
+    __shared__ float2 roots[F1 > F2 ? F1 : F2];
+    build_table<F1, THREADS>(tab1, roots);
+    if constexpr (F1 != F2) build_table<F2, THREADS>(tab2, roots);
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const float inv_mod = 1.0f / (float)CH;
+    auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
+    const int turns_per_row = p.O / 2 + 1;
+    const int64_t nturns = p.rows * turns_per_row;
+
+    u32x4 z[4][NIT4];
+    // every turn issues the same loads: a chunk that is its own mirror is read twice (the second time from cache)
+    auto request = [&](int64_t turn) {
+        const int64_t row = turn / turns_per_row;
+        const int o = (int)(turn - row * turns_per_row), om = o ? p.O - o : 0;
+        const uint32_t *src[4] = {(const uint32_t *)p.in + row * p.N + (int64_t)o * CH, (const uint32_t *)p.in + row * p.N + (int64_t)om * CH,
+                                  (const uint32_t *)p.kf + row * p.N + (int64_t)o * CH, (const uint32_t *)p.kf + row * p.N + (int64_t)om * CH};
+#pragma unroll
+        for (int it = 0; it < NIT4; ++it) {
+            const int e = 4 * (tid + it * THREADS);
+            const int ee = e < CH ? e : 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) z[t][it] = *reinterpret_cast<const u32x4 *>(src[t] + ee);
+        }
+    };
+
+    int64_t turn = blockIdx.x;
+    if (turn < nturns) request(turn);
+    for (; turn < nturns; turn += gridDim.x) {
+        const int64_t row = turn / turns_per_row;
+        const int o = (int)(turn - row * turns_per_row);
+        const bool paired = o != 0 && 2 * o != p.O;
+#pragma unroll
+        for (int it = 0; it < NIT4; ++it) {
+            const int e = 4 * (tid + it * THREADS);
+            if (e < CH) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) *reinterpret_cast<u32x4 *>(lds + t * TILE + tix(e)) = z[t][it];
+            }
+        }
+        __syncthreads();
+        if (turn + gridDim.x < nturns) request(turn + gridDim.x);
+
+        // ---- forward chunk factors of the row and of its kernel row (tiles 0..3, or 0 and 2 of a lone chunk)
+        const int nfwd = paired ? 4 : 2;
+        for (int t = wave; t < nfwd * XT; t += WAVES) {
+            const int ti = t / XT, tt = t - ti * XT;
+            stage_tile<F1, PITCH, true, true>(lds + (paired ? ti : 2 * ti) * TILE, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16,
+                                              16 * tt + l16, 0, inv_mod);
+        }
+        __syncthreads();
+        for (int t = wave; t < nfwd * YT; t += WAVES) {
+            const int ti = t / YT, tt = t - ti * YT;
+            stage_tile<F2, PITCH, false, false>(lds + (paired ? ti : 2 * ti) * TILE, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
+                                                0, 0, inv_mod);
+        }
+        __syncthreads();
+
+        // ---- separation and products.  z = a + i b and kz = ka + i kb carry two real channels each:
+        // A = (Z + conj Z') / 2, B = (Z - conj Z') / 2i with Z' the value at the mirror frequency, the same for the
+        // kernels; the inverse runs as conj o F o conj, so the tile takes conj(A Ka + i B Kb) and the mirror
+        // position conj(conj(A Ka) + i conj(B Kb)).
+        auto separate = [](uint32_t zu, uint32_t zum, uint32_t zk, uint32_t zkm, uint32_t &here, uint32_t &there) {
+            const float2 z0 = make_float2(lo_f32(zu), hi_f32(zu)), z1 = make_float2(lo_f32(zum), -hi_f32(zum));
+            const float2 k0 = make_float2(lo_f32(zk), hi_f32(zk)), k1 = make_float2(lo_f32(zkm), -hi_f32(zkm));
+            const float2 A = make_float2(0.5f * (z0.x + z1.x), 0.5f * (z0.y + z1.y));
+            const float2 Bv = make_float2(0.5f * (z0.y - z1.y), -0.5f * (z0.x - z1.x));
+            const float2 Ka = make_float2(0.5f * (k0.x + k1.x), 0.5f * (k0.y + k1.y));
+            const float2 Kb = make_float2(0.5f * (k0.y - k1.y), -0.5f * (k0.x - k1.x));
+            const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);
+            here = pack2(pa.x - pb.y, -(pa.y + pb.x));
+            there = pack2(pa.x + pb.y, pa.y - pb.x);
+        };
+        uint32_t *res0 = lds;            // the product tile of chunk o
+        uint32_t *res1 = lds + TILE;     // paired: the product tile of chunk O - o
+        if (o != 0) {
+            // the mirror of position e of chunk o is position CH - 1 - e of chunk O - o: 16-byte pieces read
+            // backwards.  A chunk that mirrors onto itself (o = O / 2): the lower half of the positions does both.
+            uint32_t *um = paired ? lds + TILE : lds, *km = paired ? lds + 3 * TILE : lds + 2 * TILE;
+            const int lim = paired ? CH : CH / 2;
+#pragma unroll
+            for (int it = 0; it < NIT4; ++it) {
+                const int e = 4 * (tid + it * THREADS);
+                if (e < lim) {
+                    const u32x4 a = *reinterpret_cast<const u32x4 *>(lds + tix(e)), b = *reinterpret_cast<const u32x4 *>(um + tix(CH - 4 - e));
+                    const u32x4 c = *reinterpret_cast<const u32x4 *>(lds + 2 * TILE + tix(e)), d = *reinterpret_cast<const u32x4 *>(km + tix(CH - 4 - e));
+                    u32x4 w, w2;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        uint32_t here, there;
+                        separate(a[t], b[3 - t], c[t], d[3 - t], here, there);
+                        w[t] = here;
+                        w2[3 - t] = there;
+                    }
+                    *reinterpret_cast<u32x4 *>(lds + tix(e)) = w;
+                    *reinterpret_cast<u32x4 *>(um + tix(CH - 4 - e)) = w2;
+                }
+            }
+        } else {
+            // chunk 0: the mirror of (j1, j2) is ((f1 - j1) mod f1, f2 - 1 - j2) for j1 > 0 and (0, (f2 - j2) mod f2)
+            // for j1 = 0, in the same tile; the products go to the free tile 1
+            res0 = lds + TILE;
+            for (int e = tid; e < CH; e += THREADS) {
+                const int j1 = e / F2, j2 = e - j1 * F2;
+                const int m = ((F1 - j1) % F1) * PITCH + (j1 ? F2 - 1 - j2 : (F2 - j2) % F2);
+                uint32_t w, w2;
+                separate(lds[j1 * PITCH + j2], lds[m], lds[2 * TILE + j1 * PITCH + j2], lds[2 * TILE + m], w, w2);
+                res0[j1 * PITCH + j2] = w;
+            }
+        }
+        __syncthreads();
+
+        // ---- inverse chunk factors, then the diagonal omega_N^(o (f2 c1 + c2)) that precedes the first factor's inverse
+        const int ninv = paired ? 2 : 1;
+        for (int t = wave; t < ninv * YT; t += WAVES) {
+            const int ti = t / YT, tt = t - ti * YT;
+            stage_tile<F2, PITCH, false, true>(ti ? res1 : res0, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * tt + l16, 0, inv_mod);
+        }
+        __syncthreads();
+        for (int t = wave; t < ninv * XT; t += WAVES) {
+            const int ti = t / XT, tt = t - ti * XT;
+            const int oo = ti ? p.O - o : o;
+            stage_tile<F1, PITCH, true, true>(ti ? res1 : res0, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16, oo * F2, oo * (16 * tt + l16),
+                                              1.0f / (float)p.N);
+        }
+        __syncthreads();
+
+        uint32_t *dst = (uint32_t *)p.out + row * p.N + (int64_t)o * CH;
+        uint32_t *dst2 = (uint32_t *)p.out + row * p.N + (int64_t)(p.O - o) * CH;
+#pragma unroll
+        for (int it = 0; it < NIT4; ++it) {
+            const int e = 4 * (tid + it * THREADS);
+            if (e < CH) {
+                *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(res0 + tix(e));
+                if (paired) *reinterpret_cast<u32x4 *>(dst2 + e) = *reinterpret_cast<const u32x4 *>(res1 + tix(e));
+            }
+        }
+        __syncthreads();
+    }
+}
+
+static size_t middle_lds_bytes(int f1, int f2)
+{
+    return ((size_t)4 * f1 * pitch_of(f2) + table_words(f1) + (f1 == f2 ? 0 : table_words(f2))) * 4;
+}
+
+template <int F1, int F2>
+static int launch_middle(const Fft2Args &p, hipStream_t s)
+{
+    constexpr int THREADS = 512;
+    const size_t lds = middle_lds_bytes(F1, F2);
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int per_cu = (int)((160 * 1024) / (lds + 1024));
+    const int64_t nturns = p.rows * (p.O / 2 + 1);
+    int64_t grid = (int64_t)ncu * (per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu);
+    if (grid > nturns) grid = nturns;
+    auto kern = conv3_middle_kernel<F1, F2, THREADS>;
+    if (lds > 48 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, p);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
 static size_t lds_bytes(int f1, int f2, int tiles = 1)
 {
     return ((size_t)tiles * f1 * pitch_of(f2) + table_words(f1) + (f1 == f2 ? 0 : table_words(f2))) * 4;
@@ -700,6 +886,35 @@ static bool chunk_built(int f1, int f2)
 bool fft2_lds_supported(int f1, int f2, monarch_dtype dt)
 {
     return dt == MONARCH_BF16 && chunk_built(f1, f2) && f2l::lds_bytes(f1, f2) + 1024 <= 160 * 1024;
+}
+
+// chunk shapes of the fused middle of a three-factor convolution: four tiles and the tables fit in LDS
+static bool middle_built(int f1, int f2)
+{
+    static const int shapes[][2] = {{64, 64}, {64, 32}, {32, 64}, {32, 32}, {16, 16}};
+    for (const auto &sh : shapes)
+        if (sh[0] == f1 && sh[1] == f2) return true;
+    return false;
+}
+
+bool conv3_middle_supported(int O, int f1, int f2, monarch_dtype dt)
+{
+    return dt == MONARCH_BF16 && O >= 2 && O % 2 == 0 && middle_built(f1, f2) && f2l::middle_lds_bytes(f1, f2) + 1024 <= 160 * 1024;
+}
+
+int launch_conv3_middle(const Fft2Args &p, hipStream_t s)
+{
+    if (p.rows == 0) return MONARCH_OK;
+    if ((int64_t)p.O * p.f1 * p.f2 != p.N || p.O % 2) return fail(MONARCH_EINVAL, "internal: chunk geometry of the fused middle");
+#define MONARCH_MID(A, B) \
+    if (p.f1 == A && p.f2 == B) return f2l::launch_middle<A, B>(p, s)
+    MONARCH_MID(64, 64);
+    MONARCH_MID(64, 32);
+    MONARCH_MID(32, 64);
+    MONARCH_MID(32, 32);
+    MONARCH_MID(16, 16);
+#undef MONARCH_MID
+    return fail(MONARCH_EINVAL, "internal: fused middle %d x %d not built", p.f1, p.f2);
 }
 
 int launch_fft2_lds(const Fft2Args &p, hipStream_t s)

@@ -122,6 +122,10 @@ int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const
                        int H, int n, int bs, monarch_dtype dt, hipStream_t s);
 bool fft2_lds_supported(int f1, int f2, monarch_dtype dt);
 int launch_fft2_lds(const Fft2Args &p, hipStream_t s);
+// Three factors, rows pairing two channels: both forward chunk transforms (row in `in`, kernel row in `kf`, each after
+// its strided pass), the Hermitian separation with the products, and the inverse chunk transform, in one launch.
+bool conv3_middle_supported(int O, int f1, int f2, monarch_dtype dt);
+int launch_conv3_middle(const Fft2Args &p, hipStream_t s);
 
 // ---- fused bf16 MFMA kernels ---------------------------------------------------------------
 

@@ -88,7 +88,10 @@ def test_ragged_shapes_fp32(mm, B, H, n, klen, factors, gates):
     (3, 2, 2000, 2000, (16, 16, 16), "normal"),   # three factors
     (2, 2, 4096, 4096, (32, 16, 64), "normal"),   # nfft = 8n
     (1, 5, 1000, 999, (32, 64), "normal"),        # B = 1: neighbouring channels share a complex row; H odd
-    (1, 4, 2048, 2048, (16, 16, 16), "normal"),   # the same with three factors
+    (1, 4, 2048, 2048, (16, 16, 16), "normal"),   # the same with three factors: every chunk stage in one kernel
+    (1, 5, 16384, 16000, (32, 32, 32), "normal"), # ... H odd: the last channel travels alone
+    (1, 3, 8000, 5000, (16, 64, 32), "normal"),   # ... unequal chunk factors, nfft > 2n
+    (1, 2, 30000, 30000, (64, 32, 32), "none"),
     (1, 2, 3000, 17, (128, 64), "none"),          # short kernel, no gates
 ])
 def test_ragged_shapes_bf16_matrix_core_passes(mm, B, H, n, klen, factors, gates):
