@@ -724,7 +724,7 @@ static int conv_chunks_lds(const void *u, const void *k, const void *g_in, const
     q.gate = g_out;
     q.n_valid = n;
     q.store = real_store;
-    q.scale = 1.0f / (float)nfft;
+    q.scale = (fused_middle ? 0.25f : 1.0f) / (float)nfft;   // the fused middle leaves the halves of its separation to this scale
     return launch_fft_pass_mfma(q, s);
 }
 

@@ -65,17 +65,21 @@ __device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
 
 // One stage on one tile of 16 columns.  STRIDED: element (c, col) at tile[c * PITCH + col] (stage X);
 // otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: row
-// tiles of the output that are needed.  TW: multiply output row j by omega_(mod)^(alpha j + beta)
-// (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors).
+// tiles of the output that are needed.
+// TW: 0 none; 1: multiply output row j by omega_(mod)^(alpha j + beta), computed here with a recurrence over
+// the row tiles (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors); 2: the same
+// factors handed in by the caller, twp[4 jt + r] for row 16 jt + 4 (lane / 16) + r (see twiddles_of).
 // GOUT (only with !STRIDED): the results do not go back into the tile but, unrounded, to gout[j * gstride + col]
 // as complex fp32 (the natural order of a two-factor transform: frequency j f1 + col).
-template <int F, int PITCH, bool STRIDED, bool TW, bool GOUT = false>
+template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false>
 __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int col, int lane, int live_ks, int want_jt,
-                                           int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0)
+                                           int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0,
+                                           const float2 *twp = nullptr)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32;
     const int kg = lane >> 4;
-    u32x4 br[KS], bi[KS];
+    // Re = Fr Br - Fi Bi: the second product takes the negated imaginary parts of the data (nb), one chain
+    u32x4 br[KS], bi[KS], nb[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         const int c0 = 32 * ks + 8 * kg;
@@ -97,13 +101,14 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
             }
         }
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            br[ks][h] = (w[2 * h] & 0xffffu) | (w[2 * h + 1] << 16);
-            bi[ks][h] = (w[2 * h] >> 16) | (w[2 * h + 1] & 0xffff0000u);
+        for (int h = 0; h < 4; ++h) {   // low halves (real parts) of two words into one, high halves into another
+            br[ks][h] = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x05040100u);
+            bi[ks][h] = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x07060302u);
+            nb[ks][h] = bi[ks][h] ^ 0x80008000u;
         }
     }
     float2 tw[4], step;
-    if constexpr (TW) {
+    if constexpr (TW == 1) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float rev = (float)((4 * kg + r) * alpha + beta) * inv_mod;   // exact: the phase stays below the modulus <= 2^24
@@ -112,26 +117,25 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
         const float rev = (float)(16 * alpha) * inv_mod;
         step = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
     }
-#pragma unroll 1
-    for (int jt = 0; jt < JT; ++jt) {
+    auto row_tile = [&](int jt) {
         if (jt < want_jt) {
-            // Re = Fr Br - Fi Bi as two chains and one subtraction (cheaper than negating an operand per k-step)
-            f32x4 dr = {0, 0, 0, 0}, ds = {0, 0, 0, 0}, di = {0, 0, 0, 0};
+            f32x4 dr = {0, 0, 0, 0}, di = {0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks < live_ks) {
                     const u32x4 ar = tab[(jt * KS + ks) * 128 + lane], ai = tab[(jt * KS + ks) * 128 + 64 + lane];
                     dr = mfma(ar, br[ks], dr);
-                    ds = mfma(ai, bi[ks], ds);
                     di = mfma(ai, br[ks], di);
+                    dr = mfma(ai, nb[ks], dr);
                     di = mfma(ar, bi[ks], di);
                 }
             }
             uint32_t o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float2 z = make_float2(dr[r] - ds[r], di[r]);
-                if constexpr (TW) z = cmul(z, tw[r]);
+                float2 z = make_float2(dr[r], di[r]);
+                if constexpr (TW == 1) z = cmul(z, tw[r]);
+                if constexpr (TW == 2) z = cmul(z, twp[4 * jt + r]);
                 o[r] = pack2(z.x, z.y);
                 if constexpr (GOUT) gout[(int64_t)(16 * jt + 4 * kg + r) * gstride + col] = z;
             }
@@ -143,11 +147,33 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
                 *reinterpret_cast<u32x4 *>(tile + col * PITCH + 16 * jt + 4 * kg) = u32x4{o[0], o[1], o[2], o[3]};
             }
         }
-        if constexpr (TW) {
+        if constexpr (TW == 1) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) tw[r] = cmul(tw[r], step);
         }
+    };
+    if constexpr (TW == 2 || F <= 64) {   // (TW == 2: the factors sit in registers, every index must be a constant)
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) row_tile(jt);
+    } else {
+#pragma unroll 1
+        for (int jt = 0; jt < JT; ++jt) row_tile(jt);
     }
+}
+
+// The diagonal of stage_tile for a fixed column, kept by the caller across calls: twp[4 jt + r] =
+// omega_(mod)^(alpha (16 jt + 4 (lane / 16) + r)).
+template <int F>
+__device__ __forceinline__ void twiddles_of(float2 *twp, int lane, int alpha, float inv_mod)
+{
+    const int kg = lane >> 4;
+#pragma unroll
+    for (int jt = 0; jt < F / 16; ++jt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float rev = (float)((16 * jt + 4 * kg + r) * alpha) * inv_mod;
+            twp[4 * jt + r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+        }
 }
 
 __device__ __forceinline__ int64_t pair_first_row(const Fft2Args &p, int64_t rc)
@@ -470,16 +496,16 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
         // ---- the two stages
         if constexpr (!INVERSE) {
             for (int t = wave; t < F2 / 16; t += WAVES)
-                stage_tile<F1, PITCH, true, true>(tile, tab1, 16 * t + l16, lane, live_x, F1 / 16, 16 * t + l16, 0, inv_mod);
+                stage_tile<F1, PITCH, true, 1>(tile, tab1, 16 * t + l16, lane, live_x, F1 / 16, 16 * t + l16, 0, inv_mod);
             __syncthreads();
             if constexpr (NAT_OUT) {
                 float2 *gout = (float2 *)p.out + rc * (int64_t)p.N;
                 for (int t = wave; t < F1 / 16; t += WAVES)
-                    stage_tile<F2, PITCH, false, false, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod,
+                    stage_tile<F2, PITCH, false, 0, true>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod,
                                                               gout, F1);
             } else {
                 for (int t = wave; t < F1 / 16; t += WAVES)
-                    stage_tile<F2, PITCH, false, false>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod);
+                    stage_tile<F2, PITCH, false, 0>(tile, tab2, 16 * t + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod);
             }
         }
         if constexpr (FUSED) {
@@ -504,7 +530,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
             // (tile index ti = 1 is the mirror chunk O - o of a paired turn)
             for (int t = wave; t < ntile * (F1 / 16); t += WAVES) {
                 const int ti = t / (F1 / 16), tt = t - ti * (F1 / 16);
-                stage_tile<F2, PITCH, false, true>(ti ? tile2 : tile, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
+                stage_tile<F2, PITCH, false, 1>(ti ? tile2 : tile, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
                                                    16 * tt + l16, 0, inv_mod);
             }
             __syncthreads();
@@ -512,12 +538,12 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
                 for (int t = wave; t < ntile * (F2 / 16); t += WAVES) {
                     const int ti = t / (F2 / 16), tt = t - ti * (F2 / 16);
                     const int o = ti ? p.O - o_here : o_here;
-                    stage_tile<F1, PITCH, true, true>(ti ? tile2 : tile, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, want_x, o * F2,
+                    stage_tile<F1, PITCH, true, 1>(ti ? tile2 : tile, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, want_x, o * F2,
                                                       o * (16 * tt + l16), 1.0f / (float)p.N);
                 }
             } else {
                 for (int t = wave; t < F2 / 16; t += WAVES)
-                    stage_tile<F1, PITCH, true, false>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, 0, 0, inv_mod);
+                    stage_tile<F1, PITCH, true, 0>(tile, tab1, 16 * t + l16, lane, (F1 + 31) / 32, want_x, 0, 0, inv_mod);
             }
         }
         __syncthreads();
@@ -612,7 +638,8 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
 // Middle of a three-factor convolution whose complex rows pair two channels (one sequence per channel), in one
 // kernel: the chunk factors of the forward transform of the row and of its kernel row, the separation of the two
 // channels' spectra by Hermitian symmetry, their products, and the chunk factors of the inverse with the diagonal
-// that precedes the first factor's inverse.  in / kf: the rows of g_in o u and of k after the strided pass on
+// that precedes the first factor's inverse; the result is 4 times the product spectrum's inverse (the halves of the
+// separation are left to the scale of the last pass).  in / kf: the rows of g_in o u and of k after the strided pass on
 // the first factor (packed bf16 pairs, chunk o of row r at (r N + o CH) words); out: the same layout, ready for
 // the strided inverse pass.
 // The spectrum at frequency m needs the one at N - m, which sits in chunk (O - o) mod O: a turn of a workgroup
@@ -638,6 +665,14 @@ __global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
     auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
     const int turns_per_row = p.O / 2 + 1;
     const int64_t nturns = p.rows * turns_per_row;
+    // A wave meets the same column in every task of a stage when the tasks of a tile divide the waves: then the
+    // diagonal between the two factors (forward after stage X, inverse after stage Y) is computed once.
+    constexpr bool HOIST = WAVES % XT == 0 && WAVES % YT == 0 && F1 <= 64 && F2 <= 64;
+    float2 twx[HOIST ? F1 / 4 : 1], twy[HOIST ? F2 / 4 : 1];
+    if constexpr (HOIST) {
+        twiddles_of<F1>(twx, lane, 16 * (wave % XT) + l16, inv_mod);
+        twiddles_of<F2>(twy, lane, 16 * (wave % YT) + l16, inv_mod);
+    }
 
     u32x4 z[4][NIT4];
     // every turn issues the same loads: a chunk that is its own mirror is read twice (the second time from cache)
@@ -676,13 +711,17 @@ __global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
         const int nfwd = paired ? 4 : 2;
         for (int t = wave; t < nfwd * XT; t += WAVES) {
             const int ti = t / XT, tt = t - ti * XT;
-            stage_tile<F1, PITCH, true, true>(lds + (paired ? ti : 2 * ti) * TILE, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16,
-                                              16 * tt + l16, 0, inv_mod);
+            if constexpr (HOIST)
+                stage_tile<F1, PITCH, true, 2>(lds + (paired ? ti : 2 * ti) * TILE, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16,
+                                               0, 0, inv_mod, nullptr, 0, twx);
+            else
+                stage_tile<F1, PITCH, true, 1>(lds + (paired ? ti : 2 * ti) * TILE, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16,
+                                               16 * tt + l16, 0, inv_mod);
         }
         __syncthreads();
         for (int t = wave; t < nfwd * YT; t += WAVES) {
             const int ti = t / YT, tt = t - ti * YT;
-            stage_tile<F2, PITCH, false, false>(lds + (paired ? ti : 2 * ti) * TILE, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
+            stage_tile<F2, PITCH, false, 0>(lds + (paired ? ti : 2 * ti) * TILE, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
                                                 0, 0, inv_mod);
         }
         __syncthreads();
@@ -690,15 +729,13 @@ __global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
         // ---- separation and products.  z = a + i b and kz = ka + i kb carry two real channels each:
         // A = (Z + conj Z') / 2, B = (Z - conj Z') / 2i with Z' the value at the mirror frequency, the same for the
         // kernels; the inverse runs as conj o F o conj, so the tile takes conj(A Ka + i B Kb) and the mirror
-        // position conj(conj(A Ka) + i conj(B Kb)).
+        // position conj(conj(A Ka) + i conj(B Kb)).  The tiles hold 4 times that: the halves are not applied here.
         auto separate = [](uint32_t zu, uint32_t zum, uint32_t zk, uint32_t zkm, uint32_t &here, uint32_t &there) {
             const float2 z0 = make_float2(lo_f32(zu), hi_f32(zu)), z1 = make_float2(lo_f32(zum), -hi_f32(zum));
             const float2 k0 = make_float2(lo_f32(zk), hi_f32(zk)), k1 = make_float2(lo_f32(zkm), -hi_f32(zkm));
-            const float2 A = make_float2(0.5f * (z0.x + z1.x), 0.5f * (z0.y + z1.y));
-            const float2 Bv = make_float2(0.5f * (z0.y - z1.y), -0.5f * (z0.x - z1.x));
-            const float2 Ka = make_float2(0.5f * (k0.x + k1.x), 0.5f * (k0.y + k1.y));
-            const float2 Kb = make_float2(0.5f * (k0.y - k1.y), -0.5f * (k0.x - k1.x));
-            const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);
+            const float2 A = make_float2(z0.x + z1.x, z0.y + z1.y), Bv = make_float2(z0.y - z1.y, z1.x - z0.x);
+            const float2 Ka = make_float2(k0.x + k1.x, k0.y + k1.y), Kb = make_float2(k0.y - k1.y, k1.x - k0.x);
+            const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);   // (the four halves are left to the caller: 1/4 in the final scale)
             here = pack2(pa.x - pb.y, -(pa.y + pb.x));
             there = pack2(pa.x + pb.y, pa.y - pb.x);
         };
@@ -745,14 +782,19 @@ __global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
         const int ninv = paired ? 2 : 1;
         for (int t = wave; t < ninv * YT; t += WAVES) {
             const int ti = t / YT, tt = t - ti * YT;
-            stage_tile<F2, PITCH, false, true>(ti ? res1 : res0, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * tt + l16, 0, inv_mod);
+            if constexpr (HOIST)
+                stage_tile<F2, PITCH, false, 2>(ti ? res1 : res0, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod,
+                                                nullptr, 0, twy);
+            else
+                stage_tile<F2, PITCH, false, 1>(ti ? res1 : res0, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * tt + l16, 0,
+                                                inv_mod);
         }
         __syncthreads();
         for (int t = wave; t < ninv * XT; t += WAVES) {
             const int ti = t / XT, tt = t - ti * XT;
             const int oo = ti ? p.O - o : o;
-            stage_tile<F1, PITCH, true, true>(ti ? res1 : res0, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16, oo * F2, oo * (16 * tt + l16),
-                                              1.0f / (float)p.N);
+            stage_tile<F1, PITCH, true, 1>(ti ? res1 : res0, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16, oo * F2, oo * (16 * tt + l16),
+                                           1.0f / (float)p.N);
         }
         __syncthreads();
 
@@ -778,7 +820,7 @@ static size_t middle_lds_bytes(int f1, int f2)
 template <int F1, int F2>
 static int launch_middle(const Fft2Args &p, hipStream_t s)
 {
-    constexpr int THREADS = 512;
+    constexpr int THREADS = 512;   // one workgroup per compute unit (four tiles and the tables take more than half of LDS)
     const size_t lds = middle_lds_bytes(F1, F2);
     int dev = 0, ncu = 0;
     MONARCH_HIP_CHECK(hipGetDevice(&dev));
