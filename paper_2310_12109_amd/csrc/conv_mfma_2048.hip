@@ -196,19 +196,22 @@ __device__ __forceinline__ void interleave_store(uint32_t *dst, const uint32_t (
     reinterpret_cast<uint4 *>(dst)[1] = o1;
 }
 
-// x.lo * g.lo + x.hi * g.hi of two packed 16-bit pairs, in fp32 (exact when one of the products is zero).
-template <typename E> __device__ __forceinline__ float dot2(uint32_t x, uint32_t g);
-template <> __device__ __forceinline__ float dot2<bf16_t>(uint32_t x, uint32_t g)
+// d[i] = x_i.lo * g_i.lo + x_i.hi * g_i.hi of packed 16-bit pairs, in fp32 (exact when one of the products is
+// zero), for i = 0..3 with x = (x0, x1, x0, x1).  One block of assembly that ends with the three wait states a
+// dot product's result needs before another kind of vector instruction may read it: the compiler inserts them
+// only for instructions it can see.
+template <typename E> __device__ __forceinline__ void dot2x4(uint32_t x0, uint32_t x1, uint32_t g0, uint32_t g1, uint32_t g2, uint32_t g3, float (&d)[4]);
+template <> __device__ __forceinline__ void dot2x4<bf16_t>(uint32_t x0, uint32_t x1, uint32_t g0, uint32_t g1, uint32_t g2, uint32_t g3, float (&d)[4])
 {
-    float d;
-    asm("v_dot2_f32_bf16 %0, %1, %2, 0" : "=v"(d) : "v"(x), "v"(g));
-    return d;
+    asm("v_dot2_f32_bf16 %0, %4, %6, 0\n\tv_dot2_f32_bf16 %1, %5, %7, 0\n\tv_dot2_f32_bf16 %2, %4, %8, 0\n\tv_dot2_f32_bf16 %3, %5, %9, 0\n\ts_nop 2"
+        : "=&v"(d[0]), "=&v"(d[1]), "=&v"(d[2]), "=&v"(d[3])
+        : "v"(x0), "v"(x1), "v"(g0), "v"(g1), "v"(g2), "v"(g3));
 }
-template <> __device__ __forceinline__ float dot2<f16_t>(uint32_t x, uint32_t g)
+template <> __device__ __forceinline__ void dot2x4<f16_t>(uint32_t x0, uint32_t x1, uint32_t g0, uint32_t g1, uint32_t g2, uint32_t g3, float (&d)[4])
 {
-    float d;
-    asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(d) : "v"(x), "v"(g));
-    return d;
+    asm("v_dot2_f32_f16 %0, %4, %6, 0\n\tv_dot2_f32_f16 %1, %5, %7, 0\n\tv_dot2_f32_f16 %2, %4, %8, 0\n\tv_dot2_f32_f16 %3, %5, %9, 0\n\ts_nop 2"
+        : "=&v"(d[0]), "=&v"(d[1]), "=&v"(d[2]), "=&v"(d[3])
+        : "v"(x0), "v"(x1), "v"(g0), "v"(g1), "v"(g2), "v"(g3));
 }
 
 // Writes two rows into the wave's staging tile as (row a | row b << 16) words at [c*ST_LD + a'],
@@ -230,8 +233,10 @@ __device__ __forceinline__ void stage_rows(uint32_t *stage, int lane, const RowL
             uint32_t o[8];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                o[2 * q] = pack16<E>(dot2<E>(r[q], ga[q] & 0xffffu), dot2<E>(m[q], gb[q] & 0xffffu));
-                o[2 * q + 1] = pack16<E>(dot2<E>(r[q], ga[q] & 0xffff0000u), dot2<E>(m[q], gb[q] & 0xffff0000u));
+                float d[4];
+                dot2x4<E>(r[q], m[q], ga[q] & 0xffffu, gb[q] & 0xffffu, ga[q] & 0xffff0000u, gb[q] & 0xffff0000u, d);
+                o[2 * q] = pack16<E>(d[0], d[1]);
+                o[2 * q + 1] = pack16<E>(d[2], d[3]);
             }
             reinterpret_cast<uint4 *>(dst)[0] = make_uint4(o[0], o[1], o[2], o[3]);
             reinterpret_cast<uint4 *>(dst)[1] = make_uint4(o[4], o[5], o[6], o[7]);

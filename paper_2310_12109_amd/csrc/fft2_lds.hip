@@ -36,18 +36,28 @@ __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
 }
 
 constexpr int pitch_of(int f2) { return f2 + 4; }              // words per tile row: 16-byte aligned, 4 banks off
-constexpr int table_words(int f) { return (f / 16) * ((f + 31) / 32) * 2 * 64 * 4; }
+// F_64 keeps only the first 32 columns of its operand table: F[j][32 + c] = (-1)^j F[j][c], and a row tile holds
+// rows of one parity (tile jt of F_64: rows 32 (jt / 2) + 2 i + jt % 2, i < 16), so the second k-step of an odd
+// tile is the first one on negated data.  Every other factor: row tile jt holds rows 16 jt + i.
+constexpr bool half_table(int f) { return f == 64; }
+constexpr int table_ks(int f) { return half_table(f) ? 1 : (f + 31) / 32; }
+constexpr int table_words(int f) { return (f / 16) * table_ks(f) * 2 * 64 * 4; }
+template <int F>
+__device__ __forceinline__ constexpr int row_of(int jt, int i)
+{
+    return half_table(F) ? 32 * (jt >> 1) + 2 * i + (jt & 1) : 16 * jt + i;
+}
 
-// A-operand table of F_f in MFMA operand order: piece ((jt * KS + ks) * 2 + part) * 64 + lane
+// A-operand table of F_f in MFMA operand order: piece ((jt * KS + ks) * 2 + part) * 64 + lane, KS = table_ks(f)
 template <int F, int THREADS>
 __device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
 {
-    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    constexpr int JT = F / 16, KS = table_ks(F);
     for (int e = threadIdx.x; e < F; e += THREADS) roots[e] = omega(e, F);
     __syncthreads();
     for (int idx = threadIdx.x; idx < JT * KS * 64; idx += THREADS) {
         const int ln = idx & 63, ks = (idx >> 6) % KS, jt = idx / (64 * KS);
-        const int j = 16 * jt + (ln & 15), c0 = 32 * ks + 8 * (ln >> 4);
+        const int j = row_of<F>(jt, ln & 15), c0 = 32 * ks + 8 * (ln >> 4);
         u32x4 re, im;
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
@@ -64,11 +74,11 @@ __device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
 }
 
 // One stage on one tile of 16 columns.  STRIDED: element (c, col) at tile[c * PITCH + col] (stage X);
-// otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: row
-// tiles of the output that are needed.
+// otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: 16-row
+// blocks of the output that are needed.
 // TW: 0 none; 1: multiply output row j by omega_(mod)^(alpha j + beta), computed here with a recurrence over
 // the row tiles (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors); 2: the same
-// factors handed in by the caller, twp[4 jt + r] for row 16 jt + 4 (lane / 16) + r (see twiddles_of).
+// factors handed in by the caller, twp[4 jt + r] for row row_of(jt, 4 (lane / 16) + r) (see twiddles_of).
 // GOUT (only with !STRIDED): the results do not go back into the tile but, unrounded, to gout[j * gstride + col]
 // as complex fp32 (the natural order of a two-factor transform: frequency j f1 + col).
 template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false>
@@ -76,7 +86,8 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
                                            int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0,
                                            const float2 *twp = nullptr)
 {
-    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    constexpr int JT = F / 16, KS = (F + 31) / 32, TKS = table_ks(F);
+    constexpr bool HALF = half_table(F);
     const int kg = lane >> 4;
     // Re = Fr Br - Fi Bi: the second product takes the negated imaginary parts of the data (nb), one chain
     u32x4 br[KS], bi[KS], nb[KS];
@@ -107,49 +118,71 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
             nb[ks][h] = bi[ks][h] ^ 0x80008000u;
         }
     }
-    float2 tw[4], step;
+    u32x4 nbr1 = {0, 0, 0, 0};   // HALF: the negated real parts of the second k-step, for the odd row tiles
+    if constexpr (HALF) nbr1 = br[1] ^ 0x80008000u;
+    // TW == 1: the factors of the rows of the current tile (HALF: of the even and the odd tile of the current pair)
+    float2 tw[HALF ? 2 : 1][4], step;
     if constexpr (TW == 1) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float rev = (float)((4 * kg + r) * alpha + beta) * inv_mod;   // exact: the phase stays below the modulus <= 2^24
-            tw[r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
-        }
-        const float rev = (float)(16 * alpha) * inv_mod;
+        for (int b = 0; b < (HALF ? 2 : 1); ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float rev = (float)(row_of<F>(b, 4 * kg + r) * alpha + beta) * inv_mod;   // exact: the phase stays below the modulus <= 2^24
+                tw[b][r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+            }
+        const float rev = (float)((HALF ? 32 : 16) * alpha) * inv_mod;
         step = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
     }
+    const int want = HALF ? (want_jt + 1) & ~1 : want_jt;   // (an even and an odd tile make one block of 32 rows)
+    uint32_t even[4] = {0u, 0u, 0u, 0u};                    // HALF, stage Y: the packed results of the even tile of the pair
     auto row_tile = [&](int jt) {
-        if (jt < want_jt) {
+        if (jt < want) {
             f32x4 dr = {0, 0, 0, 0}, di = {0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks < live_ks) {
-                    const u32x4 ar = tab[(jt * KS + ks) * 128 + lane], ai = tab[(jt * KS + ks) * 128 + 64 + lane];
-                    dr = mfma(ar, br[ks], dr);
-                    di = mfma(ai, br[ks], di);
-                    dr = mfma(ai, nb[ks], dr);
-                    di = mfma(ar, bi[ks], di);
+                    const int tk = HALF ? 0 : ks;
+                    const u32x4 ar = tab[(jt * TKS + tk) * 128 + lane], ai = tab[(jt * TKS + tk) * 128 + 64 + lane];
+                    const bool flip = HALF && ks == 1 && (jt & 1);   // this k-step's operands are minus the table's
+                    dr = mfma(ar, flip ? nbr1 : br[ks], dr);
+                    di = mfma(ai, flip ? nbr1 : br[ks], di);
+                    dr = mfma(ai, flip ? bi[ks] : nb[ks], dr);
+                    di = mfma(ar, flip ? nb[ks] : bi[ks], di);
                 }
             }
             uint32_t o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float2 z = make_float2(dr[r], di[r]);
-                if constexpr (TW == 1) z = cmul(z, tw[r]);
+                if constexpr (TW == 1) z = cmul(z, tw[HALF ? jt & 1 : 0][r]);
                 if constexpr (TW == 2) z = cmul(z, twp[4 * jt + r]);
                 o[r] = pack2(z.x, z.y);
-                if constexpr (GOUT) gout[(int64_t)(16 * jt + 4 * kg + r) * gstride + col] = z;
+                if constexpr (GOUT) gout[(int64_t)row_of<F>(jt, 4 * kg + r) * gstride + col] = z;
             }
             if constexpr (GOUT) {
             } else if constexpr (STRIDED) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tile[(16 * jt + 4 * kg + r) * PITCH + col] = o[r];
+                for (int r = 0; r < 4; ++r) tile[row_of<F>(jt, 4 * kg + r) * PITCH + col] = o[r];
+            } else if constexpr (HALF) {   // rows 32 J + 8 kg + 2 r + parity: the pair of tiles holds 8 neighbours
+                if (jt & 1) {
+                    uint32_t *dst = tile + col * PITCH + 32 * (jt >> 1) + 8 * kg;
+                    *reinterpret_cast<u32x4 *>(dst) = u32x4{even[0], o[0], even[1], o[1]};
+                    *reinterpret_cast<u32x4 *>(dst + 4) = u32x4{even[2], o[2], even[3], o[3]};
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) even[r] = o[r];
+                }
             } else {
                 *reinterpret_cast<u32x4 *>(tile + col * PITCH + 16 * jt + 4 * kg) = u32x4{o[0], o[1], o[2], o[3]};
             }
         }
         if constexpr (TW == 1) {
+            if (!HALF || (jt & 1)) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) tw[r] = cmul(tw[r], step);
+                for (int b = 0; b < (HALF ? 2 : 1); ++b)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) tw[b][r] = cmul(tw[b][r], step);
+            }
         }
     };
     if constexpr (TW == 2 || F <= 64) {   // (TW == 2: the factors sit in registers, every index must be a constant)
@@ -162,7 +195,7 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
 }
 
 // The diagonal of stage_tile for a fixed column, kept by the caller across calls: twp[4 jt + r] =
-// omega_(mod)^(alpha (16 jt + 4 (lane / 16) + r)).
+// omega_(mod)^(alpha row_of(jt, 4 (lane / 16) + r)).
 template <int F>
 __device__ __forceinline__ void twiddles_of(float2 *twp, int lane, int alpha, float inv_mod)
 {
@@ -171,7 +204,7 @@ __device__ __forceinline__ void twiddles_of(float2 *twp, int lane, int alpha, fl
     for (int jt = 0; jt < F / 16; ++jt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float rev = (float)((16 * jt + 4 * kg + r) * alpha) * inv_mod;
+            const float rev = (float)(row_of<F>(jt, 4 * kg + r) * alpha) * inv_mod;
             twp[4 * jt + r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
         }
 }
@@ -635,6 +668,28 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     }
 }
 
+// The four sums of products of the Hermitian separation of two channel-paired spectra, from packed bf16 words
+// (re | im << 16): z, k at a frequency, zm, km at its mirror; sk, skm: k and km with their halves swapped.
+//   q1 = z k + conj(zm km),   q2 = z conj(km) + conj(zm) k
+// as two-term dot products with fp32 accumulation, the signs as operand modifiers.  One block of assembly: a dot
+// product's result may be read by another kind of vector instruction only three wait states later, which the
+// compiler cannot know about for instructions it does not see; the block ends with them.
+__device__ __forceinline__ void separation_sums(uint32_t z, uint32_t zm, uint32_t k, uint32_t km, uint32_t sk, uint32_t skm,
+                                                float &q1re, float &q1im, float &q2re, float &q2im)
+{
+    asm("v_dot2_f32_bf16 %0, %4, %6, 0 neg_hi:[0,1,0]\n\t"
+        "v_dot2_f32_bf16 %1, %4, %8, 0\n\t"
+        "v_dot2_f32_bf16 %2, %4, %7, 0\n\t"
+        "v_dot2_f32_bf16 %3, %4, %9, 0 neg_lo:[0,1,0]\n\t"
+        "v_dot2_f32_bf16 %0, %5, %7, %0 neg_hi:[0,1,0]\n\t"
+        "v_dot2_f32_bf16 %1, %5, %9, %1 neg_lo:[0,1,0] neg_hi:[0,1,0]\n\t"
+        "v_dot2_f32_bf16 %2, %5, %6, %2\n\t"
+        "v_dot2_f32_bf16 %3, %5, %8, %3 neg_hi:[0,1,0]\n\t"
+        "s_nop 2"
+        : "=&v"(q1re), "=&v"(q1im), "=&v"(q2re), "=&v"(q2im)
+        : "v"(z), "v"(zm), "v"(k), "v"(km), "v"(sk), "v"(skm));
+}
+
 // Middle of a three-factor convolution whose complex rows pair two channels (one sequence per channel), in one
 // kernel: the chunk factors of the forward transform of the row and of its kernel row, the separation of the two
 // channels' spectra by Hermitian symmetry, their products, and the chunk factors of the inverse with the diagonal
@@ -647,7 +702,7 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
 // the same of k).  Chunks 0 and O / 2 mirror onto themselves and take a turn each with two tiles.  Nothing of the
 // spectra ever reaches HBM.
 template <int F1, int F2, int THREADS>
-__global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
+__global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(const Fft2Args p)
 {
     constexpr int WAVES = THREADS / 64, PITCH = pitch_of(F2), CH = F1 * F2, TILE = F1 * PITCH;
     constexpr int NIT4 = (CH + 4 * THREADS - 1) / (4 * THREADS);   // steps of 4 complex elements per thread
@@ -730,14 +785,16 @@ __global__ __launch_bounds__(THREADS) void conv3_middle_kernel(const Fft2Args p)
         // A = (Z + conj Z') / 2, B = (Z - conj Z') / 2i with Z' the value at the mirror frequency, the same for the
         // kernels; the inverse runs as conj o F o conj, so the tile takes conj(A Ka + i B Kb) and the mirror
         // position conj(conj(A Ka) + i conj(B Kb)).  The tiles hold 4 times that: the halves are not applied here.
+        // With the words kept packed, the four products Z K, Z conj K', conj Z' K, conj(Z' K') are two-term dot
+        // products (exact products, fp32 sums): Q1 = Z K + conj(Z' K'), Q2 = Z conj K' + conj Z' K,
+        // 4 A Ka = Q1 + Q2, 4 B Kb = Q2 - Q1.
         auto separate = [](uint32_t zu, uint32_t zum, uint32_t zk, uint32_t zkm, uint32_t &here, uint32_t &there) {
-            const float2 z0 = make_float2(lo_f32(zu), hi_f32(zu)), z1 = make_float2(lo_f32(zum), -hi_f32(zum));
-            const float2 k0 = make_float2(lo_f32(zk), hi_f32(zk)), k1 = make_float2(lo_f32(zkm), -hi_f32(zkm));
-            const float2 A = make_float2(z0.x + z1.x, z0.y + z1.y), Bv = make_float2(z0.y - z1.y, z1.x - z0.x);
-            const float2 Ka = make_float2(k0.x + k1.x, k0.y + k1.y), Kb = make_float2(k0.y - k1.y, k1.x - k0.x);
-            const float2 pa = cmul(A, Ka), pb = cmul(Bv, Kb);   // (the four halves are left to the caller: 1/4 in the final scale)
-            here = pack2(pa.x - pb.y, -(pa.y + pb.x));
-            there = pack2(pa.x + pb.y, pa.y - pb.x);
+            const uint32_t sk = __builtin_amdgcn_alignbit(zk, zk, 16), skm = __builtin_amdgcn_alignbit(zkm, zkm, 16);   // (im, re)
+            float q1re, q1im, q2re, q2im;
+            separation_sums(zu, zum, zk, zkm, sk, skm, q1re, q1im, q2re, q2im);
+            const float a = q1re + q2re, b = q1im - q2im, c = q1im + q2im, d = q2re - q1re;
+            here = pack2(a + b, -c - d);
+            there = pack2(a - b, c - d);
         };
         uint32_t *res0 = lds;            // the product tile of chunk o
         uint32_t *res1 = lds + TILE;     // paired: the product tile of chunk O - o
@@ -820,7 +877,7 @@ static size_t middle_lds_bytes(int f1, int f2)
 template <int F1, int F2>
 static int launch_middle(const Fft2Args &p, hipStream_t s)
 {
-    constexpr int THREADS = 512;   // one workgroup per compute unit (four tiles and the tables take more than half of LDS)
+    constexpr int THREADS = 256;   // two workgroups per compute unit when four tiles and the tables fit in half of LDS
     const size_t lds = middle_lds_bytes(F1, F2);
     int dev = 0, ncu = 0;
     MONARCH_HIP_CHECK(hipGetDevice(&dev));

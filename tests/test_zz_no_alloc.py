@@ -63,12 +63,12 @@ def test_static_scratch_fused_shape_and_size_limit():
     torch.cuda.synchronize()
     assert torch.equal(y, want)
     # beyond the static array: a clear error and no device work (the output stays untouched)
-    B, H, n = 8, 64, 8192
+    B, H, n, factors = 1, 512, 16384, (32, 32, 32)
     big = {"u": torch.zeros((B, H, n), device="cuda", dtype=torch.bfloat16), "k": torch.zeros((H, n), device="cuda", dtype=torch.bfloat16),
            "g_in": None, "g_out": None}
-    assert binding.monarch_causal_conv_workspace_bytes(B, H, n, n, (128, 128), binding.BF16) > binding.STATIC_SCRATCH_BYTES
+    assert binding.monarch_causal_conv_workspace_bytes(B, H, n, n, factors, binding.BF16) > binding.STATIC_SCRATCH_BYTES
     yb = torch.full((B, H, n), 3.0, device="cuda", dtype=torch.bfloat16)
-    rc = _static_call(lib, big, yb, (128, 128))
+    rc = _static_call(lib, big, yb, factors)
     assert rc == binding.EWORKSPACE
     assert b"static" in lib.monarch_last_error()
     torch.cuda.synchronize()
