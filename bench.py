@@ -421,14 +421,14 @@ def widening_cases():
 
 def all_cases():
     return [
-        ConvCase("c2_conv_bf16", "c2_conv", True, "conv2048_bf16_kernel", "hbm"),
+        ConvCase("c2_conv_bf16", "c2_conv", True, "conv2048_kernel<bf16>", "hbm"),
         MatmulCase(),
-        ConvCase("c2_conv_f32", "c2_conv", False, "fft_pass_mfma_f32_kernel (6 launches)", "mfma", MFMA_F32_TFLOPS),
+        ConvCase("c2_conv_f32", "c2_conv", False, "conv2048_f32_kernel", "mfma", MFMA_F32_TFLOPS),
         ConvCase("c3a_conv_bf16", "c3a_conv", True, "conv256_bf16_kernel", "hbm"),
         MlpCase("c3b_mlp_order1", "c3b_mlp", 1, "mlp_order1_split_kernel", "mfma"),
         MlpCase("c3b_mlp_order2", "c3b_mlp", 2, "factor_kernel + mlp_order1 + factor_kernel", "mfma"),
-        ConvCase("c4_conv_bf16", "c4_conv", True, "fft2_lds_kernel<128,128> (fused chunk convolution)", "mfma"),
-        ConvCase("c5a_conv_bf16", "c5a_conv", True, "fft_pass_mfma_kernel + fft2_lds_kernel<64,64> (6 launches)", "mfma"),
+        ConvCase("c4_conv_bf16", "c4_conv", True, "conv16k_bf16_kernel", "mfma"),
+        ConvCase("c5a_conv_bf16", "c5a_conv", True, "fft_pass_mfma_kernel x 3 + conv3_middle_kernel<64,64> (4 launches)", "mfma"),
         MlpCase("c5b_mlp_order1", "c5b_mlp", 1, "mlp_order1_resident_kernel", "hbm"),
         MlpCase("c5b_mlp_order2", "c5b_mlp", 2, "factor_kernel + mlp_order1_resident_kernel + factor_kernel", "hbm"),
     ]

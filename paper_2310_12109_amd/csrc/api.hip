@@ -579,13 +579,14 @@ static int conv_check(int B, int H, int n, int klen, int nfft, const int *factor
 }
 
 // Which fused kernel serves this shape: 0 = none (multi-pass path), 1 = 64 x 32 MFMA, 2 = 16 x 16 MFMA,
-// 3 = 128 x 128 MFMA.
+// 3 = 128 x 128 MFMA, 4 = 64 x 32 fp32 MFMA.
 // With n, klen <= nfft/2 the circular and the causal form coincide, so `causal` does not matter.
 static int conv_fused_path(int n, int klen, const int *factors, int nf, monarch_dtype dt)
 {
     if (factors && conv_mfma_2048_supported(n, klen, factors, nf, dt)) return 1;
     if (factors && conv_mfma_256_supported(n, klen, factors, nf, dt)) return 2;
     if (factors && conv_mfma_16k_supported(n, klen, factors, nf, dt)) return 3;
+    if (factors && conv_f32_2048_supported(n, klen, factors, nf, dt)) return 4;
     return 0;
 }
 
@@ -838,6 +839,7 @@ static int conv_run(const void *u, const void *k, const void *g_in, const void *
     if (fused == 1) return launch_conv_mfma_2048(u, k, g_in, g_out, y, B, H, n, klen, dt, s);
     if (fused == 2) return launch_conv_mfma_256(u, k, g_in, g_out, y, B, H, n, klen, s);
     if (fused == 3) return launch_conv_mfma_16k(u, k, g_in, g_out, y, B, H, n, klen, s);
+    if (fused == 4) return launch_conv_f32_2048(u, k, g_in, g_out, y, B, H, n, klen, s);
 
     const size_t buf = align_up(rows * nfft * sizeof(float2), 256);
     void *bufs[2] = {ws, (char *)ws + buf};

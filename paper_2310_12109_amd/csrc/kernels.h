@@ -139,6 +139,12 @@ bool conv_mfma_16k_supported(int n, int klen, const int *factors, int nf, monarc
 int launch_conv_mfma_16k(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                          int B, int H, int n, int klen, hipStream_t s);
 
+// Fused causal convolution, nfft = 2048 = 64 x 32, fp32 tensors and fp32 matrix-core arithmetic; n, klen <= 1024,
+// multiples of 4 (csrc/conv_f32_2048.hip)
+bool conv_f32_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
+int launch_conv_f32_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
+                         int B, int H, int n, int klen, hipStream_t s);
+
 // nfft = 256 = 16 x 16, n <= 128, klen <= 256, bf16 I/O; no workspace.
 bool conv_mfma_256_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
 int launch_conv_mfma_256(const void *u, const void *k, const void *g_in, const void *g_out, void *y,

@@ -153,6 +153,27 @@ def test_fused_64x32_bf16_many_batch_groups(mm, B, n, klen):
     assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_BF16
 
 
+@pytest.mark.parametrize("B", [5, 9, 16])
+@pytest.mark.parametrize("n,klen", [(1024, 1024), (1000, 500), (512, 512), (4, 4)])
+@pytest.mark.parametrize("gates", ["both", "in", "out", "none"])
+def test_fused_64x32_fp32(mm, B, n, klen, gates):
+    # the fp32 fused 64 x 32 kernel: short rows and kernels, each gate combination, odd batch sizes (a lone last
+    # row), more than one group of four row pairs per channel
+    announce("conv fused 64x32 fp32", B, n, klen, gates)
+    H = 3
+    w = workloads.conv_inputs(B, H, n, seed=B + n + klen + len(gates), gates="normal")
+    w["k"] = np.ascontiguousarray(w["k"][:, :klen])
+    if gates in ("out", "none"):
+        w["g_in"] = None
+    if gates in ("in", "none"):
+        w["g_out"] = None
+    y = _run(mm, w, (64, 32), False)
+    want = _oracle(w, 2048)
+    assert rel_l2(y, want) <= TOL_F32
+    num = np.linalg.norm((y - want).reshape(-1, n), axis=1)
+    assert (num / np.linalg.norm(want.reshape(-1, n), axis=1)).max() <= 2.5 * TOL_F32
+
+
 @pytest.mark.parametrize("B,H,n,klen,gates", [
     (3, 5, 8192, 8192, "both"),     # odd batch: the last pair of every channel has one row
     (4, 3, 8000, 8000, "none"),     # rows that end inside a tile row
