@@ -491,15 +491,20 @@ def run_case(torch, np, binding, workloads, oracle, case, steps, warmup, check):
 
 
 def copy_calibration(mib):
-    """Plain device-to-device copies of a known size: what FETCH_SIZE / WRITE_SIZE read for known traffic."""
+    """Plain device-to-device copies of a known size: what FETCH_SIZE / WRITE_SIZE read for known traffic, and (under
+    a kernel trace) what a kernel that only moves bytes reaches at that size.  The copies rotate over source /
+    destination pairs of more than 512 MB in total, like the timed cases."""
     import torch
     n = mib * (1 << 20)
-    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
-    dst = torch.empty_like(src)
-    for _ in range(8):
+    pairs = _nsets(2 * n, cap=16)
+    bufs = [(torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255), torch.empty(n, dtype=torch.uint8, device="cuda"))
+            for _ in range(pairs)]
+    copies = max(8, 4 * pairs)
+    for i in range(copies):
+        src, dst = bufs[i % pairs]
         dst.copy_(src)
     torch.cuda.synchronize()
-    print(json.dumps({"copy_calibration_mib": mib, "copies": 8}))
+    print(json.dumps({"copy_calibration_mib": mib, "copies": copies, "buffer_pairs": pairs}))
 
 
 def summarize_profile(directory, kernel_filter):
