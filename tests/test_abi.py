@@ -255,7 +255,9 @@ def test_conv_rejects_bad_arguments(lib):
     fac = (ctypes.c_int * 2)(64, 32)
     f = lib.monarch_causal_conv
     big = 1 << 40
-    args = dict(B=8, H=4, n=1024, klen=1024, nfft=2048)
+    # rows of 1022 elements have no fused kernel: every accepted call would need the workspace, and the calls below
+    # all fail before any launch (the pointers are fake)
+    args = dict(B=8, H=4, n=1022, klen=1022, nfft=2048)
 
     def call(u=FAKE, k=FAKE * 2, y=FAKE * 1 << 20, causal=1, dt=0, ws=FAKE * 1 << 24, wsb=big, **kw):
         a = dict(args); a.update(kw)
@@ -268,11 +270,12 @@ def test_conv_rejects_bad_arguments(lib):
     assert call(klen=4096, causal=0) == ESHAPE
     assert call(causal=2) == EINVAL
     assert call(dt=9) == EDTYPE
-    # order 2 keeps the hidden activations in the workspace (the fused order-1 kernel needs none)
-    assert call(order=2, w1l=FAKE, w2l=FAKE, ws=None, wsb=0) == EWORKSPACE
+    assert call(ws=None, wsb=0) == EWORKSPACE
     assert call(wsb=64) == EWORKSPACE
     assert call(y=FAKE) == EINVAL                        # y aliases u
-    assert lib.monarch_causal_conv_workspace_bytes(8, 4, 1024, 1024, 2048, fac, 2, 0) > 0
+    assert lib.monarch_causal_conv_workspace_bytes(8, 4, 1022, 1022, 2048, fac, 2, 0) > 0
+    for dt in (0, 1, 2):    # the fused 64 x 32 kernels (fp32, bf16, fp16) need none
+        assert lib.monarch_causal_conv_workspace_bytes(8, 4, 1024, 1024, 2048, fac, 2, dt) == 0
 
 
 def test_mlp_rejects_bad_arguments(lib):
