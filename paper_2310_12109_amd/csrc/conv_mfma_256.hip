@@ -76,7 +76,11 @@ __device__ __forceinline__ Quad dft_quad(int row, int col0)
 }
 __device__ __forceinline__ u32x4 cat(u32x2 a, u32x2 b) { return u32x4{a[0], a[1], b[0], b[1]}; }
 
-template <bool GIN, bool GOUT>
+// VEC (n a multiple of 8): the rows of the wave's four pairs travel between global memory and the wave's own LDS
+// staging area 16 bytes per lane (8 rows of 256 bytes per stream = two accesses of the wave), and the 2-byte
+// operand gathers and result scatters of the layouts below happen in LDS; otherwise every element is a 2-byte
+// global access of its own.
+template <bool GIN, bool GOUT, bool VEC>
 __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restrict__ u, const bf16_t *__restrict__ k,
                                                            const bf16_t *__restrict__ g_in, const bf16_t *__restrict__ g_out,
                                                            bf16_t *__restrict__ y, int B, int H, int n, int klen)
@@ -99,8 +103,48 @@ __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restr
     // c = 4 kg + e, groups 2, 3 the second (im) at c = 4 (kg - 2) + e
     const int member = kg >> 1, cb = 4 * (kg & 1);
     float xin[PAIRS][4], gout[PAIRS][2][2];
+    // VEC: [stream: u, g_in, g_out / y][row 2 p + member][128] per wave, rows of 256 bytes
+    __shared__ __attribute__((aligned(16))) uint16_t staging[VEC ? 4 : 1][3][VEC ? 2 * PAIRS * 128 : 8];
+    uint16_t (*st)[2 * PAIRS * 128] = reinterpret_cast<uint16_t (*)[2 * PAIRS * 128]>(&staging[VEC ? wave : 0][0][0]);
+    if constexpr (VEC) {
+        uint4 ld[3][PAIRS / 2];
 #pragma unroll
-    for (int p = 0; p < PAIRS; ++p) {
+        for (int it = 0; it < PAIRS / 2; ++it) {
+            const int r = 4 * it + (lane >> 4), b = 2 * (p0 + (r >> 1)) + (r & 1), e0 = 8 * l16;
+            const bool ok = b < B && e0 < n;
+            const int64_t at = ok ? ((int64_t)b * H + h) * n + e0 : 0;
+            const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+            ld[0][it] = *reinterpret_cast<const uint4 *>(u + at);
+            if (GIN) ld[1][it] = *reinterpret_cast<const uint4 *>(g_in + at);
+            if (GOUT) ld[2][it] = *reinterpret_cast<const uint4 *>(g_out + at);
+            if (!ok) ld[0][it] = zero4;   // (the gates of a missing element meet a zero or are never used)
+        }
+#pragma unroll
+        for (int it = 0; it < PAIRS / 2; ++it) {
+            const int off = (4 * it + (lane >> 4)) * 128 + 8 * l16;
+            *reinterpret_cast<uint4 *>(&st[0][off]) = ld[0][it];
+            if (GIN) *reinterpret_cast<uint4 *>(&st[1][off]) = ld[1][it];
+            if (GOUT) *reinterpret_cast<uint4 *>(&st[2][off]) = ld[2][it];
+        }
+        __builtin_amdgcn_wave_barrier();
+        auto f32_of = [](uint16_t h) { return __uint_as_float((uint32_t)h << 16); };
+#pragma unroll
+        for (int p = 0; p < PAIRS; ++p) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int at = (2 * p + member) * 128 + (cb + e) * 16 + l16;
+                float v = f32_of(st[0][at]);
+                if (GIN) v *= f32_of(st[1][at]);
+                xin[p][e] = v;
+            }
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int r = 0; r < 2; ++r) gout[p][m][r] = GOUT ? f32_of(st[2][(2 * p + m) * 128 + (2 * kg + r) * 16 + l16]) : 1.0f;
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PAIRS && !VEC; ++p) {
         const int b = 2 * (p0 + p) + member;
         const int64_t row = ((int64_t)b * H + h) * n;
 #pragma unroll
@@ -160,8 +204,8 @@ __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restr
     }
 
 #pragma unroll
-    for (int p = 0; p < PAIRS; ++p) {
-        if (p0 + p >= npairs) break;
+    for (int p = 0; p < PAIRS; ++p) {   // (pairs past the end compute on zeros and store nothing: one block of code, so
+                                        // that the independent chains of the four pairs can be interleaved)
         const u32x2 xa = {pack2(xin[p][0], xin[p][1]), pack2(xin[p][2], xin[p][3])};
         f32x4 tr = mfma16(xa, s1re, zero), ti = mfma16(xa, s1im, zero);           // S1
 #pragma unroll
@@ -191,13 +235,26 @@ __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restr
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             const int b = 2 * (p0 + p) + m;
-            if (b < B) {
+            if constexpr (VEC) {   // into the staging rows of the output gates (read above), stored below
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+                    st[2][(2 * p + m) * 128 + (2 * kg + r) * 16 + l16] = __builtin_bit_cast(uint16_t, (bf16_t)((m ? yi[r] : yr[r]) * gout[p][m][r]));
+            } else if (b < B) {
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
                     const int t = (2 * kg + r) * 16 + l16;
                     if (t < n) y[((int64_t)b * H + h) * n + t] = (bf16_t)((m ? yi[r] : yr[r]) * gout[p][m][r]);
                 }
             }
+        }
+    }
+    if constexpr (VEC) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < PAIRS / 2; ++it) {
+            const int r = 4 * it + (lane >> 4), b = 2 * (p0 + (r >> 1)) + (r & 1), e0 = 8 * l16;
+            if (p0 + (r >> 1) < npairs && b < B && e0 < n)
+                *reinterpret_cast<uint4 *>(y + ((int64_t)b * H + h) * n + e0) = *reinterpret_cast<const uint4 *>(&st[2][r * 128 + e0]);
         }
     }
 }
@@ -216,9 +273,16 @@ int launch_conv_mfma_256(const void *u, const void *k, const void *g_in, const v
     const int groups = (npairs + c256::PAIRS - 1) / c256::PAIRS;
     const dim3 grid((unsigned)H, (unsigned)((groups + 3) / 4));
     if (grid.y > 65535) return fail(MONARCH_ESHAPE, "batch too large for one launch");
+    const bool vec = n % 8 == 0;
 #define MONARCH_LAUNCH_C256(GI, GO)                                                                                  \
-    hipLaunchKernelGGL((c256::conv256_bf16_kernel<GI, GO>), grid, dim3(256), 0, s, (const bf16_t *)u, (const bf16_t *)k, \
-                       (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen)
+    do {                                                                                                             \
+        if (vec)                                                                                                     \
+            hipLaunchKernelGGL((c256::conv256_bf16_kernel<GI, GO, true>), grid, dim3(256), 0, s, (const bf16_t *)u,  \
+                               (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen); \
+        else                                                                                                         \
+            hipLaunchKernelGGL((c256::conv256_bf16_kernel<GI, GO, false>), grid, dim3(256), 0, s, (const bf16_t *)u, \
+                               (const bf16_t *)k, (const bf16_t *)g_in, (const bf16_t *)g_out, (bf16_t *)y, B, H, n, klen); \
+    } while (0)
     if (g_in && g_out) MONARCH_LAUNCH_C256(true, true);
     else if (g_in) MONARCH_LAUNCH_C256(true, false);
     else if (g_out) MONARCH_LAUNCH_C256(false, true);
