@@ -395,10 +395,10 @@ def widening_cases():
                 return lambda: binding.monarch_matmul3(x, *f, out=y)
             return one
         add("matmul3_f32_b%d_batch_%d" % (b, batch), "general order-3 Monarch product N=%d, fp32, batch %d" % (N, batch), "f32",
-            "mm3 forward", 2 * batch * N * 4 + 3 * N * b * 4, batch * 6.0 * N * b, batch * N, mk_mm3)
-        if batch <= 16384:
+            "mm3b16::forward_kernel" if b == 16 else "mm3::forward_kernel", 2 * batch * N * 4 + 3 * N * b * 4, batch * 6.0 * N * b, batch * N, mk_mm3)
+        if True:
             add("matmul3_backward_f32_b%d_batch_%d" % (b, batch), "gradients of the order-3 Monarch product N=%d, fp32, batch %d" % (N, batch), "f32",
-                "mm3 backward", 3 * batch * N * 4 + 6 * N * b * 4, batch * 16.0 * N * b, batch * N,
+                "mm3b16::backward_kernel (3 launches)" if b == 16 else "mm3::backward_kernel", 3 * batch * N * 4 + 6 * N * b * 4, batch * 16.0 * N * b, batch * N,
                 lambda torch, binding, workloads, rnd, f=mk_mm3: f(torch, binding, workloads, rnd, backward=True))
 
     for rows, factors in ((6144, (64, 32)), (1536, (128, 128))):

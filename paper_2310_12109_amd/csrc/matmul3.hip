@@ -422,6 +422,198 @@ static int launch(const void *x, const void *B1, const void *B2, const void *B3,
     return MONARCH_OK;
 }
 
+
+// ---- b = 16 (N = 4096), gradients, on the matrix cores ------------------------------------------------
+// Two tiles of 4 rows in LDS: `fw` takes x and the forward factors in place, `gr` takes dy (digits reversed, the
+// layout the forward leaves its result in) and the transposed factors in place, last factor first.  Where the
+// gradient of a factor's blocks is formed, its two ingredients sit at the same places of the two tiles:
+//   dB3[(m0,m1)][m2, j0] += g3[m0,m1,m2] t2[m0,m1,j0]      g2 = B3^T g3   (digit of stride 1)
+//   dB2[(m0,j0)][m1, j1] += g2[m0,m1,j0] t1[m0,j1,j0]      g1 = B2^T g2   (digit of stride S1)
+//   dB1[(j0,j1)][m0, j2] += g1[m0,j1,j0] x[j2,j1,j0]       dx = B1^T g1   (digit of stride S2)
+// and the sum over the four rows of a tile is ONE 16x16x4 MFMA per block (A = the gradient's 16 values of the four
+// rows, B = the forward values).  A wave keeps the 16 x 16 sums of its 16 blocks in registers over all tiles of the
+// workgroup and adds them to global memory once at the end (atomics: workgroups share the result).  Registers hold
+// the sums of one factor only, so each factor's gradient is a launch of its own, which recomputes the forward and
+// transposed stages it needs (7 stage passes in all instead of 5).
+constexpr int TVB = 4, NBW = 256 / WAVES;
+constexpr size_t LDS_BYTES_B = sizeof(float) * 2 * TVB * ROWP;
+
+// One factor in place on a tile of TVB rows (columns 4..15 of the MFMA repeat the rows).  TRANS: the transposed
+// block, A[c][r] = W[r][c].
+template <typename T, int SK, bool TRANS, typename At>
+__device__ __forceinline__ void stage4(float *tile, const T *__restrict__ W, int wave, int lane, At at)
+{
+    const int l16 = lane & 15, kg = lane >> 4;
+    float *mine = tile + (l16 & (TVB - 1)) * ROWP;
+    constexpr int G = 4;
+    f32x4 w[2][G];
+    float anchor = 0.0f;
+    auto request = [&](int g, f32x4 (&dst)[G]) {
+        const T *src = W;
+        asm volatile("" : "+s"(src) : "v"(anchor));
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+            const size_t blk = (size_t)(wave * NBW + g * G + u);
+            if constexpr (TRANS) {
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2) dst[u][s2] = to_f32(src[(blk * B + 4 * kg + s2) * B + l16]);   // W[blk][4 kg + s][l16]
+            } else {
+                dst[u] = ld4(src + (blk * B + l16) * B + 4 * kg);                                              // W[blk][l16][4 kg ..]
+            }
+        }
+    };
+    request(0, w[0]);
+#pragma unroll
+    for (int g = 0; g < NBW / G; ++g) {
+        if (g + 1 < NBW / G) request(g + 1, w[(g + 1) & 1]);
+#pragma unroll
+        for (int u = 0; u < G; u += 2) {
+            const int blk = wave * NBW + g * G + u;
+            float *e0 = mine + at(blk >> 4, blk & 15), *e1 = mine + at((blk + 1) >> 4, (blk + 1) & 15);
+            float b0v[4], b1v[4];
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) {
+                b0v[s2] = e0[(4 * kg + s2) * SK];
+                b1v[s2] = e1[(4 * kg + s2) * SK];
+            }
+            f32x4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) {
+                acc0 = mfma(w[g & 1][u][s2], b0v[s2], acc0);
+                acc1 = mfma(w[g & 1][u + 1][s2], b1v[s2], acc1);
+            }
+            if (l16 < TVB) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    e0[(4 * kg + r) * SK] = acc0[r];
+                    e1[(4 * kg + r) * SK] = acc1[r];
+                }
+            }
+            anchor = acc1[0];
+        }
+    }
+}
+
+// sums[u][i] += sum over the tile's rows v of gr_v[r = 4 kg + i] fw_v[c = l16] for block u of this wave
+template <int SK, typename At>
+__device__ __forceinline__ void outer4(const float *gr, const float *fw, f32x4 (&sums)[NBW], int wave, int lane, At at)
+{
+    const int l16 = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int u = 0; u < NBW; ++u) {
+        const int blk = wave * NBW + u;
+        const int off = kg * ROWP + at(blk >> 4, blk & 15) + l16 * SK;   // lane group kg = row kg of the tile
+        sums[u] = mfma(gr[off], fw[off], sums[u]);
+    }
+}
+
+// WHICH = 3, 2: the gradient of that factor's blocks; WHICH = 1: dB1 (if given) and dx (if given).
+template <typename T, int WHICH>
+__global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__ x, const T *__restrict__ B1,
+                                                           const T *__restrict__ B2, const T *__restrict__ B3,
+                                                           const T *__restrict__ dy, T *__restrict__ dx,
+                                                           float *__restrict__ dB, int64_t batch)
+{
+    extern __shared__ __attribute__((aligned(16))) float tiles[];
+    float *fw = tiles, *gr = tiles + TVB * ROWP;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const auto at1 = [](int p, int q) { return q * S1 + p; };         // block (j0, j1), digit of stride S2
+    const auto at2 = [](int p, int q) { return p * S2 + q; };         // block (m0, j0), digit of stride S1
+    const auto at3 = [](int p, int q) { return p * S2 + q * S1; };    // block (m0, m1), digit of stride 1
+    f32x4 sums[NBW];
+#pragma unroll
+    for (int u = 0; u < NBW; ++u) sums[u] = f32x4{0, 0, 0, 0};
+    const bool need_fw = dB != nullptr;
+    const int64_t ntiles = (batch + TVB - 1) / TVB;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t v0 = t * TVB;
+        // rows in (zeros past the end of the batch: they add nothing to the sums)
+#pragma unroll 4
+        for (int it = 0; it < TVB * N / 4 / THREADS; ++it) {
+            const int piece = it * THREADS + threadIdx.x, v = piece / (N / 4), j = 4 * (piece % (N / 4));
+            const bool live = v0 + v < batch;
+            const int64_t r = live ? v0 + v : 0;
+            const int d2 = j >> 8, d1 = (j >> 4) & 15, d0 = j & 15;
+            if (need_fw) {
+                f32x4 val = ld4(x + r * N + j);
+                if (!live) val = f32x4{0, 0, 0, 0};
+                float *d = fw + v * ROWP + d2 * S2 + d1 * S1 + d0;
+                d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+            }
+            f32x4 g = ld4(dy + r * N + j);   // dy[m2 = d2, m1 = d1, m0 = d0 .. d0 + 3] sits at (m0, m1, m2)
+            if (!live) g = f32x4{0, 0, 0, 0};
+            float *e = gr + v * ROWP + d0 * S2 + d1 * S1 + d2;
+            e[0] = g[0]; e[S2] = g[1]; e[2 * S2] = g[2]; e[3 * S2] = g[3];
+        }
+        __syncthreads();
+        if constexpr (WHICH == 3) {
+            stage4<T, S2, false>(fw, B1, wave, lane, at1);
+            __syncthreads();
+            stage4<T, S1, false>(fw, B2, wave, lane, at2);
+            __syncthreads();
+            outer4<1>(gr, fw, sums, wave, lane, at3);
+        } else if constexpr (WHICH == 2) {
+            stage4<T, S2, false>(fw, B1, wave, lane, at1);
+            stage4<T, 1, true>(gr, B3, wave, lane, at3);
+            __syncthreads();
+            outer4<S1>(gr, fw, sums, wave, lane, at2);
+        } else {
+            stage4<T, 1, true>(gr, B3, wave, lane, at3);
+            __syncthreads();
+            stage4<T, S1, true>(gr, B2, wave, lane, at2);
+            __syncthreads();
+            if (dB) outer4<S2>(gr, fw, sums, wave, lane, at1);
+            if (dx) {   // (the blocks of the last transposed factor are the blocks whose sums this wave just formed)
+                stage4<T, S2, true>(gr, B1, wave, lane, at1);
+                __syncthreads();
+#pragma unroll 4
+                for (int it = 0; it < TVB * N / 4 / THREADS; ++it) {
+                    const int piece = it * THREADS + threadIdx.x, v = piece / (N / 4), j = 4 * (piece % (N / 4));
+                    const float *sp = gr + v * ROWP + (j >> 8) * S2 + ((j >> 4) & 15) * S1 + (j & 15);
+                    if (v0 + v < batch) st4(dx + (v0 + v) * N + j, f32x4{sp[0], sp[1], sp[2], sp[3]});
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (dB) {
+        const int l16 = lane & 15, kg = lane >> 4;
+#pragma unroll
+        for (int u = 0; u < NBW; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) atomicAdd(dB + ((size_t)(wave * NBW + u) * B + 4 * kg + i) * B + l16, sums[u][i]);
+    }
+}
+
+template <typename T>
+static int launch_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
+                           float *dB1, float *dB2, float *dB3, int64_t batch, hipStream_t s)
+{
+    if (dB1 || dB2 || dB3)
+        hipLaunchKernelGGL(mm3::fill3_kernel, dim3(64), dim3(256), 0, s, dB1, dB2, dB3, (size_t)N * B);
+    if (batch > 0) {
+        int ncu = 0;
+        if (int rc = mm3::compute_units(&ncu)) return rc;
+        const int64_t ntiles = (batch + TVB - 1) / TVB;
+        int64_t grid = ncu;   // one workgroup (two tiles, 150 KB of LDS) per compute unit
+        if (grid > ntiles) grid = ntiles;
+#define MONARCH_LAUNCH_MM3B16(WHICHV, DXV, DBV)                                                                    \
+    do {                                                                                                           \
+        auto kern = backward_kernel<T, WHICHV>;                                                                    \
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
+                                              (int)LDS_BYTES_B));                                                  \
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), LDS_BYTES_B, s, (const T *)x, (const T *)B1, \
+                           (const T *)B2, (const T *)B3, (const T *)dy, (T *)(DXV), (float *)(DBV), batch);        \
+    } while (0)
+        if (dB3) MONARCH_LAUNCH_MM3B16(3, nullptr, dB3);
+        if (dB2) MONARCH_LAUNCH_MM3B16(2, nullptr, dB2);
+        if (dB1 || dx) MONARCH_LAUNCH_MM3B16(1, dx, dB1);
+#undef MONARCH_LAUNCH_MM3B16
+    }
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
 }  // namespace mm3b16
 
 bool matmul3_fits(int b) { return b >= 1 && b <= 16; }   // four rows of b^3 floats in 64 KB of LDS
@@ -441,6 +633,10 @@ int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3
 int launch_matmul3_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
                             float *dB1, float *dB2, float *dB3, int64_t batch, int b, monarch_dtype dt, hipStream_t s)
 {
+    if (b == 16) {
+        if (dt == MONARCH_F32) return mm3b16::launch_backward<float>(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, s);
+        return mm3b16::launch_backward<bf16_t>(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, s);
+    }
     if (dt == MONARCH_F32) return mm3::launch_backward<float>(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, b, s);
     return mm3::launch_backward<bf16_t>(x, B1, B2, B3, dy, dx, dB1, dB2, dB3, batch, b, s);
 }

@@ -87,6 +87,29 @@ def test_backward_fp32(mm, b, batch):
     assert all(g.dtype == torch.float32 for g in got[1:])
 
 
+@pytest.mark.parametrize("batch", [1, 4, 9, 1030])
+def test_backward_b16_on_the_matrix_cores(mm, batch):
+    # tiles of four rows: a lone row, one full tile, a ragged tail, several tiles per workgroup
+    announce("matmul3 backward fp32 b=16 batch", batch)
+    w = workloads.monarch_matmul3_inputs(batch, 16, seed=200 + batch)
+    got = mm.monarch_matmul3_backward(*_f(w), dev(w["dy"]))
+    want = order3.matmul3_backward(w["x"], w["B1"], w["B2"], w["B3"], w["dy"])
+    for g, x in zip(got, want):
+        assert rel_l2(host(g), x) <= TOL_F32
+
+
+def test_backward_b16_bf16_and_partial_outputs(mm):
+    announce("matmul3 backward bf16 b=16, partial outputs")
+    w = workloads.monarch_matmul3_inputs(11, 16, seed=31, bf16=True)
+    want = order3.matmul3_backward(w["x"], w["B1"], w["B2"], w["B3"], w["dy"])
+    got = mm.monarch_matmul3_backward(*_f(w, True), dev(w["dy"], True))
+    assert got[0].dtype == torch.bfloat16 and rel_l2(host(got[0]), want[0]) <= TOL_BF16
+    for g, x in zip(got[1:], want[1:]):
+        assert rel_l2(host(g), x) <= TOL_F32 * 10
+    dx, d1, d2, d3 = mm.monarch_matmul3_backward(*_f(w, True), dev(w["dy"], True), need_dB=False)
+    assert d1 is None and d2 is None and d3 is None and rel_l2(host(dx), want[0]) <= TOL_BF16
+
+
 def test_backward_bf16(mm):
     announce("matmul3 backward bf16 b=8")
     w = workloads.monarch_matmul3_inputs(17, 8, seed=3, bf16=True)
