@@ -312,6 +312,37 @@ def widening_cases():
             add("c1_backward_%s_batch_%d" % (dn, batch), "gradients of the order-2 Monarch matmul N=256, %s, batch %d" % (dn, batch), dn,
                 "matmul_backward_b16_kernel", 3 * batch * 256 * es + 2 * 4096 * (es + 4), batch * 10.0 * 256 * 16, batch * 256, mk_bwd)
 
+    # square products and the mixer with blocks of 32 and 64 (N = 1024, 4096): in place on LDS tiles, fp32 MFMA
+    for b, B in ((32, 128), (64, 32)):
+        for dn in ("f32", "bf16"):
+            es = 4 if dn == "f32" else 2
+            N, rows = b * b, B * 768
+
+            def mk_mm_b(torch, binding, workloads, rnd, b=b, N=N, rows=rows, dn=dn):
+                dt = tdt(torch, dn)
+                R, L = rnd(b, b, b, dt=dt, scale=b ** -0.5), rnd(b, b, b, dt=dt, scale=b ** -0.5)
+
+                def one():
+                    x = rnd(rows, N, dt=dt)
+                    y = torch.empty_like(x)
+                    return lambda: binding.monarch_matmul(x, R, L, out=y)
+                return one
+
+            def mk_mixer_b(torch, binding, workloads, rnd, b=b, N=N, B=B, dn=dn):
+                dt = tdt(torch, dn)
+                K = rnd(768, N, dt=dt)
+                f = [rnd(b, b, b, dt=dt, scale=b ** -0.5) for _ in range(4)]
+
+                def one():
+                    u, gi, go = (rnd(B, 768, N, dt=dt) for _ in range(3))
+                    y = torch.empty_like(u)
+                    return lambda: binding.monarch_mixer(u, K, gi, go, *f, out=y)
+                return one
+            add("matmul_%s_b%d_batch_%d" % (dn, b, rows), "order-2 Monarch matmul N=%d (%d blocks of %dx%d), %s, batch %d" % (N, b, b, b, dn, rows),
+                dn, "inpl::matmul_kernel<%d>" % b, (2 * rows * N + 2 * b ** 3) * es, rows * 4.0 * N * b, rows * N, mk_mm_b)
+            add("mixer_%s_b%d_B%d" % (dn, b, B), "learned-Monarch sequence mixer N=%d, B=%d H=768, %s" % (N, B, dn), dn,
+                "inpl::mixer_kernel<%d>" % b, (4 * rows * N + 768 * N + 4 * b ** 3) * es, rows * 8.0 * N * b, rows * N, mk_mixer_b)
+
     for B in (8, 1024):
         for dn in ("f32", "bf16"):
             es = 4 if dn == "f32" else 2

@@ -140,6 +140,8 @@ int monarch_matmul(const void *x, const void *R, const void *L, void *y, int64_t
         return fail(MONARCH_EINVAL, "y overlaps x");
     if (matmul_mfma_b16_supported(nbR, r_out, r_in, nbL, l_out, l_in, dt))
         return launch_matmul_mfma_b16(x, R, L, y, batch, dt, (hipStream_t)stream);
+    if (nbR == r_out && nbR == r_in && nbR == nbL && nbR == l_out && nbR == l_in && monarch_inplace_supported(nbR, dt))
+        return launch_matmul_inplace(x, R, L, y, batch, nbR, dt, (hipStream_t)stream);   // square, blocks of 32 or 64
     return launch_matmul_generic(x, R, L, nullptr, y, batch, nbR, r_out, r_in, nbL, l_out, l_in, 2, 0,
                                  dt, dt, dt, (hipStream_t)stream);
 }

@@ -87,6 +87,12 @@ bool matmul_backward_fits(int nbR, int r_out, int r_in, int nbL, int l_out, int 
 int launch_matmul_backward(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR,
                            float *dL, int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
                            monarch_dtype dt, hipStream_t s);
+// square order-2 products with blocks of 32 or 64, in place on LDS tiles, fp32 MFMA (csrc/monarch_inplace.hip):
+// the plain product and the gated mixer (g_in, g_out may be null); fp32 or bf16 tensors
+bool monarch_inplace_supported(int bs, monarch_dtype dt);
+int launch_matmul_inplace(const void *x, const void *R, const void *L, void *y, int64_t batch, int bs, monarch_dtype dt, hipStream_t s);
+int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
+                         const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
 // sequence mixer with two general square order-2 Monarch matrices (csrc/mixer.hip); g_in, g_out may be null
 struct MixOpt {
     int act = 0;             // between the kernel product and the second matrix: 0 none, 1 ReLU

@@ -41,6 +41,16 @@ def test_square_other_block_sizes(mm, b):
     assert rel_l2(y, oracle.matmul(w["x"], w["R"], w["L"])) <= TOL_F32
 
 
+@pytest.mark.parametrize("b,batch,bf16", [(32, 1, False), (32, 16, False), (32, 1100, False), (64, 8, False), (64, 523, False),
+                                          (32, 77, True), (64, 77, True)])
+def test_square_blocks_of_32_and_64_in_place_on_the_matrix_cores(mm, b, batch, bf16):
+    # tiles of 16 (b = 32) or 8 (b = 64) rows: one row, one tile, ragged tails, more tiles than workgroups
+    announce("matmul in place b, batch, bf16", b, batch, bf16)
+    w = workloads.monarch_matmul_inputs(batch=batch, b=b, seed=b + batch, bf16=bf16)
+    y = host(mm.monarch_matmul(dev(w["x"], bf16), dev(w["R"], bf16), dev(w["L"], bf16)))
+    assert rel_l2(y, oracle.matmul(w["x"], w["R"], w["L"])) <= (TOL_BF16 if bf16 else TOL_F32)
+
+
 @pytest.mark.parametrize("shape", [(4, 3, 2, 2, 5, 6), (4, 192, 192, 4, 768, 192), (4, 192, 768, 4, 192, 192),
                                    (16, 64, 64, 16, 256, 64), (3, 7, 5, 7, 2, 3)])
 def test_rectangular_fp32(mm, shape):

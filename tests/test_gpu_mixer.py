@@ -66,6 +66,16 @@ def test_other_block_sizes_fp32(mm, b):
     assert rel_l2(host(_run(mm, w)), _want(w)) <= TOL_F32
 
 
+@pytest.mark.parametrize("b,B,H,gates,bf16", [(32, 7, 5, (True, True), False), (32, 40, 13, (False, True), False),
+                                              (32, 9, 4, (True, False), True), (64, 3, 7, (True, True), False),
+                                              (64, 5, 9, (False, False), False), (64, 4, 6, (True, True), True)])
+def test_blocks_of_32_and_64_in_place_on_the_matrix_cores(mm, b, B, H, gates, bf16):
+    # ragged tiles whose rows change channel, each gate combination, fp32 and bf16 tensors
+    announce("mixer in place b, B, H, gates, bf16", b, B, H, gates, bf16)
+    w = workloads.mixer_inputs(B, H, b, seed=b + B + H, gates=gates, bf16=bf16)
+    assert rel_l2(host(_run(mm, w, bf16)), _want(w)) <= (TOL_BF16 if bf16 else TOL_F32)
+
+
 @pytest.mark.parametrize("b", [4, 16, 32])
 def test_bf16(mm, b):
     announce("mixer bf16 b", b)
