@@ -64,3 +64,31 @@ def mixer_backward(u, K, g_in, g_out, R1, L1, R2, L2, dy):
     out["du"] = da * gi if gi is not None else da
     out["dg_in"] = da * u if gi is not None else None
     return out
+
+
+def hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, nfft=None, causal=True):
+    """The paper's gated-convolution layer (appendix algorithm "M2 Hyena layer with heads" at head dimension 1; with
+    causal=False the bidirectional gated convolution of the M2-BERT sequence mixer), step by step in float64:
+        [X1; X2; V] = W_in u_t + b_in                 three projections of every position (W_in: (3d, d))
+        X1~, X2~, V~ = short causal depthwise convolutions along the sequence (k_short: (3d, ks)):
+                       x~[c, t] = sum_tau k_short[c, tau] x[c, t - tau]
+        O = X1~ o conv(k_long, X2~ o V~)              the gated long convolution, one kernel row per feature
+        y_t = W_out O[:, t] + b_out
+    u: (B, n, d); returns (B, n, d).  The long convolution is oracle.causal_conv (the direct sum)."""
+    from . import causal_conv
+    u = np.asarray(u, dtype=np.float64)
+    B, n, d = u.shape
+    W_in, W_out = np.asarray(W_in, dtype=np.float64), np.asarray(W_out, dtype=np.float64)
+    proj = np.einsum("cj,btj->bct", W_in, u)                           # (B, 3d, n)
+    if b_in is not None:
+        proj = proj + np.asarray(b_in, dtype=np.float64)[None, :, None]
+    ks = np.asarray(k_short, dtype=np.float64)
+    short = np.zeros_like(proj)
+    for tau in range(ks.shape[1]):                                     # x~[c, t] += k[c, tau] x[c, t - tau]
+        short[:, :, tau:] += ks[None, :, tau, None] * proj[:, :, :n - tau]
+    x1, x2, v = short[:, :d], short[:, d:2 * d], short[:, 2 * d:]
+    o = causal_conv(v, k_long, x2, x1, nfft=nfft, causal=causal)       # (B, d, n)
+    y = np.einsum("cj,bjt->btc", W_out, o)
+    if b_out is not None:
+        y = y + np.asarray(b_out, dtype=np.float64)[None, None, :]
+    return y

@@ -1,0 +1,79 @@
+"""Pins of the oracle of the gated-convolution layer (appendix algorithm "M2 Hyena layer with heads" at head
+dimension 1; Sec. 5's bidirectional gated convolution of M2-BERT with causal=False) against what does not depend on
+its code: a torch float64 composition with library convolutions, reductions to the gated convolution, causality,
+linearity in the value path, and a planted swap of the two gates."""
+import numpy as np
+import torch
+
+import oracle
+from oracle import layer
+from paper_2310_12109_amd import workloads
+
+
+def _inputs(B=2, n=24, d=6, ks=3, seed=0, bias=True):
+    w = workloads.hyena_layer_inputs(B, n, d, ks=ks, seed=seed, bias=bias)
+    return {k: (None if v is None else v.astype(np.float64)) for k, v in w.items()}
+
+
+def _run(w, **kw):
+    return layer.hyena_layer(w["u"], w["W_in"], w["b_in"], w["k_short"], w["k_long"], w["W_out"], w["b_out"], **kw)
+
+
+def test_against_torch_linear_and_library_convolutions():
+    # torch.nn.functional.linear for the projections, torch conv1d (a correlation: kernels flipped) with left padding for
+    # the short depthwise convolution, numpy.convolve for the long one
+    w = _inputs()
+    B, n, d = w["u"].shape
+    t = {k: (None if v is None else torch.from_numpy(v)) for k, v in w.items()}
+    proj = torch.nn.functional.linear(t["u"], t["W_in"], t["b_in"]).transpose(1, 2)            # (B, 3d, n)
+    ks = t["k_short"].shape[1]
+    short = torch.nn.functional.conv1d(torch.nn.functional.pad(proj, (ks - 1, 0)), t["k_short"].flip(1)[:, None, :], groups=3 * d)
+    x1, x2, v = short[:, :d].numpy(), short[:, d:2 * d].numpy(), short[:, 2 * d:].numpy()
+    o = np.empty((B, d, n))
+    for b in range(B):
+        for c in range(d):
+            o[b, c] = x1[b, c] * np.convolve(x2[b, c] * v[b, c], w["k_long"][c])[:n]
+    want = torch.nn.functional.linear(torch.from_numpy(o).transpose(1, 2), t["W_out"], t["b_out"]).numpy()
+    np.testing.assert_allclose(_run(w), want, rtol=1e-10, atol=1e-10)
+
+
+def test_diagonal_projections_and_delta_short_kernels_leave_the_gated_convolution():
+    B, n, d = 2, 16, 4
+    rng = np.random.default_rng(1)
+    u = rng.standard_normal((B, n, d))
+    a, b, c = (rng.standard_normal(d) for _ in range(3))
+    # X1 = a o u, X2 = b o u, V = c o u (per feature); the short kernels are deltas; W_out is the identity
+    W_in = np.concatenate([np.diag(a), np.diag(b), np.diag(c)])
+    k_short = np.zeros((3 * d, 3)); k_short[:, 0] = 1.0
+    k_long = rng.standard_normal((d, n))
+    y = layer.hyena_layer(u, W_in, None, k_short, k_long, np.eye(d), None)
+    ut = u.transpose(0, 2, 1)
+    want = oracle.causal_conv(c[None, :, None] * ut, k_long, b[None, :, None] * ut, a[None, :, None] * ut)
+    np.testing.assert_allclose(y, want.transpose(0, 2, 1), rtol=1e-12, atol=1e-12)
+
+
+def test_causal_layer_does_not_look_ahead_and_the_bidirectional_one_does():
+    w = _inputs(B=1, n=20, d=5, seed=3)
+    y0 = _run(w)
+    w2 = dict(w); w2["u"] = w["u"].copy(); w2["u"][0, 12:] += 1.0
+    y1 = _run(w2)
+    np.testing.assert_array_equal(y0[0, :12], y1[0, :12])
+    assert np.abs(y0[0, 12:] - y1[0, 12:]).max() > 1e-3
+    # circular (bidirectional) form with a kernel that has negative lags at its end: position 0 sees the future
+    kb = np.zeros((5, 40)); kb[:, -3:] = 1.0
+    w3 = dict(w); w3["k_long"] = kb
+    w4 = dict(w2); w4["k_long"] = kb
+    a, b = _run(w3, nfft=40, causal=False), _run(w4, nfft=40, causal=False)
+    assert np.abs(a[0, 9:12] - b[0, 9:12]).max() > 1e-3
+
+
+def test_linear_in_the_value_projection_and_the_swapped_gates_are_seen():
+    w = _inputs(seed=5, bias=False)
+    d = w["u"].shape[2]
+    y = _run(w)
+    w2 = dict(w); w2["W_in"] = w["W_in"].copy(); w2["W_in"][2 * d:] *= -2.5      # V -> -2.5 V
+    np.testing.assert_allclose(_run(w2), -2.5 * y, rtol=1e-10, atol=1e-12)
+    # the gate before the long convolution is X2, the one after it X1: swapping their projections changes the result
+    w3 = dict(w); w3["W_in"] = np.concatenate([w["W_in"][d:2 * d], w["W_in"][:d], w["W_in"][2 * d:]])
+    w3["k_short"] = np.concatenate([w["k_short"][d:2 * d], w["k_short"][:d], w["k_short"][2 * d:]])
+    assert np.abs(_run(w3) - y).max() > 1e-2
