@@ -432,6 +432,28 @@ def widening_cases():
                 "mm3b16::backward_kernel (3 launches)" if b == 16 else "mm3::backward_kernel", 3 * batch * N * 4 + 6 * N * b * 4, batch * 16.0 * N * b, batch * N,
                 lambda torch, binding, workloads, rnd, f=mk_mm3: f(torch, binding, workloads, rnd, backward=True))
 
+    # the gated-convolution layer at the shape of config 2 (B = 8, n = 1024, d = 768): four dense projections (rocBLAS),
+    # the short convolutions and the fused long convolution
+    for dn in ("bf16", "f32"):
+        es = 4 if dn == "f32" else 2
+        B, n, d = 8, 1024, 768
+
+        def mk_hy(torch, binding, workloads, rnd, dn=dn, B=B, n=n, d=d):
+            dt = tdt(torch, dn)
+            W_in, W_out = rnd(3 * d, d, dt=dt, scale=d ** -0.5), rnd(d, d, dt=dt, scale=d ** -0.5)
+            b_in, b_out = rnd(3 * d, dt=dt, scale=.1), rnd(d, dt=dt, scale=.1)
+            k_short, k_long = rnd(3 * d, 3, dt=dt, scale=.5), rnd(d, n, dt=dt, scale=.1)
+            ws = torch.empty(max(16, binding.monarch_hyena_layer_workspace_bytes(B, n, d, n, (64, 32), dt)), dtype=torch.uint8, device="cuda")
+
+            def one():
+                u = rnd(B, n, d, dt=dt)
+                y = torch.empty_like(u)
+                return lambda: binding.monarch_hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, (64, 32), ws=ws, out=y)
+            return one
+        add("hyena_layer_%s_B8_n1024_d768" % dn, "gated-convolution layer (projections, short convs, gated long conv) B=8 n=1024 d=768, %s" % dn,
+            dn, "rocBLAS GEMM x 4 + short_conv_kernel + conv2048 kernel", (2 * B * n * d + 4 * d * d + d * n) * es,
+            8.0 * B * n * d * d, B * n * d, mk_hy, bound="mfma", mfma_peak=MFMA_BF16_TFLOPS if dn == "bf16" else MFMA_F32_TFLOPS)
+
     for rows, factors in ((6144, (64, 32)), (1536, (128, 128))):
         N = factors[0] * factors[1]
         for inverse in (False, True):

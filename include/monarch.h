@@ -182,6 +182,28 @@ int monarch_m2_layer(const void *x, void *y, int64_t B, int bn, int bd,
 size_t monarch_m2_layer_workspace_bytes(int64_t B, int n, int d, monarch_dtype dt);
 
 /*
+ * The gated-convolution layer of the paper's models (appendix algorithm "M2 Hyena layer with heads" at head
+ * dimension 1; with causal = 0 the bidirectional gated convolution of the M2-BERT sequence mixer, Sec. 5):
+ *   [X1; X2; V] = W_in u[b,t,:] + b_in            W_in: (3d, d), rows 0..d-1 give X1, d..2d-1 X2, 2d..3d-1 V
+ *   X1~, X2~, V~: x~[c,t] = sum_{tau < taps} k_short[c,tau] x[c,t-tau]   (causal depthwise, k_short: (3d, taps))
+ *   O = X1~ o conv(k_long, X2~ o V~)              monarch_causal_conv over the sequence, k_long: (d, klen),
+ *                                                 nfft / factors / causal as there
+ *   y[b,t,:] = W_out O[b,:,t] + b_out             W_out: (d, d)
+ * u, y: (B, n, d); everything of type dt (MONARCH_F32 or MONARCH_BF16, fp32 accumulation); b_in, b_out may be
+ * NULL.  n a multiple of 8, 1 <= taps <= 8.  The dense projections are plain GEMMs and run in rocBLAS, which the
+ * library loads on the first call of this entry point (MONARCH_EHIP if it cannot); that library may allocate
+ * device memory of its own on first use.  ws: monarch_hyena_layer_workspace_bytes.
+ * Errors: EINVAL (null or misaligned pointer, overlap), ESHAPE (as monarch_causal_conv; n not a multiple of 8;
+ * taps outside [1, 8]), EDTYPE, EWORKSPACE, EHIP.
+ */
+int monarch_hyena_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long,
+                        const void *W_out, const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft,
+                        const int *factors, int nf, int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
+                        monarch_stream_t stream);
+size_t monarch_hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf,
+                                           monarch_dtype dt);
+
+/*
  * Convolution with a polynomial-parameterised ("blocky") Monarch matrix (appendix: the blocky Monarch algorithm,
  * the masking lemma for causality, the blocky Monarch convolution and its causality theorem).
  *

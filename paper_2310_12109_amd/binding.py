@@ -43,6 +43,9 @@ _lib.monarch_mixer_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i]
 _lib.monarch_m2_layer.argtypes = [_vp, _vp, _i64, _i, _i] + [_vp] * 12 + [ctypes.c_float, _i, _i, _vp, _sz, _vp]
 _lib.monarch_m2_layer_workspace_bytes.restype = _sz
 _lib.monarch_m2_layer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
+_lib.monarch_hyena_layer.argtypes = [_vp] * 8 + [_i] * 6 + [_vp, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_hyena_layer_workspace_bytes.restype = _sz
+_lib.monarch_hyena_layer_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _vp, _i, _i]
 _lib.monarch_mixer.argtypes = [_vp] * 9 + [_i64, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_mixer_workspace_bytes.restype = _sz
 _lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
@@ -70,7 +73,7 @@ EXPORTS = [
     "monarch_matmul3", "monarch_matmul3_backward",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
     "monarch_mixer_backward", "monarch_mixer_backward_workspace_bytes",
-    "monarch_m2_layer", "monarch_m2_layer_workspace_bytes",
+    "monarch_m2_layer", "monarch_m2_layer_workspace_bytes", "monarch_hyena_layer", "monarch_hyena_layer_workspace_bytes",
     "monarch_blocky_state_bytes", "monarch_blocky_state_offsets", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes", "monarch_causal_conv_static",
@@ -223,6 +226,33 @@ def monarch_m2_layer(x, seq, n_kernel, dim, d_kernel, gamma, beta, eps=1e-5, act
     _check(_lib.monarch_m2_layer(_ptr(x), _ptr(y), B, bn, bd, *(_ptr(t) for t in seq), _ptr(n_kernel),
                                  *(_ptr(t) for t in dim), _ptr(d_kernel), _ptr(gamma), _ptr(beta), eps, act, _dt(x),
                                  _ptr(ws), wsb, _stream()))
+    return y
+
+
+def monarch_hyena_layer_workspace_bytes(B, n, d, klen, factors, torch_dtype):
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[torch_dtype]
+    return _lib.monarch_hyena_layer_workspace_bytes(B, n, d, klen, nfft, f, nf, dt)
+
+
+def monarch_hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, factors, causal=True, ws=None, out=None):
+    """W_out (X1~ * conv(k_long, X2~ * V~)) + b_out with [X1; X2; V] = W_in u + b_in passed through short causal
+    depthwise convolutions; u: (B, n, d)."""
+    B, n, d = u.shape
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    taps, klen = k_short.shape[1], k_long.shape[1]
+    y = out if out is not None else torch.empty_like(u)
+    need = _lib.monarch_hyena_layer_workspace_bytes(B, n, d, klen, nfft, f, nf, _dt(u))
+    ws, wsb = _workspace(max(need, 16), ws, u.device)
+    _check(_lib.monarch_hyena_layer(_ptr(u), _ptr(W_in), _ptr(b_in), _ptr(k_short), _ptr(k_long), _ptr(W_out), _ptr(b_out),
+                                    _ptr(y), B, n, d, taps, klen, nfft, f, nf, 1 if causal else 0, _dt(u), _ptr(ws), wsb,
+                                    _stream()))
     return y
 
 

@@ -1,0 +1,190 @@
+// The gated-convolution layer of the paper's models (appendix algorithm "M2 Hyena layer with heads" at head
+// dimension 1; with causal = 0 the bidirectional gated convolution of the M2-BERT sequence mixer, Sec. 5):
+//   [X1; X2; V] = W_in u_t + b_in                      three dense projections of every position
+//   X1~, X2~, V~ = short causal depthwise convolutions along the sequence
+//   O = X1~ o conv(k_long, X2~ o V~)                   monarch_causal_conv with X2~ as input gate and X1~ as output gate
+//   y_t = W_out O[:, t] + b_out
+// The dense projections are plain GEMMs and go to rocBLAS (loaded on first use: the rest of the library does not
+// depend on it), written so that their results land in the (B, d, n) layout of the convolution and back in
+// (B, n, d) without a transpose pass; the short convolutions (with the projection bias) are one memory-bound kernel;
+// the long convolution is the library's own entry point.
+#include <dlfcn.h>
+#include <mutex>
+
+#include <rocblas/rocblas.h>
+
+#include "kernels.h"
+#include "monarch.h"
+
+namespace monarch {
+
+namespace hyena {
+
+struct Blas {
+    void *so = nullptr;
+    decltype(&rocblas_create_handle) create = nullptr;
+    decltype(&rocblas_set_stream) set_stream = nullptr;
+    decltype(&rocblas_gemm_strided_batched_ex) gemm = nullptr;
+    rocblas_handle handle[16] = {};
+};
+static Blas g_blas;
+static std::mutex g_blas_mutex;
+
+// the handle of the current device (created once per device), or null with the error text set
+static rocblas_handle blas_handle()
+{
+    std::lock_guard<std::mutex> lock(g_blas_mutex);
+    if (!g_blas.so) {
+        void *so = dlopen("librocblas.so", RTLD_NOW | RTLD_LOCAL);
+        if (!so) so = dlopen("/opt/rocm/lib/librocblas.so", RTLD_NOW | RTLD_LOCAL);
+        if (!so) {
+            fail(MONARCH_EHIP, "the dense projections need rocBLAS, which could not be loaded: %s", dlerror());
+            return nullptr;
+        }
+        g_blas.create = (decltype(g_blas.create))dlsym(so, "rocblas_create_handle");
+        g_blas.set_stream = (decltype(g_blas.set_stream))dlsym(so, "rocblas_set_stream");
+        g_blas.gemm = (decltype(g_blas.gemm))dlsym(so, "rocblas_gemm_strided_batched_ex");
+        if (!g_blas.create || !g_blas.set_stream || !g_blas.gemm) {
+            fail(MONARCH_EHIP, "rocBLAS lacks an entry point the dense projections need");
+            return nullptr;
+        }
+        g_blas.so = so;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) {
+        fail(MONARCH_EHIP, "no current device for the dense projections");
+        return nullptr;
+    }
+    if (!g_blas.handle[dev] && g_blas.create(&g_blas.handle[dev]) != rocblas_status_success) {
+        g_blas.handle[dev] = nullptr;
+        fail(MONARCH_EHIP, "rocblas_create_handle failed");
+        return nullptr;
+    }
+    return g_blas.handle[dev];
+}
+
+// C (row-major, per batch entry) = op over row-major operands, as one strided-batched GEMM in rocBLAS's
+// column-major terms.  All of type dt, fp32 accumulation.
+static int gemm(rocblas_handle h, rocblas_operation ta, rocblas_operation tb, int m, int n, int k, const void *a, int lda,
+                int64_t sa, const void *b, int ldb, int64_t sb, float beta, void *c, int ldc, int64_t sc, int batch,
+                monarch_dtype dt)
+{
+    const float alpha = 1.0f;
+    const rocblas_datatype t = dt == MONARCH_F32 ? rocblas_datatype_f32_r : rocblas_datatype_bf16_r;
+    const rocblas_status st = g_blas.gemm(h, ta, tb, m, n, k, &alpha, a, t, lda, sa, b, t, ldb, sb, &beta, c, t, ldc, sc, c, t, ldc,
+                                          sc, batch, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
+    if (st != rocblas_status_success) return fail(MONARCH_EHIP, "rocBLAS GEMM failed with status %d", (int)st);
+    return MONARCH_OK;
+}
+
+// out[r][t] = sum_tau ks[row kernel][tau] (in[r][t - tau] + bias[row kernel]), rows r = (i, b, c) of the (3, B, d, n)
+// tensor with kernel / bias row i d + c; 8 consecutive t per thread, the taps before them from the preceding piece.
+template <typename T>
+__global__ __launch_bounds__(256) void short_conv_kernel(const T *__restrict__ in, T *__restrict__ out, const T *__restrict__ ks,
+                                                         const T *__restrict__ bias, int64_t rows, int Bd, int d, int n, int taps)
+{
+    const int pieces = n / 8;
+    const int64_t total = rows * pieces;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = idx / pieces;
+        const int p = (int)(idx - r * pieces);
+        const int kr = (int)(r / Bd) * d + (int)(r % d);   // r = (i B + b) d + c  ->  i d + c
+        float w[8], x[16];
+#pragma unroll
+        for (int tau = 0; tau < 8; ++tau) w[tau] = tau < taps ? to_f32(ks[(int64_t)kr * taps + tau]) : 0.0f;
+        const float bv = bias ? to_f32(bias[kr]) : 0.0f;
+        const T *src = in + r * n + 8 * p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            x[8 + e] = to_f32(src[e]) + bv;
+            x[e] = p > 0 ? to_f32(src[e - 8]) + bv : 0.0f;   // positions before the start of the row contribute nothing
+        }
+        T o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int tau = 0; tau < 8; ++tau) acc = fmaf(w[tau], x[8 + e - tau], acc);
+            o[e] = from_f32<T>(acc);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[r * n + 8 * p + e] = o[e];
+    }
+}
+
+// y[b][t][c] = bias[c] (the output projection then accumulates onto it)
+template <typename T>
+__global__ __launch_bounds__(256) void bias_rows_kernel(T *__restrict__ y, const T *__restrict__ bias, int64_t total, int d)
+{
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x)
+        y[idx] = bias[idx % d];
+}
+
+template <typename T>
+static int run(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long, const void *W_out,
+               const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft, const int *factors, int nf, int causal,
+               monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    rocblas_handle h = blas_handle();
+    if (!h) return MONARCH_EHIP;
+    if (g_blas.set_stream(h, s) != rocblas_status_success) return fail(MONARCH_EHIP, "rocblas_set_stream failed");
+    const size_t es = sizeof(T);
+    const int64_t plane = (int64_t)B * d * n;              // one (B, d, n) tensor
+    char *base = (char *)ws;
+    T *proj = (T *)base, *shrt = (T *)(base + align_up(3 * plane * es, 256)), *o = (T *)(base + 2 * align_up(3 * plane * es, 256));
+    char *conv_ws = base + 2 * align_up(3 * plane * es, 256) + align_up(plane * es, 256);
+    const size_t conv_ws_bytes = ws_bytes - (size_t)(conv_ws - base);
+
+    // 1. projections: proj[i][b] (d x n) = W_in[i d .. (i + 1) d) (d x d) times u[b]^T
+    for (int i = 0; i < 3; ++i) {
+        int rc = gemm(h, rocblas_operation_transpose, rocblas_operation_none, n, d, d, u, d, (int64_t)n * d,
+                      (const T *)W_in + (int64_t)i * d * d, d, 0, 0.0f, proj + i * plane, n, (int64_t)d * n, B, dt);
+        if (rc) return rc;
+    }
+    // 2. short depthwise convolutions (with the projection bias)
+    {
+        const int64_t rows = (int64_t)3 * B * d, total = rows * (n / 8);
+        const int64_t blocks = (total + 255) / 256;
+        hipLaunchKernelGGL(short_conv_kernel<T>, dim3((unsigned)(blocks > 65536 ? 65536 : blocks)), dim3(256), 0, s, proj, shrt,
+                           (const T *)k_short, (const T *)b_in, rows, B * d, d, n, taps);
+        MONARCH_HIP_CHECK(hipGetLastError());
+    }
+    // 3. O = X1~ o conv(k_long, X2~ o V~)
+    {
+        int rc = monarch_causal_conv(shrt + 2 * plane, k_long, shrt + plane, shrt, o, B, d, n, klen, nfft, factors, nf, causal, dt, conv_ws,
+                                     conv_ws_bytes, (monarch_stream_t)s);
+        if (rc) return rc;
+    }
+    // 4. y[b] (n x d) = O[b]^T W_out^T (+ b_out, put there first)
+    float beta = 0.0f;
+    if (b_out) {
+        const int64_t total = (int64_t)B * n * d, blocks = (total + 255) / 256;
+        hipLaunchKernelGGL(bias_rows_kernel<T>, dim3((unsigned)(blocks > 65536 ? 65536 : blocks)), dim3(256), 0, s, (T *)y, (const T *)b_out,
+                           total, d);
+        MONARCH_HIP_CHECK(hipGetLastError());
+        beta = 1.0f;
+    }
+    return gemm(h, rocblas_operation_transpose, rocblas_operation_transpose, d, n, d, W_out, d, 0, o, n, (int64_t)d * n, beta, y, d,
+                (int64_t)n * d, B, dt);
+}
+
+}  // namespace hyena
+
+size_t hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, monarch_dtype dt)
+{
+    const size_t es = dtype_size(dt), plane = (size_t)B * d * n * es;
+    return 2 * align_up(3 * plane, 256) + align_up(plane, 256) + monarch_causal_conv_workspace_bytes(B, d, n, klen, nfft, factors, nf, dt);
+}
+
+int launch_hyena_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long, const void *W_out,
+                       const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft, const int *factors, int nf,
+                       int causal, monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    if (dt == MONARCH_F32)
+        return hyena::run<float>(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, dt, ws,
+                                 ws_bytes, s);
+    return hyena::run<bf16_t>(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, dt, ws,
+                              ws_bytes, s);
+}
+
+}  // namespace monarch
