@@ -77,8 +77,38 @@ static int gemm(rocblas_handle h, rocblas_operation ta, rocblas_operation tb, in
     return MONARCH_OK;
 }
 
+// eight consecutive elements with 16-byte accesses (p 16-byte aligned)
+__device__ __forceinline__ void load8(const float *p, float (&v)[8])
+{
+    const float4 a = reinterpret_cast<const float4 *>(p)[0], b = reinterpret_cast<const float4 *>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, float (&v)[8])
+{
+    const uint4 w = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[2 * e] = __uint_as_float(d[e] << 16);
+        v[2 * e + 1] = __uint_as_float(d[e] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void store8(float *p, const float (&v)[8])
+{
+    reinterpret_cast<float4 *>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4 *>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t *p, const float (&v)[8])
+{
+    bf16_t h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = from_f32<bf16_t>(v[e]);
+    *reinterpret_cast<uint4 *>(p) = *reinterpret_cast<const uint4 *>(h);
+}
+
 // out[r][t] = sum_tau ks[row kernel][tau] (in[r][t - tau] + bias[row kernel]), rows r = (i, b, c) of the (3, B, d, n)
-// tensor with kernel / bias row i d + c; 8 consecutive t per thread, the taps before them from the preceding piece.
+// tensor with kernel / bias row i d + c; 8 consecutive t per thread (16-byte accesses), the taps before them from the
+// preceding piece.
 template <typename T>
 __global__ __launch_bounds__(256) void short_conv_kernel(const T *__restrict__ in, T *__restrict__ out, const T *__restrict__ ks,
                                                          const T *__restrict__ bias, int64_t rows, int Bd, int d, int n, int taps)
@@ -89,33 +119,42 @@ __global__ __launch_bounds__(256) void short_conv_kernel(const T *__restrict__ i
         const int64_t r = idx / pieces;
         const int p = (int)(idx - r * pieces);
         const int kr = (int)(r / Bd) * d + (int)(r % d);   // r = (i B + b) d + c  ->  i d + c
-        float w[8], x[16];
+        float w[8], x[16], o[8];
 #pragma unroll
         for (int tau = 0; tau < 8; ++tau) w[tau] = tau < taps ? to_f32(ks[(int64_t)kr * taps + tau]) : 0.0f;
         const float bv = bias ? to_f32(bias[kr]) : 0.0f;
         const T *src = in + r * n + 8 * p;
+        float cur[8], prev[8];
+        load8(src, cur);
+        load8(p > 0 ? src - 8 : src, prev);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            x[8 + e] = to_f32(src[e]) + bv;
-            x[e] = p > 0 ? to_f32(src[e - 8]) + bv : 0.0f;   // positions before the start of the row contribute nothing
+            x[8 + e] = cur[e] + bv;
+            x[e] = p > 0 ? prev[e] + bv : 0.0f;   // positions before the start of the row contribute nothing
         }
-        T o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float acc = 0.0f;
 #pragma unroll
             for (int tau = 0; tau < 8; ++tau) acc = fmaf(w[tau], x[8 + e - tau], acc);
-            o[e] = from_f32<T>(acc);
+            o[e] = acc;
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) out[r * n + 8 * p + e] = o[e];
+        store8(out + r * n + 8 * p, o);
     }
 }
 
-// y[b][t][c] = bias[c] (the output projection then accumulates onto it)
+// y[b][t][c] = bias[c] (the output projection then accumulates onto it); d a multiple of 8: 16-byte stores
 template <typename T>
 __global__ __launch_bounds__(256) void bias_rows_kernel(T *__restrict__ y, const T *__restrict__ bias, int64_t total, int d)
 {
+    if (d % 8 == 0) {
+        for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; 8 * idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+            float v[8];
+            load8(bias + (8 * idx) % d, v);
+            store8(y + 8 * idx, v);
+        }
+        return;
+    }
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x)
         y[idx] = bias[idx % d];
 }
@@ -158,7 +197,7 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
     // 4. y[b] (n x d) = O[b]^T W_out^T (+ b_out, put there first)
     float beta = 0.0f;
     if (b_out) {
-        const int64_t total = (int64_t)B * n * d, blocks = (total + 255) / 256;
+        const int64_t total = (int64_t)B * n * d, blocks = (total / 8 + 255) / 256;
         hipLaunchKernelGGL(bias_rows_kernel<T>, dim3((unsigned)(blocks > 65536 ? 65536 : blocks)), dim3(256), 0, s, (T *)y, (const T *)b_out,
                            total, d);
         MONARCH_HIP_CHECK(hipGetLastError());
