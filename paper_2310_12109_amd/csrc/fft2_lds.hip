@@ -73,24 +73,20 @@ __device__ __forceinline__ void build_table(u32x4 *tab, float2 *roots)
     __syncthreads();
 }
 
-// One stage on one tile of 16 columns.  STRIDED: element (c, col) at tile[c * PITCH + col] (stage X);
-// otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: 16-row
-// blocks of the output that are needed.
-// TW: 0 none; 1: multiply output row j by omega_(mod)^(alpha j + beta), computed here with a recurrence over
-// the row tiles (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors); 2: the same
-// factors handed in by the caller, twp[4 jt + r] for row row_of(jt, 4 (lane / 16) + r) (see twiddles_of).
-// GOUT (only with !STRIDED): the results do not go back into the tile but, unrounded, to gout[j * gstride + col]
-// as complex fp32 (the natural order of a two-factor transform: frequency j f1 + col).
-template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false>
-__device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int col, int lane, int live_ks, int want_jt,
-                                           int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0,
-                                           const float2 *twp = nullptr)
+// The data operands of one stage_tile call: the real parts (br) and the imaginary parts (bi) of the 16 columns'
+// values along the contracted digit, paired for the matrix instruction.
+template <int F>
+struct StageOps {
+    u32x4 br[(F + 31) / 32], bi[(F + 31) / 32];
+};
+
+// First half of stage_tile: reads the operands of column tile `col` from the tile.  A caller that runs several
+// calls in a row on disjoint columns may read the next call's operands before it finishes the current one.
+template <int F, int PITCH, bool STRIDED>
+__device__ __forceinline__ void stage_load(const uint32_t *tile, int col, int lane, int live_ks, StageOps<F> &ops)
 {
-    constexpr int JT = F / 16, KS = (F + 31) / 32, TKS = table_ks(F);
-    constexpr bool HALF = half_table(F);
+    constexpr int KS = (F + 31) / 32;
     const int kg = lane >> 4;
-    // Re = Fr Br - Fi Bi: the second product takes the negated imaginary parts of the data (nb), one chain
-    u32x4 br[KS], bi[KS], nb[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         const int c0 = 32 * ks + 8 * kg;
@@ -113,13 +109,29 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
         }
 #pragma unroll
         for (int h = 0; h < 4; ++h) {   // low halves (real parts) of two words into one, high halves into another
-            br[ks][h] = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x05040100u);
-            bi[ks][h] = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x07060302u);
-            nb[ks][h] = bi[ks][h] ^ 0x80008000u;
+            ops.br[ks][h] = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x05040100u);
+            ops.bi[ks][h] = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x07060302u);
         }
     }
+}
+
+// Second half of stage_tile: the products with the factor's table, the diagonal, and the results back into the
+// tile (or to gout).  The table operands of the next row tile are read before the results of the current one
+// are written, so that their latency is covered by the diagonal's arithmetic.
+template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false>
+__device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, const StageOps<F> &ops, int col, int lane, int live_ks,
+                                             int want_jt, int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0,
+                                             const float2 *twp = nullptr)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32, TKS = table_ks(F);
+    constexpr bool HALF = half_table(F);
+    const int kg = lane >> 4;
+    // Re = Fr Br - Fi Bi: the second product takes the negated imaginary parts of the data (nb), one chain
+    u32x4 nb[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) nb[ks] = ops.bi[ks] ^ 0x80008000u;
     u32x4 nbr1 = {0, 0, 0, 0};   // HALF: the negated real parts of the second k-step, for the odd row tiles
-    if constexpr (HALF) nbr1 = br[1] ^ 0x80008000u;
+    if constexpr (HALF) nbr1 = ops.br[1] ^ 0x80008000u;
     // TW == 1: the factors of the rows of the current tile (HALF: of the even and the odd tile of the current pair)
     float2 tw[HALF ? 2 : 1][4], step;
     if constexpr (TW == 1) {
@@ -135,6 +147,17 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
     }
     const int want = HALF ? (want_jt + 1) & ~1 : want_jt;   // (an even and an odd tile make one block of 32 rows)
     uint32_t even[4] = {0u, 0u, 0u, 0u};                    // HALF, stage Y: the packed results of the even tile of the pair
+    u32x4 ar[TKS], ai[TKS];                                 // the table operands of the current row tile
+    auto table_of = [&](int jt) {
+#pragma unroll
+        for (int tk = 0; tk < TKS; ++tk) {
+            if (tk < live_ks) {
+                ar[tk] = tab[(jt * TKS + tk) * 128 + lane];
+                ai[tk] = tab[(jt * TKS + tk) * 128 + 64 + lane];
+            }
+        }
+    };
+    if (0 < want) table_of(0);
     auto row_tile = [&](int jt) {
         if (jt < want) {
             f32x4 dr = {0, 0, 0, 0}, di = {0, 0, 0, 0};
@@ -142,14 +165,14 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks < live_ks) {
                     const int tk = HALF ? 0 : ks;
-                    const u32x4 ar = tab[(jt * TKS + tk) * 128 + lane], ai = tab[(jt * TKS + tk) * 128 + 64 + lane];
                     const bool flip = HALF && ks == 1 && (jt & 1);   // this k-step's operands are minus the table's
-                    dr = mfma(ar, flip ? nbr1 : br[ks], dr);
-                    di = mfma(ai, flip ? nbr1 : br[ks], di);
-                    dr = mfma(ai, flip ? bi[ks] : nb[ks], dr);
-                    di = mfma(ar, flip ? nb[ks] : bi[ks], di);
+                    dr = mfma(ar[tk], flip ? nbr1 : ops.br[ks], dr);
+                    di = mfma(ai[tk], flip ? nbr1 : ops.br[ks], di);
+                    dr = mfma(ai[tk], flip ? ops.bi[ks] : nb[ks], dr);
+                    di = mfma(ar[tk], flip ? nb[ks] : ops.bi[ks], di);
                 }
             }
+            if (jt + 1 < want) table_of(jt + 1);
             uint32_t o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -192,6 +215,25 @@ __device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int
 #pragma unroll 1
         for (int jt = 0; jt < JT; ++jt) row_tile(jt);
     }
+}
+
+
+// One stage on one tile of 16 columns.  STRIDED: element (c, col) at tile[c * PITCH + col] (stage X);
+// otherwise at tile[col * PITCH + c] (stage Y).  live_ks: k-steps holding non-zero inputs; want_jt: 16-row
+// blocks of the output that are needed.
+// TW: 0 none; 1: multiply output row j by omega_(mod)^(alpha j + beta), computed here with a recurrence over
+// the row tiles (alpha = col, beta = 0, mod = f1 f2 for the diagonal between the two factors); 2: the same
+// factors handed in by the caller, twp[4 jt + r] for row row_of(jt, 4 (lane / 16) + r) (see twiddles_of).
+// GOUT (only with !STRIDED): the results do not go back into the tile but, unrounded, to gout[j * gstride + col]
+// as complex fp32 (the natural order of a two-factor transform: frequency j f1 + col).
+template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false>
+__device__ __forceinline__ void stage_tile(uint32_t *tile, const u32x4 *tab, int col, int lane, int live_ks, int want_jt,
+                                           int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0,
+                                           const float2 *twp = nullptr)
+{
+    StageOps<F> ops;
+    stage_load<F, PITCH, STRIDED>(tile, col, lane, live_ks, ops);
+    stage_finish<F, PITCH, STRIDED, TW, GOUT>(tile, tab, ops, col, lane, live_ks, want_jt, alpha, beta, inv_mod, gout, gstride, twp);
 }
 
 // The diagonal of stage_tile for a fixed column, kept by the caller across calls: twp[4 jt + r] =
@@ -668,6 +710,22 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     }
 }
 
+// Runs the tasks wave, wave + WAVES, ... < TOTAL of one stage: the operands of the next task (a different column
+// tile, so untouched by the current one's results) are read before the current task's products start.
+template <int F, int TOTAL, int WAVES, class Load, class Finish>
+__device__ __forceinline__ void staged_tasks(int wave, Load &&load, Finish &&finish)
+{
+    constexpr int NT = (TOTAL + WAVES - 1) / WAVES;
+    StageOps<F> ops[2];
+    if (wave < TOTAL) load(wave, ops[0]);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const int t = wave + i * WAVES;
+        if (i + 1 < NT && t + WAVES < TOTAL) load(t + WAVES, ops[(i + 1) & 1]);
+        if (t < TOTAL) finish(t, ops[i & 1]);
+    }
+}
+
 // The four sums of products of the Hermitian separation of two channel-paired spectra, from packed bf16 words
 // (re | im << 16): z, k at a frequency, zm, km at its mirror; sk, skm: k and km with their halves swapped.
 //   q1 = z k + conj(zm km),   q2 = z conj(km) + conj(zm) k
@@ -701,6 +759,12 @@ __device__ __forceinline__ void separation_sums(uint32_t z, uint32_t zm, uint32_
 // takes chunk o and chunk O - o of a row together, four tiles in LDS (0: u chunk o, 1: u mirror chunk, 2 and 3
 // the same of k).  Chunks 0 and O / 2 mirror onto themselves and take a turn each with two tiles.  Nothing of the
 // spectra ever reaches HBM.
+#ifdef MONARCH_TUNE_ENV
+__constant__ int g_mid_skip;
+#define MIDSKIP(b) (g_mid_skip & (b))
+#else
+#define MIDSKIP(b) false
+#endif
 template <int F1, int F2, int THREADS>
 __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(const Fft2Args p)
 {
@@ -718,7 +782,9 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const float inv_mod = 1.0f / (float)CH;
     auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
-    const int turns_per_row = p.O / 2 + 1;
+    // a turn is a chunk o in 1 .. O/2 - 1 with its mirror O - o, or (turn 0) the two chunks 0 and O/2 that mirror onto
+    // themselves: every turn carries four tiles and the same work
+    const int turns_per_row = p.O / 2;
     const int64_t nturns = p.rows * turns_per_row;
     // A wave meets the same column in every task of a stage when the tasks of a tile divide the waves: then the
     // diagonal between the two factors (forward after stage X, inverse after stage Y) is computed once.
@@ -730,10 +796,9 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
     }
 
     u32x4 z[4][NIT4];
-    // every turn issues the same loads: a chunk that is its own mirror is read twice (the second time from cache)
     auto request = [&](int64_t turn) {
         const int64_t row = turn / turns_per_row;
-        const int o = (int)(turn - row * turns_per_row), om = o ? p.O - o : 0;
+        const int o = (int)(turn - row * turns_per_row), om = o ? p.O - o : p.O / 2;
         const uint32_t *src[4] = {(const uint32_t *)p.in + row * p.N + (int64_t)o * CH, (const uint32_t *)p.in + row * p.N + (int64_t)om * CH,
                                   (const uint32_t *)p.kf + row * p.N + (int64_t)o * CH, (const uint32_t *)p.kf + row * p.N + (int64_t)om * CH};
 #pragma unroll
@@ -746,11 +811,13 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
     };
 
     int64_t turn = blockIdx.x;
-    if (turn < nturns) request(turn);
+    if (MIDSKIP(16)) {
+        for (int t = 0; t < 4; ++t)
+            for (int it = 0; it < NIT4; ++it) z[t][it] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    } else if (turn < nturns) request(turn);
     for (; turn < nturns; turn += gridDim.x) {
         const int64_t row = turn / turns_per_row;
-        const int o = (int)(turn - row * turns_per_row);
-        const bool paired = o != 0 && 2 * o != p.O;
+        const int o = (int)(turn - row * turns_per_row), om = o ? p.O - o : p.O / 2;
 #pragma unroll
         for (int it = 0; it < NIT4; ++it) {
             const int e = 4 * (tid + it * THREADS);
@@ -760,24 +827,26 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
             }
         }
         __syncthreads();
-        if (turn + gridDim.x < nturns) request(turn + gridDim.x);
+        if (!MIDSKIP(16) && turn + gridDim.x < nturns) request(turn + gridDim.x);
 
-        // ---- forward chunk factors of the row and of its kernel row (tiles 0..3, or 0 and 2 of a lone chunk)
-        const int nfwd = paired ? 4 : 2;
-        for (int t = wave; t < nfwd * XT; t += WAVES) {
-            const int ti = t / XT, tt = t - ti * XT;
-            if constexpr (HOIST)
-                stage_tile<F1, PITCH, true, 2>(lds + (paired ? ti : 2 * ti) * TILE, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16,
-                                               0, 0, inv_mod, nullptr, 0, twx);
-            else
-                stage_tile<F1, PITCH, true, 1>(lds + (paired ? ti : 2 * ti) * TILE, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16,
-                                               16 * tt + l16, 0, inv_mod);
-        }
+        // ---- forward chunk factors of the row (tiles 0, 1) and of its kernel row (tiles 2, 3)
+        constexpr int KX = (F1 + 31) / 32, KY = (F2 + 31) / 32;
+        if (!MIDSKIP(4)) {
+        staged_tasks<F1, 4 * XT, WAVES>(
+            wave, [&](int t, StageOps<F1> &ops) { stage_load<F1, PITCH, true>(lds + (t / XT) * TILE, 16 * (t % XT) + l16, lane, KX, ops); },
+            [&](int t, const StageOps<F1> &ops) {
+                const int col = 16 * (t % XT) + l16;
+                if constexpr (HOIST)
+                    stage_finish<F1, PITCH, true, 2>(lds + (t / XT) * TILE, tab1, ops, col, lane, KX, F1 / 16, 0, 0, inv_mod, nullptr, 0, twx);
+                else
+                    stage_finish<F1, PITCH, true, 1>(lds + (t / XT) * TILE, tab1, ops, col, lane, KX, F1 / 16, col, 0, inv_mod);
+            });
         __syncthreads();
-        for (int t = wave; t < nfwd * YT; t += WAVES) {
-            const int ti = t / YT, tt = t - ti * YT;
-            stage_tile<F2, PITCH, false, 0>(lds + (paired ? ti : 2 * ti) * TILE, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16,
-                                                0, 0, inv_mod);
+        staged_tasks<F2, 4 * YT, WAVES>(
+            wave, [&](int t, StageOps<F2> &ops) { stage_load<F2, PITCH, false>(lds + (t / YT) * TILE, 16 * (t % YT) + l16, lane, KY, ops); },
+            [&](int t, const StageOps<F2> &ops) {
+                stage_finish<F2, PITCH, false, 0>(lds + (t / YT) * TILE, tab2, ops, 16 * (t % YT) + l16, lane, KY, F2 / 16, 0, 0, inv_mod);
+            });
         }
         __syncthreads();
 
@@ -797,18 +866,20 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
             there = pack2(a - b, c - d);
         };
         uint32_t *res0 = lds;            // the product tile of chunk o
-        uint32_t *res1 = lds + TILE;     // paired: the product tile of chunk O - o
-        if (o != 0) {
-            // the mirror of position e of chunk o is position CH - 1 - e of chunk O - o: 16-byte pieces read
-            // backwards.  A chunk that mirrors onto itself (o = O / 2): the lower half of the positions does both.
-            uint32_t *um = paired ? lds + TILE : lds, *km = paired ? lds + 3 * TILE : lds + 2 * TILE;
-            const int lim = paired ? CH : CH / 2;
+        uint32_t *res1 = lds + TILE;     // the product tile of chunk O - o (turn 0: of chunk O / 2)
+        if (!MIDSKIP(2)) {
+        // The mirror of position e of chunk o is position CH - 1 - e of chunk O - o: 16-byte pieces read backwards.
+        // Chunk O / 2 mirrors onto itself that way: the lower half of its positions does both ends.
+        {
+            uint32_t *zu = o ? lds : lds + TILE, *zk = o ? lds + 2 * TILE : lds + 3 * TILE;
+            uint32_t *um = lds + TILE, *km = lds + 3 * TILE;
+            const int lim = o ? CH : CH / 2;
 #pragma unroll
             for (int it = 0; it < NIT4; ++it) {
                 const int e = 4 * (tid + it * THREADS);
                 if (e < lim) {
-                    const u32x4 a = *reinterpret_cast<const u32x4 *>(lds + tix(e)), b = *reinterpret_cast<const u32x4 *>(um + tix(CH - 4 - e));
-                    const u32x4 c = *reinterpret_cast<const u32x4 *>(lds + 2 * TILE + tix(e)), d = *reinterpret_cast<const u32x4 *>(km + tix(CH - 4 - e));
+                    const u32x4 a = *reinterpret_cast<const u32x4 *>(zu + tix(e)), b = *reinterpret_cast<const u32x4 *>(um + tix(CH - 4 - e));
+                    const u32x4 c = *reinterpret_cast<const u32x4 *>(zk + tix(e)), d = *reinterpret_cast<const u32x4 *>(km + tix(CH - 4 - e));
                     u32x4 w, w2;
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
@@ -817,52 +888,60 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
                         w[t] = here;
                         w2[3 - t] = there;
                     }
-                    *reinterpret_cast<u32x4 *>(lds + tix(e)) = w;
+                    *reinterpret_cast<u32x4 *>(zu + tix(e)) = w;
                     *reinterpret_cast<u32x4 *>(um + tix(CH - 4 - e)) = w2;
                 }
             }
-        } else {
-            // chunk 0: the mirror of (j1, j2) is ((f1 - j1) mod f1, f2 - 1 - j2) for j1 > 0 and (0, (f2 - j2) mod f2)
-            // for j1 = 0, in the same tile; the products go to the free tile 1
-            res0 = lds + TILE;
-            for (int e = tid; e < CH; e += THREADS) {
+        }
+        if (o == 0) {
+            // chunk 0 (tiles 0 and 2): the mirror of (j1, j2) is ((f1 - j1) mod f1, f2 - 1 - j2) for j1 > 0 and
+            // (0, (f2 - j2) mod f2) for j1 = 0, in the same tile.  One end of every such pair, taken from the rows
+            // 0 .. f1 / 2, does both ends in place; a position that is its own mirror is written once.
+            for (int e = tid; e < (F1 / 2 + 1) * F2; e += THREADS) {
                 const int j1 = e / F2, j2 = e - j1 * F2;
-                const int m = ((F1 - j1) % F1) * PITCH + (j1 ? F2 - 1 - j2 : (F2 - j2) % F2);
-                uint32_t w, w2;
-                separate(lds[j1 * PITCH + j2], lds[m], lds[2 * TILE + j1 * PITCH + j2], lds[2 * TILE + m], w, w2);
-                res0[j1 * PITCH + j2] = w;
+                const bool mine = j1 == 0 ? j2 <= F2 / 2 : (j1 < F1 / 2 || j2 < F2 / 2);
+                if (mine) {
+                    const int at = j1 * PITCH + j2;
+                    const int m = ((F1 - j1) % F1) * PITCH + (j1 ? F2 - 1 - j2 : (F2 - j2) % F2);
+                    uint32_t w, w2;
+                    separate(lds[at], lds[m], lds[2 * TILE + at], lds[2 * TILE + m], w, w2);
+                    lds[at] = w;
+                    if (m != at) lds[m] = w2;
+                }
             }
         }
-        __syncthreads();
-
-        // ---- inverse chunk factors, then the diagonal omega_N^(o (f2 c1 + c2)) that precedes the first factor's inverse
-        const int ninv = paired ? 2 : 1;
-        for (int t = wave; t < ninv * YT; t += WAVES) {
-            const int ti = t / YT, tt = t - ti * YT;
-            if constexpr (HOIST)
-                stage_tile<F2, PITCH, false, 2>(ti ? res1 : res0, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16, 0, 0, inv_mod,
-                                                nullptr, 0, twy);
-            else
-                stage_tile<F2, PITCH, false, 1>(ti ? res1 : res0, tab2, 16 * tt + l16, lane, (F2 + 31) / 32, F2 / 16, 16 * tt + l16, 0,
-                                                inv_mod);
         }
         __syncthreads();
-        for (int t = wave; t < ninv * XT; t += WAVES) {
-            const int ti = t / XT, tt = t - ti * XT;
-            const int oo = ti ? p.O - o : o;
-            stage_tile<F1, PITCH, true, 1>(ti ? res1 : res0, tab1, 16 * tt + l16, lane, (F1 + 31) / 32, F1 / 16, oo * F2, oo * (16 * tt + l16),
-                                           1.0f / (float)p.N);
+        if (!MIDSKIP(8)) {
+
+        // ---- inverse chunk factors, then the diagonal omega_N^(o (f2 c1 + c2)) that precedes the first factor's inverse
+        staged_tasks<F2, 2 * YT, WAVES>(
+            wave, [&](int t, StageOps<F2> &ops) { stage_load<F2, PITCH, false>(t / YT ? res1 : res0, 16 * (t % YT) + l16, lane, KY, ops); },
+            [&](int t, const StageOps<F2> &ops) {
+                const int col = 16 * (t % YT) + l16;
+                if constexpr (HOIST)
+                    stage_finish<F2, PITCH, false, 2>(t / YT ? res1 : res0, tab2, ops, col, lane, KY, F2 / 16, 0, 0, inv_mod, nullptr, 0, twy);
+                else
+                    stage_finish<F2, PITCH, false, 1>(t / YT ? res1 : res0, tab2, ops, col, lane, KY, F2 / 16, col, 0, inv_mod);
+            });
+        __syncthreads();
+        staged_tasks<F1, 2 * XT, WAVES>(
+            wave, [&](int t, StageOps<F1> &ops) { stage_load<F1, PITCH, true>(t / XT ? res1 : res0, 16 * (t % XT) + l16, lane, KX, ops); },
+            [&](int t, const StageOps<F1> &ops) {
+                const int col = 16 * (t % XT) + l16, oo = t / XT ? om : o;
+                stage_finish<F1, PITCH, true, 1>(t / XT ? res1 : res0, tab1, ops, col, lane, KX, F1 / 16, oo * F2, oo * col, 1.0f / (float)p.N);
+            });
         }
         __syncthreads();
 
         uint32_t *dst = (uint32_t *)p.out + row * p.N + (int64_t)o * CH;
-        uint32_t *dst2 = (uint32_t *)p.out + row * p.N + (int64_t)(p.O - o) * CH;
+        uint32_t *dst2 = (uint32_t *)p.out + row * p.N + (int64_t)om * CH;
 #pragma unroll
         for (int it = 0; it < NIT4; ++it) {
             const int e = 4 * (tid + it * THREADS);
-            if (e < CH) {
+            if (e < CH && !MIDSKIP(1)) {
                 *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(res0 + tix(e));
-                if (paired) *reinterpret_cast<u32x4 *>(dst2 + e) = *reinterpret_cast<const u32x4 *>(res1 + tix(e));
+                *reinterpret_cast<u32x4 *>(dst2 + e) = *reinterpret_cast<const u32x4 *>(res1 + tix(e));
             }
         }
         __syncthreads();
@@ -883,10 +962,19 @@ static int launch_middle(const Fft2Args &p, hipStream_t s)
     MONARCH_HIP_CHECK(hipGetDevice(&dev));
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     const int per_cu = (int)((160 * 1024) / (lds + 1024));
-    const int64_t nturns = p.rows * (p.O / 2 + 1);
+    const int64_t nturns = p.rows * (p.O / 2);
     int64_t grid = (int64_t)ncu * (per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu);
     if (grid > nturns) grid = nturns;
     auto kern = conv3_middle_kernel<F1, F2, THREADS>;
+#ifdef MONARCH_TUNE_ENV
+    static bool skip_set = false;
+    if (!skip_set) {
+        skip_set = true;
+        const char *e = getenv("MONARCH_MID_SKIP");
+        const int v = e ? atoi(e) : 0;
+        MONARCH_HIP_CHECK(hipMemcpyToSymbol(HIP_SYMBOL(g_mid_skip), &v, sizeof(int)));
+    }
+#endif
     if (lds > 48 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, p);

@@ -169,23 +169,15 @@ __device__ __forceinline__ void load_values(const FftPass &p, int64_t rc, int po
     }
 }
 
-// NT column tiles per wave: lane l16 owns the adjacent columns col0 + t, t < NT, so that NT = 2
-// doubles the width of every global access and halves the operand reads from LDS.
-template <int F, int LOAD, int STORE, bool CONTIG, int NT>
-__global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pass_mfma_kernel(const FftPass p)
+// The operands of F_f for the matrix instruction, built once per workgroup: entry [jt][ks][re, im][lane], where
+// lane (row l16, group kg) of row tile jt and k-step ks holds F[16 jt + l16][32 ks + 8 kg + e], e < 8, as bf16 pairs.
+template <int F, int THREADS>
+__device__ __forceinline__ void build_ftab(u32x4 *ftab)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32;
-    constexpr int THREADS = F == 128 ? 512 : 256, WAVES = THREADS / 64;   // the 64 KB table of f = 128 is shared by 8 waves
-    constexpr int COLS = 16 * NT;
-    constexpr bool REAL_IN = LOAD == LD_REAL || LOAD == LD_REAL_PAIR;
-    constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
-    constexpr bool REAL_B = LOAD == LD_REAL;                   // imaginary part of the input is zero
-    constexpr bool REAL_D = STORE == ST_REAL_SCALE_GATE;       // only the real part is kept
-    extern __shared__ __attribute__((aligned(16))) u32x4 ftab[];   // [JT][KS][re, im][lane]
     __shared__ float2 roots[F];
     for (int e = threadIdx.x; e < F; e += THREADS) roots[e] = omega(e, F);
     __syncthreads();
-    // A operand of row tile jt, k-step ks: lane (row l16, group kg) holds F[16 jt + l16][32 ks + 8 kg + e]
     for (int idx = threadIdx.x; idx < JT * KS * 64; idx += THREADS) {
         const int ln = idx & 63, ks = (idx >> 6) % KS, jt = idx / (64 * KS);
         const int j = 16 * jt + (ln & 15), c0 = 32 * ks + 8 * (ln >> 4);
@@ -202,6 +194,22 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
         ftab[(idx >> 6) * 128 + 64 + ln] = im;
     }
     __syncthreads();
+}
+
+// NT column tiles per wave: lane l16 owns the adjacent columns col0 + t, t < NT, so that NT = 2
+// doubles the width of every global access and halves the operand reads from LDS.
+template <int F, int LOAD, int STORE, bool CONTIG, int NT>
+__global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pass_mfma_kernel(const FftPass p)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    constexpr int THREADS = F == 128 ? 512 : 256, WAVES = THREADS / 64;   // the 64 KB table of f = 128 is shared by 8 waves
+    constexpr int COLS = 16 * NT;
+    constexpr bool REAL_IN = LOAD == LD_REAL || LOAD == LD_REAL_PAIR;
+    constexpr bool REAL_OUT = STORE == ST_REAL_SCALE_GATE || STORE == ST_REAL_PAIR;
+    constexpr bool REAL_B = LOAD == LD_REAL;                   // imaginary part of the input is zero
+    constexpr bool REAL_D = STORE == ST_REAL_SCALE_GATE;       // only the real part is kept
+    extern __shared__ __attribute__((aligned(16))) u32x4 ftab[];   // [JT][KS][re, im][lane]
+    build_ftab<F, THREADS>(ftab);
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
@@ -448,6 +456,388 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
     }
 }
 
+// ---- passes whose real rows move in 16-byte pieces --------------------------------------------
+//
+// A wave of the kernel above touches a real bf16 row 64 bytes at a time (32 columns), four rows per access:
+// half cache lines, which the memory system serves at a fraction of its rate.  The two kernels below take 128
+// columns per workgroup; the threads read or write the real rows in 16-byte pieces (256 contiguous bytes per
+// row) and the waves exchange operands and results through LDS.  They cover the first pass of a forward
+// transform of real rows (rows_in: O = 1, ST_C16) and the last pass of an inverse that ends in time order
+// (rows_out: O = 1, LD_C16, S > 1), for S a multiple of 128 and rows of a multiple of 8 elements.
+
+constexpr int RB_COLS = 128;          // columns of a workgroup's block: 32 per wave, 2 per lane
+constexpr int RB_PITCH = RB_COLS + 8; // words per LDS row: the four row groups of an access fall on different banks
+
+// First pass.  LDS holds, per plane (real parts; PAIR: imaginary parts = the second real row), the block as
+// [row pair][column] words of two bf16 (rows 2 rp, 2 rp + 1): the matrix instruction's operand pairs.
+// LS: k-steps (32 rows) that hold input; the rows past n_valid are zero and never read.
+template <int F, bool PAIR, int LS>
+__global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass p)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32, THREADS = 256, NP = PAIR ? 2 : 1;
+    static_assert(LS >= 1 && LS <= KS, "live k-steps");
+    extern __shared__ __attribute__((aligned(16))) u32x4 ftab[];
+    uint32_t *plane = reinterpret_cast<uint32_t *>(ftab + JT * KS * 128);   // [NP][16 LS][RB_PITCH]
+    build_ftab<F, THREADS>(ftab);
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int S = p.S, blocks_per_row = S / RB_COLS;
+    const int64_t nblocks = p.rows * blocks_per_row;
+    const float inv_fs = 1.0f / (float)((int64_t)F * S);
+    const bool gated = p.gate != nullptr;
+    const bf16_t *in = (const bf16_t *)p.in, *gate = gated ? (const bf16_t *)p.gate : in;
+    const int piece = tid & 15, rp0 = tid >> 4;   // this thread's pieces: columns 8 piece .. + 7 of row pairs rp0 + 16 st
+
+    u32x4 val[LS][NP][2], gat[LS][NP][2];   // [k-step][real row][row of the pair]
+    auto request = [&](int64_t blk) {
+        const int64_t rc = blk / blocks_per_row;
+        const int s0 = (int)(blk - rc * blocks_per_row) * RB_COLS + 8 * piece;
+        const int64_t ra = PAIR ? pair_first_row(p, rc) : rc;
+        const bool hasb = PAIR && ra + p.pair_stride < p.real_rows;
+#pragma unroll
+        for (int st = 0; st < LS; ++st)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int c = 2 * (rp0 + 16 * st) + q, pos = c * S + s0;
+                const int64_t at = ra * p.n_valid + (c < F && pos < p.n_valid ? pos : 0);   // past the row: any valid address
+                val[st][0][q] = *reinterpret_cast<const u32x4 *>(in + at);
+                if (gated) gat[st][0][q] = *reinterpret_cast<const u32x4 *>(gate + at);
+                if constexpr (PAIR) {
+                    const int64_t bt = hasb ? at + (int64_t)p.pair_stride * p.n_valid : at;
+                    val[st][1][q] = *reinterpret_cast<const u32x4 *>(in + bt);
+                    if (gated) gat[st][1][q] = *reinterpret_cast<const u32x4 *>(gate + bt);
+                }
+            }
+    };
+    // rounds the (gated) values to bf16 and writes the pairs of rows 2 rp, 2 rp + 1
+    auto deposit = [&](int64_t blk) {
+        const int64_t rc = blk / blocks_per_row;
+        const int s0 = (int)(blk - rc * blocks_per_row) * RB_COLS + 8 * piece;
+        const int64_t ra = PAIR ? pair_first_row(p, rc) : rc;
+        const bool hasb = PAIR && ra + p.pair_stride < p.real_rows;
+#pragma unroll
+        for (int st = 0; st < LS; ++st) {
+            const int rp = rp0 + 16 * st;
+            bool ok[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) ok[q] = 2 * rp + q < F && (2 * rp + q) * S + s0 < p.n_valid;
+#pragma unroll
+            for (int np = 0; np < NP; ++np) {
+                u32x4 v[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const bool live = ok[q] && (np == 0 || hasb);
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) v[q][h] = live ? val[st][np][q][h] : 0u;
+                }
+                u32x4 w0, w1;   // columns 0..3 and 4..7 of the piece
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    uint32_t even, odd;   // columns 2 h and 2 h + 1: (row 2 rp, row 2 rp + 1)
+                    if (gated) {
+                        const uint32_t g0 = gat[st][np][0][h], g1 = gat[st][np][1][h];
+                        even = pack2(lo_f32(v[0][h]) * lo_f32(g0), lo_f32(v[1][h]) * lo_f32(g1));
+                        odd = pack2(hi_f32(v[0][h]) * hi_f32(g0), hi_f32(v[1][h]) * hi_f32(g1));
+                    } else {
+                        even = __builtin_amdgcn_perm(v[1][h], v[0][h], 0x05040100u);
+                        odd = __builtin_amdgcn_perm(v[1][h], v[0][h], 0x07060302u);
+                    }
+                    if (h < 2) {
+                        w0[2 * h] = even;
+                        w0[2 * h + 1] = odd;
+                    } else {
+                        w1[2 * h - 4] = even;
+                        w1[2 * h - 3] = odd;
+                    }
+                }
+                uint32_t *dst = plane + (np * 16 * LS + rp) * RB_PITCH + 8 * piece;
+                *reinterpret_cast<u32x4 *>(dst) = w0;
+                *reinterpret_cast<u32x4 *>(dst + 4) = w1;
+            }
+        }
+    };
+
+    int64_t blk = blockIdx.x;
+    if (blk < nblocks) request(blk);
+    for (; blk < nblocks; blk += gridDim.x) {
+        deposit(blk);
+        __syncthreads();
+        if (blk + gridDim.x < nblocks) request(blk + gridDim.x);
+
+        // ---- B operands of this wave's 32 columns: k-step ks, slot pair h  <->  rows 32 ks + 8 kg + 2 h, + 1
+        u32x4 br[2][LS], bi[2][PAIR ? LS : 1];
+#pragma unroll
+        for (int ks = 0; ks < LS; ++ks)
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const uint32_t *src = plane + (16 * ks + 4 * kg + h) * RB_PITCH + 32 * wave + 2 * l16;
+                const uint2 r = *reinterpret_cast<const uint2 *>(src);
+                br[0][ks][h] = r.x;
+                br[1][ks][h] = r.y;
+                if constexpr (PAIR) {
+                    const uint2 i = *reinterpret_cast<const uint2 *>(src + 16 * LS * RB_PITCH);
+                    bi[0][ks][h] = i.x;
+                    bi[1][ks][h] = i.y;
+                }
+            }
+        __syncthreads();   // the planes are free for the next block
+
+        const int64_t rc = blk / blocks_per_row;
+        const int col0 = (int)(blk - rc * blocks_per_row) * RB_COLS + 32 * wave + 2 * l16;
+        // twiddle seeds: omega_(fS)^(j s) for j = 4 kg + r, stepped by omega_(fS)^(16 s) per row tile
+        float2 tw[2][4], step[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float rev = (float)((4 * kg + r) * (col0 + t)) * inv_fs;   // exact: j s < f S <= 2^24
+                tw[t][r] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+            }
+            const float rev = (float)(16 * (col0 + t)) * inv_fs;
+            step[t] = make_float2(__builtin_amdgcn_cosf(rev), __builtin_amdgcn_sinf(rev));
+        }
+        uint32_t *out = (uint32_t *)p.out + rc * p.N + col0;
+#pragma unroll 1
+        for (int jt = 0; jt < JT; ++jt) {
+            f32x4 dr[2], di[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) dr[t] = di[t] = f32x4{0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < LS; ++ks) {
+                const u32x4 ar = ftab[(jt * KS + ks) * 128 + lane], ai = ftab[(jt * KS + ks) * 128 + 64 + lane];
+                const u32x4 nai = ai ^ 0x80008000u;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    dr[t] = mfma(ar, br[t][ks], dr[t]);
+                    di[t] = mfma(ai, br[t][ks], di[t]);
+                    if constexpr (PAIR) {
+                        dr[t] = mfma(nai, bi[t][ks], dr[t]);
+                        di[t] = mfma(ar, bi[t][ks], di[t]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = 16 * jt + 4 * kg + r;
+                uint32_t w[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const float2 z = cmul(make_float2(dr[t][r], di[t][r]), tw[t][r]);
+                    w[t] = pack2(z.x, z.y);
+                }
+                store_words<2>(out + (int64_t)j * S, w);
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tw[t][r] = cmul(tw[t][r], step[t]);
+        }
+    }
+}
+
+// Last pass.  The results of a block, scaled, go to LDS as fp32 [real row][j][column]; the threads then take them
+// in pieces of 8 columns, apply the output gate and store 16 bytes.  wra: rows j kept, a multiple of 16.
+template <int F, bool PAIR>
+__global__ __launch_bounds__(256, 2) void fft_pass_rows_out_kernel(const FftPass p, const int wra)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32, THREADS = 256, NP = PAIR ? 2 : 1;
+    constexpr int MAXT = F * NP * 16 / THREADS;   // most pieces per thread
+    extern __shared__ __attribute__((aligned(16))) u32x4 ftab[];
+    float *stage = reinterpret_cast<float *>(ftab + JT * KS * 128);   // [NP][wra][RB_PITCH]
+    build_ftab<F, THREADS>(ftab);
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int S = p.S, blocks_per_row = S / RB_COLS;
+    const int64_t nblocks = p.rows * blocks_per_row;
+    const bool gated = p.gate != nullptr;
+    const int piece = tid & 15, row0 = tid >> 4;   // this thread's pieces: columns 8 piece .. + 7 of rows row0 + 16 i of [NP][wra]
+    const int npieces = NP * wra / 16;             // per thread
+
+    for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        const int64_t rc = blk / blocks_per_row;
+        const int s0 = (int)(blk - rc * blocks_per_row) * RB_COLS;
+        const int col0 = s0 + 32 * wave + 2 * l16;
+        const int64_t ra = PAIR ? pair_first_row(p, rc) : rc;
+        const bool hasb = PAIR && ra + p.pair_stride < p.real_rows;
+
+        // ---- B operands: k-step ks, slot e  <->  c = 32 ks + 8 kg + e
+        u32x4 br[2][KS], bi[2][KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int c0 = 32 * ks + 8 * kg;
+            uint32_t w[8][2];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = c0 + e < F;
+                load_words<2>((const uint32_t *)p.in + rc * p.N + col0 + (ok ? (c0 + e) * S : 0), w[e]);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) w[e][t] = ok ? w[e][t] : 0u;
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    br[t][ks][h] = __builtin_amdgcn_perm(w[2 * h + 1][t], w[2 * h][t], 0x05040100u);
+                    bi[t][ks][h] = __builtin_amdgcn_perm(w[2 * h + 1][t], w[2 * h][t], 0x07060302u);
+                }
+        }
+        // ---- the output gates of this thread's pieces, in flight during the products
+        u32x4 gat[MAXT];
+        if (gated) {
+#pragma unroll
+            for (int i = 0; i < MAXT; ++i)
+                if (i < npieces) {
+                    const int row = row0 + 16 * i, np = row / wra, j = row - np * wra;
+                    const int m = j * S + s0 + 8 * piece;
+                    const bool ok = m < p.n_valid && (np == 0 || hasb);
+                    const int64_t at = (ra + (ok ? np : 0) * (int64_t)p.pair_stride) * p.n_valid + (ok ? m : 0);
+                    gat[i] = *reinterpret_cast<const u32x4 *>((const bf16_t *)p.gate + at);
+                }
+        }
+
+#pragma unroll 1
+        for (int jt = 0; jt < JT; ++jt) {
+            if (16 * jt < wra) {
+                f32x4 dr[2], di[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) dr[t] = di[t] = f32x4{0, 0, 0, 0};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const u32x4 ar = ftab[(jt * KS + ks) * 128 + lane], ai = ftab[(jt * KS + ks) * 128 + 64 + lane];
+                    const u32x4 nai = ai ^ 0x80008000u;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        dr[t] = mfma(ar, br[t][ks], dr[t]);
+                        dr[t] = mfma(nai, bi[t][ks], dr[t]);
+                        if constexpr (PAIR) {
+                            di[t] = mfma(ai, br[t][ks], di[t]);
+                            di[t] = mfma(ar, bi[t][ks], di[t]);
+                        }
+                    }
+                }
+                // F^-1 = conj(F conj(.)) / N: the first real row is the real part, the second minus the imaginary part
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float *dst = stage + (16 * jt + 4 * kg + r) * RB_PITCH + 32 * wave + 2 * l16;
+                    *reinterpret_cast<float2 *>(dst) = make_float2(dr[0][r] * p.scale, dr[1][r] * p.scale);
+                    if constexpr (PAIR)
+                        *reinterpret_cast<float2 *>(dst + wra * RB_PITCH) = make_float2(-di[0][r] * p.scale, -di[1][r] * p.scale);
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < MAXT; ++i)
+            if (i < npieces) {
+                const int row = row0 + 16 * i, np = row / wra, j = row - np * wra;
+                const int m = j * S + s0 + 8 * piece;   // time index of the piece's first element
+                if (m < p.n_valid && (np == 0 || hasb)) {
+                    const f32x4 a = *reinterpret_cast<const f32x4 *>(stage + row * RB_PITCH + 8 * piece);
+                    const f32x4 b = *reinterpret_cast<const f32x4 *>(stage + row * RB_PITCH + 8 * piece + 4);
+                    u32x4 w;
+                    if (gated) {
+                        const u32x4 g = gat[i];
+                        w[0] = pack2(a[0] * lo_f32(g[0]), a[1] * hi_f32(g[0]));
+                        w[1] = pack2(a[2] * lo_f32(g[1]), a[3] * hi_f32(g[1]));
+                        w[2] = pack2(b[0] * lo_f32(g[2]), b[1] * hi_f32(g[2]));
+                        w[3] = pack2(b[2] * lo_f32(g[3]), b[3] * hi_f32(g[3]));
+                    } else {
+                        w[0] = pack2(a[0], a[1]);
+                        w[1] = pack2(a[2], a[3]);
+                        w[2] = pack2(b[0], b[1]);
+                        w[3] = pack2(b[2], b[3]);
+                    }
+                    const int64_t at = (ra + np * (int64_t)p.pair_stride) * p.n_valid + m;
+                    *reinterpret_cast<u32x4 *>((bf16_t *)p.out + at) = w;
+                }
+            }
+        __syncthreads();   // the stage is free for the next block
+    }
+}
+
+static int rows_kernel_grid(int64_t nblocks, size_t lds, int *grid)
+{
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    int per_cu = (int)((160 * 1024) / (lds + 1024));
+    per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
+    const int64_t cap = (int64_t)ncu * per_cu;
+    *grid = (int)(nblocks < cap ? nblocks : cap);
+    return MONARCH_OK;
+}
+
+static bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }   // (a null gate passes)
+
+// k-steps of the first pass that hold input
+static int live_ksteps(const FftPass &p) { return (int)(((int64_t)p.n_valid + 32 * (int64_t)p.S - 1) / (32 * (int64_t)p.S)); }
+
+static bool rows_in_applies(const FftPass &p)
+{
+    return (p.load == LD_REAL || p.load == LD_REAL_PAIR) && p.store == ST_C16 && p.O == 1 && p.S % RB_COLS == 0 && p.n_valid % 8 == 0 &&
+           p.n_valid > 0 && (p.f == 32 || p.f == 64) && p.dt == MONARCH_BF16 && aligned16(p.in) && aligned16(p.gate);
+}
+
+template <int F, bool PAIR, int LS>
+static int launch_rows_in_ls(const FftPass &p, hipStream_t s)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    const size_t lds = (size_t)JT * KS * 2 * 64 * 16 + (size_t)(PAIR ? 2 : 1) * 16 * LS * RB_PITCH * 4;
+    int grid = 0;
+    const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, &grid);
+    if (rc != MONARCH_OK) return rc;
+    auto kern = fft_pass_rows_in_kernel<F, PAIR, LS>;
+    if (lds > 48 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, p);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+template <int F>
+static int launch_rows_in(const FftPass &p, hipStream_t s)
+{
+    const bool pair = p.load == LD_REAL_PAIR;
+    const int ls = live_ksteps(p);
+    if constexpr (F == 64) {
+        if (ls >= 2) return pair ? launch_rows_in_ls<F, true, 2>(p, s) : launch_rows_in_ls<F, false, 2>(p, s);
+    }
+    return pair ? launch_rows_in_ls<F, true, 1>(p, s) : launch_rows_in_ls<F, false, 1>(p, s);
+}
+
+static bool rows_out_applies(const FftPass &p)
+{
+    return p.load == LD_C16 && (p.store == ST_REAL_PAIR || p.store == ST_REAL_SCALE_GATE) && p.O == 1 && p.S % RB_COLS == 0 &&
+           p.n_valid % 8 == 0 && p.n_valid > 0 && (p.f == 32 || p.f == 64) && p.dt == MONARCH_BF16 && aligned16(p.out) && aligned16(p.gate);
+}
+
+template <int F, bool PAIR>
+static int launch_rows_out_np(const FftPass &p, hipStream_t s)
+{
+    constexpr int JT = F / 16, KS = (F + 31) / 32;
+    int64_t want = ((int64_t)p.n_valid + p.S - 1) / p.S;   // rows j with outputs
+    if (want > F) want = F;
+    const int wra = (int)((want + 15) / 16) * 16;
+    const size_t lds = (size_t)JT * KS * 2 * 64 * 16 + (size_t)(PAIR ? 2 : 1) * wra * RB_PITCH * 4;
+    int grid = 0;
+    const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, &grid);
+    if (rc != MONARCH_OK) return rc;
+    auto kern = fft_pass_rows_out_kernel<F, PAIR>;
+    if (lds > 48 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, p, wra);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+template <int F>
+static int launch_rows_out(const FftPass &p, hipStream_t s)
+{
+    return p.store == ST_REAL_PAIR ? launch_rows_out_np<F, true>(p, s) : launch_rows_out_np<F, false>(p, s);
+}
+
 template <int F, int LOAD, int STORE, bool CONTIG, int NT>
 static int launch_nt(const FftPass &p, hipStream_t s)
 {
@@ -529,6 +919,8 @@ int launch_fft_pass_mfma(const FftPass &p, hipStream_t s)
              : (p.S % 16 != 0 || (real_out ? (p.O != 1 || p.load != LD_C16) : p.store != ST_C16)))
         return fail(MONARCH_EINVAL, "internal: MFMA pass geometry O=%d f=%d S=%d load=%d store=%d", p.O, p.f, p.S, p.load, p.store);
     if ((int64_t)p.O * p.f * p.S != p.N) return fail(MONARCH_EINVAL, "internal: pass geometry does not multiply to N");
+    if (fpm::rows_in_applies(p)) return p.f == 64 ? fpm::launch_rows_in<64>(p, s) : fpm::launch_rows_in<32>(p, s);
+    if (fpm::rows_out_applies(p)) return p.f == 64 ? fpm::launch_rows_out<64>(p, s) : fpm::launch_rows_out<32>(p, s);
     switch (p.f) {
     case 16: return fpm::launch_f<16>(p, s);
     case 32: return fpm::launch_f<32>(p, s);
