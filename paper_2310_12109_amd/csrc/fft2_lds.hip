@@ -82,7 +82,11 @@ struct StageOps {
 
 // First half of stage_tile: reads the operands of column tile `col` from the tile.  A caller that runs several
 // calls in a row on disjoint columns may read the next call's operands before it finishes the current one.
-template <int F, int PITCH, bool STRIDED>
+// SWZ: the tile keeps element (row, col) at column col ^ 16 when bits 3 and 4 of row differ (swz_bit), so that the
+// row groups kg and kg + 1 of a strided access (rows 8 kg + e, a multiple of 32 words apart) fall on different
+// halves of the 32 banks; a row's 16-byte pieces move together, so row-wise accesses are unchanged.
+__device__ __forceinline__ constexpr int swz_bit(int row) { return (((row >> 3) ^ (row >> 4)) & 1) << 4; }
+template <int F, int PITCH, bool STRIDED, bool SWZ = false>
 __device__ __forceinline__ void stage_load(const uint32_t *tile, int col, int lane, int live_ks, StageOps<F> &ops)
 {
     constexpr int KS = (F + 31) / 32;
@@ -96,10 +100,11 @@ __device__ __forceinline__ void stage_load(const uint32_t *tile, int col, int la
         if (ks < live_ks && c0 < F) {
             if constexpr (STRIDED) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) w[e] = tile[(c0 + e) * PITCH + col];
+                for (int e = 0; e < 8; ++e) w[e] = tile[(c0 + e) * PITCH + (SWZ ? col ^ swz_bit(8 * kg) : col)];
             } else {
-                const u32x4 v0 = *reinterpret_cast<const u32x4 *>(tile + col * PITCH + c0);
-                const u32x4 v1 = *reinterpret_cast<const u32x4 *>(tile + col * PITCH + c0 + 4);
+                const int cx = SWZ ? c0 ^ swz_bit(col) : c0;
+                const u32x4 v0 = *reinterpret_cast<const u32x4 *>(tile + col * PITCH + cx);
+                const u32x4 v1 = *reinterpret_cast<const u32x4 *>(tile + col * PITCH + cx + 4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     w[e] = v0[e];
@@ -118,7 +123,7 @@ __device__ __forceinline__ void stage_load(const uint32_t *tile, int col, int la
 // Second half of stage_tile: the products with the factor's table, the diagonal, and the results back into the
 // tile (or to gout).  The table operands of the next row tile are read before the results of the current one
 // are written, so that their latency is covered by the diagonal's arithmetic.
-template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false>
+template <int F, int PITCH, bool STRIDED, int TW, bool GOUT = false, bool TREG = false, bool SWZ = false>
 __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, const StageOps<F> &ops, int col, int lane, int live_ks,
                                              int want_jt, int alpha, int beta, float inv_mod, float2 *gout = nullptr, int gstride = 0,
                                              const float2 *twp = nullptr)
@@ -152,8 +157,13 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
 #pragma unroll
         for (int tk = 0; tk < TKS; ++tk) {
             if (tk < live_ks) {
-                ar[tk] = tab[(jt * TKS + tk) * 128 + lane];
-                ai[tk] = tab[(jt * TKS + tk) * 128 + 64 + lane];
+                if constexpr (TREG) {   // this lane's operands, kept in registers by the caller: [jt][tk][re, im]
+                    ar[tk] = tab[(jt * TKS + tk) * 2];
+                    ai[tk] = tab[(jt * TKS + tk) * 2 + 1];
+                } else {
+                    ar[tk] = tab[(jt * TKS + tk) * 128 + lane];
+                    ai[tk] = tab[(jt * TKS + tk) * 128 + 64 + lane];
+                }
             }
         }
     };
@@ -185,10 +195,11 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
             if constexpr (GOUT) {
             } else if constexpr (STRIDED) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tile[row_of<F>(jt, 4 * kg + r) * PITCH + col] = o[r];
+                for (int r = 0; r < 4; ++r)
+                    tile[row_of<F>(jt, 4 * kg + r) * PITCH + (SWZ ? col ^ swz_bit(HALF ? 8 * kg : 16 * jt + 4 * kg) : col)] = o[r];
             } else if constexpr (HALF) {   // rows 32 J + 8 kg + 2 r + parity: the pair of tiles holds 8 neighbours
                 if (jt & 1) {
-                    uint32_t *dst = tile + col * PITCH + 32 * (jt >> 1) + 8 * kg;
+                    uint32_t *dst = tile + col * PITCH + ((32 * (jt >> 1) + 8 * kg) ^ (SWZ ? swz_bit(col) : 0));
                     *reinterpret_cast<u32x4 *>(dst) = u32x4{even[0], o[0], even[1], o[1]};
                     *reinterpret_cast<u32x4 *>(dst + 4) = u32x4{even[2], o[2], even[3], o[3]};
                 } else {
@@ -196,7 +207,7 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
                     for (int r = 0; r < 4; ++r) even[r] = o[r];
                 }
             } else {
-                *reinterpret_cast<u32x4 *>(tile + col * PITCH + 16 * jt + 4 * kg) = u32x4{o[0], o[1], o[2], o[3]};
+                *reinterpret_cast<u32x4 *>(tile + col * PITCH + ((16 * jt + 4 * kg) ^ (SWZ ? swz_bit(col) : 0))) = u32x4{o[0], o[1], o[2], o[3]};
             }
         }
         if constexpr (TW == 1) {
@@ -759,12 +770,6 @@ __device__ __forceinline__ void separation_sums(uint32_t z, uint32_t zm, uint32_
 // takes chunk o and chunk O - o of a row together, four tiles in LDS (0: u chunk o, 1: u mirror chunk, 2 and 3
 // the same of k).  Chunks 0 and O / 2 mirror onto themselves and take a turn each with two tiles.  Nothing of the
 // spectra ever reaches HBM.
-#ifdef MONARCH_TUNE_ENV
-__constant__ int g_mid_skip;
-#define MIDSKIP(b) (g_mid_skip & (b))
-#else
-#define MIDSKIP(b) false
-#endif
 template <int F1, int F2, int THREADS>
 __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(const Fft2Args p)
 {
@@ -781,7 +786,19 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const float inv_mod = 1.0f / (float)CH;
-    auto tix = [](int e) { return (e / F2) * PITCH + (e % F2); };
+    constexpr bool SWZ = F1 >= 32 && F2 >= 32;   // (see stage_load)
+    auto at_of = [](int row, int col) { return row * PITCH + (SWZ ? col ^ swz_bit(row) : col); };
+    auto tix = [&](int e) { return at_of(e / F2, e % F2); };
+    // this lane's operands of the two factor matrices stay in registers for the whole kernel
+    constexpr int T1 = (F1 / 16) * table_ks(F1) * 2, T2 = (F2 / 16) * table_ks(F2) * 2;
+    u32x4 treg1[T1], treg2[F1 == F2 ? 1 : T2];
+#pragma unroll
+    for (int q = 0; q < T1; ++q) treg1[q] = tab1[q * 64 + lane];
+    if constexpr (F1 != F2) {
+#pragma unroll
+        for (int q = 0; q < T2; ++q) treg2[q] = tab2[q * 64 + lane];
+    }
+    const u32x4 *tr1 = treg1, *tr2 = F1 == F2 ? treg1 : treg2;
     // a turn is a chunk o in 1 .. O/2 - 1 with its mirror O - o, or (turn 0) the two chunks 0 and O/2 that mirror onto
     // themselves: every turn carries four tiles and the same work
     const int turns_per_row = p.O / 2;
@@ -811,10 +828,7 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
     };
 
     int64_t turn = blockIdx.x;
-    if (MIDSKIP(16)) {
-        for (int t = 0; t < 4; ++t)
-            for (int it = 0; it < NIT4; ++it) z[t][it] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-    } else if (turn < nturns) request(turn);
+    if (turn < nturns) request(turn);
     for (; turn < nturns; turn += gridDim.x) {
         const int64_t row = turn / turns_per_row;
         const int o = (int)(turn - row * turns_per_row), om = o ? p.O - o : p.O / 2;
@@ -827,27 +841,25 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
             }
         }
         __syncthreads();
-        if (!MIDSKIP(16) && turn + gridDim.x < nturns) request(turn + gridDim.x);
+        if (turn + gridDim.x < nturns) request(turn + gridDim.x);
 
         // ---- forward chunk factors of the row (tiles 0, 1) and of its kernel row (tiles 2, 3)
         constexpr int KX = (F1 + 31) / 32, KY = (F2 + 31) / 32;
-        if (!MIDSKIP(4)) {
         staged_tasks<F1, 4 * XT, WAVES>(
-            wave, [&](int t, StageOps<F1> &ops) { stage_load<F1, PITCH, true>(lds + (t / XT) * TILE, 16 * (t % XT) + l16, lane, KX, ops); },
+            wave, [&](int t, StageOps<F1> &ops) { stage_load<F1, PITCH, true, SWZ>(lds + (t / XT) * TILE, 16 * (t % XT) + l16, lane, KX, ops); },
             [&](int t, const StageOps<F1> &ops) {
                 const int col = 16 * (t % XT) + l16;
                 if constexpr (HOIST)
-                    stage_finish<F1, PITCH, true, 2>(lds + (t / XT) * TILE, tab1, ops, col, lane, KX, F1 / 16, 0, 0, inv_mod, nullptr, 0, twx);
+                    stage_finish<F1, PITCH, true, 2, false, true, SWZ>(lds + (t / XT) * TILE, tr1, ops, col, lane, KX, F1 / 16, 0, 0, inv_mod, nullptr, 0, twx);
                 else
-                    stage_finish<F1, PITCH, true, 1>(lds + (t / XT) * TILE, tab1, ops, col, lane, KX, F1 / 16, col, 0, inv_mod);
+                    stage_finish<F1, PITCH, true, 1, false, true, SWZ>(lds + (t / XT) * TILE, tr1, ops, col, lane, KX, F1 / 16, col, 0, inv_mod);
             });
         __syncthreads();
         staged_tasks<F2, 4 * YT, WAVES>(
-            wave, [&](int t, StageOps<F2> &ops) { stage_load<F2, PITCH, false>(lds + (t / YT) * TILE, 16 * (t % YT) + l16, lane, KY, ops); },
+            wave, [&](int t, StageOps<F2> &ops) { stage_load<F2, PITCH, false, SWZ>(lds + (t / YT) * TILE, 16 * (t % YT) + l16, lane, KY, ops); },
             [&](int t, const StageOps<F2> &ops) {
-                stage_finish<F2, PITCH, false, 0>(lds + (t / YT) * TILE, tab2, ops, 16 * (t % YT) + l16, lane, KY, F2 / 16, 0, 0, inv_mod);
+                stage_finish<F2, PITCH, false, 0, false, true, SWZ>(lds + (t / YT) * TILE, tr2, ops, 16 * (t % YT) + l16, lane, KY, F2 / 16, 0, 0, inv_mod);
             });
-        }
         __syncthreads();
 
         // ---- separation and products.  z = a + i b and kz = ka + i kb carry two real channels each:
@@ -867,7 +879,6 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
         };
         uint32_t *res0 = lds;            // the product tile of chunk o
         uint32_t *res1 = lds + TILE;     // the product tile of chunk O - o (turn 0: of chunk O / 2)
-        if (!MIDSKIP(2)) {
         // The mirror of position e of chunk o is position CH - 1 - e of chunk O - o: 16-byte pieces read backwards.
         // Chunk O / 2 mirrors onto itself that way: the lower half of its positions does both ends.
         {
@@ -901,8 +912,8 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
                 const int j1 = e / F2, j2 = e - j1 * F2;
                 const bool mine = j1 == 0 ? j2 <= F2 / 2 : (j1 < F1 / 2 || j2 < F2 / 2);
                 if (mine) {
-                    const int at = j1 * PITCH + j2;
-                    const int m = ((F1 - j1) % F1) * PITCH + (j1 ? F2 - 1 - j2 : (F2 - j2) % F2);
+                    const int at = at_of(j1, j2);
+                    const int m = at_of((F1 - j1) % F1, j1 ? F2 - 1 - j2 : (F2 - j2) % F2);
                     uint32_t w, w2;
                     separate(lds[at], lds[m], lds[2 * TILE + at], lds[2 * TILE + m], w, w2);
                     lds[at] = w;
@@ -910,28 +921,25 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
                 }
             }
         }
-        }
         __syncthreads();
-        if (!MIDSKIP(8)) {
 
         // ---- inverse chunk factors, then the diagonal omega_N^(o (f2 c1 + c2)) that precedes the first factor's inverse
         staged_tasks<F2, 2 * YT, WAVES>(
-            wave, [&](int t, StageOps<F2> &ops) { stage_load<F2, PITCH, false>(t / YT ? res1 : res0, 16 * (t % YT) + l16, lane, KY, ops); },
+            wave, [&](int t, StageOps<F2> &ops) { stage_load<F2, PITCH, false, SWZ>(t / YT ? res1 : res0, 16 * (t % YT) + l16, lane, KY, ops); },
             [&](int t, const StageOps<F2> &ops) {
                 const int col = 16 * (t % YT) + l16;
                 if constexpr (HOIST)
-                    stage_finish<F2, PITCH, false, 2>(t / YT ? res1 : res0, tab2, ops, col, lane, KY, F2 / 16, 0, 0, inv_mod, nullptr, 0, twy);
+                    stage_finish<F2, PITCH, false, 2, false, true, SWZ>(t / YT ? res1 : res0, tr2, ops, col, lane, KY, F2 / 16, 0, 0, inv_mod, nullptr, 0, twy);
                 else
-                    stage_finish<F2, PITCH, false, 1>(t / YT ? res1 : res0, tab2, ops, col, lane, KY, F2 / 16, col, 0, inv_mod);
+                    stage_finish<F2, PITCH, false, 1, false, true, SWZ>(t / YT ? res1 : res0, tr2, ops, col, lane, KY, F2 / 16, col, 0, inv_mod);
             });
         __syncthreads();
         staged_tasks<F1, 2 * XT, WAVES>(
-            wave, [&](int t, StageOps<F1> &ops) { stage_load<F1, PITCH, true>(t / XT ? res1 : res0, 16 * (t % XT) + l16, lane, KX, ops); },
+            wave, [&](int t, StageOps<F1> &ops) { stage_load<F1, PITCH, true, SWZ>(t / XT ? res1 : res0, 16 * (t % XT) + l16, lane, KX, ops); },
             [&](int t, const StageOps<F1> &ops) {
                 const int col = 16 * (t % XT) + l16, oo = t / XT ? om : o;
-                stage_finish<F1, PITCH, true, 1>(t / XT ? res1 : res0, tab1, ops, col, lane, KX, F1 / 16, oo * F2, oo * col, 1.0f / (float)p.N);
+                stage_finish<F1, PITCH, true, 1, false, true, SWZ>(t / XT ? res1 : res0, tr1, ops, col, lane, KX, F1 / 16, oo * F2, oo * col, 1.0f / (float)p.N);
             });
-        }
         __syncthreads();
 
         uint32_t *dst = (uint32_t *)p.out + row * p.N + (int64_t)o * CH;
@@ -939,7 +947,7 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
 #pragma unroll
         for (int it = 0; it < NIT4; ++it) {
             const int e = 4 * (tid + it * THREADS);
-            if (e < CH && !MIDSKIP(1)) {
+            if (e < CH) {
                 *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(res0 + tix(e));
                 *reinterpret_cast<u32x4 *>(dst2 + e) = *reinterpret_cast<const u32x4 *>(res1 + tix(e));
             }
@@ -966,15 +974,6 @@ static int launch_middle(const Fft2Args &p, hipStream_t s)
     int64_t grid = (int64_t)ncu * (per_cu < 1 ? 1 : per_cu > 2 ? 2 : per_cu);
     if (grid > nturns) grid = nturns;
     auto kern = conv3_middle_kernel<F1, F2, THREADS>;
-#ifdef MONARCH_TUNE_ENV
-    static bool skip_set = false;
-    if (!skip_set) {
-        skip_set = true;
-        const char *e = getenv("MONARCH_MID_SKIP");
-        const int v = e ? atoi(e) : 0;
-        MONARCH_HIP_CHECK(hipMemcpyToSymbol(HIP_SYMBOL(g_mid_skip), &v, sizeof(int)));
-    }
-#endif
     if (lds > 48 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, p);

@@ -638,11 +638,11 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass 
 
 // Last pass.  The results of a block, scaled, go to LDS as fp32 [real row][j][column]; the threads then take them
 // in pieces of 8 columns, apply the output gate and store 16 bytes.  wra: rows j kept, a multiple of 16.
-template <int F, bool PAIR>
-__global__ __launch_bounds__(256, 2) void fft_pass_rows_out_kernel(const FftPass p, const int wra)
+// MAXT: bound on the pieces per thread, NP wra / 16.
+template <int F, bool PAIR, int MAXT>
+__global__ __launch_bounds__(256, MAXT <= 4 ? 3 : 2) void fft_pass_rows_out_kernel(const FftPass p, const int wra)
 {
     constexpr int JT = F / 16, KS = (F + 31) / 32, THREADS = 256, NP = PAIR ? 2 : 1;
-    constexpr int MAXT = F * NP * 16 / THREADS;   // most pieces per thread
     extern __shared__ __attribute__((aligned(16))) u32x4 ftab[];
     float *stage = reinterpret_cast<float *>(ftab + JT * KS * 128);   // [NP][wra][RB_PITCH]
     build_ftab<F, THREADS>(ftab);
@@ -669,12 +669,7 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_out_kernel(const FftPass
             const int c0 = 32 * ks + 8 * kg;
             uint32_t w[8][2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool ok = c0 + e < F;
-                load_words<2>((const uint32_t *)p.in + rc * p.N + col0 + (ok ? (c0 + e) * S : 0), w[e]);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) w[e][t] = ok ? w[e][t] : 0u;
-            }
+            for (int e = 0; e < 8; ++e) load_words<2>((const uint32_t *)p.in + rc * p.N + col0 + (c0 + e) * S, w[e]);   // (c0 + e < F: F is 32 or 64)
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -824,7 +819,8 @@ static int launch_rows_out_np(const FftPass &p, hipStream_t s)
     int grid = 0;
     const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, &grid);
     if (rc != MONARCH_OK) return rc;
-    auto kern = fft_pass_rows_out_kernel<F, PAIR>;
+    const int npieces = (PAIR ? 2 : 1) * wra / 16;
+    auto kern = npieces <= 2 ? fft_pass_rows_out_kernel<F, PAIR, 2> : npieces <= 4 ? fft_pass_rows_out_kernel<F, PAIR, 4> : fft_pass_rows_out_kernel<F, PAIR, 8>;
     if (lds > 48 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, s, p, wra);
