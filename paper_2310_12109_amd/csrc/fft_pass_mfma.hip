@@ -41,7 +41,11 @@ __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c)
 // First of the two real rows packed as (re, im) in complex row rc; the second is pair_stride rows on.
 __device__ __forceinline__ int64_t pair_first_row(const FftPass &p, int64_t rc)
 {
-    return rc + (rc / p.pair_stride) * p.pair_stride;   // (rc / ps) * 2 ps + rc % ps
+    // 32-bit arithmetic (row counts stay far below 2^31), a shift when the stride is a power of two: a 64-bit
+    // division costs a wave some 150 scalar instructions, as much as the rest of a tile's index arithmetic
+    const uint32_t r = (uint32_t)rc, ps = (uint32_t)p.pair_stride;
+    const uint32_t q = (ps & (ps - 1)) == 0 ? r >> __builtin_ctz(ps) : r / ps;
+    return (int64_t)r + (int64_t)q * ps;   // (rc / ps) * 2 ps + rc % ps
 }
 
 // NT adjacent 32-bit words / bf16 values with one access (NT = 1 or 2; the callers guarantee the
@@ -105,7 +109,7 @@ __device__ __forceinline__ void load_values(const FftPass &p, int64_t rc, int po
         load_words<NT>((const uint32_t *)p.in + rc * p.N + pos, w);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const float2 k = p.kf[(rc % p.H) * (int64_t)p.N + pos + t];
+            const float2 k = p.kf[(int64_t)((uint32_t)rc % (uint32_t)p.H) * p.N + pos + t];
             const float2 m = cmul(make_float2(lo_f32(w[t]), hi_f32(w[t])), k);
             re[t] = m.x;
             im[t] = -m.y;
@@ -215,6 +219,8 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
     const int lane = threadIdx.x & 63, l16 = lane & 15, kg = lane >> 4;
     const int S = p.S, O = p.O;
     const int tiles_per_unit = (CONTIG ? O : S) / COLS;           // unit: a row (CONTIG) or one (row, o)
+    // O and S are products of the factors 16 .. 128, powers of two: the index arithmetic below is shifts
+    const int tpu_shift = __builtin_ctz(tiles_per_unit), o_shift = __builtin_ctz(O);
     const int64_t ntiles = p.rows * (CONTIG ? 1 : O) * tiles_per_unit;
     const float inv_fs = 1.0f / (float)((int64_t)F * S);
 
@@ -223,8 +229,8 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
         int col0;       // first of this lane's columns: s (S >= 16) or natural low index rho (S == 1)
         int base[NT];   // CONTIG: position of (o(col0 + t), c = 0); else base[0]: position of (o, c = 0, s = col0)
         if constexpr (CONTIG) {
-            rc = tile / tiles_per_unit;
-            col0 = (int)(tile - rc * tiles_per_unit) * COLS + NT * l16;
+            rc = tile >> tpu_shift;
+            col0 = (int)(tile - (rc << tpu_shift)) * COLS + NT * l16;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 int o = col0 + t;   // two factors: the digit itself; three: swap the two digits already produced
@@ -232,10 +238,10 @@ __global__ __launch_bounds__(F == 128 ? 512 : 256, F == 128 ? 4 : 2) void fft_pa
                 base[t] = o * F;
             }
         } else {
-            const int64_t unit = tile / tiles_per_unit;
-            col0 = (int)(tile - unit * tiles_per_unit) * COLS + NT * l16;
-            rc = unit / O;
-            base[0] = (int)(unit - rc * O) * F * S + col0;
+            const int64_t unit = tile >> tpu_shift;
+            col0 = (int)(tile - (unit << tpu_shift)) * COLS + NT * l16;
+            rc = unit >> o_shift;
+            base[0] = (int)(unit - (rc << o_shift)) * F * S + col0;
         }
 
         // ---- B operands: k-step ks, slot e  <->  c = 32 ks + 8 kg + e
@@ -482,7 +488,7 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass 
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int S = p.S, blocks_per_row = S / RB_COLS;
+    const int S = p.S, blocks_per_row = S / RB_COLS, bpr_shift = __builtin_ctz(blocks_per_row);   // S is a power of two
     const int64_t nblocks = p.rows * blocks_per_row;
     const float inv_fs = 1.0f / (float)((int64_t)F * S);
     const bool gated = p.gate != nullptr;
@@ -491,8 +497,8 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass 
 
     u32x4 val[LS][NP][2], gat[LS][NP][2];   // [k-step][real row][row of the pair]
     auto request = [&](int64_t blk) {
-        const int64_t rc = blk / blocks_per_row;
-        const int s0 = (int)(blk - rc * blocks_per_row) * RB_COLS + 8 * piece;
+        const int64_t rc = blk >> bpr_shift;
+        const int s0 = (int)(blk - (rc << bpr_shift)) * RB_COLS + 8 * piece;
         const int64_t ra = PAIR ? pair_first_row(p, rc) : rc;
         const bool hasb = PAIR && ra + p.pair_stride < p.real_rows;
 #pragma unroll
@@ -512,8 +518,8 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass 
     };
     // rounds the (gated) values to bf16 and writes the pairs of rows 2 rp, 2 rp + 1
     auto deposit = [&](int64_t blk) {
-        const int64_t rc = blk / blocks_per_row;
-        const int s0 = (int)(blk - rc * blocks_per_row) * RB_COLS + 8 * piece;
+        const int64_t rc = blk >> bpr_shift;
+        const int s0 = (int)(blk - (rc << bpr_shift)) * RB_COLS + 8 * piece;
         const int64_t ra = PAIR ? pair_first_row(p, rc) : rc;
         const bool hasb = PAIR && ra + p.pair_stride < p.real_rows;
 #pragma unroll
@@ -583,8 +589,8 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass 
             }
         __syncthreads();   // the planes are free for the next block
 
-        const int64_t rc = blk / blocks_per_row;
-        const int col0 = (int)(blk - rc * blocks_per_row) * RB_COLS + 32 * wave + 2 * l16;
+        const int64_t rc = blk >> bpr_shift;
+        const int col0 = (int)(blk - (rc << bpr_shift)) * RB_COLS + 32 * wave + 2 * l16;
         // twiddle seeds: omega_(fS)^(j s) for j = 4 kg + r, stepped by omega_(fS)^(16 s) per row tile
         float2 tw[2][4], step[2];
 #pragma unroll
@@ -649,15 +655,15 @@ __global__ __launch_bounds__(256, MAXT <= 4 ? 3 : 2) void fft_pass_rows_out_kern
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int S = p.S, blocks_per_row = S / RB_COLS;
+    const int S = p.S, blocks_per_row = S / RB_COLS, bpr_shift = __builtin_ctz(blocks_per_row);   // S is a power of two
     const int64_t nblocks = p.rows * blocks_per_row;
     const bool gated = p.gate != nullptr;
     const int piece = tid & 15, row0 = tid >> 4;   // this thread's pieces: columns 8 piece .. + 7 of rows row0 + 16 i of [NP][wra]
     const int npieces = NP * wra / 16;             // per thread
 
     for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
-        const int64_t rc = blk / blocks_per_row;
-        const int s0 = (int)(blk - rc * blocks_per_row) * RB_COLS;
+        const int64_t rc = blk >> bpr_shift;
+        const int s0 = (int)(blk - (rc << bpr_shift)) * RB_COLS;
         const int col0 = s0 + 32 * wave + 2 * l16;
         const int64_t ra = PAIR ? pair_first_row(p, rc) : rc;
         const bool hasb = PAIR && ra + p.pair_stride < p.real_rows;
@@ -759,6 +765,9 @@ static int rows_kernel_grid(int64_t nblocks, size_t lds, int *grid)
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     int per_cu = (int)((160 * 1024) / (lds + 1024));
     per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
+#ifdef MONARCH_TUNE_ENV
+    if (const char *e = getenv("MONARCH_ROWS_PER_CU")) per_cu = atoi(e);
+#endif
     const int64_t cap = (int64_t)ncu * per_cu;
     *grid = (int)(nblocks < cap ? nblocks : cap);
     return MONARCH_OK;
@@ -915,6 +924,8 @@ int launch_fft_pass_mfma(const FftPass &p, hipStream_t s)
              : (p.S % 16 != 0 || (real_out ? (p.O != 1 || p.load != LD_C16) : p.store != ST_C16)))
         return fail(MONARCH_EINVAL, "internal: MFMA pass geometry O=%d f=%d S=%d load=%d store=%d", p.O, p.f, p.S, p.load, p.store);
     if ((int64_t)p.O * p.f * p.S != p.N) return fail(MONARCH_EINVAL, "internal: pass geometry does not multiply to N");
+    if ((p.O & (p.O - 1)) || (p.S & (p.S - 1)) || p.rows >= (int64_t)1 << 31)   // the kernels index with shifts and 32-bit row numbers
+        return fail(MONARCH_EINVAL, "internal: MFMA pass needs power-of-two digits, got O=%d S=%d", p.O, p.S);
     if (fpm::rows_in_applies(p)) return p.f == 64 ? fpm::launch_rows_in<64>(p, s) : fpm::launch_rows_in<32>(p, s);
     if (fpm::rows_out_applies(p)) return p.f == 64 ? fpm::launch_rows_out<64>(p, s) : fpm::launch_rows_out<32>(p, s);
     switch (p.f) {
