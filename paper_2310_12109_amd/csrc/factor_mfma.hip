@@ -177,6 +177,139 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
     }
 }
 
+
+// The same factor with resident weights: a workgroup keeps going over tiles of 16 tokens (tile blockIdx.x,
+// + gridDim.x, ...).  Every wave owns the same UPW units (block, row tile) in each tile, so their weights are
+// loaded once per workgroup and stay in registers; the token rows of the next tile are requested before the
+// current tile is multiplied; each thread's pieces of the rows sit at the same places in every tile, so the
+// piece arithmetic and the bias are computed once.  NPI / NPO: 16-byte pieces per thread of a tile's input /
+// output rows (16 d / 8 pieces over 1024 threads; d <= 1024).
+template <typename E, int KS, int MODE, int UPW>
+__global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restrict__ in, E *__restrict__ out,
+                                                                 int64_t tokens, int nb, int r_out, const E *__restrict__ W,
+                                                                 const E *__restrict__ bias, int ntiles)
+{
+    constexpr int RIN = 32 * KS, TOK = 16, NPI = 2, NPO = 2;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    const int d_in = nb * RIN, d_out = nb * r_out;
+    const int ld_in = d_in + 8, ld_out = d_out + 8;
+    uint16_t *tin = lds, *tout = lds + TOK * ld_in;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+
+    const int mts = r_out / 16, units = nb * mts;
+    Pack8 a[UPW][KS];
+    int uk[UPW], umt[UPW];
+#pragma unroll
+    for (int b = 0; b < UPW; ++b) {
+        int u = wave + b * WAVES;
+        if (u >= units) u = units - 1;   // (computed and dropped)
+        uk[b] = u / mts;
+        umt[b] = u - uk[b] * mts;
+        const E *wrow = W + ((size_t)uk[b] * r_out + 16 * umt[b] + l16) * RIN + 8 * kg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) a[b][ks].q = *reinterpret_cast<const uint4 *>(wrow + 32 * ks);
+    }
+
+    // this thread's pieces of a tile: input piece q covers elements o .. o + 7 of token t
+    const int pin = d_in / 8, npin = TOK * pin, pout = d_out / 8, npout = TOK * pout;
+    int it[NPI], io[NPI], ot[NPO], oo[NPO];
+    Pack8 bv[NPO];
+#pragma unroll
+    for (int q = 0; q < NPI; ++q) {
+        const int idx = tid + q * THREADS < npin ? tid + q * THREADS : tid;   // (tid < npin: d_in >= 512)
+        it[q] = idx / pin;
+        io[q] = (idx - it[q] * pin) * 8;
+    }
+#pragma unroll
+    for (int q = 0; q < NPO; ++q) {
+        const int idx = tid + q * THREADS < npout ? tid + q * THREADS : tid;
+        ot[q] = idx / pout;
+        oo[q] = (idx - ot[q] * pout) * 8;
+        bv[q].q = make_uint4(0u, 0u, 0u, 0u);
+        if (bias) bv[q].q = *reinterpret_cast<const uint4 *>(bias + oo[q]);
+    }
+
+    Pack8 v[NPI];
+    auto request = [&](int tile) {
+#pragma unroll
+        for (int q = 0; q < NPI; ++q)
+            if (q == 0 || tid + q * THREADS < npin) {
+                int64_t tt = (int64_t)tile * TOK + it[q];
+                if (tt >= tokens) tt = tokens - 1;   // clamp: computed, never stored
+                v[q].q = *reinterpret_cast<const uint4 *>(in + tt * d_in + io[q]);
+            }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < ntiles) request(tile);
+    const uint16_t *row = tin + l16 * ld_in + 8 * kg;
+    for (; tile < ntiles; tile += gridDim.x) {
+        // token rows -> LDS, element i of a row to its block-major position
+#pragma unroll
+        for (int q = 0; q < NPI; ++q)
+            if (tid + q * THREADS < npin) {
+                uint16_t *dst = tin + it[q] * ld_in;
+                const int o = io[q];
+                if (MODE == IN_SECOND) {
+                    *reinterpret_cast<uint4 *>(dst + o) = v[q].q;
+                } else if (MODE == IN_FIRST) {        // i = c nb + k  ->  k RIN + c
+                    int c = o / nb, k = o - c * nb;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        dst[k * RIN + c] = v[q].h[e];
+                        if (++k == nb) {
+                            k = 0;
+                            ++c;
+                        }
+                    }
+                } else {                               // i = kk RIN + r (previous factor's block kk, row r)  ->  r nb + kk
+                    const int kk = o / RIN, r = o - kk * RIN;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dst[(r + e) * nb + kk] = v[q].h[e];
+                }
+            }
+        __syncthreads();
+        if (tile + (int)gridDim.x < ntiles) request(tile + gridDim.x);
+
+#pragma unroll
+        for (int b = 0; b < UPW; ++b)
+            if (wave + b * WAVES < units) {
+                f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    Pack8 xop;
+                    xop.q = *reinterpret_cast<const uint4 *>(row + uk[b] * RIN + 32 * ks);
+                    acc = h16::mfma<E>(a[b][ks].v, xop.v, acc);
+                }
+                // rows r = 16 mt + 4 kg + i of block k, token l16  ->  output position r nb + k (rounded here; the
+                // bias is added to that value at copy-out and the sum rounded again)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    tout[l16 * ld_out + (16 * umt[b] + 4 * kg + i) * nb + uk[b]] = __builtin_bit_cast(uint16_t, (E)acc[i]);
+            }
+        __syncthreads();
+
+#pragma unroll
+        for (int q = 0; q < NPO; ++q)
+            if (tid + q * THREADS < npout) {
+                const int64_t tt = (int64_t)tile * TOK + ot[q];
+                Pack8 r;
+                r.q = *reinterpret_cast<const uint4 *>(tout + ot[q] * ld_out + oo[q]);
+                if (bias) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float sum = (float)__builtin_bit_cast(E, r.h[e]) + (float)__builtin_bit_cast(E, bv[q].h[e]);
+                        r.h[e] = __builtin_bit_cast(uint16_t, (E)sum);
+                    }
+                }
+                if (tt < tokens) *reinterpret_cast<uint4 *>(out + tt * d_out + oo[q]) = r.q;
+            }
+        // (the next tile's rows go to tin, which nobody reads any more; tout is rewritten only after the next barrier)
+    }
+}
+
 }  // namespace fac
 
 bool factor_mfma_supported(int nb, int r_out, int r_in, monarch_dtype dt)
@@ -188,14 +321,80 @@ bool factor_mfma_supported(int nb, int r_out, int r_in, monarch_dtype dt)
 
 namespace {
 
+template <typename E, int KS, int MODE, int UPW>
+int launch_resident_one(const void *in, void *out, int64_t tokens, int nb, int r_out, const void *W, const void *bias,
+                        hipStream_t s)
+{
+    const size_t lds = fac::lds_bytes(16, nb, r_out, 32 * KS);
+    const int64_t ntiles = (tokens + 15) / 16;
+    if (ntiles > 0x7fffffffLL) return fail(MONARCH_ESHAPE, "too many tokens for one launch");
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    auto kern = fac::factor_resident_kernel<E, KS, MODE, UPW>;
+    if (lds > 48 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    int per_cu = 1;   // workgroups that fit a compute unit at once (registers and LDS): the grid is exactly one round
+    MONARCH_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, fac::THREADS, lds));
+    if (per_cu < 1) per_cu = 1;
+    const int64_t cap = (int64_t)ncu * per_cu;
+    const int64_t grid = ntiles < cap ? ntiles : cap;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(fac::THREADS), lds, s, (const E *)in, (E *)out, tokens, nb, r_out,
+                       (const E *)W, (const E *)bias, (int)ntiles);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+template <typename E, int KS, int UPW>
+int launch_resident_mode(const void *in, void *out, int64_t tokens, int nb, int r_out, const void *W, const void *bias,
+                         int mode, hipStream_t s)
+{
+    if (mode == fac::IN_FIRST) return launch_resident_one<E, KS, fac::IN_FIRST, UPW>(in, out, tokens, nb, r_out, W, bias, s);
+    if (mode == fac::IN_SECOND) return launch_resident_one<E, KS, fac::IN_SECOND, UPW>(in, out, tokens, nb, r_out, W, bias, s);
+    return launch_resident_one<E, KS, fac::IN_SECOND_GATHER, UPW>(in, out, tokens, nb, r_out, W, bias, s);
+}
+
+template <typename E>
+int launch_resident(const void *in, void *out, int64_t tokens, int nb, int r_out, int r_in, const void *W, const void *bias,
+                    int mode, int upw, hipStream_t s)
+{
+#define MONARCH_RES(KSV)                                                                                      \
+    case KSV:                                                                                                 \
+        if constexpr (KSV * 2 <= 12) {                                                                        \
+            if (upw == 2) return launch_resident_mode<E, KSV, 2>(in, out, tokens, nb, r_out, W, bias, mode, s); \
+        }                                                                                                     \
+        if constexpr (KSV * 4 <= 12) {                                                                        \
+            if (upw == 4) return launch_resident_mode<E, KSV, 4>(in, out, tokens, nb, r_out, W, bias, mode, s); \
+        }                                                                                                     \
+        break;
+    switch (r_in / 32) {
+        MONARCH_RES(1)
+        MONARCH_RES(2)
+        MONARCH_RES(3)
+        MONARCH_RES(4)
+        MONARCH_RES(5)
+        MONARCH_RES(6)
+    default: break;
+    }
+#undef MONARCH_RES
+    return fail(MONARCH_EINVAL, "internal: resident factor kernel %d x %d units not built", r_in / 32, upw);
+}
+
 template <typename E>
 int launch_typed(const void *in, void *out, int64_t tokens, int nb, int r_out, int r_in, const void *W,
                  const void *bias, int mode, hipStream_t s)
 {
     if (tokens == 0) return MONARCH_OK;
-    // 16 tokens per workgroup: measured faster than 32 (which halves the weight traffic out of L2
-    // but leaves one workgroup per compute unit with twice the serial copy-in / copy-out time)
-    const int tok = 16;
+    const int tok = 16;   // tokens per tile
+    {
+        // resident weights when a wave's share of them fits in registers and a thread has at most two pieces of a
+        // tile's rows on either side
+        const int units = nb * (r_out / 16), upw = (units + fac::WAVES - 1) / fac::WAVES, ks = r_in / 32;
+        const int d_in = nb * r_in, d_out = nb * r_out;
+        const int built = upw <= 2 ? 2 : 4;   // units per wave of the instantiated kernels
+        if (upw <= 4 && built * ks <= 12 && d_in >= 512 && d_in <= 1024 && d_out >= 512 && d_out <= 1024)
+            return launch_resident<E>(in, out, tokens, nb, r_out, r_in, W, bias, mode, built, s);
+    }
     const int64_t grid = (tokens + tok - 1) / tok;
     if (grid > 0x7fffffffLL) return fail(MONARCH_ESHAPE, "too many tokens for one launch");
     const size_t lds = fac::lds_bytes(tok, nb, r_out, r_in);
@@ -210,15 +409,9 @@ int launch_typed(const void *in, void *out, int64_t tokens, int nb, int r_out, i
     } while (0)
 #define MONARCH_LAUNCH_FAC_MODE(KSV)                                         \
     do {                                                                     \
-        if (tok == 32) {                                                     \
-            if (mode == fac::IN_FIRST) MONARCH_LAUNCH_FAC(KSV, fac::IN_FIRST, 2);   \
-            else if (mode == fac::IN_SECOND) MONARCH_LAUNCH_FAC(KSV, fac::IN_SECOND, 2); \
-            else MONARCH_LAUNCH_FAC(KSV, fac::IN_SECOND_GATHER, 2);          \
-        } else {                                                             \
-            if (mode == fac::IN_FIRST) MONARCH_LAUNCH_FAC(KSV, fac::IN_FIRST, 1);   \
-            else if (mode == fac::IN_SECOND) MONARCH_LAUNCH_FAC(KSV, fac::IN_SECOND, 1); \
-            else MONARCH_LAUNCH_FAC(KSV, fac::IN_SECOND_GATHER, 1);          \
-        }                                                                    \
+        if (mode == fac::IN_FIRST) MONARCH_LAUNCH_FAC(KSV, fac::IN_FIRST, 1);   \
+        else if (mode == fac::IN_SECOND) MONARCH_LAUNCH_FAC(KSV, fac::IN_SECOND, 1); \
+        else MONARCH_LAUNCH_FAC(KSV, fac::IN_SECOND_GATHER, 1);              \
     } while (0)
     switch (r_in / 32) {
     case 1: MONARCH_LAUNCH_FAC_MODE(1); break;
