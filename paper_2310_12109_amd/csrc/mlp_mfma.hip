@@ -65,6 +65,38 @@ template <typename E> __device__ __forceinline__ uint32_t gelu_pack(float z0, fl
     return pack16<E>(g0, g1);
 }
 
+// The same for pre-activations that arrive divided by four (W1 and b1 scaled by 1/4, exact in binary floating point):
+// returns GELU / 4 (the caller scales W2 by 4).  The division by four of gelu_pack is gone, and instead of clamping
+// t the last step clamps Phi to [0, 1] with the instruction's own output modifier: beyond the fitted range the
+// polynomial keeps growing (checked over every fp16 t: Phi within 8.4e-4, no NaN, infinities end at 0 or 1).
+// 10 instructions per pair.
+template <typename E> __device__ __forceinline__ uint32_t gelu_pack_quarter(float t0, float t1)
+{
+    const f16x2 t = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(t0, t1));
+    const f16x2 u = t * t - splat16(0.4f);
+    f16x2 q = splat16(4.0132f);
+    q = q * u + splat16(-2.2824f);
+    q = q * u + splat16(1.2712f);
+    q = q * u + splat16(-0.8877f);
+    q = q * u + splat16(0.7821f);
+    f16x2 w;
+    const f16x2 half = splat16(0.5f);
+    asm("v_pk_fma_f16 %0, %1, %2, %3 clamp" : "=v"(w) : "v"(t), "v"(q), "v"(half));
+    float g0, g1;   // Phi (fp16, low / high half) times the scaled pre-activation (fp32)
+    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(g0) : "v"(w), "v"(t0));
+    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(g1) : "v"(w), "v"(t1));
+    return pack16<E>(g0, g1);
+}
+
+// eight packed elements times a power of two (exact but for results below the smallest normal number)
+template <typename E> __device__ __forceinline__ uint4 scale8(uint4 v, float f)
+{
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack16<E>(lo32<E>(w[i]) * f, hi32<E>(w[i]) * f);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 // Activation of two neighbouring accumulator values, packed for the second GEMM.
 template <typename E, int ACT>
 __device__ __forceinline__ uint32_t act_pack(float z0, float z1)
@@ -243,7 +275,15 @@ __global__ __launch_bounds__(256, 1) void mlp_order1_kernel(
 // MFMA operand order, by a persistent workgroup that then walks over tiles of 256 tokens of that
 // block: wave w owns tokens 64 w .. 64 w + 63 of the tile and the whole hidden vector, so nothing is
 // summed across waves and every weight byte leaves L2 once per workgroup instead of once per 64 tokens.
-// The next tile's x operands are requested before the current tile is computed.
+// The next tile's x rows are requested before the current tile is computed.
+// Token rows move in the cheap lane order: a wave-wide 16-byte access costs the vector memory pipe about 20 cycles
+// when the four lanes of a quad stay inside one 128-byte line and about 69 when they touch four lines, which is
+// what the MFMA operand order (lane = token + 16 group) does.  So lane 4 t + p loads and stores piece p of token t
+// (a quad = 64 contiguous bytes of one row), and a per-wave LDS area of 16 token rows turns that order into the
+// operand order and back (wave-private: no barrier).  The rows of W2 are dealt to the row tiles so that tiles 2 m
+// and 2 m + 1 give a lane 8 neighbouring features: tile 2 m + h, row 4 g + r is feature 32 m + 8 g + 4 h + r.
+// With GELU the staged W1 and b1 carry a factor 1/4 and W2 a factor 4 (see gelu_pack_quarter).
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 template <typename E, int KS, int ACT>
 __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
     const E *__restrict__ x, E *__restrict__ y, int64_t tokens, int d, int d_hidden, int nb,
@@ -260,6 +300,9 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
     const E *W1b = W1 + (size_t)blk * dh * DIN;   // [dh][DIN]
     const E *W2b = W2 + (size_t)blk * DIN * dh;   // [DIN][dh]
     uint16_t *bias_lds = reinterpret_cast<uint16_t *>(lds_ops + (size_t)nch * OPS * 64);
+    constexpr int WST = 16 * (4 * KS + 1);   // a wave's exchange area: 16 token rows of 4 KS pieces, one piece of padding
+    u32x4 *wst = reinterpret_cast<u32x4 *>(lds_ops + (size_t)nch * OPS * 64 + (dh * 2 + 15) / 16 + wave * WST);
+    const int qt = lane >> 2, qp = lane & 3;   // quad order: token qt of a column tile, piece 4 i + qp of its row
 
     // stage the block's weights: piece (chunk j, op o, lane) is exactly the 16-byte operand that lane
     // will feed to the MFMA (same row / slot assignment as mlp_order1_kernel)
@@ -272,13 +315,17 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
             const int unit = 8 * (r16 >> 2) + 4 * mt + (r16 & 3);
             src = W1b + (size_t)(32 * j + unit) * DIN + 32 * ks + 8 * g;
         } else {
-            src = W2b + (size_t)(16 * (o - 2 * KS) + r16) * dh + 32 * j + 8 * g;
+            const int mt = o - 2 * KS;
+            src = W2b + (size_t)(32 * (mt >> 1) + 8 * (r16 >> 2) + 4 * (mt & 1) + (r16 & 3)) * dh + 32 * j + 8 * g;
         }
-        lds_ops[idx] = *reinterpret_cast<const uint4 *>(src);
+        uint4 piece = *reinterpret_cast<const uint4 *>(src);
+        if (ACT == 2) piece = scale8<E>(piece, o < 2 * KS ? 0.25f : 4.0f);
+        lds_ops[idx] = piece;
     }
     for (int h = tid; h < dh; h += 256) {
         uint16_t v = 0;
         if (b1) v = reinterpret_cast<const uint16_t *>(b1)[b1_interleaved ? (size_t)h * nb + blk : (size_t)blk * dh + h];
+        if (ACT == 2) v = (uint16_t)pack16<E>(lo32<E>((uint32_t)v) * 0.25f, 0.0f);
         bias_lds[h] = v;
     }
     // output bias of the rows this lane's accumulators carry: features 16 mt + 4 kg + r
@@ -286,28 +333,33 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bias2[mt][r] = b2 ? (float)b2[(size_t)blk * DIN + 16 * mt + 4 * kg + r] : 0.0f;
+        for (int r = 0; r < 4; ++r) bias2[mt][r] = b2 ? (float)b2[(size_t)blk * DIN + 32 * (mt >> 1) + 8 * kg + 4 * (mt & 1) + r] : 0.0f;
     __syncthreads();
 
     const int64_t ntiles = (tokens + 255) / 256;
-    Pack8 xnext[4][KS];
+    u32x4 xnext[4][KS];
     auto request = [&](int64_t tile) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            int64_t t = tile * 256 + 64 * wave + 16 * nt + l16;
+            int64_t t = tile * 256 + 64 * wave + 16 * nt + qt;
             if (t >= tokens) t = tokens - 1;   // clamp: the column is computed but never stored
-            const E *row = x + t * d + blk * DIN + 8 * kg;
+            const E *row = x + t * d + blk * DIN + 8 * qp;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) xnext[nt][ks].q = *reinterpret_cast<const uint4 *>(row + 32 * ks);
+            for (int ks = 0; ks < KS; ++ks) xnext[nt][ks] = *reinterpret_cast<const u32x4 *>(row + 32 * ks);
         }
     };
     if (slot < ntiles) request(slot);
     for (int64_t tile = slot; tile < ntiles; tile += wgs_per_block) {
-        Pack8 xop[4][KS];
+        u32x4 xop[4][KS];   // quad order -> operand order: lane (token l16, group kg) takes pieces 4 ks + kg of its row
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < 4; ++nt) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) xop[nt][ks] = xnext[nt][ks];
+            for (int ks = 0; ks < KS; ++ks) wst[qt * (4 * KS + 1) + 4 * ks + qp] = xnext[nt][ks];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xop[nt][ks] = wst[l16 * (4 * KS + 1) + 4 * ks + kg];
+            __builtin_amdgcn_wave_barrier();
+        }
         const int64_t after = tile + wgs_per_block;
         request(after < ntiles ? after : tile);
 
@@ -345,7 +397,7 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
                 for (int nt = 0; nt < 4; ++nt) {
                     f32x4 a = bias[mt];
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) a = mfma<E>(w1[mt][ks].v, xop[nt][ks].v, a);
+                    for (int ks = 0; ks < KS; ++ks) a = mfma<E>(w1[mt][ks].v, __builtin_bit_cast(op8, xop[nt][ks]), a);
                     hacc[mt][nt] = a;
                 }
             Pack8 hop[4];
@@ -353,29 +405,40 @@ __global__ __launch_bounds__(256, 2) void mlp_order1_resident_kernel(
             for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt) {
-                    hop[nt].d[2 * mt] = act_pack<E, ACT>(hacc[mt][nt][0], hacc[mt][nt][1]);
-                    hop[nt].d[2 * mt + 1] = act_pack<E, ACT>(hacc[mt][nt][2], hacc[mt][nt][3]);
+                    if constexpr (ACT == 2) {
+                        hop[nt].d[2 * mt] = gelu_pack_quarter<E>(hacc[mt][nt][0], hacc[mt][nt][1]);
+                        hop[nt].d[2 * mt + 1] = gelu_pack_quarter<E>(hacc[mt][nt][2], hacc[mt][nt][3]);
+                    } else {
+                        hop[nt].d[2 * mt] = act_pack<E, ACT>(hacc[mt][nt][0], hacc[mt][nt][1]);
+                        hop[nt].d[2 * mt + 1] = act_pack<E, ACT>(hacc[mt][nt][2], hacc[mt][nt][3]);
+                    }
                 }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma<E>(w2[mt].v, hop[nt].v, acc[mt][nt]);
         }
-        // accumulator rows 4 kg .. 4 kg + 3 of tile mt are 4 consecutive features of token 16 nt + l16:
-        // one 8-byte store per tile and lane (the four lane groups of a token fill a 32-byte run)
+        // the accumulators of tiles 2 m, 2 m + 1 are features 32 m + 8 kg .. + 7 of token 16 nt + l16: piece 4 m + kg of
+        // its row; through the exchange area into quad order, then 16-byte stores
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            const int64_t t = tile * 256 + 64 * wave + 16 * nt + l16;
-            if (t < tokens) {
-                E *dst = y + t * d + blk * DIN + 4 * kg;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    uint2 o;
-                    o.x = pack16<E>(acc[mt][nt][0] + bias2[mt][0], acc[mt][nt][1] + bias2[mt][1]);
-                    o.y = pack16<E>(acc[mt][nt][2] + bias2[mt][2], acc[mt][nt][3] + bias2[mt][3]);
-                    *reinterpret_cast<uint2 *>(dst + 16 * mt) = o;
-                }
+            for (int m = 0; m < KS; ++m) {
+                wst[l16 * (4 * KS + 1) + 4 * m + kg] =
+                    u32x4{pack16<E>(acc[2 * m][nt][0] + bias2[2 * m][0], acc[2 * m][nt][1] + bias2[2 * m][1]),
+                          pack16<E>(acc[2 * m][nt][2] + bias2[2 * m][2], acc[2 * m][nt][3] + bias2[2 * m][3]),
+                          pack16<E>(acc[2 * m + 1][nt][0] + bias2[2 * m + 1][0], acc[2 * m + 1][nt][1] + bias2[2 * m + 1][1]),
+                          pack16<E>(acc[2 * m + 1][nt][2] + bias2[2 * m + 1][2], acc[2 * m + 1][nt][3] + bias2[2 * m + 1][3])};
             }
+            __builtin_amdgcn_wave_barrier();
+            const int64_t t = tile * 256 + 64 * wave + 16 * nt + qt;
+            E *dst = y + t * d + blk * DIN + 8 * qp;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 o = wst[qt * (4 * KS + 1) + 4 * ks + qp];
+                if (t < tokens) *reinterpret_cast<u32x4 *>(dst + 32 * ks) = o;
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -822,8 +885,9 @@ int launch_typed(const void *x, void *y, int64_t tokens, int d, int d_hidden, in
     const int din = d / nb;
     // small blocks, many tokens: weights resident in LDS, persistent workgroups
     const int dh_blk = d_hidden / nb;
-    const size_t res_lds = (size_t)dh_blk * din * 4 + (size_t)dh_blk * 2;
-    if (din <= 64 && res_lds <= 72 * 1024 && tokens >= 2048) {
+    // the weights in operand order, the hidden bias, and the four waves' exchange areas (16 rows of din / 8 + 1 pieces)
+    const size_t res_lds = (size_t)dh_blk * din * 4 + (((size_t)dh_blk * 2 + 15) & ~(size_t)15) + (size_t)4 * 16 * (din / 8 + 1) * 16;
+    if (din <= 64 && res_lds <= 79 * 1024 && tokens >= 2048) {
         int dev = 0, ncu = 0;
         MONARCH_HIP_CHECK(hipGetDevice(&dev));
         MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
