@@ -29,11 +29,12 @@ namespace fac {
 
 constexpr int THREADS = 1024, WAVES = THREADS / 64;
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // (arrays of HIP's uint4 struct can end up in scratch memory)
 union Pack8 {
     op8 v;
     uint32_t d[4];
     uint16_t h[8];
-    uint4 q;
+    u32x4 q;
 };
 
 enum { IN_FIRST = 0, IN_SECOND = 1, IN_SECOND_GATHER = 2 };
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
             const int k = u / mts, mt = u - k * mts;
             const E *wrow = W + ((size_t)k * r_out + 16 * mt + l16) * RIN + 8 * kg;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) a[b][ks].q = *reinterpret_cast<const uint4 *>(wrow + 32 * ks);
+            for (int ks = 0; ks < KS; ++ks) a[b][ks].q = *reinterpret_cast<const u32x4 *>(wrow + 32 * ks);
         }
     };
     if (wave < units) request(wave);
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
             const int t = idx / pin, o = (idx - t * pin) * 8;
             int64_t tt = t0 + t;
             if (tt >= tokens) tt = tokens - 1;   // clamp: computed, never stored
-            v[u].q = *reinterpret_cast<const uint4 *>(in + tt * d_in + o);
+            v[u].q = *reinterpret_cast<const u32x4 *>(in + tt * d_in + o);
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
             const int t = idx / pin, o = (idx - t * pin) * 8;
             uint16_t *dst = tin + t * ld_in;
             if (MODE == IN_SECOND) {
-                *reinterpret_cast<uint4 *>(dst + o) = v[u].q;
+                *reinterpret_cast<u32x4 *>(dst + o) = v[u].q;
             } else if (MODE == IN_FIRST) {        // i = c nb + k  ->  k RIN + c
                 int c = o / nb, k = o - c * nb;
 #pragma unroll
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
                         Pack8 xop;
-                        xop.q = *reinterpret_cast<const uint4 *>(row + 16 * nt * ld_in + k * RIN + 32 * ks);
+                        xop.q = *reinterpret_cast<const u32x4 *>(row + 16 * nt * ld_in + k * RIN + 32 * ks);
                         acc = h16::mfma<E>(a[b][ks].v, xop.v, acc);
                     }
                     // rows r = 16 mt + 4 kg + i of block k, token 16 nt + l16  ->  output position r nb + k
@@ -155,9 +156,9 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
         for (int u = 0; u < 2; ++u) {
             const int idx = base + u * THREADS < nout ? base + u * THREADS : base;
             const int t = idx / pout, o = (idx - t * pout) * 8;
-            v[u].q = *reinterpret_cast<const uint4 *>(tout + t * ld_out + o);
-            bv[u].q = make_uint4(0u, 0u, 0u, 0u);
-            if (bias) bv[u].q = *reinterpret_cast<const uint4 *>(bias + o);
+            v[u].q = *reinterpret_cast<const u32x4 *>(tout + t * ld_out + o);
+            bv[u].q = u32x4{0u, 0u, 0u, 0u};
+            if (bias) bv[u].q = *reinterpret_cast<const u32x4 *>(bias + o);
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
                     v[u].h[e] = __builtin_bit_cast(uint16_t, (E)sum);
                 }
             }
-            *reinterpret_cast<uint4 *>(out + (t0 + t) * d_out + o) = v[u].q;
+            *reinterpret_cast<u32x4 *>(out + (t0 + t) * d_out + o) = v[u].q;
         }
     }
 }
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
         umt[b] = u - uk[b] * mts;
         const E *wrow = W + ((size_t)uk[b] * r_out + 16 * umt[b] + l16) * RIN + 8 * kg;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) a[b][ks].q = *reinterpret_cast<const uint4 *>(wrow + 32 * ks);
+        for (int ks = 0; ks < KS; ++ks) a[b][ks].q = *reinterpret_cast<const u32x4 *>(wrow + 32 * ks);
     }
 
     // this thread's pieces of a tile: input piece q covers elements o .. o + 7 of token t
@@ -227,8 +228,8 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
         const int idx = tid + q * THREADS < npout ? tid + q * THREADS : tid;
         ot[q] = idx / pout;
         oo[q] = (idx - ot[q] * pout) * 8;
-        bv[q].q = make_uint4(0u, 0u, 0u, 0u);
-        if (bias) bv[q].q = *reinterpret_cast<const uint4 *>(bias + oo[q]);
+        bv[q].q = u32x4{0u, 0u, 0u, 0u};
+        if (bias) bv[q].q = *reinterpret_cast<const u32x4 *>(bias + oo[q]);
     }
 
     Pack8 v[NPI];
@@ -238,7 +239,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
             if (q == 0 || tid + q * THREADS < npin) {
                 int64_t tt = (int64_t)tile * TOK + it[q];
                 if (tt >= tokens) tt = tokens - 1;   // clamp: computed, never stored
-                v[q].q = *reinterpret_cast<const uint4 *>(in + tt * d_in + io[q]);
+                v[q].q = *reinterpret_cast<const u32x4 *>(in + tt * d_in + io[q]);
             }
     };
 
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
                 uint16_t *dst = tin + it[q] * ld_in;
                 const int o = io[q];
                 if (MODE == IN_SECOND) {
-                    *reinterpret_cast<uint4 *>(dst + o) = v[q].q;
+                    *reinterpret_cast<u32x4 *>(dst + o) = v[q].q;
                 } else if (MODE == IN_FIRST) {        // i = c nb + k  ->  k RIN + c
                     int c = o / nb, k = o - c * nb;
 #pragma unroll
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     Pack8 xop;
-                    xop.q = *reinterpret_cast<const uint4 *>(row + uk[b] * RIN + 32 * ks);
+                    xop.q = *reinterpret_cast<const u32x4 *>(row + uk[b] * RIN + 32 * ks);
                     acc = h16::mfma<E>(a[b][ks].v, xop.v, acc);
                 }
                 // rows r = 16 mt + 4 kg + i of block k, token l16  ->  output position r nb + k (rounded here; the
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
             if (tid + q * THREADS < npout) {
                 const int64_t tt = (int64_t)tile * TOK + ot[q];
                 Pack8 r;
-                r.q = *reinterpret_cast<const uint4 *>(tout + ot[q] * ld_out + oo[q]);
+                r.q = *reinterpret_cast<const u32x4 *>(tout + ot[q] * ld_out + oo[q]);
                 if (bias) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
                         r.h[e] = __builtin_bit_cast(uint16_t, (E)sum);
                     }
                 }
-                if (tt < tokens) *reinterpret_cast<uint4 *>(out + tt * d_out + oo[q]) = r.q;
+                if (tt < tokens) *reinterpret_cast<u32x4 *>(out + tt * d_out + oo[q]) = r.q;
             }
         // (the next tile's rows go to tin, which nobody reads any more; tout is rewritten only after the next barrier)
     }

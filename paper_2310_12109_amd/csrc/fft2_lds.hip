@@ -80,8 +80,7 @@ struct StageOps {
     u32x4 br[(F + 31) / 32], bi[(F + 31) / 32];
 };
 
-// First half of stage_tile: reads the operands of column tile `col` from the tile.  A caller that runs several
-// calls in a row on disjoint columns may read the next call's operands before it finishes the current one.
+// First half of stage_tile: reads the operands of column tile `col` from the tile.
 // SWZ: the tile keeps element (row, col) at column col ^ 16 when bits 3 and 4 of row differ (swz_bit), so that the
 // row groups kg and kg + 1 of a strided access (rows 8 kg + e, a multiple of 32 words apart) fall on different
 // halves of the 32 banks; a row's 16-byte pieces move together, so row-wise accesses are unchanged.
@@ -167,7 +166,8 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
             }
         }
     };
-    if (0 < want) table_of(0);
+    constexpr bool AHEAD = F <= 64;   // (f = 128 runs the row tiles as a loop at 128 registers: no room to read ahead)
+    if (AHEAD && 0 < want) table_of(0);
     auto row_tile = [&](int jt) {
         if (jt < want) {
             f32x4 dr = {0, 0, 0, 0}, di = {0, 0, 0, 0};
@@ -175,6 +175,10 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks < live_ks) {
                     const int tk = HALF ? 0 : ks;
+                    if constexpr (!AHEAD) {   // one k-step's operands at a time
+                        ar[tk] = tab[(jt * TKS + tk) * 128 + lane];
+                        ai[tk] = tab[(jt * TKS + tk) * 128 + 64 + lane];
+                    }
                     const bool flip = HALF && ks == 1 && (jt & 1);   // this k-step's operands are minus the table's
                     dr = mfma(ar[tk], flip ? nbr1 : ops.br[ks], dr);
                     di = mfma(ai[tk], flip ? nbr1 : ops.br[ks], di);
@@ -182,7 +186,7 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
                     di = mfma(ar[tk], flip ? nb[ks] : ops.bi[ks], di);
                 }
             }
-            if (jt + 1 < want) table_of(jt + 1);
+            if (AHEAD && jt + 1 < want) table_of(jt + 1);
             uint32_t o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -721,19 +725,20 @@ __global__ __launch_bounds__(F1 >= 128 || F2 >= 128 ? 512 : 256) void fft2_lds_k
     }
 }
 
-// Runs the tasks wave, wave + WAVES, ... < TOTAL of one stage: the operands of the next task (a different column
-// tile, so untouched by the current one's results) are read before the current task's products start.
+// Runs the tasks wave, wave + WAVES, ... < TOTAL of one stage.  (Reading the next task's operands before the current
+// task's products was tried: no gain, 16 registers.)
 template <int F, int TOTAL, int WAVES, class Load, class Finish>
 __device__ __forceinline__ void staged_tasks(int wave, Load &&load, Finish &&finish)
 {
     constexpr int NT = (TOTAL + WAVES - 1) / WAVES;
-    StageOps<F> ops[2];
-    if (wave < TOTAL) load(wave, ops[0]);
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
         const int t = wave + i * WAVES;
-        if (i + 1 < NT && t + WAVES < TOTAL) load(t + WAVES, ops[(i + 1) & 1]);
-        if (t < TOTAL) finish(t, ops[i & 1]);
+        if (t < TOTAL) {
+            StageOps<F> ops;
+            load(t, ops);
+            finish(t, ops);
+        }
     }
 }
 
