@@ -92,6 +92,8 @@ def test_ragged_shapes_fp32(mm, B, H, n, klen, factors, gates):
     (1, 5, 16384, 16000, (32, 32, 32), "normal"), # ... H odd: the last channel travels alone
     (1, 3, 8000, 5000, (16, 64, 32), "normal"),   # ... unequal chunk factors, nfft > 2n
     (1, 2, 30000, 30000, (64, 32, 32), "none"),
+    (3, 3, 8192, 8000, (32, 32, 16), "normal"),   # three factors, B > 1: batch entries paired at a stride of H = 3 rows, odd B
+    (2, 2, 12288, 12288, (64, 16, 32), "normal"), # ... first factor 64, nfft > 2n
     (1, 2, 3000, 17, (128, 64), "none"),          # short kernel, no gates
 ])
 def test_ragged_shapes_bf16_matrix_core_passes(mm, B, H, n, klen, factors, gates):
