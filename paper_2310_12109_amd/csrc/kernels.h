@@ -97,6 +97,10 @@ int launch_hyena_layer(const void *u, const void *W_in, const void *b_in, const 
 // the plain product and the gated mixer (g_in, g_out may be null); fp32 or bf16 tensors
 bool monarch_inplace_supported(int bs, monarch_dtype dt);
 int launch_matmul_inplace(const void *x, const void *R, const void *L, void *y, int64_t batch, int bs, monarch_dtype dt, hipStream_t s);
+// Gradients of the square product with blocks of 32 (dx = M^T dy, dR, dL added to cleared buffers); batch > 0.
+bool monarch_inplace_backward_supported(int bs, monarch_dtype dt);
+int launch_matmul_backward_inplace(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR, float *dL,
+                                   int64_t batch, int bs, monarch_dtype dt, hipStream_t s);
 int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                          const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
 // sequence mixer with two general square order-2 Monarch matrices (csrc/mixer.hip); g_in, g_out may be null

@@ -2,6 +2,7 @@
 // instruction (16x16x4), fp32 or bf16 tensors, fp32 arithmetic:
 //   monarch_matmul   y = P L P R P x                                    (Sec. 3.1)
 //   monarch_mixer    y = g_out o M2 (K o M1 (g_in o u))                  (Sec. 3.2 Eq. 2 in its gated form)
+//   monarch_matmul_backward (blocks of 32)   dx = M^T dy, dR, dL            (what training the matrices of Sec. 3.1 needs)
 // A workgroup holds a tile of rows in LDS (element hi b + lo of a row at hi SH + lo) and every block-diagonal
 // factor works IN PLACE: block k reads the b elements of a row that it contracts (one digit of the index, the other
 // digit being the block's number) and writes its b results to the same places.  With x at (c, k):
@@ -28,6 +29,8 @@ __device__ __forceinline__ f32x4 ld4(const bf16_t *p)
     return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
                  __uint_as_float(w.y & 0xffff0000u)};
 }
+__device__ __forceinline__ float ld1(const float *p) { return *p; }
+__device__ __forceinline__ float ld1(const bf16_t *p) { return __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t *>(p) << 16); }
 __device__ __forceinline__ void st4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
 __device__ __forceinline__ void st4(bf16_t *p, f32x4 v)
 {
@@ -47,7 +50,9 @@ struct Geo {
 };
 
 // One factor in place.  Block blk contracts the digit that has stride SK; its other digit puts it at at(blk).
-template <typename T, int BS, int SK, typename At>
+// TRANS: the transposed blocks (lane (row i, group g) takes W[blk][(b/4) g + j][i]: a column of the block, 4-byte
+// loads that run along i across the 16 lanes of a group).
+template <typename T, int BS, int SK, bool TRANS = false, typename At>
 __device__ __forceinline__ void stage(float *tile, const T *__restrict__ W, int wave, int lane, At at)
 {
     typedef Geo<BS> G;
@@ -62,9 +67,17 @@ __device__ __forceinline__ void stage(float *tile, const T *__restrict__ W, int 
         const T *src = W;
         asm volatile("" : "+s"(src) : "v"(anchor));
         const int blk = wave * G::NBW + item / G::RT, rt = item % G::RT;
-        const T *row = src + ((size_t)blk * BS + 16 * rt + l16) * BS + G::Q * kg;
+        if constexpr (TRANS) {
+            const T *col = src + ((size_t)blk * BS + G::Q * kg) * BS + 16 * rt + l16;
 #pragma unroll
-        for (int p = 0; p < WV; ++p) dst[p] = ld4(row + 4 * p);
+            for (int p = 0; p < WV; ++p)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[p][e] = ld1(col + (size_t)(4 * p + e) * BS);
+        } else {
+            const T *row = src + ((size_t)blk * BS + 16 * rt + l16) * BS + G::Q * kg;
+#pragma unroll
+            for (int p = 0; p < WV; ++p) dst[p] = ld4(row + 4 * p);
+        }
     };
     request(0, w[0]);
 #pragma unroll
@@ -180,6 +193,151 @@ __global__ __launch_bounds__(Geo<BS>::THREADS, BS == 32 ? 2 : 1) void mixer_kern
     }
 }
 
+
+// ---- gradients (blocks of 32) ----------------------------------------------------------------------------------
+// With S = sum_v <dy_v, M x_v>, mid = R-stage of x at (r, k) and dy loaded at (r, s):
+//   dmid(r, k) = sum_s L[r][s][k] dy(r, s)    (block r of L transposed contracts s, stride 1)
+//   dx(c, k)   = sum_r R[k][r][c] dmid(r, k)  (block k of R transposed contracts r, stride SH)
+//   dL[r][s][k] = sum_v dy_v(r, s) mid_v(r, k),   dR[k][r][c] = sum_v dmid_v(r, k) x_v(c, k).
+// Two tiles of 16 rows (forward values and gradients, 148 KB): a factor's gradient is, per block and 16 x 16 piece
+// of it, four MFMAs whose contraction index is the row of the tile; the sums of a wave's four blocks (64 registers)
+// stay in registers over all tiles of the workgroup and are added to the caller's cleared buffer once.  Two
+// launches, because x is overwritten by mid and dy by dmid: one gives dx and dL, the other dR.
+
+// sum[u][it][jt] += (rows 16 it .. of side A)^T (rows 16 jt .. of side B) of block wave NBW + u, over the tile's rows
+template <int BS, int SK, typename At>
+__device__ __forceinline__ void outer(const float *ta, const float *tb, int wave, int lane, At at,
+                                      f32x4 (&sum)[Geo<BS>::NBW][Geo<BS>::RT][Geo<BS>::RT])
+{
+    typedef Geo<BS> G;
+    const int l16 = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int u = 0; u < G::NBW; ++u) {
+        const int off = at(wave * G::NBW + u);
+#pragma unroll
+        for (int q = 0; q < G::TV / 4; ++q) {   // the MFMA's contraction index kg is row 4 q + kg of the tile
+            const float *ra = ta + (4 * q + kg) * G::ROWP + off, *rb = tb + (4 * q + kg) * G::ROWP + off;
+            float a[G::RT], b[G::RT];
+#pragma unroll
+            for (int it = 0; it < G::RT; ++it) {
+                a[it] = ra[(16 * it + l16) * SK];
+                b[it] = rb[(16 * it + l16) * SK];
+            }
+#pragma unroll
+            for (int it = 0; it < G::RT; ++it)
+#pragma unroll
+                for (int jt = 0; jt < G::RT; ++jt) sum[u][it][jt] = mfma(a[it], b[jt], sum[u][it][jt]);
+        }
+    }
+}
+
+template <int BS>
+__device__ __forceinline__ void flush(float *dW, int wave, int lane, const f32x4 (&sum)[Geo<BS>::NBW][Geo<BS>::RT][Geo<BS>::RT])
+{
+    typedef Geo<BS> G;
+    const int l16 = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int u = 0; u < G::NBW; ++u)
+#pragma unroll
+        for (int it = 0; it < G::RT; ++it)
+#pragma unroll
+            for (int jt = 0; jt < G::RT; ++jt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    atomicAdd(dW + ((size_t)(wave * G::NBW + u) * BS + 16 * it + 4 * kg + r) * BS + 16 * jt + l16, sum[u][it][jt][r]);
+}
+
+// x -> fw tile at (c, k); dy -> gr tile at (r, s), zero for the rows past the batch (their x is a copy of the last row)
+template <typename T, int BS>
+__device__ __forceinline__ void load_pair(float *fw, float *gr, const T *x, const T *dy, int64_t v0, int64_t batch, bool want_x)
+{
+    typedef Geo<BS> G;
+    for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
+        const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+        const bool live = v0 + v < batch;
+        const int64_t r = live ? v0 + v : batch - 1;
+        if (want_x) {
+            const f32x4 val = ld4(x + r * G::N + i);
+            float *d = fw + v * G::ROWP + (i / BS) * G::SH + i % BS;
+            d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+        }
+        f32x4 g = ld4(dy + r * G::N + i);
+        if (!live) g = f32x4{0, 0, 0, 0};
+        float *sp = gr + v * G::ROWP + (i % BS) * G::SH + i / BS;   // dy[s b + r] at (r, s): i / b = s, i % b = r .. r + 3
+        sp[0] = g[0]; sp[G::SH] = g[1]; sp[2 * G::SH] = g[2]; sp[3 * G::SH] = g[3];
+    }
+}
+
+template <typename T, int BS, bool DX, bool DL>
+__global__ __launch_bounds__(Geo<BS>::THREADS, 1) void backward_dx_dl_kernel(const T *__restrict__ x, const T *__restrict__ R,
+                                                                               const T *__restrict__ L, const T *__restrict__ dy,
+                                                                               T *__restrict__ dx, float *__restrict__ dL, int64_t batch)
+{
+    typedef Geo<BS> G;
+    extern __shared__ __attribute__((aligned(16))) float tile[];
+    float *fw = tile, *gr = tile + G::TV * G::ROWP;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    f32x4 sum[G::NBW][G::RT][G::RT];
+#pragma unroll
+    for (int u = 0; u < G::NBW; ++u)
+#pragma unroll
+        for (int it = 0; it < G::RT; ++it)
+#pragma unroll
+            for (int jt = 0; jt < G::RT; ++jt) sum[u][it][jt] = f32x4{0, 0, 0, 0};
+    const int64_t ntiles = (batch + G::TV - 1) / G::TV;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t v0 = t * G::TV;
+        load_pair<T, BS>(fw, gr, x, dy, v0, batch, DL);
+        __syncthreads();
+        if constexpr (DL) {
+            stage<T, BS, G::SH>(fw, R, wave, lane, [](int k) { return k; });   // x -> mid
+            __syncthreads();
+            outer<BS, 1>(gr, fw, wave, lane, [](int r) { return r * G::SH; }, sum);   // dL[r][s][k]: dy(r, s) x mid(r, k)
+            __syncthreads();
+        }
+        if constexpr (DX) {
+            stage<T, BS, 1, true>(gr, L, wave, lane, [](int r) { return r * G::SH; });   // dy -> dmid
+            __syncthreads();
+            stage<T, BS, G::SH, true>(gr, R, wave, lane, [](int k) { return k; });       // dmid -> dx at (c, k)
+            __syncthreads();
+            for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
+                const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+                const float *sp = gr + v * G::ROWP + (i / BS) * G::SH + i % BS;
+                if (v0 + v < batch) st4(dx + (v0 + v) * G::N + i, f32x4{sp[0], sp[1], sp[2], sp[3]});
+            }
+            __syncthreads();
+        }
+    }
+    if constexpr (DL) flush<BS>(dL, wave, lane, sum);
+}
+
+template <typename T, int BS>
+__global__ __launch_bounds__(Geo<BS>::THREADS, 1) void backward_dr_kernel(const T *__restrict__ x, const T *__restrict__ L,
+                                                                            const T *__restrict__ dy, float *__restrict__ dR, int64_t batch)
+{
+    typedef Geo<BS> G;
+    extern __shared__ __attribute__((aligned(16))) float tile[];
+    float *fw = tile, *gr = tile + G::TV * G::ROWP;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    f32x4 sum[G::NBW][G::RT][G::RT];
+#pragma unroll
+    for (int u = 0; u < G::NBW; ++u)
+#pragma unroll
+        for (int it = 0; it < G::RT; ++it)
+#pragma unroll
+            for (int jt = 0; jt < G::RT; ++jt) sum[u][it][jt] = f32x4{0, 0, 0, 0};
+    const int64_t ntiles = (batch + G::TV - 1) / G::TV;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        load_pair<T, BS>(fw, gr, x, dy, t * G::TV, batch, true);
+        __syncthreads();
+        stage<T, BS, 1, true>(gr, L, wave, lane, [](int r) { return r * G::SH; });   // dy -> dmid at (r, k)
+        __syncthreads();
+        outer<BS, G::SH>(gr, fw, wave, lane, [](int k) { return k; }, sum);          // dR[k][r][c]: dmid(r, k) x x(c, k)
+        __syncthreads();
+    }
+    flush<BS>(dR, wave, lane, sum);
+}
+
 template <int BS>
 static int grid_for(int64_t ntiles, int64_t *grid)
 {
@@ -229,6 +387,33 @@ static int launch_mixer_t(const void *u, const void *K, const void *g_in, const 
     return launch_mixer_g<T, BS, false, false>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
 }
 
+
+template <typename T, int BS>
+static int launch_backward(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR, float *dL, int64_t batch,
+                           hipStream_t s)
+{
+    typedef Geo<BS> G;
+    const size_t lds = 2 * G::LDS_BYTES;
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t ntiles = (batch + G::TV - 1) / G::TV;
+    const unsigned grid = (unsigned)(ntiles < ncu ? ntiles : ncu);   // one workgroup per compute unit
+#define MONARCH_INPL_BWD(KERN, ...)                                                                                        \
+    do {                                                                                                                   \
+        auto kern = KERN;                                                                                                  \
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));  \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(G::THREADS), lds, s, __VA_ARGS__);                                       \
+        MONARCH_HIP_CHECK(hipGetLastError());                                                                              \
+    } while (0)
+    if (dx && dL) MONARCH_INPL_BWD((backward_dx_dl_kernel<T, BS, true, true>), (const T *)x, (const T *)R, (const T *)L, (const T *)dy, (T *)dx, dL, batch);
+    else if (dx) MONARCH_INPL_BWD((backward_dx_dl_kernel<T, BS, true, false>), (const T *)x, (const T *)R, (const T *)L, (const T *)dy, (T *)dx, dL, batch);
+    else if (dL) MONARCH_INPL_BWD((backward_dx_dl_kernel<T, BS, false, true>), (const T *)x, (const T *)R, (const T *)L, (const T *)dy, (T *)dx, dL, batch);
+    if (dR) MONARCH_INPL_BWD((backward_dr_kernel<T, BS>), (const T *)x, (const T *)L, (const T *)dy, dR, batch);
+#undef MONARCH_INPL_BWD
+    return MONARCH_OK;
+}
+
 }  // namespace inpl
 
 bool monarch_inplace_supported(int bs, monarch_dtype dt) { return (bs == 32 || bs == 64) && (dt == MONARCH_F32 || dt == MONARCH_BF16); }
@@ -249,6 +434,17 @@ int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const v
                                  : inpl::launch_mixer_t<bf16_t, 32>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
     return dt == MONARCH_F32 ? inpl::launch_mixer_t<float, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s)
                              : inpl::launch_mixer_t<bf16_t, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
+}
+
+bool monarch_inplace_backward_supported(int bs, monarch_dtype dt) { return bs == 32 && (dt == MONARCH_F32 || dt == MONARCH_BF16); }
+
+// dR and dL must have been cleared; batch > 0.
+int launch_matmul_backward_inplace(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR, float *dL,
+                                   int64_t batch, int bs, monarch_dtype dt, hipStream_t s)
+{
+    (void)bs;
+    return dt == MONARCH_F32 ? inpl::launch_backward<float, 32>(x, R, L, dy, dx, dR, dL, batch, s)
+                             : inpl::launch_backward<bf16_t, 32>(x, R, L, dy, dx, dR, dL, batch, s);
 }
 
 }  // namespace monarch

@@ -75,6 +75,36 @@ def test_bf16_config1_shape_on_the_matrix_cores(mm, batch):
     assert rel_l2(host(dR), wdR) <= 10 * TOL_F32 and rel_l2(host(dL), wdL) <= 10 * TOL_F32
 
 
+@pytest.mark.parametrize("batch", [1, 16, 100, 9000])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_blocks_of_32_on_the_matrix_cores(mm, batch, bf16):
+    # N = 1024: both factors, their transposes and the factor gradients in place on two LDS tiles of 16 rows; ragged
+    # last tile, and (batch 9000) more tiles than workgroups, so the sums stay in registers over several tiles
+    announce("matmul backward b=32 batch", batch, "bf16" if bf16 else "fp32")
+    w = workloads.monarch_matmul_inputs(batch=batch, b=32, seed=batch + 7, bf16=bf16)
+    dy = _dy(batch, 1024, batch + 8, bf16=bf16)
+    dx, dR, dL = mm.monarch_matmul_backward(dev(w["x"], bf16), dev(w["R"], bf16), dev(w["L"], bf16), dev(dy, bf16))
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    assert rel_l2(host(dx), wdx) <= (TOL_BF16 if bf16 else TOL_F32)
+    assert rel_l2(host(dR), wdR) <= 10 * TOL_F32 and rel_l2(host(dL), wdL) <= 10 * TOL_F32
+
+
+def test_blocks_of_32_partial_outputs(mm):
+    announce("matmul backward b=32 partial outputs")
+    w = workloads.monarch_matmul_inputs(batch=50, b=32, seed=21)
+    dy = _dy(50, 1024, 22)
+    x, R, L, g = dev(w["x"]), dev(w["R"]), dev(w["L"]), dev(dy)
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dR=False, need_dL=False)
+    assert dR is None and dL is None and rel_l2(host(dx), wdx) <= TOL_F32
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dx=False, need_dR=False)
+    assert dx is None and dR is None and rel_l2(host(dL), wdL) <= TOL_F32
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dx=False, need_dL=False)
+    assert dx is None and dL is None and rel_l2(host(dR), wdR) <= TOL_F32
+    again = mm.monarch_matmul_backward(x, R, L, g)   # overwritten, not accumulated
+    assert rel_l2(host(again[1]), wdR) <= TOL_F32 and rel_l2(host(again[2]), wdL) <= TOL_F32 and rel_l2(host(again[0]), wdx) <= TOL_F32
+
+
 def test_bf16_inputs(mm):
     announce("matmul backward bf16")
     w = workloads.monarch_matmul_inputs(batch=130, b=16, seed=3, bf16=True)
