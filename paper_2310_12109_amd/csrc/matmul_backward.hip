@@ -437,14 +437,16 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
 {
     if (matmul_backward_b16_supported(nbR, r_out, r_in, nbL, l_out, l_in, dt))
         return launch_matmul_backward_b16(x, R, L, dy, dx, dR, dL, batch, dt, s);
-    if (nbR == 32 && r_out == 32 && r_in == 32 && nbL == 32 && l_out == 32 && l_in == 32 && monarch_inplace_backward_supported(32, dt)) {
-        // square blocks of 32: both factors and their gradients on the fp32 matrix instruction, in place on LDS tiles
+    const int bs = nbR;
+    if ((bs == 32 || bs == 64) && r_out == bs && r_in == bs && nbL == bs && l_out == bs && l_in == bs && monarch_inplace_backward_supported(bs, dt)) {
+        // square blocks of 32 or 64: both factors and their gradients on the fp32 matrix instruction, in place on LDS tiles
+        const size_t nw = (size_t)bs * bs * bs;
         if (dR || dL) {
-            hipLaunchKernelGGL(mmb::fill_zero_kernel, dim3(64), dim3(256), 0, s, dR, dR ? (size_t)32768 : 0, dL, dL ? (size_t)32768 : 0);
+            hipLaunchKernelGGL(mmb::fill_zero_kernel, dim3(256), dim3(256), 0, s, dR, dR ? nw : 0, dL, dL ? nw : 0);
             MONARCH_HIP_CHECK(hipGetLastError());
         }
         if (batch == 0) return MONARCH_OK;
-        return launch_matmul_backward_inplace(x, R, L, dy, dx, dR, dL, batch, 32, dt, s);
+        return launch_matmul_backward_inplace(x, R, L, dy, dx, dR, dL, batch, bs, dt, s);
     }
     const mmb::Dims d = {nbR, r_out, r_in, nbL, l_out, l_in};
     if (dt == MONARCH_F32) return mmb::launch_typed<float>(x, R, L, dy, dx, dR, dL, batch, d, s);

@@ -2,7 +2,7 @@
 // instruction (16x16x4), fp32 or bf16 tensors, fp32 arithmetic:
 //   monarch_matmul   y = P L P R P x                                    (Sec. 3.1)
 //   monarch_mixer    y = g_out o M2 (K o M1 (g_in o u))                  (Sec. 3.2 Eq. 2 in its gated form)
-//   monarch_matmul_backward (blocks of 32)   dx = M^T dy, dR, dL            (what training the matrices of Sec. 3.1 needs)
+//   monarch_matmul_backward                  dx = M^T dy, dR, dL            (what training the matrices of Sec. 3.1 needs)
 // A workgroup holds a tile of rows in LDS (element hi b + lo of a row at hi SH + lo) and every block-diagonal
 // factor works IN PLACE: block k reads the b elements of a row that it contracts (one digit of the index, the other
 // digit being the block's number) and writes its b results to the same places.  With x at (c, k):
@@ -338,6 +338,185 @@ __global__ __launch_bounds__(Geo<BS>::THREADS, 1) void backward_dr_kernel(const 
     flush<BS>(dR, wave, lane, sum);
 }
 
+// ---- gradients (blocks of 64) ----------------------------------------------------------------------------------
+// The factor gradients (b^3 = 262144 floats each) do not fit in a workgroup's registers, and two tiles of eight rows
+// do not fit in LDS.  Three launches:
+//   dx: one tile of eight rows, the transposed stages of L and R (as the forward product, reversed);
+//   dL: workgroup (group g, slice) sums the 16 blocks r = 16 g .. 16 g + 15, one per wave, over the tiles of its
+//       slice of the rows: x whole (tile of four rows), the R stage restricted to the output rows r of the group
+//       (one row tile per block k), dy only at (r, s) with r in the group (a compact tile);
+//   dR: the same with the 16 blocks k of a group: dy whole, the transposed L stage restricted to the outputs k of
+//       the group, x only at (c, k) with k in the group.
+// A factor's gradient is then one MFMA per block and 16 x 16 piece (contraction index = the tile's four rows).
+constexpr int TV64 = 4;                 // rows of a gradient tile at b = 64
+constexpr int CP64 = 16 * 68 + 1;       // floats per row of the compact tile holding (r, s), r in a group of 16: r' 68 + s
+constexpr int CX64 = 64 * 20 + 1;       // floats per row of the compact tile holding (c, k), k in a group of 16: c 20 + k'
+
+// One factor in place, restricted to row tile rt0 of every block's outputs (the other positions keep their inputs).
+template <typename T, int BS, int SK, bool TRANS, typename At>
+__device__ __forceinline__ void stage_one(float *tile, const T *__restrict__ W, int wave, int lane, At at, int rt0, int tv)
+{
+    typedef Geo<BS> G;
+    const int l16 = lane & 15, kg = lane >> 4;
+    float *mine = tile + (l16 & (tv - 1)) * G::ROWP;
+    constexpr int WV = G::Q / 4;
+    f32x4 w[2][WV];
+    float anchor = 0.0f;
+    auto request = [&](int u, f32x4 (&dst)[WV]) {
+        const T *src = W;
+        asm volatile("" : "+s"(src) : "v"(anchor));
+        const int blk = wave * G::NBW + u;
+        if constexpr (TRANS) {
+            const T *col = src + ((size_t)blk * BS + G::Q * kg) * BS + 16 * rt0 + l16;
+#pragma unroll
+            for (int p = 0; p < WV; ++p)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[p][e] = ld1(col + (size_t)(4 * p + e) * BS);
+        } else {
+            const T *row = src + ((size_t)blk * BS + 16 * rt0 + l16) * BS + G::Q * kg;
+#pragma unroll
+            for (int p = 0; p < WV; ++p) dst[p] = ld4(row + 4 * p);
+        }
+    };
+    request(0, w[0]);
+#pragma unroll
+    for (int u = 0; u < G::NBW; ++u) {
+        float *e = mine + at(wave * G::NBW + u);
+        float bv[G::Q];
+#pragma unroll
+        for (int j = 0; j < G::Q; ++j) bv[j] = e[(G::Q * kg + j) * SK];
+        if (u + 1 < G::NBW) request(u + 1, w[(u + 1) & 1]);
+        f32x4 a = {0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < G::Q; ++j) a = mfma(w[u & 1][j >> 2][j & 3], bv[j], a);
+        anchor = a[0];
+        if (l16 < tv) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) e[(16 * rt0 + 4 * kg + r) * SK] = a[r];
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024, 1) void backward64_dx_kernel(const T *__restrict__ R, const T *__restrict__ L, const T *__restrict__ dy,
+                                                                  T *__restrict__ dx, int64_t batch)
+{
+    typedef Geo<64> G;
+    constexpr int BS = 64;
+    extern __shared__ __attribute__((aligned(16))) float tile[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t ntiles = (batch + G::TV - 1) / G::TV;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t v0 = t * G::TV;
+        for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
+            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+            int64_t r = v0 + v;
+            if (r >= batch) r = batch - 1;   // (rows past the end: computed, never stored)
+            const f32x4 g = ld4(dy + r * G::N + i);
+            float *sp = tile + v * G::ROWP + (i % BS) * G::SH + i / BS;   // dy[s b + r] at (r, s)
+            sp[0] = g[0]; sp[G::SH] = g[1]; sp[2 * G::SH] = g[2]; sp[3 * G::SH] = g[3];
+        }
+        __syncthreads();
+        stage<T, BS, 1, true>(tile, L, wave, lane, [](int r) { return r * G::SH; });   // dy -> dmid at (r, k)
+        __syncthreads();
+        stage<T, BS, G::SH, true>(tile, R, wave, lane, [](int k) { return k; });       // dmid -> dx at (c, k)
+        __syncthreads();
+        for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
+            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+            const float *sp = tile + v * G::ROWP + (i / BS) * G::SH + i % BS;
+            if (v0 + v < batch) st4(dx + (v0 + v) * G::N + i, f32x4{sp[0], sp[1], sp[2], sp[3]});
+        }
+        __syncthreads();
+    }
+}
+
+// WHICH = 0: dL (group of blocks r), 1: dR (group of blocks k).  blockIdx.x = 4 slice + group.
+template <typename T, int WHICH>
+__global__ __launch_bounds__(1024, 1) void backward64_factor_kernel(const T *__restrict__ x, const T *__restrict__ W,
+                                                                      const T *__restrict__ dy, float *__restrict__ dW, int64_t batch)
+{
+    typedef Geo<64> G;
+    constexpr int BS = 64, TV = TV64, CP = WHICH == 0 ? CP64 : CX64;
+    extern __shared__ __attribute__((aligned(16))) float tile[];
+    float *full = tile, *part = tile + TV * G::ROWP;   // dL: full = x -> mid, part = dy(r in group, s); dR: full = dy -> dmid, part = x(c, k in group)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int group = blockIdx.x & 3, slice = blockIdx.x >> 2, nslices = gridDim.x >> 2;
+    f32x4 sum[4][4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) sum[it][jt] = f32x4{0, 0, 0, 0};
+    const int64_t ntiles = (batch + TV - 1) / TV;
+    for (int64_t t = slice; t < ntiles; t += nslices) {
+        const int64_t v0 = t * TV;
+        // the whole rows of one operand, 16 elements (64 bytes) per 64 of the other
+        for (int piece = threadIdx.x; piece < TV * G::N / 4; piece += G::THREADS) {
+            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+            const bool live = v0 + v < batch;
+            const int64_t r = live ? v0 + v : batch - 1;
+            if (WHICH == 0) {
+                const f32x4 val = ld4(x + r * G::N + i);
+                float *d = full + v * G::ROWP + (i / BS) * G::SH + i % BS;
+                d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+            } else {
+                f32x4 g = ld4(dy + r * G::N + i);
+                if (!live) g = f32x4{0, 0, 0, 0};
+                float *sp = full + v * G::ROWP + (i % BS) * G::SH + i / BS;
+                sp[0] = g[0]; sp[G::SH] = g[1]; sp[2 * G::SH] = g[2]; sp[3 * G::SH] = g[3];
+            }
+        }
+        for (int piece = threadIdx.x; piece < TV * 64 * 4; piece += G::THREADS) {   // (one piece per thread)
+            const int v = piece >> 8, hi = (piece >> 2) & 63, q = piece & 3;   // element hi b + 16 group + 4 q ..
+            const bool live = v0 + v < batch;
+            const int64_t r = live ? v0 + v : batch - 1;
+            const int i = hi * BS + 16 * group + 4 * q;
+            if (WHICH == 0) {   // dy[s b + r], s = hi, r = 16 group + 4 q + e  ->  (r', s) at r' 68 + s
+                f32x4 g = ld4(dy + r * G::N + i);
+                if (!live) g = f32x4{0, 0, 0, 0};
+                float *sp = part + v * CP + (4 * q) * 68 + hi;
+                sp[0] = g[0]; sp[68] = g[1]; sp[2 * 68] = g[2]; sp[3 * 68] = g[3];
+            } else {            // x[c b + k], c = hi, k = 16 group + 4 q + e  ->  (c, k') at c 20 + k'
+                const f32x4 val = ld4(x + r * G::N + i);
+                float *d = part + v * CP + hi * 20 + 4 * q;
+                d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+            }
+        }
+        __syncthreads();
+        if (WHICH == 0) stage_one<T, BS, G::SH, false>(full, W, wave, lane, [](int k) { return k; }, group, TV);        // mid(r, k), r in the group
+        else stage_one<T, BS, 1, true>(full, W, wave, lane, [](int r) { return r * G::SH; }, group, TV);                // dmid(r, k), k in the group
+        __syncthreads();
+        // this wave's block: the MFMA's contraction index kg is row kg of the tiles
+        {
+            const int blk = 16 * group + wave;
+            float a[4], b[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                if (WHICH == 0) {   // dL[r][s][k]: dy(r, s) from the compact tile, mid(r, k) from the full one
+                    a[it] = part[kg * CP + wave * 68 + 16 * it + l16];
+                    b[it] = full[kg * G::ROWP + blk * G::SH + 16 * it + l16];
+                } else {            // dR[k][r][c]: dmid(r, k) from the full tile, x(c, k) from the compact one
+                    a[it] = full[kg * G::ROWP + (16 * it + l16) * G::SH + blk];
+                    b[it] = part[kg * CP + (16 * it + l16) * 20 + wave];
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 4; ++it)
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) sum[it][jt] = mfma(a[it], b[jt], sum[it][jt]);
+        }
+        __syncthreads();
+    }
+    const int blk = 16 * group + wave;
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                atomicAdd(dW + ((size_t)blk * BS + 16 * it + 4 * kg + r) * BS + 16 * jt + l16, sum[it][jt][r]);
+}
+
 template <int BS>
 static int grid_for(int64_t ntiles, int64_t *grid)
 {
@@ -414,6 +593,43 @@ static int launch_backward(const void *x, const void *R, const void *L, const vo
     return MONARCH_OK;
 }
 
+
+template <typename T>
+static int launch_backward64(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR, float *dL, int64_t batch,
+                             hipStream_t s)
+{
+    typedef Geo<64> G;
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (dx) {
+        const int64_t ntiles = (batch + G::TV - 1) / G::TV;
+        const unsigned grid = (unsigned)(ntiles < ncu ? ntiles : ncu);
+        auto kern = backward64_dx_kernel<T>;
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES));
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), G::LDS_BYTES, s, (const T *)R, (const T *)L, (const T *)dy, (T *)dx, batch);
+        MONARCH_HIP_CHECK(hipGetLastError());
+    }
+    const int64_t ntiles = (batch + TV64 - 1) / TV64;
+    int64_t slices = ncu / 4 > 0 ? ncu / 4 : 1;   // four groups of blocks per slice of the rows: one workgroup per compute unit
+    if (slices > ntiles) slices = ntiles;
+    if (dL) {
+        const size_t lds = sizeof(float) * TV64 * (G::ROWP + CP64);
+        auto kern = backward64_factor_kernel<T, 0>;
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kern, dim3((unsigned)(4 * slices)), dim3(1024), lds, s, (const T *)x, (const T *)R, (const T *)dy, dL, batch);
+        MONARCH_HIP_CHECK(hipGetLastError());
+    }
+    if (dR) {
+        const size_t lds = sizeof(float) * TV64 * (G::ROWP + CX64);
+        auto kern = backward64_factor_kernel<T, 1>;
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kern, dim3((unsigned)(4 * slices)), dim3(1024), lds, s, (const T *)x, (const T *)L, (const T *)dy, dR, batch);
+        MONARCH_HIP_CHECK(hipGetLastError());
+    }
+    return MONARCH_OK;
+}
+
 }  // namespace inpl
 
 bool monarch_inplace_supported(int bs, monarch_dtype dt) { return (bs == 32 || bs == 64) && (dt == MONARCH_F32 || dt == MONARCH_BF16); }
@@ -436,13 +652,15 @@ int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const v
                              : inpl::launch_mixer_t<bf16_t, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
 }
 
-bool monarch_inplace_backward_supported(int bs, monarch_dtype dt) { return bs == 32 && (dt == MONARCH_F32 || dt == MONARCH_BF16); }
+bool monarch_inplace_backward_supported(int bs, monarch_dtype dt) { return (bs == 32 || bs == 64) && (dt == MONARCH_F32 || dt == MONARCH_BF16); }
 
 // dR and dL must have been cleared; batch > 0.
 int launch_matmul_backward_inplace(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR, float *dL,
                                    int64_t batch, int bs, monarch_dtype dt, hipStream_t s)
 {
-    (void)bs;
+    if (bs == 64)
+        return dt == MONARCH_F32 ? inpl::launch_backward64<float>(x, R, L, dy, dx, dR, dL, batch, s)
+                                 : inpl::launch_backward64<bf16_t>(x, R, L, dy, dx, dR, dL, batch, s);
     return dt == MONARCH_F32 ? inpl::launch_backward<float, 32>(x, R, L, dy, dx, dR, dL, batch, s)
                              : inpl::launch_backward<bf16_t, 32>(x, R, L, dy, dx, dR, dL, batch, s);
 }

@@ -89,6 +89,34 @@ def test_blocks_of_32_on_the_matrix_cores(mm, batch, bf16):
     assert rel_l2(host(dR), wdR) <= 10 * TOL_F32 and rel_l2(host(dL), wdL) <= 10 * TOL_F32
 
 
+@pytest.mark.parametrize("batch", [1, 5, 100, 1500])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_blocks_of_64_on_the_matrix_cores(mm, batch, bf16):
+    # N = 4096: dx from one tile of eight rows; dL and dR from workgroups that each sum a group of 16 blocks over a slice
+    # of the rows (tiles of four rows; batch 1500: several tiles per workgroup, ragged last tile)
+    announce("matmul backward b=64 batch", batch, "bf16" if bf16 else "fp32")
+    w = workloads.monarch_matmul_inputs(batch=batch, b=64, seed=batch + 9, bf16=bf16)
+    dy = _dy(batch, 4096, batch + 10, bf16=bf16)
+    dx, dR, dL = mm.monarch_matmul_backward(dev(w["x"], bf16), dev(w["R"], bf16), dev(w["L"], bf16), dev(dy, bf16))
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    assert rel_l2(host(dx), wdx) <= (TOL_BF16 if bf16 else TOL_F32)
+    assert rel_l2(host(dR), wdR) <= 10 * TOL_F32 and rel_l2(host(dL), wdL) <= 10 * TOL_F32
+
+
+def test_blocks_of_64_partial_outputs(mm):
+    announce("matmul backward b=64 partial outputs")
+    w = workloads.monarch_matmul_inputs(batch=21, b=64, seed=31)
+    dy = _dy(21, 4096, 32)
+    x, R, L, g = dev(w["x"]), dev(w["R"]), dev(w["L"]), dev(dy)
+    wdx, wdR, wdL = oracle.matmul_backward(w["x"], w["R"], w["L"], dy)
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dR=False, need_dL=False)
+    assert dR is None and dL is None and rel_l2(host(dx), wdx) <= TOL_F32
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dx=False, need_dR=False)
+    assert dx is None and dR is None and rel_l2(host(dL), wdL) <= TOL_F32
+    dx, dR, dL = mm.monarch_matmul_backward(x, R, L, g, need_dx=False, need_dL=False)
+    assert dx is None and dL is None and rel_l2(host(dR), wdR) <= TOL_F32
+
+
 def test_blocks_of_32_partial_outputs(mm):
     announce("matmul backward b=32 partial outputs")
     w = workloads.monarch_matmul_inputs(batch=50, b=32, seed=21)
