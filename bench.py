@@ -340,6 +340,18 @@ def widening_cases():
                 return one
             add("matmul_%s_b%d_batch_%d" % (dn, b, rows), "order-2 Monarch matmul N=%d (%d blocks of %dx%d), %s, batch %d" % (N, b, b, b, dn, rows),
                 dn, "inpl::matmul_kernel<%d>" % b, (2 * rows * N + 2 * b ** 3) * es, rows * 4.0 * N * b, rows * N, mk_mm_b)
+
+            def mk_mm_bwd_b(torch, binding, workloads, rnd, b=b, N=N, rows=rows, dn=dn):
+                dt = tdt(torch, dn)
+                R, L = rnd(b, b, b, dt=dt, scale=b ** -0.5), rnd(b, b, b, dt=dt, scale=b ** -0.5)
+
+                def one():
+                    x, dy = rnd(rows, N, dt=dt), rnd(rows, N, dt=dt)
+                    return lambda: binding.monarch_matmul_backward(x, R, L, dy)
+                return one
+            add("matmul_backward_%s_b%d_batch_%d" % (dn, b, rows), "gradients of the order-2 Monarch matmul N=%d, %s, batch %d" % (N, dn, rows),
+                dn, "inpl::backward_dx_dl_kernel + backward_dr_kernel" if b == 32 else "inpl::backward64_dx_kernel + 2 x backward64_factor_kernel",
+                3 * rows * N * es + 2 * b ** 3 * (es + 4), rows * 10.0 * N * b, rows * N, mk_mm_bwd_b)
             add("mixer_%s_b%d_B%d" % (dn, b, B), "learned-Monarch sequence mixer N=%d, B=%d H=768, %s" % (N, B, dn), dn,
                 "inpl::mixer_kernel<%d>" % b, (4 * rows * N + 768 * N + 4 * b ** 3) * es, rows * 8.0 * N * b, rows * N, mk_mixer_b)
 

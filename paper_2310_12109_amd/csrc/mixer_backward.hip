@@ -110,6 +110,7 @@ static int product(const void *x, const void *R, const void *L, void *y, int64_t
                    hipStream_t s)
 {
     if (matmul_mfma_b16_supported(bs, bs, bs, bs, bs, bs, dt)) return launch_matmul_mfma_b16(x, R, L, y, rows, dt, s);
+    if (monarch_inplace_supported(bs, dt)) return launch_matmul_inplace(x, R, L, y, rows, bs, dt, s);   // blocks of 32, 64
     return launch_matmul_generic(x, R, L, nullptr, y, rows, bs, bs, bs, bs, bs, bs, 2, 0, dt, dt, dt, s);
 }
 

@@ -58,7 +58,16 @@ def test_other_block_sizes_fp32(mm, b):
     _check(mm, w, _dy(w, 3), TOL_F32)
 
 
-@pytest.mark.parametrize("b", [4, 16])
+@pytest.mark.parametrize("b,B,H", [(32, 5, 9), (64, 2, 5)])
+def test_blocks_of_32_and_64_on_the_matrix_cores(mm, b, B, H):
+    # N = 1024, 4096: the products and their gradients of the composition run in place on LDS tiles (fp32 MFMA);
+    # 45 and 10 rows: ragged tiles of 16, 8 and 4 rows
+    announce("mixer backward fp32 b, B, H", b, B, H)
+    w = workloads.mixer_inputs(B, H, b, seed=b + B)
+    _check(mm, w, _dy(w, 5), TOL_F32)
+
+
+@pytest.mark.parametrize("b", [4, 16, 32])
 def test_bf16(mm, b):
     # every intermediate row is rounded to bf16 between the kernels
     announce("mixer backward bf16 b", b)
