@@ -423,6 +423,25 @@ def widening_cases():
         add("m2_layer_%s_B%d" % (dn, B), "basic M2 layer n=d=256, B=%d, %s" % (B, dn), dn, "mixer_b16_kernel (2 launches)",
             (4 * B * 65536 + 2 * 65536) * es, B * 512 * 16.0 * 256 * 16, B * 65536, mk_layer)
 
+    for dn in ("f32", "bf16"):   # the layer at n = d = 1024: both mixers in place on the matrix cores
+        es = 4 if dn == "f32" else 2
+
+        def mk_layer32(torch, binding, workloads, rnd, dn=dn):
+            dt = tdt(torch, dn)
+            w = workloads.m2_layer_inputs(1, 32, 32, seed=0)
+            par = {k: torch.from_numpy(v).cuda().to(dt) for k, v in w.items() if k != "x"}
+            seq, dim = [par[k] for k in ("R1", "L1", "R2", "L2")], [par[k] for k in ("R3", "L3", "R4", "L4")]
+            ws = torch.empty(binding.monarch_m2_layer_workspace_bytes(64, 1024, 1024, binding.F32 if dn == "f32" else binding.BF16),
+                             dtype=torch.uint8, device="cuda")
+
+            def one():
+                x = rnd(64, 1024, 1024, dt=dt)
+                y = torch.empty_like(x)
+                return lambda: binding.monarch_m2_layer(x, seq, par["n_kernel"], dim, par["d_kernel"], par["gamma"], par["beta"], ws=ws, out=y)
+            return one
+        add("m2_layer_%s_b32_B64" % dn, "basic M2 layer n=d=1024, B=64, %s" % dn, dn, "inpl::mixer_kernel<32> (2 launches)",
+            (4 * 64 * 1048576 + 2 * 1048576) * es, 64 * 2048 * 16.0 * 1024 * 32, 64 * 1048576, mk_layer32)
+
     for b, batch in ((8, 16384), (16, 4096), (16, 65536)):
         N = b ** 3
 

@@ -101,8 +101,6 @@ int launch_matmul_inplace(const void *x, const void *R, const void *L, void *y, 
 bool monarch_inplace_backward_supported(int bs, monarch_dtype dt);
 int launch_matmul_backward_inplace(const void *x, const void *R, const void *L, const void *dy, void *dx, float *dR, float *dL,
                                    int64_t batch, int bs, monarch_dtype dt, hipStream_t s);
-int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                         const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s);
 // sequence mixer with two general square order-2 Monarch matrices (csrc/mixer.hip); g_in, g_out may be null
 struct MixOpt {
     int act = 0;             // between the kernel product and the second matrix: 0 none, 1 ReLU
@@ -112,6 +110,10 @@ struct MixOpt {
     const void *gamma = nullptr, *beta = nullptr;
     float eps = 0.0f;
 };
+bool mixer_inplace_takes(int bs, int H, monarch_dtype dt, const MixOpt &opt);
+int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
+                         const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, const MixOpt &opt,
+                         hipStream_t s);
 bool mixer_fits(int bs);
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                  const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt,

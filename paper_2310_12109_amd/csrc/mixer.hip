@@ -593,9 +593,8 @@ int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_o
         MONARCH_HIP_CHECK(hipGetLastError());
         return MONARCH_OK;
     }
-    // blocks of 32 or 64, the plain mixer: in place on the matrix cores
-    if (monarch_inplace_supported(bs, dt) && !opt.act && !opt.transposed && !opt.layer_norm)
-        return launch_mixer_inplace(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, dt, s);
+    // blocks of 32 or 64: in place on the matrix cores
+    if (mixer_inplace_takes(bs, H, dt, opt)) return launch_mixer_inplace(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, dt, opt, s);
     if (dt == MONARCH_F32) return mixg::launch_typed<float>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, opt, s);
     return mixg::launch_typed<bf16_t>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, bs, opt, s);
 }

@@ -140,26 +140,59 @@ __global__ __launch_bounds__(Geo<BS>::THREADS, BS == 32 ? 2 : 1) void matmul_ker
     }
 }
 
+// opt: the options of the basic M2 layer (Sec. 3.2): an activation after the kernel product, rows that run along the
+// middle index of a (B, N, H) tensor (transposed: a tile's TV rows are TV neighbouring h of one batch entry, moved in
+// pieces of four rows of one position), and the skip connection and layer norm over the row at the store.
 template <typename T, int BS, bool GIN, bool GOUT>
 __global__ __launch_bounds__(Geo<BS>::THREADS, BS == 32 ? 2 : 1) void mixer_kernel(
     const T *__restrict__ u, const T *__restrict__ K, const T *__restrict__ g_in, const T *__restrict__ g_out,
     const T *__restrict__ R1, const T *__restrict__ L1, const T *__restrict__ R2, const T *__restrict__ L2, T *__restrict__ y,
-    int64_t rows, int H)
+    int64_t rows, int H, const MixOpt opt)
 {
     typedef Geo<BS> G;
     extern __shared__ __attribute__((aligned(16))) float tile[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t ntiles = (rows + G::TV - 1) / G::TV;
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t v0 = t * G::TV;
-        for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
-            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
-            int64_t r = v0 + v;
-            if (r >= rows) r = rows - 1;
-            f32x4 val = ld4(u + r * G::N + i);
-            if (GIN) val *= ld4(g_in + r * G::N + i);
+    constexpr int PIECES = G::TV * G::N / 4;
+    // piece p of a tile: four elements and where they sit.  Plain rows: elements i .. i + 3 of row v; transposed: element i
+    // of rows v .. v + 3 (neighbouring h of one batch entry: contiguous in memory).
+    auto where = [&](int p, int64_t v0, int &v, int &i) -> int64_t {
+        if (opt.transposed) {
+            i = p / (G::TV / 4);
+            v = 4 * (p % (G::TV / 4));
+            // (rows is a multiple of TV here and a tile stays inside one batch entry: v0 = bt H + h0)
+            const int64_t bt = v0 / H, h0 = v0 - bt * H;
+            return (bt * G::N + i) * H + h0 + v;
+        }
+        v = p / (G::N / 4);
+        i = 4 * (p % (G::N / 4));
+        int64_t r = v0 + v;
+        if (r >= rows) r = rows - 1;   // (rows past the end: computed, never stored)
+        return r * G::N + i;
+    };
+    // the four tile words of a piece: natural position (hi, lo) = (i / b, i % b)
+    auto put = [&](int v, int i, f32x4 val) {
+        if (opt.transposed) {
+            float *d = tile + v * G::ROWP + (i / BS) * G::SH + i % BS;
+            d[0] = val[0]; d[G::ROWP] = val[1]; d[2 * G::ROWP] = val[2]; d[3 * G::ROWP] = val[3];
+        } else {
             float *d = tile + v * G::ROWP + (i / BS) * G::SH + i % BS;
             d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+        }
+    };
+    auto get = [&](int v, int i) -> f32x4 {
+        const float *d = tile + v * G::ROWP + (i / BS) * G::SH + i % BS;
+        if (opt.transposed) return f32x4{d[0], d[G::ROWP], d[2 * G::ROWP], d[3 * G::ROWP]};
+        return f32x4{d[0], d[1], d[2], d[3]};
+    };
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t v0 = t * G::TV;
+        for (int piece = threadIdx.x; piece < PIECES; piece += G::THREADS) {
+            int v, i;
+            const int64_t at = where(piece, v0, v, i);
+            f32x4 val = ld4(u + at);
+            if (GIN) val *= ld4(g_in + at);
+            put(v, i, val);
         }
         __syncthreads();
         stage<T, BS, G::SH>(tile, R1, wave, lane, [](int k) { return k; });
@@ -167,32 +200,66 @@ __global__ __launch_bounds__(Geo<BS>::THREADS, BS == 32 ? 2 : 1) void mixer_kern
         stage<T, BS, 1>(tile, L1, wave, lane, [](int r) { return r * G::SH; });
         __syncthreads();
         // kernel product: entry m = s b + r of the transform domain sits at (r, s)
-        for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
+        for (int piece = threadIdx.x; piece < PIECES; piece += G::THREADS) {
             const int v = piece / (G::N / 4), m = 4 * (piece % (G::N / 4));
             int64_t r = v0 + v;
             if (r >= rows) r = rows - 1;
             const f32x4 kv = ld4(K + (r % H) * G::N + m);
             float *sp = tile + v * G::ROWP + (m % BS) * G::SH + m / BS;
-            sp[0] *= kv[0]; sp[G::SH] *= kv[1]; sp[2 * G::SH] *= kv[2]; sp[3 * G::SH] *= kv[3];
+            f32x4 p = {sp[0] * kv[0], sp[G::SH] * kv[1], sp[2 * G::SH] * kv[2], sp[3 * G::SH] * kv[3]};
+            if (opt.act) p = f32x4{fmaxf(p[0], 0.0f), fmaxf(p[1], 0.0f), fmaxf(p[2], 0.0f), fmaxf(p[3], 0.0f)};
+            sp[0] = p[0]; sp[G::SH] = p[1]; sp[2 * G::SH] = p[2]; sp[3 * G::SH] = p[3];
         }
         __syncthreads();
         stage<T, BS, 1>(tile, R2, wave, lane, [](int k) { return k * G::SH; });
         __syncthreads();
         stage<T, BS, G::SH>(tile, L2, wave, lane, [](int r) { return r; });
         __syncthreads();
-        for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
-            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
-            if (v0 + v < rows) {
-                const float *sp = tile + v * G::ROWP + (i / BS) * G::SH + i % BS;
-                f32x4 val = {sp[0], sp[1], sp[2], sp[3]};
-                if (GOUT) val *= ld4(g_out + (v0 + v) * G::N + i);
-                st4(y + (v0 + v) * G::N + i, val);
+        if (opt.layer_norm) {
+            // result (gated) + u back into the tile, then a wave per row: mean, variance, scale and shift
+            for (int piece = threadIdx.x; piece < PIECES; piece += G::THREADS) {
+                int v, i;
+                const int64_t at = where(piece, v0, v, i);
+                f32x4 val = get(v, i);
+                if (GOUT) val *= ld4(g_out + at);
+                put(v, i, val + ld4(u + at));
+            }
+            __syncthreads();
+            for (int v = wave; v < G::TV; v += G::WAVES) {
+                const float *row = tile + v * G::ROWP;
+                float sum = 0.0f;
+                for (int j = lane; j < G::N; j += 64) sum += row[(j / BS) * G::SH + j % BS];
+                for (int m = 32; m; m >>= 1) sum += __shfl_xor(sum, m);
+                const float mean = sum / G::N;
+                float sq = 0.0f;
+                for (int j = lane; j < G::N; j += 64) {
+                    const float dlt = row[(j / BS) * G::SH + j % BS] - mean;
+                    sq += dlt * dlt;
+                }
+                for (int m = 32; m; m >>= 1) sq += __shfl_xor(sq, m);
+                const float rstd = rsqrtf(sq / G::N + opt.eps);
+                const int64_t r = v0 + v;
+                if (r < rows)
+                    for (int j = lane; j < G::N; j += 64) {
+                        const int64_t at = opt.transposed ? ((v0 / H) * G::N + j) * H + v0 % H + v : r * G::N + j;
+                        y[at] = from_f32<T>((row[(j / BS) * G::SH + j % BS] - mean) * rstd * to_f32(((const T *)opt.gamma)[j]) +
+                                            to_f32(((const T *)opt.beta)[j]));
+                    }
+            }
+        } else {
+            for (int piece = threadIdx.x; piece < PIECES; piece += G::THREADS) {
+                int v, i;
+                const int64_t at = where(piece, v0, v, i);
+                if (v0 + v < rows) {
+                    f32x4 val = get(v, i);
+                    if (GOUT) val *= ld4(g_out + at);
+                    st4(y + at, val);
+                }
             }
         }
         __syncthreads();
     }
 }
-
 
 // ---- gradients (blocks of 32) ----------------------------------------------------------------------------------
 // With S = sum_v <dy_v, M x_v>, mid = R-stage of x at (r, k) and dy loaded at (r, s):
@@ -543,7 +610,7 @@ static int launch_matmul(const void *x, const void *R, const void *L, void *y, i
 
 template <typename T, int BS, bool GIN, bool GOUT>
 static int launch_mixer_g(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                          const void *R2, const void *L2, void *y, int64_t rows, int H, hipStream_t s)
+                          const void *R2, const void *L2, void *y, int64_t rows, int H, const MixOpt &opt, hipStream_t s)
 {
     typedef Geo<BS> G;
     int64_t grid = 0;
@@ -551,19 +618,19 @@ static int launch_mixer_g(const void *u, const void *K, const void *g_in, const 
     auto kern = mixer_kernel<T, BS, GIN, GOUT>;
     MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G::THREADS), G::LDS_BYTES, s, (const T *)u, (const T *)K, (const T *)g_in,
-                       (const T *)g_out, (const T *)R1, (const T *)L1, (const T *)R2, (const T *)L2, (T *)y, rows, H);
+                       (const T *)g_out, (const T *)R1, (const T *)L1, (const T *)R2, (const T *)L2, (T *)y, rows, H, opt);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
 
 template <typename T, int BS>
 static int launch_mixer_t(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                          const void *R2, const void *L2, void *y, int64_t rows, int H, hipStream_t s)
+                          const void *R2, const void *L2, void *y, int64_t rows, int H, const MixOpt &opt, hipStream_t s)
 {
-    if (g_in && g_out) return launch_mixer_g<T, BS, true, true>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
-    if (g_in) return launch_mixer_g<T, BS, true, false>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
-    if (g_out) return launch_mixer_g<T, BS, false, true>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
-    return launch_mixer_g<T, BS, false, false>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
+    if (g_in && g_out) return launch_mixer_g<T, BS, true, true>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s);
+    if (g_in) return launch_mixer_g<T, BS, true, false>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s);
+    if (g_out) return launch_mixer_g<T, BS, false, true>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s);
+    return launch_mixer_g<T, BS, false, false>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s);
 }
 
 
@@ -641,15 +708,23 @@ int launch_matmul_inplace(const void *x, const void *R, const void *L, void *y, 
     return dt == MONARCH_F32 ? inpl::launch_matmul<float, 64>(x, R, L, y, batch, s) : inpl::launch_matmul<bf16_t, 64>(x, R, L, y, batch, s);
 }
 
+// transposed access needs whole tiles inside a batch entry
+bool mixer_inplace_takes(int bs, int H, monarch_dtype dt, const MixOpt &opt)
+{
+    if (!monarch_inplace_supported(bs, dt) || opt.act > 1) return false;
+    return !opt.transposed || H % (bs == 32 ? inpl::Geo<32>::TV : inpl::Geo<64>::TV) == 0;
+}
+
 int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
-                         const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, hipStream_t s)
+                         const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, const MixOpt &opt,
+                         hipStream_t s)
 {
     if (rows == 0) return MONARCH_OK;
     if (bs == 32)
-        return dt == MONARCH_F32 ? inpl::launch_mixer_t<float, 32>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s)
-                                 : inpl::launch_mixer_t<bf16_t, 32>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
-    return dt == MONARCH_F32 ? inpl::launch_mixer_t<float, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s)
-                             : inpl::launch_mixer_t<bf16_t, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, s);
+        return dt == MONARCH_F32 ? inpl::launch_mixer_t<float, 32>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s)
+                                 : inpl::launch_mixer_t<bf16_t, 32>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s);
+    return dt == MONARCH_F32 ? inpl::launch_mixer_t<float, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s)
+                             : inpl::launch_mixer_t<bf16_t, 64>(u, K, g_in, g_out, R1, L1, R2, L2, y, rows, H, opt, s);
 }
 
 bool monarch_inplace_backward_supported(int bs, monarch_dtype dt) { return (bs == 32 || bs == 64) && (dt == MONARCH_F32 || dt == MONARCH_BF16); }

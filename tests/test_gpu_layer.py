@@ -57,6 +57,23 @@ def test_fp32_runs_of_neighbouring_tiles(mm):
     assert err.max() <= 10 * TOL_F32      # no single row is off
 
 
+@pytest.mark.parametrize("bn,bd,B,act", [(32, 32, 2, 1), (32, 16, 2, 1), (16, 32, 3, 1), (64, 32, 1, 1), (32, 64, 1, 0), (32, 5, 2, 1)])
+def test_fp32_blocks_of_32_and_64(mm, bn, bd, B, act):
+    # n or d = 1024, 4096: that mixer runs in place on LDS tiles on the matrix cores with the layer's options (rows along the
+    # middle index of (B, n, d) in pieces of four rows; activation; skip connection and layer norm); d = 25: a tile of 16
+    # rows would straddle two sequences, so the sequence mixer takes the shape-generic kernel
+    announce("m2 layer fp32 bn, bd, B, act", bn, bd, B, act)
+    w = workloads.m2_layer_inputs(B, bn, bd, seed=bn * 100 + bd)
+    assert rel_l2(host(_run(mm, w, act=act)), _want(w, "relu" if act else "none")) <= TOL_F32
+
+
+def test_bf16_blocks_of_32(mm):
+    announce("m2 layer bf16 32, 32")
+    w = workloads.m2_layer_inputs(2, 32, 32, seed=13, bf16=True)
+    y = _run(mm, w, bf16=True)
+    assert y.dtype == torch.bfloat16 and rel_l2(host(y), _want(w)) <= TOL_BF16
+
+
 def test_no_activation(mm):
     announce("m2 layer fp32 no activation")
     w = workloads.m2_layer_inputs(2, 16, 16, seed=8)
