@@ -514,7 +514,7 @@ def all_cases():
         ConvCase("c4_conv_bf16", "c4_conv", True, "conv16k_bf16_kernel", "mfma"),
         ConvCase("c5a_conv_bf16", "c5a_conv", True, "fft_pass_rows_in_kernel x 2 + conv3_middle_kernel<64,64> + fft_pass_rows_out_kernel (4 launches)", "mfma"),
         MlpCase("c5b_mlp_order1", "c5b_mlp", 1, "mlp_order1_resident_kernel", "hbm"),
-        MlpCase("c5b_mlp_order2", "c5b_mlp", 2, "factor_kernel + mlp_order1_resident_kernel + factor_kernel", "hbm"),
+        MlpCase("c5b_mlp_order2", "c5b_mlp", 2, "factor_resident_kernel + mlp_order1_resident_kernel + factor_resident_kernel", "hbm"),
     ]
 
 

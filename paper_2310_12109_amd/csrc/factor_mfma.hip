@@ -185,6 +185,15 @@ __global__ __launch_bounds__(1024) void factor_kernel(const E *__restrict__ in, 
 // current tile is multiplied; each thread's pieces of the rows sit at the same places in every tile, so the
 // piece arithmetic and the bias are computed once.  NPI / NPO: 16-byte pieces per thread of a tile's input /
 // output rows (16 d / 8 pieces over 1024 threads; d <= 1024).
+// Position of element pos of a token row inside its LDS tile row: the 16-byte pieces of a row are permuted (piece index
+// XOR three higher bits of itself) so that the 2-byte scatters of a wave, whose targets lie a multiple of 128 bytes
+// apart, spread over the banks; SH: which bits (4 for the input tile, 3 for the output tile).
+template <int SH> __device__ __forceinline__ int swz8(int pos)
+{
+    const int piece = pos >> 3;
+    return ((piece ^ ((piece >> SH) & 7)) << 3) | (pos & 7);
+}
+
 template <typename E, int KS, int MODE, int UPW>
 __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restrict__ in, E *__restrict__ out,
                                                                  int64_t tokens, int nb, int r_out, const E *__restrict__ W,
@@ -245,7 +254,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
 
     int tile = blockIdx.x;
     if (tile < ntiles) request(tile);
-    const uint16_t *row = tin + l16 * ld_in + 8 * kg;
+    const uint16_t *row = tin + l16 * ld_in;
     for (; tile < ntiles; tile += gridDim.x) {
         // token rows -> LDS, element i of a row to its block-major position
 #pragma unroll
@@ -254,12 +263,12 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
                 uint16_t *dst = tin + it[q] * ld_in;
                 const int o = io[q];
                 if (MODE == IN_SECOND) {
-                    *reinterpret_cast<u32x4 *>(dst + o) = v[q].q;
+                    *reinterpret_cast<u32x4 *>(dst + swz8<4>(o)) = v[q].q;
                 } else if (MODE == IN_FIRST) {        // i = c nb + k  ->  k RIN + c
                     int c = o / nb, k = o - c * nb;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        dst[k * RIN + c] = v[q].h[e];
+                        dst[swz8<4>(k * RIN + c)] = v[q].h[e];
                         if (++k == nb) {
                             k = 0;
                             ++c;
@@ -268,7 +277,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
                 } else {                               // i = kk RIN + r (previous factor's block kk, row r)  ->  r nb + kk
                     const int kk = o / RIN, r = o - kk * RIN;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) dst[(r + e) * nb + kk] = v[q].h[e];
+                    for (int e = 0; e < 8; ++e) dst[swz8<4>((r + e) * nb + kk)] = v[q].h[e];
                 }
             }
         __syncthreads();
@@ -281,14 +290,14 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     Pack8 xop;
-                    xop.q = *reinterpret_cast<const u32x4 *>(row + uk[b] * RIN + 32 * ks);
+                    xop.q = *reinterpret_cast<const u32x4 *>(row + swz8<4>(uk[b] * RIN + 32 * ks + 8 * kg));
                     acc = h16::mfma<E>(a[b][ks].v, xop.v, acc);
                 }
                 // rows r = 16 mt + 4 kg + i of block k, token l16  ->  output position r nb + k (rounded here; the
                 // bias is added to that value at copy-out and the sum rounded again)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    tout[l16 * ld_out + (16 * umt[b] + 4 * kg + i) * nb + uk[b]] = __builtin_bit_cast(uint16_t, (E)acc[i]);
+                    tout[l16 * ld_out + swz8<3>((16 * umt[b] + 4 * kg + i) * nb + uk[b])] = __builtin_bit_cast(uint16_t, (E)acc[i]);
             }
         __syncthreads();
 
@@ -297,7 +306,7 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
             if (tid + q * THREADS < npout) {
                 const int64_t tt = (int64_t)tile * TOK + ot[q];
                 Pack8 r;
-                r.q = *reinterpret_cast<const u32x4 *>(tout + ot[q] * ld_out + oo[q]);
+                r.q = *reinterpret_cast<const u32x4 *>(tout + ot[q] * ld_out + swz8<3>(oo[q]));
                 if (bias) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -393,7 +402,8 @@ int launch_typed(const void *in, void *out, int64_t tokens, int nb, int r_out, i
         const int units = nb * (r_out / 16), upw = (units + fac::WAVES - 1) / fac::WAVES, ks = r_in / 32;
         const int d_in = nb * r_in, d_out = nb * r_out;
         const int built = upw <= 2 ? 2 : 4;   // units per wave of the instantiated kernels
-        if (upw <= 4 && built * ks <= 12 && d_in >= 512 && d_in <= 1024 && d_out >= 512 && d_out <= 1024)
+        // (rows of a multiple of 64 elements: the tiles permute 16-byte pieces within groups of eight)
+        if (upw <= 4 && built * ks <= 12 && d_in >= 512 && d_in <= 1024 && d_out >= 512 && d_out <= 1024 && d_in % 64 == 0 && d_out % 64 == 0)
             return launch_resident<E>(in, out, tokens, nb, r_out, r_in, W, bias, mode, built, s);
     }
     const int64_t grid = (tokens + tok - 1) / tok;
