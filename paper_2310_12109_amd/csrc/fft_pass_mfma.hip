@@ -765,9 +765,6 @@ static int rows_kernel_grid(int64_t nblocks, size_t lds, int *grid)
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     int per_cu = (int)((160 * 1024) / (lds + 1024));
     per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
-#ifdef MONARCH_TUNE_ENV
-    if (const char *e = getenv("MONARCH_ROWS_PER_CU")) per_cu = atoi(e);
-#endif
     const int64_t cap = (int64_t)ncu * per_cu;
     *grid = (int)(nblocks < cap ? nblocks : cap);
     return MONARCH_OK;
