@@ -758,14 +758,16 @@ __global__ __launch_bounds__(256, MAXT <= 4 ? 3 : 2) void fft_pass_rows_out_kern
     }
 }
 
-static int rows_kernel_grid(int64_t nblocks, size_t lds, int *grid)
+// over: workgroups per compute unit beyond those that fit at once (the last pass ran faster with twice as many, shorter
+// workgroups: 50 -> 45 us at the 64^3 convolution; the first pass did not)
+static int rows_kernel_grid(int64_t nblocks, size_t lds, int over, int *grid)
 {
     int dev = 0, ncu = 0;
     MONARCH_HIP_CHECK(hipGetDevice(&dev));
     MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     int per_cu = (int)((160 * 1024) / (lds + 1024));
     per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
-    const int64_t cap = (int64_t)ncu * per_cu;
+    const int64_t cap = (int64_t)ncu * per_cu * over;
     *grid = (int)(nblocks < cap ? nblocks : cap);
     return MONARCH_OK;
 }
@@ -787,7 +789,7 @@ static int launch_rows_in_ls(const FftPass &p, hipStream_t s)
     constexpr int JT = F / 16, KS = (F + 31) / 32;
     const size_t lds = (size_t)JT * KS * 2 * 64 * 16 + (size_t)(PAIR ? 2 : 1) * 16 * LS * RB_PITCH * 4;
     int grid = 0;
-    const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, &grid);
+    const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, 1, &grid);
     if (rc != MONARCH_OK) return rc;
     auto kern = fft_pass_rows_in_kernel<F, PAIR, LS>;
     if (lds > 48 * 1024)
@@ -823,7 +825,7 @@ static int launch_rows_out_np(const FftPass &p, hipStream_t s)
     const int wra = (int)((want + 15) / 16) * 16;
     const size_t lds = (size_t)JT * KS * 2 * 64 * 16 + (size_t)(PAIR ? 2 : 1) * wra * RB_PITCH * 4;
     int grid = 0;
-    const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, &grid);
+    const int rc = rows_kernel_grid(p.rows * (p.S / RB_COLS), lds, 2, &grid);
     if (rc != MONARCH_OK) return rc;
     const int npieces = (PAIR ? 2 : 1) * wra / 16;
     auto kern = npieces <= 2 ? fft_pass_rows_out_kernel<F, PAIR, 2> : npieces <= 4 ? fft_pass_rows_out_kernel<F, PAIR, 4> : fft_pass_rows_out_kernel<F, PAIR, 8>;
