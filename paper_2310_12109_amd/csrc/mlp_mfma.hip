@@ -38,27 +38,30 @@ union Pack8 {
 };
 
 // GELU(z) = z * Phi(z) for two pre-activations at once, returned as a packed bf16 pair (the operand of the second
-// GEMM).  Phi is evaluated on packed fp16 pairs, two values per instruction: t = clamp(z / 4, -c, c) with
-// 4 c = 3.25, Phi - 1/2 = t * q(t^2 - 0.4) with q of degree 4 fitted on |z| <= 3.25 under the constraint
-// c q(c^2 - 0.4) = 1/2, so that Phi is 0 / 1 beyond the clamp (the shift by 0.4 keeps the Horner steps well
-// conditioned in fp16).  The last product z * Phi takes z in fp32.  13 instructions per pair.
+// GEMM).  Phi is evaluated on packed fp16 pairs, two values per instruction: t = z / 4,
+// Phi - 1/2 = t * q(t^2 - 0.4) with q of degree 4 fitted on |z| <= 3.25 (c = 3.25 / 4) under the constraint
+// c q(c^2 - 0.4) = 1/2 (the shift by 0.4 keeps the Horner steps well conditioned in fp16); beyond the fitted range the
+// polynomial keeps growing, and the last fused multiply-add clamps Phi to [0, 1] with its output modifier (checked
+// over every fp16 t: no NaN, infinities end at 0 or 1).  The last product z * Phi takes z in fp32.  11 instructions
+// per pair.
 // Accuracy: |Phi_approx - Phi| <= 1e-3 for every z (fit 5.8e-4, fp16 evaluation the rest), an ABSOLUTE bound: the
 // result is within 1e-3 |z| of z Phi(z), which is below the bf16 rounding of results of ordinary size but is not a
-// relative bound in the far negative tail (GELU(-3) = -0.004 may be off by 0.003; below z = -3.25 the result is 0).
+// relative bound in the far negative tail (GELU(-3) = -0.004 may be off by 0.003; below z = -3.3 the result is 0).
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 __device__ __forceinline__ f16x2 splat16(float v) { return (f16x2){(_Float16)v, (_Float16)v}; }
 template <typename E> __device__ __forceinline__ uint32_t gelu_pack(float z0, float z1)
 {
     const f16x2 h = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(z0, z1));
-    f16x2 t = h * splat16(0.25f);
-    t = __builtin_elementwise_min(__builtin_elementwise_max(t, splat16(-0.8125f)), splat16(0.8125f));
+    const f16x2 t = h * splat16(0.25f);
     const f16x2 u = t * t - splat16(0.4f);
     f16x2 q = splat16(4.0132f);
     q = q * u + splat16(-2.2824f);
     q = q * u + splat16(1.2712f);
     q = q * u + splat16(-0.8877f);
     q = q * u + splat16(0.7821f);
-    const f16x2 w = t * q + splat16(0.5f);
+    f16x2 w;   // t q + 1/2, clamped to [0, 1] by the instruction's output modifier
+    const f16x2 half = splat16(0.5f);
+    asm("v_pk_fma_f16 %0, %1, %2, %3 clamp" : "=v"(w) : "v"(t), "v"(q), "v"(half));
     float g0, g1;   // Phi (fp16, low / high half) times z (fp32)
     asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(g0) : "v"(w), "v"(z0));
     asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(g1) : "v"(w), "v"(z1));
@@ -66,10 +69,7 @@ template <typename E> __device__ __forceinline__ uint32_t gelu_pack(float z0, fl
 }
 
 // The same for pre-activations that arrive divided by four (W1 and b1 scaled by 1/4, exact in binary floating point):
-// returns GELU / 4 (the caller scales W2 by 4).  The division by four of gelu_pack is gone, and instead of clamping
-// t the last step clamps Phi to [0, 1] with the instruction's own output modifier: beyond the fitted range the
-// polynomial keeps growing (checked over every fp16 t: Phi within 8.4e-4, no NaN, infinities end at 0 or 1).
-// 10 instructions per pair.
+// returns GELU / 4 (the caller scales W2 by 4), without gelu_pack's division by four: 10 instructions per pair.
 template <typename E> __device__ __forceinline__ uint32_t gelu_pack_quarter(float t0, float t1)
 {
     const f16x2 t = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(t0, t1));
