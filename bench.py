@@ -387,6 +387,25 @@ def widening_cases():
                 "blocky16::conv_b16_kernel", 4 * rows * 128 * es + 768 * 256 * 8 + 4 * 4096 * 8, rows / 16 * 704 * 2048.0, rows * 128,
                 mk_blocky, bound="mfma")
 
+    for dn in ("f32", "bf16"):   # the same convolution at N = 1024 (blocks of 32), n = 512: in place on LDS tiles
+        es = 4 if dn == "f32" else 2
+
+        def mk_blocky32(torch, binding, workloads, rnd, dn=dn):
+            dt = tdt(torch, dn)
+            w = workloads.blocky_inputs(1, 768, 512, 32, seed=0)
+            state = binding.monarch_blocky_prepare(*(torch.from_numpy(w[k]).cuda() for k in ("Lt", "Rt", "k")), mask=True)
+
+            def one():
+                u, gi, go = (rnd(64, 768, 512, dt=dt) for _ in range(3))
+                y = torch.empty_like(u)
+                return lambda: binding.monarch_blocky_conv(u, gi, go, state, 32, out=y)
+            return one
+        rows32 = 64 * 768
+        # executed MFMAs per tile of 16 rows: 512 (real input) + 2048 + 2048 + 512 (real part, half of the rows), 2048 FLOP each
+        add("blocky_conv_%s_b32_B64" % dn, "polynomial-parameterised Monarch causal conv N=1024 n=512, B=64 H=768, %s" % dn, dn,
+            "inpl::blocky_kernel<32>", 4 * rows32 * 512 * es + 768 * 1024 * 8 + 4 * 32768 * 8, rows32 / 16 * 5120 * 2048.0, rows32 * 512,
+            mk_blocky32, bound="mfma")
+
     for B, dn in ((8, "f32"), (256, "f32"), (256, "bf16")):
         es = 4 if dn == "f32" else 2
 

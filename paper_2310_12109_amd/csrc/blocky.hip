@@ -656,6 +656,11 @@ int launch_blocky_conv(const void *u, const void *g_in, const void *g_out, const
     if (rows == 0 || n == 0) return MONARCH_OK;
     const unsigned char *st = static_cast<const unsigned char *>(state);
     if (blocky16::supported(bs, n, dt)) return blocky16::launch(u, g_in, g_out, st, y, rows, H, n, dt, s);
+    if (blocky_inplace_takes(bs, n, dt)) {   // blocks of 32, 64: in place on LDS tiles on the matrix cores
+        const blocky::Layout l = blocky::layout(H, bs);
+        return launch_blocky_inplace(u, g_in, g_out, (const float2 *)(st + l.R1), (const float2 *)(st + l.L1), (const float2 *)(st + l.R2),
+                                     (const float2 *)(st + l.L2), (const float2 *)(st + l.Kf), y, rows, H, n, bs, dt, s);
+    }
     if (dt == MONARCH_F32) return blocky::launch_conv_typed<float>(u, g_in, g_out, st, y, rows, H, n, bs, s);
     return blocky::launch_conv_typed<bf16_t>(u, g_in, g_out, st, y, rows, H, n, bs, s);
 }

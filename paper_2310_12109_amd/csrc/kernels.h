@@ -114,6 +114,10 @@ bool mixer_inplace_takes(int bs, int H, monarch_dtype dt, const MixOpt &opt);
 int launch_mixer_inplace(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                          const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt, const MixOpt &opt,
                          hipStream_t s);
+// the polynomial-parameterised convolution with blocks of 32 or 64 on the same tiles (complex factors of a prepared state)
+bool blocky_inplace_takes(int bs, int n, monarch_dtype dt);
+int launch_blocky_inplace(const void *u, const void *g_in, const void *g_out, const float2 *R1, const float2 *L1, const float2 *R2,
+                          const float2 *L2, const float2 *Kf, void *y, int64_t rows, int H, int n, int bs, monarch_dtype dt, hipStream_t s);
 bool mixer_fits(int bs);
 int launch_mixer(const void *u, const void *K, const void *g_in, const void *g_out, const void *R1, const void *L1,
                  const void *R2, const void *L2, void *y, int64_t rows, int H, int bs, monarch_dtype dt,

@@ -584,6 +584,155 @@ __global__ __launch_bounds__(1024, 1) void backward64_factor_kernel(const T *__r
                 atomicAdd(dW + ((size_t)blk * BS + 16 * it + 4 * kg + r) * BS + 16 * jt + l16, sum[it][jt][r]);
 }
 
+// ---- the polynomial-parameterised Monarch convolution (blocks of 32 and 64) --------------------------------------
+// y = g_out o Re( M2 ( Kf o M1 (g_in o u, 0) ) )[0:n] with complex block-diagonal factors (appendix: the blocky
+// Monarch convolution): the mixer's four stages on two planes of the tile (real and imaginary parts), a complex
+// product being four real MFMA chains, two when the input is real (first stage) or only the real part is kept (last
+// stage, which also skips the row tiles of its outputs past n).  The factors are complex float32 [block][row][column]:
+// a lane reads the (b/4) complex columns of its row as (b/2) consecutive floats.
+template <int BS>
+struct CGeo {   // rows of a tile: two planes of TV rows fit in LDS
+    static constexpr int TV = BS == 32 ? 16 : 4;
+    static constexpr size_t LDS_BYTES = 2 * sizeof(float) * TV * Geo<BS>::ROWP;
+};
+
+// RTMAX: row tiles of every block's outputs that are computed (the others keep their inputs).
+template <int BS, int SK, bool REAL_IN, bool REAL_OUT, int RTMAX, typename At>
+__device__ __forceinline__ void cstage(float *tre, float *tim, const float2 *__restrict__ W, int wave, int lane, At at)
+{
+    typedef Geo<BS> G;
+    constexpr int TV = CGeo<BS>::TV;
+    const int l16 = lane & 15, kg = lane >> 4;
+    float *mre = tre + (l16 & (TV - 1)) * G::ROWP, *mim = tim + (l16 & (TV - 1)) * G::ROWP;
+    // a lane's Q complex columns of a row come in halves of 8 (4 pieces of 16 bytes), the next half requested while the
+    // current one is multiplied
+    constexpr int HALVES = G::Q / 8, WV = 4;
+    f32x4 w[2][WV];
+    float anchor = 0.0f;
+    constexpr int ITEMS = G::NBW * RTMAX * HALVES;
+    auto request = [&](int item, f32x4 (&dst)[WV]) {
+        const float2 *src = W;
+        asm volatile("" : "+s"(src) : "v"(anchor));
+        const int half = item % HALVES, rt = (item / HALVES) % RTMAX, blk = wave * G::NBW + item / (HALVES * RTMAX);
+        const float *row = reinterpret_cast<const float *>(src + ((size_t)blk * BS + 16 * rt + l16) * BS + G::Q * kg + 8 * half);
+#pragma unroll
+        for (int p = 0; p < WV; ++p) dst[p] = ld4(row + 4 * p);
+    };
+    request(0, w[0]);
+#pragma unroll
+    for (int u = 0; u < G::NBW; ++u) {
+        const int off = at(wave * G::NBW + u);
+        float *ere = mre + off, *eim = mim + off;
+        float bre[G::Q], bim[G::Q];
+#pragma unroll
+        for (int j = 0; j < G::Q; ++j) {
+            bre[j] = ere[(G::Q * kg + j) * SK];
+            if constexpr (!REAL_IN) bim[j] = eim[(G::Q * kg + j) * SK];
+        }
+        // (every input of the block is in registers by now: a row tile's results take their places at once)
+#pragma unroll
+        for (int rt = 0; rt < RTMAX; ++rt) {
+            f32x4 ar = {0, 0, 0, 0}, ai = {0, 0, 0, 0}, sub = {0, 0, 0, 0};   // real part = ar - sub
+#pragma unroll
+            for (int half = 0; half < HALVES; ++half) {
+                const int item = (u * RTMAX + rt) * HALVES + half;
+                if (item + 1 < ITEMS) request(item + 1, w[(item + 1) & 1]);
+                const f32x4 (&wc)[WV] = w[item & 1];
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = 8 * half + jj;
+                    const float wre = wc[jj >> 1][2 * (jj & 1)], wim = wc[jj >> 1][2 * (jj & 1) + 1];
+                    ar = mfma(wre, bre[j], ar);
+                    if constexpr (!REAL_IN) sub = mfma(wim, bim[j], sub);
+                    if constexpr (!REAL_OUT) {
+                        ai = mfma(wim, bre[j], ai);
+                        if constexpr (!REAL_IN) ai = mfma(wre, bim[j], ai);
+                    }
+                }
+            }
+            ar -= sub;
+            anchor = ar[0];
+            if (l16 < TV) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    ere[(16 * rt + 4 * kg + r) * SK] = ar[r];
+                    if constexpr (!REAL_OUT) eim[(16 * rt + 4 * kg + r) * SK] = ai[r];
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int BS, bool GIN, bool GOUT>
+__global__ __launch_bounds__(Geo<BS>::THREADS, 1) void blocky_kernel(
+    const T *__restrict__ u, const T *__restrict__ g_in, const T *__restrict__ g_out, const float2 *__restrict__ R1,
+    const float2 *__restrict__ L1, const float2 *__restrict__ R2, const float2 *__restrict__ L2, const float2 *__restrict__ Kf,
+    T *__restrict__ y, int64_t rows, int H, int n)
+{
+    typedef Geo<BS> G;
+    constexpr int TV = CGeo<BS>::TV;
+    extern __shared__ __attribute__((aligned(16))) float tile[];
+    float *tre = tile, *tim = tile + TV * G::ROWP;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t ntiles = (rows + TV - 1) / TV;
+    const int live_rt = ((n + BS - 1) / BS + 15) / 16;   // row tiles of the last stage that hold outputs below n
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t v0 = t * TV;
+        for (int piece = threadIdx.x; piece < TV * G::N / 4; piece += G::THREADS) {
+            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+            int64_t r = v0 + v;
+            if (r >= rows) r = rows - 1;   // (rows past the end: computed, never stored)
+            f32x4 val = {0, 0, 0, 0};      // (n is a multiple of 4: a piece is inside the row or past it)
+            if (i < n) {
+                val = ld4(u + r * n + i);
+                if (GIN) val *= ld4(g_in + r * n + i);
+            }
+            float *d = tre + v * G::ROWP + (i / BS) * G::SH + i % BS;
+            d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
+        }
+        __syncthreads();
+        cstage<BS, G::SH, true, false, G::RT>(tre, tim, R1, wave, lane, [](int k) { return k; });
+        __syncthreads();
+        cstage<BS, 1, false, false, G::RT>(tre, tim, L1, wave, lane, [](int r) { return r * G::SH; });
+        __syncthreads();
+        // kernel product: entry m = s b + r of the transform domain sits at (r, s)
+        for (int piece = threadIdx.x; piece < TV * G::N / 4; piece += G::THREADS) {
+            const int v = piece / (G::N / 4), m = 4 * (piece % (G::N / 4));
+            int64_t r = v0 + v;
+            if (r >= rows) r = rows - 1;
+            const float *kp = reinterpret_cast<const float *>(Kf + (r % H) * (int64_t)G::N + m);
+            const f32x4 k01 = ld4(kp), k23 = ld4(kp + 4);
+            const float kre[4] = {k01[0], k01[2], k23[0], k23[2]}, kim[4] = {k01[1], k01[3], k23[1], k23[3]};
+            const int at = v * G::ROWP + (m % BS) * G::SH + m / BS;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float xr = tre[at + e * G::SH], xi = tim[at + e * G::SH];
+                tre[at + e * G::SH] = xr * kre[e] - xi * kim[e];
+                tim[at + e * G::SH] = xr * kim[e] + xi * kre[e];
+            }
+        }
+        __syncthreads();
+        cstage<BS, 1, false, false, G::RT>(tre, tim, R2, wave, lane, [](int k) { return k * G::SH; });
+        __syncthreads();
+        // (only the row tiles of the outputs below n)
+        if (live_rt == 1) cstage<BS, G::SH, false, true, 1>(tre, tim, L2, wave, lane, [](int r) { return r; });
+        else if (live_rt == 2 || G::RT == 2) cstage<BS, G::SH, false, true, 2>(tre, tim, L2, wave, lane, [](int r) { return r; });
+        else if (live_rt == 3) cstage<BS, G::SH, false, true, (G::RT > 2 ? 3 : 2)>(tre, tim, L2, wave, lane, [](int r) { return r; });
+        else cstage<BS, G::SH, false, true, G::RT>(tre, tim, L2, wave, lane, [](int r) { return r; });
+        __syncthreads();
+        for (int piece = threadIdx.x; piece < TV * G::N / 4; piece += G::THREADS) {
+            const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
+            if (v0 + v < rows && i < n) {
+                const float *sp = tre + v * G::ROWP + (i / BS) * G::SH + i % BS;
+                f32x4 val = {sp[0], sp[1], sp[2], sp[3]};
+                if (GOUT) val *= ld4(g_out + (v0 + v) * n + i);
+                st4(y + (v0 + v) * n + i, val);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 template <int BS>
 static int grid_for(int64_t ntiles, int64_t *grid)
 {
@@ -697,6 +846,33 @@ static int launch_backward64(const void *x, const void *R, const void *L, const 
     return MONARCH_OK;
 }
 
+
+template <typename T, int BS>
+static int launch_blocky_t(const void *u, const void *g_in, const void *g_out, const float2 *R1, const float2 *L1, const float2 *R2,
+                           const float2 *L2, const float2 *Kf, void *y, int64_t rows, int H, int n, hipStream_t s)
+{
+    typedef Geo<BS> G;
+    int dev = 0, ncu = 0;
+    MONARCH_HIP_CHECK(hipGetDevice(&dev));
+    MONARCH_HIP_CHECK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t ntiles = (rows + CGeo<BS>::TV - 1) / CGeo<BS>::TV;
+    const unsigned grid = (unsigned)(ntiles < ncu ? ntiles : ncu);   // one workgroup per compute unit
+#define MONARCH_INPL_BLOCKY(GI, GO)                                                                                        \
+    do {                                                                                                                   \
+        auto kern = blocky_kernel<T, BS, GI, GO>;                                                                          \
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CGeo<BS>::LDS_BYTES)); \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(G::THREADS), CGeo<BS>::LDS_BYTES, s, (const T *)u, (const T *)g_in, (const T *)g_out, \
+                           R1, L1, R2, L2, Kf, (T *)y, rows, H, n);                                                        \
+    } while (0)
+    if (g_in && g_out) MONARCH_INPL_BLOCKY(true, true);
+    else if (g_in) MONARCH_INPL_BLOCKY(true, false);
+    else if (g_out) MONARCH_INPL_BLOCKY(false, true);
+    else MONARCH_INPL_BLOCKY(false, false);
+#undef MONARCH_INPL_BLOCKY
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
 }  // namespace inpl
 
 bool monarch_inplace_supported(int bs, monarch_dtype dt) { return (bs == 32 || bs == 64) && (dt == MONARCH_F32 || dt == MONARCH_BF16); }
@@ -738,6 +914,19 @@ int launch_matmul_backward_inplace(const void *x, const void *R, const void *L, 
                                  : inpl::launch_backward64<bf16_t>(x, R, L, dy, dx, dR, dL, batch, s);
     return dt == MONARCH_F32 ? inpl::launch_backward<float, 32>(x, R, L, dy, dx, dR, dL, batch, s)
                              : inpl::launch_backward<bf16_t, 32>(x, R, L, dy, dx, dR, dL, batch, s);
+}
+
+// rows of a multiple of 4 elements (16-byte pieces of fp32 rows, 8-byte pieces of bf16 rows)
+bool blocky_inplace_takes(int bs, int n, monarch_dtype dt) { return monarch_inplace_supported(bs, dt) && n >= 4 && n % 4 == 0; }
+
+int launch_blocky_inplace(const void *u, const void *g_in, const void *g_out, const float2 *R1, const float2 *L1, const float2 *R2,
+                          const float2 *L2, const float2 *Kf, void *y, int64_t rows, int H, int n, int bs, monarch_dtype dt, hipStream_t s)
+{
+    if (bs == 32)
+        return dt == MONARCH_F32 ? inpl::launch_blocky_t<float, 32>(u, g_in, g_out, R1, L1, R2, L2, Kf, y, rows, H, n, s)
+                                 : inpl::launch_blocky_t<bf16_t, 32>(u, g_in, g_out, R1, L1, R2, L2, Kf, y, rows, H, n, s);
+    return dt == MONARCH_F32 ? inpl::launch_blocky_t<float, 64>(u, g_in, g_out, R1, L1, R2, L2, Kf, y, rows, H, n, s)
+                             : inpl::launch_blocky_t<bf16_t, 64>(u, g_in, g_out, R1, L1, R2, L2, Kf, y, rows, H, n, s);
 }
 
 }  // namespace monarch

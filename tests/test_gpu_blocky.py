@@ -85,6 +85,18 @@ def test_causal_other_block_sizes_fp32(mm, b, n):
     assert rel_l2(host(_conv(mm, w, b)), _want(w)) <= TOL_F32
 
 
+@pytest.mark.parametrize("b,n,B,H,gates", [(32, 512, 9, 31, True), (32, 20, 2, 3, True), (32, 302, 2, 3, True), (64, 1000, 3, 7, True),
+                                           (64, 2048, 2, 3, False), (32, 512, 40, 13, True)])
+def test_blocks_of_32_and_64_in_place_on_the_matrix_cores(mm, b, n, B, H, gates):
+    # N = 1024, 4096: the four complex factors in place on two planes of an LDS tile (16 or 4 rows); ragged last tiles,
+    # rows of 20 elements (one row tile of the last stage), more tiles than workgroups (520 rows in tiles of 16 on at most
+    # 256 workgroups is one tile each: the 40 x 13 case has 33 tiles, the 3 x 7 case at b = 64 six tiles of four rows);
+    # n = 302 is not a multiple of 4: the shape-generic kernel
+    announce("blocky conv fp32 b, n, B, H", b, n, B, H, gates)
+    w = workloads.blocky_inputs(B, H, n, b, seed=b + n + B, noise=0.02 if b == 64 else 0.05, gates=gates)
+    assert rel_l2(host(_conv(mm, w, b)), _want(w)) <= TOL_F32
+
+
 def test_causal_n2048_fp32(mm):
     # b = 64, N = 4096: the largest block size; one row per tile
     announce("blocky conv fp32 b=64 n=2048")
