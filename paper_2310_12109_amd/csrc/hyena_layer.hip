@@ -106,9 +106,10 @@ __device__ __forceinline__ void store8(bf16_t *p, const float (&v)[8])
     *reinterpret_cast<uint4 *>(p) = *reinterpret_cast<const uint4 *>(h);
 }
 
-// out[r][t] = sum_tau ks[row kernel][tau] (in[r][t - tau] + bias[row kernel]), rows r = (i, b, c) of the (3, B, d, n)
-// tensor with kernel / bias row i d + c; 8 consecutive t per thread (16-byte accesses), the taps before them from the
-// preceding piece.
+// out[r][t] = sum_tau ks[row kernel][tau] (in[r'][t - tau] + bias[row kernel]), rows r = (i, b, c) of the (3, B, d, n)
+// tensor with kernel / bias row i d + c; the input is the projections' (B, 3, d, n) tensor, r' = (b, i, c): the three
+// projections of a batch entry are one GEMM.  8 consecutive t per thread (16-byte accesses), the taps before them
+// from the preceding piece.
 template <typename T>
 __global__ __launch_bounds__(256) void short_conv_kernel(const T *__restrict__ in, T *__restrict__ out, const T *__restrict__ ks,
                                                          const T *__restrict__ bias, int64_t rows, int Bd, int d, int n, int taps)
@@ -118,12 +119,14 @@ __global__ __launch_bounds__(256) void short_conv_kernel(const T *__restrict__ i
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = idx / pieces;
         const int p = (int)(idx - r * pieces);
-        const int kr = (int)(r / Bd) * d + (int)(r % d);   // r = (i B + b) d + c  ->  i d + c
+        const int i3 = (int)(r / Bd), rem = (int)(r - (int64_t)i3 * Bd), b = rem / d, c = rem - b * d;
+        const int kr = i3 * d + c;                          // r = (i B + b) d + c  ->  i d + c
+        const int64_t rs = ((int64_t)b * 3 + i3) * d + c;   // the same row of the (B, 3, d, n) input
         float w[8], x[16], o[8];
 #pragma unroll
         for (int tau = 0; tau < 8; ++tau) w[tau] = tau < taps ? to_f32(ks[(int64_t)kr * taps + tau]) : 0.0f;
         const float bv = bias ? to_f32(bias[kr]) : 0.0f;
-        const T *src = in + r * n + 8 * p;
+        const T *src = in + rs * n + 8 * p;
         float cur[8], prev[8];
         load8(src, cur);
         load8(p > 0 ? src - 8 : src, prev);
@@ -174,10 +177,10 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
     char *conv_ws = base + 2 * align_up(3 * plane * es, 256) + align_up(plane * es, 256);
     const size_t conv_ws_bytes = ws_bytes - (size_t)(conv_ws - base);
 
-    // 1. projections: proj[i][b] (d x n) = W_in[i d .. (i + 1) d) (d x d) times u[b]^T
-    for (int i = 0; i < 3; ++i) {
-        int rc = gemm(h, rocblas_operation_transpose, rocblas_operation_none, n, d, d, u, d, (int64_t)n * d,
-                      (const T *)W_in + (int64_t)i * d * d, d, 0, 0.0f, proj + i * plane, n, (int64_t)d * n, B, dt);
+    // 1. projections: proj[b] (3 d x n) = W_in (3 d x d) times u[b]^T, one batched GEMM
+    {
+        int rc = gemm(h, rocblas_operation_transpose, rocblas_operation_none, n, 3 * d, d, u, d, (int64_t)n * d, W_in, d, 0, 0.0f, proj,
+                      n, (int64_t)3 * d * n, B, dt);
         if (rc) return rc;
     }
     // 2. short depthwise convolutions (with the projection bias)
