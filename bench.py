@@ -501,7 +501,7 @@ def widening_cases():
                 return lambda: binding.monarch_hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, (64, 32), ws=ws, out=y)
             return one
         add("hyena_layer_%s_B8_n1024_d768" % dn, "gated-convolution layer (projections, short convs, gated long conv) B=8 n=1024 d=768, %s" % dn,
-            dn, "rocBLAS GEMM x 2 + short_conv_kernel + conv2048 kernel", (2 * B * n * d + 4 * d * d + d * n) * es,
+            dn, "rocBLAS GEMMs + short_conv_kernel + conv2048 kernel", (2 * B * n * d + 4 * d * d + d * n) * es,
             8.0 * B * n * d * d, B * n * d, mk_hy, bound="mfma", mfma_peak=MFMA_BF16_TFLOPS if dn == "bf16" else MFMA_F32_TFLOPS)
 
     for rows, factors in ((6144, (64, 32)), (1536, (128, 128))):

@@ -177,10 +177,12 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
     char *conv_ws = base + 2 * align_up(3 * plane * es, 256) + align_up(plane * es, 256);
     const size_t conv_ws_bytes = ws_bytes - (size_t)(conv_ws - base);
 
-    // 1. projections: proj[b] (3 d x n) = W_in (3 d x d) times u[b]^T, one batched GEMM
-    {
-        int rc = gemm(h, rocblas_operation_transpose, rocblas_operation_none, n, 3 * d, d, u, d, (int64_t)n * d, W_in, d, 0, 0.0f, proj,
-                      n, (int64_t)3 * d * n, B, dt);
+    // 1. projections: proj[b] (3 d x n) = W_in (3 d x d) times u[b]^T.  fp32: one batched GEMM; bf16: one per projection
+    //    (measured in one session at B = 8, n = 1024, d = 768: fp32 401 against 422 us per layer, bf16 109 against 103 us)
+    const int parts = dt == MONARCH_F32 ? 1 : 3;
+    for (int i = 0; i < parts; ++i) {
+        int rc = gemm(h, rocblas_operation_transpose, rocblas_operation_none, n, 3 * d / parts, d, u, d, (int64_t)n * d,
+                      (const T *)W_in + (int64_t)i * d * d, d, 0, 0.0f, proj + (int64_t)i * d * n, n, (int64_t)3 * d * n, B, dt);
         if (rc) return rc;
     }
     // 2. short depthwise convolutions (with the projection bias)
