@@ -504,6 +504,31 @@ def widening_cases():
             dn, "rocBLAS GEMMs + short_conv_kernel + conv2048 kernel", (2 * B * n * d + 4 * d * d + d * n) * es,
             8.0 * B * n * d * d, B * n * d, mk_hy, bound="mfma", mfma_peak=MFMA_BF16_TFLOPS if dn == "bf16" else MFMA_F32_TFLOPS)
 
+    # the same layer with heads of 16 features (the head dimension of the paper's causal models): 256 long convolutions
+    # per head and batch entry
+    for dn in ("bf16", "f32"):
+        es = 4 if dn == "f32" else 2
+        B, n, d, dh = 8, 1024, 768, 16
+
+        def mk_hyh(torch, binding, workloads, rnd, dn=dn, B=B, n=n, d=d, dh=dh):
+            dt = tdt(torch, dn)
+            W_in, W_out = rnd(3 * d, d, dt=dt, scale=d ** -0.5), rnd(d, d, dt=dt, scale=d ** -0.5)
+            b_in, b_out = rnd(3 * d, dt=dt, scale=.1), rnd(d, dt=dt, scale=.1)
+            k_short, k_long = rnd(3 * d, 3, dt=dt, scale=.5), rnd(d // dh, n, dt=dt, scale=.1)
+            ws = torch.empty(max(16, binding.monarch_hyena_heads_layer_workspace_bytes(B, n, d, n, (64, 32), dh, dt)), dtype=torch.uint8,
+                             device="cuda")
+
+            def one():
+                u = rnd(B, n, d, dt=dt)
+                y = torch.empty_like(u)
+                return lambda: binding.monarch_hyena_heads_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, (64, 32), dh, ws=ws, out=y)
+            return one
+        add("hyena_heads_layer_%s_B8_n1024_d768_dh16" % dn,
+            "gated-convolution layer with heads of 16 features B=8 n=1024 d=768, %s" % dn, dn,
+            "rocBLAS GEMMs + short_conv_kernel + heads_outer_kernel + conv2048 kernel + heads_sum_kernel",
+            (2 * B * n * d + 4 * d * d + (d // dh) * n) * es, 8.0 * B * n * d * d + dh * B * d * 2132000.0, B * n * d, mk_hyh, bound="mfma",
+            mfma_peak=MFMA_BF16_TFLOPS if dn == "bf16" else MFMA_F32_TFLOPS)
+
     for rows, factors in ((6144, (64, 32)), (1536, (128, 128))):
         N = factors[0] * factors[1]
         for inverse in (False, True):

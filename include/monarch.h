@@ -204,6 +204,25 @@ size_t monarch_hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nf
                                            monarch_dtype dt);
 
 /*
+ * The same layer with heads (appendix algorithm "M2 Hyena layer with heads"): the d features form d / head_dim heads
+ * of head_dim consecutive features, the long kernel has one row per head (k_long: (d / head_dim, klen)), and per batch
+ * entry, head and position, with i, j < head_dim numbering the features of the head,
+ *   XV[i][j] = conv(k_long[head], X2~[i] o V~[j])      the outer product of the head, convolved along the sequence
+ *   O[j]     = sum_i X1~[i] o XV[i][j]                  multiplied by X1~ position by position
+ * Projections, short convolutions and the output projection as in monarch_hyena_layer, which is this entry point at
+ * head_dim = 1.  The products X2~[i] o V~[j] and their convolutions go through the workspace as tensors of
+ * head_dim times the activation size each (rounded to dt there); the sum over i is formed in fp32.
+ * 1 <= head_dim <= 64, head_dim divides d.  ws: monarch_hyena_heads_layer_workspace_bytes.
+ * Errors: as monarch_hyena_layer; ESHAPE for a head dimension that is out of range or does not divide d.
+ */
+int monarch_hyena_heads_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long,
+                              const void *W_out, const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft,
+                              const int *factors, int nf, int causal, int head_dim, monarch_dtype dt, void *ws,
+                              size_t ws_bytes, monarch_stream_t stream);
+size_t monarch_hyena_heads_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf,
+                                                 int head_dim, monarch_dtype dt);
+
+/*
  * Convolution with a polynomial-parameterised ("blocky") Monarch matrix (appendix: the blocky Monarch algorithm,
  * the masking lemma for causality, the blocky Monarch convolution and its causality theorem).
  *

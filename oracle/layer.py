@@ -92,3 +92,36 @@ def hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, nfft=None, causal=
     if b_out is not None:
         y = y + np.asarray(b_out, dtype=np.float64)[None, None, :]
     return y
+
+
+def hyena_heads_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, head_dim, nfft=None, causal=True):
+    """The same layer with heads (appendix algorithm "M2 Hyena layer with heads"), step by step in float64: the d
+    features are d / head_dim heads of head_dim consecutive features, k_long has one row per head, and for every head
+        XV[i][j] = conv(k_long[head], X2~[i] o V~[j])     outer product per position, convolved along the sequence
+        O[j]     = sum_i X1~[i] o XV[i][j]                 the row vector X1~ times the matrix XV, per position
+    with i, j < head_dim numbering the head's features; projections, short convolutions and the output projection as in
+    hyena_layer.  u: (B, n, d); returns (B, n, d)."""
+    from . import causal_conv
+    u = np.asarray(u, dtype=np.float64)
+    B, n, d = u.shape
+    dh = int(head_dim)
+    assert d % dh == 0
+    heads = d // dh
+    W_in, W_out = np.asarray(W_in, dtype=np.float64), np.asarray(W_out, dtype=np.float64)
+    proj = np.einsum("cj,btj->bct", W_in, u)
+    if b_in is not None:
+        proj = proj + np.asarray(b_in, dtype=np.float64)[None, :, None]
+    ks = np.asarray(k_short, dtype=np.float64)
+    short = np.zeros_like(proj)
+    for tau in range(ks.shape[1]):
+        short[:, :, tau:] += ks[None, :, tau, None] * proj[:, :, :n - tau]
+    x1, x2, v = (short[:, m * d:(m + 1) * d].reshape(B, heads, dh, n) for m in range(3))
+    o = np.zeros((B, heads, dh, n))
+    for i in range(dh):
+        for j in range(dh):
+            xv = causal_conv(x2[:, :, i] * v[:, :, j], k_long, None, None, nfft=nfft, causal=causal)   # (B, heads, n)
+            o[:, :, j] += x1[:, :, i] * xv
+    y = np.einsum("cj,bjt->btc", W_out, o.reshape(B, d, n))
+    if b_out is not None:
+        y = y + np.asarray(b_out, dtype=np.float64)[None, None, :]
+    return y

@@ -46,6 +46,9 @@ _lib.monarch_m2_layer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
 _lib.monarch_hyena_layer.argtypes = [_vp] * 8 + [_i] * 6 + [_vp, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_hyena_layer_workspace_bytes.restype = _sz
 _lib.monarch_hyena_layer_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _vp, _i, _i]
+_lib.monarch_hyena_heads_layer.argtypes = [_vp] * 8 + [_i] * 6 + [_vp, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.monarch_hyena_heads_layer_workspace_bytes.restype = _sz
+_lib.monarch_hyena_heads_layer_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _vp, _i, _i, _i]
 _lib.monarch_mixer.argtypes = [_vp] * 9 + [_i64, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_mixer_workspace_bytes.restype = _sz
 _lib.monarch_mixer_workspace_bytes.argtypes = [_i64, _i, _i, _i]
@@ -74,6 +77,7 @@ EXPORTS = [
     "monarch_mixer", "monarch_mixer_workspace_bytes",
     "monarch_mixer_backward", "monarch_mixer_backward_workspace_bytes",
     "monarch_m2_layer", "monarch_m2_layer_workspace_bytes", "monarch_hyena_layer", "monarch_hyena_layer_workspace_bytes",
+    "monarch_hyena_heads_layer", "monarch_hyena_heads_layer_workspace_bytes",
     "monarch_blocky_state_bytes", "monarch_blocky_state_offsets", "monarch_blocky_prepare", "monarch_blocky_conv",
     "monarch_fft", "monarch_ifft", "monarch_fft_workspace_bytes",
     "monarch_causal_conv", "monarch_causal_conv_workspace_bytes", "monarch_causal_conv_static",
@@ -253,6 +257,33 @@ def monarch_hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, factors, c
     _check(_lib.monarch_hyena_layer(_ptr(u), _ptr(W_in), _ptr(b_in), _ptr(k_short), _ptr(k_long), _ptr(W_out), _ptr(b_out),
                                     _ptr(y), B, n, d, taps, klen, nfft, f, nf, 1 if causal else 0, _dt(u), _ptr(ws), wsb,
                                     _stream()))
+    return y
+
+
+def monarch_hyena_heads_layer_workspace_bytes(B, n, d, klen, factors, head_dim, torch_dtype):
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[torch_dtype]
+    return _lib.monarch_hyena_heads_layer_workspace_bytes(B, n, d, klen, nfft, f, nf, head_dim, dt)
+
+
+def monarch_hyena_heads_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, factors, head_dim, causal=True, ws=None, out=None):
+    """monarch_hyena_layer with heads of head_dim features: k_long (d / head_dim, klen), per head
+    O[j] = sum_i X1~[i] * conv(k_long[head], X2~[i] * V~[j]); u: (B, n, d)."""
+    B, n, d = u.shape
+    f, nf = _factors(factors)
+    nfft = 1
+    for v in factors:
+        nfft *= int(v)
+    taps, klen = k_short.shape[1], k_long.shape[1]
+    y = out if out is not None else torch.empty_like(u)
+    need = _lib.monarch_hyena_heads_layer_workspace_bytes(B, n, d, klen, nfft, f, nf, head_dim, _dt(u))
+    ws, wsb = _workspace(max(need, 16), ws, u.device)
+    _check(_lib.monarch_hyena_heads_layer(_ptr(u), _ptr(W_in), _ptr(b_in), _ptr(k_short), _ptr(k_long), _ptr(W_out), _ptr(b_out),
+                                          _ptr(y), B, n, d, taps, klen, nfft, f, nf, 1 if causal else 0, head_dim, _dt(u),
+                                          _ptr(ws), wsb, _stream()))
     return y
 
 

@@ -389,16 +389,27 @@ int monarch_m2_layer(const void *x, void *y, int64_t B, int bn, int bd,
 // ---------------------------------------------------------------------------------------------
 static int conv_check(int B, int H, int n, int klen, int nfft, const int *factors, int nf, int causal, monarch_dtype dt);
 
-size_t monarch_hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, monarch_dtype dt)
+static bool heads_ok(int B, int d, int head_dim)
 {
-    if (B <= 0 || n <= 0 || d <= 0) return 0;
-    return hyena_layer_workspace_bytes(B, n, d, klen, nfft, factors, nf, dt);
+    return head_dim >= 1 && head_dim <= 64 && d % head_dim == 0 && (int64_t)B * head_dim * head_dim <= INT32_MAX;
 }
 
-int monarch_hyena_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long,
-                        const void *W_out, const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft,
-                        const int *factors, int nf, int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
-                        monarch_stream_t stream)
+size_t monarch_hyena_heads_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, int head_dim,
+                                                 monarch_dtype dt)
+{
+    if (B <= 0 || n <= 0 || d <= 0 || !heads_ok(B, d, head_dim)) return 0;
+    return hyena_layer_workspace_bytes(B, n, d, klen, nfft, factors, nf, head_dim, dt);
+}
+
+size_t monarch_hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, monarch_dtype dt)
+{
+    return monarch_hyena_heads_layer_workspace_bytes(B, n, d, klen, nfft, factors, nf, 1, dt);
+}
+
+int monarch_hyena_heads_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long,
+                              const void *W_out, const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft,
+                              const int *factors, int nf, int causal, int head_dim, monarch_dtype dt, void *ws, size_t ws_bytes,
+                              monarch_stream_t stream)
 {
     clear_error();
     int rc = check_dtype(dt);
@@ -406,7 +417,10 @@ int monarch_hyena_layer(const void *u, const void *W_in, const void *b_in, const
     if (B < 0 || n < 1 || d < 1) return fail(MONARCH_ESHAPE, "B >= 0, n >= 1, d >= 1 required");
     if (n % 8) return fail(MONARCH_ESHAPE, "the sequence length must be a multiple of 8");
     if (taps < 1 || taps > 8) return fail(MONARCH_ESHAPE, "short kernels of 1 to 8 taps");
-    if ((int64_t)B * d * n > (int64_t)1 << 40 || (int64_t)3 * B * d > INT32_MAX) return fail(MONARCH_ESHAPE, "tensor too large");
+    if (!heads_ok(B, d, head_dim))
+        return fail(MONARCH_ESHAPE, "the head dimension must lie in [1, 64] and divide d = %d (given %d), B head_dim^2 below 2^31", d,
+                    head_dim);
+    if ((int64_t)B * d * n * head_dim > (int64_t)1 << 40 || (int64_t)3 * B * d > INT32_MAX) return fail(MONARCH_ESHAPE, "tensor too large");
     if (B == 0) return MONARCH_OK;
     const void *req[7] = {u, W_in, k_short, k_long, W_out, y, ws};
     for (int i = 0; i < 7; ++i)
@@ -414,16 +428,25 @@ int monarch_hyena_layer(const void *u, const void *W_in, const void *b_in, const
     const void *all[9] = {u, W_in, b_in, k_short, k_long, W_out, b_out, y, ws};
     for (int i = 0; i < 9; ++i)
         if (misaligned(all[i])) return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
-    const size_t need = monarch_hyena_layer_workspace_bytes(B, n, d, klen, nfft, factors, nf, dt);
+    const size_t need = monarch_hyena_heads_layer_workspace_bytes(B, n, d, klen, nfft, factors, nf, head_dim, dt);
     if (ws_bytes < need) return fail(MONARCH_EWORKSPACE, "workspace of %zu bytes needed, %zu given", need, ws_bytes);
     const size_t act = (size_t)B * n * d * dtype_size(dt);
     if (overlaps(y, act, u, act) || overlaps(ws, need, u, act) || overlaps(ws, need, y, act))
         return fail(MONARCH_EINVAL, "u, y and the workspace must not overlap");
     // the checks of the long convolution (nfft against n and klen, the factor list) before any device work
-    rc = conv_check(B, d, n, klen, nfft, factors, nf, causal, dt);
+    rc = conv_check(B * head_dim * head_dim, d / head_dim, n, klen, nfft, factors, nf, causal, dt);
     if (rc) return rc;
-    return launch_hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, dt, ws,
-                              ws_bytes, (hipStream_t)stream);
+    return launch_hyena_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, head_dim,
+                              dt, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int monarch_hyena_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long,
+                        const void *W_out, const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft,
+                        const int *factors, int nf, int causal, monarch_dtype dt, void *ws, size_t ws_bytes,
+                        monarch_stream_t stream)
+{
+    return monarch_hyena_heads_layer(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, 1,
+                                     dt, ws, ws_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------------

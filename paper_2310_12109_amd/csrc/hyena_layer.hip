@@ -8,6 +8,13 @@
 // depend on it), written so that their results land in the (B, d, n) layout of the convolution and back in
 // (B, n, d) without a transpose pass; the short convolutions (with the projection bias) are one memory-bound kernel;
 // the long convolution is the library's own entry point.
+// With a head dimension d_h > 1 (the same algorithm with its heads): the features are grouped in d / d_h heads, the long
+// kernel has one row per head, and per head and position
+//   XV[i][j] = conv(k_long[head], X2~[i] o V~[j]),  O[j] = sum_i X1~[i] o XV[i][j]          i, j < d_h
+// i.e. d_h^2 long convolutions per head.  Here: one kernel writes the products X2~[i] o V~[j] as a (B d_h^2, d / d_h, n)
+// tensor, the library's convolution runs over it (the d_h^2 products of a head are batch rows of one channel, so a
+// head's kernel spectrum is formed once per workgroup as for any batch), and one kernel forms the gated sum over i in
+// fp32.
 #include <dlfcn.h>
 #include <mutex>
 
@@ -162,10 +169,60 @@ __global__ __launch_bounds__(256) void bias_rows_kernel(T *__restrict__ y, const
         y[idx] = bias[idx % d];
 }
 
+// xv[((b dh + i) dh + j) heads + head][t] = x2[b][head dh + i][t] x v[b][head dh + j][t]: the outer products of a head
+// as batch rows of the long convolution.  A thread holds 8 consecutive t of one x2 row and writes its products with
+// the dh rows of v.
+template <typename T>
+__global__ __launch_bounds__(256) void heads_outer_kernel(const T *__restrict__ x2, const T *__restrict__ v, T *__restrict__ xv,
+                                                          int64_t total, int heads, int dh, int d, int n)
+{
+    const int pieces = n / 8;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = idx / pieces;                     // b d + head dh + i: a row of x2
+        const int p = (int)(idx - r * pieces);
+        const int c = (int)(r % d), head = c / dh, i = c - head * dh;
+        const int64_t b = r / d;
+        float a[8];
+        load8(x2 + r * n + 8 * p, a);
+        const T *vrow = v + ((b * d + head * dh) * n + 8 * p);
+        T *dst = xv + ((((b * dh + i) * dh) * heads + head) * n + 8 * p);
+        for (int j = 0; j < dh; ++j) {
+            float w[8], o[8];
+            load8(vrow + (int64_t)j * n, w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = a[e] * w[e];
+            store8(dst + (int64_t)j * heads * n, o);
+        }
+    }
+}
+
+// o[b][head dh + j][t] = sum_i x1[b][head dh + i][t] x yv[((b dh + i) dh + j) heads + head][t], the sum in fp32
+template <typename T>
+__global__ __launch_bounds__(256) void heads_sum_kernel(const T *__restrict__ x1, const T *__restrict__ yv, T *__restrict__ o,
+                                                        int64_t total, int heads, int dh, int d, int n)
+{
+    const int pieces = n / 8;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = idx / pieces;                     // b d + head dh + j
+        const int p = (int)(idx - r * pieces);
+        const int c = (int)(r % d), head = c / dh, j = c - head * dh;
+        const int64_t b = r / d;
+        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int i = 0; i < dh; ++i) {
+            float g[8], y[8];
+            load8(x1 + ((b * d + head * dh + i) * n + 8 * p), g);
+            load8(yv + ((((b * dh + i) * dh + j) * heads + head) * n + 8 * p), y);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(g[e], y[e], acc[e]);
+        }
+        store8(o + r * n + 8 * p, acc);
+    }
+}
+
 template <typename T>
 static int run(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long, const void *W_out,
                const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft, const int *factors, int nf, int causal,
-               monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s)
+               int dh, monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s)
 {
     rocblas_handle h = blas_handle();
     if (!h) return MONARCH_EHIP;
@@ -174,7 +231,10 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
     const int64_t plane = (int64_t)B * d * n;              // one (B, d, n) tensor
     char *base = (char *)ws;
     T *proj = (T *)base, *shrt = (T *)(base + align_up(3 * plane * es, 256)), *o = (T *)(base + 2 * align_up(3 * plane * es, 256));
-    char *conv_ws = base + 2 * align_up(3 * plane * es, 256) + align_up(plane * es, 256);
+    char *after_o = base + 2 * align_up(3 * plane * es, 256) + align_up(plane * es, 256);
+    const size_t outer_bytes = dh > 1 ? align_up((size_t)dh * plane * es, 256) : 0;   // B dh^2 (d / dh) n elements
+    T *xv = (T *)after_o, *yv = (T *)(after_o + outer_bytes);
+    char *conv_ws = after_o + 2 * outer_bytes;
     const size_t conv_ws_bytes = ws_bytes - (size_t)(conv_ws - base);
 
     // 1. projections: proj[b] (3 d x n) = W_in (3 d x d) times u[b]^T.  fp32: one batched GEMM; bf16: one per projection
@@ -193,8 +253,21 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
                            (const T *)k_short, (const T *)b_in, rows, B * d, d, n, taps);
         MONARCH_HIP_CHECK(hipGetLastError());
     }
-    // 3. O = X1~ o conv(k_long, X2~ o V~)
-    {
+    // 3. O = X1~ o conv(k_long, X2~ o V~); with heads: outer products, d_h^2 convolutions per head, gated sum
+    if (dh > 1) {
+        const int heads = d / dh;
+        const int64_t total = (int64_t)B * d * (n / 8), blocks = (total + 255) / 256;
+        hipLaunchKernelGGL(heads_outer_kernel<T>, dim3((unsigned)(blocks > (1 << 20) ? (1 << 20) : blocks)), dim3(256), 0, s,
+                           shrt + plane, shrt + 2 * plane, xv, total, heads, dh, d, n);
+        MONARCH_HIP_CHECK(hipGetLastError());
+        int rc = monarch_causal_conv(xv, k_long, nullptr, nullptr, yv, B * dh * dh, heads, n, klen, nfft, factors, nf, causal, dt, conv_ws,
+                                     conv_ws_bytes, (monarch_stream_t)s);
+        if (rc) return rc;
+        const int64_t total_o = (int64_t)B * d * (n / 8), blocks_o = (total_o + 255) / 256;
+        hipLaunchKernelGGL(heads_sum_kernel<T>, dim3((unsigned)(blocks_o > (1 << 20) ? (1 << 20) : blocks_o)), dim3(256), 0, s, shrt, yv, o,
+                           total_o, heads, dh, d, n);
+        MONARCH_HIP_CHECK(hipGetLastError());
+    } else {
         int rc = monarch_causal_conv(shrt + 2 * plane, k_long, shrt + plane, shrt, o, B, d, n, klen, nfft, factors, nf, causal, dt, conv_ws,
                                      conv_ws_bytes, (monarch_stream_t)s);
         if (rc) return rc;
@@ -214,20 +287,23 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
 
 }  // namespace hyena
 
-size_t hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, monarch_dtype dt)
+size_t hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, int head_dim, monarch_dtype dt)
 {
     const size_t es = dtype_size(dt), plane = (size_t)B * d * n * es;
-    return 2 * align_up(3 * plane, 256) + align_up(plane, 256) + monarch_causal_conv_workspace_bytes(B, d, n, klen, nfft, factors, nf, dt);
+    const size_t outer = head_dim > 1 ? 2 * align_up((size_t)head_dim * plane, 256) : 0;
+    const int conv_B = B * head_dim * head_dim, conv_H = d / head_dim;
+    return 2 * align_up(3 * plane, 256) + align_up(plane, 256) + outer +
+           monarch_causal_conv_workspace_bytes(conv_B, conv_H, n, klen, nfft, factors, nf, dt);
 }
 
 int launch_hyena_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long, const void *W_out,
                        const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft, const int *factors, int nf,
-                       int causal, monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s)
+                       int causal, int head_dim, monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s)
 {
     if (dt == MONARCH_F32)
-        return hyena::run<float>(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, dt, ws,
-                                 ws_bytes, s);
-    return hyena::run<bf16_t>(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, dt, ws,
+        return hyena::run<float>(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, head_dim, dt,
+                                 ws, ws_bytes, s);
+    return hyena::run<bf16_t>(u, W_in, b_in, k_short, k_long, W_out, b_out, y, B, n, d, taps, klen, nfft, factors, nf, causal, head_dim, dt, ws,
                               ws_bytes, s);
 }
 

@@ -88,11 +88,11 @@ int launch_matmul_backward(const void *x, const void *R, const void *L, const vo
                            float *dL, int64_t batch, int nbR, int r_out, int r_in, int nbL, int l_out, int l_in,
                            monarch_dtype dt, hipStream_t s);
 // the gated-convolution layer: dense projections (rocBLAS), short depthwise convolutions, the gated long convolution
-// (csrc/hyena_layer.hip); ws: hyena_layer_workspace_bytes
-size_t hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, monarch_dtype dt);
+// (csrc/hyena_layer.hip), with head_dim > 1 the outer products of the heads around it; ws: hyena_layer_workspace_bytes
+size_t hyena_layer_workspace_bytes(int B, int n, int d, int klen, int nfft, const int *factors, int nf, int head_dim, monarch_dtype dt);
 int launch_hyena_layer(const void *u, const void *W_in, const void *b_in, const void *k_short, const void *k_long, const void *W_out,
                        const void *b_out, void *y, int B, int n, int d, int taps, int klen, int nfft, const int *factors, int nf,
-                       int causal, monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s);
+                       int causal, int head_dim, monarch_dtype dt, void *ws, size_t ws_bytes, hipStream_t s);
 // square order-2 products with blocks of 32 or 64, in place on LDS tiles, fp32 MFMA (csrc/monarch_inplace.hip):
 // the plain product and the gated mixer (g_in, g_out may be null); fp32 or bf16 tensors
 bool monarch_inplace_supported(int bs, monarch_dtype dt);

@@ -81,15 +81,15 @@ def mixer_inputs(B, H, b, seed=0, gates=(True, True), bf16=False):
     return _finish(d, bf16)
 
 
-def hyena_layer_inputs(B, n, d, ks=3, klen=None, seed=0, bias=True, bf16=False):
+def hyena_layer_inputs(B, n, d, ks=3, klen=None, seed=0, bias=True, bf16=False, head_dim=1):
     """Gated-convolution layer (projections, short and long convolutions): u ~ N(0, 1) of shape (B, n, d), the
     projection matrices ~ N(0, 1/d) (W_in: (3d, d), W_out: (d, d)), biases ~ N(0, 0.1^2), short kernels
-    ~ N(0, 1/ks) of shape (3d, ks), the long kernel (d, klen) ~ N(0, 1) exp(-0.01 t)."""
+    ~ N(0, 1/ks) of shape (3d, ks), the long kernel (d / head_dim, klen) ~ N(0, 1) exp(-0.01 t) (one row per head)."""
     rng = np.random.default_rng(seed)
     klen = n if klen is None else klen
     w = {"u": rng.standard_normal((B, n, d)), "W_in": rng.standard_normal((3 * d, d)) / np.sqrt(d),
          "W_out": rng.standard_normal((d, d)) / np.sqrt(d), "k_short": rng.standard_normal((3 * d, ks)) / np.sqrt(ks),
-         "k_long": rng.standard_normal((d, klen)) * np.exp(-0.01 * np.arange(klen))[None, :]}
+         "k_long": rng.standard_normal((d // head_dim, klen)) * np.exp(-0.01 * np.arange(klen))[None, :]}
     w["b_in"] = 0.1 * rng.standard_normal(3 * d) if bias else None
     w["b_out"] = 0.1 * rng.standard_normal(d) if bias else None
     return _finish(w, bf16)

@@ -77,3 +77,72 @@ def test_linear_in_the_value_projection_and_the_swapped_gates_are_seen():
     w3 = dict(w); w3["W_in"] = np.concatenate([w["W_in"][d:2 * d], w["W_in"][:d], w["W_in"][2 * d:]])
     w3["k_short"] = np.concatenate([w["k_short"][d:2 * d], w["k_short"][:d], w["k_short"][2 * d:]])
     assert np.abs(_run(w3) - y).max() > 1e-2
+
+
+# ---- the layer with heads (the same appendix algorithm at head dimension d_h > 1) ----
+
+def _heads_inputs(B=2, n=12, d=6, dh=3, ks=2, seed=0, bias=True):
+    w = workloads.hyena_layer_inputs(B, n, d, ks=ks, seed=seed, bias=bias, head_dim=dh)
+    return {k: (None if v is None else v.astype(np.float64)) for k, v in w.items()}
+
+
+def _run_heads(w, dh, **kw):
+    return layer.hyena_heads_layer(w["u"], w["W_in"], w["b_in"], w["k_short"], w["k_long"], w["W_out"], w["b_out"], dh, **kw)
+
+
+def _short_paths(w):
+    """X1~, X2~, V~ of shape (B, d, n) from torch's linear and conv1d (not the oracle's code)."""
+    t = {k: (None if v is None else torch.from_numpy(v)) for k, v in w.items()}
+    d = w["u"].shape[2]
+    proj = torch.nn.functional.linear(t["u"], t["W_in"], t["b_in"]).transpose(1, 2)
+    ks = t["k_short"].shape[1]
+    short = torch.nn.functional.conv1d(torch.nn.functional.pad(proj, (ks - 1, 0)), t["k_short"].flip(1)[:, None, :], groups=3 * d)
+    return short[:, :d].numpy(), short[:, d:2 * d].numpy(), short[:, 2 * d:].numpy()
+
+
+def _heads_by_position(w, dh, transpose_outer=False):
+    """The algorithm as it is stated per position: the d_h x d_h matrices x2_s v_s^T are summed along the sequence with
+    the head's kernel, the row vector x1_t multiplies the result."""
+    B, n, d = w["u"].shape
+    x1, x2, v = _short_paths(w)
+    o = np.zeros((B, d, n))
+    for b in range(B):
+        for h in range(d // dh):
+            sl = slice(h * dh, (h + 1) * dh)
+            for t in range(n):
+                XV = np.zeros((dh, dh))
+                for s in range(t + 1):
+                    if t - s < w["k_long"].shape[1]:
+                        outer = np.outer(x2[b, sl, s], v[b, sl, s])
+                        XV += w["k_long"][h, t - s] * (outer.T if transpose_outer else outer)
+                o[b, sl, t] = x1[b, sl, t] @ XV
+    y = np.einsum("cj,bjt->btc", w["W_out"], o)
+    return y + w["b_out"][None, None, :] if w["b_out"] is not None else y
+
+
+def test_heads_against_the_algorithm_written_out_per_position():
+    for dh, d in ((3, 6), (2, 8), (4, 4)):
+        w = _heads_inputs(d=d, dh=dh, seed=dh)
+        np.testing.assert_allclose(_run_heads(w, dh), _heads_by_position(w, dh), rtol=1e-10, atol=1e-10)
+    # the outer product is x2 v^T, not v x2^T: the check above tells them apart
+    w = _heads_inputs(d=6, dh=3, seed=9)
+    assert np.abs(_heads_by_position(w, 3) - _heads_by_position(w, 3, transpose_outer=True)).max() > 1e-2
+
+
+def test_head_dimension_one_is_the_layer_without_heads():
+    w = _heads_inputs(d=5, dh=1, seed=4)
+    np.testing.assert_allclose(_run_heads(w, 1), _run(w), rtol=1e-12, atol=1e-12)
+
+
+def test_heads_short_kernel_and_bidirectional_forms():
+    w = _heads_inputs(B=1, n=16, d=4, dh=2, seed=6)
+    w["k_long"] = w["k_long"][:, :5]                                   # a kernel shorter than the sequence
+    np.testing.assert_allclose(_run_heads(w, 2), _heads_by_position(w, 2), rtol=1e-10, atol=1e-10)
+    # causal: no look-ahead
+    w2 = dict(w); w2["u"] = w["u"].copy(); w2["u"][0, 10:] += 1.0
+    np.testing.assert_array_equal(_run_heads(w, 2)[0, :10], _run_heads(w2, 2)[0, :10])
+    # circular form with negative lags at the end of the kernel: the past sees the future
+    kb = np.zeros((2, 32)); kb[:, -2:] = 1.0
+    w3, w4 = dict(w), dict(w2)
+    w3["k_long"] = w4["k_long"] = kb
+    assert np.abs(_run_heads(w3, 2, nfft=32, causal=False)[0, 8:10] - _run_heads(w4, 2, nfft=32, causal=False)[0, 8:10]).max() > 1e-3
