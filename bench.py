@@ -482,6 +482,27 @@ def widening_cases():
                 "mm3b16::backward_kernel (3 launches)" if b == 16 else "mm3::backward_kernel", 3 * batch * N * 4 + 6 * N * b * 4, batch * 16.0 * N * b, batch * N,
                 lambda torch, binding, workloads, rnd, f=mk_mm3: f(torch, binding, workloads, rnd, backward=True))
 
+    # the general order-p product (shape-generic LDS-tile kernels) at N = 4096 = 8^4 and 4^6
+    for b, p, batch in ((8, 4, 16384), (4, 6, 16384)):
+        N = b ** p
+
+        def mk_mmp(torch, binding, workloads, rnd, b=b, p=p, batch=batch, N=N, backward=False):
+            f = rnd(p, N // b, b, b, scale=b ** -0.5)
+
+            def one():
+                x = rnd(batch, N)
+                if backward:
+                    dy = rnd(batch, N)
+                    return lambda: binding.monarch_matmulp_backward(x, f, dy)
+                y = torch.empty_like(x)
+                return lambda: binding.monarch_matmulp(x, f, out=y)
+            return one
+        add("matmulp_f32_b%d_p%d_batch_%d" % (b, p, batch), "general order-%d Monarch product N=%d, fp32, batch %d" % (p, N, batch), "f32",
+            "mmp::forward_kernel", 2 * batch * N * 4 + p * N * b * 4, batch * 2.0 * p * N * b, batch * N, mk_mmp)
+        add("matmulp_backward_f32_b%d_p%d_batch_%d" % (b, p, batch), "gradients of the order-%d Monarch product N=%d, fp32, batch %d" % (p, N, batch),
+            "f32", "mmp::backward_kernel", 3 * batch * N * 4 + 2 * p * N * b * 4, batch * (6.0 * p - 2.0) * N * b, batch * N,
+            lambda torch, binding, workloads, rnd, f=mk_mmp: f(torch, binding, workloads, rnd, backward=True))
+
     # the gated-convolution layer at the shape of config 2 (B = 8, n = 1024, d = 768): four dense projections (rocBLAS),
     # the short convolutions and the fused long convolution
     for dn in ("bf16", "f32"):

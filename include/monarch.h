@@ -123,6 +123,30 @@ int monarch_matmul3_backward(const void *x, const void *B1, const void *B2, cons
                              monarch_stream_t stream);
 
 /*
+ * General (learned) order-p Monarch product and its gradients (Sec. 3.1: higher-order Monarch matrices; appendix
+ * definition of the p-variate Monarch matrix and the lemma that numbers the blocks of its factors).  N = b^p;
+ * B: (p, b^(p-1), b, b), the p block-diagonal factors one after the other, B[0] applied first;
+ *   M = P^R B_p P B_(p-1) P ... P B_1 P^R,   P^R the reversal of the p base-b digits of an index.
+ * With j = sum_a j_a b^a (input) and m = sum_a m_a b^a (output), factor s = 1 .. p consumes the input digit j_(p-s)
+ * and produces the output digit m_(s-1); its blocks are numbered by (m_0 .. m_(s-2), j_0 .. j_(p-s-1)), most
+ * significant first (the digits produced so far, then the input digits not yet consumed):
+ *   t_s[(m_0 .. m_(s-2), j_0 .. j_(p-s-1)), m_(s-1)] =
+ *       sum_c B_s[(m_0 .. m_(s-2), j_0 .. j_(p-s-1))][m_(s-1), c] t_(s-1)[(m_0 .. m_(s-3), j_0 .. j_(p-s-1), c), m_(s-2)]
+ * t_0[(j_0 .. j_(p-1))] = x[j], y[m] = t_p[(m_0 .. m_(p-1))].  p = 2 is monarch_matmul's P L P R P with square blocks
+ * (R = B_1, L = B_2), p = 3 is monarch_matmul3.
+ * monarch_matmulp: x, y: (batch, N); x, y and B of type dt, fp32 arithmetic.
+ * monarch_matmulp_backward: with S = sum_v <dy[v,:], y[v,:]>: dx = M^T dy (type dt) and dB = dS/dB (shaped like B,
+ * always float32, overwritten; sums over the batch by floating-point atomic adds: the last bits depend on the order
+ * of the additions).  dx or dB may be NULL (not computed).
+ * Shapes: 2 <= p <= 12, 2 <= b <= 16, b^p <= 4096; the gradients need (p + 1) b^p floats within 144 KB.
+ * Errors: EINVAL (null required pointer with batch > 0, misalignment, overlap), ESHAPE, EDTYPE, EHIP.
+ */
+int monarch_matmulp(const void *x, const void *B, void *y, int64_t batch, int b, int p, monarch_dtype dt,
+                    monarch_stream_t stream);
+int monarch_matmulp_backward(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, int b,
+                             int p, monarch_dtype dt, monarch_stream_t stream);
+
+/*
  * Sequence mixer with two general (learned) square order-2 Monarch matrices (Sec. 3.2, Eq. 2, in its gated
  * form): for every sequence b in [0, B) and channel h in [0, H)
  *   y[b,h,:] = g_out[b,h,:] o ( M2 ( K[h,:] o ( M1 ( g_in[b,h,:] o u[b,h,:] ) ) ) ),

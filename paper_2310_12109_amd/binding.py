@@ -37,6 +37,8 @@ _lib.monarch_matmul_backward_workspace_bytes.restype = _sz
 _lib.monarch_matmul_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i, _i, _i, _i, _i]
 _lib.monarch_matmul3.argtypes = [_vp] * 5 + [_i64, _i, _i, _vp]
 _lib.monarch_matmul3_backward.argtypes = [_vp] * 9 + [_i64, _i, _i, _vp]
+_lib.monarch_matmulp.argtypes = [_vp] * 3 + [_i64, _i, _i, _i, _vp]
+_lib.monarch_matmulp_backward.argtypes = [_vp] * 5 + [_i64, _i, _i, _i, _vp]
 _lib.monarch_mixer_backward.argtypes = [_vp] * 17 + [_i64, _i, _i, _i, _vp, _sz, _vp]
 _lib.monarch_mixer_backward_workspace_bytes.restype = _sz
 _lib.monarch_mixer_backward_workspace_bytes.argtypes = [_i64, _i, _i, _i]
@@ -73,7 +75,7 @@ EXPORTS = [
     "monarch_strerror", "monarch_last_error", "monarch_permutation_index",
     "monarch_matmul", "monarch_matmul_workspace_bytes",
     "monarch_matmul_backward", "monarch_matmul_backward_workspace_bytes",
-    "monarch_matmul3", "monarch_matmul3_backward",
+    "monarch_matmul3", "monarch_matmul3_backward", "monarch_matmulp", "monarch_matmulp_backward",
     "monarch_mixer", "monarch_mixer_workspace_bytes",
     "monarch_mixer_backward", "monarch_mixer_backward_workspace_bytes",
     "monarch_m2_layer", "monarch_m2_layer_workspace_bytes", "monarch_hyena_layer", "monarch_hyena_layer_workspace_bytes",
@@ -184,6 +186,23 @@ def monarch_matmul3_backward(x, B1, B2, B3, dy, need_dx=True, need_dB=True):
     _check(_lib.monarch_matmul3_backward(_ptr(x), _ptr(B1), _ptr(B2), _ptr(B3), _ptr(dy), _ptr(dx), _ptr(dB[0]),
                                          _ptr(dB[1]), _ptr(dB[2]), x.shape[0], b, _dt(x), _stream()))
     return (dx, *dB)
+
+
+def monarch_matmulp(x, B, out=None):
+    """y = M x for the order-p Monarch matrix of the factors B: (p, b^(p-1), b, b), B[0] applied first; x: (batch, b^p)."""
+    p, b = B.shape[0], B.shape[-1]
+    y = out if out is not None else torch.empty_like(x)
+    _check(_lib.monarch_matmulp(_ptr(x), _ptr(B), _ptr(y), x.shape[0], b, p, _dt(x), _stream()))
+    return y
+
+
+def monarch_matmulp_backward(x, B, dy, need_dx=True, need_dB=True):
+    """(dx, dB) of sum <dy, monarch_matmulp(x, B)>; dB is float32."""
+    p, b = B.shape[0], B.shape[-1]
+    dx = torch.empty_like(x) if need_dx else None
+    dB = torch.empty(B.shape, dtype=torch.float32, device=x.device) if need_dB else None
+    _check(_lib.monarch_matmulp_backward(_ptr(x), _ptr(B), _ptr(dy), _ptr(dx), _ptr(dB), x.shape[0], b, p, _dt(x), _stream()))
+    return dx, dB
 
 
 def monarch_mixer(u, K, g_in, g_out, R1, L1, R2, L2, out=None):

@@ -193,6 +193,63 @@ int monarch_matmul_backward(const void *x, const void *R, const void *L, const v
 }
 
 // ---------------------------------------------------------------------------------------------
+// monarch_matmulp / monarch_matmulp_backward
+// ---------------------------------------------------------------------------------------------
+
+static int check_matmulp(int64_t batch, int b, int p, bool backward, monarch_dtype dt, int *N)
+{
+    int rc = check_dtype(dt);
+    if (rc) return rc;
+    if (batch < 0) return fail(MONARCH_ESHAPE, "negative batch");
+    *N = matmulp_length(b, p, backward);
+    if (!*N)
+        return fail(MONARCH_ESHAPE, "order p = %d with blocks of %d: 2 <= p <= 12, 2 <= b <= 16, b^p <= 4096%s required", p, b,
+                    backward ? ", (p + 1) b^p floats within 144 KB" : "");
+    return MONARCH_OK;
+}
+
+int monarch_matmulp(const void *x, const void *B, void *y, int64_t batch, int b, int p, monarch_dtype dt, monarch_stream_t stream)
+{
+    clear_error();
+    int N = 0;
+    int rc = check_matmulp(batch, b, p, false, dt, &N);
+    if (rc) return rc;
+    if (batch == 0) return MONARCH_OK;
+    if (!x || !B || !y) return fail(MONARCH_EINVAL, "x, B and y must be non-NULL");
+    if (misaligned(x) || misaligned(B) || misaligned(y)) return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt), act = (size_t)batch * N * es, wb = (size_t)p * N * b * es;
+    if (overlaps(y, act, x, act) || overlaps(y, act, B, wb)) return fail(MONARCH_EINVAL, "y overlaps an input");
+    return launch_matmulp(x, B, y, batch, b, p, dt, (hipStream_t)stream);
+}
+
+int monarch_matmulp_backward(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, int b, int p,
+                             monarch_dtype dt, monarch_stream_t stream)
+{
+    clear_error();
+    int N = 0;
+    int rc = check_matmulp(batch, b, p, true, dt, &N);
+    if (rc) return rc;
+    if (!dx && !dB) return MONARCH_OK;
+    if (misaligned(x) || misaligned(B) || misaligned(dy) || misaligned(dx) || misaligned(dB))
+        return fail(MONARCH_EINVAL, "pointers must be 16-byte aligned");
+    const size_t es = dtype_size(dt), act = (size_t)batch * N * es, wn = (size_t)p * N * b;
+    if (batch > 0) {
+        if (!x || !B || !dy) return fail(MONARCH_EINVAL, "x, B and dy must be non-NULL");
+        const void *ins[3] = {x, dy, B};
+        const size_t in_bytes[3] = {act, act, wn * es};
+        const void *outs[2] = {dx, dB};
+        const size_t out_bytes[2] = {act, wn * sizeof(float)};
+        for (int o = 0; o < 2; ++o) {
+            if (!outs[o]) continue;
+            for (int i = 0; i < 3; ++i)
+                if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return fail(MONARCH_EINVAL, "an output overlaps an input");
+        }
+        if (dx && dB && overlaps(dx, act, dB, wn * sizeof(float))) return fail(MONARCH_EINVAL, "outputs overlap");
+    }
+    return launch_matmulp_backward(x, B, dy, dx, dB, batch, b, p, dt, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
 // monarch_matmul3 / monarch_matmul3_backward
 // ---------------------------------------------------------------------------------------------
 

@@ -134,6 +134,11 @@ int launch_matmul3(const void *x, const void *B1, const void *B2, const void *B3
                    monarch_dtype dt, hipStream_t s);
 int launch_matmul3_backward(const void *x, const void *B1, const void *B2, const void *B3, const void *dy, void *dx,
                             float *dB1, float *dB2, float *dB3, int64_t batch, int b, monarch_dtype dt, hipStream_t s);
+// general order-p Monarch product and its gradients (csrc/matmulp.hip); B: (p, b^(p-1), b, b); dx or dB may be null
+int matmulp_length(int b, int p, bool backward);   // b^p, or 0 for a shape the kernels do not take
+int launch_matmulp(const void *x, const void *B, void *y, int64_t batch, int b, int p, monarch_dtype dt, hipStream_t s);
+int launch_matmulp_backward(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, int b, int p,
+                            monarch_dtype dt, hipStream_t s);
 // polynomial-parameterised Monarch convolution (csrc/blocky.hip): parameter phase and per-batch phase
 bool blocky_fits(int bs);
 size_t blocky_state_bytes(int H, int bs);

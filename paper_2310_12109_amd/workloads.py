@@ -54,6 +54,14 @@ def monarch_matmul3_inputs(batch, b, seed=0, bf16=False):
     return _finish(d, bf16)
 
 
+def monarch_matmulp_inputs(batch, b, p, seed=0, bf16=False):
+    """General order-p Monarch product, N = b^p: x, dy ~ N(0, 1); the p factors B: (p, b^(p-1), b, b) ~ N(0, 1/b)."""
+    rng = np.random.default_rng(seed)
+    d = {"x": rng.standard_normal((batch, b ** p)), "dy": rng.standard_normal((batch, b ** p)),
+         "B": rng.standard_normal((p, b ** (p - 1), b, b)) / np.sqrt(b)}
+    return _finish(d, bf16)
+
+
 def m2_layer_inputs(B, bn, bd, seed=0, bf16=False):
     """Basic M2 layer: x ~ N(0, 1) of shape (B, n, d), n = bn^2, d = bd^2; eight factors ~ N(0, 1/block size);
     kernels n_kernel (d, n), d_kernel (d,) ~ N(0, 1); layer-norm weight 1 + N(0, 0.1^2), bias N(0, 0.1^2)."""
