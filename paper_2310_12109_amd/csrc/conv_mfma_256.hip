@@ -114,9 +114,9 @@ __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restr
             const bool ok = b < B && e0 < n;
             const int64_t at = ok ? ((int64_t)b * H + h) * n + e0 : 0;
             const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-            ld[0][it] = *reinterpret_cast<const uint4 *>(u + at);
-            if (GIN) ld[1][it] = *reinterpret_cast<const uint4 *>(g_in + at);
-            if (GOUT) ld[2][it] = *reinterpret_cast<const uint4 *>(g_out + at);
+            ld[0][it] = load_stream16(u + at);   // rows touched once per launch: streaming accesses
+            if (GIN) ld[1][it] = load_stream16(g_in + at);
+            if (GOUT) ld[2][it] = load_stream16(g_out + at);
             if (!ok) ld[0][it] = zero4;   // (the gates of a missing element meet a zero or are never used)
         }
 #pragma unroll
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void conv256_bf16_kernel(const bf16_t *__restr
         for (int it = 0; it < PAIRS / 2; ++it) {
             const int r = 4 * it + (lane >> 4), b = 2 * (p0 + (r >> 1)) + (r & 1), e0 = 8 * l16;
             if (p0 + (r >> 1) < npairs && b < B && e0 < n)
-                *reinterpret_cast<uint4 *>(y + ((int64_t)b * H + h) * n + e0) = *reinterpret_cast<const uint4 *>(&st[2][r * 128 + e0]);
+                store_stream16(y + ((int64_t)b * H + h) * n + e0, *reinterpret_cast<const uint4 *>(&st[2][r * 128 + e0]));
         }
     }
 }
