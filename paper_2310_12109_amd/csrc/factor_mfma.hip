@@ -248,7 +248,8 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
             if (q == 0 || tid + q * THREADS < npin) {
                 int64_t tt = (int64_t)tile * TOK + it[q];
                 if (tt >= tokens) tt = tokens - 1;   // clamp: computed, never stored
-                v[q].q = *reinterpret_cast<const u32x4 *>(in + tt * d_in + io[q]);
+                v[q].q = MODE == IN_FIRST ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(in + tt * d_in + io[q]))
+                                          : *reinterpret_cast<const u32x4 *>(in + tt * d_in + io[q]);
             }
     };
 
@@ -314,7 +315,10 @@ __global__ __launch_bounds__(1024) void factor_resident_kernel(const E *__restri
                         r.h[e] = __builtin_bit_cast(uint16_t, (E)sum);
                     }
                 }
-                if (tt < tokens) *reinterpret_cast<u32x4 *>(out + tt * d_out + oo[q]) = r.q;
+                if (tt < tokens) {
+                    if (MODE == IN_FIRST) *reinterpret_cast<u32x4 *>(out + tt * d_out + oo[q]) = r.q;
+                    else __builtin_nontemporal_store(r.q, reinterpret_cast<u32x4 *>(out + tt * d_out + oo[q]));
+                }
             }
         // (the next tile's rows go to tin, which nobody reads any more; tout is rewritten only after the next barrier)
     }
