@@ -127,7 +127,12 @@ __global__ __launch_bounds__(256, 3) void conv2048_f32_kernel(const float *__res
     // this thread's 4 consecutive elements of a row: n0 = 4 tid -> tile position (c, a .. a + 3)
     const int n0 = 4 * tid, c_of = n0 / N2, a_of = n0 % N2;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    auto load4 = [&](const float *row, int len) { return n0 < len ? *reinterpret_cast<const float4 *>(row + n0) : zero4; };
+    // rows are read once per launch and y written once: streaming accesses
+    auto load4 = [&](const float *row, int len) {
+        if (n0 >= len) return zero4;
+        const uint4 w = load_stream16(row + n0);
+        return make_float4(__uint_as_float(w.x), __uint_as_float(w.y), __uint_as_float(w.z), __uint_as_float(w.w));
+    };
     auto deposit = [&](float2 *tile, float4 re, float4 im) {
         float4 *dst = reinterpret_cast<float4 *>(tile + c_of * P + a_of);
         dst[0] = make_float4(re.x, im.x, re.y, im.y);
@@ -239,8 +244,8 @@ __global__ __launch_bounds__(256, 3) void conv2048_f32_kernel(const float *__res
                 ya = make_float4(ya.x * oa.x, ya.y * oa.y, ya.z * oa.z, ya.w * oa.w);
                 yb = make_float4(yb.x * ob.x, yb.y * ob.y, yb.z * ob.z, yb.w * ob.w);
             }
-            *reinterpret_cast<float4 *>(y + r0 + n0) = ya;
-            if (two) *reinterpret_cast<float4 *>(y + r1 + n0) = yb;
+            store_stream16(y + r0 + n0, make_uint4(__float_as_uint(ya.x), __float_as_uint(ya.y), __float_as_uint(ya.z), __float_as_uint(ya.w)));
+            if (two) store_stream16(y + r1 + n0, make_uint4(__float_as_uint(yb.x), __float_as_uint(yb.y), __float_as_uint(yb.z), __float_as_uint(yb.w)));
         }
         __syncthreads();
     }

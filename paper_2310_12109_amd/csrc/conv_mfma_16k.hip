@@ -180,7 +180,8 @@ struct Twiddle {
 // Rows of one job as loaded: two 16-byte pieces per thread of each of the (up to) four rows.
 struct RowRegs { u32x4 a[2], b[2], ga[2], gb[2]; };
 
-__device__ __forceinline__ u32x4 load_here(const bf16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
+// (rows of u, k and the gates are read once per launch, y written once: streaming accesses)
+__device__ __forceinline__ u32x4 load_here(const bf16_t *p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)); }
 
 __device__ __forceinline__ void unpack8(const u32x4 &w, float (&v)[8])
 {
@@ -498,8 +499,8 @@ __global__ __launch_bounds__(THREADS, 2) void conv16k_bf16_kernel(
         for (int it = 0; it < 2; ++it) {
             const int e = 8 * (tid + it * THREADS);
             if (e < n) {
-                *reinterpret_cast<u32x4 *>(y + ra + e) = ya[it];
-                if (hasb) *reinterpret_cast<u32x4 *>(y + rb + e) = yb[it];
+                __builtin_nontemporal_store(ya[it], reinterpret_cast<u32x4 *>(y + ra + e));
+                if (hasb) __builtin_nontemporal_store(yb[it], reinterpret_cast<u32x4 *>(y + rb + e));
             }
         }
         __syncthreads();   // the next job's rows are in the tile

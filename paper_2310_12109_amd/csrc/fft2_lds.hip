@@ -953,8 +953,10 @@ __global__ __launch_bounds__(THREADS, 512 / THREADS) void conv3_middle_kernel(co
         for (int it = 0; it < NIT4; ++it) {
             const int e = 4 * (tid + it * THREADS);
             if (e < CH) {
-                *reinterpret_cast<u32x4 *>(dst + e) = *reinterpret_cast<const u32x4 *>(res0 + tix(e));
-                *reinterpret_cast<u32x4 *>(dst2 + e) = *reinterpret_cast<const u32x4 *>(res1 + tix(e));
+                // (streaming stores, and streaming loads in the last pass that reads these rows: 261 -> 253 us at config 5a;
+                //  streaming between the first pass and this kernel gained nothing)
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(res0 + tix(e)), reinterpret_cast<u32x4 *>(dst + e));
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(res1 + tix(e)), reinterpret_cast<u32x4 *>(dst2 + e));
             }
         }
         __syncthreads();

@@ -507,12 +507,13 @@ __global__ __launch_bounds__(256, 2) void fft_pass_rows_in_kernel(const FftPass 
             for (int q = 0; q < 2; ++q) {
                 const int c = 2 * (rp0 + 16 * st) + q, pos = c * S + s0;
                 const int64_t at = ra * p.n_valid + (c < F && pos < p.n_valid ? pos : 0);   // past the row: any valid address
-                val[st][0][q] = *reinterpret_cast<const u32x4 *>(in + at);
-                if (gated) gat[st][0][q] = *reinterpret_cast<const u32x4 *>(gate + at);
+                // (real rows are read once per launch: streaming loads)
+                val[st][0][q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(in + at));
+                if (gated) gat[st][0][q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(gate + at));
                 if constexpr (PAIR) {
                     const int64_t bt = hasb ? at + (int64_t)p.pair_stride * p.n_valid : at;
-                    val[st][1][q] = *reinterpret_cast<const u32x4 *>(in + bt);
-                    if (gated) gat[st][1][q] = *reinterpret_cast<const u32x4 *>(gate + bt);
+                    val[st][1][q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(in + bt));
+                    if (gated) gat[st][1][q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(gate + bt));
                 }
             }
     };
@@ -675,7 +676,11 @@ __global__ __launch_bounds__(256, MAXT <= 4 ? 3 : 2) void fft_pass_rows_out_kern
             const int c0 = 32 * ks + 8 * kg;
             uint32_t w[8][2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) load_words<2>((const uint32_t *)p.in + rc * p.N + col0 + (c0 + e) * S, w[e]);   // (c0 + e < F: F is 32 or 64)
+            for (int e = 0; e < 8; ++e) {
+                const uint2 v = load_stream8((const uint32_t *)p.in + rc * p.N + col0 + (c0 + e) * S);   // (c0 + e < F: F is 32 or 64)
+                w[e][0] = v.x;
+                w[e][1] = v.y;
+            }
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -694,7 +699,7 @@ __global__ __launch_bounds__(256, MAXT <= 4 ? 3 : 2) void fft_pass_rows_out_kern
                     const int m = j * S + s0 + 8 * piece;
                     const bool ok = m < p.n_valid && (np == 0 || hasb);
                     const int64_t at = (ra + (ok ? np : 0) * (int64_t)p.pair_stride) * p.n_valid + (ok ? m : 0);
-                    gat[i] = *reinterpret_cast<const u32x4 *>((const bf16_t *)p.gate + at);
+                    gat[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>((const bf16_t *)p.gate + at));
                 }
         }
 
@@ -751,7 +756,7 @@ __global__ __launch_bounds__(256, MAXT <= 4 ? 3 : 2) void fft_pass_rows_out_kern
                         w[3] = pack2(b[2], b[3]);
                     }
                     const int64_t at = (ra + np * (int64_t)p.pair_stride) * p.n_valid + m;
-                    *reinterpret_cast<u32x4 *>((bf16_t *)p.out + at) = w;
+                    __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>((bf16_t *)p.out + at));   // y: written once
                 }
             }
         __syncthreads();   // the stage is free for the next block

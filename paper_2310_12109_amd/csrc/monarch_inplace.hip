@@ -32,10 +32,26 @@ __device__ __forceinline__ f32x4 ld4(const bf16_t *p)
 __device__ __forceinline__ float ld1(const float *p) { return *p; }
 __device__ __forceinline__ float ld1(const bf16_t *p) { return __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t *>(p) << 16); }
 __device__ __forceinline__ void st4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+// the same for rows that a launch reads or writes once, a wave instruction covering whole cache lines: streaming
+// accesses (the plain product: -4.8 % at b = 32, -3.5 % at b = 64 in fp32; the mixer kernel keeps ordinary accesses:
+// with the layer's transposed pieces, which take a cache line in several instructions, streaming cost 11 %)
+__device__ __forceinline__ f32x4 ld4s(const float *p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p)); }
+__device__ __forceinline__ f32x4 ld4s(const bf16_t *p)
+{
+    const uint2 w = load_stream8(p);
+    return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                 __uint_as_float(w.y & 0xffff0000u)};
+}
+__device__ __forceinline__ void st4s(float *p, f32x4 v) { __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(p)); }
 __device__ __forceinline__ void st4(bf16_t *p, f32x4 v)
 {
     const bf16_t h[4] = {from_f32<bf16_t>(v[0]), from_f32<bf16_t>(v[1]), from_f32<bf16_t>(v[2]), from_f32<bf16_t>(v[3])};
     *reinterpret_cast<uint2 *>(p) = *reinterpret_cast<const uint2 *>(h);
+}
+__device__ __forceinline__ void st4s(bf16_t *p, f32x4 v)
+{
+    const bf16_t h[4] = {from_f32<bf16_t>(v[0]), from_f32<bf16_t>(v[1]), from_f32<bf16_t>(v[2]), from_f32<bf16_t>(v[3])};
+    store_stream8(p, *reinterpret_cast<const uint2 *>(h));
 }
 
 // b = 32: tiles of 16 rows (74 KB: two workgroups of 8 waves per compute unit); b = 64: tiles of 8 rows (139 KB, one
@@ -121,7 +137,7 @@ __global__ __launch_bounds__(Geo<BS>::THREADS, BS == 32 ? 2 : 1) void matmul_ker
             const int v = piece / (G::N / 4), i = 4 * (piece % (G::N / 4));
             int64_t r = v0 + v;
             if (r >= batch) r = batch - 1;   // (rows past the end: computed, never stored)
-            const f32x4 val = ld4(x + r * G::N + i);
+            const f32x4 val = ld4s(x + r * G::N + i);
             float *d = tile + v * G::ROWP + (i / BS) * G::SH + i % BS;
             d[0] = val[0]; d[1] = val[1]; d[2] = val[2]; d[3] = val[3];
         }
@@ -134,7 +150,7 @@ __global__ __launch_bounds__(Geo<BS>::THREADS, BS == 32 ? 2 : 1) void matmul_ker
         for (int piece = threadIdx.x; piece < G::TV * G::N / 4; piece += G::THREADS) {
             const int v = piece / (G::N / 4), m = 4 * (piece % (G::N / 4));
             const float *sp = tile + v * G::ROWP + (m % BS) * G::SH + m / BS;
-            if (v0 + v < batch) st4(y + (v0 + v) * G::N + m, f32x4{sp[0], sp[G::SH], sp[2 * G::SH], sp[3 * G::SH]});
+            if (v0 + v < batch) st4s(y + (v0 + v) * G::N + m, f32x4{sp[0], sp[G::SH], sp[2 * G::SH], sp[3 * G::SH]});
         }
         __syncthreads();
     }
