@@ -527,6 +527,7 @@ def widening_cases():
 
     # the same layer with heads of 16 features (the head dimension of the paper's causal models): 256 long convolutions
     # per head and batch entry
+    from paper_2310_12109_amd import costmodel
     for dn in ("bf16", "f32"):
         es = 4 if dn == "f32" else 2
         B, n, d, dh = 8, 1024, 768, 16
@@ -547,7 +548,8 @@ def widening_cases():
         add("hyena_heads_layer_%s_B8_n1024_d768_dh16" % dn,
             "gated-convolution layer with heads of 16 features B=8 n=1024 d=768, %s" % dn, dn,
             "rocBLAS GEMMs + short_conv_kernel + heads_outer_kernel + conv2048 kernel + heads_sum_kernel",
-            (2 * B * n * d + 4 * d * d + (d // dh) * n) * es, 8.0 * B * n * d * d + dh * B * d * 2132000.0, B * n * d, mk_hyh, bound="mfma",
+            (2 * B * n * d + 4 * d * d + (d // dh) * n) * es, 8.0 * B * n * d * d + costmodel.conv_executed_flops(B * dh * dh, d // dh, (64, 32)),
+            B * n * d, mk_hyh, bound="mfma",
             mfma_peak=MFMA_BF16_TFLOPS if dn == "bf16" else MFMA_F32_TFLOPS)
 
     for rows, factors in ((6144, (64, 32)), (1536, (128, 128))):
