@@ -560,7 +560,8 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
         if constexpr (F32) {
             for (int q = wave; q < nchunks; q += 4) {
                 const int64_t at = base + 256 * q + 4 * lane;
-                if (at <= last_piece) *reinterpret_cast<f32x4 *>(y + at) = *reinterpret_cast<const f32x4 *>(xb + q * CH + 4 * lane);
+                if (at <= last_piece)   // (y is written once per launch: streaming stores)
+                    __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(xb + q * CH + 4 * lane), reinterpret_cast<f32x4 *>(y + at));
             }
         } else {
             for (int q = wave; 512 * q < 16 * n; q += 4) {
@@ -568,8 +569,7 @@ __global__ __launch_bounds__(256, 2) void conv_b16_kernel(const T *__restrict__ 
                 if (f < 16 * n && base + f <= last_piece) {
                     const f32x4 lo = *reinterpret_cast<const f32x4 *>(xb + chunked(f));
                     const f32x4 hi = *reinterpret_cast<const f32x4 *>(xb + chunked(f) + 4);
-                    *reinterpret_cast<uint4 *>(y + base + f) =
-                        uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+                    store_stream16(y + base + f, uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])});
                 }
             }
         }

@@ -361,7 +361,8 @@ __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int64_t v = v0 + b0 + q;
-                    if (v < batch) *reinterpret_cast<f32x4 *>(dx + v * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(gs + (b0 + q) * LDX + 4 * lane);
+                    if (v < batch)   // (dx is written once per launch: streaming stores)
+                        __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(gs + (b0 + q) * LDX + 4 * lane), reinterpret_cast<f32x4 *>(dx + v * N + 4 * lane));
                 }
             } else {
 #pragma unroll
@@ -370,8 +371,8 @@ __global__ __launch_bounds__(256, 2) void matmul_backward_b16_kernel(
                     const f32x4 lo = *reinterpret_cast<const f32x4 *>(gs + vv * LDX + 8 * (lane & 31));
                     const f32x4 hi = *reinterpret_cast<const f32x4 *>(gs + vv * LDX + 8 * (lane & 31) + 4);
                     if (v0 + vv < batch)
-                        *reinterpret_cast<uint4 *>(dx + (v0 + vv) * N + 8 * (lane & 31)) =
-                            uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+                        store_stream16(dx + (v0 + vv) * N + 8 * (lane & 31),
+                                       uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])});
                 }
             }
             __syncthreads();   // before the next tile's rows land

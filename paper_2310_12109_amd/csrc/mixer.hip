@@ -524,7 +524,8 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int64_t r = r0 + b0 + q;
-                if (r < rows) *reinterpret_cast<f32x4 *>(y + r * N + 4 * lane) = *reinterpret_cast<const f32x4 *>(bufC + (b0 + q) * LDX + 4 * lane);
+                if (r < rows)   // (y is written once per launch, whole cache lines per instruction: streaming stores)
+                    __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(bufC + (b0 + q) * LDX + 4 * lane), reinterpret_cast<f32x4 *>(y + r * N + 4 * lane));
             }
         } else {
 #pragma unroll
@@ -533,8 +534,8 @@ __global__ __launch_bounds__(256, 2) void mixer_b16_kernel(const T *__restrict__
                 const f32x4 lo = *reinterpret_cast<const f32x4 *>(bufC + v * LDX + 8 * (lane & 31));
                 const f32x4 hi = *reinterpret_cast<const f32x4 *>(bufC + v * LDX + 8 * (lane & 31) + 4);
                 if (r0 + v < rows)
-                    *reinterpret_cast<uint4 *>(y + (r0 + v) * N + 8 * (lane & 31)) =
-                        uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+                    store_stream16(y + (r0 + v) * N + 8 * (lane & 31),
+                                   uint4{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])});
             }
         }
         // (no barrier here: the next tile's first barrier comes before anything of this tile's buffers is rewritten,
