@@ -194,7 +194,8 @@ __device__ __forceinline__ void stage_finish(uint32_t *tile, const u32x4 *tab, c
                 if constexpr (TW == 1) z = cmul(z, tw[HALF ? jt & 1 : 0][r]);
                 if constexpr (TW == 2) z = cmul(z, twp[4 * jt + r]);
                 o[r] = pack2(z.x, z.y);
-                if constexpr (GOUT) gout[(int64_t)row_of<F>(jt, 4 * kg + r) * gstride + col] = z;
+                if constexpr (GOUT)   // the spectrum leaves in natural order, 128-byte runs per 16 lanes, written once: streaming stores
+                    store_stream8(&gout[(int64_t)row_of<F>(jt, 4 * kg + r) * gstride + col], make_uint2(__float_as_uint(z.x), __float_as_uint(z.y)));
             }
             if constexpr (GOUT) {
             } else if constexpr (STRIDED) {
