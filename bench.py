@@ -547,7 +547,8 @@ def widening_cases():
             return one
         add("hyena_heads_layer_%s_B8_n1024_d768_dh16" % dn,
             "gated-convolution layer with heads of 16 features B=8 n=1024 d=768, %s" % dn, dn,
-            "rocBLAS GEMMs + short_conv_kernel + heads_outer_kernel + conv2048 kernel + heads_sum_kernel",
+            "rocBLAS GEMMs + short_conv_kernel + conv2048 kernel (outer products on its loads) + heads_sum_kernel" if dn == "bf16"
+            else "rocBLAS GEMMs + short_conv_kernel + heads_outer_kernel + conv2048 kernel + heads_sum_kernel",
             (2 * B * n * d + 4 * d * d + (d // dh) * n) * es, 8.0 * B * n * d * d + costmodel.conv_executed_flops(B * dh * dh, d // dh, (64, 32)),
             B * n * d, mk_hyh, bound="mfma",
             mfma_peak=MFMA_BF16_TFLOPS if dn == "bf16" else MFMA_F32_TFLOPS)

@@ -167,14 +167,14 @@ __device__ __forceinline__ uint4 load_chunk(const E *row, int ch, int len)
 struct RowLoad { uint4 a[2], b[2]; };
 
 // Both pointers must be valid rows (no null checks: the loads stay free of branches).
-template <bool FULL, typename E>
+template <bool FULL, bool STREAM, typename E>
 __device__ __forceinline__ void load_rows(RowLoad &ld, int lane, const E *r0, const E *r1, int len)
 {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int ch = lane + 64 * half;
-        ld.a[half] = load_chunk<FULL, true, E>(r0, ch, len);
-        ld.b[half] = load_chunk<FULL, true, E>(r1, ch, len);
+        ld.a[half] = load_chunk<FULL, STREAM, E>(r0, ch, len);
+        ld.b[half] = load_chunk<FULL, STREAM, E>(r1, ch, len);
     }
 }
 
@@ -362,10 +362,14 @@ __device__ __forceinline__ void inverse_chunk(const Smem &sm, int lane, int l16,
 // FULL: n == klen == 1024, every row load is unconditional.  GIN / GOUT: the gates are present.
 // Keeping the loads free of branches lets the compiler wait for exactly the load it needs
 // (k first, then u and g_in, g_out last) instead of draining all of them at once.
-template <typename E, bool FULL, bool GIN, bool GOUT>
+// HEADS (the gated-convolution layer with heads of dh features): the batch index of the
+// convolution is ((b dh + i) dh + j) and the channel the head; u is read from row (b, head dh + j) and g_in from row
+// (b, head dh + i) of tensors of d = H dh channels, so the outer products X2[i] o V[j] of a head are formed on the loads
+// and never stored.  y keeps the plain (batch, channel) rows.
+template <typename E, bool FULL, bool GIN, bool GOUT, bool HEADS = false>
 __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
     const E *__restrict__ u, const E *__restrict__ k, const E *__restrict__ g_in,
-    const E *__restrict__ g_out, E *__restrict__ y, int B, int H, int n, int klen)
+    const E *__restrict__ g_out, E *__restrict__ y, int B, int H, int n, int klen, int dh = 1)
 {
     __shared__ Smem sm;
     const int tid = threadIdx.x;
@@ -380,6 +384,14 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
     // branch (its data is ignored: the imaginary part is forced to zero, the store is skipped)
     const int b0 = active ? 2 * p : 0, b1 = two ? 2 * p + 1 : b0;
     const size_t row0 = ((size_t)b0 * H + h) * n, row1 = ((size_t)b1 * H + h) * n;
+    size_t urow0 = row0, urow1 = row1, grow0 = row0, grow1 = row1;
+    if constexpr (HEADS) {
+        const int d = H * dh, dd = dh * dh;
+        urow0 = ((size_t)(b0 / dd) * d + h * dh + b0 % dh) * n;
+        urow1 = ((size_t)(b1 / dd) * d + h * dh + b1 % dh) * n;
+        grow0 = ((size_t)(b0 / dd) * d + h * dh + (b0 / dh) % dh) * n;
+        grow1 = ((size_t)(b1 / dd) * d + h * dh + (b1 / dh) % dh) * n;
+    }
 
     // Constant tables first (they come from L2 and gate everything else), then the rows.
     static_assert(sizeof(TwiddleTable) == (4 * 256 + 64) * sizeof(uint4), "twiddle copy assumes 1088 pieces");
@@ -399,9 +411,9 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
     }
     RowLoad ldk, ldx, ldg, ldo;
     load_row<FULL, E>(ldk, lane, k + (size_t)h * klen, klen);
-    load_rows<FULL, E>(ldx, lane, u + row0, u + row1, n);
+    load_rows<FULL, !HEADS, E>(ldx, lane, u + urow0, u + urow1, n);   // (with heads a row is read dh times: ordinary loads)
 
-    if (GIN) load_rows<FULL, E>(ldg, lane, g_in + row0, g_in + row1, n);
+    if (GIN) load_rows<FULL, !HEADS, E>(ldg, lane, g_in + grow0, g_in + grow1, n);
     {
         uint4 *dst = reinterpret_cast<uint4 *>(&sm.tw[0][0]);
         dst[tid] = tw0;
@@ -442,7 +454,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
             sm.kf_im[wave][m][lane] = make_float4(zi[m][0] * inv, zi[m][1] * inv, zi[m][2] * inv, zi[m][3] * inv);
         }
     }
-    if (GOUT) load_rows<FULL, E>(ldo, lane, g_out + row0, g_out + row1, n);
+    if (GOUT) load_rows<FULL, true, E>(ldo, lane, g_out + row0, g_out + row1, n);
     __syncthreads();   // k_f complete
     if (!active) return;
     if (!two) {   // single row: its partner's data was only a placeholder
@@ -595,6 +607,31 @@ static int launch_typed(const void *u, const void *k, const void *g_in, const vo
 #undef MONARCH_LAUNCH_C2048
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
+}
+
+// The long convolutions of the gated-convolution layer with heads: v, x2: (B, d, n) with d = heads dh; k: (heads, klen);
+// yv: (B dh^2, heads, n), row ((b dh + i) dh + j, head) = conv(k[head], x2[b, head dh + i] o v[b, head dh + j]).
+template <typename E>
+static int launch_heads_typed(const void *v, const void *k, const void *x2, void *yv, int B, int heads, int dh, int n, int klen,
+                              hipStream_t s)
+{
+    const int64_t cb = (int64_t)B * dh * dh, groups = ((cb + 1) / 2 + 3) / 4, grid = heads * groups;
+    if (grid > 0x7fffffffLL) return fail(MONARCH_ESHAPE, "B*d*head_dim too large for one launch");
+    if (n == c2048::NHALF && klen == c2048::NHALF)
+        hipLaunchKernelGGL((c2048::conv2048_kernel<E, true, true, false, true>), dim3((unsigned)grid), dim3(256), 0, s, (const E *)v,
+                           (const E *)k, (const E *)x2, (const E *)nullptr, (E *)yv, (int)cb, heads, n, klen, dh);
+    else
+        hipLaunchKernelGGL((c2048::conv2048_kernel<E, false, true, false, true>), dim3((unsigned)grid), dim3(256), 0, s, (const E *)v,
+                           (const E *)k, (const E *)x2, (const E *)nullptr, (E *)yv, (int)cb, heads, n, klen, dh);
+    MONARCH_HIP_CHECK(hipGetLastError());
+    return MONARCH_OK;
+}
+
+int launch_conv_mfma_2048_heads(const void *v, const void *k, const void *x2, void *yv, int B, int heads, int dh, int n, int klen,
+                                monarch_dtype dt, hipStream_t s)
+{
+    if (dt == MONARCH_F16) return launch_heads_typed<f16_t>(v, k, x2, yv, B, heads, dh, n, klen, s);
+    return launch_heads_typed<bf16_t>(v, k, x2, yv, B, heads, dh, n, klen, s);
 }
 
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,

@@ -11,10 +11,11 @@
 // With a head dimension d_h > 1 (the same algorithm with its heads): the features are grouped in d / d_h heads, the long
 // kernel has one row per head, and per head and position
 //   XV[i][j] = conv(k_long[head], X2~[i] o V~[j]),  O[j] = sum_i X1~[i] o XV[i][j]          i, j < d_h
-// i.e. d_h^2 long convolutions per head.  Here: one kernel writes the products X2~[i] o V~[j] as a (B d_h^2, d / d_h, n)
-// tensor, the library's convolution runs over it (the d_h^2 products of a head are batch rows of one channel, so a
-// head's kernel spectrum is formed once per workgroup as for any batch), and one kernel forms the gated sum over i in
-// fp32.
+// i.e. d_h^2 long convolutions per head.  Here: the d_h^2 products of a head are batch rows of one channel of the long
+// convolution (a head's kernel spectrum is formed once per workgroup as for any batch), and one kernel forms the gated
+// sum over i in fp32.  For 16-bit tensors and nfft = 2048 = 64 x 32 the fused convolution kernel reads X2~[i] and V~[j]
+// through the head's index map and forms the products on its loads; otherwise one kernel writes them as a
+// (B d_h^2, d / d_h, n) tensor for the library's convolution.
 #include <dlfcn.h>
 #include <mutex>
 
@@ -256,13 +257,19 @@ static int run(const void *u, const void *W_in, const void *b_in, const void *k_
     // 3. O = X1~ o conv(k_long, X2~ o V~); with heads: outer products, d_h^2 convolutions per head, gated sum
     if (dh > 1) {
         const int heads = d / dh;
-        const int64_t total = (int64_t)B * d * (n / 8), blocks = (total + 255) / 256;
-        hipLaunchKernelGGL(heads_outer_kernel<T>, dim3((unsigned)(blocks > (1 << 20) ? (1 << 20) : blocks)), dim3(256), 0, s,
-                           shrt + plane, shrt + 2 * plane, xv, total, heads, dh, d, n);
-        MONARCH_HIP_CHECK(hipGetLastError());
-        int rc = monarch_causal_conv(xv, k_long, nullptr, nullptr, yv, B * dh * dh, heads, n, klen, nfft, factors, nf, causal, dt, conv_ws,
-                                     conv_ws_bytes, (monarch_stream_t)s);
-        if (rc) return rc;
+        if (conv_mfma_2048_supported(n, klen, factors, nf, dt)) {
+            // the fused 64 x 32 kernel reads V~[j] and X2~[i] through the head's index map: no tensor of outer products
+            int rc = launch_conv_mfma_2048_heads(shrt + 2 * plane, k_long, shrt + plane, yv, B, heads, dh, n, klen, dt, s);
+            if (rc) return rc;
+        } else {
+            const int64_t total = (int64_t)B * d * (n / 8), blocks = (total + 255) / 256;
+            hipLaunchKernelGGL(heads_outer_kernel<T>, dim3((unsigned)(blocks > (1 << 20) ? (1 << 20) : blocks)), dim3(256), 0, s,
+                               shrt + plane, shrt + 2 * plane, xv, total, heads, dh, d, n);
+            MONARCH_HIP_CHECK(hipGetLastError());
+            int rc = monarch_causal_conv(xv, k_long, nullptr, nullptr, yv, B * dh * dh, heads, n, klen, nfft, factors, nf, causal, dt,
+                                         conv_ws, conv_ws_bytes, (monarch_stream_t)s);
+            if (rc) return rc;
+        }
         const int64_t total_o = (int64_t)B * d * (n / 8), blocks_o = (total_o + 255) / 256;
         hipLaunchKernelGGL(heads_sum_kernel<T>, dim3((unsigned)(blocks_o > (1 << 20) ? (1 << 20) : blocks_o)), dim3(256), 0, s, shrt, yv, o,
                            total_o, heads, dh, d, n);

@@ -160,6 +160,9 @@ int launch_conv3_middle(const Fft2Args &p, hipStream_t s);
 bool conv_mfma_2048_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);
 int launch_conv_mfma_2048(const void *u, const void *k, const void *g_in, const void *g_out, void *y,
                           int B, int H, int n, int klen, monarch_dtype dt, hipStream_t s);
+// the d_h^2 long convolutions per head of the gated-convolution layer with heads, outer products formed on the loads
+int launch_conv_mfma_2048_heads(const void *v, const void *k, const void *x2, void *yv, int B, int heads, int dh, int n, int klen,
+                                monarch_dtype dt, hipStream_t s);
 
 // nfft = 16384 = 128 x 128, n <= 8192, klen <= 8192 (both multiples of 8), bf16 I/O; no workspace.
 bool conv_mfma_16k_supported(int n, int klen, const int *factors, int nf, monarch_dtype dt);

@@ -93,7 +93,10 @@ def test_heads_fp32(mm, B, n, d, dh, ks, factors, bias):
         np.testing.assert_array_equal(_run_heads(mm, w, factors, 1, False), _run(mm, w, factors, False))
 
 
-@pytest.mark.parametrize("B,n,d,dh,ks,factors", [(2, 1024, 64, 16, 3, (64, 32)), (5, 128, 40, 8, 3, (16, 16))])
+# (64, 32): the fused kernel forms the outer products on its loads (full rows, short rows, an odd number of batch rows);
+# (16, 16): the outer-product kernel and the library's convolution
+@pytest.mark.parametrize("B,n,d,dh,ks,factors", [(2, 1024, 64, 16, 3, (64, 32)), (3, 512, 24, 4, 3, (64, 32)), (1, 1000, 9, 3, 2, (64, 32)),
+                                                 (5, 128, 40, 8, 3, (16, 16))])
 def test_heads_bf16(mm, B, n, d, dh, ks, factors):
     announce("hyena layer with heads bf16", B, n, d, dh, ks, factors)
     w = workloads.hyena_layer_inputs(B, n, d, ks=ks, seed=n + d + dh + 1, bf16=True, head_dim=dh)
