@@ -138,7 +138,7 @@ int monarch_matmul3_backward(const void *x, const void *B1, const void *B2, cons
  * monarch_matmulp_backward: with S = sum_v <dy[v,:], y[v,:]>: dx = M^T dy (type dt) and dB = dS/dB (shaped like B,
  * always float32, overwritten; sums over the batch by floating-point atomic adds: the last bits depend on the order
  * of the additions).  dx or dB may be NULL (not computed).
- * Shapes: 2 <= p <= 12, 2 <= b <= 16, b^p <= 4096; the gradients need (p + 1) b^p floats within 144 KB.
+ * Shapes: 2 <= p <= 12, 2 <= b <= 16, b^p <= 4096.
  * Errors: EINVAL (null required pointer with batch > 0, misalignment, overlap), ESHAPE, EDTYPE, EHIP.
  */
 int monarch_matmulp(const void *x, const void *B, void *y, int64_t batch, int b, int p, monarch_dtype dt,

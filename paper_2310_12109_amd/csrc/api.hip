@@ -203,8 +203,7 @@ static int check_matmulp(int64_t batch, int b, int p, bool backward, monarch_dty
     if (batch < 0) return fail(MONARCH_ESHAPE, "negative batch");
     *N = matmulp_length(b, p, backward);
     if (!*N)
-        return fail(MONARCH_ESHAPE, "order p = %d with blocks of %d: 2 <= p <= 12, 2 <= b <= 16, b^p <= 4096%s required", p, b,
-                    backward ? ", (p + 1) b^p floats within 144 KB" : "");
+        return fail(MONARCH_ESHAPE, "order p = %d with blocks of %d: 2 <= p <= 12, 2 <= b <= 16, b^p <= 4096 required", p, b);
     return MONARCH_OK;
 }
 

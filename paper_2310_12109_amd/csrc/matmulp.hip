@@ -12,10 +12,10 @@
 // The permutations are LDS index maps; rows stay on chip between the factors.  fp32 arithmetic on tiles of rows in
 // LDS, any b and p with b^p <= 4096 (the shape-generic kernels of the family: no matrix-core path of their own;
 // p = 3 with blocks of 16 goes to the matrix-core kernels of csrc/matmul3.hip).
-// Forward: in place.  A tile of 8 rows keeps ONE layout from load to store: digit position p - s of the index holds
-// j_(p-s) until factor s replaces it by m_(s-1), so a block reads its b values at stride b^(p-s) and writes its b
-// results to the same places, the load is a plain copy and only the store reverses the digits.
-// Gradients: p + 1 buffers (t_0 .. t_(p-1) and the running gradient) in the layouts of the formula above.
+// In place: a tile of rows keeps ONE layout from load to store: digit position p - s of the index holds j_(p-s)
+// until factor s replaces it by m_(s-1), so a block reads its b values at stride b^(p-s) and writes its b results to
+// the same places, the load is a plain copy and only the store reverses the digits.  The gradients keep a second tile
+// for the running gradient in the same layout and recompute the forward values each factor needs.
 #include "kernels.h"
 
 namespace monarch {
@@ -41,43 +41,51 @@ __device__ __forceinline__ int reversed(int j, int b, int p)
     return r;
 }
 
-// Where factor s reads the element that meets column 0 of block K (position in t_(s-1)), and the step to the next
-// column: the block number (hi, mid, lo) = (m_0 .. m_(s-3), m_(s-2), j_0 .. j_(p-s-1)) reads (hi, lo, c, mid).
-__device__ __forceinline__ int in_base(const Geo &g, int s, int K, int &step)
+// In-place layout of a tile of rows: digit position p - s of the LDS index holds j_(p-s) until factor s replaces it by
+// m_(s-1).  Block item = (m_0 .. m_(s-2)) b^(p-s) + (j_(p-s-1) .. j_0) of factor s: its b values sit at `at + c lo`,
+// lo = b^(p-s), and its block number has the j digits in reverse.
+struct Item {
+    int at, K;
+};
+__device__ __forceinline__ Item block_item(const Geo &g, int s, int item)
 {
-    if (s == 1) {
-        step = 1;
-        return K * g.b;
-    }
-    const int lo = g.lo[s], hi = K / (lo * g.b), rem = K - hi * lo * g.b, mid = rem / lo, l = rem - mid * lo;
-    step = g.b;
-    return (hi * lo + l) * g.b * g.b + mid;
+    const int lo = g.lo[s], hi = item / lo, J = item - hi * lo;
+    return {hi * lo * g.b + J, hi * lo + reversed(J, g.b, g.p - s)};
 }
 
-// t_s = factor s of t_(s-1) on TV rows
-template <typename T, int TV>
-__device__ __forceinline__ void factor(const Geo &g, int s, const float *in, float *out, const T *__restrict__ W)
+// Factor s on NV rows, in place.  BM = b rounded up to 2, 4, 8 or 16 (register arrays of a fixed size; the columns
+// beyond b carry zero weights).
+template <typename T, int BM, int NV>
+__device__ __forceinline__ void stage_inplace(const Geo &g, int s, float *buf, const T *__restrict__ B)
 {
-    const int N = g.N, b = g.b;
-    for (int o = threadIdx.x; o < N; o += THREADS) {
-        int step;
-        const int base = in_base(g, s, o / b, step);
-        float acc[TV];
+    const int N = g.N, b = g.b, lo = g.lo[s], nblk = N / b;
+    const T *Ws = B + (size_t)(s - 1) * N * b;
+    for (int item = threadIdx.x; item < nblk; item += THREADS) {
+        const Item it = block_item(g, s, item);
+        float *at = buf + it.at;
+        const T *W = Ws + (size_t)it.K * b * b;
+        float in[BM][NV];
 #pragma unroll
-        for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
-        const T *w = W + (size_t)o * b;
-        for (int c = 0; c < b; ++c) {
-            const float wv = to_f32(w[c]);
+        for (int c = 0; c < BM; ++c)
 #pragma unroll
-            for (int v = 0; v < TV; ++v) acc[v] = fmaf(wv, in[v * N + base + c * step], acc[v]);
+            for (int v = 0; v < NV; ++v) in[c][v] = c < b ? at[v * N + c * lo] : 0.0f;
+        for (int r = 0; r < b; ++r) {
+            float acc[NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < BM; ++c) {
+                const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) acc[v] = fmaf(w, in[c][v], acc[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < NV; ++v) at[v * N + r * lo] = acc[v];
         }
-#pragma unroll
-        for (int v = 0; v < TV; ++v) out[v * N + o] = acc[v];
     }
 }
 
-// Forward, in place, tiles of FT rows; BM = b rounded up to 2, 4, 8 or 16 (register arrays of a fixed size; the
-// columns beyond b carry zero weights).
+// Forward: tiles of FT rows, one buffer.
 constexpr int FT = 8;
 
 template <typename T, int BM>
@@ -85,39 +93,14 @@ __global__ __launch_bounds__(THREADS) void forward_kernel(const T *__restrict__ 
                                                           int64_t batch, Geo g)
 {
     extern __shared__ float lds[];
-    const int N = g.N, b = g.b, p = g.p, nblk = N / b;
+    const int N = g.N, b = g.b, p = g.p;
     const int64_t ntiles = (batch + FT - 1) / FT;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t v0 = tile * FT;
         for (int idx = threadIdx.x; idx < FT * N; idx += THREADS) lds[idx] = v0 + idx / N < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
         __syncthreads();
         for (int s = 1; s <= p; ++s) {
-            const int lo = g.lo[s];                                  // the stride of the digit this factor works on
-            const T *Ws = B + (size_t)(s - 1) * N * b;
-            for (int item = threadIdx.x; item < nblk; item += THREADS) {
-                // item = (m_0 .. m_(s-2)) b^(p-s) + (j_(p-s-1) .. j_0); the block number has the j digits in reverse
-                const int hi = item / lo, J = item - hi * lo;
-                float *at = lds + hi * lo * b + J;
-                const T *W = Ws + (size_t)(hi * lo + reversed(J, b, p - s)) * b * b;
-                float in[BM][FT];
-#pragma unroll
-                for (int c = 0; c < BM; ++c)
-#pragma unroll
-                    for (int v = 0; v < FT; ++v) in[c][v] = c < b ? at[v * N + c * lo] : 0.0f;
-                for (int r = 0; r < b; ++r) {
-                    float acc[FT];
-#pragma unroll
-                    for (int v = 0; v < FT; ++v) acc[v] = 0.0f;
-#pragma unroll
-                    for (int c = 0; c < BM; ++c) {
-                        const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
-#pragma unroll
-                        for (int v = 0; v < FT; ++v) acc[v] = fmaf(w, in[c][v], acc[v]);
-                    }
-#pragma unroll
-                    for (int v = 0; v < FT; ++v) at[v * N + r * lo] = acc[v];
-                }
-            }
+            stage_inplace<T, BM, FT>(g, s, lds, B);
             __syncthreads();
         }
         // digit position p - 1 - a now holds m_a: y[m] sits at the reversed index
@@ -129,72 +112,90 @@ __global__ __launch_bounds__(THREADS) void forward_kernel(const T *__restrict__ 
     }
 }
 
-// Gradients on tiles of TV rows: p + 1 buffers of TV rows of N floats in LDS (t_0 .. t_(p-1) and the running
-// gradient).  The adjoint of each factor, last factor first; the gradient with respect to t_(s-1) overwrites t_(s-1)
-// once dB_s has been formed from it.  Every entry of dB is summed over the rows of a tile in a register and receives
-// one atomic add per tile.
-template <typename T, int TV>
+// Gradients: tiles of BT rows in two buffers of the in-place layout, S (forward values) and G (the running gradient).
+// G starts as dy in the layout the forward leaves y in (digits reversed).  For s = p .. 1: S <- x and factors 1 .. s - 1
+// in place (t_(s-1): recomputed, p (p - 1) / 2 factor applications per tile instead of p + 1 buffers, so four rows
+// fit at N = 4096 instead of one); a block's b forward values and its b gradients then sit at the same places of
+// S and G: dB_s[K][r, c] += sum over the rows of G[r] S[c] (one atomic add per entry and tile), and the gradient with
+// respect to t_(s-1) replaces G in place, G[c] <- sum_r B_s[K][r, c] G[r].  After s = 1 G is dx in natural order.
+constexpr int BT = 4;
+
+template <typename T, int BM>
 __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__ x, const T *__restrict__ B, const T *__restrict__ dy,
                                                            T *__restrict__ dx, float *__restrict__ dB, int64_t batch, Geo g)
 {
     extern __shared__ float lds[];
-    const int N = g.N, b = g.b, p = g.p;
-    const int64_t ntiles = (batch + TV - 1) / TV;
+    const int N = g.N, b = g.b, p = g.p, nblk = N / b;
+    float *S = lds, *G = lds + BT * N;
+    const int64_t ntiles = (batch + BT - 1) / BT;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t v0 = tile * TV;
-        float *grad = lds + (size_t)p * TV * N;          // buffer p: the gradient with respect to t_p
-        for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
-            const int v = idx / N, j = idx - v * N;
-            const bool live = v0 + v < batch;            // rows past the end are zero: they add nothing to the sums
-            const int at = v * N + reversed(j, b, p);
-            lds[at] = live ? to_f32(x[v0 * N + idx]) : 0.0f;
-            grad[at] = live ? to_f32(dy[v0 * N + idx]) : 0.0f;
-        }
-        __syncthreads();
-        for (int s = 1; s < p; ++s) {
-            factor<T, TV>(g, s, lds + (size_t)(s - 1) * TV * N, lds + (size_t)s * TV * N, B + (size_t)(s - 1) * N * b);
-            __syncthreads();
+        const int64_t v0 = tile * BT;
+        for (int idx = threadIdx.x; idx < BT * N; idx += THREADS) {
+            const int v = idx / N, m = idx - v * N;   // rows past the end are zero: they add nothing to the sums
+            G[v * N + reversed(m, b, p)] = v0 + v < batch ? to_f32(dy[v0 * N + idx]) : 0.0f;
         }
         for (int s = p; s >= 1; --s) {
-            float *prev = lds + (size_t)(s - 1) * TV * N;            // t_(s-1)
-            const T *W = B + (size_t)(s - 1) * N * b;
-            // dB_s[K][r, c] += grad[K, r] t_(s-1)[position of (K, c)]
-            if (dB)
+            if (dB) {
+                for (int idx = threadIdx.x; idx < BT * N; idx += THREADS) S[idx] = v0 + idx / N < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
+                __syncthreads();
+                for (int q = 1; q < s; ++q) {
+                    stage_inplace<T, BM, BT>(g, q, S, B);
+                    __syncthreads();
+                }
+            } else {
+                __syncthreads();
+            }
+            const bool back = s > 1 || dx != nullptr;   // the gradient with respect to t_(s-1) is needed
+            const int lo = g.lo[s];
+            const T *Ws = B + (size_t)(s - 1) * N * b;
+            float *dBs = dB ? dB + (size_t)(s - 1) * N * b : nullptr;
+            // dB_s[K][r, c]: one thread per entry, neighbouring lanes neighbouring entries (the atomic adds of a wave
+            // instruction fall into two cache lines; with one thread per block they fell into 64 and the kernel was slower
+            // than with one row per tile)
+            if (dB) {
                 for (int e = threadIdx.x; e < N * b; e += THREADS) {
-                    const int o = e / b, c = e - o * b;
-                    int step;
-                    const int at = in_base(g, s, o / b, step) + c * step;
+                    const int c = e % b, o = e / b, r = o % b, K = o / b;
+                    const int hi = K / lo, at = hi * lo * b + reversed(K - hi * lo, b, p - s);
                     float acc = 0.0f;
 #pragma unroll
-                    for (int v = 0; v < TV; ++v) acc = fmaf(grad[v * N + o], prev[v * N + at], acc);
-                    atomicAdd(dB + (size_t)(s - 1) * N * b + e, acc);
+                    for (int v = 0; v < BT; ++v) acc = fmaf(G[v * N + at + r * lo], S[v * N + at + c * lo], acc);
+                    atomicAdd(dBs + e, acc);
                 }
-            if (s == 1 && !dx) break;
-            __syncthreads();
-            // gradient with respect to t_(s-1): [position of (K, c)] = sum_r B_s[K][r, c] grad[K, r]
-            for (int e = threadIdx.x; e < N; e += THREADS) {
-                const int K = e / b, c = e - K * b;
-                int step;
-                const int at = in_base(g, s, K, step) + c * step;
-                float acc[TV];
-#pragma unroll
-                for (int v = 0; v < TV; ++v) acc[v] = 0.0f;
-                for (int r = 0; r < b; ++r) {
-                    const float w = to_f32(W[((size_t)K * b + r) * b + c]);
-#pragma unroll
-                    for (int v = 0; v < TV; ++v) acc[v] = fmaf(w, grad[v * N + K * b + r], acc[v]);
-                }
-#pragma unroll
-                for (int v = 0; v < TV; ++v) prev[v * N + at] = acc[v];
+                if (back) __syncthreads();   // every gradient read before the blocks overwrite G
             }
+            if (back)
+                for (int item = threadIdx.x; item < nblk; item += THREADS) {
+                    const Item it = block_item(g, s, item);
+                    float *gat = G + it.at;
+                    const T *W = Ws + (size_t)it.K * b * b;
+                    float out[BM][BT];
+#pragma unroll
+                    for (int c = 0; c < BM; ++c)
+#pragma unroll
+                        for (int v = 0; v < BT; ++v) out[c][v] = 0.0f;
+                    for (int r = 0; r < b; ++r) {
+                        float gr[BT];
+#pragma unroll
+                        for (int v = 0; v < BT; ++v) gr[v] = gat[v * N + r * lo];
+#pragma unroll
+                        for (int c = 0; c < BM; ++c) {
+                            const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
+#pragma unroll
+                            for (int v = 0; v < BT; ++v) out[c][v] = fmaf(w, gr[v], out[c][v]);
+                        }
+                    }
+#pragma unroll
+                    for (int c = 0; c < BM; ++c)
+                        if (c < b) {
+#pragma unroll
+                            for (int v = 0; v < BT; ++v) gat[v * N + c * lo] = out[c][v];
+                        }
+                }
             __syncthreads();
-            grad = prev;
         }
         if (dx)
-            for (int idx = threadIdx.x; idx < TV * N; idx += THREADS) {
-                const int v = idx / N, j = idx - v * N;
-                if (v0 + v < batch) dx[v0 * N + idx] = from_f32<T>(grad[v * N + reversed(j, b, p)]);
-            }
+            for (int idx = threadIdx.x; idx < BT * N; idx += THREADS)
+                if (v0 + idx / N < batch) dx[v0 * N + idx] = from_f32<T>(G[idx]);
         __syncthreads();
     }
 }
@@ -217,17 +218,6 @@ static Geo geometry(int b, int p)
         for (int a = 0; a < p - s; ++a) g.lo[s] *= b;
     }
     return g;
-}
-
-constexpr size_t LDS_LIMIT = 144 * 1024;
-
-// rows per tile: as many of 8, 4, 2, 1 as nbuf buffers of rows of N floats allow (more rows per tile: every weight
-// read from L2 serves more rows)
-static int rows_per_tile(int nbuf, int N)
-{
-    int tv = 8;
-    while (tv > 1 && (size_t)nbuf * tv * N * sizeof(float) > 96 * 1024) tv >>= 1;
-    return tv;
 }
 
 static int compute_units(int *ncu)
@@ -268,38 +258,33 @@ static int launch_forward(const void *x, const void *B, void *y, int64_t batch, 
     return launch_forward_bm<T, 16>(x, B, y, batch, g, s);
 }
 
-template <typename T>
-static int launch_backward(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, const Geo &g, hipStream_t s)
+template <typename T, int BM>
+static int launch_backward_bm(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, const Geo &g, hipStream_t s)
 {
-    const int nbuf = g.p + 1;
-    const int tv = rows_per_tile(nbuf, g.N);
-    const size_t lds = (size_t)nbuf * tv * g.N * sizeof(float);
+    const size_t lds = (size_t)2 * BT * g.N * sizeof(float);
     int ncu = 0;
     if (int rc = compute_units(&ncu)) return rc;
-    const int64_t grid = grid_for(ncu, lds, (batch + tv - 1) / tv);
-#define MONARCH_LAUNCH_MMP(TVV)                                                                                              \
-    do {                                                                                                                     \
-        auto kern = backward_kernel<T, TVV>;                                                                                 \
-        if (lds > 64 * 1024)                                                                                                 \
-            MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(THREADS), lds, s, (const T *)x, (const T *)B, (const T *)dy,     \
-                           (T *)dx, dB, batch, g);                                                                           \
-    } while (0)
-    switch (tv) {
-    case 8: MONARCH_LAUNCH_MMP(8); break;
-    case 4: MONARCH_LAUNCH_MMP(4); break;
-    case 2: MONARCH_LAUNCH_MMP(2); break;
-    default: MONARCH_LAUNCH_MMP(1); break;
-    }
-#undef MONARCH_LAUNCH_MMP
+    auto kern = backward_kernel<T, BM>;
+    if (lds > 64 * 1024)
+        MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid_for(ncu, lds, (batch + BT - 1) / BT)), dim3(THREADS), lds, s, (const T *)x, (const T *)B,
+                       (const T *)dy, (T *)dx, dB, batch, g);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
 }
 
+template <typename T>
+static int launch_backward(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, const Geo &g, hipStream_t s)
+{
+    if (g.b <= 2) return launch_backward_bm<T, 2>(x, B, dy, dx, dB, batch, g, s);
+    if (g.b <= 4) return launch_backward_bm<T, 4>(x, B, dy, dx, dB, batch, g, s);
+    if (g.b <= 8) return launch_backward_bm<T, 8>(x, B, dy, dx, dB, batch, g, s);
+    return launch_backward_bm<T, 16>(x, B, dy, dx, dB, batch, g, s);
+}
+
 }  // namespace mmp
 
-// b^p if the shape is one the kernels take (2 <= p <= 12, 2 <= b <= 16, b^p <= 4096, and for the gradients p + 1
-// rows of b^p floats within the LDS of a compute unit), else 0
+// b^p if the shape is one the kernels take (2 <= p <= 12, 2 <= b <= 16, b^p <= 4096), else 0
 int matmulp_length(int b, int p, bool backward)
 {
     if (p < 2 || p > mmp::MAXP || b < 2 || b > 16) return 0;
@@ -308,7 +293,7 @@ int matmulp_length(int b, int p, bool backward)
         N *= b;
         if (N > 4096) return 0;
     }
-    if (backward && (size_t)(p + 1) * N * sizeof(float) > mmp::LDS_LIMIT) return 0;
+    (void)backward;   // forward (8 rows in one buffer) and gradients (4 rows in two) need the same 128 KB at most
     return (int)N;
 }
 
