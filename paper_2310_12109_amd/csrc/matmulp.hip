@@ -44,6 +44,24 @@ __device__ __forceinline__ int reversed(int j, int b, int p)
 // In-place layout of a tile of rows: digit position p - s of the LDS index holds j_(p-s) until factor s replaces it by
 // m_(s-1).  Block item = (m_0 .. m_(s-2)) b^(p-s) + (j_(p-s-1) .. j_0) of factor s: its b values sit at `at + c lo`,
 // lo = b^(p-s), and its block number has the j digits in reverse.
+// Position i of a row sits at LDS word i + i / 32 (row pitch N + N / 32): the digit-reversed gather of the store and
+// the unit-stride factors, whose lanes are a power of b apart, would otherwise meet in one bank.
+__device__ __forceinline__ int pad(int i) { return i + (i >> 5); }
+__host__ __device__ __forceinline__ int pitch(int N) { return N + (N >> 5); }
+
+// four consecutive weights (16- or 8-byte aligned: b a multiple of 4)
+__device__ __forceinline__ void load_w4(const float *p, float (&w)[4])
+{
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+}
+__device__ __forceinline__ void load_w4(const bf16_t *p, float (&w)[4])
+{
+    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+
 struct Item {
     int at, K;
 };
@@ -53,34 +71,48 @@ __device__ __forceinline__ Item block_item(const Geo &g, int s, int item)
     return {hi * lo * g.b + J, hi * lo + reversed(J, g.b, g.p - s)};
 }
 
-// Factor s on NV rows, in place.  BM = b rounded up to 2, 4, 8 or 16 (register arrays of a fixed size; the columns
-// beyond b carry zero weights).
-template <typename T, int BM, int NV>
+// Factor s on a tile of ROWS rows, in place; a work item is a block and NV of the rows.  BM = b rounded up to 2, 4, 8 or
+// 16 (register arrays of a fixed size; the columns beyond b carry zero weights).
+template <typename T, int BM, int NV, int ROWS = NV>
 __device__ __forceinline__ void stage_inplace(const Geo &g, int s, float *buf, const T *__restrict__ B)
 {
-    const int N = g.N, b = g.b, lo = g.lo[s], nblk = N / b;
+    const int N = g.N, NP = pitch(N), b = g.b, lo = g.lo[s], nblk = N / b;
     const T *Ws = B + (size_t)(s - 1) * N * b;
-    for (int item = threadIdx.x; item < nblk; item += THREADS) {
+    for (int work = threadIdx.x; work < nblk * (ROWS / NV); work += blockDim.x) {
+        const int item = work % nblk, chunk = work / nblk;
         const Item it = block_item(g, s, item);
-        float *at = buf + it.at;
+        float *at = buf + chunk * NV * NP;
         const T *W = Ws + (size_t)it.K * b * b;
         float in[BM][NV];
 #pragma unroll
         for (int c = 0; c < BM; ++c)
 #pragma unroll
-            for (int v = 0; v < NV; ++v) in[c][v] = c < b ? at[v * N + c * lo] : 0.0f;
+            for (int v = 0; v < NV; ++v) in[c][v] = c < b ? at[v * NP + pad(it.at + c * lo)] : 0.0f;
         for (int r = 0; r < b; ++r) {
             float acc[NV];
 #pragma unroll
             for (int v = 0; v < NV; ++v) acc[v] = 0.0f;
+            // a lane reads its own block (its own cache line per load instruction): four weights per load where b allows
+            if (BM >= 4 && (b & 3) == 0) {
 #pragma unroll
-            for (int c = 0; c < BM; ++c) {
-                const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
+                for (int c4 = 0; c4 < BM / 4; ++c4) {
+                    float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (4 * c4 < b) load_w4(W + r * b + 4 * c4, w);
 #pragma unroll
-                for (int v = 0; v < NV; ++v) acc[v] = fmaf(w, in[c][v], acc[v]);
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) acc[v] = fmaf(w[e], in[4 * c4 + e][v], acc[v]);
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < BM; ++c) {
+                    const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) acc[v] = fmaf(w, in[c][v], acc[v]);
+                }
             }
 #pragma unroll
-            for (int v = 0; v < NV; ++v) at[v * N + r * lo] = acc[v];
+            for (int v = 0; v < NV; ++v) at[v * NP + pad(it.at + r * lo)] = acc[v];
         }
     }
 }
@@ -89,24 +121,27 @@ __device__ __forceinline__ void stage_inplace(const Geo &g, int s, float *buf, c
 constexpr int FT = 8;
 
 template <typename T, int BM>
-__global__ __launch_bounds__(THREADS) void forward_kernel(const T *__restrict__ x, const T *__restrict__ B, T *__restrict__ y,
+__global__ __launch_bounds__(1024) void forward_kernel(const T *__restrict__ x, const T *__restrict__ B, T *__restrict__ y,
                                                           int64_t batch, Geo g)
 {
     extern __shared__ float lds[];
-    const int N = g.N, b = g.b, p = g.p;
+    const int N = g.N, NP = pitch(N), b = g.b, p = g.p;
     const int64_t ntiles = (batch + FT - 1) / FT;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t v0 = tile * FT;
-        for (int idx = threadIdx.x; idx < FT * N; idx += THREADS) lds[idx] = v0 + idx / N < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
+        for (int idx = threadIdx.x; idx < FT * N; idx += blockDim.x) {
+            const int v = idx / N, j = idx - v * N;
+            lds[v * NP + pad(j)] = v0 + v < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
+        }
         __syncthreads();
         for (int s = 1; s <= p; ++s) {
-            stage_inplace<T, BM, FT>(g, s, lds, B);
+            stage_inplace<T, BM, FT / 2, FT>(g, s, lds, B);
             __syncthreads();
         }
         // digit position p - 1 - a now holds m_a: y[m] sits at the reversed index
-        for (int idx = threadIdx.x; idx < FT * N; idx += THREADS) {
+        for (int idx = threadIdx.x; idx < FT * N; idx += blockDim.x) {
             const int v = idx / N, m = idx - v * N;
-            if (v0 + v < batch) y[v0 * N + idx] = from_f32<T>(lds[v * N + reversed(m, b, p)]);
+            if (v0 + v < batch) y[v0 * N + idx] = from_f32<T>(lds[v * NP + pad(reversed(m, b, p))]);
         }
         __syncthreads();
     }
@@ -125,18 +160,21 @@ __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__
                                                            T *__restrict__ dx, float *__restrict__ dB, int64_t batch, Geo g)
 {
     extern __shared__ float lds[];
-    const int N = g.N, b = g.b, p = g.p, nblk = N / b;
-    float *S = lds, *G = lds + BT * N;
+    const int N = g.N, NP = pitch(N), b = g.b, p = g.p, nblk = N / b;
+    float *S = lds, *G = lds + BT * NP;
     const int64_t ntiles = (batch + BT - 1) / BT;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t v0 = tile * BT;
         for (int idx = threadIdx.x; idx < BT * N; idx += THREADS) {
             const int v = idx / N, m = idx - v * N;   // rows past the end are zero: they add nothing to the sums
-            G[v * N + reversed(m, b, p)] = v0 + v < batch ? to_f32(dy[v0 * N + idx]) : 0.0f;
+            G[v * NP + pad(reversed(m, b, p))] = v0 + v < batch ? to_f32(dy[v0 * N + idx]) : 0.0f;
         }
         for (int s = p; s >= 1; --s) {
             if (dB) {
-                for (int idx = threadIdx.x; idx < BT * N; idx += THREADS) S[idx] = v0 + idx / N < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
+                for (int idx = threadIdx.x; idx < BT * N; idx += THREADS) {
+                    const int v = idx / N, j = idx - v * N;
+                    S[v * NP + pad(j)] = v0 + v < batch ? to_f32(x[v0 * N + idx]) : 0.0f;
+                }
                 __syncthreads();
                 for (int q = 1; q < s; ++q) {
                     stage_inplace<T, BM, BT>(g, q, S, B);
@@ -158,7 +196,7 @@ __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__
                     const int hi = K / lo, at = hi * lo * b + reversed(K - hi * lo, b, p - s);
                     float acc = 0.0f;
 #pragma unroll
-                    for (int v = 0; v < BT; ++v) acc = fmaf(G[v * N + at + r * lo], S[v * N + at + c * lo], acc);
+                    for (int v = 0; v < BT; ++v) acc = fmaf(G[v * NP + pad(at + r * lo)], S[v * NP + pad(at + c * lo)], acc);
                     atomicAdd(dBs + e, acc);
                 }
                 if (back) __syncthreads();   // every gradient read before the blocks overwrite G
@@ -166,7 +204,7 @@ __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__
             if (back)
                 for (int item = threadIdx.x; item < nblk; item += THREADS) {
                     const Item it = block_item(g, s, item);
-                    float *gat = G + it.at;
+                    float *gat = G;
                     const T *W = Ws + (size_t)it.K * b * b;
                     float out[BM][BT];
 #pragma unroll
@@ -176,26 +214,38 @@ __global__ __launch_bounds__(THREADS) void backward_kernel(const T *__restrict__
                     for (int r = 0; r < b; ++r) {
                         float gr[BT];
 #pragma unroll
-                        for (int v = 0; v < BT; ++v) gr[v] = gat[v * N + r * lo];
+                        for (int v = 0; v < BT; ++v) gr[v] = gat[v * NP + pad(it.at + r * lo)];
+                        if (BM >= 4 && (b & 3) == 0) {
 #pragma unroll
-                        for (int c = 0; c < BM; ++c) {
-                            const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
+                            for (int c4 = 0; c4 < BM / 4; ++c4) {
+                                float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                                if (4 * c4 < b) load_w4(W + r * b + 4 * c4, w);
 #pragma unroll
-                            for (int v = 0; v < BT; ++v) out[c][v] = fmaf(w, gr[v], out[c][v]);
+                                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                                    for (int v = 0; v < BT; ++v) out[4 * c4 + e][v] = fmaf(w[e], gr[v], out[4 * c4 + e][v]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int c = 0; c < BM; ++c) {
+                                const float w = c < b ? to_f32(W[r * b + c]) : 0.0f;
+#pragma unroll
+                                for (int v = 0; v < BT; ++v) out[c][v] = fmaf(w, gr[v], out[c][v]);
+                            }
                         }
                     }
 #pragma unroll
                     for (int c = 0; c < BM; ++c)
                         if (c < b) {
 #pragma unroll
-                            for (int v = 0; v < BT; ++v) gat[v * N + c * lo] = out[c][v];
+                            for (int v = 0; v < BT; ++v) gat[v * NP + pad(it.at + c * lo)] = out[c][v];
                         }
                 }
             __syncthreads();
         }
         if (dx)
             for (int idx = threadIdx.x; idx < BT * N; idx += THREADS)
-                if (v0 + idx / N < batch) dx[v0 * N + idx] = from_f32<T>(G[idx]);
+                if (v0 + idx / N < batch) dx[v0 * N + idx] = from_f32<T>(G[(idx / N) * NP + pad(idx % N)]);
         __syncthreads();
     }
 }
@@ -237,13 +287,16 @@ static int64_t grid_for(int ncu, size_t lds, int64_t ntiles)
 template <typename T, int BM>
 static int launch_forward_bm(const void *x, const void *B, void *y, int64_t batch, const Geo &g, hipStream_t s)
 {
-    const size_t lds = (size_t)FT * g.N * sizeof(float);
+    const size_t lds = (size_t)FT * pitch(g.N) * sizeof(float);
     int ncu = 0;
     if (int rc = compute_units(&ncu)) return rc;
     auto kern = forward_kernel<T, BM>;
     if (lds > 64 * 1024)
         MONARCH_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid_for(ncu, lds, (batch + FT - 1) / FT)), dim3(THREADS), lds, s, (const T *)x, (const T *)B,
+    // one thread per (block, half of the rows) of a factor, 256 to 1024 of them
+    int threads = (2 * (g.N / g.b) + 255) / 256 * 256;
+    threads = threads > 1024 ? 1024 : threads;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid_for(ncu, lds, (batch + FT - 1) / FT)), dim3(threads), lds, s, (const T *)x, (const T *)B,
                        (T *)y, batch, g);
     MONARCH_HIP_CHECK(hipGetLastError());
     return MONARCH_OK;
@@ -261,7 +314,7 @@ static int launch_forward(const void *x, const void *B, void *y, int64_t batch, 
 template <typename T, int BM>
 static int launch_backward_bm(const void *x, const void *B, const void *dy, void *dx, float *dB, int64_t batch, const Geo &g, hipStream_t s)
 {
-    const size_t lds = (size_t)2 * BT * g.N * sizeof(float);
+    const size_t lds = (size_t)2 * BT * pitch(g.N) * sizeof(float);
     int ncu = 0;
     if (int rc = compute_units(&ncu)) return rc;
     auto kern = backward_kernel<T, BM>;
