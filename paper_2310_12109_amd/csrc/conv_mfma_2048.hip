@@ -398,17 +398,11 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
     const uint4 *tw_src = reinterpret_cast<const uint4 *>(&g_twiddles);
     const uint4 tw0 = tw_src[tid], tw1 = tw_src[tid + 256], tw2 = tw_src[tid + 512], tw3 = tw_src[tid + 768];
     const uint4 tw4 = tw_src[1024 + (tid & 63)];   // every wave fetches the same tail; wave 0 stores it
-    COp F[2], G[2];
-    {
-        const uint4 *ops = reinterpret_cast<const uint4 *>(operands<E>().v[lane]);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            F[t].r = __builtin_bit_cast(op8, ops[2 * t]);
-            F[t].i = __builtin_bit_cast(op8, ops[2 * t + 1]);
-            G[t].r = __builtin_bit_cast(op8, ops[4 + 2 * t]);
-            G[t].i = __builtin_bit_cast(op8, ops[5 + 2 * t]);
-        }
-    }
+    // The per-lane operand table (8 KB, the same for the four waves) is fetched once per workgroup: two pieces per
+    // thread, through the area of LDS that k_f fills later (each lane fetching its own 128 bytes, 32 KB per workgroup,
+    // cost 3.5 %: the constants share the compute unit's vector memory path with the rows).
+    const uint4 *ops_src = reinterpret_cast<const uint4 *>(&operands<E>());
+    const uint4 op0 = ops_src[tid], op1 = ops_src[tid + 256];
     RowLoad ldk, ldx, ldg, ldo;
     load_row<FULL, E>(ldk, lane, k + (size_t)h * klen, klen);
     load_rows<FULL, !HEADS, E>(ldx, lane, u + urow0, u + urow1, n);   // (with heads a row is read dh times: ordinary loads)
@@ -422,12 +416,21 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
         dst[tid + 768] = tw3;
         if (wave == 0) dst[1024 + lane] = tw4;
     }
+    uint4 *ops_lds = reinterpret_cast<uint4 *>(&sm.kf_re[0][0][0]);   // piece j of lane l at [j][l]
+    ops_lds[(tid & 7) * 64 + (tid >> 3)] = op0;
+    ops_lds[(tid & 7) * 64 + 32 + (tid >> 3)] = op1;
+    __syncthreads();   // twiddle and operand tables complete
+    COp F[2], G[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
+        F[t].r = __builtin_bit_cast(op8, ops_lds[(2 * t) * 64 + lane]);
+        F[t].i = __builtin_bit_cast(op8, ops_lds[(2 * t + 1) * 64 + lane]);
+        G[t].r = __builtin_bit_cast(op8, ops_lds[(4 + 2 * t) * 64 + lane]);
+        G[t].i = __builtin_bit_cast(op8, ops_lds[(5 + 2 * t) * 64 + lane]);
         F[t].ni = neg_all(F[t].i);
         G[t].ni = neg_all(G[t].i);
     }
-    __syncthreads();   // twiddle table complete
+    __syncthreads();   // every wave holds its operands: the area is free for k_f
     const uint32_t lane_sign = (l16 & 1) ? 0x80008000u : 0u;   // (-1)^(row of this lane) on every slot
 
     // spectrum of the kernel: wave w transforms spectrum columns 16w .. 16w+15
