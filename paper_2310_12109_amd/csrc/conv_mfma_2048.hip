@@ -403,8 +403,10 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
     // cost 3.5 %: the constants share the compute unit's vector memory path with the rows).
     const uint4 *ops_src = reinterpret_cast<const uint4 *>(&operands<E>());
     const uint4 op0 = ops_src[tid], op1 = ops_src[tid + 256];
-    RowLoad ldk, ldx, ldg, ldo;
-    load_row<FULL, E>(ldk, lane, k + (size_t)h * klen, klen);
+    // k is staged once for the four waves: thread t brings elements 4 t .. 4 t + 3 (ordinary loads: 8 bytes per lane)
+    RowLoad ldx, ldg, ldo;
+    uint2 kraw = make_uint2(0u, 0u);
+    if (FULL || 4 * tid < klen) kraw = *reinterpret_cast<const uint2 *>(k + (size_t)h * klen + 4 * tid);
     load_rows<FULL, !HEADS, E>(ldx, lane, u + urow0, u + urow1, n);   // (with heads a row is read dh times: ordinary loads)
 
     if (GIN) load_rows<FULL, !HEADS, E>(ldg, lane, g_in + grow0, g_in + grow1, n);
@@ -416,10 +418,15 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
         dst[tid + 768] = tw3;
         if (wave == 0) dst[1024 + lane] = tw4;
     }
+    {   // k into the first wave's staging tile, imaginary halves zero (same word layout as stage_rows)
+        const int ch = tid >> 1;
+        uint32_t *dst = sm.stage[0] + (ch >> 2) * ST_LD + (ch & 3) * 8 + 4 * (tid & 1);
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(kraw.x & 0xffffu, kraw.x >> 16, kraw.y & 0xffffu, kraw.y >> 16);
+    }
     uint4 *ops_lds = reinterpret_cast<uint4 *>(&sm.kf_re[0][0][0]);   // piece j of lane l at [j][l]
     ops_lds[(tid & 7) * 64 + (tid >> 3)] = op0;
     ops_lds[(tid & 7) * 64 + 32 + (tid >> 3)] = op1;
-    __syncthreads();   // twiddle and operand tables complete
+    __syncthreads();   // twiddle and operand tables and k complete
     COp F[2], G[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -435,10 +442,8 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
 
     // spectrum of the kernel: wave w transforms spectrum columns 16w .. 16w+15
     {
-        stage_rows<E>(stage, lane, ldk, ldk, false);
-        __builtin_amdgcn_wave_barrier();
         op8 xr[2], xi[2];
-        read_stage_operands(stage, l16, kg, xr, xi);
+        read_stage_operands(sm.stage[0], l16, kg, xr, xi);   // (the first wave's tile is rewritten only after the next barrier)
         if (wave >= 2) {   // spectrum columns 32..63: (-1)^c on the data (odd slots)
             xr[0] = flip(xr[0], 0x80000000u);
             xr[1] = flip(xr[1], 0x80000000u);
