@@ -84,7 +84,7 @@ template <typename E> constexpr uint32_t half_bits(double v);
 template <> constexpr uint32_t half_bits<bf16_t>(double v) { return bf16_bits(v); }
 template <> constexpr uint32_t half_bits<f16_t>(double v) { return f16_bits(v); }
 
-struct TwiddleTable { float v[N1][TW_LD][2]; };
+struct TwiddleTable { float v[N1][N2][2]; };   // unpadded in memory (16 KB); the copy in LDS has rows of TW_LD
 constexpr TwiddleTable make_twiddles()
 {
     TwiddleTable t{};
@@ -394,10 +394,9 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
     }
 
     // Constant tables first (they come from L2 and gate everything else), then the rows.
-    static_assert(sizeof(TwiddleTable) == (4 * 256 + 64) * sizeof(uint4), "twiddle copy assumes 1088 pieces");
+    static_assert(sizeof(TwiddleTable) == 4 * 256 * sizeof(uint4), "twiddle copy assumes 1024 pieces of two entries");
     const uint4 *tw_src = reinterpret_cast<const uint4 *>(&g_twiddles);
     const uint4 tw0 = tw_src[tid], tw1 = tw_src[tid + 256], tw2 = tw_src[tid + 512], tw3 = tw_src[tid + 768];
-    const uint4 tw4 = tw_src[1024 + (tid & 63)];   // every wave fetches the same tail; wave 0 stores it
     // The per-lane operand table (8 KB, the same for the four waves) is fetched once per workgroup: two pieces per
     // thread, through the area of LDS that k_f fills later (each lane fetching its own 128 bytes, 32 KB per workgroup,
     // cost 3.5 %: the constants share the compute unit's vector memory path with the rows).
@@ -411,12 +410,15 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
 
     if (GIN) load_rows<FULL, !HEADS, E>(ldg, lane, g_in + grow0, g_in + grow1, n);
     {
-        uint4 *dst = reinterpret_cast<uint4 *>(&sm.tw[0][0]);
-        dst[tid] = tw0;
-        dst[tid + 256] = tw1;
-        dst[tid + 512] = tw2;
-        dst[tid + 768] = tw3;
-        if (wave == 0) dst[1024 + lane] = tw4;
+        // piece p = entries (i, a), (i, a + 1) with i = p / 16, a = 2 (p % 16): rows of TW_LD entries in LDS (16-byte aligned:
+        // TW_LD and a are even)
+        static_assert(TW_LD % 2 == 0 && N2 == 32, "twiddle pieces");
+        const uint4 twv[4] = {tw0, tw1, tw2, tw3};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int p = tid + 256 * q;
+            *reinterpret_cast<uint4 *>(&sm.tw[p >> 4][2 * (p & 15)]) = twv[q];
+        }
     }
     {   // k into the first wave's staging tile, imaginary halves zero (same word layout as stage_rows)
         const int ch = tid >> 1;
