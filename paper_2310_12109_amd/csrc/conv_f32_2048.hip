@@ -44,6 +44,21 @@ constexpr RootTable make_roots()
     return t;
 }
 __device__ const RootTable g_roots = make_roots();   // w[e] = exp(+2 pi i e / 2048)
+// the twiddles w^(i a) by (i, a): the 16 lanes of a group read 128 contiguous bytes (gathered from the table of roots at
+// index i a every lane asked for a cache line of its own, eight times per thread at the head of the kernel)
+struct TwiddleTable { float2 v[N1][N2]; };
+constexpr TwiddleTable make_twiddles()
+{
+    TwiddleTable t{};
+    for (int i = 0; i < N1; ++i)
+        for (int a = 0; a < N2; ++a) {
+            const croots::CosSin r = croots::unit_root(i * a, NFFT);
+            t.v[i][a].x = (float)r.c;
+            t.v[i][a].y = (float)r.s;
+        }
+    return t;
+}
+__device__ const TwiddleTable g_twiddles = make_twiddles();
 
 struct Smem {
     float2 tile[2][N1 * P];
@@ -143,7 +158,7 @@ __global__ __launch_bounds__(256, 3) void conv2048_f32_kernel(const float *__res
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) tw[t][r] = g_roots.w[(16 * wave + 4 * kg + r) * (16 * t + l16)];
+        for (int r = 0; r < 4; ++r) tw[t][r] = g_twiddles.v[16 * wave + 4 * kg + r][16 * t + l16];
 
     float2 *tA = sm.tile[0], *tB = sm.tile[1];
     f32x4 zr[2], zi[2];
