@@ -480,8 +480,7 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
             op8 xr[2], xi[2];
             read_stage_operands(stage, l16, kg, xr, xi);
             __builtin_amdgcn_wave_barrier();
-            // the tile is free again: park the output gates in it, same word layout
-            if (GOUT) stage_rows<E>(stage, lane, ldo, ldo, false);
+            // (the tile is free again)
 
             // B operands of the last factor: [kstep = contraction rows 32ks..32ks+31][column tile nt]
             Pack8 wr_op[2][2], wi_op[2][2];
@@ -539,6 +538,9 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
             // rows c = 16mt + 4kg + r, column a = 16nt + l16: gate in fp32, round once, park in the
             // staging tile (all gate words are read before the first result is written)
             __builtin_amdgcn_sched_barrier(0);
+            // The output gates are parked in the staging tile (same word layout) only now: waiting for them before the
+            // transforms put their arrival on the path of the workgroups that receive their rows last.
+            if (GOUT) stage_rows<E>(stage, lane, ldo, ldo, false);
             __builtin_amdgcn_wave_barrier();
             uint32_t gw[2][2][4];
             if (GOUT) {
