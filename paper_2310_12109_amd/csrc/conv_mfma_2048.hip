@@ -464,7 +464,6 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
             sm.kf_im[wave][m][lane] = make_float4(zi[m][0] * inv, zi[m][1] * inv, zi[m][2] * inv, zi[m][3] * inv);
         }
     }
-    if (GOUT) load_rows<FULL, true, E>(ldo, lane, g_out + row0, g_out + row1, n);
     __syncthreads();   // k_f complete
     if (!active) return;
     if (!two) {   // single row: its partner's data was only a placeholder
@@ -496,6 +495,9 @@ __global__ __launch_bounds__(256, WAVES_PER_SIMD) void conv2048_kernel(
                 forward_chunk<E, 1, true>(sm, l16, kg, xr, xi, F[1], G, zr, zi);
                 inverse_chunk<E, 1>(sm, lane, l16, kg, zr, zi, G, wr_op[0], wi_op[0]);
             }
+            // The output gates are asked for here, half-way through the transforms: needed last, they queue behind the rows
+            // that other workgroups of the compute unit still wait for (asked for before the transforms: +2 %).
+            if (GOUT) load_rows<FULL, true, E>(ldo, lane, g_out + row0, g_out + row1, n);
             // spectrum columns 32..63 see F64[c][32 + i'] = (-1)^c F64[c][i']: negate the odd slots of the data
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
